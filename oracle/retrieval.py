@@ -1,0 +1,125 @@
+"""Oracle: draft retrieval from a per-key pool (Sec. 3.2 pool construction, Sec. 3.3 Eq. 5).
+
+TEST INFRASTRUCTURE ONLY -- never imported by the product package.
+
+The paper keeps each group's old texts in a trie whose nodes carry tokens, looks up the
+last n context tokens, shrinks n when too little comes back and prefers high-frequency
+tokens when too much does.  Here that is written on plain sets of pool positions, by a
+naive scan of the key's sub-pool, so that the answer does not depend on any index
+structure:
+
+  * the sub-pool of a key is the concatenation, in the order supplied, of the sequences
+    tagged with that key; sub-pools are laid out by ascending key ("regrouped pool");
+  * an occurrence of an n-gram w is a position e with P[e-n+1..e] == w, all inside one
+    sequence, whose successor e+1 lies in the same sequence;
+  * for n = min(n_max, context length) down to n_min: take all occurrences; extend a chain
+    one token at a time by the most frequent successor among the surviving occurrences
+    (ties -> smallest token id), keeping only the occurrences that agree with it; stop
+    after K tokens or when no survivor has a successor left;
+  * the first n whose chain has >= min_tokens tokens wins; otherwise the longest chain seen
+    (ties -> larger n); nothing found -> draft_len 0, match_n 0, pool_index -1;
+  * pool_index is the smallest surviving position (flat index in the regrouped pool), so
+    P[pool_index+1 .. pool_index+draft_len] equals the draft.
+
+This equals greedy descent of the paper's trie from the node the suffix reaches, always
+into the child with the highest frequency (frequency = number of occurrences of the path).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+class RegroupedPool:
+    """Flat tokens grouped by ascending key plus per-position sequence bounds."""
+
+    def __init__(self, tokens, seq_off, seq_key):
+        tokens = np.asarray(tokens, dtype=np.int32)
+        seq_off = np.asarray(seq_off, dtype=np.int64)
+        seq_key = np.asarray(seq_key, dtype=np.int64)
+        n_seq = seq_key.size
+        order = np.argsort(seq_key, kind="stable")          # ascending key, supply order within a key
+        lens = (seq_off[1:] - seq_off[:-1])[order]
+        new_off = np.zeros(n_seq + 1, dtype=np.int64)
+        np.cumsum(lens, out=new_off[1:])
+        P = np.empty(int(new_off[-1]), dtype=np.int32)
+        for i, s in enumerate(order):
+            P[new_off[i]:new_off[i + 1]] = tokens[seq_off[s]:seq_off[s + 1]]
+        self.P = P
+        self.seq_begin = np.repeat(new_off[:-1], lens)      # per position: first index of its sequence
+        self.seq_end = np.repeat(new_off[1:], lens)         # per position: one past its sequence
+        self.key_range = {}
+        keys_sorted = seq_key[order]
+        i = 0
+        while i < n_seq:
+            j = i
+            while j < n_seq and keys_sorted[j] == keys_sorted[i]:
+                j += 1
+            self.key_range[int(keys_sorted[i])] = (int(new_off[i]), int(new_off[j]))
+            i = j
+
+
+def _occurrences(pool: RegroupedPool, lo: int, hi: int, w: np.ndarray) -> np.ndarray:
+    """All positions e in [lo, hi) that end an in-sequence copy of w and have an in-sequence successor."""
+    n = w.size
+    e = np.arange(lo, hi, dtype=np.int64)
+    ok = (e - n + 1 >= pool.seq_begin[lo:hi]) & (e + 1 < pool.seq_end[lo:hi])
+    e = e[ok]
+    for j in range(n):                       # compare the j-th token from the end
+        e = e[pool.P[e - j] == w[n - 1 - j]]
+    return e
+
+
+def _greedy_chain(pool: RegroupedPool, M: np.ndarray, K: int):
+    chain = []
+    for j in range(1, K + 1):
+        alive = M[M + j < pool.seq_end[M]]
+        if alive.size == 0:
+            break
+        succ = pool.P[alive + j]
+        vals, counts = np.unique(succ, return_counts=True)   # vals ascending -> first max = smallest id
+        tok = vals[np.argmax(counts)]
+        chain.append(int(tok))
+        M = alive[succ == tok]
+    return chain, M
+
+
+def retrieve_one(pool: RegroupedPool, key: int, ctx_tail, n_min: int, n_max: int, K: int,
+                 min_tokens: int = 1):
+    """ctx_tail: the last tokens of the context, right-aligned; entries < 0 are left padding.
+    Returns (drafts list, match_n, pool_index)."""
+    ctx = np.asarray(ctx_tail, dtype=np.int64)
+    valid = 0
+    while valid < ctx.size and ctx[ctx.size - 1 - valid] >= 0:
+        valid += 1
+    min_tokens = max(1, min_tokens)
+    rng_ = pool.key_range.get(int(key))
+    if rng_ is None or K <= 0:
+        return [], 0, -1
+    lo, hi = rng_
+    best = ([], 0, -1)
+    for n in range(min(n_max, valid), max(n_min, 1) - 1, -1):
+        M0 = _occurrences(pool, lo, hi, ctx[ctx.size - n:])
+        if M0.size == 0:
+            continue
+        chain, M = _greedy_chain(pool, M0, K)
+        cand = (chain, n, int(M.min()))
+        if len(chain) >= min_tokens:
+            return cand
+        if len(chain) > len(best[0]):
+            best = cand
+    return best
+
+
+def retrieve(pool: RegroupedPool, keys, ctx_tails, n_min: int, n_max: int, K: int, min_tokens: int = 1):
+    """Batched form.  Returns drafts int32[B][K] (-1 padded), draft_len int32[B],
+    match_n int32[B], pool_index int64[B]."""
+    B = len(keys)
+    drafts = np.full((B, K), -1, dtype=np.int32)
+    dl = np.zeros(B, dtype=np.int32)
+    mn = np.zeros(B, dtype=np.int32)
+    pi = np.full(B, -1, dtype=np.int64)
+    for b in range(B):
+        c, n, idx = retrieve_one(pool, keys[b], ctx_tails[b], n_min, n_max, K, min_tokens)
+        drafts[b, :len(c)] = c
+        dl[b], mn[b], pi[b] = len(c), n, idx
+    return drafts, dl, mn, pi

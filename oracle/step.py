@@ -1,0 +1,76 @@
+"""Oracle: one whole Draft-then-Verify decoding step and the loops built from it
+(Sec. 2.1 Eq. 1-4; Sec. 3.3-3.4).
+
+TEST INFRASTRUCTURE ONLY -- never imported by the product package.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import acceptance, retrieval
+from .decoder import Decoder
+
+
+class Sequence:
+    """One generation stream: its pool key, every token so far, and its KV cache.
+    The last token (`pending`) is not in the cache yet; it is row 0 of the next forward."""
+
+    def __init__(self, dec: Decoder, key: int, prompt, capacity: int):
+        prompt = [int(t) for t in prompt]
+        assert len(prompt) >= 1
+        self.key = int(key)
+        self.tokens = prompt[:]
+        self.cache = dec.new_cache(capacity)
+        if len(prompt) > 1:                     # prefill everything but the last token
+            dec.hidden(self.cache, prompt[:-1])
+            self.cache.commit(len(prompt) - 1)
+
+    @property
+    def pending(self) -> int:
+        return self.tokens[-1]
+
+
+def autoregressive_greedy(dec: Decoder, seq: Sequence, n_new: int):
+    """Eq. 1 with argmax: one forward per token.  Returns the n_new generated tokens."""
+    out = []
+    for _ in range(n_new):
+        logits = dec.verify_forward(seq.cache, [seq.pending])
+        seq.cache.commit(1)
+        t = int(np.argmax(logits[0]))
+        seq.tokens.append(t)
+        out.append(t)
+    return out
+
+
+def verify_step(dec: Decoder, seqs, drafts, draft_len, k: int, p: float, mode: int = 0,
+                return_logits: bool = False):
+    """Verify given drafts for every sequence (R = K+1 rows each), apply the acceptance rule,
+    commit accepted tokens.  drafts int[B][K] (-1 padded; padded rows are fed token 0 and
+    their outputs ignored)."""
+    drafts = np.asarray(drafts)
+    B, K = drafts.shape
+    logits = np.empty((B, K + 1, dec.V), dtype=np.float64)
+    for b, s in enumerate(seqs):
+        row_tokens = [s.pending] + [int(t) if j < draft_len[b] else 0 for j, t in enumerate(drafts[b])]
+        logits[b] = dec.verify_forward(s.cache, row_tokens)
+    acc, out, stats, gaps = acceptance.verify_batch(logits, drafts, draft_len, k, p, mode)
+    for b, s in enumerate(seqs):
+        s.cache.commit(int(acc[b]) + 1)          # pending + accepted drafts become permanent
+        s.tokens.extend(int(t) for t in out[b, :acc[b] + 1])
+    res = {"accept_len": acc, "out_tokens": out, "stats": stats, "argmax_gap": gaps}
+    if return_logits:
+        res["logits"] = logits
+    return res
+
+
+def laser_step(dec: Decoder, pool: retrieval.RegroupedPool, seqs, n_min: int, n_max: int, K: int,
+               k: int, p: float, mode: int = 0, min_tokens: int = 1, return_logits: bool = False):
+    """retrieve -> verify -> accept -> commit for a batch of sequences."""
+    tails = []
+    for s in seqs:
+        t = s.tokens[-n_max:]
+        tails.append([-1] * (n_max - len(t)) + t)
+    drafts, dl, mn, pi = retrieval.retrieve(pool, [s.key for s in seqs], tails, n_min, n_max, K, min_tokens)
+    res = verify_step(dec, seqs, drafts, dl, k, p, mode, return_logits)
+    res.update({"drafts": drafts, "draft_len": dl, "match_n": mn, "pool_index": pi})
+    return res
