@@ -1,0 +1,208 @@
+/*
+ * laser.h -- C ABI of the MI355X (gfx950) library for the per-step hot path of
+ * retrieval-based Draft-then-Verify decoding with a Customized Retrieval Pool and Relaxed
+ * Verification (arxiv 2408.05676, "LASER").
+ *
+ * One decoding step of one batch is
+ *     laser_retrieve_drafts -> laser_verify_step -> laser_kv_commit (-> laser_ctx_advance)
+ * all asynchronous on one HIP stream, with no device->host traffic.
+ *
+ * Conventions
+ *   - Pointers are tagged [host] or [dev]. [dev] buffers are owned by the caller (for example
+ *     PyTorch tensors) and only borrowed for the duration of the stream-ordered call.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). Calls enqueue work and
+ *     return; they synchronise only where stated.
+ *   - Every function returns LASER_OK (0) or a negative LASER_E_* code; laser_last_error() gives a
+ *     thread-local message for the last failure. Data-dependent outcomes (unknown key, no match,
+ *     nothing accepted) are results, not errors.
+ *   - Token ids are int32 >= 0; -1 pads. bf16 / fp16 = bfloat16 / IEEE half bit patterns in uint16.
+ *   - Numerics: weights bf16 as given; activations that feed matrix products and the KV cache are
+ *     fp16; accumulation, softmax, norms and the residual stream are fp32.
+ *   - A handle must not be used from two streams or two host threads at the same time (the model
+ *     handle owns activation workspace, the KV handle owns host-side page bookkeeping).
+ */
+#ifndef LASER_H
+#define LASER_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LASER_OK             0
+#define LASER_E_INVALID_ARG (-1) /* null pointer, negative size, value out of its documented range */
+#define LASER_E_SHAPE       (-2) /* model/cache shape the kernels do not support */
+#define LASER_E_OOM_PAGES   (-3) /* KV page pool or a sequence's reserved capacity exhausted */
+#define LASER_E_HIP         (-4) /* a HIP runtime call failed */
+#define LASER_E_LIMIT       (-5) /* size beyond a documented maximum */
+
+#define LASER_MAX_NGRAM   8      /* longest context suffix that can be indexed (n_max)            */
+#define LASER_MAX_DRAFT   63     /* largest K (drafts per sequence per step); R = K+1 <= 64 rows    */
+#define LASER_MAX_TOPK    8      /* largest k of the top-k condition                                */
+
+/* acceptance rule selector (Sec. 3.4). rank = number of vocabulary entries ordered before the draft
+ * (higher logit first, smaller id on ties); q = softmax probability of the draft at temperature 1. */
+#define LASER_MODE_RV          0 /* Eq. 8: rank < k  and  q > p   (Eq. 4 greedy = k 1, p < 0)       */
+#define LASER_MODE_RV_OR_TOP1  1 /* rank == 0  or  Eq. 8                                             */
+#define LASER_MODE_TOPK_ONLY   2 /* Eq. 7 alone: rank < k                                            */
+#define LASER_MODE_TOPP_ONLY   3 /* threshold-only ablation: rank == 0  or  q > p                    */
+
+typedef struct laser_pool  laser_pool;   /* regrouped token pool + suffix index, device memory, library-owned */
+typedef struct laser_model laser_model;  /* borrowed weight views + library-owned workspace and RoPE table     */
+typedef struct laser_kv    laser_kv;     /* paged fp16 KV cache: page pool, block tables, lengths; library-owned */
+
+const char* laser_last_error(void);
+const char* laser_version(void);
+
+/* ------------------------------------------------------------------------------------------------
+ * Retrieval pool (Sec. 3.2: one pool per group of users/items, built from their earlier texts;
+ * Sec. 3.3 Eq. 5: Retrieve(D, last n tokens, K)).
+ *
+ * laser_pool_build: groups the sequences by key (ascending key; supply order kept inside a key) into
+ * one flat "regrouped pool" and indexes, for every key and every n in 1..n_max, each n-gram that
+ * lies inside one sequence and is followed by at least one token of that sequence.
+ *   tokens  [host] int32[seq_off[n_seq]]   all sequences back to back
+ *   seq_off [host] int64[n_seq+1]          start of each sequence, ascending, seq_off[0] = 0
+ *   seq_key [host] int64[n_seq]            opaque key (user / item / group id) of each sequence
+ *   n_max   1..LASER_MAX_NGRAM
+ * Host work (sorting, hashing) runs inside the call; device copies are enqueued on `stream` and the
+ * call synchronises that stream before returning. Total tokens must stay below 2^32 - 1.
+ * The pool is immutable afterwards. *out is written only on success.
+ */
+int laser_pool_build(const int32_t* tokens, const int64_t* seq_off, const int64_t* seq_key,
+                     int64_t n_seq, int n_max, void* stream, laser_pool** out);
+int laser_pool_destroy(laser_pool* pool);
+
+/* Sizes of a built pool; any out pointer may be NULL. */
+int laser_pool_info(const laser_pool* pool, int64_t* n_tokens, int64_t* n_keys,
+                    int64_t* n_index_entries, int64_t* device_bytes);
+/* Copy regrouped tokens [start, start+count) to host memory (synchronous; for checks and tools). */
+int laser_pool_read_tokens(const laser_pool* pool, int64_t start, int64_t count, int32_t* out_host);
+
+/* laser_retrieve_drafts (Sec. 3.3): for each of B contexts, try n = min(n_max, valid tail length)
+ * down to n_min; at the first n whose n-gram occurs in the key's sub-pool, follow the most frequent
+ * successor (ties -> smaller token id) among the surviving occurrences for up to K tokens; accept
+ * that n if the chain has >= min_tokens tokens, otherwise keep the longest chain seen (ties ->
+ * larger n).
+ *   keys       [dev] int64[B]
+ *   ctx_tail   [dev] int32[B][n_max]  last n_max context tokens, right-aligned, -1 padded on the left
+ *   drafts     [dev] int32[B][K]      out: chain, -1 padded
+ *   draft_len  [dev] int32[B]         out: 0..K
+ *   match_n    [dev] int32[B]         out: suffix length used, 0 if nothing was found
+ *   pool_index [dev] int64[B]         out: smallest regrouped-pool position e of a surviving occurrence
+ *                                          (tokens e+1 .. e+draft_len are the drafts), -1 if none
+ * n_max must not exceed the pool's n_max; 1 <= n_min <= n_max; 0 <= K <= LASER_MAX_DRAFT; B >= 0.
+ * Results are exact (no hash false positives) and independent of scheduling.
+ */
+int laser_retrieve_drafts(const laser_pool* pool, const int64_t* keys, const int32_t* ctx_tail,
+                          int B, int n_min, int n_max, int K, int min_tokens,
+                          int32_t* drafts, int32_t* draft_len, int32_t* match_n,
+                          int64_t* pool_index, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Target model (Sec. 2.1 Eq. 1/3, Sec. 3.4 Eq. 6: the LLM that yields K+1 distributions per pass).
+ * Pre-norm decoder: RMSNorm, rotary positions (element i paired with i + head_dim/2), multi-head
+ * causal attention, SwiGLU FFN, no biases, untied embedding / output head.
+ * All weight pointers are [dev], row-major [out_features][in_features], bf16 unless noted, and
+ * must stay valid and unchanged while the handle lives.
+ */
+typedef struct laser_model_desc {
+    int32_t n_layers, d_model, n_heads, ffn, vocab;
+    int32_t max_rows;       /* largest B*(K+1) any call will use (sizes the workspace)            */
+    int32_t max_batch;      /* largest B                                                          */
+    int32_t max_pos;        /* positions 0..max_pos-1 get a RoPE table entry                      */
+    float   eps;            /* RMSNorm epsilon                                                    */
+    float   rope_base;
+    const uint16_t* wqkv;   /* [L][3d][d]  rows: query | key | value projection                   */
+    const uint16_t* wo;     /* [L][d][d]                                                          */
+    const uint16_t* wgu;    /* [L][2F][d]  rows: gate | up projection                             */
+    const uint16_t* wdown;  /* [L][d][F]                                                          */
+    const float*    g1;     /* [L][d] float32 pre-attention norm gain                             */
+    const float*    g2;     /* [L][d] float32 pre-FFN norm gain                                   */
+    const uint16_t* emb;    /* [V][d]                                                             */
+    const uint16_t* wlm;    /* [V][d]                                                             */
+    const float*    gf;     /* [d] float32 final norm gain                                        */
+} laser_model_desc;
+
+/* Supported: head_dim 64 or 128; d_model, ffn multiples of 128; vocab multiple of 16 (else
+ * LASER_E_SHAPE). Allocates workspace and the RoPE table; synchronises `stream`. n_layers may be 0
+ * (head-only use). */
+int laser_model_create(const laser_model_desc* desc, void* stream, laser_model** out);
+int laser_model_destroy(laser_model* model);
+
+/* ------------------------------------------------------------------------------------------------
+ * Paged KV cache. A sequence slot owns a list of pages (page_size tokens each); `len` tokens are
+ * committed, the next R slots are scratch for the step in flight. Pages are reserved from the host
+ * without reading device state: the library keeps, per slot, an upper bound of `len`.
+ */
+typedef struct laser_kv_desc {
+    int32_t n_layers, n_heads, head_dim;
+    int32_t page_size;          /* tokens per page: 16                                            */
+    int32_t n_pages;            /* pages in the pool (each page spans all layers and heads)       */
+    int32_t max_seqs;           /* sequence slots 0..max_seqs-1                                   */
+    int32_t max_pages_per_seq;
+} laser_kv_desc;
+
+int laser_kv_create(const laser_kv_desc* desc, void* stream, laser_kv** out);
+int laser_kv_destroy(laser_kv* kv);
+/* Make slot `seq` able to hold n_tokens tokens (committed + in flight). Grows only.
+ * LASER_E_OOM_PAGES if the pool or max_pages_per_seq cannot cover it (nothing changes then). */
+int laser_kv_seq_reserve(laser_kv* kv, int seq, int n_tokens, void* stream);
+/* Return the slot's pages to the pool and set its length to 0. */
+int laser_kv_seq_release(laser_kv* kv, int seq, void* stream);
+/* Load externally produced keys/values (already rotated) for tokens [0, n_tokens) of one layer:
+ * k, v [dev] fp16 [n_tokens][n_heads][head_dim]. Needs reserved capacity; does not change `len`. */
+int laser_kv_import(laser_kv* kv, int seq, int layer, const uint16_t* k, const uint16_t* v,
+                    int n_tokens, void* stream);
+/* Set the committed length of a slot (after laser_kv_import, or to roll back). */
+int laser_kv_seq_set_len(laser_kv* kv, int seq, int len, void* stream);
+/* Read back the committed lengths of B slots (synchronises `stream`) and tighten the host bounds. */
+int laser_kv_read_lens(laser_kv* kv, const int32_t* seq_ids /*[host] B*/, int B,
+                       int32_t* lens_out /*[host] B*/, void* stream);
+
+/* laser_verify_step (Eq. 3 / Eq. 6 forward, Eq. 4 / 7 / 8 acceptance, correction rule of Sec. 2.1).
+ * For sequence b, rows r = 0..K hold the tokens [pending[b], drafts[b][0..K-1]] at positions
+ * len+r; their keys/values go to cache slots len..len+K; row r attends to slots 0..len+r. The
+ * output head and the acceptance rule are fused: logits are not materialised unless logits_dbg is
+ * given. Drafts j >= draft_len[b] are padding (fed as token 0, never accepted).
+ *   seq_ids    [host] int32[B]      KV slots, all different
+ *   pending    [dev]  int32[B]      last emitted token of each sequence (not yet in the cache)
+ *   drafts     [dev]  int32[B][K]
+ *   draft_len  [dev]  int32[B]      0..K
+ *   topk 1..LASER_MAX_TOPK, p, mode: see LASER_MODE_*
+ *   accept_len [dev]  int32[B]      out: a = number of leading drafts accepted
+ *   out_tokens [dev]  int32[B][K+1] out: drafts 0..a-1, then argmax of row a (smallest id on ties),
+ *                                   then -1
+ *   logits_dbg [dev]  float[B][K+1][V] or NULL
+ * Needs (host bound of len) + K+1 <= reserved capacity for every slot, else LASER_E_OOM_PAGES.
+ * Does not change `len`: call laser_kv_commit.
+ */
+int laser_verify_step(laser_model* model, laser_kv* kv, const int32_t* seq_ids,
+                      const int32_t* pending, const int32_t* drafts, const int32_t* draft_len,
+                      int B, int K, int topk, float p, int mode,
+                      int32_t* accept_len, int32_t* out_tokens, float* logits_dbg, void* stream);
+
+/* Output head + acceptance alone, on given final-normed hidden states h [dev] fp16 [B][K+1][d]. */
+int laser_verify_head(laser_model* model, const uint16_t* h, const int32_t* drafts,
+                      const int32_t* draft_len, int B, int K, int topk, float p, int mode,
+                      int32_t* accept_len, int32_t* out_tokens, float* logits_dbg, void* stream);
+
+/* laser_kv_commit ("all drafted tokens after the failing position are discarded", Sec. 2.1):
+ * len[seq_ids[b]] += accept_len[b] + 1, i.e. the pending token and the accepted drafts become
+ * permanent; later slots are dead and get overwritten by the next step.
+ *   seq_ids [host] int32[B];  accept_len [dev] int32[B] (values 0..K of the verify call before it)
+ */
+int laser_kv_commit(laser_kv* kv, const int32_t* seq_ids, const int32_t* accept_len, int B,
+                    void* stream);
+
+/* Device-side bookkeeping between steps: append the emitted tokens out_tokens[b][0..accept_len[b]]
+ * to the context tail (keeping the last n_max tokens) and make the last of them the new pending
+ * token.  ctx_tail [dev] int32[B][n_max] in/out, pending [dev] int32[B] out. */
+int laser_ctx_advance(int32_t* ctx_tail, int32_t* pending, const int32_t* out_tokens,
+                      const int32_t* accept_len, int B, int K, int n_max, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LASER_H */

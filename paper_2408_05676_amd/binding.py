@@ -1,0 +1,288 @@
+"""ctypes marshalling for the C ABI declared in include/laser.h (same names, same arguments).
+
+There is no fallback of any kind: if liblaser.so is missing or a call fails, LaserError is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+MODE_RV, MODE_RV_OR_TOP1, MODE_TOPK_ONLY, MODE_TOPP_ONLY = 0, 1, 2, 3
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class LaserError(RuntimeError):
+    pass
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "liblaser.so")
+
+
+class _ModelDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "ffn", "vocab",
+                                         "max_rows", "max_batch", "max_pos")] + \
+               [("eps", C.c_float), ("rope_base", C.c_float)] + \
+               [(n, C.c_void_p) for n in ("wqkv", "wo", "wgu", "wdown", "g1", "g2", "emb", "wlm", "gf")]
+
+
+class _KVDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "n_heads", "head_dim", "page_size", "n_pages",
+                                         "max_seqs", "max_pages_per_seq")]
+
+
+def lib():
+    """Load liblaser.so once and declare the prototypes."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise LaserError(f"{path} is not built; run `python -m paper_2408_05676_amd.build` "
+                         "(or __graft_entry__.build()) first. There is no fallback path.")
+    L = C.CDLL(path)
+    vp, i32, i64, f32 = C.c_void_p, C.c_int, C.c_int64, C.c_float
+    L.laser_last_error.restype = C.c_char_p
+    L.laser_version.restype = C.c_char_p
+    protos = {
+        "laser_pool_build": [vp, vp, vp, i64, i32, vp, C.POINTER(vp)],
+        "laser_pool_destroy": [vp],
+        "laser_pool_info": [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)],
+        "laser_pool_read_tokens": [vp, i64, i64, vp],
+        "laser_retrieve_drafts": [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp],
+        "laser_model_create": [C.POINTER(_ModelDesc), vp, C.POINTER(vp)],
+        "laser_model_destroy": [vp],
+        "laser_kv_create": [C.POINTER(_KVDesc), vp, C.POINTER(vp)],
+        "laser_kv_destroy": [vp],
+        "laser_kv_seq_reserve": [vp, i32, i32, vp],
+        "laser_kv_seq_release": [vp, i32, vp],
+        "laser_kv_import": [vp, i32, i32, vp, vp, i32, vp],
+        "laser_kv_seq_set_len": [vp, i32, i32, vp],
+        "laser_kv_read_lens": [vp, vp, i32, vp, vp],
+        "laser_verify_step": [vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, i32, vp, vp, vp, vp],
+        "laser_verify_head": [vp, vp, vp, vp, i32, i32, i32, f32, i32, vp, vp, vp, vp],
+        "laser_kv_commit": [vp, vp, vp, i32, vp],
+        "laser_ctx_advance": [vp, vp, vp, vp, i32, i32, i32, vp],
+    }
+    for name, args in protos.items():
+        fn = getattr(L, name)
+        fn.argtypes = args
+        fn.restype = C.c_int
+    _LIB = L
+    return L
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise LaserError(f"{what} failed with code {rc}: {lib().laser_last_error().decode()}")
+
+
+def _stream(stream=None) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise LaserError(f"{name} must be a contiguous CUDA tensor of {dtype}")
+    return t.data_ptr()
+
+
+def _host_i32(a, name: str) -> np.ndarray:
+    arr = np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+    if arr.ndim != 1:
+        raise LaserError(f"{name} must be one-dimensional")
+    return arr
+
+
+class Pool:
+    """laser_pool_build / laser_pool_destroy."""
+
+    def __init__(self, tokens, seq_off, seq_key, n_max: int, stream=None):
+        tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+        seq_off = np.ascontiguousarray(seq_off, dtype=np.int64)
+        seq_key = np.ascontiguousarray(seq_key, dtype=np.int64)
+        if seq_off.size != seq_key.size + 1:
+            raise LaserError("seq_off must have n_seq + 1 entries")
+        if seq_key.size and int(seq_off[-1]) != tokens.size:
+            raise LaserError("seq_off[-1] must equal the number of tokens")
+        self._h = C.c_void_p()
+        self.n_max = n_max
+        _check(lib().laser_pool_build(tokens.ctypes.data, seq_off.ctypes.data, seq_key.ctypes.data,
+                                      seq_key.size, n_max, _stream(stream), C.byref(self._h)),
+               "laser_pool_build")
+
+    def info(self) -> dict:
+        v = [C.c_int64() for _ in range(4)]
+        _check(lib().laser_pool_info(self._h, *[C.byref(x) for x in v]), "laser_pool_info")
+        return dict(zip(("n_tokens", "n_keys", "n_index_entries", "device_bytes"), (x.value for x in v)))
+
+    def read_tokens(self, start: int, count: int) -> np.ndarray:
+        out = np.empty(count, dtype=np.int32)
+        _check(lib().laser_pool_read_tokens(self._h, start, count, out.ctypes.data), "laser_pool_read_tokens")
+        return out
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h:
+            lib().laser_pool_destroy(self._h)
+            self._h = C.c_void_p()
+
+    __del__ = close
+
+
+def retrieve_drafts(pool: Pool, keys: torch.Tensor, ctx_tail: torch.Tensor, n_min: int, n_max: int,
+                    K: int, min_tokens: int = 1, out=None, stream=None):
+    """laser_retrieve_drafts. Returns (drafts [B][K], draft_len [B], match_n [B], pool_index [B])."""
+    B = keys.shape[0]
+    if ctx_tail.shape != (B, n_max):
+        raise LaserError("ctx_tail must be [B][n_max]")
+    dev = keys.device
+    if out is None:
+        out = (torch.empty((B, K), dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+               torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int64, device=dev))
+    drafts, dl, mn, pi = out
+    _check(lib().laser_retrieve_drafts(pool._h, _dev(keys, torch.int64, "keys"), _dev(ctx_tail, torch.int32, "ctx_tail"),
+                                       B, n_min, n_max, K, min_tokens,
+                                       _dev(drafts, torch.int32, "drafts") if K > 0 else None,
+                                       _dev(dl, torch.int32, "draft_len"), _dev(mn, torch.int32, "match_n"),
+                                       _dev(pi, torch.int64, "pool_index"), _stream(stream)),
+           "laser_retrieve_drafts")
+    return drafts, dl, mn, pi
+
+
+class Model:
+    """laser_model_create / laser_model_destroy. `weights` maps the names of laser_model_desc to
+    CUDA tensors (bf16 matrices stacked over layers, float32 gains); they are borrowed, and kept
+    alive by this object."""
+
+    def __init__(self, n_layers, d_model, n_heads, ffn, vocab, weights: dict, max_rows: int, max_batch: int,
+                 max_pos: int, eps: float = 1e-6, rope_base: float = 10000.0, stream=None):
+        self.n_layers, self.d, self.n_heads, self.ffn, self.vocab = n_layers, d_model, n_heads, ffn, vocab
+        self.max_rows, self.max_batch = max_rows, max_batch
+        self._keep = dict(weights)
+        d = _ModelDesc(n_layers, d_model, n_heads, ffn, vocab, max_rows, max_batch, max_pos, eps, rope_base)
+        for name in ("wqkv", "wo", "wgu", "wdown", "emb", "wlm"):
+            t = weights.get(name)
+            if t is None:
+                if n_layers == 0 and name != "wlm":
+                    continue
+                raise LaserError(f"missing weight {name}")
+            setattr(d, name, _dev(t, torch.bfloat16, name))
+        for name in ("g1", "g2", "gf"):
+            t = weights.get(name)
+            if t is None:
+                if n_layers == 0:
+                    continue
+                raise LaserError(f"missing weight {name}")
+            setattr(d, name, _dev(t, torch.float32, name))
+        self._h = C.c_void_p()
+        _check(lib().laser_model_create(C.byref(d), _stream(stream), C.byref(self._h)), "laser_model_create")
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h:
+            lib().laser_model_destroy(self._h)
+            self._h = C.c_void_p()
+
+    __del__ = close
+
+
+class KVCache:
+    """laser_kv_create and the per-slot calls."""
+
+    def __init__(self, n_layers, n_heads, head_dim, n_pages, max_seqs, max_pages_per_seq, page_size=16,
+                 stream=None):
+        self.page_size = page_size
+        d = _KVDesc(n_layers, n_heads, head_dim, page_size, n_pages, max_seqs, max_pages_per_seq)
+        self._h = C.c_void_p()
+        _check(lib().laser_kv_create(C.byref(d), _stream(stream), C.byref(self._h)), "laser_kv_create")
+
+    def reserve(self, seq: int, n_tokens: int, stream=None):
+        _check(lib().laser_kv_seq_reserve(self._h, seq, n_tokens, _stream(stream)), "laser_kv_seq_reserve")
+
+    def release(self, seq: int, stream=None):
+        _check(lib().laser_kv_seq_release(self._h, seq, _stream(stream)), "laser_kv_seq_release")
+
+    def import_layer(self, seq: int, layer: int, k: torch.Tensor, v: torch.Tensor, stream=None):
+        n = k.shape[0]
+        _check(lib().laser_kv_import(self._h, seq, layer, _dev(k, torch.float16, "k"), _dev(v, torch.float16, "v"),
+                                     n, _stream(stream)), "laser_kv_import")
+
+    def set_len(self, seq: int, n: int, stream=None):
+        _check(lib().laser_kv_seq_set_len(self._h, seq, n, _stream(stream)), "laser_kv_seq_set_len")
+
+    def read_lens(self, seq_ids, stream=None) -> np.ndarray:
+        ids = _host_i32(seq_ids, "seq_ids")
+        out = np.empty(ids.size, dtype=np.int32)
+        _check(lib().laser_kv_read_lens(self._h, ids.ctypes.data, ids.size, out.ctypes.data, _stream(stream)),
+               "laser_kv_read_lens")
+        return out
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h:
+            lib().laser_kv_destroy(self._h)
+            self._h = C.c_void_p()
+
+    __del__ = close
+
+
+def verify_step(model: Model, kv: KVCache, seq_ids, pending: torch.Tensor, drafts: torch.Tensor,
+                draft_len: torch.Tensor, topk: int, p: float, mode: int = MODE_RV, want_logits: bool = False,
+                out=None, stream=None):
+    """laser_verify_step. Returns (accept_len [B], out_tokens [B][K+1], logits [B][K+1][V] or None)."""
+    ids = _host_i32(seq_ids, "seq_ids")
+    B, K = drafts.shape
+    dev = pending.device
+    if out is None:
+        out = (torch.empty(B, dtype=torch.int32, device=dev), torch.empty((B, K + 1), dtype=torch.int32, device=dev))
+    acc, toks = out
+    logits = torch.empty((B, K + 1, model.vocab), dtype=torch.float32, device=dev) if want_logits else None
+    _check(lib().laser_verify_step(model._h, kv._h, ids.ctypes.data, _dev(pending, torch.int32, "pending"),
+                                   _dev(drafts, torch.int32, "drafts") if K > 0 else None,
+                                   _dev(draft_len, torch.int32, "draft_len"), B, K, topk, p, mode,
+                                   _dev(acc, torch.int32, "accept_len"), _dev(toks, torch.int32, "out_tokens"),
+                                   logits.data_ptr() if want_logits else None, _stream(stream)),
+           "laser_verify_step")
+    return acc, toks, logits
+
+
+def verify_head(model: Model, h: torch.Tensor, drafts: torch.Tensor, draft_len: torch.Tensor, topk: int,
+                p: float, mode: int = MODE_RV, want_logits: bool = False, out=None, stream=None):
+    """laser_verify_head on final-normed hidden states h fp16 [B][K+1][d]."""
+    B, K = drafts.shape
+    if h.shape != (B, K + 1, model.d):
+        raise LaserError("h must be [B][K+1][d]")
+    dev = h.device
+    if out is None:
+        out = (torch.empty(B, dtype=torch.int32, device=dev), torch.empty((B, K + 1), dtype=torch.int32, device=dev))
+    acc, toks = out
+    logits = torch.empty((B, K + 1, model.vocab), dtype=torch.float32, device=dev) if want_logits else None
+    _check(lib().laser_verify_head(model._h, _dev(h, torch.float16, "h"),
+                                   _dev(drafts, torch.int32, "drafts") if K > 0 else None,
+                                   _dev(draft_len, torch.int32, "draft_len"), B, K, topk, p, mode,
+                                   _dev(acc, torch.int32, "accept_len"), _dev(toks, torch.int32, "out_tokens"),
+                                   logits.data_ptr() if want_logits else None, _stream(stream)),
+           "laser_verify_head")
+    return acc, toks, logits
+
+
+def kv_commit(kv: KVCache, seq_ids, accept_len: torch.Tensor, stream=None):
+    """laser_kv_commit."""
+    ids = _host_i32(seq_ids, "seq_ids")
+    _check(lib().laser_kv_commit(kv._h, ids.ctypes.data, _dev(accept_len, torch.int32, "accept_len"), ids.size,
+                                 _stream(stream)), "laser_kv_commit")
+
+
+def ctx_advance(ctx_tail: torch.Tensor, pending: torch.Tensor, out_tokens: torch.Tensor, accept_len: torch.Tensor,
+                stream=None):
+    """laser_ctx_advance."""
+    B, n_max = ctx_tail.shape
+    K = out_tokens.shape[1] - 1
+    _check(lib().laser_ctx_advance(_dev(ctx_tail, torch.int32, "ctx_tail"), _dev(pending, torch.int32, "pending"),
+                                   _dev(out_tokens, torch.int32, "out_tokens"), _dev(accept_len, torch.int32, "accept_len"),
+                                   B, K, n_max, _stream(stream)), "laser_ctx_advance")

@@ -1,0 +1,244 @@
+// Fused output head + acceptance (Sec. 3.4 Eq. 7-8; greedy Eq. 4; correction rule of Sec. 2.1).
+//
+// Pass 1 (lm_head_kernel): every wavefront owns a contiguous chunk of the vocabulary, streams those
+// rows of the head matrix once through the matrix cores against all verified rows, and keeps, per
+// row, running softmax statistics (max, sum of exp), the arg-max (smaller id on ties), the logit of
+// the row's draft token, and its chunk's best LASER_MAX_TOPK (logit, id) pairs -- all in registers.
+// Logits are never written unless a debug buffer is passed.
+// Pass 2 (accept_kernel): one block per sequence merges the per-chunk partials. The draft's rank is
+// the number of partial-list entries ordered before it; if a chunk hides an entry that precedes the
+// draft, that chunk already contributes >= LASER_MAX_TOPK >= k listed ones, so "rank < k" is exact.
+// The block then scans the rows left to right and emits accepted drafts plus the correction token.
+#include <cmath>
+
+#include "gemm_skinny.h"
+#include "state.h"
+
+namespace laser {
+
+constexpr int KT = LASER_MAX_TOPK;
+
+struct HeadArgs {
+    const uint16_t* W; const uint16_t* H; int M, V, d, tiles_per_wave, chunks;
+    const int32_t* row_x;
+    float* hp_max; float* hp_sum; int32_t* hp_arg; float* hp_topv; int32_t* hp_topi; float* hp_lx;
+    float* logits_dbg;
+};
+
+__global__ void head_rows_kernel(const int32_t* drafts, const int32_t* draft_len, int B, int K, int vocab,
+                                 int32_t* row_x, float* hp_lx) {
+    const int m = blockIdx.x * blockDim.x + threadIdx.x, R = K + 1;
+    if (m >= B * R) return;
+    const int b = m / R, r = m % R;
+    int x = (r < K && r < draft_len[b]) ? drafts[(size_t)b * K + r] : -1;
+    if (x >= vocab) x = -1;
+    row_x[m] = x;
+    hp_lx[m] = -INFINITY;
+}
+
+// ordering of (logit, id): larger logit first, smaller id on ties
+__device__ inline bool before(float v, int i, float w, int j) { return v > w || (v == w && i < j); }
+
+struct RowStat {
+    float mx, sum, lx;
+    int arg;
+    float tv[KT];
+    int ti[KT];
+    __device__ void init() {
+        mx = -INFINITY; sum = 0.f; lx = -INFINITY; arg = 0x7FFFFFFF;
+#pragma unroll
+        for (int j = 0; j < KT; ++j) { tv[j] = -INFINITY; ti[j] = 0x7FFFFFFF; }
+    }
+    __device__ void push_top(float v, int n) {
+        if (!before(v, n, tv[KT - 1], ti[KT - 1])) return;
+        tv[KT - 1] = v; ti[KT - 1] = n;
+#pragma unroll
+        for (int j = KT - 1; j > 0; --j) {
+            if (before(tv[j], ti[j], tv[j - 1], ti[j - 1])) {
+                float fv = tv[j]; tv[j] = tv[j - 1]; tv[j - 1] = fv;
+                int fi = ti[j]; ti[j] = ti[j - 1]; ti[j - 1] = fi;
+            }
+        }
+    }
+    __device__ void add(float v, int n) {
+        if (v > mx) { sum = sum * __expf(mx - v) + 1.f; mx = v; arg = n; }   // ids arrive ascending per lane
+        else sum += __expf(v - mx);
+        push_top(v, n);
+    }
+    __device__ void merge_from_lane(int src_xor) {
+        const float omx = __shfl_xor(mx, src_xor), osum = __shfl_xor(sum, src_xor), olx = __shfl_xor(lx, src_xor);
+        const int oarg = __shfl_xor(arg, src_xor);
+        float otv[KT]; int oti[KT];
+#pragma unroll
+        for (int j = 0; j < KT; ++j) { otv[j] = __shfl_xor(tv[j], src_xor); oti[j] = __shfl_xor(ti[j], src_xor); }
+        const float M = fmaxf(mx, omx);
+        if (M != -INFINITY) sum = sum * __expf(mx - M) + osum * __expf(omx - M);
+        if (before(omx, oarg, mx, arg)) arg = oarg;
+        mx = M;
+        lx = fmaxf(lx, olx);
+#pragma unroll
+        for (int j = 0; j < KT; ++j) push_top(otv[j], oti[j]);
+    }
+};
+
+template <int MB>
+__global__ __launch_bounds__(256) void lm_head_kernel(HeadArgs a) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r = lane & 15, g = lane >> 4;
+    const int chunk = blockIdx.x * 4 + wave;
+    if (chunk >= a.chunks) return;
+    const int ntiles = a.V / 16;
+    const int t0 = chunk * a.tiles_per_wave, t1 = min(ntiles, t0 + a.tiles_per_wave);
+    const int row0 = blockIdx.y * MB * 16;
+
+    RowStat st[MB];
+    int x[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        st[mb].init();
+        const int row = row0 + mb * 16 + r;
+        x[mb] = row < a.M ? a.row_x[row] : -1;
+    }
+    for (int t = t0; t < t1; ++t) {
+        float4_t acc[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) acc[mb] = float4_t{0.f, 0.f, 0.f, 0.f};
+        wave_gemm_tile<MB>(a.W + (size_t)t * 16 * a.d, (size_t)a.d, a.H, a.d, a.M, row0, 0, a.d, acc);
+        const int n = t * 16 + 4 * g;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                st[mb].add(acc[mb][i], n + i);
+                if (n + i == x[mb]) st[mb].lx = acc[mb][i];
+            }
+            const int row = row0 + mb * 16 + r;
+            if (a.logits_dbg && row < a.M)
+                *reinterpret_cast<float4*>(a.logits_dbg + (size_t)row * a.V + n) =
+                    make_float4(acc[mb][0], acc[mb][1], acc[mb][2], acc[mb][3]);
+        }
+    }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        st[mb].merge_from_lane(16);
+        st[mb].merge_from_lane(32);
+        const int row = row0 + mb * 16 + r;
+        if (g == 0 && row < a.M) {
+            const size_t o = (size_t)row * a.chunks + chunk;
+            a.hp_max[o] = st[mb].mx; a.hp_sum[o] = st[mb].sum; a.hp_arg[o] = st[mb].arg;
+#pragma unroll
+            for (int j = 0; j < KT; ++j) { a.hp_topv[o * KT + j] = st[mb].tv[j]; a.hp_topi[o * KT + j] = st[mb].ti[j]; }
+            if (st[mb].lx != -INFINITY) a.hp_lx[row] = st[mb].lx;
+        }
+    }
+}
+
+struct AcceptArgs {
+    const float* hp_max; const float* hp_sum; const int32_t* hp_arg; const float* hp_topv; const int32_t* hp_topi;
+    const float* hp_lx; const int32_t* row_x; const int32_t* drafts; const int32_t* draft_len;
+    int K, chunks, topk, mode; float p;
+    int32_t* accept_len; int32_t* out_tokens;
+};
+
+__global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
+    __shared__ float s_f[4][3];
+    __shared__ int s_i[4][2];
+    __shared__ int row_ok[LASER_MAX_DRAFT + 1], row_arg[LASER_MAX_DRAFT + 1];
+    const int b = blockIdx.x, R = a.K + 1;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int r = 0; r < R; ++r) {
+        const int row = b * R + r;
+        const int x = a.row_x[row];
+        const float lx = a.hp_lx[row];
+        float mx = -INFINITY, sum = 0.f;
+        int arg = 0x7FFFFFFF, ahead = 0;
+        for (int c = threadIdx.x; c < a.chunks; c += 256) {
+            const size_t o = (size_t)row * a.chunks + c;
+            const float cm = a.hp_max[o], cs = a.hp_sum[o];
+            const int ca = a.hp_arg[o];
+            const float M = fmaxf(mx, cm);
+            sum = sum * __expf(mx - M) + cs * __expf(cm - M);
+            if (before(cm, ca, mx, arg)) arg = ca;
+            mx = M;
+            if (x >= 0)
+#pragma unroll
+                for (int j = 0; j < KT; ++j) {
+                    const float v = a.hp_topv[o * KT + j];
+                    const int i = a.hp_topi[o * KT + j];
+                    ahead += (i != x && before(v, i, lx, x)) ? 1 : 0;
+                }
+        }
+        for (int off = 32; off > 0; off >>= 1) {
+            const float omx = __shfl_xor(mx, off), osum = __shfl_xor(sum, off);
+            const int oarg = __shfl_xor(arg, off);
+            ahead += __shfl_xor(ahead, off);
+            const float M = fmaxf(mx, omx);
+            if (M != -INFINITY) sum = sum * __expf(mx - M) + osum * __expf(omx - M);
+            if (before(omx, oarg, mx, arg)) arg = oarg;
+            mx = M;
+        }
+        __syncthreads();
+        if (lane == 0) { s_f[wave][0] = mx; s_f[wave][1] = sum; s_i[wave][0] = arg; s_i[wave][1] = ahead; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float M = -INFINITY, S = 0.f; int A = 0x7FFFFFFF, rank = 0;
+            for (int w = 0; w < 4; ++w) {
+                const float wm = s_f[w][0];
+                const float nm = fmaxf(M, wm);
+                if (nm != -INFINITY) S = S * __expf(M - nm) + s_f[w][1] * __expf(wm - nm);
+                if (before(wm, s_i[w][0], M, A)) A = s_i[w][0];
+                M = nm;
+                rank += s_i[w][1];
+            }
+            bool ok = false;
+            if (x >= 0) {
+                const float q = __expf(lx - M) / S;
+                const bool in_k = rank < a.topk, above = q > a.p, top1 = rank == 0;
+                ok = a.mode == LASER_MODE_RV ? (in_k && above)
+                   : a.mode == LASER_MODE_RV_OR_TOP1 ? (top1 || (in_k && above))
+                   : a.mode == LASER_MODE_TOPK_ONLY ? in_k : (top1 || above);
+            }
+            row_ok[r] = ok ? 1 : 0;
+            row_arg[r] = A;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int dl = a.draft_len[b];
+        dl = dl < 0 ? 0 : (dl > a.K ? a.K : dl);
+        int n = 0;
+        while (n < dl && row_ok[n]) ++n;
+        a.accept_len[b] = n;
+        int32_t* out = a.out_tokens + (size_t)b * R;
+        for (int j = 0; j < R; ++j) out[j] = j < n ? a.drafts[(size_t)b * a.K + j] : (j == n ? row_arg[n] : -1);
+    }
+}
+
+int run_head(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len, int B, int K,
+             int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, float* logits_dbg,
+             hipStream_t stream) {
+    const int R = K + 1, M = B * R;
+    hipLaunchKernelGGL(head_rows_kernel, dim3((M + 255) / 256), dim3(256), 0, stream, drafts, draft_len, B, K,
+                       m->d.vocab, m->row_x, m->hp_lx);
+    const int ntiles = m->d.vocab / 16;
+    const int tpw = (ntiles + 1023) / 1024;
+    HeadArgs a{m->d.wlm, h, M, m->d.vocab, m->d.d_model, tpw, m->head_chunks, m->row_x,
+               m->hp_max, m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx, logits_dbg};
+    const int mblocks = (M + 15) / 16;
+    const int MB = mblocks >= 4 ? 4 : mblocks;
+    const int passes = (mblocks + MB - 1) / MB;
+    dim3 grid((unsigned)((m->head_chunks + 3) / 4), (unsigned)passes);
+    switch (MB) {
+        case 1: hipLaunchKernelGGL(lm_head_kernel<1>, grid, dim3(256), 0, stream, a); break;
+        case 2: hipLaunchKernelGGL(lm_head_kernel<2>, grid, dim3(256), 0, stream, a); break;
+        case 3: hipLaunchKernelGGL(lm_head_kernel<3>, grid, dim3(256), 0, stream, a); break;
+        default: hipLaunchKernelGGL(lm_head_kernel<4>, grid, dim3(256), 0, stream, a); break;
+    }
+    AcceptArgs aa{m->hp_max, m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx, m->row_x, drafts, draft_len,
+                  K, m->head_chunks, topk, mode, p, accept_len, out_tokens};
+    hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(256), 0, stream, aa);
+    LASER_HIP_CHECK(hipGetLastError());
+    return LASER_OK;
+}
+
+}  // namespace laser

@@ -1,0 +1,522 @@
+// Verify forward of the target model (Sec. 2.1 Eq. 3, Sec. 3.4 Eq. 6): R = K+1 rows per sequence
+// against the paged KV cache. Generic kernel set: works for any row count; the shapes it is tuned
+// for are the few-row, weight-streaming ones.
+#include <cmath>
+#include <vector>
+
+#include "gemm_skinny.h"
+#include "state.h"
+
+namespace laser {
+
+int run_head(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len, int B, int K,
+             int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, float* logits_dbg,
+             hipStream_t stream);
+
+// ------------------------------------------------------------------------------------------------
+__device__ inline float block_sum_256(float v, float* sm /*[4]*/) {
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    const int w = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sm[w] = v;
+    __syncthreads();
+    return sm[0] + sm[1] + sm[2] + sm[3];
+}
+
+// One block per row: token lookup, embedding gather, first RMSNorm, row position.
+__global__ __launch_bounds__(256) void embed_rmsnorm_kernel(
+    const uint16_t* __restrict__ emb, const float* __restrict__ gain, const int32_t* __restrict__ pending,
+    const int32_t* __restrict__ drafts, const int32_t* __restrict__ draft_len, const int32_t* __restrict__ seq_ids,
+    const int32_t* __restrict__ lens, int R, int d, int vocab, float eps,
+    float* __restrict__ x, uint16_t* __restrict__ xn, int32_t* __restrict__ row_pos) {
+    __shared__ float sm[4];
+    const int m = blockIdx.x, b = m / R, r = m % R, K = R - 1;
+    int tok = r == 0 ? pending[b] : ((r - 1) < draft_len[b] ? drafts[(size_t)b * K + r - 1] : 0);
+    if (tok < 0 || tok >= vocab) tok = 0;
+    if (threadIdx.x == 0) row_pos[m] = lens[seq_ids[b]] + r;
+    const uint16_t* e = emb + (size_t)tok * d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += 256) { float v = bf16_to_f32(e[i]); ss += v * v; }
+    ss = block_sum_256(ss, sm);
+    const float rs = rsqrtf(ss / (float)d + eps);
+    for (int i = threadIdx.x; i < d; i += 256) {
+        float v = bf16_to_f32(e[i]);
+        x[(size_t)m * d + i] = v;
+        xn[(size_t)m * d + i] = f32_to_f16(v * rs * gain[i]);
+    }
+}
+
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
+                                                      int d, float eps, uint16_t* __restrict__ xn) {
+    __shared__ float sm[4];
+    const size_t m = blockIdx.x;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += 256) { float v = x[m * d + i]; ss += v * v; }
+    ss = block_sum_256(ss, sm);
+    const float rs = rsqrtf(ss / (float)d + eps);
+    for (int i = threadIdx.x; i < d; i += 256) xn[m * d + i] = f32_to_f16(x[m * d + i] * rs * gain[i]);
+}
+
+// ------------------------------------------------------------------------------------------------
+enum { EPI_F32 = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
+
+struct GemmArgs {
+    const uint16_t* W;      // [N][Kd]  (EPI_SWIGLU: [2N][Kd], gate rows then up rows)
+    const uint16_t* X;      // [M][Kd]
+    int M, N, Kd, S;
+    float* outf;            // EPI_F32: [M][N] store;  EPI_RESID: [M][N] accumulate
+    uint16_t* outh;         // EPI_SWIGLU: [M][N] fp16
+};
+
+template <int MB, int EPI>
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
+    constexpr int NA = EPI == EPI_SWIGLU ? 2 : 1;
+    __shared__ float red[4][NA][MB][4][64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int unit = blockIdx.x * 4 + wave;
+    const int tile = unit / a.S, ks = unit % a.S;
+    const int ntiles = a.N / 16;
+    const int row0 = blockIdx.y * MB * 16;
+    const bool active = tile < ntiles;
+    const int ksteps = a.Kd / kGemmKStep;
+    const int per = (ksteps + a.S - 1) / a.S;
+    const int kbeg = ks * per * kGemmKStep;
+    const int kend = min(a.Kd, kbeg + per * kGemmKStep);
+
+    float4_t acc[NA][MB];
+#pragma unroll
+    for (int s = 0; s < NA; ++s)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) acc[s][mb] = float4_t{0.f, 0.f, 0.f, 0.f};
+    if (active) {
+        wave_gemm_tile<MB>(a.W + (size_t)tile * 16 * a.Kd, (size_t)a.Kd, a.X, a.Kd, a.M, row0, kbeg, kend, acc[0]);
+        if (NA == 2)
+            wave_gemm_tile<MB>(a.W + ((size_t)a.N + (size_t)tile * 16) * a.Kd, (size_t)a.Kd, a.X, a.Kd, a.M, row0,
+                               kbeg, kend, acc[NA - 1]);
+    }
+    if (a.S > 1) {
+#pragma unroll
+        for (int s = 0; s < NA; ++s)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) red[wave][s][mb][i][lane] = acc[s][mb][i];
+        __syncthreads();
+        if (ks == 0) {
+            for (int o = 1; o < a.S; ++o)
+#pragma unroll
+                for (int s = 0; s < NA; ++s)
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) acc[s][mb][i] += red[wave + o][s][mb][i][lane];
+        }
+    }
+    if (!active || ks != 0) return;
+    const int r = lane & 15, g = lane >> 4;
+    const int n = tile * 16 + 4 * g;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        const int row = row0 + mb * 16 + r;
+        if (row >= a.M) continue;
+        if (EPI == EPI_F32) {
+            *reinterpret_cast<float4*>(a.outf + (size_t)row * a.N + n) =
+                make_float4(acc[0][mb][0], acc[0][mb][1], acc[0][mb][2], acc[0][mb][3]);
+        } else if (EPI == EPI_RESID) {
+            float4* p = reinterpret_cast<float4*>(a.outf + (size_t)row * a.N + n);
+            float4 v = *p;
+            v.x += acc[0][mb][0]; v.y += acc[0][mb][1]; v.z += acc[0][mb][2]; v.w += acc[0][mb][3];
+            *p = v;
+        } else {
+            Frag4 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float gt = acc[0][mb][i], up = acc[NA - 1][mb][i];
+                o.h[i] = f32_to_f16(gt / (1.f + __expf(-gt)) * up);
+            }
+            *reinterpret_cast<uint2*>(a.outh + (size_t)row * a.N + n) = o.u;
+        }
+    }
+}
+
+template <int EPI>
+static int launch_gemm(const GemmArgs& a0, hipStream_t stream) {
+    GemmArgs a = a0;
+    const int ntiles = a.N / 16;
+    const int mblocks = (a.M + 15) / 16;
+    const int MB = mblocks >= 5 ? 5 : mblocks;
+    const int passes = (mblocks + MB - 1) / MB;
+    int S = 1;
+    while (S < 4 && (long)ntiles * passes * S < 2048 && (a.Kd / kGemmKStep) >= 2 * S * 2) S *= 2;
+    a.S = S;
+    dim3 grid((unsigned)((ntiles * S + 3) / 4), (unsigned)passes);
+    switch (MB) {
+        case 1: hipLaunchKernelGGL((gemm_skinny_kernel<1, EPI>), grid, dim3(256), 0, stream, a); break;
+        case 2: hipLaunchKernelGGL((gemm_skinny_kernel<2, EPI>), grid, dim3(256), 0, stream, a); break;
+        case 3: hipLaunchKernelGGL((gemm_skinny_kernel<3, EPI>), grid, dim3(256), 0, stream, a); break;
+        case 4: hipLaunchKernelGGL((gemm_skinny_kernel<4, EPI>), grid, dim3(256), 0, stream, a); break;
+        default: hipLaunchKernelGGL((gemm_skinny_kernel<5, EPI>), grid, dim3(256), 0, stream, a); break;
+    }
+    LASER_HIP_CHECK(hipGetLastError());
+    return LASER_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// One block per row: rotate q and k, store q (fp16) and the row's k, v into its cache slot.
+struct RopeArgs {
+    const float* qkv; const int32_t* row_pos; const int32_t* seq_ids; const int32_t* block_table;
+    const float2* rope; uint16_t* q; uint16_t* kpages; uint16_t* vpages;
+    int R, d, H, dh, mpps, layer, n_pages;
+};
+
+__global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a) {
+    const int m = blockIdx.x, b = m / a.R;
+    const int pos = a.row_pos[m];
+    const int pg = a.block_table[(size_t)a.seq_ids[b] * a.mpps + pos / kPageSize], tp = pos % kPageSize;
+    const int half = a.dh / 2;
+    const float* row = a.qkv + (size_t)m * 3 * a.d;
+    for (int idx = threadIdx.x; idx < a.d / 2; idx += 256) {
+        const int h = idx / half, i = idx % half;
+        const float2 cs = a.rope[(size_t)pos * half + i];
+        const int c0 = h * a.dh + i, c1 = c0 + half;
+        const float qa = row[c0], qb = row[c1];
+        a.q[(size_t)m * a.d + c0] = f32_to_f16(qa * cs.x - qb * cs.y);
+        a.q[(size_t)m * a.d + c1] = f32_to_f16(qa * cs.y + qb * cs.x);
+        const float ka = row[a.d + c0], kb = row[a.d + c1];
+        const size_t base = (((size_t)a.layer * a.n_pages + pg) * a.H + h) * kPageSize * a.dh;
+        a.kpages[base + (size_t)tp * a.dh + i] = f32_to_f16(ka * cs.x - kb * cs.y);
+        a.kpages[base + (size_t)tp * a.dh + i + half] = f32_to_f16(ka * cs.y + kb * cs.x);
+        a.vpages[base + (size_t)i * kPageSize + tp] = f32_to_f16(row[2 * a.d + c0]);
+        a.vpages[base + (size_t)(i + half) * kPageSize + tp] = f32_to_f16(row[2 * a.d + c1]);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Attention of the R new rows of one (sequence, head) over cache + new slots, one 16-token page per
+// wave step, online softmax, optional split over the context (partials merged by attn_combine).
+struct AttnArgs {
+    const uint16_t* q; const uint16_t* kpages; const uint16_t* vpages;
+    const int32_t* seq_ids; const int32_t* lens; const int32_t* block_table;
+    uint16_t* out; float* part;
+    int R, d, H, mpps, layer, n_pages, nsplit, nqt;
+    float scale;
+};
+
+template <int DH>
+__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
+    constexpr int NC32 = DH / 32, NC16 = DH / 16;
+    __shared__ float sm_m[4][16], sm_l[4][16];
+    __shared__ float sm_o[4][16][DH];
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int split = blockIdx.z % a.nsplit, qt = blockIdx.z / a.nsplit;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r = lane & 15, g = lane >> 4;
+    const int slot = a.seq_ids[b];
+    const int len = a.lens[slot];
+    const int qrow = qt * 16 + r;                       // this lane's query row in the S^T layout
+    const int rows_here = min(a.R - qt * 16, 16);
+    const int last_tok = len + qt * 16 + rows_here - 1;  // last slot any row of this tile may see
+    const int npages = last_tok / kPageSize + 1;
+    const int pps = (npages + a.nsplit - 1) / a.nsplit;
+    const int p0 = split * pps, p1 = min(npages, p0 + pps);
+
+    Frag8 bq[NC32];
+    {
+        const int rowc = min(qrow, a.R - 1);
+        const uint16_t* qp = a.q + ((size_t)b * a.R + rowc) * a.d + (size_t)h * DH + g * 8;
+#pragma unroll
+        for (int c = 0; c < NC32; ++c) bq[c].u = *reinterpret_cast<const uint4*>(qp + c * 32);
+    }
+    float m_run = -INFINITY, l_run = 0.f;
+    float4_t acc[NC16];
+#pragma unroll
+    for (int c = 0; c < NC16; ++c) acc[c] = float4_t{0.f, 0.f, 0.f, 0.f};
+    const int32_t* bt = a.block_table + (size_t)slot * a.mpps;
+
+    for (int p = p0 + wave; p < p1; p += 4) {
+        const int pg = bt[p];
+        const size_t base = (((size_t)a.layer * a.n_pages + pg) * a.H + h) * kPageSize * DH;
+        const uint16_t* kp = a.kpages + base + (size_t)r * DH + g * 8;
+        float4_t s = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < NC32; ++c) {
+            Frag8 ak;
+            ak.u = *reinterpret_cast<const uint4*>(kp + c * 32);
+            s = mfma_16x16x32(ak, bq[c], s);            // s[i] = K[tok 4g+i] . Q[row r]
+        }
+        float sv[4], mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int t = p * kPageSize + 4 * g + i;
+            const bool vis = (qrow < a.R) && (t <= len + qrow);
+            sv[i] = vis ? s[i] * a.scale : -INFINITY;
+            mx = fmaxf(mx, sv[i]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = (m_new == -INFINITY) ? 1.f : __expf(m_run - m_new);   // m_run = -inf -> 0
+        Frag4 pa;
+        float rs = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float pv = (sv[i] == -INFINITY) ? 0.f : __expf(sv[i] - m_new);
+            rs += pv;
+            pa.h[i] = f32_to_f16(pv);
+        }
+        rs += __shfl_xor(rs, 16);
+        rs += __shfl_xor(rs, 32);
+        l_run = l_run * alpha + rs;
+        m_run = m_new;
+        float al[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) al[i] = __shfl(alpha, 4 * g + i);     // accumulator rows are q = 4g+i
+        const uint16_t* vp = a.vpages + base + (size_t)r * kPageSize + 4 * g;
+#pragma unroll
+        for (int c = 0; c < NC16; ++c) {
+            Frag4 bv;
+            bv.u = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * kPageSize);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[c][i] *= al[i];
+            acc[c] = mfma_16x16x16(pa, bv, acc[c]);     // acc[c][i] = O[q 4g+i][channel 16c + r]
+        }
+    }
+    // ---- merge the four waves ----
+    if (g == 0) { sm_m[wave][r] = m_run; sm_l[wave][r] = l_run; }
+#pragma unroll
+    for (int c = 0; c < NC16; ++c)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sm_o[wave][4 * g + i][c * 16 + r] = acc[c][i];
+    __syncthreads();
+    float* part = a.part + ((((size_t)b * a.H + h) * a.nqt + qt) * a.nsplit + split) * (32 + 16 * DH);
+    for (int idx = threadIdx.x; idx < 16 * DH; idx += 256) {
+        const int q = idx / DH, c = idx % DH;
+        float M = fmaxf(fmaxf(sm_m[0][q], sm_m[1][q]), fmaxf(sm_m[2][q], sm_m[3][q]));
+        float L = 0.f, O = 0.f;
+        if (M != -INFINITY) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float f = __expf(sm_m[w][q] - M);
+                L += sm_l[w][q] * f;
+                O += sm_o[w][q][c] * f;
+            }
+        }
+        if (a.nsplit == 1) {
+            const int row = qt * 16 + q;
+            if (row < a.R) a.out[((size_t)b * a.R + row) * a.d + (size_t)h * DH + c] = f32_to_f16(L > 0.f ? O / L : 0.f);
+        } else {
+            if (c == 0) { part[q] = M; part[16 + q] = L; }
+            part[32 + idx] = O;
+        }
+    }
+}
+
+template <int DH>
+__global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
+    const int h = blockIdx.x, b = blockIdx.y / a.nqt, qt = blockIdx.y % a.nqt;
+    const float* part = a.part + (((size_t)b * a.H + h) * a.nqt + qt) * a.nsplit * (32 + 16 * DH);
+    for (int idx = threadIdx.x; idx < 16 * DH; idx += 256) {
+        const int q = idx / DH, c = idx % DH;
+        const int row = qt * 16 + q;
+        if (row >= a.R) continue;
+        float M = -INFINITY;
+        for (int s = 0; s < a.nsplit; ++s) M = fmaxf(M, part[(size_t)s * (32 + 16 * DH) + q]);
+        float L = 0.f, O = 0.f;
+        if (M != -INFINITY)
+            for (int s = 0; s < a.nsplit; ++s) {
+                const float* ps = part + (size_t)s * (32 + 16 * DH);
+                const float f = __expf(ps[q] - M);
+                L += ps[16 + q] * f;
+                O += ps[32 + idx] * f;
+            }
+        a.out[((size_t)b * a.R + row) * a.d + (size_t)h * DH + c] = f32_to_f16(L > 0.f ? O / L : 0.f);
+    }
+}
+
+__global__ void rope_table_kernel(float2* tab, int max_pos, int half, int dh, double base) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)max_pos * half) return;
+    const int pos = (int)(i / half), j = (int)(i % half);
+    const double ang = (double)pos * pow(base, -2.0 * (double)j / (double)dh);
+    tab[i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+// ------------------------------------------------------------------------------------------------
+static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, const int32_t* drafts,
+                   const int32_t* draft_len, int B, int K, int max_len_ub, hipStream_t stream) {
+    const laser_model_desc& d = m->d;
+    const int R = K + 1, M = B * R, dm = d.d_model, F = d.ffn;
+    hipLaunchKernelGGL(embed_rmsnorm_kernel, dim3(M), dim3(256), 0, stream, d.emb, d.g1, pending, drafts, draft_len,
+                       ids_dev, kv->len, R, dm, d.vocab, d.eps, m->x, m->xn, m->row_pos);
+    const int nqt = (R + 15) / 16;
+    const int npages_ub = (max_len_ub + R + kPageSize - 1) / kPageSize;
+    int nsplit = (1024 + d.n_heads * B * nqt - 1) / (d.n_heads * B * nqt);
+    nsplit = std::max(1, std::min(nsplit, (npages_ub + 3) / 4));
+    const size_t part_need = (size_t)B * d.n_heads * nqt * nsplit * (32 + 16 * m->dh);
+    if (nsplit > 1 && part_need > m->att_part_floats) {
+        if (m->att_part) LASER_HIP_CHECK(hipFree(m->att_part));
+        m->att_part = nullptr;
+        LASER_HIP_CHECK(hipMalloc((void**)&m->att_part, part_need * 4));
+        m->att_part_floats = part_need;
+    }
+    for (int l = 0; l < d.n_layers; ++l) {
+        int rc;
+        if (l > 0)
+            hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.g1 + (size_t)l * dm, dm, d.eps, m->xn);
+        GemmArgs g{d.wqkv + (size_t)l * 3 * dm * dm, m->xn, M, 3 * dm, dm, 1, m->qkv, nullptr};
+        if ((rc = launch_gemm<EPI_F32>(g, stream))) return rc;
+        RopeArgs ra{m->qkv, m->row_pos, ids_dev, kv->block_table, m->rope, m->q, kv->kpages, kv->vpages,
+                    R, dm, d.n_heads, m->dh, kv->d.max_pages_per_seq, l, kv->d.n_pages};
+        hipLaunchKernelGGL(rope_kv_kernel, dim3(M), dim3(256), 0, stream, ra);
+        AttnArgs aa{m->q, kv->kpages, kv->vpages, ids_dev, kv->len, kv->block_table, m->attn, m->att_part,
+                    R, dm, d.n_heads, kv->d.max_pages_per_seq, l, kv->d.n_pages, nsplit, nqt, 1.0f / sqrtf((float)m->dh)};
+        dim3 ag(d.n_heads, B, nsplit * nqt);
+        if (m->dh == 128) hipLaunchKernelGGL(attn_kernel<128>, ag, dim3(256), 0, stream, aa);
+        else hipLaunchKernelGGL(attn_kernel<64>, ag, dim3(256), 0, stream, aa);
+        if (nsplit > 1) {
+            dim3 cg(d.n_heads, B * nqt);
+            if (m->dh == 128) hipLaunchKernelGGL(attn_combine_kernel<128>, cg, dim3(256), 0, stream, aa);
+            else hipLaunchKernelGGL(attn_combine_kernel<64>, cg, dim3(256), 0, stream, aa);
+        }
+        GemmArgs go{d.wo + (size_t)l * dm * dm, m->attn, M, dm, dm, 1, m->x, nullptr};
+        if ((rc = launch_gemm<EPI_RESID>(go, stream))) return rc;
+        hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.g2 + (size_t)l * dm, dm, d.eps, m->xn);
+        GemmArgs gg{d.wgu + (size_t)l * 2 * F * dm, m->xn, M, F, dm, 1, nullptr, m->act};
+        if ((rc = launch_gemm<EPI_SWIGLU>(gg, stream))) return rc;
+        GemmArgs gd{d.wdown + (size_t)l * dm * F, m->act, M, dm, F, 1, m->x, nullptr};
+        if ((rc = launch_gemm<EPI_RESID>(gd, stream))) return rc;
+    }
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.gf, dm, d.eps, m->xn);
+    LASER_HIP_CHECK(hipGetLastError());
+    return LASER_OK;
+}
+
+}  // namespace laser
+
+using namespace laser;
+
+extern "C" int laser_model_destroy(laser_model* h) {
+    if (!h) return LASER_OK;
+    Model* m = reinterpret_cast<Model*>(h);
+    void* ptrs[] = {m->x, m->xn, m->qkv, m->q, m->attn, m->act, m->row_pos, m->att_part, m->rope, m->hp_max,
+                    m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx, m->row_x};
+    for (void* p : ptrs) if (p) (void)hipFree(p);
+    delete m;
+    return LASER_OK;
+}
+
+extern "C" int laser_model_create(const laser_model_desc* desc, void* stream_, laser_model** out) {
+    LASER_REQUIRE(desc && out, LASER_E_INVALID_ARG, "NULL argument");
+    const laser_model_desc& d = *desc;
+    hipStream_t stream = (hipStream_t)stream_;
+    LASER_REQUIRE(d.n_layers >= 0 && d.d_model > 0 && d.n_heads > 0 && d.vocab > 0 && d.max_rows > 0 && d.max_batch > 0,
+                  LASER_E_INVALID_ARG, "non-positive size in laser_model_desc");
+    LASER_REQUIRE(d.d_model % d.n_heads == 0, LASER_E_SHAPE, "d_model not divisible by n_heads");
+    const int dh = d.d_model / d.n_heads;
+    LASER_REQUIRE(dh == 64 || dh == 128, LASER_E_SHAPE, "head_dim %d unsupported (64 or 128)", dh);
+    LASER_REQUIRE(d.d_model % 128 == 0 && d.vocab % 16 == 0, LASER_E_SHAPE, "d_model must be a multiple of 128, vocab of 16");
+    LASER_REQUIRE(d.wlm != nullptr, LASER_E_INVALID_ARG, "wlm is NULL");
+    if (d.n_layers > 0) {
+        LASER_REQUIRE(d.ffn > 0 && d.ffn % 128 == 0, LASER_E_SHAPE, "ffn must be a positive multiple of 128");
+        LASER_REQUIRE(d.max_pos > 0, LASER_E_INVALID_ARG, "max_pos must be positive");
+        LASER_REQUIRE(d.wqkv && d.wo && d.wgu && d.wdown && d.g1 && d.g2 && d.emb && d.gf, LASER_E_INVALID_ARG, "NULL weight pointer");
+    }
+    Model* m = new Model();
+    m->d = d;
+    m->dh = dh;
+    auto fail = [&](int rc) { laser_model_destroy(reinterpret_cast<laser_model*>(m)); return rc; };
+#define M_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) { set_error("%s: %s", #expr, hipGetErrorString(e_)); return fail(LASER_E_HIP); } } while (0)
+    const size_t R = (size_t)d.max_rows, dm = (size_t)d.d_model;
+    M_TRY(hipMalloc((void**)&m->xn, R * dm * 2));
+    M_TRY(hipMalloc((void**)&m->row_x, R * 4));
+    M_TRY(hipMalloc((void**)&m->hp_lx, R * 4));
+    if (d.n_layers > 0) {
+        M_TRY(hipMalloc((void**)&m->x, R * dm * 4));
+        M_TRY(hipMalloc((void**)&m->qkv, R * dm * 3 * 4));
+        M_TRY(hipMalloc((void**)&m->q, R * dm * 2));
+        M_TRY(hipMalloc((void**)&m->attn, R * dm * 2));
+        M_TRY(hipMalloc((void**)&m->act, R * (size_t)d.ffn * 2));
+        M_TRY(hipMalloc((void**)&m->row_pos, R * 4));
+        const size_t nt = (size_t)d.max_pos * (dh / 2);
+        M_TRY(hipMalloc((void**)&m->rope, nt * sizeof(float2)));
+        hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((nt + 255) / 256)), dim3(256), 0, stream, m->rope,
+                           d.max_pos, dh / 2, dh, (double)d.rope_base);
+    }
+    // output-head partials: one per (row, vocabulary chunk)
+    {
+        const int ntiles = d.vocab / 16;
+        const int tpw = (ntiles + 1023) / 1024;
+        m->head_chunks = (ntiles + tpw - 1) / tpw;
+        const size_t n = R * (size_t)m->head_chunks;
+        M_TRY(hipMalloc((void**)&m->hp_max, n * 4));
+        M_TRY(hipMalloc((void**)&m->hp_sum, n * 4));
+        M_TRY(hipMalloc((void**)&m->hp_arg, n * 4));
+        M_TRY(hipMalloc((void**)&m->hp_topv, n * LASER_MAX_TOPK * 4));
+        M_TRY(hipMalloc((void**)&m->hp_topi, n * LASER_MAX_TOPK * 4));
+    }
+    M_TRY(hipStreamSynchronize(stream));
+#undef M_TRY
+    *out = reinterpret_cast<laser_model*>(m);
+    return LASER_OK;
+}
+
+static int check_step_args(const Model* m, int B, int K, int topk, int mode, const void* draft_len,
+                           const void* drafts, const void* accept_len, const void* out_tokens) {
+    LASER_REQUIRE(m != nullptr, LASER_E_INVALID_ARG, "model is NULL");
+    LASER_REQUIRE(B >= 0 && B <= m->d.max_batch, LASER_E_INVALID_ARG, "B %d outside 0..max_batch %d", B, m->d.max_batch);
+    LASER_REQUIRE(K >= 0 && K <= LASER_MAX_DRAFT, LASER_E_INVALID_ARG, "K %d outside 0..%d", K, LASER_MAX_DRAFT);
+    LASER_REQUIRE((long)B * (K + 1) <= m->d.max_rows, LASER_E_LIMIT, "B*(K+1) = %ld exceeds max_rows %d", (long)B * (K + 1), m->d.max_rows);
+    LASER_REQUIRE(topk >= 1 && topk <= LASER_MAX_TOPK, LASER_E_INVALID_ARG, "topk %d outside 1..%d", topk, LASER_MAX_TOPK);
+    LASER_REQUIRE(mode >= 0 && mode <= 3, LASER_E_INVALID_ARG, "unknown mode %d", mode);
+    LASER_REQUIRE(B == 0 || (draft_len && accept_len && out_tokens && (drafts || K == 0)), LASER_E_INVALID_ARG, "NULL device buffer");
+    return LASER_OK;
+}
+
+extern "C" int laser_verify_step(laser_model* mh, laser_kv* kh, const int32_t* seq_ids, const int32_t* pending,
+                                 const int32_t* drafts, const int32_t* draft_len, int B, int K, int topk, float p,
+                                 int mode, int32_t* accept_len, int32_t* out_tokens, float* logits_dbg, void* stream_) {
+    Model* m = reinterpret_cast<Model*>(mh);
+    KV* kv = reinterpret_cast<KV*>(kh);
+    hipStream_t stream = (hipStream_t)stream_;
+    int rc = check_step_args(m, B, K, topk, mode, draft_len, drafts, accept_len, out_tokens);
+    if (rc) return rc;
+    LASER_REQUIRE(kv != nullptr, LASER_E_INVALID_ARG, "kv is NULL");
+    LASER_REQUIRE(m->d.n_layers > 0, LASER_E_SHAPE, "model has no layers (head-only handle)");
+    LASER_REQUIRE(kv->d.n_layers == m->d.n_layers && kv->d.n_heads == m->d.n_heads && kv->d.head_dim == m->dh,
+                  LASER_E_SHAPE, "KV cache shape does not match the model");
+    if (B == 0) return LASER_OK;
+    LASER_REQUIRE(seq_ids && pending, LASER_E_INVALID_ARG, "NULL argument");
+    LASER_REQUIRE(B <= kv->d.max_seqs, LASER_E_INVALID_ARG, "B exceeds max_seqs");
+    const int R = K + 1;
+    int max_ub = 0;
+    {
+        std::vector<char> seen(kv->d.max_seqs, 0);
+        for (int b = 0; b < B; ++b) {
+            const int s = seq_ids[b];
+            LASER_REQUIRE(s >= 0 && s < kv->d.max_seqs, LASER_E_INVALID_ARG, "sequence slot %d out of range", s);
+            LASER_REQUIRE(!seen[s], LASER_E_INVALID_ARG, "sequence slot %d appears twice", s);
+            seen[s] = 1;
+            LASER_REQUIRE(kv->h_len_ub[s] + R <= kv->h_npages[s] * kPageSize, LASER_E_OOM_PAGES,
+                          "slot %d: length bound %d + %d rows exceeds the %d tokens reserved", s, kv->h_len_ub[s], R,
+                          kv->h_npages[s] * kPageSize);
+            LASER_REQUIRE(kv->h_len_ub[s] + R <= m->d.max_pos, LASER_E_LIMIT, "slot %d: position would exceed max_pos %d", s, m->d.max_pos);
+            max_ub = std::max(max_ub, kv->h_len_ub[s]);
+        }
+    }
+    const int32_t* ids_dev = nullptr;
+    if ((rc = kv->stage_ids(seq_ids, B, stream, &ids_dev))) return rc;
+    for (int b = 0; b < B; ++b) kv->h_last_rows[seq_ids[b]] = R;
+    if ((rc = forward(m, kv, ids_dev, pending, drafts, draft_len, B, K, max_ub, stream))) return rc;
+    return run_head(m, m->xn, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens, logits_dbg, stream);
+}
+
+extern "C" int laser_verify_head(laser_model* mh, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len,
+                                 int B, int K, int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens,
+                                 float* logits_dbg, void* stream) {
+    Model* m = reinterpret_cast<Model*>(mh);
+    int rc = check_step_args(m, B, K, topk, mode, draft_len, drafts, accept_len, out_tokens);
+    if (rc) return rc;
+    if (B == 0) return LASER_OK;
+    LASER_REQUIRE(h != nullptr, LASER_E_INVALID_ARG, "h is NULL");
+    return run_head(m, h, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens, logits_dbg, (hipStream_t)stream);
+}

@@ -1,0 +1,464 @@
+// Retrieval pool: host-side construction of the regrouped pool and its suffix index, and the
+// per-context lookup + frequency-greedy chain kernel (Sec. 3.2 pool construction, Sec. 3.3 Eq. 5).
+//
+// Index layout (all device resident, immutable after the build):
+//   P[N]        int32   tokens, sub-pools laid out by ascending key
+//   seq_end[N]  uint32  per position: one past the last position of its sequence
+//   sa[Ne]      uint32  every position that has an in-sequence successor, sorted inside its
+//                       sub-pool by the text read backwards from it (P[e], P[e-1], ... up to n_max
+//                       tokens, "before the sequence start" ordering first), then by position.
+//                       All occurrences of any n-gram (n <= n_max) are therefore one contiguous,
+//                       position-ascending run of sa.
+//   table[cap]  16 B    open addressing (linear probing, load <= 0.5): (key, n, n-gram) -> run in sa
+// A lookup hashes (key, n, suffix), probes, and confirms a hit by comparing key, n and the actual
+// tokens at the run's first occurrence, so hash collisions cannot produce a false match.
+#include <algorithm>
+#include <cstring>
+#include <numeric>
+#include <thread>
+#include <vector>
+
+#include "common.h"
+
+namespace laser {
+
+struct Pool {
+    int32_t* P = nullptr;
+    uint32_t* seq_end = nullptr;
+    uint32_t* sa = nullptr;
+    IndexEntry* table = nullptr;
+    uint64_t cap_mask = 0;
+    int64_t n_tokens = 0, n_keys = 0, n_entries = 0, n_sa = 0, device_bytes = 0;
+    int n_max = 0;
+};
+
+// ------------------------------------------------------------------------------------ kernel
+constexpr int kCand = 2048;        // occurrences a wave keeps in LDS
+constexpr int kVote = 1024;        // vote-table slots (power of two)
+constexpr int kVoteFill = 768;     // distinct tokens beyond which a vote pass is split
+constexpr int kEmptyTok = -1;
+
+__device__ inline uint32_t fmix32(uint32_t h) {   // bijective 32-bit mixer
+    h ^= h >> 16; h *= 0x85EBCA6Bu; h ^= h >> 13; h *= 0xC2B2AE35u; h ^= h >> 16;
+    return h;
+}
+
+struct RetrieveArgs {
+    const int32_t* P; const uint32_t* seq_end; const uint32_t* sa; const IndexEntry* table;
+    uint64_t cap_mask;
+    const int64_t* keys; const int32_t* ctx_tail;
+    int B, n_min, n_max, K, min_tokens;
+    int32_t* drafts; int32_t* draft_len; int32_t* match_n; int64_t* pool_index;
+};
+
+// One wavefront (= one workgroup of 64 lanes) per context.
+__global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
+    __shared__ uint32_t cand[kCand];
+    __shared__ int vote_tok[kVote];
+    __shared__ int vote_cnt[kVote];
+    __shared__ int chain[LASER_MAX_DRAFT + 1];
+    __shared__ int best_chain[LASER_MAX_DRAFT + 1];
+    __shared__ int sh_distinct;
+
+    const int b = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int64_t key = a.keys[b];
+    const int32_t* tail = a.ctx_tail + (size_t)b * a.n_max;
+
+    int valid = 0;
+    while (valid < a.n_max && tail[a.n_max - 1 - valid] >= 0) ++valid;
+
+    int best_len = 0, best_n = 0;
+    long long best_idx = -1;
+    int res_len = 0, res_n = 0;
+    long long res_idx = -1;
+    bool done = false;
+
+    const int n_hi = valid < a.n_max ? valid : a.n_max;
+    for (int n = n_hi; n >= a.n_min && !done && a.K > 0; --n) {
+        // ---- index probe (every lane does the same probe; addresses are uniform) ----
+        const int32_t* w = tail + (a.n_max - n);
+        uint64_t slot = ngram_hash(key, n, w) & a.cap_mask;
+        uint32_t start = 0, count = 0;
+        for (;;) {
+            IndexEntry e = a.table[slot];
+            if (e.count_n == 0) break;
+            if (e.key == key && (int)(e.count_n >> 28) == n) {
+                uint32_t e0 = a.sa[e.start];
+                bool same = true;
+                for (int i = 0; i < n; ++i) same = same && (a.P[e0 - (n - 1) + i] == w[i]);
+                if (same) { start = e.start; count = e.count_n & 0x0FFFFFFFu; break; }
+            }
+            slot = (slot + 1) & a.cap_mask;
+        }
+        if (count == 0) continue;
+
+        // ---- frequency-greedy chain over the occurrences sa[start .. start+count) ----
+        // Survivors are either materialised in LDS (m <= kCand) or, while there are too many,
+        // re-derived from the run by re-checking the chain so far.
+        bool in_lds = count <= (uint32_t)kCand;
+        uint32_t m = count;
+        if (in_lds)
+            for (uint32_t i = lane; i < count; i += 64) cand[i] = a.sa[start + i];
+        __syncthreads();
+
+        int len = 0;
+        for (int j = 1; j <= a.K; ++j) {
+            int win_tok = -1, win_cnt = 0;
+            // The vote may need several passes when too many distinct successors show up.
+            for (uint32_t nparts = 1;; nparts *= 2) {
+                win_tok = -1; win_cnt = 0;
+                bool overflow = false;
+                for (uint32_t part = 0; part < nparts && !overflow; ++part) {
+                    for (int i = lane; i < kVote; i += 64) { vote_tok[i] = kEmptyTok; vote_cnt[i] = 0; }
+                    if (lane == 0) sh_distinct = 0;
+                    __syncthreads();
+                    const uint32_t total = in_lds ? m : count;
+                    for (uint32_t i0 = 0; i0 < total; i0 += 64) {
+                        uint32_t i = i0 + lane;
+                        if (i < total) {
+                            uint32_t e = in_lds ? cand[i] : a.sa[start + i];
+                            bool ok = (e + (uint32_t)j) < a.seq_end[e];
+                            if (ok && !in_lds)
+                                for (int c = 1; c < j; ++c) ok = ok && (a.P[e + c] == chain[c - 1]);
+                            if (ok) {
+                                int tok = a.P[e + j];
+                                uint32_t hh = fmix32((uint32_t)tok);
+                                if (nparts == 1 || (hh / kVote) % nparts == part) {
+                                    uint32_t s = hh & (kVote - 1);
+                                    for (int probe = 0; probe < kVote; ++probe) {
+                                        int cur = vote_tok[s];
+                                        if (cur == kEmptyTok) {
+                                            int prev = atomicCAS(&vote_tok[s], kEmptyTok, tok);
+                                            if (prev == kEmptyTok) { atomicAdd(&sh_distinct, 1); cur = tok; }
+                                            else cur = prev;
+                                        }
+                                        if (cur == tok) { atomicAdd(&vote_cnt[s], 1); break; }
+                                        s = (s + 1) & (kVote - 1);
+                                    }
+                                }
+                            }
+                        }
+                        // stop feeding a table that is getting too full; the pass will be split
+                        if ((i0 & 1023u) == 960u) {
+                            __syncthreads();
+                            if (sh_distinct > kVoteFill) break;
+                        }
+                    }
+                    __syncthreads();
+                    overflow = sh_distinct > kVoteFill;
+                    __syncthreads();               // everyone has read the counter before it is reset
+                    if (overflow) break;
+                    // best of this part: larger count, then smaller token id
+                    int bt = -1, bc = 0;
+                    for (int i = lane; i < kVote; i += 64) {
+                        int c = vote_cnt[i], t = vote_tok[i];
+                        if (c > bc || (c == bc && c > 0 && t < bt)) { bc = c; bt = t; }
+                    }
+                    for (int off = 32; off > 0; off >>= 1) {
+                        int oc = __shfl_xor(bc, off), ot = __shfl_xor(bt, off);
+                        if (oc > bc || (oc == bc && oc > 0 && ot < bt)) { bc = oc; bt = ot; }
+                    }
+                    if (bc > win_cnt || (bc == win_cnt && bc > 0 && bt < win_tok)) { win_cnt = bc; win_tok = bt; }
+                    __syncthreads();
+                }
+                if (!overflow) break;
+            }
+            if (win_cnt == 0) break;       // no survivor has a successor left
+            if (lane == 0) chain[j - 1] = win_tok;
+            len = j;
+            // ---- keep the occurrences that agree with the winner ----
+            if (in_lds) {
+                uint32_t out = 0;
+                for (uint32_t i0 = 0; i0 < m; i0 += 64) {
+                    uint32_t i = i0 + lane;
+                    uint32_t e = 0; bool keep = false;
+                    if (i < m) {
+                        e = cand[i];
+                        keep = (e + (uint32_t)j) < a.seq_end[e] && a.P[e + j] == win_tok;
+                    }
+                    uint64_t mask = __ballot(keep);
+                    uint32_t pos = out + __popcll(mask & ((1ull << lane) - 1ull));
+                    __syncthreads();               // all reads of this chunk precede the writes
+                    if (keep) cand[pos] = e;       // pos <= i: never overtakes unread entries
+                    out += __popcll(mask);
+                }
+                m = out;
+                __syncthreads();
+            } else {
+                __syncthreads();
+                if ((uint32_t)win_cnt <= (uint32_t)kCand) {   // few enough now: materialise
+                    uint32_t out = 0;
+                    for (uint32_t i0 = 0; i0 < count; i0 += 64) {
+                        uint32_t i = i0 + lane;
+                        uint32_t e = 0; bool keep = false;
+                        if (i < count) {
+                            e = a.sa[start + i];
+                            keep = (e + (uint32_t)j) < a.seq_end[e];
+                            for (int c = 1; c <= j && keep; ++c) keep = (a.P[e + c] == chain[c - 1]);
+                        }
+                        uint64_t mask = __ballot(keep);
+                        uint32_t pos = out + __popcll(mask & ((1ull << lane) - 1ull));
+                        if (keep) cand[pos] = e;
+                        out += __popcll(mask);
+                    }
+                    m = out;
+                    in_lds = true;
+                    __syncthreads();
+                }
+            }
+        }
+        // ---- smallest surviving position ----
+        uint32_t mn = 0xFFFFFFFFu;
+        if (in_lds) {
+            for (uint32_t i = lane; i < m; i += 64) mn = min(mn, cand[i]);
+        } else {
+            for (uint32_t i = lane; i < count; i += 64) {
+                uint32_t e = a.sa[start + i];
+                bool keep = (e + (uint32_t)len) < a.seq_end[e];
+                for (int c = 1; c <= len && keep; ++c) keep = (a.P[e + c] == chain[c - 1]);
+                if (keep) mn = min(mn, e);
+            }
+        }
+        for (int off = 32; off > 0; off >>= 1) mn = min(mn, (uint32_t)__shfl_xor((int)mn, off));
+        __syncthreads();
+
+        if (len >= a.min_tokens) {
+            res_len = len; res_n = n; res_idx = (long long)mn; done = true;
+        } else if (len > best_len) {
+            best_len = len; best_n = n; best_idx = (long long)mn;
+            for (int i = lane; i < len; i += 64) best_chain[i] = chain[i];
+            __syncthreads();
+        }
+    }
+    const int* src = chain;
+    if (!done) { res_len = best_len; res_n = best_n; res_idx = best_idx; src = best_chain; }
+    __syncthreads();
+    for (int i = lane; i < a.K; i += 64) a.drafts[(size_t)b * a.K + i] = i < res_len ? src[i] : -1;
+    if (lane == 0) {
+        a.draft_len[b] = res_len;
+        a.match_n[b] = res_len > 0 ? res_n : 0;
+        a.pool_index[b] = res_len > 0 ? res_idx : -1;
+    }
+}
+
+// ------------------------------------------------------------------------------------ host build
+namespace {
+
+struct SubPool { int64_t key; uint32_t begin, end; };
+
+}  // namespace
+
+static int build_pool(const int32_t* tokens, const int64_t* seq_off, const int64_t* seq_key,
+                      int64_t n_seq, int n_max, hipStream_t stream, Pool** out) {
+    const int64_t n_tok = n_seq > 0 ? seq_off[n_seq] : 0;
+    LASER_REQUIRE(n_tok < 0xFFFFFFFFll, LASER_E_LIMIT, "pool of %lld tokens exceeds 2^32-2", (long long)n_tok);
+    for (int64_t s = 0; s < n_seq; ++s)
+        LASER_REQUIRE(seq_off[s + 1] >= seq_off[s], LASER_E_INVALID_ARG, "seq_off not ascending at %lld", (long long)s);
+
+    // 1. regroup: ascending key, supply order inside a key
+    std::vector<int64_t> order(n_seq);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int64_t x, int64_t y) { return seq_key[x] < seq_key[y]; });
+
+    std::vector<int32_t> P((size_t)n_tok);
+    std::vector<uint32_t> seq_begin((size_t)n_tok), seq_end((size_t)n_tok);
+    std::vector<SubPool> subs;
+    {
+        uint32_t pos = 0;
+        for (int64_t i = 0; i < n_seq; ++i) {
+            const int64_t s = order[i];
+            const uint32_t len = (uint32_t)(seq_off[s + 1] - seq_off[s]);
+            if (subs.empty() || subs.back().key != seq_key[s]) subs.push_back({seq_key[s], pos, pos});
+            for (uint32_t t = 0; t < len; ++t) {
+                const int32_t tok = tokens[seq_off[s] + t];
+                LASER_REQUIRE(tok >= 0, LASER_E_INVALID_ARG, "negative token in sequence %lld", (long long)s);
+                P[pos + t] = tok;
+                seq_begin[pos + t] = pos;
+                seq_end[pos + t] = pos + len;
+            }
+            pos += len;
+            subs.back().end = pos;
+        }
+    }
+
+    // 2. sorted occurrence array: per sub-pool, positions with a successor, by reversed text
+    std::vector<uint32_t> sa;
+    sa.reserve((size_t)n_tok);
+    std::vector<uint32_t> sub_sa_begin(subs.size() + 1);
+    for (size_t g = 0; g < subs.size(); ++g) {
+        sub_sa_begin[g] = (uint32_t)sa.size();
+        for (uint32_t e = subs[g].begin; e < subs[g].end; ++e)
+            if (e + 1 < seq_end[e]) sa.push_back(e);
+    }
+    sub_sa_begin[subs.size()] = (uint32_t)sa.size();
+
+    auto back_tok = [&](uint32_t e, int i) -> int64_t {       // i-th token back from e, or -1 before the sequence
+        return (e - seq_begin[e] >= (uint32_t)i) ? (int64_t)P[e - i] : -1;
+    };
+    auto less = [&](uint32_t x, uint32_t y) {
+        for (int i = 0; i < n_max; ++i) {
+            const int64_t a = back_tok(x, i), b = back_tok(y, i);
+            if (a != b) return a < b;
+        }
+        return x < y;
+    };
+    {
+        const unsigned hw = std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
+        const size_t G = subs.size();
+        if (G <= 1 || hw == 1) {
+            for (size_t g = 0; g < G; ++g)
+                std::sort(sa.begin() + sub_sa_begin[g], sa.begin() + sub_sa_begin[g + 1], less);
+        } else {
+            // split the sub-pools into hw contiguous chunks of roughly equal size
+            std::vector<std::thread> th;
+            std::vector<size_t> cut(hw + 1, G);
+            cut[0] = 0;
+            const uint64_t total = sa.size();
+            size_t g = 0;
+            for (unsigned t = 1; t < hw; ++t) {
+                const uint64_t target = total * t / hw;
+                while (g < G && sub_sa_begin[g] < target) ++g;
+                cut[t] = g;
+            }
+            for (unsigned t = 0; t < hw; ++t)
+                th.emplace_back([&, t] {
+                    for (size_t q = cut[t]; q < cut[t + 1]; ++q)
+                        std::sort(sa.begin() + sub_sa_begin[q], sa.begin() + sub_sa_begin[q + 1], less);
+                });
+            for (auto& x : th) x.join();
+        }
+    }
+
+    // 3. runs of equal n-grams -> table entries
+    auto same_ngram = [&](uint32_t x, uint32_t y, int n) {
+        for (int i = 0; i < n; ++i) {
+            const int64_t a = back_tok(x, i), b = back_tok(y, i);
+            if (a < 0 || a != b) return false;
+        }
+        return true;
+    };
+    auto has_n = [&](uint32_t e, int n) { return e - seq_begin[e] >= (uint32_t)(n - 1); };
+
+    // two passes over the runs (count, then insert) keep the host footprint at the table itself
+    auto for_each_run = [&](auto&& fn) -> bool {
+        for (size_t g = 0; g < subs.size(); ++g) {
+            const uint32_t lo = sub_sa_begin[g], hi = sub_sa_begin[g + 1];
+            for (int n = 1; n <= n_max; ++n) {
+                uint32_t i = lo;
+                while (i < hi) {
+                    if (!has_n(sa[i], n)) { ++i; continue; }
+                    uint32_t j = i + 1;
+                    while (j < hi && same_ngram(sa[i], sa[j], n)) ++j;
+                    if (!fn(g, n, i, j - i)) return false;
+                    i = j;
+                }
+            }
+        }
+        return true;
+    };
+    uint64_t n_runs = 0;
+    uint32_t longest = 0;
+    for_each_run([&](size_t, int, uint32_t, uint32_t c) { ++n_runs; longest = std::max(longest, c); return true; });
+    LASER_REQUIRE(longest < (1u << 28), LASER_E_LIMIT, "an n-gram occurs %u times (limit 2^28-1)", longest);
+    uint64_t cap = 16;
+    while (cap < 2 * n_runs) cap <<= 1;
+    std::vector<IndexEntry> table(cap);
+    std::memset(table.data(), 0, cap * sizeof(IndexEntry));
+    for_each_run([&](size_t g, int n, uint32_t start, uint32_t c) {
+        int32_t w[LASER_MAX_NGRAM];
+        const uint32_t e0 = sa[start];
+        for (int i = 0; i < n; ++i) w[i] = P[e0 - (n - 1) + i];
+        uint64_t slot = ngram_hash(subs[g].key, n, w) & (cap - 1);
+        while (table[slot].count_n != 0) slot = (slot + 1) & (cap - 1);
+        table[slot] = {subs[g].key, start, c | ((uint32_t)n << 28)};
+        return true;
+    });
+
+    // 4. upload
+    Pool* p = new Pool();
+    p->n_tokens = n_tok; p->n_keys = (int64_t)subs.size(); p->n_entries = (int64_t)n_runs;
+    p->n_sa = (int64_t)sa.size(); p->n_max = n_max; p->cap_mask = cap - 1;
+    auto up = [&](void** dst, const void* src, size_t bytes) -> int {
+        const size_t alloc = bytes ? bytes : 16;
+        LASER_HIP_CHECK(hipMalloc(dst, alloc));
+        p->device_bytes += (int64_t)alloc;
+        if (bytes) LASER_HIP_CHECK(hipMemcpyAsync(*dst, src, bytes, hipMemcpyHostToDevice, stream));
+        return LASER_OK;
+    };
+    int rc;
+    if ((rc = up((void**)&p->P, P.data(), P.size() * 4)) || (rc = up((void**)&p->seq_end, seq_end.data(), seq_end.size() * 4)) ||
+        (rc = up((void**)&p->sa, sa.data(), sa.size() * 4)) || (rc = up((void**)&p->table, table.data(), cap * sizeof(IndexEntry)))) {
+        (void)hipFree(p->P); (void)hipFree(p->seq_end); (void)hipFree(p->sa); (void)hipFree(p->table);
+        delete p;
+        return rc;
+    }
+    LASER_HIP_CHECK(hipStreamSynchronize(stream));
+    *out = p;
+    return LASER_OK;
+}
+
+}  // namespace laser
+
+using namespace laser;
+
+extern "C" int laser_pool_build(const int32_t* tokens, const int64_t* seq_off, const int64_t* seq_key,
+                                int64_t n_seq, int n_max, void* stream, laser_pool** out) {
+    LASER_REQUIRE(out != nullptr, LASER_E_INVALID_ARG, "out is NULL");
+    LASER_REQUIRE(n_seq >= 0, LASER_E_INVALID_ARG, "n_seq < 0");
+    LASER_REQUIRE(n_seq == 0 || (tokens && seq_off && seq_key), LASER_E_INVALID_ARG, "NULL input array");
+    LASER_REQUIRE(n_max >= 1 && n_max <= LASER_MAX_NGRAM, LASER_E_INVALID_ARG, "n_max %d outside 1..%d", n_max, LASER_MAX_NGRAM);
+    LASER_REQUIRE(n_seq == 0 || seq_off[0] == 0, LASER_E_INVALID_ARG, "seq_off[0] != 0");
+    Pool* p = nullptr;
+    int rc = build_pool(tokens, seq_off, seq_key, n_seq, n_max, (hipStream_t)stream, &p);
+    if (rc == LASER_OK) *out = reinterpret_cast<laser_pool*>(p);
+    return rc;
+}
+
+extern "C" int laser_pool_destroy(laser_pool* pool) {
+    if (!pool) return LASER_OK;
+    Pool* p = reinterpret_cast<Pool*>(pool);
+    (void)hipFree(p->P); (void)hipFree(p->seq_end); (void)hipFree(p->sa); (void)hipFree(p->table);
+    delete p;
+    return LASER_OK;
+}
+
+extern "C" int laser_pool_info(const laser_pool* pool, int64_t* n_tokens, int64_t* n_keys,
+                               int64_t* n_index_entries, int64_t* device_bytes) {
+    LASER_REQUIRE(pool != nullptr, LASER_E_INVALID_ARG, "pool is NULL");
+    const Pool* p = reinterpret_cast<const Pool*>(pool);
+    if (n_tokens) *n_tokens = p->n_tokens;
+    if (n_keys) *n_keys = p->n_keys;
+    if (n_index_entries) *n_index_entries = p->n_entries;
+    if (device_bytes) *device_bytes = p->device_bytes;
+    return LASER_OK;
+}
+
+extern "C" int laser_pool_read_tokens(const laser_pool* pool, int64_t start, int64_t count, int32_t* out_host) {
+    LASER_REQUIRE(pool != nullptr && out_host != nullptr, LASER_E_INVALID_ARG, "NULL argument");
+    const Pool* p = reinterpret_cast<const Pool*>(pool);
+    LASER_REQUIRE(start >= 0 && count >= 0 && start + count <= p->n_tokens, LASER_E_INVALID_ARG,
+                  "range [%lld, +%lld) outside the pool", (long long)start, (long long)count);
+    if (count) LASER_HIP_CHECK(hipMemcpy(out_host, p->P + start, (size_t)count * 4, hipMemcpyDeviceToHost));
+    return LASER_OK;
+}
+
+extern "C" int laser_retrieve_drafts(const laser_pool* pool, const int64_t* keys, const int32_t* ctx_tail,
+                                     int B, int n_min, int n_max, int K, int min_tokens,
+                                     int32_t* drafts, int32_t* draft_len, int32_t* match_n,
+                                     int64_t* pool_index, void* stream) {
+    LASER_REQUIRE(pool != nullptr, LASER_E_INVALID_ARG, "pool is NULL");
+    const Pool* p = reinterpret_cast<const Pool*>(pool);
+    LASER_REQUIRE(B >= 0, LASER_E_INVALID_ARG, "B < 0");
+    LASER_REQUIRE(K >= 0 && K <= LASER_MAX_DRAFT, LASER_E_INVALID_ARG, "K %d outside 0..%d", K, LASER_MAX_DRAFT);
+    LASER_REQUIRE(n_max >= 1 && n_max <= p->n_max, LASER_E_INVALID_ARG, "n_max %d outside 1..%d (the pool's)", n_max, p->n_max);
+    LASER_REQUIRE(n_min >= 1 && n_min <= n_max, LASER_E_INVALID_ARG, "n_min %d outside 1..n_max", n_min);
+    if (B == 0) return LASER_OK;
+    LASER_REQUIRE(keys && ctx_tail && draft_len && match_n && pool_index && (drafts || K == 0),
+                  LASER_E_INVALID_ARG, "NULL device buffer");
+    RetrieveArgs a{p->P, p->seq_end, p->sa, p->table, p->cap_mask, keys, ctx_tail,
+                   B, n_min, n_max, K, min_tokens < 1 ? 1 : min_tokens, drafts, draft_len, match_n, pool_index};
+    hipLaunchKernelGGL(retrieve_kernel, dim3(B), dim3(64), 0, (hipStream_t)stream, a);
+    LASER_HIP_CHECK(hipGetLastError());
+    return LASER_OK;
+}

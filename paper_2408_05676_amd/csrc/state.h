@@ -1,0 +1,66 @@
+// Host-side state behind the opaque laser_model / laser_kv handles.
+#pragma once
+
+#include <vector>
+
+#include "common.h"
+
+namespace laser {
+
+constexpr int kPageSize = 16;     // tokens per KV page (fixed: one MFMA token tile)
+constexpr int kIdSlots = 64;      // ring of staged seq-id vectors
+
+// KV page layouts (fp16), per layer l, page g, head h:
+//   kpages[((l * n_pages + g) * H + h) * 16 * dh + t * dh + c]     token-major  (t = slot in page)
+//   vpages[((l * n_pages + g) * H + h) * dh * 16 + c * 16 + t]     channel-major (transposed)
+// so that a 16-token page of one head is one contiguous 4 KiB block (dh = 128) in either pool and
+// both feed the matrix cores without an in-kernel transpose.
+struct KV {
+    laser_kv_desc d{};
+    uint16_t* kpages = nullptr;
+    uint16_t* vpages = nullptr;
+    int32_t* block_table = nullptr;   // [dev] [max_seqs][max_pages_per_seq]
+    int32_t* len = nullptr;           // [dev] [max_seqs] committed tokens
+    // host bookkeeping
+    std::vector<int32_t> h_block_table;
+    std::vector<int32_t> h_npages;    // pages owned per slot
+    std::vector<int32_t> h_len_ub;    // upper bound of len per slot
+    std::vector<int32_t> h_last_rows; // R of the last verify per slot (commit adds at most this)
+    std::vector<int32_t> free_pages;
+    // staging ring for per-call seq-id vectors
+    int32_t* ids_pinned = nullptr;    // [kIdSlots][max_seqs]
+    int32_t* ids_dev = nullptr;       // [kIdSlots][max_seqs]
+    hipEvent_t ids_ev[kIdSlots]{};
+    bool ids_used[kIdSlots]{};
+    int ids_next = 0;
+
+    int stage_ids(const int32_t* host_ids, int B, hipStream_t stream, const int32_t** dev_out);
+    size_t page_elems() const { return (size_t)d.n_heads * kPageSize * d.head_dim; }
+};
+
+struct Model {
+    laser_model_desc d{};
+    int dh = 0;
+    // workspace (device)
+    float* x = nullptr;          // [max_rows][d]   residual stream
+    uint16_t* xn = nullptr;      // [max_rows][d]   normed activations (fp16)
+    float* qkv = nullptr;        // [max_rows][3d]
+    uint16_t* q = nullptr;       // [max_rows][d]   rotated queries (fp16)
+    uint16_t* attn = nullptr;    // [max_rows][d]
+    uint16_t* act = nullptr;     // [max_rows][F]
+    int32_t* row_pos = nullptr;  // [max_rows]
+    float* att_part = nullptr;   // attention split partials
+    size_t att_part_floats = 0;
+    float2* rope = nullptr;      // [max_pos][dh/2] (cos, sin)
+    // output-head partials
+    int head_chunks = 0;
+    float* hp_max = nullptr;     // [max_rows][chunks]
+    float* hp_sum = nullptr;
+    int32_t* hp_arg = nullptr;
+    float* hp_topv = nullptr;    // [max_rows][chunks][LASER_MAX_TOPK]
+    int32_t* hp_topi = nullptr;
+    float* hp_lx = nullptr;      // [max_rows]
+    int32_t* row_x = nullptr;    // [max_rows] draft token of the row or -1
+};
+
+}  // namespace laser

@@ -1,0 +1,175 @@
+"""GPU parity: laser_verify_step / laser_verify_head / laser_kv_commit vs the oracle, through the
+C ABI. Logits within 2e-2 abs + 1e-2 rel; accepted lengths and emitted tokens identical except
+decisions whose oracle margin lies inside that tolerance (counted and printed)."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import acceptance, step
+from oracle.decoder import Decoder
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _laser():
+    import paper_2408_05676_amd as laser
+    return laser
+
+
+def _oracle(sh):
+    w = synth.gen_all_weights(sh)
+    return Decoder(sh.n_layers, sh.d, sh.n_heads, sh.ffn, sh.vocab, w, sh.eps, sh.rope_base)
+
+
+def _run_steps(sh, B, ctx_len, K, n_steps, k, p, mode=0, seed=1, ragged=False):
+    laser = _laser()
+    dec = _oracle(sh)
+    cap = ctx_len + (K + 1) * (n_steps + 1) + 16
+    model = gu.make_model(sh, max_rows=B * max(K + 1, 16), max_batch=B, max_pos=cap + 16)
+    kv = gu.make_kv(sh, n_pages=B * (cap // 16 + 2), max_seqs=B + 3, max_pages_per_seq=cap // 16 + 2)
+    seq_ids = [B + 2 - b for b in range(B)]                             # non-trivial slot numbers
+    prompts = synth.uniform_tokens(seed, 50, 0, B * ctx_len, sh.vocab).reshape(B, ctx_len)
+    for s in seq_ids:
+        kv.reserve(s, cap)
+    pend = gu.prefill(model, kv, seq_ids, prompts, chunk=16 if not ragged else 7)
+    seqs = [step.Sequence(dec, 0, prompts[b], cap) for b in range(B)]
+    assert kv.read_lens(seq_ids).tolist() == [ctx_len - 1] * B
+    r = np.random.default_rng(seed)
+    flips_total, worst = 0, 0.0
+    for it in range(n_steps):
+        # drafts: a mix of the oracle's own greedy continuation (so something gets accepted),
+        # near misses and random tokens; ragged draft lengths
+        drafts = r.integers(0, sh.vocab, size=(B, K)).astype(np.int32)
+        dl = np.full(B, K, dtype=np.int32)
+        for b in range(B):
+            if (b + it) % 3 != 2:
+                probe = step.Sequence.__new__(step.Sequence)
+                probe.key, probe.tokens = 0, list(seqs[b].tokens)
+                probe.cache = dec.new_cache(cap)
+                probe.cache.k[:], probe.cache.v[:] = seqs[b].cache.k, seqs[b].cache.v
+                probe.cache.length = seqs[b].cache.length
+                good = step.autoregressive_greedy(dec, probe, K)
+                n_good = int(r.integers(0, K + 1))
+                drafts[b, :n_good] = good[:n_good]
+            if ragged:
+                dl[b] = int(r.integers(0, K + 1))
+                drafts[b, dl[b]:] = -1
+        d_dev = torch.tensor(drafts, device="cuda")
+        dl_dev = torch.tensor(dl, device="cuda")
+        acc, out, logits = laser.verify_step(model, kv, seq_ids, pend, d_dev, dl_dev, k, p, mode, want_logits=True)
+        laser.kv_commit(kv, seq_ids, acc)
+        torch.cuda.synchronize()
+        ora = step.verify_step(dec, seqs, drafts, dl, k, p, mode, return_logits=True)
+        ok, max_err, ratio = gu.logits_close(logits.cpu().numpy().astype(np.float64), ora["logits"])
+        worst = max(worst, ratio)
+        assert ok, f"step {it}: logits off: max abs err {max_err}, {ratio:.2f}x the bound"
+        acc_g, out_g = acc.cpu().numpy(), out.cpu().numpy()
+        flips, bad = gu.classify_step(acc_g, out_g, ora, drafts, dl, k, p)
+        assert not bad, f"step {it}: decisions differ outside tolerance: {bad}"
+        flips_total += flips
+        if flips:       # the two sides now hold different texts: stop comparing this run
+            break
+        assert (acc_g <= dl).all() and (acc_g >= 0).all()
+        pend = torch.tensor([s.pending for s in seqs], dtype=torch.int32, device="cuda")
+        assert kv.read_lens(seq_ids).tolist() == [s.cache.length for s in seqs]
+    print(f"[{sh.name} B={B} K={K} k={k} p={p} mode={mode}] worst logit error {worst:.3f} of bound, "
+          f"in-tolerance flips {flips_total}")
+    model.close(); kv.close()
+    return flips_total
+
+
+@pytest.mark.parametrize("shape_name", ["tiny", "tiny128"])
+def test_tiny_strict_and_relaxed(shape_name):
+    sh = synth.SHAPES[shape_name].with_(lm_gain=4.0)
+    _run_steps(sh, B=2, ctx_len=64, K=4, n_steps=4, k=1, p=-1.0)
+    _run_steps(sh, B=2, ctx_len=64, K=4, n_steps=4, k=2, p=0.1)
+
+
+def test_tiny_ragged_batch_modes_and_large_k():
+    sh = synth.SHAPES["tiny"].with_(lm_gain=4.0)
+    _run_steps(sh, B=5, ctx_len=37, K=7, n_steps=3, k=3, p=0.05, mode=1, seed=2, ragged=True)
+    _run_steps(sh, B=3, ctx_len=20, K=20, n_steps=2, k=2, p=0.1, mode=2, seed=3, ragged=True)   # R = 21: two query tiles
+    _run_steps(sh, B=7, ctx_len=18, K=0, n_steps=3, k=1, p=-1.0, seed=4)                        # plain greedy decode
+    _run_steps(sh, B=2, ctx_len=300, K=5, n_steps=2, k=8, p=0.01, mode=3, seed=5)               # many pages, context split
+
+
+def test_head_only_closed_forms_and_brute_force():
+    laser = _laser()
+    V, d = 2048, 256
+    r = np.random.default_rng(0)
+    sh = synth.ModelShape("h", 0, d, 2, 1024, V)
+    wlm = synth.gen_weight(sh, "wlm")
+    model = laser.Model(0, d, 2, 1024, V, {"wlm": torch.tensor(wlm, device="cuda").to(torch.bfloat16)}, 256, 16, 0)
+    B, K = 6, 5
+    h = synth.round_to_bf16_f32(r.standard_normal((B, K + 1, d)).astype(np.float32) * 3)
+    logits = h.astype(np.float64) @ wlm.astype(np.float64).T
+    drafts = np.empty((B, K), dtype=np.int32)
+    order = np.argsort(-logits, axis=-1, kind="stable")
+    for b in range(B):
+        for j in range(K):
+            drafts[b, j] = order[b, j, (b + j) % 4]              # ranks 0..3
+    dl = np.array([5, 5, 3, 0, 5, 1], dtype=np.int32)
+    for (k, p, mode) in [(1, -1.0, 0), (2, 0.1, 0), (4, 0.0, 0), (2, 0.1, 1), (3, 0.0, 2), (1, 0.02, 3)]:
+        acc, out, lg = laser.verify_head(model, torch.tensor(h, device="cuda").to(torch.float16),
+                                         torch.tensor(drafts, device="cuda"), torch.tensor(dl, device="cuda"),
+                                         k, p, mode, want_logits=True)
+        torch.cuda.synchronize()
+        ok, max_err, ratio = gu.logits_close(lg.cpu().numpy().astype(np.float64), logits)
+        assert ok and max_err < 1e-3, (max_err, ratio)         # same rounded inputs: only fp32 summation order differs
+        oa, oo, stats, gaps = acceptance.verify_batch(logits, drafts, dl, k, p, mode)
+        ora = {"accept_len": oa, "out_tokens": oo, "stats": stats, "argmax_gap": gaps, "logits": logits}
+        flips, bad = gu.classify_step(acc.cpu().numpy(), out.cpu().numpy(), ora, drafts, dl, k, p, slack=0.01)
+        assert not bad and flips == 0, (k, p, mode, bad)
+    # uniform logits (zero head): q = 1/V, rank = token id, argmax = 0
+    z = laser.Model(0, d, 2, 1024, V, {"wlm": torch.zeros((V, d), device="cuda", dtype=torch.bfloat16)}, 256, 16, 0)
+    dr = torch.tensor([[0, 0, 1], [1, 0, 0], [2, 2, 2]], dtype=torch.int32, device="cuda")
+    hl = torch.ones((3, 4, d), device="cuda", dtype=torch.float16)
+    three = torch.full((3,), 3, dtype=torch.int32, device="cuda")
+    acc, out, _ = laser.verify_head(z, hl, dr, three, 2, 1.0 / V - 1e-6, 0)
+    assert acc.cpu().tolist() == [3, 3, 0] and out.cpu().tolist() == [[0, 0, 1, 0], [1, 0, 0, 0], [0, -1, -1, -1]]
+    acc, out, _ = laser.verify_head(z, hl, dr, three, 2, 1.0 / V, 0)     # strict '>' at the threshold
+    assert acc.cpu().tolist() == [0, 0, 0]
+    acc, out, _ = laser.verify_head(z, hl, dr, three, 1, -1.0, 0)        # greedy: only token 0 passes
+    assert acc.cpu().tolist() == [2, 0, 0]
+    model.close(); z.close()
+
+
+def test_argument_errors_and_capacity():
+    laser = _laser()
+    sh = synth.SHAPES["tiny"]
+    model = gu.make_model(sh, max_rows=32, max_batch=4, max_pos=128)
+    kv = gu.make_kv(sh, n_pages=6, max_seqs=4, max_pages_per_seq=4)
+    pend = torch.zeros(2, dtype=torch.int32, device="cuda")
+    dr = torch.zeros((2, 3), dtype=torch.int32, device="cuda")
+    dl = torch.zeros(2, dtype=torch.int32, device="cuda")
+    with pytest.raises(laser.LaserError, match="reserved"):
+        laser.verify_step(model, kv, [0, 1], pend, dr, dl, 1, 0.0)       # nothing reserved yet
+    kv.reserve(0, 64)
+    with pytest.raises(laser.LaserError):
+        kv.reserve(1, 64)                                                 # 4 + 4 pages > pool of 6
+    kv.reserve(1, 32)
+    with pytest.raises(laser.LaserError):
+        kv.reserve(2, 100)                                                # > max_pages_per_seq
+    with pytest.raises(laser.LaserError, match="twice"):
+        laser.verify_step(model, kv, [1, 1], pend, dr, dl, 1, 0.0)
+    with pytest.raises(laser.LaserError):
+        laser.verify_step(model, kv, [0, 1], pend, dr, dl, 9, 0.0)       # topk too large
+    with pytest.raises(laser.LaserError):
+        laser.verify_step(model, kv, [0, 7], pend, dr, dl, 1, 0.0)       # slot out of range
+    with pytest.raises(laser.LaserError):
+        laser.kv_commit(kv, [0, 1], dl)                                   # commit without verify
+    acc, out, _ = laser.verify_step(model, kv, [0, 1], pend, dr, dl, 1, 0.0)
+    laser.kv_commit(kv, [0, 1], acc)
+    assert kv.read_lens([0, 1]).tolist() == [1, 1] and acc.cpu().tolist() == [0, 0]
+    kv.release(1)
+    kv.reserve(2, 32)                                                     # pages of slot 1 are reusable
+    assert kv.read_lens([1]).tolist() == [0]
+    # context bookkeeping kernel
+    tail = torch.tensor([[-1, 5, 6], [1, 2, 3]], dtype=torch.int32, device="cuda")
+    outt = torch.tensor([[7, 8, 9, -1], [4, -1, -1, -1]], dtype=torch.int32, device="cuda")
+    al = torch.tensor([2, 0], dtype=torch.int32, device="cuda")
+    laser.ctx_advance(tail, pend, outt, al)
+    assert tail.cpu().tolist() == [[7, 8, 9], [2, 3, 4]] and pend.cpu().tolist() == [9, 4]
+    model.close(); kv.close()
