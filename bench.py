@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the retrieve -> verify -> accept -> commit step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c4|1b|tiny]
+
+A "step" is one pass of the whole hot path over the batch: laser_retrieve_drafts,
+laser_verify_step (embedding .. fused head + acceptance), laser_kv_commit, laser_ctx_advance.
+All inputs are resident in HBM before the timed region. Prints ONE JSON line.
+
+Workload (seeded, synthetic): random-init weights of the named shape; contexts and pools from the
+template + substitution recipe; the pool additionally holds a noisy copy of the model's own greedy
+continuation of each benchmark context (the paper builds its pools from the same model's earlier
+outputs), so that drafts are accepted in multi-token chunks that break where the copy was
+substituted. `value` counts the tokens the step really emitted (accepted drafts + 1 per step).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+WORKLOADS = {
+    #        shape  B   ctx   K  pool             n_max  default steps
+    "c3": dict(shape="7b", B=1, ctx=1024, K=8, pool="7b_latency", n_max=3, steps=40, warmup=5,
+               label="7B shape latency: B=1, context 1024, K=8, pool 2k x 256 tokens (BASELINE configs[2])"),
+    "c4": dict(shape="7b", B=64, ctx=512, K=10, pool="7b_throughput", n_max=3, steps=20, warmup=3,
+               label="7B shape throughput: B=64, prompt 512 + generated, K=10, paged KV (BASELINE configs[3])"),
+    "1b": dict(shape="1b", B=8, ctx=512, K=8, pool="1b", n_max=3, steps=40, warmup=5,
+               label="1B shape: B=8, context 512, K=8 (BASELINE configs[1])"),
+    "tiny": dict(shape="tiny", B=2, ctx=64, K=4, pool="tiny", n_max=3, steps=20, warmup=3,
+                 label="Tiny: B=2, context 64, K=4 (BASELINE configs[0])"),
+}
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(sh, B, K, ctx_len):
+    """Bytes one step must move: every streamed weight once, the cached K/V of every sequence once,
+    the new K/V written once."""
+    R = K + 1
+    w = sh.n_params() * 2
+    kv_read = sh.n_layers * B * (ctx_len + R) * sh.d * 2 * 2
+    kv_write = sh.n_layers * B * R * sh.d * 2 * 2
+    return w + kv_read + kv_write
+
+
+def host_threads() -> int:
+    n = len(os.sched_getaffinity(0))
+    env = os.environ.get("OMP_NUM_THREADS")
+    return min(n, int(env)) if env and env.isdigit() else n
+
+
+def cpu_baseline(sh, wl, tokens_per_step, n_sample_layers=2):
+    """Time the oracle (as it stands) on a bounded sample of the same step: retrieval on the real
+    pool for the batch, `n_sample_layers` decoder layers + final norm + head + acceptance on
+    R rows per sequence against a cache of the configured length holding seeded random K/V."""
+    import synth
+    from oracle import acceptance, retrieval
+    from oracle.decoder import Decoder
+
+    B, K, ctx_len = min(wl["B"], 2), wl["K"], wl["ctx"]
+    R = K + 1
+    Ls = min(n_sample_layers, sh.n_layers)
+    weights = {}
+    for l in range(Ls):
+        for n in ("wqkv", "wo", "wgu", "wdown", "g1", "g2"):
+            weights[(n, l)] = synth.gen_weight(sh, n, l)
+    for n in ("emb", "wlm", "gf"):
+        weights[(n, -1)] = synth.gen_weight(sh, n)
+    dec = Decoder(Ls, sh.d, sh.n_heads, sh.ffn, sh.vocab, weights, sh.eps, sh.rope_base)
+    caches = []
+    for b in range(B):
+        c = dec.new_cache(ctx_len + R)
+        n = Ls * (ctx_len - 1) * sh.d
+        c.k[:, :ctx_len - 1] = synth.approx_normal_f32(7, 900 + b, 0, n, 1.3).reshape(Ls, ctx_len - 1, sh.n_heads, sh.head_dim)
+        c.v[:, :ctx_len - 1] = synth.approx_normal_f32(7, 950 + b, 0, n, 1.3).reshape(Ls, ctx_len - 1, sh.n_heads, sh.head_dim)
+        c.length = ctx_len - 1
+        caches.append(c)
+    spec = synth.POOLS[wl["pool"]]
+    pool = synth.gen_pool(spec)
+    opool = retrieval.RegroupedPool(pool["tokens"], pool["seq_off"], pool["seq_key"])
+    ctx = synth.gen_contexts(spec, B, ctx_len, wl["n_max"], salt=1, min_remaining=K)
+    rows = synth.uniform_tokens(11, 1, 0, B * R, sh.vocab).reshape(B, R)
+
+    t0 = time.perf_counter()
+    drafts, dl, _, _ = retrieval.retrieve(opool, ctx["keys"], ctx["ctx"][:, -wl["n_max"]:], 1, wl["n_max"], K)
+    t_retr = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    hs = [dec.hidden(caches[b], rows[b]) for b in range(B)]
+    t_layers = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    logits = np.stack([dec.head(h) for h in hs])
+    acceptance.verify_batch(logits, drafts, dl, 2, 0.1, 0)
+    t_head = time.perf_counter() - t0
+    scale_b = wl["B"] / B
+    est = (t_retr + t_layers * (sh.n_layers / max(Ls, 1)) + t_head) * scale_b
+    return {
+        "value": wl["B"] * tokens_per_step / est, "unit": "accepted tokens/s", "cores": host_threads(), "kind": "oracle",
+        "sample": (f"{B} of {wl['B']} sequences, {Ls} of {sh.n_layers} layers + head + retrieval + acceptance, "
+                   f"float64 numpy; layer time scaled x{sh.n_layers / max(Ls, 1):g}, batch x{scale_b:g} (extrapolated); "
+                   f"tokens/step taken equal to the GPU run's"),
+        "est_step_s": est, "measured_s": t_retr + t_layers + t_head,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="c3", choices=sorted(WORKLOADS))
+    ap.add_argument("--regime", default="rv", choices=["rv", "strict", "floor"],
+                    help="rv: k=2 p=0.1 (Eq. 8) on a sharpened head; strict: greedy (Eq. 4); floor: no pool replay")
+    ap.add_argument("--lm-gain", type=float, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the path needs no collectives; see DESIGN.md on sharding). "
+              "--gpus N with N > 1 is not supported.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth
+    from synth.model import torch_gen_weight
+    import paper_2408_05676_amd as laser
+    from paper_2408_05676_amd.harness import Engine, stacked_weights
+
+    wl = WORKLOADS[args.workload]
+    steps = args.steps if args.steps is not None else wl["steps"]
+    warmup = args.warmup if args.warmup is not None else wl["warmup"]
+    B, K, ctx_len, n_max = wl["B"], wl["K"], wl["ctx"], wl["n_max"]
+    R = K + 1
+    topk, p, mode = (1, -1.0, 0) if args.regime == "strict" else (2, 0.1, 0)
+    gain = args.lm_gain if args.lm_gain is not None else (5.0 if args.regime == "rv" else 1.0)
+    sh = synth.SHAPES[wl["shape"]].with_(lm_gain=gain)
+    dev = "cuda"
+    torch.cuda.set_device(0)
+
+    t_setup = time.perf_counter()
+    weights = stacked_weights(lambda n, l: torch_gen_weight(sh, n, l, dev), sh, dev)
+    n_gen = (steps + warmup) * R + 16                       # tokens the replayed continuation must cover
+    max_len = ctx_len + 2 * n_gen + R + 32
+    eng = Engine(sh, weights, B, K, max_len, n_max)
+    spec = synth.POOLS[wl["pool"]]
+    ctx = synth.gen_contexts(spec, B, ctx_len, n_max, salt=1, min_remaining=K)
+    eng.prefill(ctx["ctx"])
+
+    pool_data = synth.gen_pool(spec)
+    toks, off, keys = pool_data["tokens"], pool_data["seq_off"], pool_data["seq_key"]
+    if args.regime != "floor":
+        cont = eng.generate_greedy(n_gen)                   # the model's own continuation (HIP path)
+        extra = []
+        for b in range(B):
+            text = np.concatenate([ctx["ctx"][b, -n_max:], cont[b]]).astype(np.int32)
+            noisy = synth.noisy_copy(spec, text, salt=b)
+            noisy[:n_max] = text[:n_max]
+            extra.append(noisy)
+        toks = np.concatenate([toks] + extra)
+        off = np.concatenate([off, off[-1] + np.cumsum([len(e) for e in extra])]).astype(np.int64)
+        keys = np.concatenate([keys, ctx["keys"]]).astype(np.int64)
+        for b in range(B):                                  # roll back to the state after prefill
+            eng.kv.set_len(b, ctx_len - 1)
+        eng.pending.copy_(torch.as_tensor(np.ascontiguousarray(ctx["ctx"][:, -1]), dtype=torch.int32))
+        eng.ctx_tail.copy_(torch.as_tensor(np.ascontiguousarray(ctx["ctx"][:, -n_max:]), dtype=torch.int32))
+    pool = laser.Pool(toks, off, keys, n_max)
+    eng.set_pool(pool, ctx["keys"])
+    torch.cuda.synchronize()
+    setup_s = time.perf_counter() - t_setup
+
+    for _ in range(warmup):
+        eng.step(topk, p, mode)
+    torch.cuda.synchronize()
+    len0 = eng.kv.read_lens(eng.seq_ids).astype(np.int64)
+    eng.model.profile_begin(steps * sh.n_layers)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        eng.step(topk, p, mode)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu_ms = e0.elapsed_time(e1)
+    dom_ms, dom_n = eng.model.profile_end()
+    len1 = eng.kv.read_lens(eng.seq_ids).astype(np.int64)
+    emitted = int((len1 - len0).sum())
+    elapsed = max(wall, gpu_ms / 1e3)
+    tokens_per_step = emitted / (steps * B)
+    value = emitted / elapsed
+
+    # dominant kernel: the gate/up projection GEMM (largest weight stream of every layer)
+    dom_bytes = 2 * sh.ffn * sh.d * 2 + B * R * sh.d * 2 + B * R * sh.ffn * 2
+    dom_avg_s = dom_ms / 1e3 / max(dom_n, 1)
+    achieved = dom_bytes / dom_avg_s / 1e9 if dom_n else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("bytes_per_launch")
+    step_bytes = algorithmic_bytes(sh, B, K, ctx_len + int((len0 - (ctx_len - 1)).mean()))
+    out = {
+        "metric": "accepted tokens/s per verify step (7B shape, bs 1 & 64); % HBM / MFMA peak",
+        "value": value, "unit": "accepted tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": elapsed * 1e3 / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 weights x fp16 activations, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": wl["label"], "batch": B, "context": ctx_len, "K": K, "regime": args.regime,
+                   "topk": topk, "p": p, "lm_gain": gain, "tokens_per_step": tokens_per_step,
+                   "gpu_ms_per_step": gpu_ms / steps, "setup_s": setup_s,
+                   "step_algorithmic_GB": step_bytes / 1e9,
+                   "step_hbm_frac": step_bytes / (gpu_ms / 1e3 / steps) / 1e9 / HBM_PEAK_GBS},
+        "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel<gate/up SwiGLU>", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "bytes_per_launch": dom_bytes, "avg_launch_us": dom_avg_s * 1e6, "launches": dom_n},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(sh, wl, tokens_per_step)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

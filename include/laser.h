@@ -202,6 +202,13 @@ int laser_kv_commit(laser_kv* kv, const int32_t* seq_ids, const int32_t* accept_
 int laser_ctx_advance(int32_t* ctx_tail, int32_t* pending, const int32_t* out_tokens,
                       const int32_t* accept_len, int B, int K, int n_max, void* stream);
 
+/* Timing of the dominant kernel of laser_verify_step (the gate/up projection GEMM, which streams the
+ * largest weight matrix of every layer): between begin and end, HIP events are recorded on the
+ * call's stream right before and after each of its launches, up to max_records launches.
+ * laser_profile_end synchronises `stream` and returns the summed kernel time and the launch count. */
+int laser_profile_begin(laser_model* model, int max_records);
+int laser_profile_end(laser_model* model, void* stream, float* total_ms, int* n_launches);
+
 #ifdef __cplusplus
 }
 #endif

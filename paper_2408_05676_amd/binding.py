@@ -68,6 +68,8 @@ def lib():
         "laser_verify_head": [vp, vp, vp, vp, i32, i32, i32, f32, i32, vp, vp, vp, vp],
         "laser_kv_commit": [vp, vp, vp, i32, vp],
         "laser_ctx_advance": [vp, vp, vp, vp, i32, i32, i32, vp],
+        "laser_profile_begin": [vp, i32],
+        "laser_profile_end": [vp, vp, C.POINTER(C.c_float), C.POINTER(C.c_int)],
     }
     for name, args in protos.items():
         fn = getattr(L, name)
@@ -183,6 +185,14 @@ class Model:
             setattr(d, name, _dev(t, torch.float32, name))
         self._h = C.c_void_p()
         _check(lib().laser_model_create(C.byref(d), _stream(stream), C.byref(self._h)), "laser_model_create")
+
+    def profile_begin(self, max_records: int):
+        _check(lib().laser_profile_begin(self._h, max_records), "laser_profile_begin")
+
+    def profile_end(self, stream=None):
+        ms, n = C.c_float(), C.c_int()
+        _check(lib().laser_profile_end(self._h, _stream(stream), C.byref(ms), C.byref(n)), "laser_profile_end")
+        return ms.value, n.value
 
     def close(self):
         if getattr(self, "_h", None) is not None and self._h:

@@ -382,7 +382,10 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
         if ((rc = launch_gemm<EPI_RESID>(go, stream))) return rc;
         hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.g2 + (size_t)l * dm, dm, d.eps, m->xn);
         GemmArgs gg{d.wgu + (size_t)l * 2 * F * dm, m->xn, M, F, dm, 1, nullptr, m->act};
+        const bool prof = m->prof_on && m->prof_n < m->prof_cap;
+        if (prof) LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n], stream));
         if ((rc = launch_gemm<EPI_SWIGLU>(gg, stream))) return rc;
+        if (prof) { LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n + 1], stream)); ++m->prof_n; }
         GemmArgs gd{d.wdown + (size_t)l * dm * F, m->act, M, dm, F, 1, m->x, nullptr};
         if ((rc = launch_gemm<EPI_RESID>(gd, stream))) return rc;
     }
@@ -401,6 +404,7 @@ extern "C" int laser_model_destroy(laser_model* h) {
     void* ptrs[] = {m->x, m->xn, m->qkv, m->q, m->attn, m->act, m->row_pos, m->att_part, m->rope, m->hp_max,
                     m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx, m->row_x};
     for (void* p : ptrs) if (p) (void)hipFree(p);
+    for (hipEvent_t e : m->prof_ev) (void)hipEventDestroy(e);
     delete m;
     return LASER_OK;
 }
@@ -519,4 +523,34 @@ extern "C" int laser_verify_head(laser_model* mh, const uint16_t* h, const int32
     if (B == 0) return LASER_OK;
     LASER_REQUIRE(h != nullptr, LASER_E_INVALID_ARG, "h is NULL");
     return run_head(m, h, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens, logits_dbg, (hipStream_t)stream);
+}
+
+extern "C" int laser_profile_begin(laser_model* mh, int max_records) {
+    Model* m = reinterpret_cast<Model*>(mh);
+    LASER_REQUIRE(m != nullptr && max_records > 0 && max_records <= (1 << 20), LASER_E_INVALID_ARG, "bad argument");
+    while ((int)m->prof_ev.size() < 2 * max_records) {
+        hipEvent_t e;
+        LASER_HIP_CHECK(hipEventCreate(&e));
+        m->prof_ev.push_back(e);
+    }
+    m->prof_cap = max_records;
+    m->prof_n = 0;
+    m->prof_on = true;
+    return LASER_OK;
+}
+
+extern "C" int laser_profile_end(laser_model* mh, void* stream, float* total_ms, int* n_launches) {
+    Model* m = reinterpret_cast<Model*>(mh);
+    LASER_REQUIRE(m != nullptr && total_ms && n_launches, LASER_E_INVALID_ARG, "NULL argument");
+    m->prof_on = false;
+    LASER_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
+    double tot = 0.0;
+    for (int i = 0; i < m->prof_n; ++i) {
+        float ms = 0.f;
+        LASER_HIP_CHECK(hipEventElapsedTime(&ms, m->prof_ev[2 * i], m->prof_ev[2 * i + 1]));
+        tot += ms;
+    }
+    *total_ms = (float)tot;
+    *n_launches = m->prof_n;
+    return LASER_OK;
 }

@@ -79,6 +79,12 @@ def _substitute(spec: PoolSpec, toks: np.ndarray, stream_salt: int, start: int) 
     return np.where(u < spec.sub_rate, r, toks.reshape(-1)).astype(np.int32)
 
 
+def noisy_copy(spec: PoolSpec, toks: np.ndarray, salt: int) -> np.ndarray:
+    """A copy of `toks` with the pool's substitution noise (seeded by `salt`)."""
+    toks = np.asarray(toks, dtype=np.int32)
+    return _substitute(spec, toks.copy(), 50 + salt, 0).reshape(toks.shape)
+
+
 def gen_pool(spec: PoolSpec):
     """Returns dict(tokens int32[N], seq_off int64[n_seq+1], seq_key int64[n_seq],
     seq_rank int64[n_seq], seq_template int64[n_seq])."""
