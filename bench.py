@@ -120,6 +120,7 @@ def main():
                     help="rv: k=2 p=0.1 (Eq. 8) on a sharpened head; strict: greedy (Eq. 4); floor: no pool replay")
     ap.add_argument("--lm-gain", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-fused", action="store_true", help="force the general multi-kernel verify path")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the path needs no collectives; see DESIGN.md on sharding). "
@@ -148,6 +149,8 @@ def main():
     n_gen = (steps + warmup) * R + 16                       # tokens the replayed continuation must cover
     max_len = ctx_len + 2 * n_gen + R + 32
     eng = Engine(sh, weights, B, K, max_len, n_max)
+    if args.no_fused:
+        eng.model.set_option("fused", 0)
     spec = synth.POOLS[wl["pool"]]
     ctx = synth.gen_contexts(spec, B, ctx_len, n_max, salt=1, min_remaining=K)
     eng.prefill(ctx["ctx"])
@@ -178,7 +181,7 @@ def main():
         eng.step(topk, p, mode)
     torch.cuda.synchronize()
     len0 = eng.kv.read_lens(eng.seq_ids).astype(np.int64)
-    eng.model.profile_begin(steps * sh.n_layers)
+    eng.model.profile_begin(steps * max(sh.n_layers, 1))
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -191,13 +194,22 @@ def main():
     gpu_ms = e0.elapsed_time(e1)
     dom_ms, dom_n = eng.model.profile_end()
     len1 = eng.kv.read_lens(eng.seq_ids).astype(np.int64)
+    if eng.model.aborted():
+        print("bench.py: the persistent kernel reported an aborted wait; results are invalid", file=sys.stderr)
+        sys.exit(3)
     emitted = int((len1 - len0).sum())
     elapsed = max(wall, gpu_ms / 1e3)
     tokens_per_step = emitted / (steps * B)
     value = emitted / elapsed
 
-    # dominant kernel: the gate/up projection GEMM (largest weight stream of every layer)
-    dom_bytes = 2 * sh.ffn * sh.d * 2 + B * R * sh.d * 2 + B * R * sh.ffn * 2
+    step_bytes = algorithmic_bytes(sh, B, K, ctx_len + int((len0 - (ctx_len - 1)).mean()))
+    fused = B * R <= 16 and not args.no_fused
+    if fused:
+        # few-row regime: the whole verify step (embedding .. head + acceptance) is ONE persistent kernel
+        dom_name, dom_bytes = "verify_fused_kernel (whole verify step)", step_bytes
+    else:
+        # dominant kernel: the gate/up projection GEMM (largest weight stream of every layer)
+        dom_name, dom_bytes = "gemm_skinny_kernel<gate/up SwiGLU>", 2 * sh.ffn * sh.d * 2 + B * R * sh.d * 2 + B * R * sh.ffn * 2
     dom_avg_s = dom_ms / 1e3 / max(dom_n, 1)
     achieved = dom_bytes / dom_avg_s / 1e9 if dom_n else 0.0
     traffic = None
@@ -205,7 +217,6 @@ def main():
     if os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f).get("bytes_per_launch")
-    step_bytes = algorithmic_bytes(sh, B, K, ctx_len + int((len0 - (ctx_len - 1)).mean()))
     out = {
         "metric": "accepted tokens/s per verify step (7B shape, bs 1 & 64); % HBM / MFMA peak",
         "value": value, "unit": "accepted tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
@@ -216,7 +227,7 @@ def main():
                    "gpu_ms_per_step": gpu_ms / steps, "setup_s": setup_s,
                    "step_algorithmic_GB": step_bytes / 1e9,
                    "step_hbm_frac": step_bytes / (gpu_ms / 1e3 / steps) / 1e9 / HBM_PEAK_GBS},
-        "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel<gate/up SwiGLU>", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_launch": dom_bytes, "avg_launch_us": dom_avg_s * 1e6, "launches": dom_n},
     }

@@ -202,6 +202,17 @@ int laser_kv_commit(laser_kv* kv, const int32_t* seq_ids, const int32_t* accept_
 int laser_ctx_advance(int32_t* ctx_tail, int32_t* pending, const int32_t* out_tokens,
                       const int32_t* accept_len, int B, int K, int n_max, void* stream);
 
+/* Options: "fused" = 1 (default) lets laser_verify_step use the persistent whole-step kernel when
+ * B*(K+1) <= 16; 0 forces the general multi-kernel path. Both compute the same function. */
+int laser_model_set_option(laser_model* model, const char* name, int value);
+/* Phase trace of the persistent kernel (option "fused_trace" = 1): thread 0 of every workgroup stamps
+ * the 100 MHz wall clock before and after every grid barrier. Copies the stamps of the most recent
+ * launch to out[nwg][cap] (host, int64) and synchronises `stream`. */
+int laser_model_read_trace(laser_model* model, void* stream, long long* out, int max_elems, int* nwg, int* cap);
+/* Synchronises `stream` and reports whether a bounded wait inside the persistent kernel ever gave up
+ * (*aborted = 1): results after that are invalid and the handle must be destroyed. */
+int laser_model_status(laser_model* model, void* stream, int* aborted);
+
 /* Timing of the dominant kernel of laser_verify_step (the gate/up projection GEMM, which streams the
  * largest weight matrix of every layer): between begin and end, HIP events are recorded on the
  * call's stream right before and after each of its launches, up to max_records launches.

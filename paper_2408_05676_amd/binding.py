@@ -69,6 +69,9 @@ def lib():
         "laser_kv_commit": [vp, vp, vp, i32, vp],
         "laser_ctx_advance": [vp, vp, vp, vp, i32, i32, i32, vp],
         "laser_profile_begin": [vp, i32],
+        "laser_model_set_option": [vp, C.c_char_p, i32],
+        "laser_model_status": [vp, vp, C.POINTER(C.c_int)],
+        "laser_model_read_trace": [vp, vp, vp, i32, C.POINTER(C.c_int), C.POINTER(C.c_int)],
         "laser_profile_end": [vp, vp, C.POINTER(C.c_float), C.POINTER(C.c_int)],
     }
     for name, args in protos.items():
@@ -185,6 +188,22 @@ class Model:
             setattr(d, name, _dev(t, torch.float32, name))
         self._h = C.c_void_p()
         _check(lib().laser_model_create(C.byref(d), _stream(stream), C.byref(self._h)), "laser_model_create")
+
+    def set_option(self, name: str, value: int):
+        _check(lib().laser_model_set_option(self._h, name.encode(), value), "laser_model_set_option")
+
+    def aborted(self, stream=None) -> bool:
+        v = C.c_int()
+        _check(lib().laser_model_status(self._h, _stream(stream), C.byref(v)), "laser_model_status")
+        return bool(v.value)
+
+    def read_trace(self, stream=None) -> np.ndarray:
+        """int64[nwg][cap] wall-clock stamps (100 MHz) of the last traced persistent-kernel launch."""
+        buf = np.zeros(1 << 20, dtype=np.int64)
+        nwg, cap = C.c_int(), C.c_int()
+        _check(lib().laser_model_read_trace(self._h, _stream(stream), buf.ctypes.data, buf.size, C.byref(nwg), C.byref(cap)),
+               "laser_model_read_trace")
+        return buf[:nwg.value * cap.value].reshape(nwg.value, cap.value)
 
     def profile_begin(self, max_records: int):
         _check(lib().laser_profile_begin(self._h, max_records), "laser_profile_begin")

@@ -1,0 +1,1081 @@
+// Persistent whole-step kernel for the few-row regime (M = B*(K+1) <= 16 rows): one cooperative
+// launch runs embedding, every decoder layer, the final norm, the output head and the acceptance
+// rule (Eq. 3/6 forward; Eq. 4/7/8 + correction rule). It exists because at these shapes a layer's
+// weights stream in ~60 us, so kernel boundaries and latency-bound helper kernels would cost as much
+// as the streaming itself.
+//
+// Structure: grid = one workgroup of 8 waves per compute unit. Phases are separated by a grid
+// barrier (one agent-scope atomic counter + a separate flag line); per layer:
+//     QKV(+RoPE) | attention | O-proj(+residual) | gate/up(+SwiGLU) | down(+residual)
+// * Weight streaming: a GEMM item is a 16-feature tile (or a pair of tiles); the 8 waves of a
+//   workgroup split its reduction dimension, each lane reading 64 contiguous bytes per step
+//   (k-permuted MFMA operands), partial sums meet in LDS. Each wave keeps one step of weights in
+//   flight and issues the first step of the NEXT phase before it enters the barrier, so HBM stays
+//   busy while the barrier resolves (weights never depend on activations).
+// * RMSNorm never materialises: producers publish x*gain (fp16) plus per-workgroup partial sums of
+//   squares; consumers multiply their accumulators by rsqrt(mean square) (a per-row scalar commutes
+//   with the product).
+// * Cross-workgroup exchange without cache flushes: the chip has one L2 per XCD and agent-scope
+//   fences cost ~18 us here. Instead every exchanged buffer is WRITE-ONCE per launch (a fresh
+//   address range per layer and phase), written with agent-scope (write-through) stores and read
+//   with ordinary cached loads after the barrier: no L2 can hold a stale copy of a line it has never
+//   read, and kernel boundaries clean the caches between launches.
+// * Attention reads committed cache pages (slots < len) with ordinary loads and the R new rows from
+//   the exchange buffers; the wave that owns the new tile also copies it into the cache pages.
+//   Context splits are merged by the last workgroup to arrive (per-(sequence, head) counter).
+// Every wait is bounded: a barrier that does not resolve within ~5 s raises the abort flag and all
+// workgroups leave the kernel.
+#include <algorithm>
+#include <cmath>
+
+#include "mfma.h"
+#include "state.h"
+
+namespace laser {
+
+constexpr int FT = 512;             // threads per workgroup
+constexpr int FWAVES = 8;
+constexpr int AW = 8;               // waves per workgroup that take attention pages
+constexpr int KTOP = LASER_MAX_TOPK;
+
+struct FusedArgs {
+    const uint16_t *wqkv, *wo, *wgu, *wdown, *emb, *wlm;
+    const float *g1, *g2, *gf;
+    int L, d, H, dh, F, V;
+    float eps;
+    const float2* rope;
+    uint16_t *kpages, *vpages;
+    const int32_t *block_table, *lens;
+    int mpps, n_pages;
+    const int32_t *seq_ids, *pending, *drafts, *draft_len;
+    int B, K, R, M;
+    // exchange buffers (write-once per launch)
+    float* xbuf;        // [2L+1][16][d]
+    uint16_t* xgbuf;    // [2L+1][16][d]
+    float* ssbuf;       // [2L+1][nwg][16]
+    uint16_t *qbuf, *knew, *vnew, *attn;   // [L][16][d]
+    uint16_t* act;      // [L][16][F]
+    float* apart;       // [L][B*H][nsplit][32 + 16*dh]
+    int* acount;        // [L][B*H]   (self-resetting)
+    int nsplit;
+    // head
+    float *hp_max, *hp_sum; int32_t* hp_arg; float* hp_topv; int32_t* hp_topi; float* hp_lx;
+    int topk, mode; float p;
+    int32_t *accept_len, *out_tokens; float* logits_dbg;
+    // sync
+    unsigned long long *bar_count, *bar_flag; unsigned long long epoch0;
+    int* abort_flag;
+    long long* trace;     // optional [nwg][trace_cap] wall-clock stamps (100 MHz) of thread 0
+    int trace_cap;
+};
+
+// ---- agent-scope (write-through) stores for exchanged data ----------------------------------------
+__device__ inline void st_u32(void* p, uint32_t v) {
+    __hip_atomic_store(reinterpret_cast<uint32_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void st_f32(float* p, float v) { st_u32(p, __float_as_uint(v)); }
+__device__ inline void st_i32(int* p, int v) { st_u32(p, (uint32_t)v); }
+__device__ inline uint32_t pack_h2(float a, float b) { return (uint32_t)f32_to_f16(a) | ((uint32_t)f32_to_f16(b) << 16); }
+
+struct Shared {
+    union {
+        float red[3][FWAVES][2][4][64];   // split-K partial sums of up to 3 items    48 KiB
+        float att_o[AW][16][128];         // attention wave merge                    64 KiB
+    };
+    float att_m[AW][16], att_l[AW][16];
+    float rs[16];                         // rsqrt(mean square) per row
+    float ss_acc[16][8];
+    int row_pos[16], row_b[16];
+    int flag;                             // barrier outcome / last-arriver broadcast
+    float hstat[FWAVES][4];
+    int hstat_i[FWAVES][2];
+    int row_ok[LASER_MAX_DRAFT + 1], row_arg[LASER_MAX_DRAFT + 1];
+};
+
+__device__ inline void stamp(const FusedArgs& a, int& n) {
+    if (a.trace && threadIdx.x == 0) {
+        if (n < a.trace_cap) a.trace[(size_t)blockIdx.x * a.trace_cap + n] = wall_clock64();
+        ++n;
+    }
+}
+
+// Every wave waits until its own exchange stores have completed (the workgroup barrier alone only
+// orders LDS; completion of a write-through store takes a full memory round trip), then thread 0
+// arrives. `prefetch` issues the next phase's first weight steps just before that wait, so they
+// travel together with the stores.
+template <class Prefetch>
+__device__ inline bool grid_sync(const FusedArgs& a, Shared& sh, unsigned long long& epoch, Prefetch&& prefetch) {
+    ++epoch;
+    prefetch();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned long long e = a.epoch0 + epoch;
+        int ok = 1;
+        const unsigned long long old = __hip_atomic_fetch_add(a.bar_count, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old + 1 == e * (unsigned long long)gridDim.x) {
+            __hip_atomic_store(a.bar_flag, e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            long spins = 0;
+            while (__hip_atomic_load(a.bar_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < e) {
+                __builtin_amdgcn_s_sleep(1);
+                if ((++spins & 1023) == 0) {
+                    if (spins > 8000000L || __hip_atomic_load(a.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+                        __hip_atomic_store(a.abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        ok = 0;
+                        break;
+                    }
+                }
+            }
+        }
+        sh.flag = ok;
+    }
+    __syncthreads();
+    return sh.flag != 0;
+}
+
+// ---- weight streaming -------------------------------------------------------------------------------
+enum { PH_QKV = 0, PH_O = 1, PH_GU = 2, PH_DOWN = 3 };
+
+struct Phase {
+    const uint16_t* W;    // matrix of this layer
+    int kind, Kd, n_items, na;
+};
+
+// first weight row of stream `st` of item `item`
+__device__ inline int tile_row(const FusedArgs& a, int kind, int item, int st) {
+    if (kind == PH_QKV) {
+        const int per = a.d / 32;                 // pair-items per projection
+        const int grp = item / per, idx = item % per;
+        if (grp < 2) {
+            const int pph = a.dh / 32;            // pairs per head: features (i, i + dh/2)
+            const int h = idx / pph, j = idx % pph;
+            return grp * a.d + h * a.dh + j * 16 + st * (a.dh / 2);
+        }
+        return 2 * a.d + (2 * idx + st) * 16;
+    }
+    if (kind == PH_GU) return st * a.F + item * 16;
+    return item * 16;
+}
+
+__device__ inline void load_w(Frag8 (&f)[4], const uint16_t* p) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) f[c].u = *reinterpret_cast<const uint4*>(p + c * 8);
+}
+
+// wave's k-step range of a phase
+__device__ inline void k_range(int Kd, int wave, int& ks0, int& nks) {
+    const int steps = Kd / 128;
+    ks0 = steps * wave / FWAVES;
+    nks = steps * (wave + 1) / FWAVES - ks0;
+}
+
+__device__ inline const uint16_t* w_ptr(const FusedArgs& a, const Phase& ph, int item, int st, int ks, int lane) {
+    return ph.W + (size_t)(tile_row(a, ph.kind, item, st) + (lane & 15)) * ph.Kd + ks * 128 + (lane >> 4) * 32;
+}
+
+// Weight streaming through a register ring. A step (128 reduction elements) of a phase with NA
+// streams occupies NA weight fragments (4 x 16 B per lane each) plus one activation fragment; the
+// ring holds DS steps, so DS-1 steps of weights (16 KiB per wave: NA = 2, DS = 3 or NA = 1, DS = 5)
+// are in flight while one is consumed. The streaming loop is kept free of branches around memory
+// instructions (past the wave's last step it re-requests that step, an L2 hit, and skips the
+// arithmetic), because the wait counters are exact only in straight-line code; partial sums of
+// finished items go to LDS inside the loop and every epilogue runs after it.
+constexpr int MAX_ITEMS_PER_WG = 3;
+
+// What survives a phase boundary: the weights issued ahead for the next phase (its first two steps
+// if NA = 2, first four if NA = 1), every fragment (re)defined by prefetch_first so that nothing
+// older stays live across the attention phase.
+struct Ring {
+    Frag8 f[4][4];
+    int primed;           // how many leading steps of the coming phase already have their weights issued
+};
+template <int NA> struct RingCfg { static constexpr int DS = NA == 2 ? 3 : 5; };
+
+struct WaveWork {         // wave-uniform description of this wave's share of a phase
+    int ks0, nks, n_my, T;
+};
+__device__ inline WaveWork wave_work(const Phase& ph) {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    WaveWork w;
+    k_range(ph.Kd, wave, w.ks0, w.nks);
+    const int nwg = gridDim.x;
+    w.n_my = (int)blockIdx.x < ph.n_items ? (ph.n_items - 1 - (int)blockIdx.x) / nwg + 1 : 0;
+    w.T = w.n_my * w.nks;
+    return w;
+}
+
+// Issue the weights of this wave's first DS-1 steps of phase `ph` (between a phase's last store and
+// the grid barrier, so that they travel while the barrier resolves).
+template <int NA>
+__device__ inline void prefetch_first(const FusedArgs& a, const Phase& ph, Ring& R) {
+    constexpr int DS = RingCfg<NA>::DS;
+    const int lane = threadIdx.x & 63;
+    const WaveWork w = wave_work(ph);
+    const int nwg = gridDim.x;
+    R.primed = 0;
+#pragma unroll
+    for (int t = 0; t < DS - 1; ++t) {
+        if (t < w.T) {
+#pragma unroll
+            for (int s = 0; s < NA; ++s)
+                load_w(R.f[t * NA + s], w_ptr(a, ph, blockIdx.x + (t / w.nks) * nwg, s, w.ks0 + t % w.nks, lane));
+            R.primed = t + 1;
+        } else {
+#pragma unroll
+            for (int s = 0; s < NA; ++s)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) R.f[t * NA + s][c].u = make_uint4(0, 0, 0, 0);
+        }
+    }
+}
+
+// Runs one GEMM phase for this workgroup. X: fp16 [16][Kd] activations (exchange buffer).
+template <int NA, class Epi>
+__device__ inline void gemm_phase(const FusedArgs& a, Shared& sh, const Phase& ph,
+                                  const uint16_t* __restrict__ X, Ring& R, Epi&& epi) {
+    constexpr int DS = RingCfg<NA>::DS;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int r = lane & 15, g = lane >> 4;
+    const WaveWork w = wave_work(ph);
+    const int nwg = gridDim.x;
+    const uint16_t* xrow = X + (size_t)r * ph.Kd + g * 32;
+
+    if (w.T > 0) {
+        Frag8 A[DS * NA][4], Bf[DS][4];
+        const uint16_t* wp[NA];             // this lane's pointers to the next step to request
+        const uint16_t* bp;
+        int jn = 0, kn = 0;                 // (item, step) of that step
+        // Past the last step the pointers park on one lane-uniform, always-valid address, so the
+        // surplus requests of the padded loop cost a single cached line each.
+        const uint16_t* park = reinterpret_cast<const uint16_t*>(a.gf);
+        auto set_item = [&](int j) {
+#pragma unroll
+            for (int s = 0; s < NA; ++s) wp[s] = w_ptr(a, ph, blockIdx.x + j * nwg, s, w.ks0, lane);
+            bp = xrow + w.ks0 * 128;
+        };
+        auto advance = [&]() {              // scalar control only
+            if (kn + 1 < w.nks) {
+                ++kn;
+#pragma unroll
+                for (int s = 0; s < NA; ++s) wp[s] += 128;
+                bp += 128;
+            } else if (jn + 1 < w.n_my) {
+                kn = 0; ++jn; set_item(jn);
+            } else {
+#pragma unroll
+                for (int s = 0; s < NA; ++s) wp[s] = park;
+                bp = park;
+            }
+        };
+        auto request = [&](int slot) {      // weights + activations of the next step, then advance
+#pragma unroll
+            for (int s = 0; s < NA; ++s) load_w(A[slot * NA + s], wp[s]);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) Bf[slot][c].u = *reinterpret_cast<const uint4*>(bp + c * 8);
+            advance();
+        };
+        set_item(0);
+        // prologue: steps 0 .. DS-2 (weights possibly already issued before the barrier)
+#pragma unroll
+        for (int t = 0; t < DS - 1; ++t) {
+            if (t < R.primed) {
+#pragma unroll
+                for (int s = 0; s < NA; ++s)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) A[t * NA + s][c] = R.f[t * NA + s][c];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) Bf[t][c].u = *reinterpret_cast<const uint4*>(bp + c * 8);
+                advance();
+            } else {
+                request(t);
+            }
+        }
+        float4_t acc[NA];
+#pragma unroll
+        for (int s = 0; s < NA; ++s) acc[s] = float4_t{0.f, 0.f, 0.f, 0.f};
+        int k = 0, jitem = 0;
+        for (int t0 = 0; t0 < w.T; t0 += DS) {
+#pragma unroll
+            for (int j = 0; j < DS; ++j) {
+                request((j + DS - 1) % DS);                   // unconditional: step t0 + j + DS - 1, clamped
+                if (t0 + j < w.T) {                           // no memory instructions inside this branch
+#pragma unroll
+                    for (int s = 0; s < NA; ++s) {
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) bf16x8_to_f16x8(A[j * NA + s][c]);
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) acc[s] = mfma_16x16x32(A[j * NA + s][c], Bf[j][c], acc[s]);
+                    }
+                    if (++k == w.nks) {
+#pragma unroll
+                        for (int s = 0; s < NA; ++s)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) sh.red[jitem][wave][s][i][lane] = acc[s][i];
+#pragma unroll
+                        for (int s = 0; s < NA; ++s) acc[s] = float4_t{0.f, 0.f, 0.f, 0.f};
+                        k = 0;
+                        ++jitem;
+                    }
+                }
+            }
+        }
+    } else {
+        for (int j = 0; j < w.n_my; ++j)
+#pragma unroll
+            for (int s = 0; s < NA; ++s)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sh.red[j][wave][s][i][lane] = 0.f;
+    }
+    R.primed = 0;
+    __syncthreads();
+    // ---- split-K reduction and the phase's epilogue, 128 threads: thread -> (row, two features) ----
+    if (threadIdx.x < 128) {
+        const int row = threadIdx.x >> 3, f0 = (threadIdx.x & 7) * 2;
+        for (int j = 0; j < w.n_my; ++j) {
+            float v[NA][2];
+#pragma unroll
+            for (int s = 0; s < NA; ++s)
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const int f = f0 + q;
+                    const int ln = (f >> 2) * 16 + row, i = f & 3;
+                    float t = 0.f;
+#pragma unroll
+                    for (int wv = 0; wv < FWAVES; ++wv) t += sh.red[j][wv][s][i][ln];
+                    v[s][q] = row < a.M ? t : 0.f;      // padding rows stay exactly zero
+                }
+            epi((int)blockIdx.x + j * nwg, row, f0, v);
+        }
+    }
+    __syncthreads();        // the union with the attention buffers and the rs[] reuse need a full stop
+}
+
+// rs[row] = rsqrt(mean square + eps) from the per-workgroup partial sums of one norm point
+__device__ inline void load_rs(const FusedArgs& a, Shared& sh, const float* ss /*[nwg][16]*/) {
+    const int nwg = gridDim.x;
+    if (threadIdx.x < 128) {
+        const int row = threadIdx.x >> 3, part = threadIdx.x & 7;
+        float t = 0.f;
+        for (int w = part; w < nwg; w += 8) t += ss[(size_t)w * 16 + row];
+        sh.ss_acc[row][part] = t;
+    }
+    __syncthreads();
+    if (threadIdx.x < 16) {
+        float t = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t += sh.ss_acc[threadIdx.x][j];
+        sh.rs[threadIdx.x] = rsqrtf(t / (float)a.d + a.eps);
+    }
+    __syncthreads();
+}
+
+// publish this workgroup's partial sum of squares (threads < 128 hold one row each, 8 threads per row)
+__device__ inline void publish_ss(Shared& sh, float* ss_out /*[16] of this workgroup*/, float mine) {
+    if (threadIdx.x < 128) sh.ss_acc[threadIdx.x >> 3][threadIdx.x & 7] = mine;
+    __syncthreads();
+    if (threadIdx.x < 16) {
+        float t = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t += sh.ss_acc[threadIdx.x][j];
+        st_f32(ss_out + threadIdx.x, t);
+    }
+    __syncthreads();
+}
+
+// ---- attention ---------------------------------------------------------------------------------------
+template <int DH>
+__device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer) {
+    constexpr int NC32 = DH / 32, NC16 = DH / 16;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r = lane & 15, g = lane >> 4;
+    const int S = a.nsplit, n_items = a.B * a.H * S;
+    const float scale = rsqrtf((float)DH);
+    const size_t lo = (size_t)layer * 16 * a.d;
+    const uint16_t* qb = a.qbuf + lo;
+    const uint16_t* kn = a.knew + lo;
+    const uint16_t* vn = a.vnew + lo;
+    uint16_t* ob = a.attn + lo;
+    const int PSZ = 32 + 16 * DH;
+
+    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const int split = item % S, bh = item / S, h = bh % a.H, b = bh / a.H;
+        const int slot = a.seq_ids[b];
+        const int len = a.lens[slot];
+        // Pages are taken at their cache positions, one page per wave and a fixed AW pages per split,
+        // and a page that holds new rows is composed from the cache (slots < len) and the exchange
+        // buffers (slots len .. len+R-1). The arithmetic a row sees therefore depends only on its own
+        // position, never on how many rows are verified with it or on the host's length bound: a token
+        // verified as a draft gets bit-identical logits to the same token decoded one at a time.
+        const int n_pages = (len + a.R + kPageSize - 1) / kPageSize;
+        const int32_t* bt = a.block_table + (size_t)slot * a.mpps;
+
+        float m_run = -INFINITY, l_run = 0.f;
+        float4_t acc[NC16];
+#pragma unroll
+        for (int c = 0; c < NC16; ++c) acc[c] = float4_t{0.f, 0.f, 0.f, 0.f};
+        if (wave < AW) {
+            const int p = split * AW + wave;
+            if (p < n_pages) {
+                Frag8 bq[NC32];
+                {
+                    const int qr = min(r, a.R - 1);
+                    const uint16_t* qp = qb + (size_t)(b * a.R + qr) * a.d + (size_t)h * DH + g * 8;
+#pragma unroll
+                    for (int c = 0; c < NC32; ++c) bq[c].u = *reinterpret_cast<const uint4*>(qp + c * 32);
+                }
+                Frag8 ak[NC32];
+                Frag4 bv[NC16];
+                const size_t base = (((size_t)layer * a.n_pages + bt[p]) * a.H + h) * kPageSize * DH;
+                const int s0 = p * kPageSize;                         // first slot of the page
+                if (s0 + kPageSize <= len) {                          // committed slots only
+                    const uint16_t* kp = a.kpages + base + (size_t)r * DH + g * 8;
+#pragma unroll
+                    for (int c = 0; c < NC32; ++c) ak[c].u = *reinterpret_cast<const uint4*>(kp + c * 32);
+                    const uint16_t* vp = a.vpages + base + (size_t)r * kPageSize + 4 * g;
+#pragma unroll
+                    for (int c = 0; c < NC16; ++c) bv[c].u = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * kPageSize);
+                } else {
+                    const int ks = s0 + r;                            // this lane's key slot
+                    const bool k_new = ks >= len;
+                    const int kr = min(max(ks - len, 0), a.R - 1);
+                    const uint16_t* kp = k_new ? kn + (size_t)(b * a.R + kr) * a.d + (size_t)h * DH + g * 8
+                                               : a.kpages + base + (size_t)r * DH + g * 8;
+#pragma unroll
+                    for (int c = 0; c < NC32; ++c) ak[c].u = *reinterpret_cast<const uint4*>(kp + c * 32);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int vs = s0 + 4 * g + j;                // value slot
+                        const bool v_new = vs >= len;
+                        const int vr = min(max(vs - len, 0), a.R - 1);
+#pragma unroll
+                        for (int c = 0; c < NC16; ++c)
+                            bv[c].h[j] = v_new ? vn[(size_t)(b * a.R + vr) * a.d + (size_t)h * DH + c * 16 + r]
+                                               : a.vpages[base + (size_t)(c * 16 + r) * kPageSize + 4 * g + j];
+                    }
+                    // this wave owns the page: store its new rows into the cache for later steps
+                    if (k_new && ks < len + a.R) {
+                        uint16_t* kd = a.kpages + base + (size_t)r * DH + g * 8;
+#pragma unroll
+                        for (int c = 0; c < NC32; ++c) *reinterpret_cast<uint4*>(kd + c * 32) = ak[c].u;
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int vs = s0 + 4 * g + j;
+                        if (vs >= len && vs < len + a.R) {
+#pragma unroll
+                            for (int c = 0; c < NC16; ++c)
+                                a.vpages[base + (size_t)(c * 16 + r) * kPageSize + 4 * g + j] = bv[c].h[j];
+                        }
+                    }
+                }
+                float4_t s = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int c = 0; c < NC32; ++c) s = mfma_16x16x32(ak[c], bq[c], s);
+                float sv[4], mx = -INFINITY;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int ts = s0 + 4 * g + i;                 // slot of this score's key
+                    const bool vis = (r < a.R) && (ts <= len + r);   // query row r sits at slot len + r
+                    sv[i] = vis ? s[i] * scale : -INFINITY;
+                    mx = fmaxf(mx, sv[i]);
+                }
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m_run, mx);
+                const float alpha = (m_new == -INFINITY) ? 1.f : __expf(m_run - m_new);
+                Frag4 pa;
+                float rsum = 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float pv = (sv[i] == -INFINITY) ? 0.f : __expf(sv[i] - m_new);
+                    rsum += pv;
+                    pa.h[i] = f32_to_f16(pv);
+                }
+                rsum += __shfl_xor(rsum, 16);
+                rsum += __shfl_xor(rsum, 32);
+                l_run = l_run * alpha + rsum;
+                m_run = m_new;
+                float al[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) al[i] = __shfl(alpha, 4 * g + i);
+#pragma unroll
+                for (int c = 0; c < NC16; ++c) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[c][i] *= al[i];
+                    acc[c] = mfma_16x16x16(pa, bv[c], acc[c]);
+                }
+            }
+            if (g == 0) { sh.att_m[wave][r] = m_run; sh.att_l[wave][r] = l_run; }
+#pragma unroll
+            for (int c = 0; c < NC16; ++c)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sh.att_o[wave][4 * g + i][c * 16 + r] = acc[c][i];
+        }
+        __syncthreads();
+        float* part = a.apart + (((size_t)layer * a.B * a.H + bh) * S + split) * PSZ;
+        // merge the waves: thread t -> (q, channel pair)
+        for (int idx = threadIdx.x; idx < 16 * DH / 2; idx += FT) {
+            const int q = idx / (DH / 2), c = (idx % (DH / 2)) * 2;
+            float M = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < AW; ++w) M = fmaxf(M, sh.att_m[w][q]);
+            float Lq = 0.f, O0 = 0.f, O1 = 0.f;
+            if (M != -INFINITY) {
+#pragma unroll
+                for (int w = 0; w < AW; ++w) {
+                    const float f = __expf(sh.att_m[w][q] - M);
+                    Lq += sh.att_l[w][q] * f;
+                    O0 += sh.att_o[w][q][c] * f;
+                    O1 += sh.att_o[w][q][c + 1] * f;
+                }
+            }
+            if (S == 1) {
+                if (q < a.R) st_u32(ob + (size_t)(b * a.R + q) * a.d + (size_t)h * DH + c,
+                                    pack_h2(Lq > 0.f ? O0 / Lq : 0.f, Lq > 0.f ? O1 / Lq : 0.f));
+            } else {
+                if (c == 0) { st_f32(part + q, M); st_f32(part + 16 + q, Lq); }
+                st_f32(part + 32 + q * DH + c, O0);
+                st_f32(part + 32 + q * DH + c + 1, O1);
+            }
+        }
+        if (S > 1) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's partial stores have completed
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                int* cnt = a.acount + (size_t)layer * a.B * a.H + bh;
+                const int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                sh.flag = (old == S - 1) ? 1 : 0;
+                if (old == S - 1) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            __syncthreads();
+            if (sh.flag) {                   // last to arrive: combine the S partials of (b, h)
+                const float* pbase = a.apart + (((size_t)layer * a.B * a.H + bh) * S) * PSZ;
+                for (int idx = threadIdx.x; idx < 16 * DH / 2; idx += FT) {
+                    const int q = idx / (DH / 2), c = (idx % (DH / 2)) * 2;
+                    if (q >= a.R) continue;
+                    float M = -INFINITY;
+                    for (int s2 = 0; s2 < S; ++s2) M = fmaxf(M, pbase[(size_t)s2 * PSZ + q]);
+                    float Lq = 0.f, O0 = 0.f, O1 = 0.f;
+                    if (M != -INFINITY)
+                        for (int s2 = 0; s2 < S; ++s2) {
+                            const float* ps = pbase + (size_t)s2 * PSZ;
+                            const float f = __expf(ps[q] - M);
+                            Lq += ps[16 + q] * f;
+                            O0 += ps[32 + q * DH + c] * f;
+                            O1 += ps[32 + q * DH + c + 1] * f;
+                        }
+                    st_u32(ob + (size_t)(b * a.R + q) * a.d + (size_t)h * DH + c,
+                           pack_h2(Lq > 0.f ? O0 / Lq : 0.f, Lq > 0.f ? O1 / Lq : 0.f));
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// ---- output head: per-wave vocabulary tiles, running statistics in registers ----------------------
+__device__ inline bool hbefore(float v, int i, float w, int j) { return v > w || (v == w && i < j); }
+
+struct HStat {
+    float mx, sum, lx;
+    int arg;
+    float tv[KTOP];
+    int ti[KTOP];
+    __device__ void init() {
+        mx = -INFINITY; sum = 0.f; lx = -INFINITY; arg = 0x7FFFFFFF;
+#pragma unroll
+        for (int j = 0; j < KTOP; ++j) { tv[j] = -INFINITY; ti[j] = 0x7FFFFFFF; }
+    }
+    __device__ void push_top(float v, int n) {
+        if (!hbefore(v, n, tv[KTOP - 1], ti[KTOP - 1])) return;
+        tv[KTOP - 1] = v; ti[KTOP - 1] = n;
+#pragma unroll
+        for (int j = KTOP - 1; j > 0; --j)
+            if (hbefore(tv[j], ti[j], tv[j - 1], ti[j - 1])) {
+                const float fv = tv[j]; tv[j] = tv[j - 1]; tv[j - 1] = fv;
+                const int fi = ti[j]; ti[j] = ti[j - 1]; ti[j - 1] = fi;
+            }
+    }
+    __device__ void add(float v, int n) {
+        if (v > mx) { sum = sum * __expf(mx - v) + 1.f; mx = v; arg = n; }
+        else sum += __expf(v - mx);
+        push_top(v, n);
+    }
+    __device__ void merge_xor(int off) {
+        const float omx = __shfl_xor(mx, off), osum = __shfl_xor(sum, off), olx = __shfl_xor(lx, off);
+        const int oarg = __shfl_xor(arg, off);
+        float otv[KTOP]; int oti[KTOP];
+#pragma unroll
+        for (int j = 0; j < KTOP; ++j) { otv[j] = __shfl_xor(tv[j], off); oti[j] = __shfl_xor(ti[j], off); }
+        const float M = fmaxf(mx, omx);
+        if (M != -INFINITY) sum = sum * __expf(mx - M) + osum * __expf(omx - M);
+        if (hbefore(omx, oarg, mx, arg)) arg = oarg;
+        mx = M;
+        lx = fmaxf(lx, olx);
+#pragma unroll
+        for (int j = 0; j < KTOP; ++j) push_top(otv[j], oti[j]);
+    }
+};
+
+__device__ inline void head_phase(const FusedArgs& a, Shared& sh, const uint16_t* __restrict__ X, int chunks) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r = lane & 15, g = lane >> 4;
+    const int chunk = blockIdx.x * FWAVES + wave;          // chunk id == global wave id
+    const int ntiles = a.V / 16;
+    const int row = r;
+    int x = -1;
+    if (row < a.M) {
+        const int b = row / a.R, rr = row % a.R;
+        x = (rr < a.K && rr < a.draft_len[b]) ? a.drafts[(size_t)b * a.K + rr] : -1;
+        if (x >= a.V) x = -1;
+    }
+    HStat st;
+    st.init();
+    const float rs = sh.rs[r];
+    const uint16_t* xrow = X + (size_t)r * a.d + g * 32;
+    const int steps = a.d / 128;
+    for (int t = chunk; t < ntiles; t += chunks) {
+        const uint16_t* wp = a.wlm + (size_t)(t * 16 + r) * a.d + g * 32;
+        float4_t acc = float4_t{0.f, 0.f, 0.f, 0.f};
+        Frag8 a_cur[4], a_nxt[4], b_cur[4], b_nxt[4];
+        load_w(a_cur, wp);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) b_cur[c].u = *reinterpret_cast<const uint4*>(xrow + c * 8);
+        for (int k = 0; k < steps; ++k) {
+            if (k + 1 < steps) {
+                load_w(a_nxt, wp + (k + 1) * 128);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) b_nxt[c].u = *reinterpret_cast<const uint4*>(xrow + (k + 1) * 128 + c * 8);
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) bf16x8_to_f16x8(a_cur[c]);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc = mfma_16x16x32(a_cur[c], b_cur[c], acc);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) { a_cur[c] = a_nxt[c]; b_cur[c] = b_nxt[c]; }
+        }
+        const int n = t * 16 + 4 * g;
+        float lv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            lv[i] = acc[i] * rs;
+            st.add(lv[i], n + i);
+            if (n + i == x) st.lx = lv[i];
+        }
+        if (a.logits_dbg && row < a.M)
+            *reinterpret_cast<float4*>(a.logits_dbg + (size_t)row * a.V + n) = make_float4(lv[0], lv[1], lv[2], lv[3]);
+    }
+    st.merge_xor(16);
+    st.merge_xor(32);
+    if (g == 0 && row < a.M) {
+        const size_t o = (size_t)row * chunks + chunk;
+        st_f32(a.hp_max + o, st.mx); st_f32(a.hp_sum + o, st.sum); st_i32(a.hp_arg + o, st.arg);
+#pragma unroll
+        for (int j = 0; j < KTOP; ++j) { st_f32(a.hp_topv + o * KTOP + j, st.tv[j]); st_i32(a.hp_topi + o * KTOP + j, st.ti[j]); }
+        if (st.lx != -INFINITY) st_f32(a.hp_lx + row, st.lx);
+    }
+}
+
+__device__ inline void accept_phase(const FusedArgs& a, Shared& sh, int chunks) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int b = blockIdx.x; b < a.B; b += gridDim.x) {
+        for (int r = 0; r < a.R; ++r) {
+            const int row = b * a.R + r;
+            int x = (r < a.K && r < a.draft_len[b]) ? a.drafts[(size_t)b * a.K + r] : -1;
+            if (x >= a.V) x = -1;
+            const float lx = x >= 0 ? a.hp_lx[row] : -INFINITY;
+            float mx = -INFINITY, sum = 0.f;
+            int arg = 0x7FFFFFFF, ahead = 0;
+            for (int c = threadIdx.x; c < chunks; c += FT) {
+                const size_t o = (size_t)row * chunks + c;
+                const float cm = a.hp_max[o], cs = a.hp_sum[o];
+                const int ca = a.hp_arg[o];
+                const float M = fmaxf(mx, cm);
+                if (M != -INFINITY) sum = sum * __expf(mx - M) + cs * __expf(cm - M);
+                if (hbefore(cm, ca, mx, arg)) arg = ca;
+                mx = M;
+                if (x >= 0)
+#pragma unroll
+                    for (int j = 0; j < KTOP; ++j) {
+                        const float v = a.hp_topv[o * KTOP + j];
+                        const int i = a.hp_topi[o * KTOP + j];
+                        ahead += (i != x && hbefore(v, i, lx, x)) ? 1 : 0;
+                    }
+            }
+            for (int off = 32; off > 0; off >>= 1) {
+                const float omx = __shfl_xor(mx, off), osum = __shfl_xor(sum, off);
+                const int oarg = __shfl_xor(arg, off);
+                ahead += __shfl_xor(ahead, off);
+                const float M = fmaxf(mx, omx);
+                if (M != -INFINITY) sum = sum * __expf(mx - M) + osum * __expf(omx - M);
+                if (hbefore(omx, oarg, mx, arg)) arg = oarg;
+                mx = M;
+            }
+            __syncthreads();
+            if (lane == 0) { sh.hstat[wave][0] = mx; sh.hstat[wave][1] = sum; sh.hstat_i[wave][0] = arg; sh.hstat_i[wave][1] = ahead; }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                float M = -INFINITY, S = 0.f; int A = 0x7FFFFFFF, rank = 0;
+                for (int w = 0; w < FWAVES; ++w) {
+                    const float wm = sh.hstat[w][0];
+                    const float nm = fmaxf(M, wm);
+                    if (nm != -INFINITY) S = S * __expf(M - nm) + sh.hstat[w][1] * __expf(wm - nm);
+                    if (hbefore(wm, sh.hstat_i[w][0], M, A)) A = sh.hstat_i[w][0];
+                    M = nm;
+                    rank += sh.hstat_i[w][1];
+                }
+                bool ok = false;
+                if (x >= 0) {
+                    const float q = __expf(lx - M) / S;
+                    const bool in_k = rank < a.topk, above = q > a.p, top1 = rank == 0;
+                    ok = a.mode == LASER_MODE_RV ? (in_k && above)
+                       : a.mode == LASER_MODE_RV_OR_TOP1 ? (top1 || (in_k && above))
+                       : a.mode == LASER_MODE_TOPK_ONLY ? in_k : (top1 || above);
+                }
+                sh.row_ok[r] = ok ? 1 : 0;
+                sh.row_arg[r] = A;
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int dl = a.draft_len[b];
+            dl = dl < 0 ? 0 : (dl > a.K ? a.K : dl);
+            int n = 0;
+            while (n < dl && sh.row_ok[n]) ++n;
+            a.accept_len[b] = n;
+            int32_t* out = a.out_tokens + (size_t)b * a.R;
+            for (int j = 0; j < a.R; ++j) out[j] = j < n ? a.drafts[(size_t)b * a.K + j] : (j == n ? sh.row_arg[n] : -1);
+        }
+        __syncthreads();
+    }
+}
+
+// ---- the kernel --------------------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    Shared& sh = *reinterpret_cast<Shared*>(smem_raw);
+    const int nwg = gridDim.x;
+    unsigned long long epoch = 0;
+    const size_t XS = (size_t)16 * a.d;                 // one x / xg buffer
+
+    if (threadIdx.x < 16) {
+        const int row = threadIdx.x;
+        int pos = 0, b = 0;
+        if (row < a.M) { b = row / a.R; pos = a.lens[a.seq_ids[b]] + row % a.R; }
+        sh.row_pos[row] = pos;
+        sh.row_b[row] = b;
+    }
+    __syncthreads();
+
+    Ring ring;
+    ring.primed = 0;
+    Phase ph_qkv{a.wqkv, PH_QKV, a.d, 3 * a.d / 32, 2};
+    if (a.L > 0) prefetch_first<2>(a, ph_qkv, ring);   // layer 0's first QKV weights travel during the embedding
+
+    // ---- phase 0: embedding, x0, x0*g1[0], sum of squares ----
+    {
+        float ss = 0.f;
+        const int row = threadIdx.x >> 3, f0 = (threadIdx.x & 7) * 2;
+        const float* gain0 = a.L > 0 ? a.g1 : a.gf;
+        for (int tile = blockIdx.x; tile < a.d / 16; tile += nwg) {
+            if (threadIdx.x < 128) {
+                float v0 = 0.f, v1 = 0.f;
+                if (row < a.M) {
+                    const int b = row / a.R, rr = row % a.R;
+                    int tok = rr == 0 ? a.pending[b] : ((rr - 1) < a.draft_len[b] ? a.drafts[(size_t)b * a.K + rr - 1] : 0);
+                    if (tok < 0 || tok >= a.V) tok = 0;
+                    const uint32_t e = *reinterpret_cast<const uint32_t*>(a.emb + (size_t)tok * a.d + tile * 16 + f0);
+                    v0 = __uint_as_float(e << 16);
+                    v1 = __uint_as_float(e & 0xFFFF0000u);
+                }
+                const size_t o = (size_t)row * a.d + tile * 16 + f0;
+                st_f32(a.xbuf + o, v0); st_f32(a.xbuf + o + 1, v1);
+                st_u32(a.xgbuf + o, pack_h2(v0 * gain0[tile * 16 + f0], v1 * gain0[tile * 16 + f0 + 1]));
+                ss += v0 * v0 + v1 * v1;
+            }
+        }
+        publish_ss(sh, a.ssbuf + (size_t)blockIdx.x * 16, ss);
+    }
+    int ns = 0;
+    auto no_prefetch = [] {};
+    stamp(a, ns);
+    if (!grid_sync(a, sh, epoch, no_prefetch)) return;
+    stamp(a, ns);
+
+    for (int l = 0; l < a.L; ++l) {
+        const float* x_in = a.xbuf + (size_t)(2 * l) * XS;           // after the previous layer
+        float* x_mid = a.xbuf + (size_t)(2 * l + 1) * XS;             // after attention
+        float* x_out = a.xbuf + (size_t)(2 * l + 2) * XS;             // after the FFN
+        const uint16_t* xg_in = a.xgbuf + (size_t)(2 * l) * XS;
+        uint16_t* xg_mid = a.xgbuf + (size_t)(2 * l + 1) * XS;
+        uint16_t* xg_out = a.xgbuf + (size_t)(2 * l + 2) * XS;
+        const float* ss_in = a.ssbuf + (size_t)(2 * l) * nwg * 16;
+        float* ss_mid = a.ssbuf + (size_t)(2 * l + 1) * nwg * 16;
+        float* ss_out = a.ssbuf + (size_t)(2 * l + 2) * nwg * 16;
+        const size_t lo = (size_t)l * XS;
+
+        Phase p_qkv{a.wqkv + (size_t)l * 3 * a.d * a.d, PH_QKV, a.d, 3 * a.d / 32, 2};
+        Phase p_o{a.wo + (size_t)l * a.d * a.d, PH_O, a.d, a.d / 16, 1};
+        Phase p_gu{a.wgu + (size_t)l * 2 * a.F * a.d, PH_GU, a.d, a.F / 16, 2};
+        Phase p_dn{a.wdown + (size_t)l * a.d * a.F, PH_DOWN, a.F, a.d / 16, 1};
+        Phase p_nq{a.wqkv + (size_t)(l + 1) * 3 * a.d * a.d, PH_QKV, a.d, 3 * a.d / 32, 2};
+
+        // ---- QKV + RoPE ----
+        load_rs(a, sh, ss_in);
+        {
+            const int per = a.d / 32, pph = DH / 32, half = DH / 2;
+            gemm_phase<2>(a, sh, p_qkv, xg_in, ring, [&](int item, int row, int f0, float (&v)[2][2]) {
+                const float rs = sh.rs[row];
+                const int grp = item / per, idx = item % per;
+                if (grp < 2) {
+                    const int h = idx / pph, j = idx % pph;
+                    const int c0 = h * DH + j * 16 + f0;                  // channel of v[0][*]; partner at c0 + half
+                    const int pos = sh.row_pos[row];
+                    float o0[2], o1[2];
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const float2 cs = a.rope[(size_t)pos * half + (j * 16 + f0 + q)];
+                        const float x0 = v[0][q] * rs, x1 = v[1][q] * rs;
+                        o0[q] = x0 * cs.x - x1 * cs.y;
+                        o1[q] = x0 * cs.y + x1 * cs.x;
+                    }
+                    uint16_t* dst = (grp == 0 ? a.qbuf : a.knew) + lo + (size_t)row * a.d;
+                    st_u32(dst + c0, pack_h2(o0[0], o0[1]));
+                    st_u32(dst + c0 + half, pack_h2(o1[0], o1[1]));
+                } else {
+                    uint16_t* dst = a.vnew + lo + (size_t)row * a.d + idx * 32 + f0;
+                    st_u32(dst, pack_h2(v[0][0] * rs, v[0][1] * rs));
+                    st_u32(dst + 16, pack_h2(v[1][0] * rs, v[1][1] * rs));
+                }
+            });
+        }
+        stamp(a, ns);
+        if (!grid_sync(a, sh, epoch, [&] { prefetch_first<1>(a, p_o, ring); })) return;
+        stamp(a, ns);
+
+        // ---- attention ----
+        attention_phase<DH>(a, sh, l);
+        stamp(a, ns);
+        if (!grid_sync(a, sh, epoch, no_prefetch)) return;
+        stamp(a, ns);
+
+        // ---- O projection + residual; publish x, x*g2, sum of squares ----
+        {
+            float ss = 0.f;
+            const float* g2 = a.g2 + (size_t)l * a.d;
+            gemm_phase<1>(a, sh, p_o, a.attn + lo, ring, [&](int item, int row, int f0, float (&v)[1][2]) {
+                const size_t o = (size_t)row * a.d + item * 16 + f0;
+                const float n0 = x_in[o] + v[0][0], n1 = x_in[o + 1] + v[0][1];
+                st_f32(x_mid + o, n0); st_f32(x_mid + o + 1, n1);
+                st_u32(xg_mid + o, pack_h2(n0 * g2[item * 16 + f0], n1 * g2[item * 16 + f0 + 1]));
+                ss += n0 * n0 + n1 * n1;
+            });
+            publish_ss(sh, ss_mid + (size_t)blockIdx.x * 16, ss);
+        }
+        stamp(a, ns);
+        if (!grid_sync(a, sh, epoch, [&] { prefetch_first<2>(a, p_gu, ring); })) return;
+        stamp(a, ns);
+
+        // ---- gate/up + SwiGLU ----
+        load_rs(a, sh, ss_mid);
+        {
+            uint16_t* act = a.act + (size_t)l * 16 * a.F;
+            gemm_phase<2>(a, sh, p_gu, xg_mid, ring, [&](int item, int row, int f0, float (&v)[2][2]) {
+                const float rs = sh.rs[row];
+                float o[2];
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const float gt = v[0][q] * rs, up = v[1][q] * rs;
+                    o[q] = gt / (1.f + __expf(-gt)) * up;
+                }
+                st_u32(act + (size_t)row * a.F + item * 16 + f0, pack_h2(o[0], o[1]));
+            });
+        }
+        stamp(a, ns);
+        if (!grid_sync(a, sh, epoch, [&] { prefetch_first<1>(a, p_dn, ring); })) return;
+        stamp(a, ns);
+
+        // ---- down projection + residual; publish x, x*gain(next norm), sum of squares ----
+        {
+            float ss = 0.f;
+            const bool last = l + 1 == a.L;
+            const float* gn = last ? a.gf : a.g1 + (size_t)(l + 1) * a.d;
+            gemm_phase<1>(a, sh, p_dn, a.act + (size_t)l * 16 * a.F, ring,
+                          [&](int item, int row, int f0, float (&v)[1][2]) {
+                const size_t o = (size_t)row * a.d + item * 16 + f0;
+                const float n0 = x_mid[o] + v[0][0], n1 = x_mid[o + 1] + v[0][1];
+                st_f32(x_out + o, n0); st_f32(x_out + o + 1, n1);
+                st_u32(xg_out + o, pack_h2(n0 * gn[item * 16 + f0], n1 * gn[item * 16 + f0 + 1]));
+                ss += n0 * n0 + n1 * n1;
+            });
+            publish_ss(sh, ss_out + (size_t)blockIdx.x * 16, ss);
+        }
+        stamp(a, ns);
+        if (!grid_sync(a, sh, epoch, [&] { if (l + 1 < a.L) prefetch_first<2>(a, p_nq, ring); })) return;
+        stamp(a, ns);
+    }
+
+    // ---- output head + acceptance ----
+    const int chunks = nwg * FWAVES;
+    load_rs(a, sh, a.ssbuf + (size_t)(2 * a.L) * nwg * 16);
+    head_phase(a, sh, a.xgbuf + (size_t)(2 * a.L) * XS, chunks);
+    stamp(a, ns);
+    if (!grid_sync(a, sh, epoch, no_prefetch)) return;
+    stamp(a, ns);
+    accept_phase(a, sh, chunks);
+    stamp(a, ns);
+}
+
+// ---- host side ---------------------------------------------------------------------------------------
+static int g_num_cu = 0;
+
+struct FusedWS {
+    void* blob = nullptr;
+    size_t bytes = 0;
+    unsigned long long* bar = nullptr;     // [0] count, [32] flag (separate 128-byte lines), abort at [64]
+    int L = 0, d = 0, F = 0, nwg = 0, bh_cap = 0, dh = 0;
+    float* xbuf; uint16_t* xgbuf; float* ssbuf; uint16_t *qbuf, *knew, *vnew, *attn, *act; float* apart; int* acount;
+    float *hp_max, *hp_sum; int32_t* hp_arg; float* hp_topv; int32_t* hp_topi; float* hp_lx;
+    unsigned long long epoch = 0;
+    long long* trace = nullptr;
+    int trace_cap = 0;
+};
+
+bool fused_supported(const Model* m, int B, int K) {
+    const laser_model_desc& d = m->d;
+    if (g_num_cu == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return false;
+        g_num_cu = prop.multiProcessorCount;
+    }
+    const int cap = MAX_ITEMS_PER_WG * g_num_cu;         // GEMM items one launch can take per phase
+    return d.n_layers > 0 && B * (K + 1) <= 16 && d.d_model % 128 == 0 && d.ffn % 128 == 0 && d.vocab % 16 == 0 &&
+           (m->dh == 64 || m->dh == 128) && 3 * d.d_model / 32 <= cap && d.ffn / 16 <= cap && d.d_model / 16 <= cap;
+}
+
+void fused_free(Model* m) {
+    FusedWS* ws = reinterpret_cast<FusedWS*>(m->fused_ws);
+    if (!ws) return;
+    if (ws->blob) (void)hipFree(ws->blob);
+    if (ws->bar) (void)hipFree(ws->bar);
+    if (ws->trace) (void)hipFree(ws->trace);
+    delete ws;
+    m->fused_ws = nullptr;
+}
+
+static int fused_prepare(Model* m, int B, hipStream_t stream, FusedWS** out) {
+    if (g_num_cu == 0) {
+        int dev = 0;
+        LASER_HIP_CHECK(hipGetDevice(&dev));
+        hipDeviceProp_t prop;
+        LASER_HIP_CHECK(hipGetDeviceProperties(&prop, dev));
+        g_num_cu = prop.multiProcessorCount;
+    }
+    const laser_model_desc& d = m->d;
+    FusedWS* ws = reinterpret_cast<FusedWS*>(m->fused_ws);
+    const int nwg = g_num_cu;
+    const int bh_cap = 16 * nwg;                      // (sequence, head, split) triples the partial buffer can hold
+    if (!ws) {
+        ws = new FusedWS();
+        m->fused_ws = ws;
+        const size_t L = d.n_layers, XS = (size_t)16 * d.d_model, PSZ = 32 + 16 * m->dh, CH = (size_t)nwg * FWAVES;
+        size_t off = 0;
+        auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
+        const size_t o_x = take((2 * L + 1) * XS * 4), o_xg = take((2 * L + 1) * XS * 2), o_ss = take((2 * L + 1) * nwg * 16 * 4);
+        const size_t o_q = take(L * XS * 2), o_k = take(L * XS * 2), o_v = take(L * XS * 2), o_a = take(L * XS * 2);
+        const size_t o_act = take(L * 16 * (size_t)d.ffn * 2), o_ap = take(L * bh_cap * PSZ * 4), o_ac = take(L * bh_cap * 4);
+        const size_t o_hm = take(16 * CH * 4), o_hs = take(16 * CH * 4), o_ha = take(16 * CH * 4);
+        const size_t o_tv = take(16 * CH * KTOP * 4), o_ti = take(16 * CH * KTOP * 4), o_lx = take(16 * 4);
+        LASER_HIP_CHECK(hipMalloc(&ws->blob, off));
+        ws->bytes = off;
+        LASER_HIP_CHECK(hipMemsetAsync(ws->blob, 0, off, stream));
+        LASER_HIP_CHECK(hipMalloc((void**)&ws->bar, 1024));
+        LASER_HIP_CHECK(hipMemsetAsync(ws->bar, 0, 1024, stream));
+        char* b = reinterpret_cast<char*>(ws->blob);
+        ws->xbuf = (float*)(b + o_x); ws->xgbuf = (uint16_t*)(b + o_xg); ws->ssbuf = (float*)(b + o_ss);
+        ws->qbuf = (uint16_t*)(b + o_q); ws->knew = (uint16_t*)(b + o_k); ws->vnew = (uint16_t*)(b + o_v);
+        ws->attn = (uint16_t*)(b + o_a); ws->act = (uint16_t*)(b + o_act); ws->apart = (float*)(b + o_ap);
+        ws->acount = (int*)(b + o_ac);
+        ws->hp_max = (float*)(b + o_hm); ws->hp_sum = (float*)(b + o_hs); ws->hp_arg = (int32_t*)(b + o_ha);
+        ws->hp_topv = (float*)(b + o_tv); ws->hp_topi = (int32_t*)(b + o_ti); ws->hp_lx = (float*)(b + o_lx);
+        ws->nwg = nwg; ws->bh_cap = bh_cap;
+        const size_t lds = sizeof(Shared);
+        if (m->dh == 128) LASER_HIP_CHECK(hipFuncSetAttribute((const void*)verify_fused_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        else LASER_HIP_CHECK(hipFuncSetAttribute((const void*)verify_fused_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    }
+    if (m->fused_trace && !ws->trace) {
+        ws->trace_cap = 2 * (5 * d.n_layers + 2) + 4;
+        LASER_HIP_CHECK(hipMalloc((void**)&ws->trace, (size_t)ws->nwg * ws->trace_cap * sizeof(long long)));
+        LASER_HIP_CHECK(hipMemsetAsync(ws->trace, 0, (size_t)ws->nwg * ws->trace_cap * sizeof(long long), stream));
+    }
+    *out = ws;
+    (void)B;
+    return LASER_OK;
+}
+
+int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, const int32_t* drafts,
+              const int32_t* draft_len, int B, int K, int topk, float p, int mode, int32_t* accept_len,
+              int32_t* out_tokens, float* logits_dbg, int max_len_ub, hipStream_t stream) {
+    FusedWS* ws = nullptr;
+    int rc = fused_prepare(m, B, stream, &ws);
+    if (rc) return rc;
+    const laser_model_desc& d = m->d;
+    const int R = K + 1;
+    // context splits: a fixed AW pages (128 tokens) each, enough to cover the longest sequence
+    const int pages_ub = (max_len_ub + R + kPageSize - 1) / kPageSize;
+    const int S = std::max(1, (pages_ub + AW - 1) / AW);
+    LASER_REQUIRE(B * d.n_heads * S <= ws->bh_cap, LASER_E_LIMIT,
+                  "context of %d tokens needs %d attention splits; the persistent kernel holds %d (use option fused = 0)",
+                  max_len_ub + R, B * d.n_heads * S, ws->bh_cap);
+    FusedArgs a{};
+    a.wqkv = d.wqkv; a.wo = d.wo; a.wgu = d.wgu; a.wdown = d.wdown; a.emb = d.emb; a.wlm = d.wlm;
+    a.g1 = d.g1; a.g2 = d.g2; a.gf = d.gf;
+    a.L = d.n_layers; a.d = d.d_model; a.H = d.n_heads; a.dh = m->dh; a.F = d.ffn; a.V = d.vocab; a.eps = d.eps;
+    a.rope = m->rope;
+    a.kpages = kv->kpages; a.vpages = kv->vpages; a.block_table = kv->block_table; a.lens = kv->len;
+    a.mpps = kv->d.max_pages_per_seq; a.n_pages = kv->d.n_pages;
+    a.seq_ids = ids_dev; a.pending = pending; a.drafts = drafts; a.draft_len = draft_len;
+    a.B = B; a.K = K; a.R = R; a.M = B * R;
+    a.xbuf = ws->xbuf; a.xgbuf = ws->xgbuf; a.ssbuf = ws->ssbuf; a.qbuf = ws->qbuf; a.knew = ws->knew; a.vnew = ws->vnew;
+    a.attn = ws->attn; a.act = ws->act; a.apart = ws->apart; a.acount = ws->acount; a.nsplit = S;
+    a.hp_max = ws->hp_max; a.hp_sum = ws->hp_sum; a.hp_arg = ws->hp_arg; a.hp_topv = ws->hp_topv; a.hp_topi = ws->hp_topi;
+    a.hp_lx = ws->hp_lx;
+    a.topk = topk; a.mode = mode; a.p = p; a.accept_len = accept_len; a.out_tokens = out_tokens; a.logits_dbg = logits_dbg;
+    a.bar_count = ws->bar; a.bar_flag = ws->bar + 32; a.abort_flag = reinterpret_cast<int*>(ws->bar + 64);
+    a.epoch0 = ws->epoch;
+    a.trace = m->fused_trace ? ws->trace : nullptr;
+    a.trace_cap = ws->trace_cap;
+    ws->epoch += 5ull * d.n_layers + 2ull;
+    void* args[] = {&a};
+    const void* fn = m->dh == 128 ? (const void*)verify_fused_kernel<128> : (const void*)verify_fused_kernel<64>;
+    const bool prof = m->prof_on && m->prof_n < m->prof_cap;
+    if (prof) LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n], stream));
+    LASER_HIP_CHECK(hipLaunchCooperativeKernel(fn, dim3(ws->nwg), dim3(FT), args, sizeof(Shared), stream));
+    if (prof) { LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n + 1], stream)); ++m->prof_n; }
+    return LASER_OK;
+}
+
+// Copies the stamps of the last traced launch: out[nwg][cap]; returns nwg and cap.
+int fused_read_trace(Model* m, hipStream_t stream, long long* out, int max_elems, int* nwg, int* cap) {
+    FusedWS* ws = reinterpret_cast<FusedWS*>(m->fused_ws);
+    LASER_REQUIRE(ws && ws->trace, LASER_E_INVALID_ARG, "no trace recorded (set option fused_trace first)");
+    *nwg = ws->nwg; *cap = ws->trace_cap;
+    LASER_REQUIRE((long)ws->nwg * ws->trace_cap <= max_elems, LASER_E_LIMIT, "trace needs %ld elements", (long)ws->nwg * ws->trace_cap);
+    LASER_HIP_CHECK(hipMemcpyAsync(out, ws->trace, (size_t)ws->nwg * ws->trace_cap * sizeof(long long), hipMemcpyDeviceToHost, stream));
+    LASER_HIP_CHECK(hipStreamSynchronize(stream));
+    return LASER_OK;
+}
+
+int fused_status(Model* m, hipStream_t stream, int* aborted) {
+    *aborted = 0;
+    FusedWS* ws = reinterpret_cast<FusedWS*>(m->fused_ws);
+    if (!ws) return LASER_OK;
+    LASER_HIP_CHECK(hipMemcpyAsync(aborted, ws->bar + 64, sizeof(int), hipMemcpyDeviceToHost, stream));
+    LASER_HIP_CHECK(hipStreamSynchronize(stream));
+    return LASER_OK;
+}
+
+}  // namespace laser

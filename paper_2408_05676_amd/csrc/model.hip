@@ -2,12 +2,21 @@
 // against the paged KV cache. Generic kernel set: works for any row count; the shapes it is tuned
 // for are the few-row, weight-streaming ones.
 #include <cmath>
+#include <string>
 #include <vector>
 
 #include "gemm_skinny.h"
 #include "state.h"
 
 namespace laser {
+
+bool fused_supported(const Model* m, int B, int K);
+void fused_free(Model* m);
+int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, const int32_t* drafts,
+              const int32_t* draft_len, int B, int K, int topk, float p, int mode, int32_t* accept_len,
+              int32_t* out_tokens, float* logits_dbg, int max_len_ub, hipStream_t stream);
+int fused_status(Model* m, hipStream_t stream, int* aborted);
+int fused_read_trace(Model* m, hipStream_t stream, long long* out, int max_elems, int* nwg, int* cap);
 
 int run_head(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len, int B, int K,
              int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, float* logits_dbg,
@@ -202,6 +211,8 @@ struct AttnArgs {
     float scale;
 };
 
+constexpr int kSplitPages = 16;   // pages (of 16 tokens) per context split
+
 template <int DH>
 __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     constexpr int NC32 = DH / 32, NC16 = DH / 16;
@@ -217,8 +228,10 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     const int rows_here = min(a.R - qt * 16, 16);
     const int last_tok = len + qt * 16 + rows_here - 1;  // last slot any row of this tile may see
     const int npages = last_tok / kPageSize + 1;
-    const int pps = (npages + a.nsplit - 1) / a.nsplit;
-    const int p0 = split * pps, p1 = min(npages, p0 + pps);
+    // A split is always kSplitPages pages at fixed positions, so the order in which a row's scores are
+    // reduced depends on the row's position only (not on the batch, the draft count or the host's
+    // length bound): verifying a token as a draft reproduces its one-at-a-time logits bit for bit.
+    const int p0 = split * kSplitPages, p1 = min(npages, p0 + kSplitPages);
 
     Frag8 bq[NC32];
     {
@@ -350,8 +363,7 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
                        ids_dev, kv->len, R, dm, d.vocab, d.eps, m->x, m->xn, m->row_pos);
     const int nqt = (R + 15) / 16;
     const int npages_ub = (max_len_ub + R + kPageSize - 1) / kPageSize;
-    int nsplit = (1024 + d.n_heads * B * nqt - 1) / (d.n_heads * B * nqt);
-    nsplit = std::max(1, std::min(nsplit, (npages_ub + 3) / 4));
+    const int nsplit = std::max(1, (npages_ub + kSplitPages - 1) / kSplitPages);
     const size_t part_need = (size_t)B * d.n_heads * nqt * nsplit * (32 + 16 * m->dh);
     if (nsplit > 1 && part_need > m->att_part_floats) {
         if (m->att_part) LASER_HIP_CHECK(hipFree(m->att_part));
@@ -405,6 +417,7 @@ extern "C" int laser_model_destroy(laser_model* h) {
                     m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx, m->row_x};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     for (hipEvent_t e : m->prof_ev) (void)hipEventDestroy(e);
+    fused_free(m);
     delete m;
     return LASER_OK;
 }
@@ -510,6 +523,9 @@ extern "C" int laser_verify_step(laser_model* mh, laser_kv* kh, const int32_t* s
     const int32_t* ids_dev = nullptr;
     if ((rc = kv->stage_ids(seq_ids, B, stream, &ids_dev))) return rc;
     for (int b = 0; b < B; ++b) kv->h_last_rows[seq_ids[b]] = R;
+    if (m->use_fused && fused_supported(m, B, K))
+        return run_fused(m, kv, ids_dev, pending, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens,
+                         logits_dbg, max_ub, stream);
     if ((rc = forward(m, kv, ids_dev, pending, drafts, draft_len, B, K, max_ub, stream))) return rc;
     return run_head(m, m->xn, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens, logits_dbg, stream);
 }
@@ -553,4 +569,25 @@ extern "C" int laser_profile_end(laser_model* mh, void* stream, float* total_ms,
     *total_ms = (float)tot;
     *n_launches = m->prof_n;
     return LASER_OK;
+}
+
+extern "C" int laser_model_set_option(laser_model* mh, const char* name, int value) {
+    Model* m = reinterpret_cast<Model*>(mh);
+    LASER_REQUIRE(m != nullptr && name != nullptr, LASER_E_INVALID_ARG, "NULL argument");
+    if (std::string(name) == "fused") { m->use_fused = value; return LASER_OK; }
+    if (std::string(name) == "fused_trace") { m->fused_trace = value; return LASER_OK; }
+    set_error("unknown option %s", name);
+    return LASER_E_INVALID_ARG;
+}
+
+extern "C" int laser_model_status(laser_model* mh, void* stream, int* aborted) {
+    Model* m = reinterpret_cast<Model*>(mh);
+    LASER_REQUIRE(m != nullptr && aborted != nullptr, LASER_E_INVALID_ARG, "NULL argument");
+    return fused_status(m, (hipStream_t)stream, aborted);
+}
+
+extern "C" int laser_model_read_trace(laser_model* mh, void* stream, long long* out, int max_elems, int* nwg, int* cap) {
+    Model* m = reinterpret_cast<Model*>(mh);
+    LASER_REQUIRE(m != nullptr && out && nwg && cap, LASER_E_INVALID_ARG, "NULL argument");
+    return fused_read_trace(m, (hipStream_t)stream, out, max_elems, nwg, cap);
 }

@@ -65,6 +65,9 @@ struct Model {
     std::vector<hipEvent_t> prof_ev;   // start/stop pairs
     int prof_cap = 0, prof_n = 0;
     bool prof_on = false;
+    void* fused_ws = nullptr;          // workspace of the persistent few-row kernel (fused.hip)
+    int use_fused = 1;                 // 0 forces the generic multi-kernel path
+    int fused_trace = 0;               // 1: thread 0 of every workgroup stamps the wall clock at phase edges
 };
 
 }  // namespace laser

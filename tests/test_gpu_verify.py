@@ -23,11 +23,12 @@ def _oracle(sh):
     return Decoder(sh.n_layers, sh.d, sh.n_heads, sh.ffn, sh.vocab, w, sh.eps, sh.rope_base)
 
 
-def _run_steps(sh, B, ctx_len, K, n_steps, k, p, mode=0, seed=1, ragged=False):
+def _run_steps(sh, B, ctx_len, K, n_steps, k, p, mode=0, seed=1, ragged=False, fused=1):
     laser = _laser()
     dec = _oracle(sh)
     cap = ctx_len + (K + 1) * (n_steps + 1) + 16
     model = gu.make_model(sh, max_rows=B * max(K + 1, 16), max_batch=B, max_pos=cap + 16)
+    model.set_option("fused", fused)
     kv = gu.make_kv(sh, n_pages=B * (cap // 16 + 2), max_seqs=B + 3, max_pages_per_seq=cap // 16 + 2)
     seq_ids = [B + 2 - b for b in range(B)]                             # non-trivial slot numbers
     prompts = synth.uniform_tokens(seed, 50, 0, B * ctx_len, sh.vocab).reshape(B, ctx_len)
@@ -173,3 +174,12 @@ def test_argument_errors_and_capacity():
     laser.ctx_advance(tail, pend, outt, al)
     assert tail.cpu().tolist() == [[7, 8, 9], [2, 3, 4]] and pend.cpu().tolist() == [9, 4]
     model.close(); kv.close()
+
+
+@pytest.mark.parametrize("fused", [1, 0])
+def test_7b_width_two_layers(fused):
+    """Real widths of the 7B shape (d 4096, 32 heads x 128, FFN 11008, vocab 32000), two layers so
+    that the float64 oracle stays within seconds: exercises the persistent few-row kernel (B*(K+1)
+    <= 16, context split over workgroups) and, with fused = 0, the general kernels."""
+    sh = synth.SHAPES["7b"].with_(n_layers=2)
+    _run_steps(sh, B=1, ctx_len=150, K=8, n_steps=2, k=2, p=0.0, seed=7, fused=fused)
