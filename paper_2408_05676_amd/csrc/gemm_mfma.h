@@ -1,0 +1,157 @@
+// LDS-tiled matrix-core GEMM for many activation rows (M = B*(K+1) in the hundreds):
+//   Y[M][N] = X[M][Kd] * W[N][Kd]^T,  X fp16, W bf16 (widened to fp16 on its way into LDS), fp32 accumulate.
+//
+// Workgroup tile 128 x 128, reduction step 32, 256 threads = 2 x 2 waves of 64 x 64, each wave
+// 2 x 2 v_mfma_f32_32x32x16_f16 tiles (64 accumulator registers). Global loads for step k+1 are
+// issued into registers before the matrix work of step k and written to the other LDS buffer after
+// it (one workgroup barrier per step). LDS rows are padded from 64 to 80 bytes so that the 16-byte
+// operand reads of 32 consecutive rows spread over all banks.
+//
+// v_mfma_f32_32x32x16_f16, wave64, lane l, g = l / 32:
+//   A: lane holds A[row = l % 32][k = 8 g .. 8 g + 7];  B: lane holds B[k = 8 g .. 8 g + 7][col = l % 32]
+//   D: lane holds D[row = 8 (i / 4) + 4 g + i % 4][col = l % 32], i = 0..15
+//
+// Workgroup ids are remapped so that the workgroups sharing a weight tile (same n-tile, all m-tiles)
+// have consecutive "virtual" ids on ONE XCD (hardware deals consecutive ids round-robin over the 8
+// XCDs, each with its own L2): the weight tile is then fetched from HBM once and hit in that L2.
+#pragma once
+
+#include "mfma.h"
+
+namespace laser {
+
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+constexpr int GM_BM = 128, GM_BN = 128, GM_BK = 32, GM_LD = 40;   // LD: halves per padded LDS row
+
+struct GemmTileArgs {
+    const uint16_t* W;      // [N][Kd] bf16   (SwiGLU: [2F][Kd], gate rows then up rows; N = F)
+    const uint16_t* X;      // [M][Kd] fp16
+    int M, N, Kd;
+    int tiles_m, tiles_n;   // tiles_n counts 128-column tiles (SwiGLU: 64-feature tiles)
+    float* outf;            // EPI_F32: [M][N] store; EPI_RESID: [M][N] accumulate
+    uint16_t* outh;         // EPI_SWIGLU: [M][N] fp16
+};
+
+enum { GEPI_F32 = 0, GEPI_RESID = 1, GEPI_SWIGLU = 2 };
+
+__device__ inline float16_t mfma_32x32x16(const Frag8& a, const Frag8& b, float16_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a.v, b.v, c, 0, 0, 0);
+}
+
+// weight row behind tile column j (0..127) of n-tile tn
+template <int EPI>
+__device__ inline int w_row(const GemmTileArgs& a, int tn, int j) {
+    if (EPI == GEPI_SWIGLU) {
+        // columns of a wave: [32 gate | 32 up] of the same 32 features, so that one lane holds both
+        const int wn = j >> 6, ct = (j >> 5) & 1, c = j & 31;
+        return (ct ? a.N : 0) + tn * 64 + wn * 32 + c;
+    }
+    return tn * GM_BN + j;
+}
+
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmTileArgs a) {
+    __shared__ __attribute__((aligned(16))) uint16_t sA[2][GM_BM][GM_LD];
+    __shared__ __attribute__((aligned(16))) uint16_t sB[2][GM_BN][GM_LD];
+    // ---- XCD-aware tile order ----
+    const int total = a.tiles_m * a.tiles_n;
+    const int per_xcd = (total + 7) / 8;
+    const int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (v >= total) return;
+    const int tn = v / a.tiles_m, tm = v % a.tiles_m;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lr = lane & 31, lg = lane >> 5;
+
+    // global -> LDS staging: thread t moves rows (t / 4) and (t / 4 + 64), 16 bytes at k-chunk t % 4
+    const int srow = tid >> 2, sk = (tid & 3) * 8;
+    const uint16_t* xa[2];
+    const uint16_t* wb[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        int row = tm * GM_BM + srow + 64 * i;
+        row = row < a.M ? row : a.M - 1;
+        xa[i] = a.X + (size_t)row * a.Kd + sk;
+        int wr = w_row<EPI>(a, tn, srow + 64 * i);
+        const int wmax = (EPI == GEPI_SWIGLU ? 2 * a.N : a.N) - 1;
+        wr = wr < wmax ? wr : wmax;
+        wb[i] = a.W + (size_t)wr * a.Kd + sk;
+    }
+    float16_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    Frag8 ra[2], rb[2];
+    auto gload = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            ra[i].u = *reinterpret_cast<const uint4*>(xa[i] + k0);
+            rb[i].u = *reinterpret_cast<const uint4*>(wb[i] + k0);
+        }
+    };
+    auto lstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            bf16x8_to_f16x8(rb[i]);
+            *reinterpret_cast<uint4*>(&sA[buf][srow + 64 * i][sk]) = ra[i].u;
+            *reinterpret_cast<uint4*>(&sB[buf][srow + 64 * i][sk]) = rb[i].u;
+        }
+    };
+    gload(0);
+    lstore(0);
+    __syncthreads();
+    const int nk = a.Kd / GM_BK;
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) gload((kt + 1) * GM_BK);
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            Frag8 fa[2], fb[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                fa[i].u = *reinterpret_cast<const uint4*>(&sA[buf][wm * 64 + i * 32 + lr][kk * 16 + lg * 8]);
+                fb[i].u = *reinterpret_cast<const uint4*>(&sB[buf][wn * 64 + i * 32 + lr][kk * 16 + lg * 8]);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = mfma_32x32x16(fa[i], fb[j], acc[i][j]);
+        }
+        if (kt + 1 < nk) lstore(buf ^ 1);
+        __syncthreads();
+    }
+    // ---- epilogue: lane holds column lr of each 32-wide tile, rows 8 (e / 4) + 4 lg + e % 4 ----
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int row = tm * GM_BM + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * lg + (e & 3);
+            if (row >= a.M) continue;
+            if (EPI == GEPI_SWIGLU) {
+                const int feat = tn * 64 + wn * 32 + lr;
+                if (feat < a.N) {
+                    const float gt = acc[i][0][e], up = acc[i][1][e];
+                    a.outh[(size_t)row * a.N + feat] = f32_to_f16(gt / (1.f + __expf(-gt)) * up);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int col = tn * GM_BN + wn * 64 + j * 32 + lr;
+                    if (col < a.N) {
+                        float* p = a.outf + (size_t)row * a.N + col;
+                        if (EPI == GEPI_RESID) *p += acc[i][j][e];
+                        else *p = acc[i][j][e];
+                    }
+                }
+            }
+        }
+    }
+}
+
+}  // namespace laser

@@ -5,6 +5,7 @@
 #include <string>
 #include <vector>
 
+#include "gemm_mfma.h"
 #include "gemm_skinny.h"
 #include "state.h"
 
@@ -148,9 +149,21 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
     }
 }
 
+constexpr int kSkinnyMaxRows = 80;   // beyond this the weights would be streamed more than once
+
 template <int EPI>
 static int launch_gemm(const GemmArgs& a0, hipStream_t stream) {
     GemmArgs a = a0;
+    if (a.M > kSkinnyMaxRows) {
+        GemmTileArgs t{a.W, a.X, a.M, a.N, a.Kd, (a.M + GM_BM - 1) / GM_BM,
+                       EPI == EPI_SWIGLU ? (a.N + 63) / 64 : (a.N + GM_BN - 1) / GM_BN, a.outf, a.outh};
+        const int total = t.tiles_m * t.tiles_n;
+        dim3 grid((unsigned)(((total + 7) / 8) * 8));
+        constexpr int GE = EPI == EPI_F32 ? GEPI_F32 : (EPI == EPI_RESID ? GEPI_RESID : GEPI_SWIGLU);
+        hipLaunchKernelGGL((gemm_mfma_kernel<GE>), grid, dim3(256), 0, stream, t);
+        LASER_HIP_CHECK(hipGetLastError());
+        return LASER_OK;
+    }
     const int ntiles = a.N / 16;
     const int mblocks = (a.M + 15) / 16;
     const int MB = mblocks >= 5 ? 5 : mblocks;

@@ -176,6 +176,16 @@ def test_argument_errors_and_capacity():
     model.close(); kv.close()
 
 
+def test_many_rows_use_the_tiled_matrix_core_gemm():
+    """M = B*(K+1) > 80 rows switches the projections to the LDS-tiled kernel (128 x 128 tiles):
+    tile tails in M, several m-tiles, SwiGLU column pairing."""
+    sh = synth.SHAPES["tiny"].with_(lm_gain=4.0)
+    _run_steps(sh, B=13, ctx_len=21, K=7, n_steps=2, k=2, p=0.05, seed=11, ragged=True)      # M = 104
+    _run_steps(sh, B=37, ctx_len=18, K=6, n_steps=1, k=2, p=0.05, seed=12)                   # M = 259: 3 m-tiles
+    sh7 = synth.SHAPES["7b"].with_(n_layers=1)
+    _run_steps(sh7, B=12, ctx_len=24, K=8, n_steps=1, k=2, p=0.0, seed=13)                   # M = 108 at 7B width
+
+
 @pytest.mark.parametrize("fused", [1, 0])
 def test_7b_width_two_layers(fused):
     """Real widths of the 7B shape (d 4096, 32 heads x 128, FFN 11008, vocab 32000), two layers so
