@@ -39,6 +39,7 @@ WORKLOADS = {
 }
 
 HBM_PEAK_GBS = 8000.0
+MFMA_F16_PEAK_TFLOPS = 2500.0
 
 
 def algorithmic_bytes(sh, B, K, ctx_len):
@@ -120,7 +121,13 @@ def main():
                     help="rv: k=2 p=0.1 (Eq. 8) on a sharpened head; strict: greedy (Eq. 4); floor: no pool replay")
     ap.add_argument("--lm-gain", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-fused", action="store_true", help="force the general multi-kernel verify path")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch one plain 1 GiB device copy before the timed region (a kernel of known "
+                         "traffic against which hardware byte counters are scaled)")
+    ap.add_argument("--path", default="auto", choices=["auto", "fused", "generic"],
+                    help="few-row workloads can run the verify step as one persistent kernel (fused) or as the "
+                         "general multi-kernel path; auto times a few steps of each and keeps the faster")
+    ap.add_argument("--no-fused", action="store_true", help="same as --path generic")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the path needs no collectives; see DESIGN.md on sharding). "
@@ -149,8 +156,10 @@ def main():
     n_gen = (steps + warmup) * R + 16                       # tokens the replayed continuation must cover
     max_len = ctx_len + 2 * n_gen + R + 32
     eng = Engine(sh, weights, B, K, max_len, n_max)
-    if args.no_fused:
-        eng.model.set_option("fused", 0)
+    path = "generic" if args.no_fused else args.path
+    fused_possible = B * R <= 16 and sh.n_layers > 0
+    if not fused_possible:
+        path = "generic"
     spec = synth.POOLS[wl["pool"]]
     ctx = synth.gen_contexts(spec, B, ctx_len, n_max, salt=1, min_remaining=K)
     eng.prefill(ctx["ctx"])
@@ -176,6 +185,35 @@ def main():
     eng.set_pool(pool, ctx["keys"])
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t_setup
+
+    def rollback():
+        for b in range(B):
+            eng.kv.set_len(b, ctx_len - 1)
+        eng.pending.copy_(torch.as_tensor(np.ascontiguousarray(ctx["ctx"][:, -1]), dtype=torch.int32))
+        eng.ctx_tail.copy_(torch.as_tensor(np.ascontiguousarray(ctx["ctx"][:, -n_max:]), dtype=torch.int32))
+
+    path_ms = {}
+    if path == "auto":
+        for name, flag in (("fused", 1), ("generic", 0)):
+            eng.model.set_option("fused", flag)
+            eng.step(topk, p, mode)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(4):
+                eng.step(topk, p, mode)
+            torch.cuda.synchronize()
+            path_ms[name] = (time.perf_counter() - t0) * 1e3 / 4
+            rollback()
+        path = min(path_ms, key=path_ms.get)
+    eng.model.set_option("fused", 1 if path == "fused" else 0)
+
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(warmup):
         eng.step(topk, p, mode)
@@ -203,17 +241,27 @@ def main():
     value = emitted / elapsed
 
     step_bytes = algorithmic_bytes(sh, B, K, ctx_len + int((len0 - (ctx_len - 1)).mean()))
-    fused = B * R <= 16 and not args.no_fused
-    if fused:
-        # few-row regime: the whole verify step (embedding .. head + acceptance) is ONE persistent kernel
-        dom_name, dom_bytes = "verify_fused_kernel (whole verify step)", step_bytes
-    else:
-        # dominant kernel: the gate/up projection GEMM (largest weight stream of every layer)
-        dom_name, dom_bytes = "gemm_skinny_kernel<gate/up SwiGLU>", 2 * sh.ffn * sh.d * 2 + B * R * sh.d * 2 + B * R * sh.ffn * 2
+    M = B * R
     dom_avg_s = dom_ms / 1e3 / max(dom_n, 1)
-    achieved = dom_bytes / dom_avg_s / 1e9 if dom_n else 0.0
+    if path == "fused":
+        # few-row regime: the whole verify step (embedding .. head + acceptance) is ONE persistent kernel
+        dom_name, dom_work, bound = "verify_fused_kernel (whole verify step)", step_bytes, "hbm"
+    elif M <= 80:
+        # dominant kernel: the gate/up projection (largest weight stream of every layer), weight-streaming form
+        dom_name, bound = "gemm_skinny_kernel<gate/up SwiGLU>", "hbm"
+        dom_work = 2 * sh.ffn * sh.d * 2 + M * sh.d * 2 + M * sh.ffn * 2
+    else:
+        # many rows: the same projection runs as the LDS-tiled matrix-core GEMM and is compute-bound
+        dom_name, bound = "gemm_mfma_kernel<gate/up SwiGLU>", "mfma"
+        dom_work = 2.0 * M * 2 * sh.ffn * sh.d
+    if bound == "hbm":
+        peak, unit, achieved = HBM_PEAK_GBS, "GB/s", (dom_work / dom_avg_s / 1e9 if dom_n else 0.0)
+        work_key = "bytes_per_launch"
+    else:
+        peak, unit, achieved = MFMA_F16_PEAK_TFLOPS, "TFLOP/s", (dom_work / dom_avg_s / 1e12 if dom_n else 0.0)
+        work_key = "flops_per_launch"
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}_{path}.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f).get("bytes_per_launch")
@@ -224,13 +272,16 @@ def main():
         "dtype": "bf16 weights x fp16 activations, fp32 accumulate", "data": "synthetic",
         "config": {"workload": wl["label"], "batch": B, "context": ctx_len, "K": K, "regime": args.regime,
                    "topk": topk, "p": p, "lm_gain": gain, "tokens_per_step": tokens_per_step,
-                   "gpu_ms_per_step": gpu_ms / steps, "setup_s": setup_s,
+                   "gpu_ms_per_step": gpu_ms / steps, "setup_s": setup_s, "path": path, "path_probe_ms": path_ms,
                    "step_algorithmic_GB": step_bytes / 1e9,
                    "step_hbm_frac": step_bytes / (gpu_ms / 1e3 / steps) / 1e9 / HBM_PEAK_GBS},
-        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "bytes_per_launch": dom_bytes, "avg_launch_us": dom_avg_s * 1e6, "launches": dom_n},
+        "roofline": {"bound": bound, "kernel": dom_name, "achieved": achieved,
+                     "peak": peak, "unit": unit, "frac": achieved / peak, "traffic": traffic,
+                     work_key: dom_work, "avg_launch_us": dom_avg_s * 1e6, "launches": dom_n},
     }
+    eng.close()
+    pool.close()
+    del weights
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(sh, wl, tokens_per_step)
     print(json.dumps(out))

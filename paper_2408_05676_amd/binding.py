@@ -5,6 +5,7 @@ There is no fallback of any kind: if liblaser.so is missing or a call fails, Las
 from __future__ import annotations
 
 import ctypes as C
+import sys
 import os
 
 import numpy as np
@@ -138,7 +139,10 @@ class Pool:
             lib().laser_pool_destroy(self._h)
             self._h = C.c_void_p()
 
-    __del__ = close
+    def __del__(self):
+        # at interpreter shutdown the HIP runtime may already be gone; the process frees everything
+        if not sys.is_finalizing():
+            self.close()
 
 
 def retrieve_drafts(pool: Pool, keys: torch.Tensor, ctx_tail: torch.Tensor, n_min: int, n_max: int,
@@ -218,7 +222,10 @@ class Model:
             lib().laser_model_destroy(self._h)
             self._h = C.c_void_p()
 
-    __del__ = close
+    def __del__(self):
+        # at interpreter shutdown the HIP runtime may already be gone; the process frees everything
+        if not sys.is_finalizing():
+            self.close()
 
 
 class KVCache:
@@ -257,7 +264,10 @@ class KVCache:
             lib().laser_kv_destroy(self._h)
             self._h = C.c_void_p()
 
-    __del__ = close
+    def __del__(self):
+        # at interpreter shutdown the HIP runtime may already be gone; the process frees everything
+        if not sys.is_finalizing():
+            self.close()
 
 
 def verify_step(model: Model, kv: KVCache, seq_ids, pending: torch.Tensor, drafts: torch.Tensor,
