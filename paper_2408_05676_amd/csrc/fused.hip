@@ -7,11 +7,12 @@
 // Structure: grid = one workgroup of 8 waves per compute unit. Phases are separated by a grid
 // barrier (one agent-scope atomic counter + a separate flag line); per layer:
 //     QKV(+RoPE) | attention | O-proj(+residual) | gate/up(+SwiGLU) | down(+residual)
-// * Weight streaming: a GEMM item is a 16-feature tile (or a pair of tiles); the 8 waves of a
+// * Weight streaming: a GEMM unit is a 16-feature tile (or a pair of tiles); the 8 waves of a
 //   workgroup split its reduction dimension, each lane reading 64 contiguous bytes per step
-//   (k-permuted MFMA operands), partial sums meet in LDS. Each wave keeps one step of weights in
-//   flight and issues the first step of the NEXT phase before it enters the barrier, so HBM stays
-//   busy while the barrier resolves (weights never depend on activations).
+//   (k-permuted MFMA operands), partial sums meet in LDS. Each wave keeps 16 KiB of weights in
+//   flight in a register ring and issues the first steps of the NEXT phase while the barrier
+//   resolves, so HBM stays busy (weights never depend on activations). The few activation rows are
+//   staged into LDS once per workgroup and phase instead of being re-read per step.
 // * RMSNorm never materialises: producers publish x*gain (fp16) plus per-workgroup partial sums of
 //   squares; consumers multiply their accumulators by rsqrt(mean square) (a per-row scalar commutes
 //   with the product).
@@ -36,6 +37,7 @@ namespace laser {
 constexpr int FT = 512;             // threads per workgroup
 constexpr int FWAVES = 8;
 constexpr int AW = 8;               // waves per workgroup that take attention pages
+constexpr int PPW = 2;              // consecutive pages per wave and context split (16 pages = 256 tokens per split)
 constexpr int KTOP = LASER_MAX_TOPK;
 
 struct FusedArgs {
@@ -58,6 +60,7 @@ struct FusedArgs {
     float* apart;       // [L][B*H][nsplit][32 + 16*dh]
     int* acount;        // [L][B*H]   (self-resetting)
     int nsplit;
+    int xs_steps;       // reduction steps (of 128) whose activations fit the LDS staging area
     // head
     float *hp_max, *hp_sum; int32_t* hp_arg; float* hp_topv; int32_t* hp_topi; float* hp_lx;
     int topk, mode; float p;
@@ -77,22 +80,39 @@ __device__ inline void st_f32(float* p, float v) { st_u32(p, __float_as_uint(v))
 __device__ inline void st_i32(int* p, int v) { st_u32(p, (uint32_t)v); }
 __device__ inline uint32_t pack_h2(float a, float b) { return (uint32_t)f32_to_f16(a) | ((uint32_t)f32_to_f16(b) << 16); }
 
+constexpr int MAX_UNITS = 6;         // 16-row weight tiles one wave slot can accumulate per phase
 struct Shared {
-    union {
-        float red[3][FWAVES][2][4][64];   // split-K partial sums of up to 3 items    48 KiB
-        float att_o[AW][16][128];         // attention wave merge                    64 KiB
-    };
     float att_m[AW][16], att_l[AW][16];
     float rs[16];                         // rsqrt(mean square) per row
-    float ss_acc[16][8];
+    float ss_acc[16][32];
     int row_pos[16], row_b[16];
     int flag;                             // barrier outcome / last-arriver broadcast
     float hstat[FWAVES][4];
     int hstat_i[FWAVES][2];
     int row_ok[LASER_MAX_DRAFT + 1], row_arg[LASER_MAX_DRAFT + 1];
+    union alignas(16) {
+        float red[MAX_UNITS][FWAVES][4][64];   // per (unit slot, wave) partial tiles   48 KiB
+        float att_o[AW][16][128];                  // attention wave merge                  64 KiB
+    };
 };
+// Staged activations start right behind `red` and run to the end of the launch's dynamic LDS; they
+// overlap the tail of att_o, which is never live at the same time.
+constexpr size_t XS_OFFSET = offsetof(Shared, red) + sizeof(float) * MAX_UNITS * FWAVES * 4 * 64;
 
+// optional finer stamps inside the GEMM phases of layer `layer`: slot = 3 * phase + {0: staged, 1: streamed, 2: epilogue done}
+// Stamps exist only in the TR = true instantiation of the kernel: even a never-taken branch around a
+// store makes the compiler's wait counters conservative at its join, which would stall the streaming.
+template <bool TR>
+__device__ inline void stamp_fine(const FusedArgs& a, int layer, int slot) {
+    if constexpr (!TR) return;
+    if (a.trace && threadIdx.x == 0 && layer >= 0) {
+        const int i = 2 * (5 * a.L + 2) + 4 + 16 * layer + slot;
+        if (i < a.trace_cap) a.trace[(size_t)blockIdx.x * a.trace_cap + i] = wall_clock64();
+    }
+}
+template <bool TR>
 __device__ inline void stamp(const FusedArgs& a, int& n) {
+    if constexpr (!TR) return;
     if (a.trace && threadIdx.x == 0) {
         if (n < a.trace_cap) a.trace[(size_t)blockIdx.x * a.trace_cap + n] = wall_clock64();
         ++n;
@@ -101,21 +121,24 @@ __device__ inline void stamp(const FusedArgs& a, int& n) {
 
 // Every wave waits until its own exchange stores have completed (the workgroup barrier alone only
 // orders LDS; completion of a write-through store takes a full memory round trip), then thread 0
-// arrives. `prefetch` issues the next phase's first weight steps just before that wait, so they
-// travel together with the stores.
+// arrives. `prefetch` issues the next phase's first weight steps right after the arrival, so they
+// travel while the barrier resolves without delaying the arrival itself.
 template <class Prefetch>
 __device__ inline bool grid_sync(const FusedArgs& a, Shared& sh, unsigned long long& epoch, Prefetch&& prefetch) {
     ++epoch;
-    prefetch();
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    const unsigned long long e = a.epoch0 + epoch;
+    bool last = false;
     if (threadIdx.x == 0) {
-        const unsigned long long e = a.epoch0 + epoch;
-        int ok = 1;
         const unsigned long long old = __hip_atomic_fetch_add(a.bar_count, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (old + 1 == e * (unsigned long long)gridDim.x) {
-            __hip_atomic_store(a.bar_flag, e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        } else {
+        last = old + 1 == e * (unsigned long long)gridDim.x;
+        if (last) __hip_atomic_store(a.bar_flag, e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    prefetch();
+    if (threadIdx.x == 0) {
+        int ok = 1;
+        if (!last) {
             long spins = 0;
             while (__hip_atomic_load(a.bar_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < e) {
                 __builtin_amdgcn_s_sleep(1);
@@ -135,27 +158,49 @@ __device__ inline bool grid_sync(const FusedArgs& a, Shared& sh, unsigned long l
 }
 
 // ---- weight streaming -------------------------------------------------------------------------------
-enum { PH_QKV = 0, PH_O = 1, PH_GU = 2, PH_DOWN = 3 };
+enum { PH_QKV = 0, PH_O = 1, PH_GU = 2, PH_DOWN = 3, PH_HEAD = 4 };
 
 struct Phase {
     const uint16_t* W;    // matrix of this layer
-    int kind, Kd, n_items, na;
+    int kind, Kd;
 };
 
-// first weight row of stream `st` of item `item`
-__device__ inline int tile_row(const FusedArgs& a, int kind, int item, int st) {
+__device__ inline int count_mine(int n, int first, int stride) { return first < n ? (n - 1 - first) / stride + 1 : 0; }
+
+// A *unit* is one 16-row weight tile streamed over this wave's share of the reduction dimension.
+// Units of a wave slot in a phase (all waves of a workgroup share them, splitting k, except in the
+// output head where every wave owns whole tiles):
+//   QKV : per owned index i (of d/16): the two tiles of one rotary pair of q or k, then (after all
+//         pairs) one tile of v  -> 3 units per index, so every workgroup streams the same bytes
+//   O, DOWN : one tile per owned index
+//   GU  : pair items (gate tile + up tile of the same 16 features), two streams per step
+//   HEAD: vocabulary tiles, indexed by global wave id
+__device__ inline int n_units(const FusedArgs& a, int kind) {
+    const int nwg = gridDim.x, w = blockIdx.x;
+    if (kind == PH_QKV) return 3 * count_mine(a.d / 16, w, nwg);
+    if (kind == PH_GU) return count_mine(a.F / 16, w, nwg);
+    if (kind == PH_HEAD) return count_mine(a.V / 16, w * FWAVES + (int)(threadIdx.x >> 6), nwg * FWAVES);
+    return count_mine(a.d / 16, w, nwg);
+}
+
+// first weight row of stream `st` of unit `u`
+__device__ inline int unit_row(const FusedArgs& a, int kind, int u, int st) {
+    const int nwg = gridDim.x, w = blockIdx.x;
     if (kind == PH_QKV) {
-        const int per = a.d / 32;                 // pair-items per projection
-        const int grp = item / per, idx = item % per;
-        if (grp < 2) {
-            const int pph = a.dh / 32;            // pairs per head: features (i, i + dh/2)
+        const int c = count_mine(a.d / 16, w, nwg);
+        if (u < 2 * c) {
+            const int item = w + (u >> 1) * nwg;      // rotary pair: index over q pairs, then k pairs
+            const int per = a.d / 32;                 // pairs per projection
+            const int grp = item / per, idx = item % per;
+            const int pph = a.dh / 32;                // pairs per head: features (i, i + dh/2)
             const int h = idx / pph, j = idx % pph;
-            return grp * a.d + h * a.dh + j * 16 + st * (a.dh / 2);
+            return grp * a.d + h * a.dh + j * 16 + (u & 1) * (a.dh / 2);
         }
-        return 2 * a.d + (2 * idx + st) * 16;
+        return 2 * a.d + (w + (u - 2 * c) * nwg) * 16;
     }
-    if (kind == PH_GU) return st * a.F + item * 16;
-    return item * 16;
+    if (kind == PH_GU) return st * a.F + (w + u * nwg) * 16;
+    if (kind == PH_HEAD) return (w * FWAVES + (int)(threadIdx.x >> 6) + u * nwg * FWAVES) * 16;
+    return (w + u * nwg) * 16;
 }
 
 __device__ inline void load_w(Frag8 (&f)[4], const uint16_t* p) {
@@ -163,63 +208,74 @@ __device__ inline void load_w(Frag8 (&f)[4], const uint16_t* p) {
     for (int c = 0; c < 4; ++c) f[c].u = *reinterpret_cast<const uint4*>(p + c * 8);
 }
 
-// wave's k-step range of a phase
-__device__ inline void k_range(int Kd, int wave, int& ks0, int& nks) {
-    const int steps = Kd / 128;
-    ks0 = steps * wave / FWAVES;
-    nks = steps * (wave + 1) / FWAVES - ks0;
+// The reduction dimension is processed in chunks whose activations fit the LDS staging area
+// (xs_steps steps of 128 elements for the launch's row count); chunk c of a Kd-long reduction:
+__device__ inline int n_chunks(const FusedArgs& a, int Kd) { return (Kd / 128 + a.xs_steps - 1) / a.xs_steps; }
+__device__ inline void chunk_range(const FusedArgs& a, int Kd, int c, int& cs0, int& cs1) {
+    const int steps = Kd / 128, nch = n_chunks(a, Kd);
+    cs0 = steps * c / nch;
+    cs1 = steps * (c + 1) / nch;
 }
 
-__device__ inline const uint16_t* w_ptr(const FusedArgs& a, const Phase& ph, int item, int st, int ks, int lane) {
-    return ph.W + (size_t)(tile_row(a, ph.kind, item, st) + (lane & 15)) * ph.Kd + ks * 128 + (lane >> 4) * 32;
+struct WaveWork {         // wave-uniform description of this wave's share of one chunk of a phase
+    int cs0, ncs;         // the chunk: first step, steps
+    int ks0, nks;         // this wave's steps inside it
+    int n_my, T;          // units, total steps
+};
+__device__ inline WaveWork wave_work(const FusedArgs& a, const Phase& ph, int chunk) {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    WaveWork w;
+    int cs1;
+    chunk_range(a, ph.Kd, chunk, w.cs0, cs1);
+    w.ncs = cs1 - w.cs0;
+    if (ph.kind == PH_HEAD) { w.ks0 = w.cs0; w.nks = w.ncs; }
+    else {
+        w.ks0 = w.cs0 + w.ncs * wave / FWAVES;
+        w.nks = w.cs0 + w.ncs * (wave + 1) / FWAVES - w.ks0;
+    }
+    w.n_my = __builtin_amdgcn_readfirstlane(n_units(a, ph.kind));
+    w.T = w.n_my * w.nks;
+    return w;
+}
+
+__device__ inline const uint16_t* w_ptr(const FusedArgs& a, const Phase& ph, int u, int st, int ks, int lane) {
+    return ph.W + (size_t)(unit_row(a, ph.kind, u, st) + (lane & 15)) * ph.Kd + ks * 128 + (lane >> 4) * 32;
 }
 
 // Weight streaming through a register ring. A step (128 reduction elements) of a phase with NA
-// streams occupies NA weight fragments (4 x 16 B per lane each) plus one activation fragment; the
-// ring holds DS steps, so DS-1 steps of weights (16 KiB per wave: NA = 2, DS = 3 or NA = 1, DS = 5)
-// are in flight while one is consumed. The streaming loop is kept free of branches around memory
-// instructions (past the wave's last step it re-requests that step, an L2 hit, and skips the
-// arithmetic), because the wait counters are exact only in straight-line code; partial sums of
-// finished items go to LDS inside the loop and every epilogue runs after it.
-constexpr int MAX_ITEMS_PER_WG = 3;
+// streams occupies NA weight fragments (4 x 16 B per lane each); the ring holds DS steps, so DS-1
+// steps of weights (16 KiB per wave: NA = 2, DS = 3 or NA = 1, DS = 5) are in flight while one is
+// consumed. The activation operand is NOT loaded per step from global memory: measured on this chip,
+// per-step activation loads (L2 hits) cut the weight streaming rate by 30-45 % because they share the
+// vector-memory path; the phase's activations are staged into LDS once per workgroup and read from
+// there. The streaming loop is kept free of branches around vector-memory instructions (past the
+// wave's last step it re-requests one cached line and skips the arithmetic), because the wait
+// counters are exact only in straight-line code; finished units leave their partial sums in LDS
+// inside the loop and every epilogue runs after it.
 
 // What survives a phase boundary: the weights issued ahead for the next phase (its first two steps
 // if NA = 2, first four if NA = 1), every fragment (re)defined by prefetch_first so that nothing
 // older stays live across the attention phase.
 struct Ring {
     Frag8 f[4][4];
-    int primed;           // how many leading steps of the coming phase already have their weights issued
+    int primed;           // how many leading steps of the coming chunk already have their weights issued
 };
 template <int NA> struct RingCfg { static constexpr int DS = NA == 2 ? 3 : 5; };
 
-struct WaveWork {         // wave-uniform description of this wave's share of a phase
-    int ks0, nks, n_my, T;
-};
-__device__ inline WaveWork wave_work(const Phase& ph) {
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    WaveWork w;
-    k_range(ph.Kd, wave, w.ks0, w.nks);
-    const int nwg = gridDim.x;
-    w.n_my = (int)blockIdx.x < ph.n_items ? (ph.n_items - 1 - (int)blockIdx.x) / nwg + 1 : 0;
-    w.T = w.n_my * w.nks;
-    return w;
-}
-
-// Issue the weights of this wave's first DS-1 steps of phase `ph` (between a phase's last store and
-// the grid barrier, so that they travel while the barrier resolves).
+// Issue the weights of this wave's first DS-1 steps of chunk `chunk` of phase `ph` (called while a
+// grid barrier resolves or activations are being staged: weights never depend on activations).
 template <int NA>
-__device__ inline void prefetch_first(const FusedArgs& a, const Phase& ph, Ring& R) {
+__device__ inline void prefetch_first(const FusedArgs& a, const Phase& ph, int chunk, Ring& R) {
     constexpr int DS = RingCfg<NA>::DS;
     const int lane = threadIdx.x & 63;
-    const WaveWork w = wave_work(ph);
-    const int nwg = gridDim.x;
+    const WaveWork w = wave_work(a, ph, chunk);
     R.primed = 0;
 #pragma unroll
     for (int t = 0; t < DS - 1; ++t) {
         if (t < w.T) {
 #pragma unroll
             for (int s = 0; s < NA; ++s)
-                load_w(R.f[t * NA + s], w_ptr(a, ph, blockIdx.x + (t / w.nks) * nwg, s, w.ks0 + t % w.nks, lane));
+                load_w(R.f[t * NA + s], w_ptr(a, ph, t / w.nks, s, w.ks0 + t % w.nks, lane));
             R.primed = t + 1;
         } else {
 #pragma unroll
@@ -230,52 +286,68 @@ __device__ inline void prefetch_first(const FusedArgs& a, const Phase& ph, Ring&
     }
 }
 
-// Runs one GEMM phase for this workgroup. X: fp16 [16][Kd] activations (exchange buffer).
-template <int NA, class Epi>
-__device__ inline void gemm_phase(const FusedArgs& a, Shared& sh, const Phase& ph,
-                                  const uint16_t* __restrict__ X, Ring& R, Epi&& epi) {
+// Copy rows 0..M-1, steps cs0 .. cs0+ncs-1 of the fp16 activations X[16][Kd] into LDS
+// (row stride ncs*256 + 16 bytes: the 16-byte operand reads of 16 rows then fall into distinct banks).
+__device__ inline void stage_x(const FusedArgs& a, uint4* xs, const uint16_t* X, int Kd, int cs0, int ncs) {
+    constexpr int Q = 16;                       // 16-byte pieces per thread and pass: one pass covers 16 rows x 32 steps
+    const int per_row = ncs * 16, total = a.M * per_row, stride = per_row + 1, ld = Kd / 8;
+    const uint32_t inv = 0xFFFFFFFFu / (uint32_t)per_row + 1u;     // i / per_row == umulhi(i, inv) for i * per_row < 2^32
+    const uint4* src = reinterpret_cast<const uint4*>(X) + cs0 * 16;
+    for (int i0 = threadIdx.x; i0 < total; i0 += FT * Q) {
+        uint4 v[Q];
+        int dst[Q];
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            // every load is issued unconditionally (clamped index): a load under a branch would be
+            // waited for at the branch's join and the pieces would arrive one round trip after the other
+            const int i = i0 + q * FT, ic = min(i, total - 1);
+            const int row = (int)__umulhi((uint32_t)ic, inv), c = ic - row * per_row;
+            dst[q] = i < total ? row * stride + c : -1;
+            v[q] = src[(size_t)row * ld + c];
+        }
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+            if (dst[q] >= 0) xs[dst[q]] = v[q];
+    }
+}
+
+// Streams one chunk: this wave's units x steps, partial sums of finished units to sh.red
+// (stored on the first chunk, accumulated on later ones; slot = unit * NA + stream).
+template <int NA>
+__device__ inline void stream_chunk(const FusedArgs& a, Shared& sh, const uint4* xs, const Phase& ph,
+                                    const WaveWork& w, bool first, Ring& R) {
     constexpr int DS = RingCfg<NA>::DS;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
-    const WaveWork w = wave_work(ph);
-    const int nwg = gridDim.x;
-    const uint16_t* xrow = X + (size_t)r * ph.Kd + g * 32;
-
     if (w.T > 0) {
-        Frag8 A[DS * NA][4], Bf[DS][4];
+        Frag8 A[DS * NA][4];
         const uint16_t* wp[NA];             // this lane's pointers to the next step to request
-        const uint16_t* bp;
-        int jn = 0, kn = 0;                 // (item, step) of that step
+        int jn = 0, kn = 0;                 // (unit, step) of that step
         // Past the last step the pointers park on one lane-uniform, always-valid address, so the
         // surplus requests of the padded loop cost a single cached line each.
         const uint16_t* park = reinterpret_cast<const uint16_t*>(a.gf);
-        auto set_item = [&](int j) {
+        auto set_unit = [&](int j) {
 #pragma unroll
-            for (int s = 0; s < NA; ++s) wp[s] = w_ptr(a, ph, blockIdx.x + j * nwg, s, w.ks0, lane);
-            bp = xrow + w.ks0 * 128;
+            for (int s = 0; s < NA; ++s) wp[s] = w_ptr(a, ph, j, s, w.ks0, lane);
         };
         auto advance = [&]() {              // scalar control only
             if (kn + 1 < w.nks) {
                 ++kn;
 #pragma unroll
                 for (int s = 0; s < NA; ++s) wp[s] += 128;
-                bp += 128;
             } else if (jn + 1 < w.n_my) {
-                kn = 0; ++jn; set_item(jn);
+                kn = 0; ++jn; set_unit(jn);
             } else {
 #pragma unroll
                 for (int s = 0; s < NA; ++s) wp[s] = park;
-                bp = park;
             }
         };
-        auto request = [&](int slot) {      // weights + activations of the next step, then advance
+        auto request = [&](int slot) {      // weights of the next step, then advance
 #pragma unroll
             for (int s = 0; s < NA; ++s) load_w(A[slot * NA + s], wp[s]);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) Bf[slot][c].u = *reinterpret_cast<const uint4*>(bp + c * 8);
             advance();
         };
-        set_item(0);
+        set_unit(0);
         // prologue: steps 0 .. DS-2 (weights possibly already issued before the barrier)
 #pragma unroll
         for (int t = 0; t < DS - 1; ++t) {
@@ -284,55 +356,84 @@ __device__ inline void gemm_phase(const FusedArgs& a, Shared& sh, const Phase& p
                 for (int s = 0; s < NA; ++s)
 #pragma unroll
                     for (int c = 0; c < 4; ++c) A[t * NA + s][c] = R.f[t * NA + s][c];
-#pragma unroll
-                for (int c = 0; c < 4; ++c) Bf[t][c].u = *reinterpret_cast<const uint4*>(bp + c * 8);
                 advance();
             } else {
                 request(t);
             }
         }
+        // this lane's activation operand: row r (padding rows read row 0; their results are dropped)
+        const uint4* xl = xs + (r < a.M ? r : 0) * (w.ncs * 16 + 1) + (w.ks0 - w.cs0) * 16 + g * 4;
         float4_t acc[NA];
 #pragma unroll
         for (int s = 0; s < NA; ++s) acc[s] = float4_t{0.f, 0.f, 0.f, 0.f};
-        int k = 0, jitem = 0;
+        int k = 0, junit = 0;
         for (int t0 = 0; t0 < w.T; t0 += DS) {
 #pragma unroll
             for (int j = 0; j < DS; ++j) {
                 request((j + DS - 1) % DS);                   // unconditional: step t0 + j + DS - 1, clamped
-                if (t0 + j < w.T) {                           // no memory instructions inside this branch
+                if (t0 + j < w.T) {                           // no vector-memory instructions inside this branch
+                    Frag8 Bf[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) Bf[c].u = xl[k * 16 + c];
 #pragma unroll
                     for (int s = 0; s < NA; ++s) {
 #pragma unroll
                         for (int c = 0; c < 4; ++c) bf16x8_to_f16x8(A[j * NA + s][c]);
 #pragma unroll
-                        for (int c = 0; c < 4; ++c) acc[s] = mfma_16x16x32(A[j * NA + s][c], Bf[j][c], acc[s]);
+                        for (int c = 0; c < 4; ++c) acc[s] = mfma_16x16x32(A[j * NA + s][c], Bf[c], acc[s]);
                     }
                     if (++k == w.nks) {
 #pragma unroll
                         for (int s = 0; s < NA; ++s)
 #pragma unroll
-                            for (int i = 0; i < 4; ++i) sh.red[jitem][wave][s][i][lane] = acc[s][i];
+                            for (int i = 0; i < 4; ++i) {
+                                float* slot = &sh.red[junit * NA + s][wave][i][lane];
+                                *slot = first ? acc[s][i] : *slot + acc[s][i];
+                            }
 #pragma unroll
                         for (int s = 0; s < NA; ++s) acc[s] = float4_t{0.f, 0.f, 0.f, 0.f};
                         k = 0;
-                        ++jitem;
+                        ++junit;
                     }
                 }
             }
         }
-    } else {
-        for (int j = 0; j < w.n_my; ++j)
+    } else if (first) {
+        for (int j = 0; j < w.n_my * NA; ++j)
 #pragma unroll
-            for (int s = 0; s < NA; ++s)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) sh.red[j][wave][s][i][lane] = 0.f;
+            for (int i = 0; i < 4; ++i) sh.red[j][wave][i][lane] = 0.f;
     }
     R.primed = 0;
+}
+
+// Streams a whole phase: for every chunk stage its activations, stream, and issue the next chunk's
+// first weights before the staging barrier. On return sh.red holds every unit's partial sums and
+// all waves have passed a workgroup barrier.
+template <int NA, bool TR>
+__device__ inline void stream_phase(const FusedArgs& a, Shared& sh, uint4* xs, const Phase& ph,
+                                    const uint16_t* __restrict__ X, Ring& R, int trace_layer = -1, int trace_slot = 0) {
+    const int nch = n_chunks(a, ph.Kd);
+    for (int c = 0; c < nch; ++c) {
+        const WaveWork w = wave_work(a, ph, c);
+        if (c > 0) __syncthreads();                     // every wave has finished reading the previous chunk
+        if (c == 0) stamp_fine<TR>(a, trace_layer, trace_slot + 2);
+        stage_x(a, xs, X, ph.Kd, w.cs0, w.ncs);
+        __syncthreads();
+        if (c == 0) stamp_fine<TR>(a, trace_layer, trace_slot);
+        stream_chunk<NA>(a, sh, xs, ph, w, c == 0, R);
+        if (c + 1 < nch) prefetch_first<NA>(a, ph, c + 1, R);
+    }
     __syncthreads();
-    // ---- split-K reduction and the phase's epilogue, 128 threads: thread -> (row, two features) ----
+    stamp_fine<TR>(a, trace_layer, trace_slot + 1);
+}
+
+// Split-K reduction and epilogue of a GEMM phase, 128 threads: thread -> (row, two features).
+// epi(unit, row, f0, v[NA][2]) receives the finished sums of features f0, f0+1 of the unit's tile(s).
+template <int NA, class Epi>
+__device__ inline void reduce_epilogue(const FusedArgs& a, Shared& sh, int n_my, Epi&& epi) {
     if (threadIdx.x < 128) {
         const int row = threadIdx.x >> 3, f0 = (threadIdx.x & 7) * 2;
-        for (int j = 0; j < w.n_my; ++j) {
+        for (int j = 0; j < n_my; ++j) {
             float v[NA][2];
 #pragma unroll
             for (int s = 0; s < NA; ++s)
@@ -342,30 +443,37 @@ __device__ inline void gemm_phase(const FusedArgs& a, Shared& sh, const Phase& p
                     const int ln = (f >> 2) * 16 + row, i = f & 3;
                     float t = 0.f;
 #pragma unroll
-                    for (int wv = 0; wv < FWAVES; ++wv) t += sh.red[j][wv][s][i][ln];
+                    for (int wv = 0; wv < FWAVES; ++wv) t += sh.red[j * NA + s][wv][i][ln];
                     v[s][q] = row < a.M ? t : 0.f;      // padding rows stay exactly zero
                 }
-            epi((int)blockIdx.x + j * nwg, row, f0, v);
+            epi(j, row, f0, v);
         }
     }
-    __syncthreads();        // the union with the attention buffers and the rs[] reuse need a full stop
+    __syncthreads();        // sh.red is free again (it shares LDS with the attention buffers)
 }
 
-// rs[row] = rsqrt(mean square + eps) from the per-workgroup partial sums of one norm point
-__device__ inline void load_rs(const FusedArgs& a, Shared& sh, const float* ss /*[nwg][16]*/) {
-    const int nwg = gridDim.x;
-    if (threadIdx.x < 128) {
-        const int row = threadIdx.x >> 3, part = threadIdx.x & 7;
-        float t = 0.f;
-        for (int w = part; w < nwg; w += 8) t += ss[(size_t)w * 16 + row];
-        sh.ss_acc[row][part] = t;
+// rs[row] = rsqrt(mean square + eps) from the per-workgroup partial sums of one norm point.
+// ss_issue starts the loads (8 per thread) so that they travel with the phase's weights;
+// ss_finish reduces them in a fixed order after the streaming loop.
+__device__ inline void ss_issue(const float* ss /*[nwg][16]*/, float (&v)[8]) {
+    const int nwg = gridDim.x, row = threadIdx.x & 15, part = threadIdx.x >> 4;      // 32 parts
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        // unconditional load (see stage_x); the value is first looked at in ss_finish, after the streaming
+        v[i] = ss[(size_t)min(part + 32 * i, nwg - 1) * 16 + row];
     }
+}
+__device__ inline void ss_finish(const FusedArgs& a, Shared& sh, const float (&v)[8]) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t += ((int)(threadIdx.x >> 4) + 32 * i < (int)gridDim.x) ? v[i] : 0.f;
+    sh.ss_acc[threadIdx.x & 15][threadIdx.x >> 4] = t;
     __syncthreads();
     if (threadIdx.x < 16) {
-        float t = 0.f;
+        float s = 0.f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) t += sh.ss_acc[threadIdx.x][j];
-        sh.rs[threadIdx.x] = rsqrtf(t / (float)a.d + a.eps);
+        for (int j = 0; j < 32; ++j) s += sh.ss_acc[threadIdx.x][j];
+        sh.rs[threadIdx.x] = rsqrtf(s / (float)a.d + a.eps);
     }
     __syncthreads();
 }
@@ -402,7 +510,7 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
         const int split = item % S, bh = item / S, h = bh % a.H, b = bh / a.H;
         const int slot = a.seq_ids[b];
         const int len = a.lens[slot];
-        // Pages are taken at their cache positions, one page per wave and a fixed AW pages per split,
+        // Pages are taken at their cache positions, PPW consecutive pages per wave and a fixed AW*PPW pages per split,
         // and a page that holds new rows is composed from the cache (slots < len) and the exchange
         // buffers (slots len .. len+R-1). The arithmetic a row sees therefore depends only on its own
         // position, never on how many rows are verified with it or on the host's length bound: a token
@@ -415,8 +523,8 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
 #pragma unroll
         for (int c = 0; c < NC16; ++c) acc[c] = float4_t{0.f, 0.f, 0.f, 0.f};
         if (wave < AW) {
-            const int p = split * AW + wave;
-            if (p < n_pages) {
+            const int pbase = (split * AW + wave) * PPW;
+            if (pbase < n_pages) {
                 Frag8 bq[NC32];
                 {
                     const int qr = min(r, a.R - 1);
@@ -424,86 +532,97 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
 #pragma unroll
                     for (int c = 0; c < NC32; ++c) bq[c].u = *reinterpret_cast<const uint4*>(qp + c * 32);
                 }
-                Frag8 ak[NC32];
-                Frag4 bv[NC16];
-                const size_t base = (((size_t)layer * a.n_pages + bt[p]) * a.H + h) * kPageSize * DH;
-                const int s0 = p * kPageSize;                         // first slot of the page
-                if (s0 + kPageSize <= len) {                          // committed slots only
-                    const uint16_t* kp = a.kpages + base + (size_t)r * DH + g * 8;
+                Frag8 ak[PPW][NC32];
+                Frag4 bv[PPW][NC16];
+                // first the loads of every fully committed page of this wave, so that they travel together
 #pragma unroll
-                    for (int c = 0; c < NC32; ++c) ak[c].u = *reinterpret_cast<const uint4*>(kp + c * 32);
-                    const uint16_t* vp = a.vpages + base + (size_t)r * kPageSize + 4 * g;
+                for (int pp = 0; pp < PPW; ++pp) {
+                    const int p = pbase + pp, s0 = p * kPageSize;
+                    if (p < n_pages && s0 + kPageSize <= len) {
+                        const size_t base = (((size_t)layer * a.n_pages + bt[p]) * a.H + h) * kPageSize * DH;
+                        const uint16_t* kp = a.kpages + base + (size_t)r * DH + g * 8;
 #pragma unroll
-                    for (int c = 0; c < NC16; ++c) bv[c].u = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * kPageSize);
-                } else {
-                    const int ks = s0 + r;                            // this lane's key slot
-                    const bool k_new = ks >= len;
-                    const int kr = min(max(ks - len, 0), a.R - 1);
-                    const uint16_t* kp = k_new ? kn + (size_t)(b * a.R + kr) * a.d + (size_t)h * DH + g * 8
-                                               : a.kpages + base + (size_t)r * DH + g * 8;
+                        for (int c = 0; c < NC32; ++c) ak[pp][c].u = *reinterpret_cast<const uint4*>(kp + c * 32);
+                        const uint16_t* vp = a.vpages + base + (size_t)r * kPageSize + 4 * g;
 #pragma unroll
-                    for (int c = 0; c < NC32; ++c) ak[c].u = *reinterpret_cast<const uint4*>(kp + c * 32);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int vs = s0 + 4 * g + j;                // value slot
-                        const bool v_new = vs >= len;
-                        const int vr = min(max(vs - len, 0), a.R - 1);
-#pragma unroll
-                        for (int c = 0; c < NC16; ++c)
-                            bv[c].h[j] = v_new ? vn[(size_t)(b * a.R + vr) * a.d + (size_t)h * DH + c * 16 + r]
-                                               : a.vpages[base + (size_t)(c * 16 + r) * kPageSize + 4 * g + j];
+                        for (int c = 0; c < NC16; ++c) bv[pp][c].u = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * kPageSize);
                     }
-                    // this wave owns the page: store its new rows into the cache for later steps
-                    if (k_new && ks < len + a.R) {
-                        uint16_t* kd = a.kpages + base + (size_t)r * DH + g * 8;
+                }
 #pragma unroll
-                        for (int c = 0; c < NC32; ++c) *reinterpret_cast<uint4*>(kd + c * 32) = ak[c].u;
-                    }
+                for (int pp = 0; pp < PPW; ++pp) {
+                    const int p = pbase + pp, s0 = p * kPageSize;       // s0: first slot of the page
+                    if (p >= n_pages) continue;
+                    if (s0 + kPageSize > len) {                         // the page holds new rows
+                        const size_t base = (((size_t)layer * a.n_pages + bt[p]) * a.H + h) * kPageSize * DH;
+                        const int ks = s0 + r;                            // this lane's key slot
+                        const bool k_new = ks >= len;
+                        const int kr = min(max(ks - len, 0), a.R - 1);
+                        const uint16_t* kp = k_new ? kn + (size_t)(b * a.R + kr) * a.d + (size_t)h * DH + g * 8
+                                                   : a.kpages + base + (size_t)r * DH + g * 8;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int vs = s0 + 4 * g + j;
-                        if (vs >= len && vs < len + a.R) {
+                        for (int c = 0; c < NC32; ++c) ak[pp][c].u = *reinterpret_cast<const uint4*>(kp + c * 32);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int vs = s0 + 4 * g + j;                // value slot
+                            const bool v_new = vs >= len;
+                            const int vr = min(max(vs - len, 0), a.R - 1);
 #pragma unroll
                             for (int c = 0; c < NC16; ++c)
-                                a.vpages[base + (size_t)(c * 16 + r) * kPageSize + 4 * g + j] = bv[c].h[j];
+                                bv[pp][c].h[j] = v_new ? vn[(size_t)(b * a.R + vr) * a.d + (size_t)h * DH + c * 16 + r]
+                                                       : a.vpages[base + (size_t)(c * 16 + r) * kPageSize + 4 * g + j];
+                        }
+                        // this wave owns the page: store its new rows into the cache for later steps
+                        if (k_new && ks < len + a.R) {
+                            uint16_t* kd = a.kpages + base + (size_t)r * DH + g * 8;
+#pragma unroll
+                            for (int c = 0; c < NC32; ++c) *reinterpret_cast<uint4*>(kd + c * 32) = ak[pp][c].u;
+                        }
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int vs = s0 + 4 * g + j;
+                            if (vs >= len && vs < len + a.R) {
+#pragma unroll
+                                for (int c = 0; c < NC16; ++c)
+                                    a.vpages[base + (size_t)(c * 16 + r) * kPageSize + 4 * g + j] = bv[pp][c].h[j];
+                            }
                         }
                     }
-                }
-                float4_t s = float4_t{0.f, 0.f, 0.f, 0.f};
+                    float4_t s = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int c = 0; c < NC32; ++c) s = mfma_16x16x32(ak[c], bq[c], s);
-                float sv[4], mx = -INFINITY;
+                    for (int c = 0; c < NC32; ++c) s = mfma_16x16x32(ak[pp][c], bq[c], s);
+                    float sv[4], mx = -INFINITY;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int ts = s0 + 4 * g + i;                 // slot of this score's key
-                    const bool vis = (r < a.R) && (ts <= len + r);   // query row r sits at slot len + r
-                    sv[i] = vis ? s[i] * scale : -INFINITY;
-                    mx = fmaxf(mx, sv[i]);
-                }
-                mx = fmaxf(mx, __shfl_xor(mx, 16));
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m_run, mx);
-                const float alpha = (m_new == -INFINITY) ? 1.f : __expf(m_run - m_new);
-                Frag4 pa;
-                float rsum = 0.f;
+                    for (int i = 0; i < 4; ++i) {
+                        const int ts = s0 + 4 * g + i;                 // slot of this score's key
+                        const bool vis = (r < a.R) && (ts <= len + r);   // query row r sits at slot len + r
+                        sv[i] = vis ? s[i] * scale : -INFINITY;
+                        mx = fmaxf(mx, sv[i]);
+                    }
+                    mx = fmaxf(mx, __shfl_xor(mx, 16));
+                    mx = fmaxf(mx, __shfl_xor(mx, 32));
+                    const float m_new = fmaxf(m_run, mx);
+                    const float alpha = (m_new == -INFINITY) ? 1.f : __expf(m_run - m_new);
+                    Frag4 pa;
+                    float rsum = 0.f;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float pv = (sv[i] == -INFINITY) ? 0.f : __expf(sv[i] - m_new);
-                    rsum += pv;
-                    pa.h[i] = f32_to_f16(pv);
-                }
-                rsum += __shfl_xor(rsum, 16);
-                rsum += __shfl_xor(rsum, 32);
-                l_run = l_run * alpha + rsum;
-                m_run = m_new;
-                float al[4];
+                    for (int i = 0; i < 4; ++i) {
+                        const float pv = (sv[i] == -INFINITY) ? 0.f : __expf(sv[i] - m_new);
+                        rsum += pv;
+                        pa.h[i] = f32_to_f16(pv);
+                    }
+                    rsum += __shfl_xor(rsum, 16);
+                    rsum += __shfl_xor(rsum, 32);
+                    l_run = l_run * alpha + rsum;
+                    m_run = m_new;
+                    float al[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) al[i] = __shfl(alpha, 4 * g + i);
+                    for (int i = 0; i < 4; ++i) al[i] = __shfl(alpha, 4 * g + i);
 #pragma unroll
-                for (int c = 0; c < NC16; ++c) {
+                    for (int c = 0; c < NC16; ++c) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) acc[c][i] *= al[i];
-                    acc[c] = mfma_16x16x16(pa, bv[c], acc[c]);
+                        for (int i = 0; i < 4; ++i) acc[c][i] *= al[i];
+                        acc[c] = mfma_16x16x16(pa, bv[pp][c], acc[c]);
+                    }
                 }
             }
             if (g == 0) { sh.att_m[wave][r] = m_run; sh.att_l[wave][r] = l_run; }
@@ -618,11 +737,12 @@ struct HStat {
     }
 };
 
-__device__ inline void head_phase(const FusedArgs& a, Shared& sh, const uint16_t* __restrict__ X, int chunks) {
+// Consumes the logits tiles a wave has accumulated in sh.red (unit u of global wave `chunk` is
+// vocabulary tile chunk + u * chunks): per-row running statistics, partial results per wave.
+__device__ inline void head_epilogue(const FusedArgs& a, Shared& sh, int chunks) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
     const int chunk = blockIdx.x * FWAVES + wave;          // chunk id == global wave id
-    const int ntiles = a.V / 16;
     const int row = r;
     int x = -1;
     if (row < a.M) {
@@ -633,33 +753,14 @@ __device__ inline void head_phase(const FusedArgs& a, Shared& sh, const uint16_t
     HStat st;
     st.init();
     const float rs = sh.rs[r];
-    const uint16_t* xrow = X + (size_t)r * a.d + g * 32;
-    const int steps = a.d / 128;
-    for (int t = chunk; t < ntiles; t += chunks) {
-        const uint16_t* wp = a.wlm + (size_t)(t * 16 + r) * a.d + g * 32;
-        float4_t acc = float4_t{0.f, 0.f, 0.f, 0.f};
-        Frag8 a_cur[4], a_nxt[4], b_cur[4], b_nxt[4];
-        load_w(a_cur, wp);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) b_cur[c].u = *reinterpret_cast<const uint4*>(xrow + c * 8);
-        for (int k = 0; k < steps; ++k) {
-            if (k + 1 < steps) {
-                load_w(a_nxt, wp + (k + 1) * 128);
-#pragma unroll
-                for (int c = 0; c < 4; ++c) b_nxt[c].u = *reinterpret_cast<const uint4*>(xrow + (k + 1) * 128 + c * 8);
-            }
-#pragma unroll
-            for (int c = 0; c < 4; ++c) bf16x8_to_f16x8(a_cur[c]);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc = mfma_16x16x32(a_cur[c], b_cur[c], acc);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) { a_cur[c] = a_nxt[c]; b_cur[c] = b_nxt[c]; }
-        }
+    const int n_my = n_units(a, PH_HEAD);
+    for (int u = 0; u < n_my; ++u) {
+        const int t = chunk + u * chunks;
         const int n = t * 16 + 4 * g;
         float lv[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            lv[i] = acc[i] * rs;
+            lv[i] = sh.red[u][wave][i][lane] * rs;
             st.add(lv[i], n + i);
             if (n + i == x) st.lx = lv[i];
         }
@@ -752,7 +853,7 @@ __device__ inline void accept_phase(const FusedArgs& a, Shared& sh, int chunks) 
 }
 
 // ---- the kernel --------------------------------------------------------------------------------------
-template <int DH>
+template <int DH, bool TR>
 __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Shared& sh = *reinterpret_cast<Shared*>(smem_raw);
@@ -771,8 +872,8 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
 
     Ring ring;
     ring.primed = 0;
-    Phase ph_qkv{a.wqkv, PH_QKV, a.d, 3 * a.d / 32, 2};
-    if (a.L > 0) prefetch_first<2>(a, ph_qkv, ring);   // layer 0's first QKV weights travel during the embedding
+    uint4* xs = reinterpret_cast<uint4*>(smem_raw + XS_OFFSET);
+    const Phase p_head{a.wlm, PH_HEAD, a.d};
 
     // ---- phase 0: embedding, x0, x0*g1[0], sum of squares ----
     {
@@ -800,11 +901,16 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
     }
     int ns = 0;
     auto no_prefetch = [] {};
-    stamp(a, ns);
-    if (!grid_sync(a, sh, epoch, no_prefetch)) return;
-    stamp(a, ns);
 
     for (int l = 0; l < a.L; ++l) {
+        // The barrier that ends the previous layer (or the embedding) opens the loop body, so that the
+        // weights issued ahead during it are never carried around the loop's back edge.
+        {
+            const Phase p_q{a.wqkv + (size_t)l * 3 * a.d * a.d, PH_QKV, a.d};
+            stamp<TR>(a, ns);
+            if (!grid_sync(a, sh, epoch, [&] { prefetch_first<1>(a, p_q, 0, ring); })) return;
+            stamp<TR>(a, ns);
+        }
         const float* x_in = a.xbuf + (size_t)(2 * l) * XS;           // after the previous layer
         float* x_mid = a.xbuf + (size_t)(2 * l + 1) * XS;             // after attention
         float* x_out = a.xbuf + (size_t)(2 * l + 2) * XS;             // after the FFN
@@ -816,28 +922,35 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         float* ss_out = a.ssbuf + (size_t)(2 * l + 2) * nwg * 16;
         const size_t lo = (size_t)l * XS;
 
-        Phase p_qkv{a.wqkv + (size_t)l * 3 * a.d * a.d, PH_QKV, a.d, 3 * a.d / 32, 2};
-        Phase p_o{a.wo + (size_t)l * a.d * a.d, PH_O, a.d, a.d / 16, 1};
-        Phase p_gu{a.wgu + (size_t)l * 2 * a.F * a.d, PH_GU, a.d, a.F / 16, 2};
-        Phase p_dn{a.wdown + (size_t)l * a.d * a.F, PH_DOWN, a.F, a.d / 16, 1};
-        Phase p_nq{a.wqkv + (size_t)(l + 1) * 3 * a.d * a.d, PH_QKV, a.d, 3 * a.d / 32, 2};
+        const Phase p_qkv{a.wqkv + (size_t)l * 3 * a.d * a.d, PH_QKV, a.d};
+        const Phase p_o{a.wo + (size_t)l * a.d * a.d, PH_O, a.d};
+        const Phase p_gu{a.wgu + (size_t)l * 2 * a.F * a.d, PH_GU, a.d};
+        const Phase p_dn{a.wdown + (size_t)l * a.d * a.F, PH_DOWN, a.F};
+        const int w = blockIdx.x;
 
         // ---- QKV + RoPE ----
-        load_rs(a, sh, ss_in);
         {
+            float ssv[8];
+            ss_issue(ss_in, ssv);
+            stream_phase<1, TR>(a, sh, xs, p_qkv, xg_in, ring, l, 0);
+            ss_finish(a, sh, ssv);
             const int per = a.d / 32, pph = DH / 32, half = DH / 2;
-            gemm_phase<2>(a, sh, p_qkv, xg_in, ring, [&](int item, int row, int f0, float (&v)[2][2]) {
+            const int cnt = count_mine(a.d / 16, w, nwg);
+            float keep[2] = {0.f, 0.f};
+            reduce_epilogue<1>(a, sh, 3 * cnt, [&](int u, int row, int f0, float (&v)[1][2]) {
                 const float rs = sh.rs[row];
-                const int grp = item / per, idx = item % per;
-                if (grp < 2) {
+                if (u < 2 * cnt) {
+                    if ((u & 1) == 0) { keep[0] = v[0][0]; keep[1] = v[0][1]; return; }   // first half of a rotary pair
+                    const int item = w + (u >> 1) * nwg;
+                    const int grp = item / per, idx = item % per;
                     const int h = idx / pph, j = idx % pph;
-                    const int c0 = h * DH + j * 16 + f0;                  // channel of v[0][*]; partner at c0 + half
+                    const int c0 = h * DH + j * 16 + f0;                  // channel of keep[*]; partner at c0 + half
                     const int pos = sh.row_pos[row];
                     float o0[2], o1[2];
 #pragma unroll
                     for (int q = 0; q < 2; ++q) {
                         const float2 cs = a.rope[(size_t)pos * half + (j * 16 + f0 + q)];
-                        const float x0 = v[0][q] * rs, x1 = v[1][q] * rs;
+                        const float x0 = keep[q] * rs, x1 = v[0][q] * rs;
                         o0[q] = x0 * cs.x - x1 * cs.y;
                         o1[q] = x0 * cs.y + x1 * cs.x;
                     }
@@ -845,27 +958,28 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
                     st_u32(dst + c0, pack_h2(o0[0], o0[1]));
                     st_u32(dst + c0 + half, pack_h2(o1[0], o1[1]));
                 } else {
-                    uint16_t* dst = a.vnew + lo + (size_t)row * a.d + idx * 32 + f0;
-                    st_u32(dst, pack_h2(v[0][0] * rs, v[0][1] * rs));
-                    st_u32(dst + 16, pack_h2(v[1][0] * rs, v[1][1] * rs));
+                    const int idx = w + (u - 2 * cnt) * nwg;
+                    st_u32(a.vnew + lo + (size_t)row * a.d + idx * 16 + f0, pack_h2(v[0][0] * rs, v[0][1] * rs));
                 }
             });
         }
-        stamp(a, ns);
-        if (!grid_sync(a, sh, epoch, [&] { prefetch_first<1>(a, p_o, ring); })) return;
-        stamp(a, ns);
+        stamp<TR>(a, ns);
+        if (!grid_sync(a, sh, epoch, [&] { prefetch_first<1>(a, p_o, 0, ring); })) return;
+        stamp<TR>(a, ns);
 
         // ---- attention ----
         attention_phase<DH>(a, sh, l);
-        stamp(a, ns);
+        stamp<TR>(a, ns);
         if (!grid_sync(a, sh, epoch, no_prefetch)) return;
-        stamp(a, ns);
+        stamp<TR>(a, ns);
 
         // ---- O projection + residual; publish x, x*g2, sum of squares ----
         {
             float ss = 0.f;
             const float* g2 = a.g2 + (size_t)l * a.d;
-            gemm_phase<1>(a, sh, p_o, a.attn + lo, ring, [&](int item, int row, int f0, float (&v)[1][2]) {
+            stream_phase<1, TR>(a, sh, xs, p_o, a.attn + lo, ring, l, 3);
+            reduce_epilogue<1>(a, sh, n_units(a, PH_O), [&](int u, int row, int f0, float (&v)[1][2]) {
+                const int item = w + u * nwg;
                 const size_t o = (size_t)row * a.d + item * 16 + f0;
                 const float n0 = x_in[o] + v[0][0], n1 = x_in[o + 1] + v[0][1];
                 st_f32(x_mid + o, n0); st_f32(x_mid + o + 1, n1);
@@ -874,15 +988,19 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
             });
             publish_ss(sh, ss_mid + (size_t)blockIdx.x * 16, ss);
         }
-        stamp(a, ns);
-        if (!grid_sync(a, sh, epoch, [&] { prefetch_first<2>(a, p_gu, ring); })) return;
-        stamp(a, ns);
+        stamp<TR>(a, ns);
+        if (!grid_sync(a, sh, epoch, [&] { prefetch_first<2>(a, p_gu, 0, ring); })) return;
+        stamp<TR>(a, ns);
 
         // ---- gate/up + SwiGLU ----
-        load_rs(a, sh, ss_mid);
         {
+            float ssv[8];
+            ss_issue(ss_mid, ssv);
+            stream_phase<2, TR>(a, sh, xs, p_gu, xg_mid, ring, l, 6);
+            ss_finish(a, sh, ssv);
             uint16_t* act = a.act + (size_t)l * 16 * a.F;
-            gemm_phase<2>(a, sh, p_gu, xg_mid, ring, [&](int item, int row, int f0, float (&v)[2][2]) {
+            reduce_epilogue<2>(a, sh, n_units(a, PH_GU), [&](int u, int row, int f0, float (&v)[2][2]) {
+                const int item = w + u * nwg;
                 const float rs = sh.rs[row];
                 float o[2];
 #pragma unroll
@@ -893,17 +1011,18 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
                 st_u32(act + (size_t)row * a.F + item * 16 + f0, pack_h2(o[0], o[1]));
             });
         }
-        stamp(a, ns);
-        if (!grid_sync(a, sh, epoch, [&] { prefetch_first<1>(a, p_dn, ring); })) return;
-        stamp(a, ns);
+        stamp<TR>(a, ns);
+        if (!grid_sync(a, sh, epoch, [&] { prefetch_first<1>(a, p_dn, 0, ring); })) return;
+        stamp<TR>(a, ns);
 
         // ---- down projection + residual; publish x, x*gain(next norm), sum of squares ----
         {
             float ss = 0.f;
             const bool last = l + 1 == a.L;
             const float* gn = last ? a.gf : a.g1 + (size_t)(l + 1) * a.d;
-            gemm_phase<1>(a, sh, p_dn, a.act + (size_t)l * 16 * a.F, ring,
-                          [&](int item, int row, int f0, float (&v)[1][2]) {
+            stream_phase<1, TR>(a, sh, xs, p_dn, a.act + (size_t)l * 16 * a.F, ring, l, 9);
+            reduce_epilogue<1>(a, sh, n_units(a, PH_DOWN), [&](int u, int row, int f0, float (&v)[1][2]) {
+                const int item = w + u * nwg;
                 const size_t o = (size_t)row * a.d + item * 16 + f0;
                 const float n0 = x_mid[o] + v[0][0], n1 = x_mid[o + 1] + v[0][1];
                 st_f32(x_out + o, n0); st_f32(x_out + o + 1, n1);
@@ -912,24 +1031,40 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
             });
             publish_ss(sh, ss_out + (size_t)blockIdx.x * 16, ss);
         }
-        stamp(a, ns);
-        if (!grid_sync(a, sh, epoch, [&] { if (l + 1 < a.L) prefetch_first<2>(a, p_nq, ring); })) return;
-        stamp(a, ns);
     }
+    stamp<TR>(a, ns);
+    if (!grid_sync(a, sh, epoch, [&] { prefetch_first<1>(a, p_head, 0, ring); })) return;
+    stamp<TR>(a, ns);
 
     // ---- output head + acceptance ----
     const int chunks = nwg * FWAVES;
-    load_rs(a, sh, a.ssbuf + (size_t)(2 * a.L) * nwg * 16);
-    head_phase(a, sh, a.xgbuf + (size_t)(2 * a.L) * XS, chunks);
-    stamp(a, ns);
+    {
+        float ssv[8];
+        ss_issue(a.ssbuf + (size_t)(2 * a.L) * nwg * 16, ssv);
+        stream_phase<1, TR>(a, sh, xs, p_head, a.xgbuf + (size_t)(2 * a.L) * XS, ring);
+        ss_finish(a, sh, ssv);
+        head_epilogue(a, sh, chunks);
+    }
+    stamp<TR>(a, ns);
     if (!grid_sync(a, sh, epoch, no_prefetch)) return;
-    stamp(a, ns);
+    stamp<TR>(a, ns);
     accept_phase(a, sh, chunks);
-    stamp(a, ns);
+    stamp<TR>(a, ns);
 }
 
 // ---- host side ---------------------------------------------------------------------------------------
 static int g_num_cu = 0;
+static int g_lds_max = 0;            // largest dynamic LDS one workgroup may ask for
+
+static bool query_device() {
+    if (g_num_cu) return true;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return false;
+    g_lds_max = (int)std::min<size_t>(prop.sharedMemPerBlock, 160 * 1024);
+    g_num_cu = prop.multiProcessorCount;
+    return true;
+}
 
 struct FusedWS {
     void* blob = nullptr;
@@ -945,15 +1080,15 @@ struct FusedWS {
 
 bool fused_supported(const Model* m, int B, int K) {
     const laser_model_desc& d = m->d;
-    if (g_num_cu == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return false;
-        g_num_cu = prop.multiProcessorCount;
-    }
-    const int cap = MAX_ITEMS_PER_WG * g_num_cu;         // GEMM items one launch can take per phase
-    return d.n_layers > 0 && B * (K + 1) <= 16 && d.d_model % 128 == 0 && d.ffn % 128 == 0 && d.vocab % 16 == 0 &&
-           (m->dh == 64 || m->dh == 128) && 3 * d.d_model / 32 <= cap && d.ffn / 16 <= cap && d.d_model / 16 <= cap;
+    if (!query_device()) return false;
+    const int nwg = g_num_cu, M = B * (K + 1);
+    auto per = [](int n, int lanes) { return (n + lanes - 1) / lanes; };
+    // every wave slot accumulates at most MAX_UNITS tiles per phase; the norm reduction reads <= 256 partials
+    return d.n_layers > 0 && M >= 1 && M <= 16 && d.d_model % 128 == 0 && d.ffn % 128 == 0 && d.vocab % 16 == 0 &&
+           (m->dh == 64 || m->dh == 128) && nwg <= 256 &&
+           3 * per(d.d_model / 16, nwg) <= MAX_UNITS && 2 * per(d.ffn / 16, nwg) <= MAX_UNITS &&
+           per(d.vocab / 16, nwg * FWAVES) <= MAX_UNITS &&
+           g_lds_max >= (int)sizeof(Shared) && ((size_t)g_lds_max - XS_OFFSET) / M >= 272;
 }
 
 void fused_free(Model* m) {
@@ -967,13 +1102,7 @@ void fused_free(Model* m) {
 }
 
 static int fused_prepare(Model* m, int B, hipStream_t stream, FusedWS** out) {
-    if (g_num_cu == 0) {
-        int dev = 0;
-        LASER_HIP_CHECK(hipGetDevice(&dev));
-        hipDeviceProp_t prop;
-        LASER_HIP_CHECK(hipGetDeviceProperties(&prop, dev));
-        g_num_cu = prop.multiProcessorCount;
-    }
+    LASER_REQUIRE(query_device(), LASER_E_HIP, "cannot query the device");
     const laser_model_desc& d = m->d;
     FusedWS* ws = reinterpret_cast<FusedWS*>(m->fused_ws);
     const int nwg = g_num_cu;
@@ -1002,12 +1131,13 @@ static int fused_prepare(Model* m, int B, hipStream_t stream, FusedWS** out) {
         ws->hp_max = (float*)(b + o_hm); ws->hp_sum = (float*)(b + o_hs); ws->hp_arg = (int32_t*)(b + o_ha);
         ws->hp_topv = (float*)(b + o_tv); ws->hp_topi = (int32_t*)(b + o_ti); ws->hp_lx = (float*)(b + o_lx);
         ws->nwg = nwg; ws->bh_cap = bh_cap;
-        const size_t lds = sizeof(Shared);
-        if (m->dh == 128) LASER_HIP_CHECK(hipFuncSetAttribute((const void*)verify_fused_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        else LASER_HIP_CHECK(hipFuncSetAttribute((const void*)verify_fused_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        const size_t lds = (size_t)g_lds_max;
+        const void* fns[4] = {(const void*)verify_fused_kernel<128, false>, (const void*)verify_fused_kernel<128, true>,
+                              (const void*)verify_fused_kernel<64, false>, (const void*)verify_fused_kernel<64, true>};
+        for (const void* f : fns) LASER_HIP_CHECK(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     }
     if (m->fused_trace && !ws->trace) {
-        ws->trace_cap = 2 * (5 * d.n_layers + 2) + 4;
+        ws->trace_cap = 2 * (5 * d.n_layers + 2) + 4 + 16 * d.n_layers;
         LASER_HIP_CHECK(hipMalloc((void**)&ws->trace, (size_t)ws->nwg * ws->trace_cap * sizeof(long long)));
         LASER_HIP_CHECK(hipMemsetAsync(ws->trace, 0, (size_t)ws->nwg * ws->trace_cap * sizeof(long long), stream));
     }
@@ -1024,9 +1154,9 @@ int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, 
     if (rc) return rc;
     const laser_model_desc& d = m->d;
     const int R = K + 1;
-    // context splits: a fixed AW pages (128 tokens) each, enough to cover the longest sequence
+    // context splits: a fixed AW * PPW pages (256 tokens) each, enough to cover the longest sequence
     const int pages_ub = (max_len_ub + R + kPageSize - 1) / kPageSize;
-    const int S = std::max(1, (pages_ub + AW - 1) / AW);
+    const int S = std::max(1, (pages_ub + AW * PPW - 1) / (AW * PPW));
     LASER_REQUIRE(B * d.n_heads * S <= ws->bh_cap, LASER_E_LIMIT,
                   "context of %d tokens needs %d attention splits; the persistent kernel holds %d (use option fused = 0)",
                   max_len_ub + R, B * d.n_heads * S, ws->bh_cap);
@@ -1041,6 +1171,7 @@ int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, 
     a.B = B; a.K = K; a.R = R; a.M = B * R;
     a.xbuf = ws->xbuf; a.xgbuf = ws->xgbuf; a.ssbuf = ws->ssbuf; a.qbuf = ws->qbuf; a.knew = ws->knew; a.vnew = ws->vnew;
     a.attn = ws->attn; a.act = ws->act; a.apart = ws->apart; a.acount = ws->acount; a.nsplit = S;
+    a.xs_steps = (int)((((size_t)g_lds_max - XS_OFFSET) / a.M - 16) / 256);
     a.hp_max = ws->hp_max; a.hp_sum = ws->hp_sum; a.hp_arg = ws->hp_arg; a.hp_topv = ws->hp_topv; a.hp_topi = ws->hp_topi;
     a.hp_lx = ws->hp_lx;
     a.topk = topk; a.mode = mode; a.p = p; a.accept_len = accept_len; a.out_tokens = out_tokens; a.logits_dbg = logits_dbg;
@@ -1050,10 +1181,12 @@ int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, 
     a.trace_cap = ws->trace_cap;
     ws->epoch += 5ull * d.n_layers + 2ull;
     void* args[] = {&a};
-    const void* fn = m->dh == 128 ? (const void*)verify_fused_kernel<128> : (const void*)verify_fused_kernel<64>;
+    const bool tr = a.trace != nullptr;
+    const void* fn = m->dh == 128 ? (tr ? (const void*)verify_fused_kernel<128, true> : (const void*)verify_fused_kernel<128, false>)
+                                  : (tr ? (const void*)verify_fused_kernel<64, true> : (const void*)verify_fused_kernel<64, false>);
     const bool prof = m->prof_on && m->prof_n < m->prof_cap;
     if (prof) LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n], stream));
-    LASER_HIP_CHECK(hipLaunchCooperativeKernel(fn, dim3(ws->nwg), dim3(FT), args, sizeof(Shared), stream));
+    LASER_HIP_CHECK(hipLaunchCooperativeKernel(fn, dim3(ws->nwg), dim3(FT), args, (size_t)g_lds_max, stream));
     if (prof) { LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n + 1], stream)); ++m->prof_n; }
     return LASER_OK;
 }
