@@ -86,9 +86,8 @@ struct Shared {
     float rs[16];                         // rsqrt(mean square) per row
     float ss_acc[16][32];
     int row_pos[16], row_b[16];
+    int seq_slot[16], seq_len[16];        // per sequence of the batch: cache slot, committed length
     int flag;                             // barrier outcome / last-arriver broadcast
-    float hstat[FWAVES][4];
-    int hstat_i[FWAVES][2];
     int row_ok[LASER_MAX_DRAFT + 1], row_arg[LASER_MAX_DRAFT + 1];
     union alignas(16) {
         float red[MAX_UNITS][FWAVES][4][64];   // per (unit slot, wave) partial tiles   48 KiB
@@ -508,8 +507,8 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
 
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
         const int split = item % S, bh = item / S, h = bh % a.H, b = bh / a.H;
-        const int slot = a.seq_ids[b];
-        const int len = a.lens[slot];
+        const int slot = sh.seq_slot[b];
+        const int len = sh.seq_len[b];
         // Pages are taken at their cache positions, PPW consecutive pages per wave and a fixed AW*PPW pages per split,
         // and a page that holds new rows is composed from the cache (slots < len) and the exchange
         // buffers (slots len .. len+R-1). The arithmetic a row sees therefore depends only on its own
@@ -534,19 +533,18 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
                 }
                 Frag8 ak[PPW][NC32];
                 Frag4 bv[PPW][NC16];
-                // first the loads of every fully committed page of this wave, so that they travel together
+                // First the cache loads of all pages of this wave, unconditionally (a page index past the end
+                // is clamped, and a page that holds new rows is patched below), so that they share one round trip.
 #pragma unroll
                 for (int pp = 0; pp < PPW; ++pp) {
-                    const int p = pbase + pp, s0 = p * kPageSize;
-                    if (p < n_pages && s0 + kPageSize <= len) {
-                        const size_t base = (((size_t)layer * a.n_pages + bt[p]) * a.H + h) * kPageSize * DH;
-                        const uint16_t* kp = a.kpages + base + (size_t)r * DH + g * 8;
+                    const int p = min(pbase + pp, n_pages - 1);
+                    const size_t base = (((size_t)layer * a.n_pages + bt[p]) * a.H + h) * kPageSize * DH;
+                    const uint16_t* kp = a.kpages + base + (size_t)r * DH + g * 8;
 #pragma unroll
-                        for (int c = 0; c < NC32; ++c) ak[pp][c].u = *reinterpret_cast<const uint4*>(kp + c * 32);
-                        const uint16_t* vp = a.vpages + base + (size_t)r * kPageSize + 4 * g;
+                    for (int c = 0; c < NC32; ++c) ak[pp][c].u = *reinterpret_cast<const uint4*>(kp + c * 32);
+                    const uint16_t* vp = a.vpages + base + (size_t)r * kPageSize + 4 * g;
 #pragma unroll
-                        for (int c = 0; c < NC16; ++c) bv[pp][c].u = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * kPageSize);
-                    }
+                    for (int c = 0; c < NC16; ++c) bv[pp][c].u = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * kPageSize);
                 }
 #pragma unroll
                 for (int pp = 0; pp < PPW; ++pp) {
@@ -557,19 +555,24 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
                         const int ks = s0 + r;                            // this lane's key slot
                         const bool k_new = ks >= len;
                         const int kr = min(max(ks - len, 0), a.R - 1);
-                        const uint16_t* kp = k_new ? kn + (size_t)(b * a.R + kr) * a.d + (size_t)h * DH + g * 8
-                                                   : a.kpages + base + (size_t)r * DH + g * 8;
+                        {   // new rows: unconditional loads (clamped row), then select, so that they share a round trip
+                            const uint16_t* kp = kn + (size_t)(b * a.R + kr) * a.d + (size_t)h * DH + g * 8;
+                            Frag8 nk[NC32];
+                            uint16_t nv[4][NC16];
 #pragma unroll
-                        for (int c = 0; c < NC32; ++c) ak[pp][c].u = *reinterpret_cast<const uint4*>(kp + c * 32);
+                            for (int c = 0; c < NC32; ++c) nk[c].u = *reinterpret_cast<const uint4*>(kp + c * 32);
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const int vs = s0 + 4 * g + j;                // value slot
-                            const bool v_new = vs >= len;
-                            const int vr = min(max(vs - len, 0), a.R - 1);
+                            for (int j = 0; j < 4; ++j) {
+                                const int vr = min(max(s0 + 4 * g + j - len, 0), a.R - 1);
 #pragma unroll
-                            for (int c = 0; c < NC16; ++c)
-                                bv[pp][c].h[j] = v_new ? vn[(size_t)(b * a.R + vr) * a.d + (size_t)h * DH + c * 16 + r]
-                                                       : a.vpages[base + (size_t)(c * 16 + r) * kPageSize + 4 * g + j];
+                                for (int c = 0; c < NC16; ++c) nv[j][c] = vn[(size_t)(b * a.R + vr) * a.d + (size_t)h * DH + c * 16 + r];
+                            }
+#pragma unroll
+                            for (int c = 0; c < NC32; ++c) if (k_new) ak[pp][c].u = nk[c].u;
+#pragma unroll
+                            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                                for (int c = 0; c < NC16; ++c) if (s0 + 4 * g + j >= len) bv[pp][c].h[j] = nv[j][c];
                         }
                         // this wave owns the page: store its new rows into the cache for later steps
                         if (k_new && ks < len + a.R) {
@@ -672,20 +675,36 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
                 const float* pbase = a.apart + (((size_t)layer * a.B * a.H + bh) * S) * PSZ;
                 for (int idx = threadIdx.x; idx < 16 * DH / 2; idx += FT) {
                     const int q = idx / (DH / 2), c = (idx % (DH / 2)) * 2;
-                    if (q >= a.R) continue;
-                    float M = -INFINITY;
-                    for (int s2 = 0; s2 < S; ++s2) M = fmaxf(M, pbase[(size_t)s2 * PSZ + q]);
-                    float Lq = 0.f, O0 = 0.f, O1 = 0.f;
-                    if (M != -INFINITY)
-                        for (int s2 = 0; s2 < S; ++s2) {
-                            const float* ps = pbase + (size_t)s2 * PSZ;
-                            const float f = __expf(ps[q] - M);
-                            Lq += ps[16 + q] * f;
-                            O0 += ps[32 + q * DH + c] * f;
-                            O1 += ps[32 + q * DH + c + 1] * f;
+                    // the partials of up to 8 splits travel together (unconditional, clamped loads): a loop
+                    // with one dependent round trip per split would cost more than the attention itself
+                    float M = -INFINITY, Lq = 0.f, O0 = 0.f, O1 = 0.f;
+                    for (int s0 = 0; s0 < S; s0 += 8) {
+                        float pm[8], pl[8];
+                        float2 po[8];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const float* ps = pbase + (size_t)min(s0 + j, S - 1) * PSZ;
+                            pm[j] = ps[q]; pl[j] = ps[16 + q];
+                            po[j] = *reinterpret_cast<const float2*>(ps + 32 + q * DH + c);
                         }
-                    st_u32(ob + (size_t)(b * a.R + q) * a.d + (size_t)h * DH + c,
-                           pack_h2(Lq > 0.f ? O0 / Lq : 0.f, Lq > 0.f ? O1 / Lq : 0.f));
+                        float Mn = M;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) if (s0 + j < S) Mn = fmaxf(Mn, pm[j]);
+                        if (Mn != -INFINITY) {
+                            const float f0 = __expf(M - Mn);           // M = -inf on the first group: exp gives 0
+                            Lq *= f0; O0 *= f0; O1 *= f0;
+#pragma unroll
+                            for (int j = 0; j < 8; ++j)
+                                if (s0 + j < S) {
+                                    const float f = __expf(pm[j] - Mn);
+                                    Lq += pl[j] * f; O0 += po[j].x * f; O1 += po[j].y * f;
+                                }
+                        }
+                        M = Mn;
+                    }
+                    if (q < a.R)
+                        st_u32(ob + (size_t)(b * a.R + q) * a.d + (size_t)h * DH + c,
+                               pack_h2(Lq > 0.f ? O0 / Lq : 0.f, Lq > 0.f ? O1 / Lq : 0.f));
                 }
             }
         }
@@ -727,6 +746,9 @@ struct HStat {
         float otv[KTOP]; int oti[KTOP];
 #pragma unroll
         for (int j = 0; j < KTOP; ++j) { otv[j] = __shfl_xor(tv[j], off); oti[j] = __shfl_xor(ti[j], off); }
+        merge(omx, osum, olx, oarg, otv, oti);
+    }
+    __device__ void merge(float omx, float osum, float olx, int oarg, const float (&otv)[KTOP], const int (&oti)[KTOP]) {
         const float M = fmaxf(mx, omx);
         if (M != -INFINITY) sum = sum * __expf(mx - M) + osum * __expf(omx - M);
         if (hbefore(omx, oarg, mx, arg)) arg = oarg;
@@ -737,12 +759,12 @@ struct HStat {
     }
 };
 
-// Consumes the logits tiles a wave has accumulated in sh.red (unit u of global wave `chunk` is
-// vocabulary tile chunk + u * chunks): per-row running statistics, partial results per wave.
-__device__ inline void head_epilogue(const FusedArgs& a, Shared& sh, int chunks) {
+// Consumes the logits tiles a wave has accumulated in sh.red (unit u of global wave gw is vocabulary
+// tile gw + u * waves of the launch): per-row running statistics, merged per workgroup.
+__device__ inline void head_epilogue(const FusedArgs& a, Shared& sh, uint4* xs, int chunks) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
-    const int chunk = blockIdx.x * FWAVES + wave;          // chunk id == global wave id
+    const int gw = blockIdx.x * FWAVES + wave, ngw = gridDim.x * FWAVES;     // global wave id, waves of the launch
     const int row = r;
     int x = -1;
     if (row < a.M) {
@@ -755,7 +777,7 @@ __device__ inline void head_epilogue(const FusedArgs& a, Shared& sh, int chunks)
     const float rs = sh.rs[r];
     const int n_my = n_units(a, PH_HEAD);
     for (int u = 0; u < n_my; ++u) {
-        const int t = chunk + u * chunks;
+        const int t = gw + u * ngw;
         const int n = t * 16 + 4 * g;
         float lv[4];
 #pragma unroll
@@ -769,40 +791,71 @@ __device__ inline void head_epilogue(const FusedArgs& a, Shared& sh, int chunks)
     }
     st.merge_xor(16);
     st.merge_xor(32);
-    if (g == 0 && row < a.M) {
-        const size_t o = (size_t)row * chunks + chunk;
-        st_f32(a.hp_max + o, st.mx); st_f32(a.hp_sum + o, st.sum); st_i32(a.hp_arg + o, st.arg);
+    // merge the 8 waves of the workgroup (fixed order) so that the acceptance phase reads one record per
+    // workgroup and row; the staging area is free by now
+    float* ws_f = reinterpret_cast<float*>(xs);                   // [FWAVES][16][3 + KTOP]
+    int* ws_i = reinterpret_cast<int*>(ws_f + FWAVES * 16 * (3 + KTOP));   // [FWAVES][16][1 + KTOP]
+    if (g == 0) {
+        float* f = ws_f + (wave * 16 + r) * (3 + KTOP);
+        int* i = ws_i + (wave * 16 + r) * (1 + KTOP);
+        f[0] = st.mx; f[1] = st.sum; f[2] = st.lx; i[0] = st.arg;
 #pragma unroll
-        for (int j = 0; j < KTOP; ++j) { st_f32(a.hp_topv + o * KTOP + j, st.tv[j]); st_i32(a.hp_topi + o * KTOP + j, st.ti[j]); }
-        if (st.lx != -INFINITY) st_f32(a.hp_lx + row, st.lx);
+        for (int j = 0; j < KTOP; ++j) { f[3 + j] = st.tv[j]; i[1 + j] = st.ti[j]; }
+    }
+    __syncthreads();
+    if (threadIdx.x < 16 && (int)threadIdx.x < a.M) {
+        const int rr = threadIdx.x;
+        HStat m;
+        m.init();
+        for (int w = 0; w < FWAVES; ++w) {
+            const float* f = ws_f + (w * 16 + rr) * (3 + KTOP);
+            const int* i = ws_i + (w * 16 + rr) * (1 + KTOP);
+            float otv[KTOP]; int oti[KTOP];
+#pragma unroll
+            for (int j = 0; j < KTOP; ++j) { otv[j] = f[3 + j]; oti[j] = i[1 + j]; }
+            m.merge(f[0], f[1], f[2], i[0], otv, oti);
+        }
+        const size_t o = (size_t)rr * chunks + blockIdx.x;
+        st_f32(a.hp_max + o, m.mx); st_f32(a.hp_sum + o, m.sum); st_i32(a.hp_arg + o, m.arg);
+#pragma unroll
+        for (int j = 0; j < KTOP; ++j) { st_f32(a.hp_topv + o * KTOP + j, m.tv[j]); st_i32(a.hp_topi + o * KTOP + j, m.ti[j]); }
+        if (m.lx != -INFINITY) st_f32(a.hp_lx + rr, m.lx);
     }
 }
 
+// One workgroup per sequence, one wave per row (rows wave, wave + 8, ..): lanes stride over the
+// per-workgroup records (`chunks` = workgroups of the launch), four records in flight per lane.
 __device__ inline void accept_phase(const FusedArgs& a, Shared& sh, int chunks) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     for (int b = blockIdx.x; b < a.B; b += gridDim.x) {
-        for (int r = 0; r < a.R; ++r) {
+        for (int r = wave; r < a.R; r += FWAVES) {
             const int row = b * a.R + r;
             int x = (r < a.K && r < a.draft_len[b]) ? a.drafts[(size_t)b * a.K + r] : -1;
             if (x >= a.V) x = -1;
             const float lx = x >= 0 ? a.hp_lx[row] : -INFINITY;
             float mx = -INFINITY, sum = 0.f;
             int arg = 0x7FFFFFFF, ahead = 0;
-            for (int c = threadIdx.x; c < chunks; c += FT) {
-                const size_t o = (size_t)row * chunks + c;
-                const float cm = a.hp_max[o], cs = a.hp_sum[o];
-                const int ca = a.hp_arg[o];
-                const float M = fmaxf(mx, cm);
-                if (M != -INFINITY) sum = sum * __expf(mx - M) + cs * __expf(cm - M);
-                if (hbefore(cm, ca, mx, arg)) arg = ca;
-                mx = M;
-                if (x >= 0)
+            for (int c0 = lane; c0 < chunks; c0 += 64 * 4) {
+                float cm[4], cs[4], tv[4][KTOP];
+                int ca[4], ti[4][KTOP];
 #pragma unroll
-                    for (int j = 0; j < KTOP; ++j) {
-                        const float v = a.hp_topv[o * KTOP + j];
-                        const int i = a.hp_topi[o * KTOP + j];
-                        ahead += (i != x && hbefore(v, i, lx, x)) ? 1 : 0;
-                    }
+                for (int q = 0; q < 4; ++q) {          // unconditional loads (clamped), all in flight together
+                    const size_t o = (size_t)row * chunks + min(c0 + 64 * q, chunks - 1);
+                    cm[q] = a.hp_max[o]; cs[q] = a.hp_sum[o]; ca[q] = a.hp_arg[o];
+#pragma unroll
+                    for (int j = 0; j < KTOP; ++j) { tv[q][j] = a.hp_topv[o * KTOP + j]; ti[q][j] = a.hp_topi[o * KTOP + j]; }
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (c0 + 64 * q >= chunks) continue;
+                    const float M = fmaxf(mx, cm[q]);
+                    if (M != -INFINITY) sum = sum * __expf(mx - M) + cs[q] * __expf(cm[q] - M);
+                    if (hbefore(cm[q], ca[q], mx, arg)) arg = ca[q];
+                    mx = M;
+                    if (x >= 0)
+#pragma unroll
+                        for (int j = 0; j < KTOP; ++j) ahead += (ti[q][j] != x && hbefore(tv[q][j], ti[q][j], lx, x)) ? 1 : 0;
+                }
             }
             for (int off = 32; off > 0; off >>= 1) {
                 const float omx = __shfl_xor(mx, off), osum = __shfl_xor(sum, off);
@@ -813,29 +866,17 @@ __device__ inline void accept_phase(const FusedArgs& a, Shared& sh, int chunks) 
                 if (hbefore(omx, oarg, mx, arg)) arg = oarg;
                 mx = M;
             }
-            __syncthreads();
-            if (lane == 0) { sh.hstat[wave][0] = mx; sh.hstat[wave][1] = sum; sh.hstat_i[wave][0] = arg; sh.hstat_i[wave][1] = ahead; }
-            __syncthreads();
-            if (threadIdx.x == 0) {
-                float M = -INFINITY, S = 0.f; int A = 0x7FFFFFFF, rank = 0;
-                for (int w = 0; w < FWAVES; ++w) {
-                    const float wm = sh.hstat[w][0];
-                    const float nm = fmaxf(M, wm);
-                    if (nm != -INFINITY) S = S * __expf(M - nm) + sh.hstat[w][1] * __expf(wm - nm);
-                    if (hbefore(wm, sh.hstat_i[w][0], M, A)) A = sh.hstat_i[w][0];
-                    M = nm;
-                    rank += sh.hstat_i[w][1];
-                }
+            if (lane == 0) {
                 bool ok = false;
                 if (x >= 0) {
-                    const float q = __expf(lx - M) / S;
-                    const bool in_k = rank < a.topk, above = q > a.p, top1 = rank == 0;
+                    const float q = __expf(lx - mx) / sum;
+                    const bool in_k = ahead < a.topk, above = q > a.p, top1 = ahead == 0;
                     ok = a.mode == LASER_MODE_RV ? (in_k && above)
                        : a.mode == LASER_MODE_RV_OR_TOP1 ? (top1 || (in_k && above))
                        : a.mode == LASER_MODE_TOPK_ONLY ? in_k : (top1 || above);
                 }
                 sh.row_ok[r] = ok ? 1 : 0;
-                sh.row_arg[r] = A;
+                sh.row_arg[r] = arg;
             }
         }
         __syncthreads();
@@ -867,6 +908,9 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         if (row < a.M) { b = row / a.R; pos = a.lens[a.seq_ids[b]] + row % a.R; }
         sh.row_pos[row] = pos;
         sh.row_b[row] = b;
+        const int sl = row < a.B ? a.seq_ids[row] : 0;
+        sh.seq_slot[row] = sl;
+        sh.seq_len[row] = row < a.B ? a.lens[sl] : 0;
     }
     __syncthreads();
 
@@ -1037,13 +1081,13 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
     stamp<TR>(a, ns);
 
     // ---- output head + acceptance ----
-    const int chunks = nwg * FWAVES;
+    const int chunks = nwg;            // one record per workgroup and row goes from the head to the acceptance phase
     {
         float ssv[8];
         ss_issue(a.ssbuf + (size_t)(2 * a.L) * nwg * 16, ssv);
         stream_phase<1, TR>(a, sh, xs, p_head, a.xgbuf + (size_t)(2 * a.L) * XS, ring);
         ss_finish(a, sh, ssv);
-        head_epilogue(a, sh, chunks);
+        head_epilogue(a, sh, xs, chunks);
     }
     stamp<TR>(a, ns);
     if (!grid_sync(a, sh, epoch, no_prefetch)) return;
@@ -1088,7 +1132,7 @@ bool fused_supported(const Model* m, int B, int K) {
            (m->dh == 64 || m->dh == 128) && nwg <= 256 &&
            3 * per(d.d_model / 16, nwg) <= MAX_UNITS && 2 * per(d.ffn / 16, nwg) <= MAX_UNITS &&
            per(d.vocab / 16, nwg * FWAVES) <= MAX_UNITS &&
-           g_lds_max >= (int)sizeof(Shared) && ((size_t)g_lds_max - XS_OFFSET) / M >= 272;
+           g_lds_max >= (int)sizeof(Shared) && (size_t)g_lds_max >= XS_OFFSET + 16384 && ((size_t)g_lds_max - XS_OFFSET) / M >= 272;
 }
 
 void fused_free(Model* m) {
