@@ -62,3 +62,110 @@ def test_7b_latency_strict_speculation_reproduces_greedy_decoding(fused):
         print(f"[7b fused={fused}] {kind}: {len(produced)} tokens in {steps} steps, identical to greedy decoding")
     assert not eng.model.aborted()
     eng.close()
+
+
+def test_7b_throughput_strict_speculation_reproduces_greedy_decoding():
+    """The same property at the throughput shape (32 layers, B = 64, prompt 512, K = 10, paged cache):
+    M = 704 rows per step on the tiled matrix-core GEMMs. The reference text is decoded with the same
+    launch shape (K = 10 rows per sequence, no drafts), so every row goes through identical arithmetic;
+    each sequence then gets its own mix of right and wrong drafts."""
+    sh = synth.SHAPES["7b"]
+    B, K, ctx_len, N = 64, 10, 512, 23
+    laser, eng = _engine(sh, B, K, ctx_len, 160, 0)
+    ctx = synth.gen_contexts(synth.POOLS["7b_throughput"], B, ctx_len, 3, salt=1, min_remaining=K)
+    eng.prefill(ctx["ctx"])
+    first = torch.as_tensor(np.ascontiguousarray(ctx["ctx"][:, -1]), dtype=torch.int32).cuda()
+
+    # reference: one token per step and sequence
+    eng.pending.copy_(first)
+    eng.drafts.fill_(-1)
+    eng.draft_len.fill_(0)
+    ref = np.empty((B, N), dtype=np.int32)
+    for i in range(N):
+        acc, out, _ = laser.verify_step(eng.model, eng.kv, eng.seq_ids, eng.pending, eng.drafts, eng.draft_len, 1, -1.0, 0)
+        assert int(acc.abs().sum()) == 0
+        laser.kv_commit(eng.kv, eng.seq_ids, acc)
+        eng.pending.copy_(out[:, 0])
+        ref[:, i] = out[:, 0].cpu().numpy()
+        eng.kv.read_lens(eng.seq_ids)                    # tightens the host's length bound (it assumes K+1 per step)
+    assert eng.kv.read_lens(eng.seq_ids).tolist() == [ctx_len - 1 + N] * B
+
+    # speculation: sequence b's drafts are right up to a cut of its own (K = all right), then wrong
+    r = np.random.default_rng(3)
+    for b in range(B):
+        eng.kv.set_len(b, ctx_len - 1)
+    done = np.zeros(B, dtype=np.int64)                      # tokens produced so far per sequence
+    produced = [[] for _ in range(B)]
+    pend = ctx["ctx"][:, -1].astype(np.int32).copy()
+    steps = 0
+    while (done + K + 1 <= N).all():
+        d = np.stack([ref[b, done[b]:done[b] + K] for b in range(B)]).astype(np.int32)
+        cut = r.integers(0, K + 1, size=B)
+        cut[::7] = K
+        for b in range(B):
+            if cut[b] < K:
+                d[b, cut[b]] = (d[b, cut[b]] + 1 + int(r.integers(0, sh.vocab - 1))) % sh.vocab    # certainly wrong
+                d[b, cut[b] + 1:] = r.integers(0, sh.vocab, size=K - cut[b] - 1)
+        eng.pending.copy_(torch.as_tensor(pend))
+        eng.drafts.copy_(torch.as_tensor(d))
+        eng.draft_len.fill_(K)
+        acc, out, _ = laser.verify_step(eng.model, eng.kv, eng.seq_ids, eng.pending, eng.drafts, eng.draft_len, 1, -1.0, 0)
+        laser.kv_commit(eng.kv, eng.seq_ids, acc)
+        a, o = acc.cpu().numpy(), out.cpu().numpy()
+        assert a.tolist() == cut.tolist(), steps           # exactly the right drafts are accepted
+        for b in range(B):
+            produced[b] += o[b, :a[b] + 1].tolist()
+            pend[b] = o[b, a[b]]
+        done += a + 1
+        steps += 1
+        eng.kv.read_lens(eng.seq_ids)
+    for b in range(B):
+        assert produced[b] == ref[b, :len(produced[b])].tolist(), b
+    assert eng.kv.read_lens(eng.seq_ids).tolist() == (ctx_len - 1 + done).tolist()
+    print(f"[7b throughput] {int(done.sum())} tokens in {steps} steps of 704 rows, identical to one-token decoding")
+    eng.close()
+
+
+def test_head_stress_shape_sampled_against_the_oracle():
+    """Output head + acceptance at the stress shape (d 4096, vocabulary 128256, 256 sequences x 16 rows =
+    4096 rows) through laser_verify_head; the oracle recomputes three whole sequences (48 rows) from the
+    same weights and hidden states; every sequence's emitted row is checked for form."""
+    import paper_2408_05676_amd as laser
+    from oracle import acceptance
+    from tests import gpu_util as gu
+    sh = synth.SHAPES["head128k"]
+    B, K = 256, 15
+    R = K + 1
+    w = torch_gen_weight(sh, "wlm", -1, "cuda").contiguous()
+    model = laser.Model(0, sh.d, sh.n_heads, sh.ffn, sh.vocab, {"wlm": w}, B * R, B, 0)
+    g = torch.Generator(device="cuda").manual_seed(7)
+    # hidden states with a planted direction so that some drafts clear the threshold: h = a * w[t] + noise
+    planted = torch.randint(0, sh.vocab, (B, R), generator=g, device="cuda")
+    noise = torch.randn((B, R, sh.d), generator=g, device="cuda") * 0.5
+    amp = 5.0 + torch.rand((B, R, 1), generator=g, device="cuda") * 9.0
+    h = (amp * w[planted].float() + noise).to(torch.float16)    # planted logit ~ 1.64 amp against ~N(0, 0.64^2) others
+    drafts = planted[:, :K].to(torch.int32).clone()
+    wrong = torch.rand((B, K), generator=g, device="cuda") < 0.12
+    drafts[wrong] = torch.randint(0, sh.vocab, (int(wrong.sum()),), generator=g, device="cuda", dtype=torch.int32)
+    dl = torch.randint(0, K + 1, (B,), generator=g, device="cuda", dtype=torch.int32)
+    dl[::5] = K
+    k, p = 2, 0.1
+    acc, out, lg = laser.verify_head(model, h, drafts, dl, k, p, 0, want_logits=True)
+    torch.cuda.synchronize()
+    a, o, d_np, dl_np = acc.cpu().numpy(), out.cpu().numpy(), drafts.cpu().numpy(), dl.cpu().numpy()
+    assert (a >= 0).all() and (a <= dl_np).all()
+    for b in range(B):
+        assert o[b, :a[b]].tolist() == d_np[b, :a[b]].tolist() and 0 <= o[b, a[b]] < sh.vocab and (o[b, a[b] + 1:] == -1).all()
+    S = [0, 117, 255]
+    w64 = w.float().cpu().numpy().astype(np.float64)
+    h64 = h[S].float().cpu().numpy().astype(np.float64)
+    logits = h64 @ w64.T                                      # [3][16][V]
+    ok, max_err, ratio = gu.logits_close(lg[S].cpu().numpy().astype(np.float64), logits)
+    assert ok, (max_err, ratio)
+    oa, oo, stats, gaps = acceptance.verify_batch(logits, d_np[S], dl_np[S], k, p, 0)
+    ora = {"accept_len": oa, "out_tokens": oo, "stats": stats, "argmax_gap": gaps, "logits": logits}
+    flips, bad = gu.classify_step(a[S], o[S], ora, d_np[S], dl_np[S], k, p)
+    assert not bad, bad
+    print(f"[head 128k] 4096 rows; sampled sequences: worst logit error {ratio:.3f} of bound, flips {flips}, "
+          f"accepted lengths {a[S].tolist()} (oracle {list(map(int, oa))}), mean accepted {a.mean():.2f}")
+    model.close()
