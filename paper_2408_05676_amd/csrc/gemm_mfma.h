@@ -2,14 +2,14 @@
 //   Y[M][N] = X[M][Kd] * W[N][Kd]^T,  X fp16, W bf16 (widened to fp16 on its way into LDS), fp32 accumulate.
 //
 // Workgroup tile 128 x 128, 256 threads = 2 x 2 waves of 64 x 64, each wave 2 x 2
-// v_mfma_f32_32x32x16_f16 tiles (64 accumulator registers). Global loads for step k+1 are issued
-// into registers before the matrix work of step k and written to the single, 12 KiB LDS buffer after
-// it; several workgroups per CU interleave. LDS rows are padded (32 -> 48 bytes) against bank
-// conflicts. Reduction step: 16. Measured at M = 704, N = 12288, K = 4096 (the step has to move
-// 1.18 GB of L2 hits): step 16 -> 170 us, 32 -> 260 us, 64 -> 242 us, 128 -> 270 us; a 256 x 128 tile
-// -> 320 us. Counters show 89 % L2 hits and only 145 MB fetched from HBM per launch, i.e. the
-// XCD-aware tile order works and the kernel is bound by how the L2-hit traffic is requested, not by
-// HBM or by the matrix cores (which reach 46 % of peak when the loads are stubbed out).
+// v_mfma_f32_32x32x16_f16 tiles (64 accumulator registers). Reduction step 64; a thread keeps the
+// global loads of the next step in flight in registers while the current one is written to one of two
+// LDS buffers (36 KiB each pair, rows padded 128 -> 144 bytes against bank conflicts) and multiplied;
+// one workgroup barrier per step; two workgroups per CU. Measured at M = 704, N = 12288, K = 4096:
+// 108-114 us = 25 % of the fp16 matrix peak (reduction step 32: 115-120 us, 16: 170 us, 128: 151 us).
+// Counters show 89 % L2 hits and the weights fetched from HBM once per launch, i.e. the XCD-aware tile
+// order works; what is left is the quantisation of 576 tiles over 256 CUs (75 %) and the L2 -> LDS ->
+// register path.
 //
 // v_mfma_f32_32x32x16_f16, wave64, lane l, g = l / 32:
 //   A: lane holds A[row = l % 32][k = 8 g .. 8 g + 7];  B: lane holds B[k = 8 g .. 8 g + 7][col = l % 32]
@@ -20,13 +20,16 @@
 // XCDs, each with its own L2): the weight tile is then fetched from HBM once and hit in that L2.
 #pragma once
 
+#include <type_traits>
+
 #include "mfma.h"
 
 namespace laser {
 
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
-constexpr int GM_BM = 128, GM_BN = 128, GM_BK = 16, GM_LD = 24;   // LD: halves per padded LDS row
+constexpr int GM_BM = 128, GM_BN = 128, GM_BK = 64, GM_LD = 72;   // LD: halves per padded LDS row
+constexpr int GM_DEPTH = 2;         // k-steps of global loads in flight per thread (even)
 
 struct GemmTileArgs {
     const uint16_t* W;      // [N][Kd] bf16   (SwiGLU: [2F][Kd], gate rows then up rows; N = F)
@@ -54,13 +57,19 @@ __device__ inline int w_row(const GemmTileArgs& a, int tn, int j) {
     return tn * GM_BN + j;
 }
 
+template <int J, int N, class F>
+__device__ inline void static_for(F&& f) {
+    if constexpr (J < N) { f(std::integral_constant<int, J>{}); static_for<J + 1, N>(f); }
+}
+
 template <int EPI>
-__global__ __launch_bounds__(256, 4) void gemm_mfma_kernel(GemmTileArgs a) {
+__global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
     constexpr int CH = GM_BK / 8;            // 16-byte chunks per tile row and k-step
     constexpr int RPT = 256 / CH;            // rows staged per pass of the 256 threads
     constexpr int ST = GM_BM / RPT;          // passes (GM_BM == GM_BN)
-    __shared__ __attribute__((aligned(16))) uint16_t sA[GM_BM][GM_LD];
-    __shared__ __attribute__((aligned(16))) uint16_t sB[GM_BN][GM_LD];
+    constexpr int D = GM_DEPTH;
+    __shared__ __attribute__((aligned(16))) uint16_t sA[2][GM_BM][GM_LD];
+    __shared__ __attribute__((aligned(16))) uint16_t sB[2][GM_BN][GM_LD];
     // ---- XCD-aware tile order ----
     const int total = a.tiles_m * a.tiles_n;
     const int per_xcd = (total + 7) / 8;
@@ -94,46 +103,54 @@ __global__ __launch_bounds__(256, 4) void gemm_mfma_kernel(GemmTileArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    Frag8 ra[ST], rb[ST];
-    const int nk = a.Kd / GM_BK;
-    auto gload = [&](int kt) {
+    // Register ring of D k-steps. The element type must be a native vector: an array of HIP's uint4
+    // (a struct) that is only copied as a whole is not promoted to registers and lands in scratch.
+    u32x4 ra[D][ST], rb[D][ST];
+    const int nk = a.Kd / GM_BK;             // the host guarantees Kd % GM_BK == 0
+    auto gload = [&](auto slot_c, int kt) {
+        constexpr int slot = decltype(slot_c)::value;
+        kt = kt < nk ? kt : nk - 1;          // unconditional, clamped: a load under a branch would be waited for at once
 #pragma unroll
         for (int i = 0; i < ST; ++i) {
-            ra[i].u = *reinterpret_cast<const uint4*>(xa[i] + kt * GM_BK);
-            rb[i].u = *reinterpret_cast<const uint4*>(wb[i] + kt * GM_BK);
+            ra[slot][i] = *reinterpret_cast<const u32x4*>(xa[i] + kt * GM_BK);
+            rb[slot][i] = *reinterpret_cast<const u32x4*>(wb[i] + kt * GM_BK);
         }
     };
-    auto lstore = [&]() {
+    static_for<0, D - 1>([&](auto sc) { gload(sc, decltype(sc)::value); });
+    for (int kt0 = 0; kt0 < nk; kt0 += D) {
+        static_for<0, D>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            constexpr int buf = j & 1;       // D is even
+            const int kt = kt0 + j;
+            gload(std::integral_constant<int, (j + D - 1) % D>{}, kt + D - 1);
+            __builtin_amdgcn_sched_barrier(0);
+            const unsigned keep = kt < nk ? 0xFFFFFFFFu : 0u;     // steps past the end contribute zeros (no branch)
 #pragma unroll
-        for (int i = 0; i < ST; ++i) {
-            bf16x8_to_f16x8(rb[i]);
-            *reinterpret_cast<uint4*>(&sA[srow + RPT * i][sk]) = ra[i].u;
-            *reinterpret_cast<uint4*>(&sB[srow + RPT * i][sk]) = rb[i].u;
-        }
-    };
-    gload(0);
-    lstore();
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) gload(kt + 1);
-#pragma unroll
-        for (int kk = 0; kk < GM_BK / 16; ++kk) {
-            Frag8 fa[2], fb[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                fa[i].u = *reinterpret_cast<const uint4*>(&sA[wm * 64 + i * 32 + lr][kk * 16 + lg * 8]);
-                fb[i].u = *reinterpret_cast<const uint4*>(&sB[wn * 64 + i * 32 + lr][kk * 16 + lg * 8]);
+            for (int i = 0; i < ST; ++i) {
+                Frag8 fw;
+                fw.v4 = rb[j][i];
+                bf16x8_to_f16x8(fw);
+                *reinterpret_cast<u32x4*>(&sA[buf][srow + RPT * i][sk]) = ra[j][i] & keep;
+                *reinterpret_cast<u32x4*>(&sB[buf][srow + RPT * i][sk]) = fw.v4;
             }
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = mfma_32x32x16(fa[i], fb[j], acc[i][j]);
-        }
-        __syncthreads();                    // every wave has finished reading the buffer
-        if (kt + 1 < nk) {
-            lstore();
+            // One barrier per step: a wave may run one step ahead (into the other buffer); it cannot
+            // overwrite this buffer before every wave has passed the next step's barrier, i.e. has
+            // finished reading it.
             __syncthreads();
-        }
+#pragma unroll
+            for (int kk = 0; kk < GM_BK / 16; ++kk) {
+                Frag8 fa[2], fb[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    fa[i].v4 = *reinterpret_cast<const u32x4*>(&sA[buf][wm * 64 + i * 32 + lr][kk * 16 + lg * 8]);
+                    fb[i].v4 = *reinterpret_cast<const u32x4*>(&sB[buf][wn * 64 + i * 32 + lr][kk * 16 + lg * 8]);
+                }
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int jj = 0; jj < 2; ++jj) acc[i][jj] = mfma_32x32x16(fa[i], fb[jj], acc[i][jj]);
+            }
+        });
     }
     // ---- epilogue: lane holds column lr of each 32-wide tile, rows 8 (e / 4) + 4 lg + e % 4 ----
 #pragma unroll

@@ -25,9 +25,11 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));   // native 16-byte vector (arrays of it stay in registers)
 
 union Frag8 {            // 8 x 16-bit = 16 bytes (fp16 for MFMA operands; raw bf16 right after a weight load)
     uint4 u;
+    u32x4 v4;
     uint32_t w[4];
     half8_t v;
     half2_t v2[4];
