@@ -35,7 +35,7 @@ struct GemmTileArgs {
     const uint16_t* W;      // [N][Kd] bf16   (SwiGLU: [2F][Kd], gate rows then up rows; N = F)
     const uint16_t* X;      // [M][Kd] fp16
     int M, N, Kd;
-    int tiles_m, tiles_n;   // tiles_n counts 128-column tiles (SwiGLU: 64-feature tiles)
+    int tiles_m, tiles_n;   // tiles_n counts BN-column tiles (SwiGLU: 64-feature tiles)
     float* outf;            // EPI_F32: [M][N] store; EPI_RESID: [M][N] accumulate
     uint16_t* outh;         // EPI_SWIGLU: [M][N] fp16
 };
@@ -46,15 +46,15 @@ __device__ inline float16_t mfma_32x32x16(const Frag8& a, const Frag8& b, float1
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(a.v, b.v, c, 0, 0, 0);
 }
 
-// weight row behind tile column j (0..127) of n-tile tn
-template <int EPI>
+// weight row behind tile column j (0..BN-1) of n-tile tn
+template <int EPI, int BN>
 __device__ inline int w_row(const GemmTileArgs& a, int tn, int j) {
     if (EPI == GEPI_SWIGLU) {
         // columns of a wave: [32 gate | 32 up] of the same 32 features, so that one lane holds both
         const int wn = j >> 6, ct = (j >> 5) & 1, c = j & 31;
         return (ct ? a.N : 0) + tn * 64 + wn * 32 + c;
     }
-    return tn * GM_BN + j;
+    return tn * BN + j;
 }
 
 template <int J, int N, class F>
@@ -62,14 +62,20 @@ __device__ inline void static_for(F&& f) {
     if constexpr (J < N) { f(std::integral_constant<int, J>{}); static_for<J + 1, N>(f); }
 }
 
-template <int EPI>
+// BN = 128: 2 x 2 waves of 64 x 64. BN = 64 (narrow outputs, where 128-column tiles would leave CUs
+// without work): 2 x 2 waves of 64 x 32. The SwiGLU epilogue needs BN = 128.
+template <int EPI, int BN>
 __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
+    static_assert(BN == 128 || (BN == 64 && EPI != GEPI_SWIGLU), "tile width");
     constexpr int CH = GM_BK / 8;            // 16-byte chunks per tile row and k-step
     constexpr int RPT = 256 / CH;            // rows staged per pass of the 256 threads
-    constexpr int ST = GM_BM / RPT;          // passes (GM_BM == GM_BN)
+    constexpr int ST = GM_BM / RPT;          // passes over the activation rows
+    constexpr int STB = BN / RPT;            // passes over the weight rows
+    constexpr int WN = BN / 2;               // columns per wave
+    constexpr int NJ = WN / 32;              // 32-column MFMA tiles per wave
     constexpr int D = GM_DEPTH;
     __shared__ __attribute__((aligned(16))) uint16_t sA[2][GM_BM][GM_LD];
-    __shared__ __attribute__((aligned(16))) uint16_t sB[2][GM_BN][GM_LD];
+    __shared__ __attribute__((aligned(16))) uint16_t sB[2][BN][GM_LD];
     // ---- XCD-aware tile order ----
     const int total = a.tiles_m * a.tiles_n;
     const int per_xcd = (total + 7) / 8;
@@ -84,37 +90,39 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
     // global -> LDS staging: thread t moves chunk t % CH of rows t / CH + RPT i of both operands
     const int srow = tid / CH, sk = (tid % CH) * 8;
     const uint16_t* xa[ST];
-    const uint16_t* wb[ST];
+    const uint16_t* wb[STB];
 #pragma unroll
     for (int i = 0; i < ST; ++i) {
         int row = tm * GM_BM + srow + RPT * i;
         row = row < a.M ? row : a.M - 1;
         xa[i] = a.X + (size_t)row * a.Kd + sk;
-        int wr = w_row<EPI>(a, tn, srow + RPT * i);
+    }
+#pragma unroll
+    for (int i = 0; i < STB; ++i) {
+        int wr = w_row<EPI, BN>(a, tn, srow + RPT * i);
         const int wmax = (EPI == GEPI_SWIGLU ? 2 * a.N : a.N) - 1;
         wr = wr < wmax ? wr : wmax;
         wb[i] = a.W + (size_t)wr * a.Kd + sk;
     }
-    float16_t acc[2][2];
+    float16_t acc[2][NJ];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     // Register ring of D k-steps. The element type must be a native vector: an array of HIP's uint4
     // (a struct) that is only copied as a whole is not promoted to registers and lands in scratch.
-    u32x4 ra[D][ST], rb[D][ST];
+    u32x4 ra[D][ST], rb[D][STB];
     const int nk = a.Kd / GM_BK;             // the host guarantees Kd % GM_BK == 0
     auto gload = [&](auto slot_c, int kt) {
         constexpr int slot = decltype(slot_c)::value;
         kt = kt < nk ? kt : nk - 1;          // unconditional, clamped: a load under a branch would be waited for at once
 #pragma unroll
-        for (int i = 0; i < ST; ++i) {
-            ra[slot][i] = *reinterpret_cast<const u32x4*>(xa[i] + kt * GM_BK);
-            rb[slot][i] = *reinterpret_cast<const u32x4*>(wb[i] + kt * GM_BK);
-        }
+        for (int i = 0; i < ST; ++i) ra[slot][i] = *reinterpret_cast<const u32x4*>(xa[i] + kt * GM_BK);
+#pragma unroll
+        for (int i = 0; i < STB; ++i) rb[slot][i] = *reinterpret_cast<const u32x4*>(wb[i] + kt * GM_BK);
     };
     static_for<0, D - 1>([&](auto sc) { gload(sc, decltype(sc)::value); });
     for (int kt0 = 0; kt0 < nk; kt0 += D) {
@@ -126,11 +134,12 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
             __builtin_amdgcn_sched_barrier(0);
             const unsigned keep = kt < nk ? 0xFFFFFFFFu : 0u;     // steps past the end contribute zeros (no branch)
 #pragma unroll
-            for (int i = 0; i < ST; ++i) {
+            for (int i = 0; i < ST; ++i) *reinterpret_cast<u32x4*>(&sA[buf][srow + RPT * i][sk]) = ra[j][i] & keep;
+#pragma unroll
+            for (int i = 0; i < STB; ++i) {
                 Frag8 fw;
                 fw.v4 = rb[j][i];
                 bf16x8_to_f16x8(fw);
-                *reinterpret_cast<u32x4*>(&sA[buf][srow + RPT * i][sk]) = ra[j][i] & keep;
                 *reinterpret_cast<u32x4*>(&sB[buf][srow + RPT * i][sk]) = fw.v4;
             }
             // One barrier per step: a wave may run one step ahead (into the other buffer); it cannot
@@ -139,16 +148,17 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
             __syncthreads();
 #pragma unroll
             for (int kk = 0; kk < GM_BK / 16; ++kk) {
-                Frag8 fa[2], fb[2];
+                Frag8 fa[2], fb[NJ];
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
+                for (int i = 0; i < 2; ++i)
                     fa[i].v4 = *reinterpret_cast<const u32x4*>(&sA[buf][wm * 64 + i * 32 + lr][kk * 16 + lg * 8]);
-                    fb[i].v4 = *reinterpret_cast<const u32x4*>(&sB[buf][wn * 64 + i * 32 + lr][kk * 16 + lg * 8]);
-                }
+#pragma unroll
+                for (int i = 0; i < NJ; ++i)
+                    fb[i].v4 = *reinterpret_cast<const u32x4*>(&sB[buf][wn * WN + i * 32 + lr][kk * 16 + lg * 8]);
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
-                    for (int jj = 0; jj < 2; ++jj) acc[i][jj] = mfma_32x32x16(fa[i], fb[jj], acc[i][jj]);
+                    for (int jj = 0; jj < NJ; ++jj) acc[i][jj] = mfma_32x32x16(fa[i], fb[jj], acc[i][jj]);
             }
         });
     }
@@ -162,13 +172,13 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
             if (EPI == GEPI_SWIGLU) {
                 const int feat = tn * 64 + wn * 32 + lr;
                 if (feat < a.N) {
-                    const float gt = acc[i][0][e], up = acc[i][1][e];
+                    const float gt = acc[i][0][e], up = acc[i][NJ - 1][e];
                     a.outh[(size_t)row * a.N + feat] = f32_to_f16(gt / (1.f + __expf(-gt)) * up);
                 }
             } else {
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int col = tn * GM_BN + wn * 64 + j * 32 + lr;
+                for (int j = 0; j < NJ; ++j) {
+                    const int col = tn * BN + wn * WN + j * 32 + lr;
                     if (col < a.N) {
                         float* p = a.outf + (size_t)row * a.N + col;
                         if (EPI == GEPI_RESID) *p += acc[i][j][e];

@@ -155,12 +155,24 @@ template <int EPI>
 static int launch_gemm(const GemmArgs& a0, hipStream_t stream) {
     GemmArgs a = a0;
     if (a.M > kSkinnyMaxRows) {
-        GemmTileArgs t{a.W, a.X, a.M, a.N, a.Kd, (a.M + GM_BM - 1) / GM_BM,
-                       EPI == EPI_SWIGLU ? (a.N + 63) / 64 : (a.N + GM_BN - 1) / GM_BN, a.outf, a.outh};
+        constexpr int GE = EPI == EPI_F32 ? GEPI_F32 : (EPI == EPI_RESID ? GEPI_RESID : GEPI_SWIGLU);
+        const int tiles_m = (a.M + GM_BM - 1) / GM_BM;
+        int ncu = 0;
+        LASER_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, 0));
+        // narrow outputs: 128-column tiles would leave compute units without work; 64-column tiles double the count
+        const bool narrow = EPI != EPI_SWIGLU && (long)tiles_m * ((a.N + 127) / 128) * 4 < (long)ncu * 5;
+        const int bn = narrow ? 64 : 128;
+        GemmTileArgs t{a.W, a.X, a.M, a.N, a.Kd, tiles_m, EPI == EPI_SWIGLU ? (a.N + 63) / 64 : (a.N + bn - 1) / bn, a.outf, a.outh};
         const int total = t.tiles_m * t.tiles_n;
         dim3 grid((unsigned)(((total + 7) / 8) * 8));
-        constexpr int GE = EPI == EPI_F32 ? GEPI_F32 : (EPI == EPI_RESID ? GEPI_RESID : GEPI_SWIGLU);
-        hipLaunchKernelGGL((gemm_mfma_kernel<GE>), grid, dim3(256), 0, stream, t);
+        if constexpr (EPI != EPI_SWIGLU) {
+            if (narrow) {
+                hipLaunchKernelGGL((gemm_mfma_kernel<GE, 64>), grid, dim3(256), 0, stream, t);
+                LASER_HIP_CHECK(hipGetLastError());
+                return LASER_OK;
+            }
+        }
+        hipLaunchKernelGGL((gemm_mfma_kernel<GE, 128>), grid, dim3(256), 0, stream, t);
         LASER_HIP_CHECK(hipGetLastError());
         return LASER_OK;
     }
