@@ -9,14 +9,21 @@
 // the number of partial-list entries ordered before it; if a chunk hides an entry that precedes the
 // draft, that chunk already contributes >= LASER_MAX_TOPK >= k listed ones, so "rank < k" is exact.
 // The block then scans the rows left to right and emits accepted drafts plus the correction token.
+//
+// Many rows (M > 80): streaming the head matrix once per 64 rows would read it M/64 times. Instead the
+// logits go through the LDS-tiled matrix-core GEMM into an fp32 workspace (written and read once:
+// 8 bytes per logit against the 2 * d flops it costs), head_stats_kernel reduces each row (max, sum of
+// exp, arg-max, the draft's logit and its exact rank) and decides it, head_scan_kernel scans the rows.
 #include <cmath>
 
+#include "gemm_mfma.h"
 #include "gemm_skinny.h"
 #include "state.h"
 
 namespace laser {
 
 constexpr int KT = LASER_MAX_TOPK;
+constexpr int kHeadStreamMaxRows = 80;   // beyond this the head matrix goes through the tiled GEMM
 
 struct HeadArgs {
     const uint16_t* W; const uint16_t* H; int M, V, d, tiles_per_wave, chunks;
@@ -214,12 +221,111 @@ __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
     }
 }
 
+// One workgroup per row of the logits matrix: softmax statistics, arg-max (smaller id on ties), the
+// draft's logit, the number of vocabulary entries ordered before the draft, and the row's decision.
+struct StatsArgs {
+    const float* logits; const int32_t* row_x; int V, topk, mode; float p;
+    int32_t* row_ok; int32_t* row_arg;
+};
+
+__global__ __launch_bounds__(256) void head_stats_kernel(StatsArgs a) {
+    __shared__ float s_f[4][2];
+    __shared__ int s_i[4][2];
+    const int row = blockIdx.x;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const float* l = a.logits + (size_t)row * a.V;
+    const int x = a.row_x[row];
+    const float lx = x >= 0 ? l[x] : -INFINITY;
+    float mx = -INFINITY, sum = 0.f;
+    int arg = 0x7FFFFFFF, ahead = 0;
+    for (int n = threadIdx.x * 4; n < a.V; n += 256 * 4) {          // V is a multiple of 16
+        const float4 v = *reinterpret_cast<const float4*>(l + n);
+        const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (e[i] > mx) { sum = sum * __expf(mx - e[i]) + 1.f; mx = e[i]; arg = n + i; }   // ids ascend per thread
+            else sum += __expf(e[i] - mx);
+            ahead += (n + i != x && before(e[i], n + i, lx, x)) ? 1 : 0;
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const float omx = __shfl_xor(mx, off), osum = __shfl_xor(sum, off);
+        const int oarg = __shfl_xor(arg, off);
+        ahead += __shfl_xor(ahead, off);
+        const float M = fmaxf(mx, omx);
+        if (M != -INFINITY) sum = sum * __expf(mx - M) + osum * __expf(omx - M);
+        if (before(omx, oarg, mx, arg)) arg = oarg;
+        mx = M;
+    }
+    if (lane == 0) { s_f[wave][0] = mx; s_f[wave][1] = sum; s_i[wave][0] = arg; s_i[wave][1] = ahead; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float M = -INFINITY, S = 0.f; int A = 0x7FFFFFFF, rank = 0;
+        for (int w = 0; w < 4; ++w) {
+            const float wm = s_f[w][0];
+            const float nm = fmaxf(M, wm);
+            if (nm != -INFINITY) S = S * __expf(M - nm) + s_f[w][1] * __expf(wm - nm);
+            if (before(wm, s_i[w][0], M, A)) A = s_i[w][0];
+            M = nm;
+            rank += s_i[w][1];
+        }
+        bool ok = false;
+        if (x >= 0) {
+            const float q = __expf(lx - M) / S;
+            const bool in_k = rank < a.topk, above = q > a.p, top1 = rank == 0;
+            ok = a.mode == LASER_MODE_RV ? (in_k && above)
+               : a.mode == LASER_MODE_RV_OR_TOP1 ? (top1 || (in_k && above))
+               : a.mode == LASER_MODE_TOPK_ONLY ? in_k : (top1 || above);
+        }
+        a.row_ok[row] = ok ? 1 : 0;
+        a.row_arg[row] = A;
+    }
+}
+
+// One thread per sequence: longest accepted prefix, then the correction token (Sec. 2.1).
+__global__ void head_scan_kernel(const int32_t* row_ok, const int32_t* row_arg, const int32_t* drafts,
+                                 const int32_t* draft_len, int B, int K, int32_t* accept_len, int32_t* out_tokens) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x, R = K + 1;
+    if (b >= B) return;
+    int dl = draft_len[b];
+    dl = dl < 0 ? 0 : (dl > K ? K : dl);
+    int n = 0;
+    while (n < dl && row_ok[b * R + n]) ++n;
+    accept_len[b] = n;
+    int32_t* out = out_tokens + (size_t)b * R;
+    for (int j = 0; j < R; ++j) out[j] = j < n ? drafts[(size_t)b * K + j] : (j == n ? row_arg[b * R + n] : -1);
+}
+
 int run_head(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len, int B, int K,
              int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, float* logits_dbg,
              hipStream_t stream) {
     const int R = K + 1, M = B * R;
     hipLaunchKernelGGL(head_rows_kernel, dim3((M + 255) / 256), dim3(256), 0, stream, drafts, draft_len, B, K,
                        m->d.vocab, m->row_x, m->hp_lx);
+    if (M > kHeadStreamMaxRows) {
+        float* logits = logits_dbg;
+        if (!logits) {                                   // workspace for max_rows x vocab logits, on first use
+            if (!m->logits_ws) {
+                const size_t bytes = (size_t)m->d.max_rows * m->d.vocab * sizeof(float);
+                hipError_t e = hipMalloc((void**)&m->logits_ws, bytes);
+                LASER_REQUIRE(e == hipSuccess, LASER_E_HIP, "hipMalloc of the %zu-byte logits workspace failed: %s", bytes,
+                              hipGetErrorString(e));
+            }
+            logits = m->logits_ws;
+        }
+        const int tiles_m = (M + GM_BM - 1) / GM_BM, tiles_n = (m->d.vocab + 127) / 128;
+        GemmTileArgs t{m->d.wlm, h, M, m->d.vocab, m->d.d_model, tiles_m, tiles_n, logits, nullptr};
+        hipLaunchKernelGGL((gemm_mfma_kernel<GEPI_F32, 128>), dim3((unsigned)(((tiles_m * tiles_n + 7) / 8) * 8)), dim3(256), 0,
+                           stream, t);
+        int32_t* row_ok = m->hp_arg;                     // per-row scratch: the streaming path's buffers are free here
+        int32_t* row_arg = m->hp_arg + M;
+        StatsArgs sa{logits, m->row_x, m->d.vocab, topk, mode, p, row_ok, row_arg};
+        hipLaunchKernelGGL(head_stats_kernel, dim3(M), dim3(256), 0, stream, sa);
+        hipLaunchKernelGGL(head_scan_kernel, dim3((B + 63) / 64), dim3(64), 0, stream, row_ok, row_arg, drafts, draft_len,
+                           B, K, accept_len, out_tokens);
+        LASER_HIP_CHECK(hipGetLastError());
+        return LASER_OK;
+    }
     const int ntiles = m->d.vocab / 16;
     const int tpw = (ntiles + 1023) / 1024;
     HeadArgs a{m->d.wlm, h, M, m->d.vocab, m->d.d_model, tpw, m->head_chunks, m->row_x,

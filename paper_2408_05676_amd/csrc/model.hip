@@ -439,7 +439,7 @@ extern "C" int laser_model_destroy(laser_model* h) {
     if (!h) return LASER_OK;
     Model* m = reinterpret_cast<Model*>(h);
     void* ptrs[] = {m->x, m->xn, m->qkv, m->q, m->attn, m->act, m->row_pos, m->att_part, m->rope, m->hp_max,
-                    m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx, m->row_x};
+                    m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx, m->row_x, m->logits_ws};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     for (hipEvent_t e : m->prof_ev) (void)hipEventDestroy(e);
     fused_free(m);

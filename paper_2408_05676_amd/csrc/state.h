@@ -61,6 +61,7 @@ struct Model {
     int32_t* hp_topi = nullptr;
     float* hp_lx = nullptr;      // [max_rows]
     int32_t* row_x = nullptr;    // [max_rows] draft token of the row or -1
+    float* logits_ws = nullptr;  // [max_rows][vocab] fp32, allocated at the first many-row head call
     // optional timing of the dominant kernel (laser_profile_begin / laser_profile_end)
     std::vector<hipEvent_t> prof_ev;   // start/stop pairs
     int prof_cap = 0, prof_n = 0;
