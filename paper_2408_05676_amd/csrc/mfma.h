@@ -25,7 +25,8 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));   // native 16-byte vector (arrays of it stay in registers)
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));   // native 16-byte vector (arrays of it stay in registers)
 
 union Frag8 {            // 8 x 16-bit = 16 bytes (fp16 for MFMA operands; raw bf16 right after a weight load)
     uint4 u;
@@ -37,6 +38,7 @@ union Frag8 {            // 8 x 16-bit = 16 bytes (fp16 for MFMA operands; raw b
 };
 union Frag4 {            // 4 x fp16 = 8 bytes
     uint2 u;
+    u32x2 v2;
     half4_t v;
     uint16_t h[4];
 };

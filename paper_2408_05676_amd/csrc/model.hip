@@ -271,17 +271,28 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     for (int c = 0; c < NC16; ++c) acc[c] = float4_t{0.f, 0.f, 0.f, 0.f};
     const int32_t* bt = a.block_table + (size_t)slot * a.mpps;
 
-    for (int p = p0 + wave; p < p1; p += 4) {
+    // Pages p0 + wave, + 4, ..: the K and V fragments of the next page are requested before the current
+    // one is multiplied (unconditionally: past the wave's last page the current page is requested again,
+    // a cache hit), so a wave always has one page in flight.
+    auto load_page = [&](int p, Frag8 (&ak)[NC32], Frag4 (&bv)[NC16]) {
         const int pg = bt[p];
         const size_t base = (((size_t)a.layer * a.n_pages + pg) * a.H + h) * kPageSize * DH;
         const uint16_t* kp = a.kpages + base + (size_t)r * DH + g * 8;
+#pragma unroll
+        for (int c = 0; c < NC32; ++c) ak[c].v4 = *reinterpret_cast<const u32x4*>(kp + c * 32);
+        const uint16_t* vp = a.vpages + base + (size_t)r * kPageSize + 4 * g;
+#pragma unroll
+        for (int c = 0; c < NC16; ++c) bv[c].v2 = *reinterpret_cast<const u32x2*>(vp + (size_t)c * 16 * kPageSize);
+    };
+    Frag8 ak[NC32], akn[NC32];
+    Frag4 bv[NC16], bvn[NC16];
+    int p = p0 + wave;
+    if (p < p1) load_page(p, ak, bv);
+    for (; p < p1; p += 4) {
+        load_page(p + 4 < p1 ? p + 4 : p, akn, bvn);
         float4_t s = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int c = 0; c < NC32; ++c) {
-            Frag8 ak;
-            ak.u = *reinterpret_cast<const uint4*>(kp + c * 32);
-            s = mfma_16x16x32(ak, bq[c], s);            // s[i] = K[tok 4g+i] . Q[row r]
-        }
+        for (int c = 0; c < NC32; ++c) s = mfma_16x16x32(ak[c], bq[c], s);      // s[i] = K[tok 4g+i] . Q[row r]
         float sv[4], mx = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -309,15 +320,16 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         float al[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) al[i] = __shfl(alpha, 4 * g + i);     // accumulator rows are q = 4g+i
-        const uint16_t* vp = a.vpages + base + (size_t)r * kPageSize + 4 * g;
 #pragma unroll
         for (int c = 0; c < NC16; ++c) {
-            Frag4 bv;
-            bv.u = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * kPageSize);
 #pragma unroll
             for (int i = 0; i < 4; ++i) acc[c][i] *= al[i];
-            acc[c] = mfma_16x16x16(pa, bv, acc[c]);     // acc[c][i] = O[q 4g+i][channel 16c + r]
+            acc[c] = mfma_16x16x16(pa, bv[c], acc[c]);  // acc[c][i] = O[q 4g+i][channel 16c + r]
         }
+#pragma unroll
+        for (int c = 0; c < NC32; ++c) ak[c] = akn[c];
+#pragma unroll
+        for (int c = 0; c < NC16; ++c) bv[c] = bvn[c];
     }
     // ---- merge the four waves ----
     if (g == 0) { sm_m[wave][r] = m_run; sm_l[wave][r] = l_run; }
