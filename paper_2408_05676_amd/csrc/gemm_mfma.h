@@ -112,6 +112,9 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+    // a wave whose 64 rows all lie past M (ragged last m-tile) stages and synchronises but multiplies nothing
+    const bool dead = __builtin_amdgcn_readfirstlane(tm * GM_BM + wm * 64) >= a.M;
+
     // Register ring of D k-steps. The element type must be a native vector: an array of HIP's uint4
     // (a struct) that is only copied as a whole is not promoted to registers and lands in scratch.
     u32x4 ra[D][ST], rb[D][STB];
@@ -146,6 +149,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
             // overwrite this buffer before every wave has passed the next step's barrier, i.e. has
             // finished reading it.
             __syncthreads();
+            if (!dead)
 #pragma unroll
             for (int kk = 0; kk < GM_BK / 16; ++kk) {
                 Frag8 fa[2], fb[NJ];
