@@ -164,8 +164,12 @@ int laser_kv_read_lens(laser_kv* kv, const int32_t* seq_ids /*[host] B*/, int B,
 /* laser_verify_step (Eq. 3 / Eq. 6 forward, Eq. 4 / 7 / 8 acceptance, correction rule of Sec. 2.1).
  * For sequence b, rows r = 0..K hold the tokens [pending[b], drafts[b][0..K-1]] at positions
  * len+r; their keys/values go to cache slots len..len+K; row r attends to slots 0..len+r. The
- * output head and the acceptance rule are fused: logits are not materialised unless logits_dbg is
- * given. Drafts j >= draft_len[b] are padding (fed as token 0, never accepted).
+ * output head and the acceptance rule are fused: with up to 80 rows (B*(K+1)) logits are never
+ * stored unless logits_dbg is given; with more rows they pass once through an fp32 workspace of
+ * max_rows * vocab floats that the model handle allocates at the first such call (that call
+ * synchronises; LASER_E_HIP if the allocation fails). With B*(K+1) <= 16 the whole step is one
+ * persistent cooperative kernel (see laser_model_set_option). Drafts j >= draft_len[b] are padding
+ * (fed as token 0, never accepted).
  *   seq_ids    [host] int32[B]      KV slots, all different
  *   pending    [dev]  int32[B]      last emitted token of each sequence (not yet in the cache)
  *   drafts     [dev]  int32[B][K]
