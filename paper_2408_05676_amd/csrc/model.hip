@@ -60,11 +60,39 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
                                                       int d, float eps, uint16_t* __restrict__ xn) {
     __shared__ float sm[4];
     const size_t m = blockIdx.x;
+    // the row stays in registers between the two passes (up to 8192 columns; d is a multiple of 128)
+    constexpr int NV = 8;
+    const int n4 = d / 4;
+    const float4* xr = reinterpret_cast<const float4*>(x + m * d);
+    float4 v[NV];
     float ss = 0.f;
-    for (int i = threadIdx.x; i < d; i += 256) { float v = x[m * d + i]; ss += v * v; }
+#pragma unroll
+    for (int c = 0; c < NV; ++c) {
+        const int i = c * 256 + threadIdx.x;
+        v[c] = xr[i < n4 ? i : 0];
+        if (i < n4) ss += v[c].x * v[c].x + v[c].y * v[c].y + v[c].z * v[c].z + v[c].w * v[c].w;
+    }
+    for (int i = NV * 256 + threadIdx.x; i < n4; i += 256) {
+        const float4 t = xr[i];
+        ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+    }
     ss = block_sum_256(ss, sm);
     const float rs = rsqrtf(ss / (float)d + eps);
-    for (int i = threadIdx.x; i < d; i += 256) xn[m * d + i] = f32_to_f16(x[m * d + i] * rs * gain[i]);
+    const float4* g4 = reinterpret_cast<const float4*>(gain);
+    uint2* out = reinterpret_cast<uint2*>(xn + m * d);
+    auto emit = [&](int i, const float4& t) {
+        const float4 g = g4[i];
+        Frag4 o;
+        o.h[0] = f32_to_f16(t.x * rs * g.x); o.h[1] = f32_to_f16(t.y * rs * g.y);
+        o.h[2] = f32_to_f16(t.z * rs * g.z); o.h[3] = f32_to_f16(t.w * rs * g.w);
+        out[i] = o.u;
+    };
+#pragma unroll
+    for (int c = 0; c < NV; ++c) {
+        const int i = c * 256 + threadIdx.x;
+        if (i < n4) emit(i, v[c]);
+    }
+    for (int i = NV * 256 + threadIdx.x; i < n4; i += 256) emit(i, xr[i]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -207,21 +235,39 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a) {
     const int m = blockIdx.x, b = m / a.R;
     const int pos = a.row_pos[m];
     const int pg = a.block_table[(size_t)a.seq_ids[b] * a.mpps + pos / kPageSize], tp = pos % kPageSize;
-    const int half = a.dh / 2;
+    const int half = a.dh / 2;                            // a multiple of 4 (dh is 64 or 128)
     const float* row = a.qkv + (size_t)m * 3 * a.d;
-    for (int idx = threadIdx.x; idx < a.d / 2; idx += 256) {
+    // a thread takes 4 consecutive rotary pairs (i .. i+3, partners at + half) of one head: 16-byte loads, 8-byte stores
+    for (int idx = threadIdx.x * 4; idx < a.d / 2; idx += 256 * 4) {
         const int h = idx / half, i = idx % half;
-        const float2 cs = a.rope[(size_t)pos * half + i];
         const int c0 = h * a.dh + i, c1 = c0 + half;
-        const float qa = row[c0], qb = row[c1];
-        a.q[(size_t)m * a.d + c0] = f32_to_f16(qa * cs.x - qb * cs.y);
-        a.q[(size_t)m * a.d + c1] = f32_to_f16(qa * cs.y + qb * cs.x);
-        const float ka = row[a.d + c0], kb = row[a.d + c1];
+        const float4 csa = *reinterpret_cast<const float4*>(a.rope + (size_t)pos * half + i);       // (cos, sin) x 2
+        const float4 csb = *reinterpret_cast<const float4*>(a.rope + (size_t)pos * half + i + 2);
+        const float4 qa = *reinterpret_cast<const float4*>(row + c0), qb = *reinterpret_cast<const float4*>(row + c1);
+        const float4 ka = *reinterpret_cast<const float4*>(row + a.d + c0), kb = *reinterpret_cast<const float4*>(row + a.d + c1);
+        const float4 va = *reinterpret_cast<const float4*>(row + 2 * a.d + c0), vb = *reinterpret_cast<const float4*>(row + 2 * a.d + c1);
+        const float co[4] = {csa.x, csa.z, csb.x, csb.z}, si[4] = {csa.y, csa.w, csb.y, csb.w};
+        const float q0[4] = {qa.x, qa.y, qa.z, qa.w}, q1[4] = {qb.x, qb.y, qb.z, qb.w};
+        const float k0[4] = {ka.x, ka.y, ka.z, ka.w}, k1[4] = {kb.x, kb.y, kb.z, kb.w};
+        const float v0[4] = {va.x, va.y, va.z, va.w}, v1[4] = {vb.x, vb.y, vb.z, vb.w};
+        Frag4 oq0, oq1, ok0, ok1;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            oq0.h[j] = f32_to_f16(q0[j] * co[j] - q1[j] * si[j]);
+            oq1.h[j] = f32_to_f16(q0[j] * si[j] + q1[j] * co[j]);
+            ok0.h[j] = f32_to_f16(k0[j] * co[j] - k1[j] * si[j]);
+            ok1.h[j] = f32_to_f16(k0[j] * si[j] + k1[j] * co[j]);
+        }
+        *reinterpret_cast<uint2*>(a.q + (size_t)m * a.d + c0) = oq0.u;
+        *reinterpret_cast<uint2*>(a.q + (size_t)m * a.d + c1) = oq1.u;
         const size_t base = (((size_t)a.layer * a.n_pages + pg) * a.H + h) * kPageSize * a.dh;
-        a.kpages[base + (size_t)tp * a.dh + i] = f32_to_f16(ka * cs.x - kb * cs.y);
-        a.kpages[base + (size_t)tp * a.dh + i + half] = f32_to_f16(ka * cs.y + kb * cs.x);
-        a.vpages[base + (size_t)i * kPageSize + tp] = f32_to_f16(row[2 * a.d + c0]);
-        a.vpages[base + (size_t)(i + half) * kPageSize + tp] = f32_to_f16(row[2 * a.d + c1]);
+        *reinterpret_cast<uint2*>(a.kpages + base + (size_t)tp * a.dh + i) = ok0.u;
+        *reinterpret_cast<uint2*>(a.kpages + base + (size_t)tp * a.dh + i + half) = ok1.u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            a.vpages[base + (size_t)(i + j) * kPageSize + tp] = f32_to_f16(v0[j]);
+            a.vpages[base + (size_t)(i + j + half) * kPageSize + tp] = f32_to_f16(v1[j]);
+        }
     }
 }
 
