@@ -126,41 +126,17 @@ def cpu_baseline(sh, wl, tokens_per_step, n_sample_layers=4):
     }
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c3", choices=sorted(WORKLOADS))
-    ap.add_argument("--regime", default="rv", choices=["rv", "strict", "floor"],
-                    help="rv: k=2 p=0.1 (Eq. 8) on a sharpened head; strict: greedy (Eq. 4); floor: no pool replay")
-    ap.add_argument("--lm-gain", type=float, default=None)
-    ap.add_argument("--replay-noise", type=float, default=None,
-                    help="substitution rate of the replayed copy of the model's own continuation that is added to the "
-                         "pool (default: the rate that puts the accepted length per step into the band the paper reports)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="also launch one plain 1 GiB device copy before the timed region (a kernel of known "
-                         "traffic against which hardware byte counters are scaled)")
-    ap.add_argument("--path", default="auto", choices=["auto", "fused", "generic"],
-                    help="few-row workloads can run the verify step as one persistent kernel (fused) or as the "
-                         "general multi-kernel path; auto times a few steps of each and keeps the faster")
-    ap.add_argument("--no-fused", action="store_true", help="same as --path generic")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (the path needs no collectives; see DESIGN.md on sharding). "
-              "--gpus N with N > 1 is not supported.", file=sys.stderr)
-        sys.exit(2)
-
+def run_workload(args, name, steps, warmup, weights_cache):
+    """Builds the engine for workload `name`, times `steps` steps and returns (result dict, shape, workload, tokens/step)."""
     import torch
     import synth
     from synth.model import torch_gen_weight
     import paper_2408_05676_amd as laser
     from paper_2408_05676_amd.harness import Engine, stacked_weights
 
-    wl = WORKLOADS[args.workload]
-    steps = args.steps if args.steps is not None else wl["steps"]
-    warmup = args.warmup if args.warmup is not None else wl["warmup"]
+    wl = WORKLOADS[name]
+    steps = steps if steps is not None else wl["steps"]
+    warmup = warmup if warmup is not None else wl["warmup"]
     B, K, ctx_len, n_max = wl["B"], wl["K"], wl["ctx"], wl["n_max"]
     R = K + 1
     topk, p, mode = (1, -1.0, 0) if args.regime == "strict" else (2, 0.1, 0)
@@ -170,7 +146,11 @@ def main():
     torch.cuda.set_device(0)
 
     t_setup = time.perf_counter()
-    weights = stacked_weights(lambda n, l: torch_gen_weight(sh, n, l, dev), sh, dev)
+    wkey = (wl["shape"], gain)
+    if wkey not in weights_cache:
+        weights_cache.clear()
+        weights_cache[wkey] = stacked_weights(lambda n, l: torch_gen_weight(sh, n, l, dev), sh, dev)
+    weights = weights_cache[wkey]
     n_gen = (steps + warmup) * R + 16                       # tokens the replayed continuation must cover
     max_len = ctx_len + 2 * n_gen + R + 32
     eng = Engine(sh, weights, B, K, max_len, n_max)
@@ -193,7 +173,7 @@ def main():
     path_ms = {}
     if path == "auto":
         rollback()
-        for name, flag in (("fused", 1), ("generic", 0)):
+        for pname, flag in (("fused", 1), ("generic", 0)):
             eng.model.set_option("fused", flag)
             eng.step(topk, p, mode)
             torch.cuda.synchronize()
@@ -201,7 +181,7 @@ def main():
             for _ in range(4):
                 eng.step(topk, p, mode)
             torch.cuda.synchronize()
-            path_ms[name] = (time.perf_counter() - t0) * 1e3 / 4
+            path_ms[pname] = (time.perf_counter() - t0) * 1e3 / 4
             rollback()
         path = min(path_ms, key=path_ms.get)
     eng.model.set_option("fused", 1 if path == "fused" else 0)
@@ -280,7 +260,7 @@ def main():
         peak, unit, achieved = MFMA_F16_PEAK_TFLOPS, "TFLOP/s", (dom_work / dom_avg_s / 1e12 if dom_n else 0.0)
         work_key = "flops_per_launch"
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}_{path}.json")
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{name}_{path}.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f).get("bytes_per_launch")
@@ -301,7 +281,45 @@ def main():
     }
     eng.close()
     pool.close()
-    del weights
+    return out, sh, wl, tokens_per_step
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="c3", choices=sorted(WORKLOADS))
+    ap.add_argument("--regime", default="rv", choices=["rv", "strict", "floor"],
+                    help="rv: k=2 p=0.1 (Eq. 8) on a sharpened head; strict: greedy (Eq. 4); floor: no pool replay")
+    ap.add_argument("--lm-gain", type=float, default=None)
+    ap.add_argument("--replay-noise", type=float, default=None,
+                    help="substitution rate of the replayed copy of the model's own continuation that is added to the "
+                         "pool (default: the rate that puts the accepted length per step into the band the paper reports)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch one plain 1 GiB device copy before the timed region (a kernel of known "
+                         "traffic against which hardware byte counters are scaled)")
+    ap.add_argument("--path", default="auto", choices=["auto", "fused", "generic"],
+                    help="few-row workloads can run the verify step as one persistent kernel (fused) or as the "
+                         "general multi-kernel path; auto times a few steps of each and keeps the faster")
+    ap.add_argument("--no-fused", action="store_true", help="same as --path generic")
+    ap.add_argument("--no-throughput", action="store_true",
+                    help="with the default (batch 1) workload, skip the batch-64 workload that is otherwise measured as well")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the path needs no collectives; see DESIGN.md on sharding). "
+              "--gpus N with N > 1 is not supported.", file=sys.stderr)
+        sys.exit(2)
+
+    weights_cache = {}
+    out, sh, wl, tokens_per_step = run_workload(args, args.workload, args.steps, args.warmup, weights_cache)
+    if args.workload == "c3" and not args.no_throughput:
+        # the metric names batch 1 AND batch 64 of the 7B shape: the batch-64 workload runs right after, on the same
+        # weights, and is reported inside the same line (`value` stays the batch-1 workload's)
+        o4, _, _, _ = run_workload(args, "c4", None, None, weights_cache)
+        out["throughput_workload"] = {k: o4[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "config", "roofline")}
+    weights_cache.clear()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(sh, wl, tokens_per_step)
     print(json.dumps(out))
