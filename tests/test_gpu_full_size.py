@@ -166,6 +166,53 @@ def test_head_stress_shape_sampled_against_the_oracle():
     ora = {"accept_len": oa, "out_tokens": oo, "stats": stats, "argmax_gap": gaps, "logits": logits}
     flips, bad = gu.classify_step(a[S], o[S], ora, d_np[S], dl_np[S], k, p)
     assert not bad, bad
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        laser.verify_head(model, h, drafts, dl, k, p, 0, out=(acc, out))
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 5
+    print(f"[head 128k] {ms:.2f} ms per launch = {2.0 * B * R * sh.d * sh.vocab / ms / 1e9:.0f} TFLOP/s")
     print(f"[head 128k] 4096 rows; sampled sequences: worst logit error {ratio:.3f} of bound, flips {flips}, "
           f"accepted lengths {a[S].tolist()} (oracle {list(map(int, oa))}), mean accepted {a.mean():.2f}")
     model.close()
+
+
+def test_retrieval_stress_shape_full_size():
+    """Draft retrieval at the stress shape: 100 M pool tokens in 1 M keyed sub-pools (lognormal lengths),
+    4096 concurrent contexts, suffix length 1..4, K = 16. The regrouped token array and all 4096 results
+    are compared with the oracle bit for bit (its lookups only touch the contexts' own sub-pools)."""
+    import paper_2408_05676_amd as laser
+    from oracle.retrieval import RegroupedPool, retrieve
+    spec = synth.POOLS["stress"]
+    assert spec.n_seq == 1_000_000
+    pool = synth.gen_pool(spec)
+    B, n_max, K = 4096, 4, 16
+    ctx = synth.gen_contexts(spec, B, 8, n_max, salt=5)
+    tails = np.ascontiguousarray(ctx["ctx"][:, -n_max:]).astype(np.int32)
+    P = laser.Pool(pool["tokens"], pool["seq_off"], pool["seq_key"], n_max)
+    ora = RegroupedPool(pool["tokens"], pool["seq_off"], pool["seq_key"])
+    info = P.info()
+    assert info["n_tokens"] == ora.P.size == pool["tokens"].size and info["n_keys"] == len(ora.key_range)
+    for start in (0, ora.P.size // 2, ora.P.size - 4096):              # sampled windows of the regrouped array
+        assert (P.read_tokens(start, 4096) == ora.P[start:start + 4096]).all()
+    g = laser.retrieve_drafts(P, torch.tensor(ctx["keys"].astype(np.int64), device="cuda"), torch.tensor(tails, device="cuda"),
+                              1, n_max, K, 1)
+    torch.cuda.synchronize()
+    d, dl, mn, pi = (t.cpu().numpy() for t in g)
+    od, odl, omn, opi = retrieve(ora, ctx["keys"], tails, 1, n_max, K, 1)
+    assert (dl == odl).all() and (mn == omn).all() and (pi == opi).all() and (d == od).all()
+    hit = dl > 0
+    for b in np.nonzero(hit)[0][:512]:                                 # the chain literally occurs in the pool
+        assert (ora.P[pi[b] + 1:pi[b] + 1 + dl[b]] == d[b, :dl[b]]).all()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    kd, td = torch.tensor(ctx["keys"].astype(np.int64), device="cuda"), torch.tensor(tails, device="cuda")
+    e0.record()
+    for _ in range(20):
+        laser.retrieve_drafts(P, kd, td, 1, n_max, K, 1, out=g)
+    e1.record()
+    torch.cuda.synchronize()
+    print(f"[retrieval stress] {ora.P.size} tokens, {len(ora.key_range)} keys, {int(hit.sum())} of {B} contexts matched, "
+          f"mean draft length {dl[hit].mean():.2f}; {e0.elapsed_time(e1) * 1e3 / 20:.1f} us per batch of {B} lookups")
+    P.close()
