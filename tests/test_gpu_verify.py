@@ -230,3 +230,15 @@ def test_7b_throughput_launch_shape_sampled():
     tiled matrix-core GEMMs, paged cache) with two layers; the oracle follows three of the 64 sequences."""
     sh = synth.SHAPES["7b"].with_(n_layers=2)
     _run_steps(sh, B=64, ctx_len=36, K=10, n_steps=1, k=2, p=0.0, seed=22, sample=[0, 29, 63], fused=0)
+
+
+@pytest.mark.parametrize("fused", [1, 0])
+def test_persistent_kernel_edge_shapes(fused):
+    """Row counts and contexts at the edges of the few-row path: one row (M = 1), exactly 16 rows over two
+    sequences, ragged draft lengths, a context of more than 8 splits (2200 tokens: the split merge works in
+    groups of 8), and a context that ends exactly on a page boundary."""
+    sh = synth.SHAPES["tiny128"].with_(lm_gain=4.0)
+    _run_steps(sh, B=1, ctx_len=33, K=0, n_steps=3, k=1, p=-1.0, seed=31, fused=fused)                  # M = 1
+    _run_steps(sh, B=2, ctx_len=49, K=7, n_steps=3, k=2, p=0.05, seed=32, ragged=True, fused=fused)     # M = 16
+    _run_steps(sh, B=1, ctx_len=2200, K=8, n_steps=2, k=2, p=0.05, seed=33, fused=fused)                # 9+ splits
+    _run_steps(sh, B=3, ctx_len=17, K=4, n_steps=4, k=2, p=0.05, seed=34, fused=fused)                  # len = 16: page edge
