@@ -1,0 +1,81 @@
+"""GPU parity of the whole decoding loop on the Tiny configuration (2 layers, d 256, 4 heads, FFN 1024,
+vocabulary 2048; B = 2, context 64, K = 4; pool of 500 x 64 tokens from 20 templates, 10 % substitutions,
+suffix length 1..3): laser_retrieve_drafts -> laser_verify_step -> laser_kv_commit -> laser_ctx_advance,
+several steps in a row, against oracle.step.laser_step. Drafts, pool positions, accepted lengths and emitted
+tokens must be identical step by step (a step whose deciding margin lies inside the logit tolerance may
+differ: it is counted and ends the comparison, since the two texts have then diverged)."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import retrieval, step
+from oracle.decoder import Decoder
+from synth.model import torch_gen_weight
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("fused", [1, 0])
+@pytest.mark.parametrize("k,p", [(1, -1.0), (2, 0.004)])
+def test_tiny_configuration_full_loop(fused, k, p):
+    import paper_2408_05676_amd as laser
+    from paper_2408_05676_amd.harness import Engine, stacked_weights
+    sh = synth.SHAPES["tiny"].with_(lm_gain=4.0)
+    B, K, ctx_len, n_max, n_steps = 2, 4, 64, 3, 10
+    spec = synth.POOLS["tiny"]
+    pool_data = synth.gen_pool(spec)
+    ctx = synth.gen_contexts(spec, B, ctx_len, n_max, salt=2, min_remaining=K)
+    cap = ctx_len + (K + 1) * (n_steps + 2) + 16
+
+    dec = Decoder(sh.n_layers, sh.d, sh.n_heads, sh.ffn, sh.vocab, synth.gen_all_weights(sh), sh.eps, sh.rope_base)
+    # the pool also holds a noisy copy of the oracle's own greedy continuation of each context (what the paper's
+    # pools are: earlier outputs of the same model), so that multi-token chunks get accepted
+    toks, off, keys = pool_data["tokens"], pool_data["seq_off"], pool_data["seq_key"]
+    extra = []
+    for b in range(B):
+        probe = step.Sequence(dec, int(ctx["keys"][b]), ctx["ctx"][b], cap)
+        cont = step.autoregressive_greedy(dec, probe, (K + 1) * n_steps)
+        text = np.concatenate([ctx["ctx"][b, -n_max:], np.asarray(cont)]).astype(np.int32)
+        noisy = synth.noisy_copy(spec.with_(sub_rate=0.06), text, salt=b)
+        noisy[:n_max] = text[:n_max]
+        extra.append(noisy)
+    toks = np.concatenate([toks] + extra)
+    off = np.concatenate([off, off[-1] + np.cumsum([len(e) for e in extra])]).astype(np.int64)
+    keys = np.concatenate([keys, ctx["keys"]]).astype(np.int64)
+
+    opool = retrieval.RegroupedPool(toks, off, keys)
+    seqs = [step.Sequence(dec, int(ctx["keys"][b]), ctx["ctx"][b], cap) for b in range(B)]
+
+    weights = stacked_weights(lambda n, l: torch_gen_weight(sh, n, l, "cuda"), sh)
+    eng = Engine(sh, weights, B, K, cap, n_max)
+    eng.model.set_option("fused", fused)
+    eng.prefill(ctx["ctx"])
+    pool = laser.Pool(toks, off, keys, n_max)
+    eng.set_pool(pool, ctx["keys"])
+
+    emitted, flips = 0, 0
+    for it in range(n_steps):
+        eng.step(k, p)
+        torch.cuda.synchronize()
+        ora = step.laser_step(dec, opool, seqs, 1, n_max, K, k, p, 0, return_logits=True)
+        d, dl = eng.drafts.cpu().numpy(), eng.draft_len.cpu().numpy()
+        assert (dl == ora["draft_len"]).all() and (d == ora["drafts"]).all(), it
+        assert (eng.match_n.cpu().numpy() == ora["match_n"]).all() and (eng.pool_index.cpu().numpy() == ora["pool_index"]).all(), it
+        acc, out = eng.accept_len.cpu().numpy(), eng.out_tokens.cpu().numpy()
+        f, bad = gu.classify_step(acc, out, ora, ora["drafts"], ora["draft_len"], k, p)
+        assert not bad, (it, bad)
+        flips += f
+        if f:
+            break
+        emitted += int(acc.sum()) + B
+        assert eng.kv.read_lens(eng.seq_ids).tolist() == [s.cache.length for s in seqs]
+        assert eng.pending.cpu().tolist() == [s.pending for s in seqs]
+        tails = [([-1] * n_max + list(s.tokens))[-n_max:] for s in seqs]
+        assert eng.ctx_tail.cpu().tolist() == tails
+    print(f"[tiny loop fused={fused} k={k} p={p}] {it + 1} steps, {emitted} tokens emitted "
+          f"({emitted / max(1, (it + 1) * B):.2f} per step and sequence), in-tolerance flips {flips}")
+    assert emitted > (it + 1) * B or flips, "no draft was ever accepted: the replayed continuation is not being found"
+    eng.close()
+    pool.close()
