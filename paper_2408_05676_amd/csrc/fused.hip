@@ -46,21 +46,28 @@ struct FusedArgs {
     int L, d, H, dh, F, V;
     float eps;
     const float2* rope;
-    uint16_t *kpages, *vpages;
+    uint16_t *kpages, *klpages, *vpages;
     const int32_t *block_table, *lens;
     int mpps, n_pages;
     const int32_t *seq_ids, *pending, *drafts, *draft_len;
     int B, K, R, M;
     // exchange buffers (write-once per launch)
     float* xbuf;        // [2L+1][16][d]
-    uint16_t* xgbuf;    // [2L+1][16][d]
+    uint16_t* xgbuf;    // [2L+1][16][d]   high plane of x * gain
+    uint8_t* xglbuf;    // [2L+1][16][d]   8-bit low plane: x * gain = xgbuf + xglbuf / 4096 (split operands, see mfma.h)
     float* ssbuf;       // [2L+1][nwg][16]
-    uint16_t *qbuf, *knew, *vnew, *attn;   // [L][16][d]
+    uint16_t *qbuf, *knew, *attn;          // [L][16][d]
+    uint16_t* vnew;     // [L][16][H][dh][16]  new values in the cache's page layout (channel-major): entry
+                        // (b * npp + i) holds the new rows of sequence b that fall into its i-th page from len / 16
+                        // on (npp = 1 if R == 1, else 2; B * npp <= 16 because B * R <= 16)
+    uint16_t *qlbuf, *knewl;               // [L][16][d]      fp16 low planes of queries and new keys
+    uint8_t* attnl;                        // [L][16][d]      8-bit low plane of the attention output
     uint16_t* act;      // [L][16][F]
     float* apart;       // [L][B*H][nsplit][32 + 16*dh]
     int* acount;        // [L][B*H]   (self-resetting)
     int nsplit;
-    int xs_steps;       // reduction steps (of 128) whose activations fit the LDS staging area
+    int xs_steps;       // reduction steps (of 128) whose activations fit the LDS staging area, single plane
+    int xs_steps2;      // the same for split activations (fp16 high plane + 8-bit low plane)
     // head
     float *hp_max, *hp_sum; int32_t* hp_arg; float* hp_topv; int32_t* hp_topi; float* hp_lx;
     int topk, mode; float p;
@@ -78,6 +85,9 @@ __device__ inline void st_u32(void* p, uint32_t v) {
 }
 __device__ inline void st_f32(float* p, float v) { st_u32(p, __float_as_uint(v)); }
 __device__ inline void st_i32(int* p, int v) { st_u32(p, (uint32_t)v); }
+__device__ inline void st_u16(void* p, uint16_t v) {
+    __hip_atomic_store(reinterpret_cast<uint16_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ inline uint32_t pack_h2(float a, float b) { return (uint32_t)f32_to_f16(a) | ((uint32_t)f32_to_f16(b) << 16); }
 
 constexpr int MAX_UNITS = 6;         // 16-row weight tiles one wave slot can accumulate per phase
@@ -162,6 +172,7 @@ enum { PH_QKV = 0, PH_O = 1, PH_GU = 2, PH_DOWN = 3, PH_HEAD = 4 };
 struct Phase {
     const uint16_t* W;    // matrix of this layer
     int kind, Kd;
+    int planes;           // planes of its activations: 2 = split (fp16 high + 8-bit low), 1 = single fp16
 };
 
 __device__ inline int count_mine(int n, int first, int stride) { return first < n ? (n - 1 - first) / stride + 1 : 0; }
@@ -209,9 +220,12 @@ __device__ inline void load_w(Frag8 (&f)[4], const uint16_t* p) {
 
 // The reduction dimension is processed in chunks whose activations fit the LDS staging area
 // (xs_steps steps of 128 elements for the launch's row count); chunk c of a Kd-long reduction:
-__device__ inline int n_chunks(const FusedArgs& a, int Kd) { return (Kd / 128 + a.xs_steps - 1) / a.xs_steps; }
-__device__ inline void chunk_range(const FusedArgs& a, int Kd, int c, int& cs0, int& cs1) {
-    const int steps = Kd / 128, nch = n_chunks(a, Kd);
+__device__ inline int n_chunks(const FusedArgs& a, const Phase& ph) {
+    const int xs = ph.planes == 2 ? a.xs_steps2 : a.xs_steps;
+    return (ph.Kd / 128 + xs - 1) / xs;
+}
+__device__ inline void chunk_range(const FusedArgs& a, const Phase& ph, int c, int& cs0, int& cs1) {
+    const int steps = ph.Kd / 128, nch = n_chunks(a, ph);
     cs0 = steps * c / nch;
     cs1 = steps * (c + 1) / nch;
 }
@@ -225,7 +239,7 @@ __device__ inline WaveWork wave_work(const FusedArgs& a, const Phase& ph, int ch
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     WaveWork w;
     int cs1;
-    chunk_range(a, ph.Kd, chunk, w.cs0, cs1);
+    chunk_range(a, ph, chunk, w.cs0, cs1);
     w.ncs = cs1 - w.cs0;
     if (ph.kind == PH_HEAD) { w.ks0 = w.cs0; w.nks = w.ncs; }
     else {
@@ -285,13 +299,17 @@ __device__ inline void prefetch_first(const FusedArgs& a, const Phase& ph, int c
     }
 }
 
-// Copy rows 0..M-1, steps cs0 .. cs0+ncs-1 of the fp16 activations X[16][Kd] into LDS
-// (row stride ncs*256 + 16 bytes: the 16-byte operand reads of 16 rows then fall into distinct banks).
-__device__ inline void stage_x(const FusedArgs& a, uint4* xs, const uint16_t* X, int Kd, int cs0, int ncs) {
+// Copy rows 0..M-1, steps cs0 .. cs0+ncs-1 of the fp16 activations X[16][Kd] into LDS and, for split
+// activations, of their 8-bit low plane Xlo[16][Kd] right behind them in the same LDS row: a row is
+// ncs*256 bytes (+ ncs*128 bytes) + 16 bytes of padding, so that the 16-byte operand reads of 16 rows
+// fall into distinct banks.
+__device__ inline void stage_x(const FusedArgs& a, uint4* xs, const uint16_t* X, const uint8_t* Xlo, int Kd, int cs0, int ncs) {
     constexpr int Q = 16;                       // 16-byte pieces per thread and pass: one pass covers 16 rows x 32 steps
-    const int per_row = ncs * 16, total = a.M * per_row, stride = per_row + 1, ld = Kd / 8;
+    const int hi_row = ncs * 16, per_row = Xlo ? hi_row + ncs * 8 : hi_row;
+    const int total = a.M * per_row, stride = per_row + 1;
     const uint32_t inv = 0xFFFFFFFFu / (uint32_t)per_row + 1u;     // i / per_row == umulhi(i, inv) for i * per_row < 2^32
     const uint4* src = reinterpret_cast<const uint4*>(X) + cs0 * 16;
+    const uint4* src_lo = reinterpret_cast<const uint4*>(Xlo ? (const void*)Xlo : (const void*)X) + cs0 * 8;
     for (int i0 = threadIdx.x; i0 < total; i0 += FT * Q) {
         uint4 v[Q];
         int dst[Q];
@@ -302,7 +320,9 @@ __device__ inline void stage_x(const FusedArgs& a, uint4* xs, const uint16_t* X,
             const int i = i0 + q * FT, ic = min(i, total - 1);
             const int row = (int)__umulhi((uint32_t)ic, inv), c = ic - row * per_row;
             dst[q] = i < total ? row * stride + c : -1;
-            v[q] = src[(size_t)row * ld + c];
+            const bool low = c >= hi_row;
+            const uint4* p = low ? src_lo + (size_t)row * (Kd / 16) + (c - hi_row) : src + (size_t)row * (Kd / 8) + c;
+            v[q] = *p;
         }
 #pragma unroll
         for (int q = 0; q < Q; ++q)
@@ -312,7 +332,7 @@ __device__ inline void stage_x(const FusedArgs& a, uint4* xs, const uint16_t* X,
 
 // Streams one chunk: this wave's units x steps, partial sums of finished units to sh.red
 // (stored on the first chunk, accumulated on later ones; slot = unit * NA + stream).
-template <int NA>
+template <int NA, bool SPLIT>
 __device__ inline void stream_chunk(const FusedArgs& a, Shared& sh, const uint4* xs, const Phase& ph,
                                     const WaveWork& w, bool first, Ring& R) {
     constexpr int DS = RingCfg<NA>::DS;
@@ -361,25 +381,38 @@ __device__ inline void stream_chunk(const FusedArgs& a, Shared& sh, const uint4*
             }
         }
         // this lane's activation operand: row r (padding rows read row 0; their results are dropped)
-        const uint4* xl = xs + (r < a.M ? r : 0) * (w.ncs * 16 + 1) + (w.ks0 - w.cs0) * 16 + g * 4;
-        float4_t acc[NA];
+        const uint4* xrow = xs + (r < a.M ? r : 0) * (w.ncs * (SPLIT ? 24 : 16) + 1);
+        const uint4* xl = xrow + (w.ks0 - w.cs0) * 16 + g * 4;
+        const uint4* xlo = xrow + w.ncs * 16 + (w.ks0 - w.cs0) * 8 + g * 2;    // 8-bit low plane behind the high plane
+        float4_t acc[NA], acl[NA];
 #pragma unroll
-        for (int s = 0; s < NA; ++s) acc[s] = float4_t{0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < NA; ++s) { acc[s] = float4_t{0.f, 0.f, 0.f, 0.f}; acl[s] = float4_t{0.f, 0.f, 0.f, 0.f}; }
         int k = 0, junit = 0;
         for (int t0 = 0; t0 < w.T; t0 += DS) {
 #pragma unroll
             for (int j = 0; j < DS; ++j) {
                 request((j + DS - 1) % DS);                   // unconditional: step t0 + j + DS - 1, clamped
                 if (t0 + j < w.T) {                           // no vector-memory instructions inside this branch
-                    Frag8 Bf[4];
+                    Frag8 Bf[4], Bl[4];
 #pragma unroll
                     for (int c = 0; c < 4; ++c) Bf[c].u = xl[k * 16 + c];
+                    if constexpr (SPLIT) {
+                        const uint4 l0 = xlo[k * 8], l1 = xlo[k * 8 + 1];
+                        b8x8_to_f16x8(l0.x, l0.y, Bl[0]);
+                        b8x8_to_f16x8(l0.z, l0.w, Bl[1]);
+                        b8x8_to_f16x8(l1.x, l1.y, Bl[2]);
+                        b8x8_to_f16x8(l1.z, l1.w, Bl[3]);
+                    }
 #pragma unroll
                     for (int s = 0; s < NA; ++s) {
 #pragma unroll
                         for (int c = 0; c < 4; ++c) bf16x8_to_f16x8(A[j * NA + s][c]);
 #pragma unroll
                         for (int c = 0; c < 4; ++c) acc[s] = mfma_16x16x32(A[j * NA + s][c], Bf[c], acc[s]);
+                        if constexpr (SPLIT) {
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) acl[s] = mfma_16x16x32(A[j * NA + s][c], Bl[c], acl[s]);
+                        }
                     }
                     if (++k == w.nks) {
 #pragma unroll
@@ -387,10 +420,11 @@ __device__ inline void stream_chunk(const FusedArgs& a, Shared& sh, const uint4*
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
                                 float* slot = &sh.red[junit * NA + s][wave][i][lane];
-                                *slot = first ? acc[s][i] : *slot + acc[s][i];
+                                const float t = SPLIT ? acc[s][i] + acl[s][i] * kLoInv : acc[s][i];
+                                *slot = first ? t : *slot + t;
                             }
 #pragma unroll
-                        for (int s = 0; s < NA; ++s) acc[s] = float4_t{0.f, 0.f, 0.f, 0.f};
+                        for (int s = 0; s < NA; ++s) { acc[s] = float4_t{0.f, 0.f, 0.f, 0.f}; acl[s] = float4_t{0.f, 0.f, 0.f, 0.f}; }
                         k = 0;
                         ++junit;
                     }
@@ -408,18 +442,19 @@ __device__ inline void stream_chunk(const FusedArgs& a, Shared& sh, const uint4*
 // Streams a whole phase: for every chunk stage its activations, stream, and issue the next chunk's
 // first weights before the staging barrier. On return sh.red holds every unit's partial sums and
 // all waves have passed a workgroup barrier.
-template <int NA, bool TR>
+template <int NA, bool SPLIT, bool TR>
 __device__ inline void stream_phase(const FusedArgs& a, Shared& sh, uint4* xs, const Phase& ph,
-                                    const uint16_t* __restrict__ X, Ring& R, int trace_layer = -1, int trace_slot = 0) {
-    const int nch = n_chunks(a, ph.Kd);
+                                    const uint16_t* __restrict__ X, const uint8_t* __restrict__ Xlo, Ring& R,
+                                    int trace_layer = -1, int trace_slot = 0) {
+    const int nch = n_chunks(a, ph);
     for (int c = 0; c < nch; ++c) {
         const WaveWork w = wave_work(a, ph, c);
         if (c > 0) __syncthreads();                     // every wave has finished reading the previous chunk
         if (c == 0) stamp_fine<TR>(a, trace_layer, trace_slot + 2);
-        stage_x(a, xs, X, ph.Kd, w.cs0, w.ncs);
+        stage_x(a, xs, X, SPLIT ? Xlo : nullptr, ph.Kd, w.cs0, w.ncs);
         __syncthreads();
         if (c == 0) stamp_fine<TR>(a, trace_layer, trace_slot);
-        stream_chunk<NA>(a, sh, xs, ph, w, c == 0, R);
+        stream_chunk<NA, SPLIT>(a, sh, xs, ph, w, c == 0, R);
         if (c + 1 < nch) prefetch_first<NA>(a, ph, c + 1, R);
     }
     __syncthreads();
@@ -500,9 +535,12 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
     const float scale = rsqrtf((float)DH);
     const size_t lo = (size_t)layer * 16 * a.d;
     const uint16_t* qb = a.qbuf + lo;
+    const uint16_t* qlb = a.qlbuf + lo;
     const uint16_t* kn = a.knew + lo;
-    const uint16_t* vn = a.vnew + lo;
+    const uint16_t* knl = a.knewl + lo;
+    const uint16_t* vn = a.vnew + lo * kPageSize;
     uint16_t* ob = a.attn + lo;
+    uint8_t* obl = a.attnl + lo;
     const int PSZ = 32 + 16 * DH;
 
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
@@ -524,27 +562,41 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
         if (wave < AW) {
             const int pbase = (split * AW + wave) * PPW;
             if (pbase < n_pages) {
-                Frag8 bq[NC32];
+                Frag8 bq[NC32], bql[NC32];
                 {
                     const int qr = min(r, a.R - 1);
-                    const uint16_t* qp = qb + (size_t)(b * a.R + qr) * a.d + (size_t)h * DH + g * 8;
+                    const size_t qo = (size_t)(b * a.R + qr) * a.d + (size_t)h * DH + g * 8;
 #pragma unroll
-                    for (int c = 0; c < NC32; ++c) bq[c].u = *reinterpret_cast<const uint4*>(qp + c * 32);
+                    for (int c = 0; c < NC32; ++c) bq[c].u = *reinterpret_cast<const uint4*>(qb + qo + c * 32);
+#pragma unroll
+                    for (int c = 0; c < NC32; ++c) bql[c].u = *reinterpret_cast<const uint4*>(qlb + qo + c * 32);
                 }
-                Frag8 ak[PPW][NC32];
-                Frag4 bv[PPW][NC16];
-                // First the cache loads of all pages of this wave, unconditionally (a page index past the end
-                // is clamped, and a page that holds new rows is patched below), so that they share one round trip.
+                Frag8 ak[PPW][NC32], akl[PPW][NC32];
+                Frag4 bv[PPW][NC16], nv[PPW][NC16];
+                const int npp = a.R == 1 ? 1 : 2, pg0 = len / kPageSize;
+                // All loads of this wave's pages first, unconditionally (a page index past the end is clamped), so
+                // that they share one round trip. A key slot at or past len is a NEW row: its lane reads the
+                // exchange buffer instead of the cache page (pointer select, same registers). New values come
+                // from the page-shaped exchange buffer and are merged token by token below.
 #pragma unroll
                 for (int pp = 0; pp < PPW; ++pp) {
                     const int p = min(pbase + pp, n_pages - 1);
                     const size_t base = (((size_t)layer * a.n_pages + bt[p]) * a.H + h) * kPageSize * DH;
-                    const uint16_t* kp = a.kpages + base + (size_t)r * DH + g * 8;
+                    const int ks = p * kPageSize + r;                   // this lane's key slot
+                    const size_t ko = (size_t)(b * a.R + min(max(ks - len, 0), a.R - 1)) * a.d + (size_t)h * DH + g * 8;
+                    const uint16_t* kp = ks >= len ? kn + ko : a.kpages + base + (size_t)r * DH + g * 8;
+                    const uint16_t* klp = ks >= len ? knl + ko : a.klpages + base + (size_t)r * DH + g * 8;
 #pragma unroll
                     for (int c = 0; c < NC32; ++c) ak[pp][c].u = *reinterpret_cast<const uint4*>(kp + c * 32);
+#pragma unroll
+                    for (int c = 0; c < NC32; ++c) akl[pp][c].u = *reinterpret_cast<const uint4*>(klp + c * 32);
                     const uint16_t* vp = a.vpages + base + (size_t)r * kPageSize + 4 * g;
 #pragma unroll
                     for (int c = 0; c < NC16; ++c) bv[pp][c].u = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * kPageSize);
+                    const int pi = min(max(p - pg0, 0), npp - 1);
+                    const uint16_t* nvp = vn + ((size_t)(b * npp + pi) * a.H + h) * kPageSize * DH + (size_t)r * kPageSize + 4 * g;
+#pragma unroll
+                    for (int c = 0; c < NC16; ++c) nv[pp][c].u = *reinterpret_cast<const uint2*>(nvp + (size_t)c * 16 * kPageSize);
                 }
 #pragma unroll
                 for (int pp = 0; pp < PPW; ++pp) {
@@ -552,33 +604,19 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
                     if (p >= n_pages) continue;
                     if (s0 + kPageSize > len) {                         // the page holds new rows
                         const size_t base = (((size_t)layer * a.n_pages + bt[p]) * a.H + h) * kPageSize * DH;
-                        const int ks = s0 + r;                            // this lane's key slot
-                        const bool k_new = ks >= len;
-                        const int kr = min(max(ks - len, 0), a.R - 1);
-                        {   // new rows: unconditional loads (clamped row), then select, so that they share a round trip
-                            const uint16_t* kp = kn + (size_t)(b * a.R + kr) * a.d + (size_t)h * DH + g * 8;
-                            Frag8 nk[NC32];
-                            uint16_t nv[4][NC16];
+                        const int ks = s0 + r;
 #pragma unroll
-                            for (int c = 0; c < NC32; ++c) nk[c].u = *reinterpret_cast<const uint4*>(kp + c * 32);
+                        for (int j = 0; j < 4; ++j)
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                const int vr = min(max(s0 + 4 * g + j - len, 0), a.R - 1);
-#pragma unroll
-                                for (int c = 0; c < NC16; ++c) nv[j][c] = vn[(size_t)(b * a.R + vr) * a.d + (size_t)h * DH + c * 16 + r];
-                            }
-#pragma unroll
-                            for (int c = 0; c < NC32; ++c) if (k_new) ak[pp][c].u = nk[c].u;
-#pragma unroll
-                            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                                for (int c = 0; c < NC16; ++c) if (s0 + 4 * g + j >= len) bv[pp][c].h[j] = nv[j][c];
-                        }
+                            for (int c = 0; c < NC16; ++c) if (s0 + 4 * g + j >= len) bv[pp][c].h[j] = nv[pp][c].h[j];
                         // this wave owns the page: store its new rows into the cache for later steps
-                        if (k_new && ks < len + a.R) {
+                        if (ks >= len && ks < len + a.R) {
                             uint16_t* kd = a.kpages + base + (size_t)r * DH + g * 8;
+                            uint16_t* kld = a.klpages + base + (size_t)r * DH + g * 8;
 #pragma unroll
                             for (int c = 0; c < NC32; ++c) *reinterpret_cast<uint4*>(kd + c * 32) = ak[pp][c].u;
+#pragma unroll
+                            for (int c = 0; c < NC32; ++c) *reinterpret_cast<uint4*>(kld + c * 32) = akl[pp][c].u;
                         }
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
@@ -590,9 +628,16 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
                             }
                         }
                     }
-                    float4_t s = float4_t{0.f, 0.f, 0.f, 0.f};
+                    // both operands split: hi.hi + 2^-12 (hi.lo + lo.hi), in the order the general path uses
+                    float4_t s = float4_t{0.f, 0.f, 0.f, 0.f}, sl = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int c = 0; c < NC32; ++c) s = mfma_16x16x32(ak[pp][c], bq[c], s);
+#pragma unroll
+                    for (int c = 0; c < NC32; ++c) sl = mfma_16x16x32(ak[pp][c], bql[c], sl);
+#pragma unroll
+                    for (int c = 0; c < NC32; ++c) sl = mfma_16x16x32(akl[pp][c], bq[c], sl);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) s[i] += sl[i] * kLoInv;
                     float sv[4], mx = -INFINITY;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
@@ -653,8 +698,14 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
                 }
             }
             if (S == 1) {
-                if (q < a.R) st_u32(ob + (size_t)(b * a.R + q) * a.d + (size_t)h * DH + c,
-                                    pack_h2(Lq > 0.f ? O0 / Lq : 0.f, Lq > 0.f ? O1 / Lq : 0.f));
+                if (q < a.R) {
+                    uint32_t hi;
+                    uint16_t lw;
+                    split_pack_h2_b8(Lq > 0.f ? O0 / Lq : 0.f, Lq > 0.f ? O1 / Lq : 0.f, hi, lw);
+                    const size_t o = (size_t)(b * a.R + q) * a.d + (size_t)h * DH + c;
+                    st_u32(ob + o, hi);
+                    st_u16(obl + o, lw);
+                }
             } else {
                 if (c == 0) { st_f32(part + q, M); st_f32(part + 16 + q, Lq); }
                 st_f32(part + 32 + q * DH + c, O0);
@@ -702,9 +753,14 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
                         }
                         M = Mn;
                     }
-                    if (q < a.R)
-                        st_u32(ob + (size_t)(b * a.R + q) * a.d + (size_t)h * DH + c,
-                               pack_h2(Lq > 0.f ? O0 / Lq : 0.f, Lq > 0.f ? O1 / Lq : 0.f));
+                    if (q < a.R) {
+                        uint32_t hi;
+                        uint16_t lw;
+                        split_pack_h2_b8(Lq > 0.f ? O0 / Lq : 0.f, Lq > 0.f ? O1 / Lq : 0.f, hi, lw);
+                        const size_t o = (size_t)(b * a.R + q) * a.d + (size_t)h * DH + c;
+                        st_u32(ob + o, hi);
+                        st_u16(obl + o, lw);
+                    }
                 }
             }
         }
@@ -917,7 +973,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
     Ring ring;
     ring.primed = 0;
     uint4* xs = reinterpret_cast<uint4*>(smem_raw + XS_OFFSET);
-    const Phase p_head{a.wlm, PH_HEAD, a.d};
+    const Phase p_head{a.wlm, PH_HEAD, a.d, 1};
 
     // ---- phase 0: embedding, x0, x0*g1[0], sum of squares ----
     {
@@ -937,7 +993,11 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
                 }
                 const size_t o = (size_t)row * a.d + tile * 16 + f0;
                 st_f32(a.xbuf + o, v0); st_f32(a.xbuf + o + 1, v1);
-                st_u32(a.xgbuf + o, pack_h2(v0 * gain0[tile * 16 + f0], v1 * gain0[tile * 16 + f0 + 1]));
+                uint32_t hi;
+                uint16_t lw;
+                split_pack_h2_b8(v0 * gain0[tile * 16 + f0], v1 * gain0[tile * 16 + f0 + 1], hi, lw);
+                st_u32(a.xgbuf + o, hi);
+                st_u16(a.xglbuf + o, lw);
                 ss += v0 * v0 + v1 * v1;
             }
         }
@@ -950,7 +1010,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         // The barrier that ends the previous layer (or the embedding) opens the loop body, so that the
         // weights issued ahead during it are never carried around the loop's back edge.
         {
-            const Phase p_q{a.wqkv + (size_t)l * 3 * a.d * a.d, PH_QKV, a.d};
+            const Phase p_q{a.wqkv + (size_t)l * 3 * a.d * a.d, PH_QKV, a.d, 2};
             stamp<TR>(a, ns);
             if (!grid_sync(a, sh, epoch, [&] { prefetch_first<1>(a, p_q, 0, ring); })) return;
             stamp<TR>(a, ns);
@@ -961,22 +1021,25 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         const uint16_t* xg_in = a.xgbuf + (size_t)(2 * l) * XS;
         uint16_t* xg_mid = a.xgbuf + (size_t)(2 * l + 1) * XS;
         uint16_t* xg_out = a.xgbuf + (size_t)(2 * l + 2) * XS;
+        const uint8_t* xgl_in = a.xglbuf + (size_t)(2 * l) * XS;
+        uint8_t* xgl_mid = a.xglbuf + (size_t)(2 * l + 1) * XS;
+        uint8_t* xgl_out = a.xglbuf + (size_t)(2 * l + 2) * XS;
         const float* ss_in = a.ssbuf + (size_t)(2 * l) * nwg * 16;
         float* ss_mid = a.ssbuf + (size_t)(2 * l + 1) * nwg * 16;
         float* ss_out = a.ssbuf + (size_t)(2 * l + 2) * nwg * 16;
         const size_t lo = (size_t)l * XS;
 
-        const Phase p_qkv{a.wqkv + (size_t)l * 3 * a.d * a.d, PH_QKV, a.d};
-        const Phase p_o{a.wo + (size_t)l * a.d * a.d, PH_O, a.d};
-        const Phase p_gu{a.wgu + (size_t)l * 2 * a.F * a.d, PH_GU, a.d};
-        const Phase p_dn{a.wdown + (size_t)l * a.d * a.F, PH_DOWN, a.F};
+        const Phase p_qkv{a.wqkv + (size_t)l * 3 * a.d * a.d, PH_QKV, a.d, 2};
+        const Phase p_o{a.wo + (size_t)l * a.d * a.d, PH_O, a.d, 2};
+        const Phase p_gu{a.wgu + (size_t)l * 2 * a.F * a.d, PH_GU, a.d, 2};
+        const Phase p_dn{a.wdown + (size_t)l * a.d * a.F, PH_DOWN, a.F, 1};
         const int w = blockIdx.x;
 
         // ---- QKV + RoPE ----
         {
             float ssv[8];
             ss_issue(ss_in, ssv);
-            stream_phase<1, TR>(a, sh, xs, p_qkv, xg_in, ring, l, 0);
+            stream_phase<1, true, TR>(a, sh, xs, p_qkv, xg_in, xgl_in, ring, l, 0);
             ss_finish(a, sh, ssv);
             const int per = a.d / 32, pph = DH / 32, half = DH / 2;
             const int cnt = count_mine(a.d / 16, w, nwg);
@@ -998,12 +1061,25 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
                         o0[q] = x0 * cs.x - x1 * cs.y;
                         o1[q] = x0 * cs.y + x1 * cs.x;
                     }
+                    // queries and keys are published split (fp16 high and low planes)
                     uint16_t* dst = (grp == 0 ? a.qbuf : a.knew) + lo + (size_t)row * a.d;
-                    st_u32(dst + c0, pack_h2(o0[0], o0[1]));
-                    st_u32(dst + c0 + half, pack_h2(o1[0], o1[1]));
+                    uint16_t* dstl = (grp == 0 ? a.qlbuf : a.knewl) + lo + (size_t)row * a.d;
+                    uint32_t hi, lw;
+                    split_pack_h2(o0[0], o0[1], hi, lw);
+                    st_u32(dst + c0, hi); st_u32(dstl + c0, lw);
+                    split_pack_h2(o1[0], o1[1], hi, lw);
+                    st_u32(dst + c0 + half, hi); st_u32(dstl + c0 + half, lw);
                 } else {
                     const int idx = w + (u - 2 * cnt) * nwg;
-                    st_u32(a.vnew + lo + (size_t)row * a.d + idx * 16 + f0, pack_h2(v[0][0] * rs, v[0][1] * rs));
+                    // values go into the page-shaped exchange buffer at the row's slot of its page
+                    const int bb = sh.row_b[row], pos = sh.row_pos[row], npp = a.R == 1 ? 1 : 2;
+                    const int pi = row < a.M ? pos / kPageSize - sh.seq_len[bb] / kPageSize : 0;
+                    const int ch = idx * 16 + f0;                          // channel (head * dh + c) of v[0][0]
+                    uint16_t* dst = a.vnew + lo * kPageSize + ((size_t)(bb * npp + pi) * a.d + ch) * kPageSize + pos % kPageSize;
+                    if (row < a.M) {                                       // padding rows have no slot
+                        st_u16(dst, f32_to_f16(v[0][0] * rs));
+                        st_u16(dst + kPageSize, f32_to_f16(v[0][1] * rs));
+                    }
                 }
             });
         }
@@ -1021,13 +1097,17 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         {
             float ss = 0.f;
             const float* g2 = a.g2 + (size_t)l * a.d;
-            stream_phase<1, TR>(a, sh, xs, p_o, a.attn + lo, ring, l, 3);
+            stream_phase<1, true, TR>(a, sh, xs, p_o, a.attn + lo, a.attnl + lo, ring, l, 3);
             reduce_epilogue<1>(a, sh, n_units(a, PH_O), [&](int u, int row, int f0, float (&v)[1][2]) {
                 const int item = w + u * nwg;
                 const size_t o = (size_t)row * a.d + item * 16 + f0;
                 const float n0 = x_in[o] + v[0][0], n1 = x_in[o + 1] + v[0][1];
                 st_f32(x_mid + o, n0); st_f32(x_mid + o + 1, n1);
-                st_u32(xg_mid + o, pack_h2(n0 * g2[item * 16 + f0], n1 * g2[item * 16 + f0 + 1]));
+                uint32_t hi;
+                uint16_t lw;
+                split_pack_h2_b8(n0 * g2[item * 16 + f0], n1 * g2[item * 16 + f0 + 1], hi, lw);
+                st_u32(xg_mid + o, hi);
+                st_u16(xgl_mid + o, lw);
                 ss += n0 * n0 + n1 * n1;
             });
             publish_ss(sh, ss_mid + (size_t)blockIdx.x * 16, ss);
@@ -1040,7 +1120,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         {
             float ssv[8];
             ss_issue(ss_mid, ssv);
-            stream_phase<2, TR>(a, sh, xs, p_gu, xg_mid, ring, l, 6);
+            stream_phase<2, true, TR>(a, sh, xs, p_gu, xg_mid, xgl_mid, ring, l, 6);
             ss_finish(a, sh, ssv);
             uint16_t* act = a.act + (size_t)l * 16 * a.F;
             reduce_epilogue<2>(a, sh, n_units(a, PH_GU), [&](int u, int row, int f0, float (&v)[2][2]) {
@@ -1064,13 +1144,17 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
             float ss = 0.f;
             const bool last = l + 1 == a.L;
             const float* gn = last ? a.gf : a.g1 + (size_t)(l + 1) * a.d;
-            stream_phase<1, TR>(a, sh, xs, p_dn, a.act + (size_t)l * 16 * a.F, ring, l, 9);
+            stream_phase<1, false, TR>(a, sh, xs, p_dn, a.act + (size_t)l * 16 * a.F, nullptr, ring, l, 9);
             reduce_epilogue<1>(a, sh, n_units(a, PH_DOWN), [&](int u, int row, int f0, float (&v)[1][2]) {
                 const int item = w + u * nwg;
                 const size_t o = (size_t)row * a.d + item * 16 + f0;
                 const float n0 = x_mid[o] + v[0][0], n1 = x_mid[o + 1] + v[0][1];
                 st_f32(x_out + o, n0); st_f32(x_out + o + 1, n1);
-                st_u32(xg_out + o, pack_h2(n0 * gn[item * 16 + f0], n1 * gn[item * 16 + f0 + 1]));
+                uint32_t hi;
+                uint16_t lw;
+                split_pack_h2_b8(n0 * gn[item * 16 + f0], n1 * gn[item * 16 + f0 + 1], hi, lw);
+                st_u32(xg_out + o, hi);
+                st_u16(xgl_out + o, lw);
                 ss += n0 * n0 + n1 * n1;
             });
             publish_ss(sh, ss_out + (size_t)blockIdx.x * 16, ss);
@@ -1085,7 +1169,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
     {
         float ssv[8];
         ss_issue(a.ssbuf + (size_t)(2 * a.L) * nwg * 16, ssv);
-        stream_phase<1, TR>(a, sh, xs, p_head, a.xgbuf + (size_t)(2 * a.L) * XS, ring);
+        stream_phase<1, false, TR>(a, sh, xs, p_head, a.xgbuf + (size_t)(2 * a.L) * XS, nullptr, ring);
         ss_finish(a, sh, ssv);
         head_epilogue(a, sh, xs, chunks);
     }
@@ -1115,7 +1199,8 @@ struct FusedWS {
     size_t bytes = 0;
     unsigned long long* bar = nullptr;     // [0] count, [32] flag (separate 128-byte lines), abort at [64]
     int L = 0, d = 0, F = 0, nwg = 0, bh_cap = 0, dh = 0;
-    float* xbuf; uint16_t* xgbuf; float* ssbuf; uint16_t *qbuf, *knew, *vnew, *attn, *act; float* apart; int* acount;
+    float* xbuf; uint16_t* xgbuf; uint8_t* xglbuf; float* ssbuf; uint16_t *qbuf, *knew, *vnew, *attn, *act;
+    uint16_t *qlbuf, *knewl; uint8_t* attnl; float* apart; int* acount;
     float *hp_max, *hp_sum; int32_t* hp_arg; float* hp_topv; int32_t* hp_topi; float* hp_lx;
     unsigned long long epoch = 0;
     long long* trace = nullptr;
@@ -1132,7 +1217,7 @@ bool fused_supported(const Model* m, int B, int K) {
            (m->dh == 64 || m->dh == 128) && nwg <= 256 &&
            3 * per(d.d_model / 16, nwg) <= MAX_UNITS && 2 * per(d.ffn / 16, nwg) <= MAX_UNITS &&
            per(d.vocab / 16, nwg * FWAVES) <= MAX_UNITS &&
-           g_lds_max >= (int)sizeof(Shared) && (size_t)g_lds_max >= XS_OFFSET + 16384 && ((size_t)g_lds_max - XS_OFFSET) / M >= 272;
+           g_lds_max >= (int)sizeof(Shared) && (size_t)g_lds_max >= XS_OFFSET + 16384 && ((size_t)g_lds_max - XS_OFFSET) / M >= 400;
 }
 
 void fused_free(Model* m) {
@@ -1158,7 +1243,8 @@ static int fused_prepare(Model* m, int B, hipStream_t stream, FusedWS** out) {
         size_t off = 0;
         auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
         const size_t o_x = take((2 * L + 1) * XS * 4), o_xg = take((2 * L + 1) * XS * 2), o_ss = take((2 * L + 1) * nwg * 16 * 4);
-        const size_t o_q = take(L * XS * 2), o_k = take(L * XS * 2), o_v = take(L * XS * 2), o_a = take(L * XS * 2);
+        const size_t o_q = take(L * XS * 2), o_k = take(L * XS * 2), o_v = take(L * XS * kPageSize * 2), o_a = take(L * XS * 2);
+        const size_t o_xgl = take((2 * L + 1) * XS), o_ql = take(L * XS * 2), o_kl = take(L * XS * 2), o_al = take(L * XS);
         const size_t o_act = take(L * 16 * (size_t)d.ffn * 2), o_ap = take(L * bh_cap * PSZ * 4), o_ac = take(L * bh_cap * 4);
         const size_t o_hm = take(16 * CH * 4), o_hs = take(16 * CH * 4), o_ha = take(16 * CH * 4);
         const size_t o_tv = take(16 * CH * KTOP * 4), o_ti = take(16 * CH * KTOP * 4), o_lx = take(16 * 4);
@@ -1172,6 +1258,8 @@ static int fused_prepare(Model* m, int B, hipStream_t stream, FusedWS** out) {
         ws->qbuf = (uint16_t*)(b + o_q); ws->knew = (uint16_t*)(b + o_k); ws->vnew = (uint16_t*)(b + o_v);
         ws->attn = (uint16_t*)(b + o_a); ws->act = (uint16_t*)(b + o_act); ws->apart = (float*)(b + o_ap);
         ws->acount = (int*)(b + o_ac);
+        ws->xglbuf = (uint8_t*)(b + o_xgl); ws->qlbuf = (uint16_t*)(b + o_ql); ws->knewl = (uint16_t*)(b + o_kl);
+        ws->attnl = (uint8_t*)(b + o_al);
         ws->hp_max = (float*)(b + o_hm); ws->hp_sum = (float*)(b + o_hs); ws->hp_arg = (int32_t*)(b + o_ha);
         ws->hp_topv = (float*)(b + o_tv); ws->hp_topi = (int32_t*)(b + o_ti); ws->hp_lx = (float*)(b + o_lx);
         ws->nwg = nwg; ws->bh_cap = bh_cap;
@@ -1209,13 +1297,15 @@ int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, 
     a.g1 = d.g1; a.g2 = d.g2; a.gf = d.gf;
     a.L = d.n_layers; a.d = d.d_model; a.H = d.n_heads; a.dh = m->dh; a.F = d.ffn; a.V = d.vocab; a.eps = d.eps;
     a.rope = m->rope;
-    a.kpages = kv->kpages; a.vpages = kv->vpages; a.block_table = kv->block_table; a.lens = kv->len;
+    a.kpages = kv->kpages; a.klpages = kv->klpages; a.vpages = kv->vpages; a.block_table = kv->block_table; a.lens = kv->len;
     a.mpps = kv->d.max_pages_per_seq; a.n_pages = kv->d.n_pages;
     a.seq_ids = ids_dev; a.pending = pending; a.drafts = drafts; a.draft_len = draft_len;
     a.B = B; a.K = K; a.R = R; a.M = B * R;
     a.xbuf = ws->xbuf; a.xgbuf = ws->xgbuf; a.ssbuf = ws->ssbuf; a.qbuf = ws->qbuf; a.knew = ws->knew; a.vnew = ws->vnew;
     a.attn = ws->attn; a.act = ws->act; a.apart = ws->apart; a.acount = ws->acount; a.nsplit = S;
+    a.xglbuf = ws->xglbuf; a.qlbuf = ws->qlbuf; a.knewl = ws->knewl; a.attnl = ws->attnl;
     a.xs_steps = (int)((((size_t)g_lds_max - XS_OFFSET) / a.M - 16) / 256);
+    a.xs_steps2 = (int)((((size_t)g_lds_max - XS_OFFSET) / a.M - 16) / 384);
     a.hp_max = ws->hp_max; a.hp_sum = ws->hp_sum; a.hp_arg = ws->hp_arg; a.hp_topv = ws->hp_topv; a.hp_topi = ws->hp_topi;
     a.hp_lx = ws->hp_lx;
     a.topk = topk; a.mode = mode; a.p = p; a.accept_len = accept_len; a.out_tokens = out_tokens; a.logits_dbg = logits_dbg;

@@ -28,12 +28,13 @@ namespace laser {
 
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
-constexpr int GM_BM = 128, GM_BN = 128, GM_BK = 64, GM_LD = 72;   // LD: halves per padded LDS row
+constexpr int GM_BM = 128, GM_BN = 128;
 constexpr int GM_DEPTH = 2;         // k-steps of global loads in flight per thread (even)
 
 struct GemmTileArgs {
     const uint16_t* W;      // [N][Kd] bf16   (SwiGLU: [2F][Kd], gate rows then up rows; N = F)
     const uint16_t* X;      // [M][Kd] fp16
+    const uint16_t* Xlo;    // [M][Kd] low plane of split activations (x = X + Xlo / 4096), SPLIT kernels only
     int M, N, Kd;
     int tiles_m, tiles_n;   // tiles_n counts BN-column tiles (SwiGLU: 64-feature tiles)
     float* outf;            // EPI_F32: [M][N] store; EPI_RESID: [M][N] accumulate
@@ -64,9 +65,14 @@ __device__ inline void static_for(F&& f) {
 
 // BN = 128: 2 x 2 waves of 64 x 64. BN = 64 (narrow outputs, where 128-column tiles would leave CUs
 // without work): 2 x 2 waves of 64 x 32. The SwiGLU epilogue needs BN = 128.
-template <int EPI, int BN>
+// SPLIT: the activations come as two fp16 planes; every weight fragment meets both (second accumulator
+// set, folded in with the factor 2^-12 at the end). The reduction step drops to 32 so that the third
+// LDS tile still leaves room for two workgroups per CU.
+template <int EPI, int BN, bool SPLIT>
 __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
     static_assert(BN == 128 || (BN == 64 && EPI != GEPI_SWIGLU), "tile width");
+    constexpr int GM_BK = SPLIT ? 32 : 64;   // reduction step
+    constexpr int GM_LD = GM_BK + 8;         // halves per padded LDS row (16-byte reads of 8 rows fall into distinct banks)
     constexpr int CH = GM_BK / 8;            // 16-byte chunks per tile row and k-step
     constexpr int RPT = 256 / CH;            // rows staged per pass of the 256 threads
     constexpr int ST = GM_BM / RPT;          // passes over the activation rows
@@ -76,6 +82,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
     constexpr int D = GM_DEPTH;
     __shared__ __attribute__((aligned(16))) uint16_t sA[2][GM_BM][GM_LD];
     __shared__ __attribute__((aligned(16))) uint16_t sB[2][BN][GM_LD];
+    __shared__ __attribute__((aligned(16))) uint16_t sAl[SPLIT ? 2 : 1][SPLIT ? GM_BM : 1][SPLIT ? GM_LD : 8];
     // ---- XCD-aware tile order ----
     const int total = a.tiles_m * a.tiles_n;
     const int per_xcd = (total + 7) / 8;
@@ -90,12 +97,14 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
     // global -> LDS staging: thread t moves chunk t % CH of rows t / CH + RPT i of both operands
     const int srow = tid / CH, sk = (tid % CH) * 8;
     const uint16_t* xa[ST];
+    const uint16_t* xl[ST];
     const uint16_t* wb[STB];
 #pragma unroll
     for (int i = 0; i < ST; ++i) {
         int row = tm * GM_BM + srow + RPT * i;
         row = row < a.M ? row : a.M - 1;
         xa[i] = a.X + (size_t)row * a.Kd + sk;
+        xl[i] = SPLIT ? a.Xlo + (size_t)row * a.Kd + sk : nullptr;
     }
 #pragma unroll
     for (int i = 0; i < STB; ++i) {
@@ -105,25 +114,33 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
         wb[i] = a.W + (size_t)wr * a.Kd + sk;
     }
     float16_t acc[2][NJ];
+    float16_t acl[SPLIT ? 2 : 1][SPLIT ? NJ : 1];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+            for (int e = 0; e < 16; ++e) {
+                acc[i][j][e] = 0.f;
+                if constexpr (SPLIT) acl[i][j][e] = 0.f;
+            }
 
     // a wave whose 64 rows all lie past M (ragged last m-tile) stages and synchronises but multiplies nothing
     const bool dead = __builtin_amdgcn_readfirstlane(tm * GM_BM + wm * 64) >= a.M;
 
     // Register ring of D k-steps. The element type must be a native vector: an array of HIP's uint4
     // (a struct) that is only copied as a whole is not promoted to registers and lands in scratch.
-    u32x4 ra[D][ST], rb[D][STB];
+    u32x4 ra[D][ST], rb[D][STB], rl[D][SPLIT ? ST : 1];
     const int nk = a.Kd / GM_BK;             // the host guarantees Kd % GM_BK == 0
     auto gload = [&](auto slot_c, int kt) {
         constexpr int slot = decltype(slot_c)::value;
         kt = kt < nk ? kt : nk - 1;          // unconditional, clamped: a load under a branch would be waited for at once
 #pragma unroll
         for (int i = 0; i < ST; ++i) ra[slot][i] = *reinterpret_cast<const u32x4*>(xa[i] + kt * GM_BK);
+        if constexpr (SPLIT) {
+#pragma unroll
+            for (int i = 0; i < ST; ++i) rl[slot][i] = *reinterpret_cast<const u32x4*>(xl[i] + kt * GM_BK);
+        }
 #pragma unroll
         for (int i = 0; i < STB; ++i) rb[slot][i] = *reinterpret_cast<const u32x4*>(wb[i] + kt * GM_BK);
     };
@@ -138,6 +155,10 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
             const unsigned keep = kt < nk ? 0xFFFFFFFFu : 0u;     // steps past the end contribute zeros (no branch)
 #pragma unroll
             for (int i = 0; i < ST; ++i) *reinterpret_cast<u32x4*>(&sA[buf][srow + RPT * i][sk]) = ra[j][i] & keep;
+            if constexpr (SPLIT) {
+#pragma unroll
+                for (int i = 0; i < ST; ++i) *reinterpret_cast<u32x4*>(&sAl[buf][srow + RPT * i][sk]) = rl[j][i] & keep;
+            }
 #pragma unroll
             for (int i = 0; i < STB; ++i) {
                 Frag8 fw;
@@ -163,8 +184,26 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
                     for (int jj = 0; jj < NJ; ++jj) acc[i][jj] = mfma_32x32x16(fa[i], fb[jj], acc[i][jj]);
+                if constexpr (SPLIT) {
+                    Frag8 fl[2];
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+                        fl[i].v4 = *reinterpret_cast<const u32x4*>(&sAl[buf][wm * 64 + i * 32 + lr][kk * 16 + lg * 8]);
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int jj = 0; jj < NJ; ++jj) acl[i][jj] = mfma_32x32x16(fl[i], fb[jj], acl[i][jj]);
+                }
             }
         });
+    }
+    if constexpr (SPLIT) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] += acl[i][j][e] * kLoInv;
     }
     // ---- epilogue: lane holds column lr of each 32-wide tile, rows 8 (e / 4) + 4 lg + e % 4 ----
 #pragma unroll

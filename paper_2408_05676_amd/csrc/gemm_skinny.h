@@ -17,19 +17,25 @@ namespace laser {
 constexpr int kGemmKStep = 128;   // reduction elements per wave step
 
 // acc[mb][i] <-> feature (n0 + 4*(lane/16) + i), row (row0 + 16*mb + lane%16)
-template <int MB>
+// SPLIT: the activations come as two fp16 planes (X, Xlo with x = X + Xlo / 4096); the weight fragment
+// meets both and the low products are accumulated apart, then folded in.
+template <int MB, bool SPLIT>
 __device__ inline void wave_gemm_tile(const uint16_t* __restrict__ Wrow0, size_t ldw,
-                                      const uint16_t* __restrict__ X, int ldx, int M, int row0,
+                                      const uint16_t* __restrict__ X, const uint16_t* __restrict__ Xlo, int ldx, int M, int row0,
                                       int kbeg, int kend, float4_t (&acc)[MB]) {
     const int lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
     const uint16_t* wp = Wrow0 + (size_t)r * ldw + g * 32;
     const uint16_t* xp[MB];
+    const uint16_t* xlp[MB];
+    float4_t acl[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         int row = row0 + mb * 16 + r;
         row = row < M ? row : M - 1;
         xp[mb] = X + (size_t)row * ldx + g * 32;
+        xlp[mb] = SPLIT ? Xlo + (size_t)row * ldx + g * 32 : nullptr;
+        acl[mb] = float4_t{0.f, 0.f, 0.f, 0.f};
     }
     Frag8 a_cur[4], a_nxt[4];
     if (kbeg < kend) {
@@ -51,9 +57,22 @@ __device__ inline void wave_gemm_tile(const uint16_t* __restrict__ Wrow0, size_t
             for (int c = 0; c < 4; ++c) b[c].u = *reinterpret_cast<const uint4*>(xp[mb] + k0 + c * 8);
 #pragma unroll
             for (int c = 0; c < 4; ++c) acc[mb] = mfma_16x16x32(a_cur[c], b[c], acc[mb]);
+            if constexpr (SPLIT) {
+                Frag8 bl[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) bl[c].u = *reinterpret_cast<const uint4*>(xlp[mb] + k0 + c * 8);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acl[mb] = mfma_16x16x32(a_cur[c], bl[c], acl[mb]);
+            }
         }
 #pragma unroll
         for (int c = 0; c < 4; ++c) a_cur[c] = a_nxt[c];
+    }
+    if constexpr (SPLIT) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[mb][i] += acl[mb][i] * kLoInv;
     }
 }
 

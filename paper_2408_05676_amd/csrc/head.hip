@@ -110,7 +110,7 @@ __global__ __launch_bounds__(256) void lm_head_kernel(HeadArgs a) {
         float4_t acc[MB];
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) acc[mb] = float4_t{0.f, 0.f, 0.f, 0.f};
-        wave_gemm_tile<MB>(a.W + (size_t)t * 16 * a.d, (size_t)a.d, a.H, a.d, a.M, row0, 0, a.d, acc);
+        wave_gemm_tile<MB, false>(a.W + (size_t)t * 16 * a.d, (size_t)a.d, a.H, nullptr, a.d, a.M, row0, 0, a.d, acc);
         const int n = t * 16 + 4 * g;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
@@ -314,8 +314,8 @@ int run_head(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* 
             logits = m->logits_ws;
         }
         const int tiles_m = (M + GM_BM - 1) / GM_BM, tiles_n = (m->d.vocab + 127) / 128;
-        GemmTileArgs t{m->d.wlm, h, M, m->d.vocab, m->d.d_model, tiles_m, tiles_n, logits, nullptr};
-        hipLaunchKernelGGL((gemm_mfma_kernel<GEPI_F32, 128>), dim3((unsigned)(((tiles_m * tiles_n + 7) / 8) * 8)), dim3(256), 0,
+        GemmTileArgs t{m->d.wlm, h, nullptr, M, m->d.vocab, m->d.d_model, tiles_m, tiles_n, logits, nullptr};
+        hipLaunchKernelGGL((gemm_mfma_kernel<GEPI_F32, 128, false>), dim3((unsigned)(((tiles_m * tiles_n + 7) / 8) * 8)), dim3(256), 0,
                            stream, t);
         int32_t* row_ok = m->hp_arg;                     // per-row scratch: the streaming path's buffers are free here
         int32_t* row_arg = m->hp_arg + M;

@@ -50,7 +50,7 @@ __global__ void ctx_advance_kernel(int32_t* ctx_tail, int32_t* pending, const in
 }
 
 // k, v: [n_tokens][H][dh] -> pages of one layer
-__global__ void kv_import_kernel(uint16_t* kpages, uint16_t* vpages, const int32_t* block_row,
+__global__ void kv_import_kernel(uint16_t* kpages, uint16_t* klpages, uint16_t* vpages, const int32_t* block_row,
                                  const uint16_t* k, const uint16_t* v, int n_tokens, int H, int dh,
                                  int layer, int n_pages) {
     const size_t total = (size_t)n_tokens * H * dh;
@@ -62,6 +62,7 @@ __global__ void kv_import_kernel(uint16_t* kpages, uint16_t* vpages, const int32
     const int pg = block_row[t / kPageSize], tp = t % kPageSize;
     const size_t base = (((size_t)layer * n_pages + pg) * H + h) * kPageSize * dh;
     kpages[base + (size_t)tp * dh + c] = k[i];
+    klpages[base + (size_t)tp * dh + c] = 0;          // imported keys are plain fp16
     vpages[base + (size_t)c * kPageSize + tp] = v[i];
 }
 
@@ -84,6 +85,7 @@ extern "C" int laser_kv_create(const laser_kv_desc* desc, void* stream_, laser_k
     auto fail = [&](int rc) { laser_kv_destroy(reinterpret_cast<laser_kv*>(kv)); return rc; };
 #define KV_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) { set_error("%s: %s", #expr, hipGetErrorString(e_)); return fail(LASER_E_HIP); } } while (0)
     KV_TRY(hipMalloc((void**)&kv->kpages, pool_elems * 2));
+    KV_TRY(hipMalloc((void**)&kv->klpages, pool_elems * 2));
     KV_TRY(hipMalloc((void**)&kv->vpages, pool_elems * 2));
     KV_TRY(hipMalloc((void**)&kv->block_table, bt * 4));
     KV_TRY(hipMalloc((void**)&kv->len, (size_t)d.max_seqs * 4));
@@ -93,6 +95,7 @@ extern "C" int laser_kv_create(const laser_kv_desc* desc, void* stream_, laser_k
     // Pages start as zeros: masked-out cache slots are multiplied by probability 0 in the value
     // product, which must not meet NaN/Inf bit patterns left in fresh memory.
     KV_TRY(hipMemsetAsync(kv->kpages, 0, pool_elems * 2, stream));
+    KV_TRY(hipMemsetAsync(kv->klpages, 0, pool_elems * 2, stream));
     KV_TRY(hipMemsetAsync(kv->vpages, 0, pool_elems * 2, stream));
     KV_TRY(hipMemsetAsync(kv->block_table, 0, bt * 4, stream));
     KV_TRY(hipMemsetAsync(kv->len, 0, (size_t)d.max_seqs * 4, stream));
@@ -111,7 +114,7 @@ extern "C" int laser_kv_create(const laser_kv_desc* desc, void* stream_, laser_k
 extern "C" int laser_kv_destroy(laser_kv* h) {
     if (!h) return LASER_OK;
     KV* kv = reinterpret_cast<KV*>(h);
-    (void)hipFree(kv->kpages); (void)hipFree(kv->vpages); (void)hipFree(kv->block_table);
+    (void)hipFree(kv->kpages); (void)hipFree(kv->klpages); (void)hipFree(kv->vpages); (void)hipFree(kv->block_table);
     (void)hipFree(kv->len); (void)hipFree(kv->ids_dev);
     if (kv->ids_pinned) (void)hipHostFree(kv->ids_pinned);
     for (int i = 0; i < kIdSlots; ++i) if (kv->ids_ev[i]) (void)hipEventDestroy(kv->ids_ev[i]);
@@ -184,7 +187,7 @@ extern "C" int laser_kv_import(laser_kv* h, int seq, int layer, const uint16_t* 
     LASER_REQUIRE(k && v, LASER_E_INVALID_ARG, "NULL k/v");
     const size_t total = (size_t)n_tokens * kv->d.n_heads * kv->d.head_dim;
     hipLaunchKernelGGL(kv_import_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
-                       kv->kpages, kv->vpages, kv->block_table + (size_t)seq * kv->d.max_pages_per_seq, k, v,
+                       kv->kpages, kv->klpages, kv->vpages, kv->block_table + (size_t)seq * kv->d.max_pages_per_seq, k, v,
                        n_tokens, kv->d.n_heads, kv->d.head_dim, layer, kv->d.n_pages);
     LASER_HIP_CHECK(hipGetLastError());
     return LASER_OK;

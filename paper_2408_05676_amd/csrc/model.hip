@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void embed_rmsnorm_kernel(
     const uint16_t* __restrict__ emb, const float* __restrict__ gain, const int32_t* __restrict__ pending,
     const int32_t* __restrict__ drafts, const int32_t* __restrict__ draft_len, const int32_t* __restrict__ seq_ids,
     const int32_t* __restrict__ lens, int R, int d, int vocab, float eps,
-    float* __restrict__ x, uint16_t* __restrict__ xn, int32_t* __restrict__ row_pos) {
+    float* __restrict__ x, uint16_t* __restrict__ xn, uint16_t* __restrict__ xn_lo, int32_t* __restrict__ row_pos) {
     __shared__ float sm[4];
     const int m = blockIdx.x, b = m / R, r = m % R, K = R - 1;
     int tok = r == 0 ? pending[b] : ((r - 1) < draft_len[b] ? drafts[(size_t)b * K + r - 1] : 0);
@@ -52,12 +52,13 @@ __global__ __launch_bounds__(256) void embed_rmsnorm_kernel(
     for (int i = threadIdx.x; i < d; i += 256) {
         float v = bf16_to_f32(e[i]);
         x[(size_t)m * d + i] = v;
-        xn[(size_t)m * d + i] = f32_to_f16(v * rs * gain[i]);
+        split_f16(v * rs * gain[i], xn[(size_t)m * d + i], xn_lo[(size_t)m * d + i]);
     }
 }
 
+// xn_lo may be NULL (the final norm feeds the output head, which takes single fp16 rows).
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
-                                                      int d, float eps, uint16_t* __restrict__ xn) {
+                                                      int d, float eps, uint16_t* __restrict__ xn, uint16_t* __restrict__ xn_lo) {
     __shared__ float sm[4];
     const size_t m = blockIdx.x;
     // the row stays in registers between the two passes (up to 8192 columns; d is a multiple of 128)
@@ -80,12 +81,14 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
     const float rs = rsqrtf(ss / (float)d + eps);
     const float4* g4 = reinterpret_cast<const float4*>(gain);
     uint2* out = reinterpret_cast<uint2*>(xn + m * d);
+    uint2* out_lo = xn_lo ? reinterpret_cast<uint2*>(xn_lo + m * d) : nullptr;
     auto emit = [&](int i, const float4& t) {
         const float4 g = g4[i];
-        Frag4 o;
-        o.h[0] = f32_to_f16(t.x * rs * g.x); o.h[1] = f32_to_f16(t.y * rs * g.y);
-        o.h[2] = f32_to_f16(t.z * rs * g.z); o.h[3] = f32_to_f16(t.w * rs * g.w);
+        Frag4 o, ol;
+        split_f16(t.x * rs * g.x, o.h[0], ol.h[0]); split_f16(t.y * rs * g.y, o.h[1], ol.h[1]);
+        split_f16(t.z * rs * g.z, o.h[2], ol.h[2]); split_f16(t.w * rs * g.w, o.h[3], ol.h[3]);
         out[i] = o.u;
+        if (out_lo) out_lo[i] = ol.u;
     };
 #pragma unroll
     for (int c = 0; c < NV; ++c) {
@@ -101,12 +104,13 @@ enum { EPI_F32 = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
 struct GemmArgs {
     const uint16_t* W;      // [N][Kd]  (EPI_SWIGLU: [2N][Kd], gate rows then up rows)
     const uint16_t* X;      // [M][Kd]
+    const uint16_t* Xlo;    // [M][Kd] low plane of split activations, or NULL
     int M, N, Kd, S;
     float* outf;            // EPI_F32: [M][N] store;  EPI_RESID: [M][N] accumulate
     uint16_t* outh;         // EPI_SWIGLU: [M][N] fp16
 };
 
-template <int MB, int EPI>
+template <int MB, int EPI, bool SPLIT>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
     constexpr int NA = EPI == EPI_SWIGLU ? 2 : 1;
     __shared__ float red[4][NA][MB][4][64];
@@ -127,10 +131,10 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) acc[s][mb] = float4_t{0.f, 0.f, 0.f, 0.f};
     if (active) {
-        wave_gemm_tile<MB>(a.W + (size_t)tile * 16 * a.Kd, (size_t)a.Kd, a.X, a.Kd, a.M, row0, kbeg, kend, acc[0]);
+        wave_gemm_tile<MB, SPLIT>(a.W + (size_t)tile * 16 * a.Kd, (size_t)a.Kd, a.X, a.Xlo, a.Kd, a.M, row0, kbeg, kend, acc[0]);
         if (NA == 2)
-            wave_gemm_tile<MB>(a.W + ((size_t)a.N + (size_t)tile * 16) * a.Kd, (size_t)a.Kd, a.X, a.Kd, a.M, row0,
-                               kbeg, kend, acc[NA - 1]);
+            wave_gemm_tile<MB, SPLIT>(a.W + ((size_t)a.N + (size_t)tile * 16) * a.Kd, (size_t)a.Kd, a.X, a.Xlo, a.Kd, a.M, row0,
+                                      kbeg, kend, acc[NA - 1]);
     }
     if (a.S > 1) {
 #pragma unroll
@@ -190,17 +194,23 @@ static int launch_gemm(const GemmArgs& a0, hipStream_t stream) {
         // narrow outputs: 128-column tiles would leave compute units without work; 64-column tiles double the count
         const bool narrow = EPI != EPI_SWIGLU && (long)tiles_m * ((a.N + 127) / 128) * 4 < (long)ncu * 5;
         const int bn = narrow ? 64 : 128;
-        GemmTileArgs t{a.W, a.X, a.M, a.N, a.Kd, tiles_m, EPI == EPI_SWIGLU ? (a.N + 63) / 64 : (a.N + bn - 1) / bn, a.outf, a.outh};
+        GemmTileArgs t{a.W, a.X, a.Xlo, a.M, a.N, a.Kd, tiles_m, EPI == EPI_SWIGLU ? (a.N + 63) / 64 : (a.N + bn - 1) / bn, a.outf, a.outh};
         const int total = t.tiles_m * t.tiles_n;
         dim3 grid((unsigned)(((total + 7) / 8) * 8));
+        auto go = [&](auto bnc, auto splitc) {
+            hipLaunchKernelGGL((gemm_mfma_kernel<GE, decltype(bnc)::value, decltype(splitc)::value>), grid, dim3(256), 0, stream, t);
+        };
+        using std::integral_constant;
         if constexpr (EPI != EPI_SWIGLU) {
             if (narrow) {
-                hipLaunchKernelGGL((gemm_mfma_kernel<GE, 64>), grid, dim3(256), 0, stream, t);
+                if (a.Xlo) go(integral_constant<int, 64>{}, integral_constant<bool, true>{});
+                else go(integral_constant<int, 64>{}, integral_constant<bool, false>{});
                 LASER_HIP_CHECK(hipGetLastError());
                 return LASER_OK;
             }
         }
-        hipLaunchKernelGGL((gemm_mfma_kernel<GE, 128>), grid, dim3(256), 0, stream, t);
+        if (a.Xlo) go(integral_constant<int, 128>{}, integral_constant<bool, true>{});
+        else go(integral_constant<int, 128>{}, integral_constant<bool, false>{});
         LASER_HIP_CHECK(hipGetLastError());
         return LASER_OK;
     }
@@ -212,12 +222,23 @@ static int launch_gemm(const GemmArgs& a0, hipStream_t stream) {
     while (S < 4 && (long)ntiles * passes * S < 2048 && (a.Kd / kGemmKStep) >= 2 * S * 2) S *= 2;
     a.S = S;
     dim3 grid((unsigned)((ntiles * S + 3) / 4), (unsigned)passes);
+    // the down projection (EPI_RESID without a low plane) is the only unsplit product
+    constexpr bool kMaySplit = true, kMayPlain = EPI == EPI_RESID;
+    auto go = [&](auto mbc) {
+        constexpr int mb = decltype(mbc)::value;
+        if (a.Xlo) {
+            if constexpr (kMaySplit) hipLaunchKernelGGL((gemm_skinny_kernel<mb, EPI, true>), grid, dim3(256), 0, stream, a);
+        } else {
+            if constexpr (kMayPlain) hipLaunchKernelGGL((gemm_skinny_kernel<mb, EPI, false>), grid, dim3(256), 0, stream, a);
+        }
+    };
+    LASER_REQUIRE(a.Xlo || kMayPlain, LASER_E_INVALID_ARG, "this product needs split activations");
     switch (MB) {
-        case 1: hipLaunchKernelGGL((gemm_skinny_kernel<1, EPI>), grid, dim3(256), 0, stream, a); break;
-        case 2: hipLaunchKernelGGL((gemm_skinny_kernel<2, EPI>), grid, dim3(256), 0, stream, a); break;
-        case 3: hipLaunchKernelGGL((gemm_skinny_kernel<3, EPI>), grid, dim3(256), 0, stream, a); break;
-        case 4: hipLaunchKernelGGL((gemm_skinny_kernel<4, EPI>), grid, dim3(256), 0, stream, a); break;
-        default: hipLaunchKernelGGL((gemm_skinny_kernel<5, EPI>), grid, dim3(256), 0, stream, a); break;
+        case 1: go(std::integral_constant<int, 1>{}); break;
+        case 2: go(std::integral_constant<int, 2>{}); break;
+        case 3: go(std::integral_constant<int, 3>{}); break;
+        case 4: go(std::integral_constant<int, 4>{}); break;
+        default: go(std::integral_constant<int, 5>{}); break;
     }
     LASER_HIP_CHECK(hipGetLastError());
     return LASER_OK;
@@ -227,7 +248,7 @@ static int launch_gemm(const GemmArgs& a0, hipStream_t stream) {
 // One block per row: rotate q and k, store q (fp16) and the row's k, v into its cache slot.
 struct RopeArgs {
     const float* qkv; const int32_t* row_pos; const int32_t* seq_ids; const int32_t* block_table;
-    const float2* rope; uint16_t* q; uint16_t* kpages; uint16_t* vpages;
+    const float2* rope; uint16_t* q; uint16_t* q_lo; uint16_t* kpages; uint16_t* klpages; uint16_t* vpages;
     int R, d, H, dh, mpps, layer, n_pages;
 };
 
@@ -250,19 +271,23 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a) {
         const float q0[4] = {qa.x, qa.y, qa.z, qa.w}, q1[4] = {qb.x, qb.y, qb.z, qb.w};
         const float k0[4] = {ka.x, ka.y, ka.z, ka.w}, k1[4] = {kb.x, kb.y, kb.z, kb.w};
         const float v0[4] = {va.x, va.y, va.z, va.w}, v1[4] = {vb.x, vb.y, vb.z, vb.w};
-        Frag4 oq0, oq1, ok0, ok1;
+        Frag4 oq0, oq1, ok0, ok1, lq0, lq1, lk0, lk1;     // queries and keys are split (hi, lo planes)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            oq0.h[j] = f32_to_f16(q0[j] * co[j] - q1[j] * si[j]);
-            oq1.h[j] = f32_to_f16(q0[j] * si[j] + q1[j] * co[j]);
-            ok0.h[j] = f32_to_f16(k0[j] * co[j] - k1[j] * si[j]);
-            ok1.h[j] = f32_to_f16(k0[j] * si[j] + k1[j] * co[j]);
+            split_f16(q0[j] * co[j] - q1[j] * si[j], oq0.h[j], lq0.h[j]);
+            split_f16(q0[j] * si[j] + q1[j] * co[j], oq1.h[j], lq1.h[j]);
+            split_f16(k0[j] * co[j] - k1[j] * si[j], ok0.h[j], lk0.h[j]);
+            split_f16(k0[j] * si[j] + k1[j] * co[j], ok1.h[j], lk1.h[j]);
         }
         *reinterpret_cast<uint2*>(a.q + (size_t)m * a.d + c0) = oq0.u;
         *reinterpret_cast<uint2*>(a.q + (size_t)m * a.d + c1) = oq1.u;
+        *reinterpret_cast<uint2*>(a.q_lo + (size_t)m * a.d + c0) = lq0.u;
+        *reinterpret_cast<uint2*>(a.q_lo + (size_t)m * a.d + c1) = lq1.u;
         const size_t base = (((size_t)a.layer * a.n_pages + pg) * a.H + h) * kPageSize * a.dh;
         *reinterpret_cast<uint2*>(a.kpages + base + (size_t)tp * a.dh + i) = ok0.u;
         *reinterpret_cast<uint2*>(a.kpages + base + (size_t)tp * a.dh + i + half) = ok1.u;
+        *reinterpret_cast<uint2*>(a.klpages + base + (size_t)tp * a.dh + i) = lk0.u;
+        *reinterpret_cast<uint2*>(a.klpages + base + (size_t)tp * a.dh + i + half) = lk1.u;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             a.vpages[base + (size_t)(i + j) * kPageSize + tp] = f32_to_f16(v0[j]);
@@ -275,9 +300,9 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a) {
 // Attention of the R new rows of one (sequence, head) over cache + new slots, one 16-token page per
 // wave step, online softmax, optional split over the context (partials merged by attn_combine).
 struct AttnArgs {
-    const uint16_t* q; const uint16_t* kpages; const uint16_t* vpages;
+    const uint16_t* q; const uint16_t* q_lo; const uint16_t* kpages; const uint16_t* klpages; const uint16_t* vpages;
     const int32_t* seq_ids; const int32_t* lens; const int32_t* block_table;
-    uint16_t* out; float* part;
+    uint16_t* out; uint16_t* out_lo; float* part;
     int R, d, H, mpps, layer, n_pages, nsplit, nqt;
     float scale;
 };
@@ -304,12 +329,14 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     // length bound): verifying a token as a draft reproduces its one-at-a-time logits bit for bit.
     const int p0 = split * kSplitPages, p1 = min(npages, p0 + kSplitPages);
 
-    Frag8 bq[NC32];
+    Frag8 bq[NC32], bql[NC32];
     {
         const int rowc = min(qrow, a.R - 1);
-        const uint16_t* qp = a.q + ((size_t)b * a.R + rowc) * a.d + (size_t)h * DH + g * 8;
+        const size_t qo = ((size_t)b * a.R + rowc) * a.d + (size_t)h * DH + g * 8;
 #pragma unroll
-        for (int c = 0; c < NC32; ++c) bq[c].u = *reinterpret_cast<const uint4*>(qp + c * 32);
+        for (int c = 0; c < NC32; ++c) bq[c].u = *reinterpret_cast<const uint4*>(a.q + qo + c * 32);
+#pragma unroll
+        for (int c = 0; c < NC32; ++c) bql[c].u = *reinterpret_cast<const uint4*>(a.q_lo + qo + c * 32);
     }
     float m_run = -INFINITY, l_run = 0.f;
     float4_t acc[NC16];
@@ -320,25 +347,35 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     // Pages p0 + wave, + 4, ..: the K and V fragments of the next page are requested before the current
     // one is multiplied (unconditionally: past the wave's last page the current page is requested again,
     // a cache hit), so a wave always has one page in flight.
-    auto load_page = [&](int p, Frag8 (&ak)[NC32], Frag4 (&bv)[NC16]) {
+    auto load_page = [&](int p, Frag8 (&ak)[NC32], Frag8 (&akl)[NC32], Frag4 (&bv)[NC16]) {
         const int pg = bt[p];
         const size_t base = (((size_t)a.layer * a.n_pages + pg) * a.H + h) * kPageSize * DH;
         const uint16_t* kp = a.kpages + base + (size_t)r * DH + g * 8;
+        const uint16_t* klp = a.klpages + base + (size_t)r * DH + g * 8;
 #pragma unroll
         for (int c = 0; c < NC32; ++c) ak[c].v4 = *reinterpret_cast<const u32x4*>(kp + c * 32);
+#pragma unroll
+        for (int c = 0; c < NC32; ++c) akl[c].v4 = *reinterpret_cast<const u32x4*>(klp + c * 32);
         const uint16_t* vp = a.vpages + base + (size_t)r * kPageSize + 4 * g;
 #pragma unroll
         for (int c = 0; c < NC16; ++c) bv[c].v2 = *reinterpret_cast<const u32x2*>(vp + (size_t)c * 16 * kPageSize);
     };
-    Frag8 ak[NC32], akn[NC32];
+    Frag8 ak[NC32], akn[NC32], akl[NC32], akln[NC32];
     Frag4 bv[NC16], bvn[NC16];
     int p = p0 + wave;
-    if (p < p1) load_page(p, ak, bv);
+    if (p < p1) load_page(p, ak, akl, bv);
     for (; p < p1; p += 4) {
-        load_page(p + 4 < p1 ? p + 4 : p, akn, bvn);
-        float4_t s = float4_t{0.f, 0.f, 0.f, 0.f};
+        load_page(p + 4 < p1 ? p + 4 : p, akn, akln, bvn);
+        // s[i] = K[tok 4g+i] . Q[row r] with both operands split: hi.hi + 2^-12 (hi.lo + lo.hi)
+        float4_t s = float4_t{0.f, 0.f, 0.f, 0.f}, sl = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int c = 0; c < NC32; ++c) s = mfma_16x16x32(ak[c], bq[c], s);      // s[i] = K[tok 4g+i] . Q[row r]
+        for (int c = 0; c < NC32; ++c) s = mfma_16x16x32(ak[c], bq[c], s);
+#pragma unroll
+        for (int c = 0; c < NC32; ++c) sl = mfma_16x16x32(ak[c], bql[c], sl);
+#pragma unroll
+        for (int c = 0; c < NC32; ++c) sl = mfma_16x16x32(akl[c], bq[c], sl);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s[i] += sl[i] * kLoInv;
         float sv[4], mx = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -373,7 +410,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
             acc[c] = mfma_16x16x16(pa, bv[c], acc[c]);  // acc[c][i] = O[q 4g+i][channel 16c + r]
         }
 #pragma unroll
-        for (int c = 0; c < NC32; ++c) ak[c] = akn[c];
+        for (int c = 0; c < NC32; ++c) { ak[c] = akn[c]; akl[c] = akln[c]; }
 #pragma unroll
         for (int c = 0; c < NC16; ++c) bv[c] = bvn[c];
     }
@@ -399,7 +436,10 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         }
         if (a.nsplit == 1) {
             const int row = qt * 16 + q;
-            if (row < a.R) a.out[((size_t)b * a.R + row) * a.d + (size_t)h * DH + c] = f32_to_f16(L > 0.f ? O / L : 0.f);
+            if (row < a.R) {
+                const size_t o = ((size_t)b * a.R + row) * a.d + (size_t)h * DH + c;
+                split_f16(L > 0.f ? O / L : 0.f, a.out[o], a.out_lo[o]);
+            }
         } else {
             if (c == 0) { part[q] = M; part[16 + q] = L; }
             part[32 + idx] = O;
@@ -425,7 +465,8 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
                 L += ps[16 + q] * f;
                 O += ps[32 + idx] * f;
             }
-        a.out[((size_t)b * a.R + row) * a.d + (size_t)h * DH + c] = f32_to_f16(L > 0.f ? O / L : 0.f);
+        const size_t o = ((size_t)b * a.R + row) * a.d + (size_t)h * DH + c;
+        split_f16(L > 0.f ? O / L : 0.f, a.out[o], a.out_lo[o]);
     }
 }
 
@@ -443,7 +484,7 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
     const laser_model_desc& d = m->d;
     const int R = K + 1, M = B * R, dm = d.d_model, F = d.ffn;
     hipLaunchKernelGGL(embed_rmsnorm_kernel, dim3(M), dim3(256), 0, stream, d.emb, d.g1, pending, drafts, draft_len,
-                       ids_dev, kv->len, R, dm, d.vocab, d.eps, m->x, m->xn, m->row_pos);
+                       ids_dev, kv->len, R, dm, d.vocab, d.eps, m->x, m->xn, m->xn_lo, m->row_pos);
     const int nqt = (R + 15) / 16;
     const int npages_ub = (max_len_ub + R + kPageSize - 1) / kPageSize;
     const int nsplit = std::max(1, (npages_ub + kSplitPages - 1) / kSplitPages);
@@ -457,13 +498,13 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
     for (int l = 0; l < d.n_layers; ++l) {
         int rc;
         if (l > 0)
-            hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.g1 + (size_t)l * dm, dm, d.eps, m->xn);
-        GemmArgs g{d.wqkv + (size_t)l * 3 * dm * dm, m->xn, M, 3 * dm, dm, 1, m->qkv, nullptr};
+            hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.g1 + (size_t)l * dm, dm, d.eps, m->xn, m->xn_lo);
+        GemmArgs g{d.wqkv + (size_t)l * 3 * dm * dm, m->xn, m->xn_lo, M, 3 * dm, dm, 1, m->qkv, nullptr};
         if ((rc = launch_gemm<EPI_F32>(g, stream))) return rc;
-        RopeArgs ra{m->qkv, m->row_pos, ids_dev, kv->block_table, m->rope, m->q, kv->kpages, kv->vpages,
+        RopeArgs ra{m->qkv, m->row_pos, ids_dev, kv->block_table, m->rope, m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages,
                     R, dm, d.n_heads, m->dh, kv->d.max_pages_per_seq, l, kv->d.n_pages};
         hipLaunchKernelGGL(rope_kv_kernel, dim3(M), dim3(256), 0, stream, ra);
-        AttnArgs aa{m->q, kv->kpages, kv->vpages, ids_dev, kv->len, kv->block_table, m->attn, m->att_part,
+        AttnArgs aa{m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages, ids_dev, kv->len, kv->block_table, m->attn, m->attn_lo, m->att_part,
                     R, dm, d.n_heads, kv->d.max_pages_per_seq, l, kv->d.n_pages, nsplit, nqt, 1.0f / sqrtf((float)m->dh)};
         dim3 ag(d.n_heads, B, nsplit * nqt);
         if (m->dh == 128) hipLaunchKernelGGL(attn_kernel<128>, ag, dim3(256), 0, stream, aa);
@@ -473,18 +514,18 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
             if (m->dh == 128) hipLaunchKernelGGL(attn_combine_kernel<128>, cg, dim3(256), 0, stream, aa);
             else hipLaunchKernelGGL(attn_combine_kernel<64>, cg, dim3(256), 0, stream, aa);
         }
-        GemmArgs go{d.wo + (size_t)l * dm * dm, m->attn, M, dm, dm, 1, m->x, nullptr};
+        GemmArgs go{d.wo + (size_t)l * dm * dm, m->attn, m->attn_lo, M, dm, dm, 1, m->x, nullptr};
         if ((rc = launch_gemm<EPI_RESID>(go, stream))) return rc;
-        hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.g2 + (size_t)l * dm, dm, d.eps, m->xn);
-        GemmArgs gg{d.wgu + (size_t)l * 2 * F * dm, m->xn, M, F, dm, 1, nullptr, m->act};
+        hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.g2 + (size_t)l * dm, dm, d.eps, m->xn, m->xn_lo);
+        GemmArgs gg{d.wgu + (size_t)l * 2 * F * dm, m->xn, m->xn_lo, M, F, dm, 1, nullptr, m->act};
         const bool prof = m->prof_on && m->prof_n < m->prof_cap;
         if (prof) LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n], stream));
         if ((rc = launch_gemm<EPI_SWIGLU>(gg, stream))) return rc;
         if (prof) { LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n + 1], stream)); ++m->prof_n; }
-        GemmArgs gd{d.wdown + (size_t)l * dm * F, m->act, M, dm, F, 1, m->x, nullptr};
+        GemmArgs gd{d.wdown + (size_t)l * dm * F, m->act, nullptr, M, dm, F, 1, m->x, nullptr};
         if ((rc = launch_gemm<EPI_RESID>(gd, stream))) return rc;
     }
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.gf, dm, d.eps, m->xn);
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.gf, dm, d.eps, m->xn, (uint16_t*)nullptr);
     LASER_HIP_CHECK(hipGetLastError());
     return LASER_OK;
 }
@@ -496,7 +537,7 @@ using namespace laser;
 extern "C" int laser_model_destroy(laser_model* h) {
     if (!h) return LASER_OK;
     Model* m = reinterpret_cast<Model*>(h);
-    void* ptrs[] = {m->x, m->xn, m->qkv, m->q, m->attn, m->act, m->row_pos, m->att_part, m->rope, m->hp_max,
+    void* ptrs[] = {m->x, m->xn, m->xn_lo, m->q_lo, m->attn_lo, m->qkv, m->q, m->attn, m->act, m->row_pos, m->att_part, m->rope, m->hp_max,
                     m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx, m->row_x, m->logits_ws};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     for (hipEvent_t e : m->prof_ev) (void)hipEventDestroy(e);
@@ -535,6 +576,9 @@ extern "C" int laser_model_create(const laser_model_desc* desc, void* stream_, l
         M_TRY(hipMalloc((void**)&m->qkv, R * dm * 3 * 4));
         M_TRY(hipMalloc((void**)&m->q, R * dm * 2));
         M_TRY(hipMalloc((void**)&m->attn, R * dm * 2));
+        M_TRY(hipMalloc((void**)&m->xn_lo, R * dm * 2));
+        M_TRY(hipMalloc((void**)&m->q_lo, R * dm * 2));
+        M_TRY(hipMalloc((void**)&m->attn_lo, R * dm * 2));
         M_TRY(hipMalloc((void**)&m->act, R * (size_t)d.ffn * 2));
         M_TRY(hipMalloc((void**)&m->row_pos, R * 4));
         const size_t nt = (size_t)d.max_pos * (dh / 2);

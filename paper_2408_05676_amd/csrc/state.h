@@ -14,10 +14,12 @@ constexpr int kIdSlots = 64;      // ring of staged seq-id vectors
 //   kpages[((l * n_pages + g) * H + h) * 16 * dh + t * dh + c]     token-major  (t = slot in page)
 //   vpages[((l * n_pages + g) * H + h) * dh * 16 + c * 16 + t]     channel-major (transposed)
 // so that a 16-token page of one head is one contiguous 4 KiB block (dh = 128) in either pool and
-// both feed the matrix cores without an in-kernel transpose.
+// both feed the matrix cores without an in-kernel transpose. Keys are stored split (see mfma.h):
+// klpages holds the low plane in the kpages layout.
 struct KV {
     laser_kv_desc d{};
     uint16_t* kpages = nullptr;
+    uint16_t* klpages = nullptr;      // low plane of the split keys, same layout as kpages: k = kpages + klpages / 4096
     uint16_t* vpages = nullptr;
     int32_t* block_table = nullptr;   // [dev] [max_seqs][max_pages_per_seq]
     int32_t* len = nullptr;           // [dev] [max_seqs] committed tokens
@@ -43,7 +45,10 @@ struct Model {
     int dh = 0;
     // workspace (device)
     float* x = nullptr;          // [max_rows][d]   residual stream
-    uint16_t* xn = nullptr;      // [max_rows][d]   normed activations (fp16)
+    uint16_t* xn = nullptr;      // [max_rows][d]   normed activations (fp16, high plane)
+    uint16_t* xn_lo = nullptr;   // [max_rows][d]   their low plane (x = xn + xn_lo / 4096); likewise q_lo, attn_lo
+    uint16_t* q_lo = nullptr;
+    uint16_t* attn_lo = nullptr;
     float* qkv = nullptr;        // [max_rows][3d]
     uint16_t* q = nullptr;       // [max_rows][d]   rotated queries (fp16)
     uint16_t* attn = nullptr;    // [max_rows][d]
