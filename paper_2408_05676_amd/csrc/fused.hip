@@ -46,7 +46,8 @@ struct FusedArgs {
     int L, d, H, dh, F, V;
     float eps;
     const float2* rope;
-    uint16_t *kpages, *klpages, *vpages;
+    uint16_t *kpages, *vpages;
+    uint8_t* klpages;
     const int32_t *block_table, *lens;
     int mpps, n_pages;
     const int32_t *seq_ids, *pending, *drafts, *draft_len;
@@ -60,8 +61,8 @@ struct FusedArgs {
     uint16_t* vnew;     // [L][16][H][dh][16]  new values in the cache's page layout (channel-major): entry
                         // (b * npp + i) holds the new rows of sequence b that fall into its i-th page from len / 16
                         // on (npp = 1 if R == 1, else 2; B * npp <= 16 because B * R <= 16)
-    uint16_t *qlbuf, *knewl;               // [L][16][d]      fp16 low planes of queries and new keys
-    uint8_t* attnl;                        // [L][16][d]      8-bit low plane of the attention output
+    uint16_t* qlbuf;                       // [L][16][d]      fp16 low plane of the queries
+    uint8_t *knewl, *attnl;                // [L][16][d]      8-bit low planes of the new keys and of the attention output
     uint16_t* act;      // [L][16][F]
     float* apart;       // [L][B*H][nsplit][32 + 16*dh]
     int* acount;        // [L][B*H]   (self-resetting)
@@ -526,7 +527,7 @@ __device__ inline void publish_ss(Shared& sh, float* ss_out /*[16] of this workg
 }
 
 // ---- attention ---------------------------------------------------------------------------------------
-template <int DH>
+template <int DH, bool TR>
 __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer) {
     constexpr int NC32 = DH / 32, NC16 = DH / 16;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -537,7 +538,7 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
     const uint16_t* qb = a.qbuf + lo;
     const uint16_t* qlb = a.qlbuf + lo;
     const uint16_t* kn = a.knew + lo;
-    const uint16_t* knl = a.knewl + lo;
+    const uint8_t* knl = a.knewl + lo;
     const uint16_t* vn = a.vnew + lo * kPageSize;
     uint16_t* ob = a.attn + lo;
     uint8_t* obl = a.attnl + lo;
@@ -562,61 +563,79 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
         if (wave < AW) {
             const int pbase = (split * AW + wave) * PPW;
             if (pbase < n_pages) {
+                // Two round trips: (1) the block-table entries of this wave's pages; (2) the query fragments and
+                // every key / value fragment. All addresses of (2) are formed before its first load is issued, and
+                // the scheduling fences keep anything else (in particular reloads of spilled pointers, which
+                // would wait for all earlier loads) out of the load block.
+                int pg[PPW];
+#pragma unroll
+                for (int pp = 0; pp < PPW; ++pp) pg[pp] = bt[min(pbase + pp, n_pages - 1)];
                 Frag8 bq[NC32], bql[NC32];
-                {
-                    const int qr = min(r, a.R - 1);
-                    const size_t qo = (size_t)(b * a.R + qr) * a.d + (size_t)h * DH + g * 8;
-#pragma unroll
-                    for (int c = 0; c < NC32; ++c) bq[c].u = *reinterpret_cast<const uint4*>(qb + qo + c * 32);
-#pragma unroll
-                    for (int c = 0; c < NC32; ++c) bql[c].u = *reinterpret_cast<const uint4*>(qlb + qo + c * 32);
-                }
-                Frag8 ak[PPW][NC32], akl[PPW][NC32];
+                const size_t qo = (size_t)(b * a.R + min(r, a.R - 1)) * a.d + (size_t)h * DH + g * 8;
+                const uint16_t *qp = qb + qo, *qlp = qlb + qo;
+                Frag8 ak[PPW][NC32];
+                uint2 akl[PPW][NC32];               // 8-bit low plane of the keys, widened right before use
                 Frag4 bv[PPW][NC16], nv[PPW][NC16];
                 const int npp = a.R == 1 ? 1 : 2, pg0 = len / kPageSize;
-                // All loads of this wave's pages first, unconditionally (a page index past the end is clamped), so
-                // that they share one round trip. A key slot at or past len is a NEW row: its lane reads the
-                // exchange buffer instead of the cache page (pointer select, same registers). New values come
-                // from the page-shaped exchange buffer and are merged token by token below.
+                // A key slot at or past len is a NEW row: its lane reads the exchange buffer instead of the cache
+                // page (pointer select, same registers). New values come from the page-shaped exchange buffer
+                // and are merged token by token below.
+                const uint16_t *kp[PPW], *vp[PPW], *nvp[PPW];
+                const uint8_t* klp[PPW];
+                size_t pbase_off[PPW];
+                bool p_new[PPW];
 #pragma unroll
                 for (int pp = 0; pp < PPW; ++pp) {
                     const int p = min(pbase + pp, n_pages - 1);
-                    const size_t base = (((size_t)layer * a.n_pages + bt[p]) * a.H + h) * kPageSize * DH;
+                    p_new[pp] = p >= pg0;
+                    const size_t base = (((size_t)layer * a.n_pages + pg[pp]) * a.H + h) * kPageSize * DH;
+                    pbase_off[pp] = base;
                     const int ks = p * kPageSize + r;                   // this lane's key slot
                     const size_t ko = (size_t)(b * a.R + min(max(ks - len, 0), a.R - 1)) * a.d + (size_t)h * DH + g * 8;
-                    const uint16_t* kp = ks >= len ? kn + ko : a.kpages + base + (size_t)r * DH + g * 8;
-                    const uint16_t* klp = ks >= len ? knl + ko : a.klpages + base + (size_t)r * DH + g * 8;
-#pragma unroll
-                    for (int c = 0; c < NC32; ++c) ak[pp][c].u = *reinterpret_cast<const uint4*>(kp + c * 32);
-#pragma unroll
-                    for (int c = 0; c < NC32; ++c) akl[pp][c].u = *reinterpret_cast<const uint4*>(klp + c * 32);
-                    const uint16_t* vp = a.vpages + base + (size_t)r * kPageSize + 4 * g;
-#pragma unroll
-                    for (int c = 0; c < NC16; ++c) bv[pp][c].u = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * kPageSize);
+                    kp[pp] = ks >= len ? kn + ko : a.kpages + base + (size_t)r * DH + g * 8;
+                    klp[pp] = ks >= len ? knl + ko : a.klpages + base + (size_t)r * DH + g * 8;
+                    vp[pp] = a.vpages + base + (size_t)r * kPageSize + 4 * g;
+                    // pages without new rows read one shared line instead (the loads stay unconditional)
                     const int pi = min(max(p - pg0, 0), npp - 1);
-                    const uint16_t* nvp = vn + ((size_t)(b * npp + pi) * a.H + h) * kPageSize * DH + (size_t)r * kPageSize + 4 * g;
-#pragma unroll
-                    for (int c = 0; c < NC16; ++c) nv[pp][c].u = *reinterpret_cast<const uint2*>(nvp + (size_t)c * 16 * kPageSize);
+                    nvp[pp] = p >= pg0 ? vn + ((size_t)(b * npp + pi) * a.H + h) * kPageSize * DH + (size_t)r * kPageSize + 4 * g : vn;
                 }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int c = 0; c < NC32; ++c) bq[c].u = *reinterpret_cast<const uint4*>(qp + c * 32);
+#pragma unroll
+                for (int c = 0; c < NC32; ++c) bql[c].u = *reinterpret_cast<const uint4*>(qlp + c * 32);
+#pragma unroll
+                for (int pp = 0; pp < PPW; ++pp) {
+#pragma unroll
+                    for (int c = 0; c < NC32; ++c) ak[pp][c].u = *reinterpret_cast<const uint4*>(kp[pp] + c * 32);
+#pragma unroll
+                    for (int c = 0; c < NC32; ++c) akl[pp][c] = *reinterpret_cast<const uint2*>(klp[pp] + c * 32);
+#pragma unroll
+                    for (int c = 0; c < NC16; ++c) bv[pp][c].u = *reinterpret_cast<const uint2*>(vp[pp] + (size_t)c * 16 * kPageSize);
+#pragma unroll
+                    for (int c = 0; c < NC16; ++c) nv[pp][c].u = *reinterpret_cast<const uint2*>(nvp[pp] + (p_new[pp] ? (size_t)c * 16 * kPageSize : 0));
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int pp = 0; pp < PPW; ++pp) {
                     const int p = pbase + pp, s0 = p * kPageSize;       // s0: first slot of the page
                     if (p >= n_pages) continue;
+                    // new rows' values replace the cache's (unconditional selects: nothing here may be sunk into a branch)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int c = 0; c < NC16; ++c) bv[pp][c].h[j] = (s0 + 4 * g + j >= len) ? nv[pp][c].h[j] : bv[pp][c].h[j];
                     if (s0 + kPageSize > len) {                         // the page holds new rows
-                        const size_t base = (((size_t)layer * a.n_pages + bt[p]) * a.H + h) * kPageSize * DH;
+                        const size_t base = pbase_off[pp];
                         const int ks = s0 + r;
-#pragma unroll
-                        for (int j = 0; j < 4; ++j)
-#pragma unroll
-                            for (int c = 0; c < NC16; ++c) if (s0 + 4 * g + j >= len) bv[pp][c].h[j] = nv[pp][c].h[j];
                         // this wave owns the page: store its new rows into the cache for later steps
                         if (ks >= len && ks < len + a.R) {
                             uint16_t* kd = a.kpages + base + (size_t)r * DH + g * 8;
-                            uint16_t* kld = a.klpages + base + (size_t)r * DH + g * 8;
+                            uint8_t* kld = a.klpages + base + (size_t)r * DH + g * 8;
 #pragma unroll
                             for (int c = 0; c < NC32; ++c) *reinterpret_cast<uint4*>(kd + c * 32) = ak[pp][c].u;
 #pragma unroll
-                            for (int c = 0; c < NC32; ++c) *reinterpret_cast<uint4*>(kld + c * 32) = akl[pp][c].u;
+                            for (int c = 0; c < NC32; ++c) *reinterpret_cast<uint2*>(kld + c * 32) = akl[pp][c];
                         }
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
@@ -635,7 +654,11 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
 #pragma unroll
                     for (int c = 0; c < NC32; ++c) sl = mfma_16x16x32(ak[pp][c], bql[c], sl);
 #pragma unroll
-                    for (int c = 0; c < NC32; ++c) sl = mfma_16x16x32(akl[pp][c], bq[c], sl);
+                    for (int c = 0; c < NC32; ++c) {
+                        Frag8 kl;
+                        b8x8_to_f16x8(akl[pp][c].x, akl[pp][c].y, kl);
+                        sl = mfma_16x16x32(kl, bq[c], sl);
+                    }
 #pragma unroll
                     for (int i = 0; i < 4; ++i) s[i] += sl[i] * kLoInv;
                     float sv[4], mx = -INFINITY;
@@ -673,6 +696,7 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
                     }
                 }
             }
+            stamp_fine<TR>(a, layer, 12);
             if (g == 0) { sh.att_m[wave][r] = m_run; sh.att_l[wave][r] = l_run; }
 #pragma unroll
             for (int c = 0; c < NC16; ++c)
@@ -715,6 +739,7 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
         if (S > 1) {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's partial stores have completed
             __syncthreads();
+            stamp_fine<TR>(a, layer, 13);
             if (threadIdx.x == 0) {
                 int* cnt = a.acount + (size_t)layer * a.B * a.H + bh;
                 const int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -722,6 +747,7 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
                 if (old == S - 1) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             __syncthreads();
+            stamp_fine<TR>(a, layer, 14);
             if (sh.flag) {                   // last to arrive: combine the S partials of (b, h)
                 const float* pbase = a.apart + (((size_t)layer * a.B * a.H + bh) * S) * PSZ;
                 for (int idx = threadIdx.x; idx < 16 * DH / 2; idx += FT) {
@@ -1061,14 +1087,22 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
                         o0[q] = x0 * cs.x - x1 * cs.y;
                         o1[q] = x0 * cs.y + x1 * cs.x;
                     }
-                    // queries and keys are published split (fp16 high and low planes)
-                    uint16_t* dst = (grp == 0 ? a.qbuf : a.knew) + lo + (size_t)row * a.d;
-                    uint16_t* dstl = (grp == 0 ? a.qlbuf : a.knewl) + lo + (size_t)row * a.d;
+                    // queries and keys are published split: queries with an fp16 low plane, keys with the
+                    // 8-bit low plane the cache keeps
+                    const size_t ro = lo + (size_t)row * a.d;
                     uint32_t hi, lw;
-                    split_pack_h2(o0[0], o0[1], hi, lw);
-                    st_u32(dst + c0, hi); st_u32(dstl + c0, lw);
-                    split_pack_h2(o1[0], o1[1], hi, lw);
-                    st_u32(dst + c0 + half, hi); st_u32(dstl + c0 + half, lw);
+                    uint16_t l8;
+                    if (grp == 0) {
+                        split_pack_h2(o0[0], o0[1], hi, lw);
+                        st_u32(a.qbuf + ro + c0, hi); st_u32(a.qlbuf + ro + c0, lw);
+                        split_pack_h2(o1[0], o1[1], hi, lw);
+                        st_u32(a.qbuf + ro + c0 + half, hi); st_u32(a.qlbuf + ro + c0 + half, lw);
+                    } else {
+                        split_pack_h2_b8(o0[0], o0[1], hi, l8);
+                        st_u32(a.knew + ro + c0, hi); st_u16(a.knewl + ro + c0, l8);
+                        split_pack_h2_b8(o1[0], o1[1], hi, l8);
+                        st_u32(a.knew + ro + c0 + half, hi); st_u16(a.knewl + ro + c0 + half, l8);
+                    }
                 } else {
                     const int idx = w + (u - 2 * cnt) * nwg;
                     // values go into the page-shaped exchange buffer at the row's slot of its page
@@ -1088,7 +1122,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         stamp<TR>(a, ns);
 
         // ---- attention ----
-        attention_phase<DH>(a, sh, l);
+        attention_phase<DH, TR>(a, sh, l);
         stamp<TR>(a, ns);
         if (!grid_sync(a, sh, epoch, no_prefetch)) return;
         stamp<TR>(a, ns);
@@ -1200,7 +1234,7 @@ struct FusedWS {
     unsigned long long* bar = nullptr;     // [0] count, [32] flag (separate 128-byte lines), abort at [64]
     int L = 0, d = 0, F = 0, nwg = 0, bh_cap = 0, dh = 0;
     float* xbuf; uint16_t* xgbuf; uint8_t* xglbuf; float* ssbuf; uint16_t *qbuf, *knew, *vnew, *attn, *act;
-    uint16_t *qlbuf, *knewl; uint8_t* attnl; float* apart; int* acount;
+    uint16_t* qlbuf; uint8_t *knewl, *attnl; float* apart; int* acount;
     float *hp_max, *hp_sum; int32_t* hp_arg; float* hp_topv; int32_t* hp_topi; float* hp_lx;
     unsigned long long epoch = 0;
     long long* trace = nullptr;
@@ -1244,7 +1278,7 @@ static int fused_prepare(Model* m, int B, hipStream_t stream, FusedWS** out) {
         auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
         const size_t o_x = take((2 * L + 1) * XS * 4), o_xg = take((2 * L + 1) * XS * 2), o_ss = take((2 * L + 1) * nwg * 16 * 4);
         const size_t o_q = take(L * XS * 2), o_k = take(L * XS * 2), o_v = take(L * XS * kPageSize * 2), o_a = take(L * XS * 2);
-        const size_t o_xgl = take((2 * L + 1) * XS), o_ql = take(L * XS * 2), o_kl = take(L * XS * 2), o_al = take(L * XS);
+        const size_t o_xgl = take((2 * L + 1) * XS), o_ql = take(L * XS * 2), o_kl = take(L * XS), o_al = take(L * XS);
         const size_t o_act = take(L * 16 * (size_t)d.ffn * 2), o_ap = take(L * bh_cap * PSZ * 4), o_ac = take(L * bh_cap * 4);
         const size_t o_hm = take(16 * CH * 4), o_hs = take(16 * CH * 4), o_ha = take(16 * CH * 4);
         const size_t o_tv = take(16 * CH * KTOP * 4), o_ti = take(16 * CH * KTOP * 4), o_lx = take(16 * 4);
@@ -1258,7 +1292,7 @@ static int fused_prepare(Model* m, int B, hipStream_t stream, FusedWS** out) {
         ws->qbuf = (uint16_t*)(b + o_q); ws->knew = (uint16_t*)(b + o_k); ws->vnew = (uint16_t*)(b + o_v);
         ws->attn = (uint16_t*)(b + o_a); ws->act = (uint16_t*)(b + o_act); ws->apart = (float*)(b + o_ap);
         ws->acount = (int*)(b + o_ac);
-        ws->xglbuf = (uint8_t*)(b + o_xgl); ws->qlbuf = (uint16_t*)(b + o_ql); ws->knewl = (uint16_t*)(b + o_kl);
+        ws->xglbuf = (uint8_t*)(b + o_xgl); ws->qlbuf = (uint16_t*)(b + o_ql); ws->knewl = (uint8_t*)(b + o_kl);
         ws->attnl = (uint8_t*)(b + o_al);
         ws->hp_max = (float*)(b + o_hm); ws->hp_sum = (float*)(b + o_hs); ws->hp_arg = (int32_t*)(b + o_ha);
         ws->hp_topv = (float*)(b + o_tv); ws->hp_topi = (int32_t*)(b + o_ti); ws->hp_lx = (float*)(b + o_lx);

@@ -50,7 +50,7 @@ __global__ void ctx_advance_kernel(int32_t* ctx_tail, int32_t* pending, const in
 }
 
 // k, v: [n_tokens][H][dh] -> pages of one layer
-__global__ void kv_import_kernel(uint16_t* kpages, uint16_t* klpages, uint16_t* vpages, const int32_t* block_row,
+__global__ void kv_import_kernel(uint16_t* kpages, uint8_t* klpages, uint16_t* vpages, const int32_t* block_row,
                                  const uint16_t* k, const uint16_t* v, int n_tokens, int H, int dh,
                                  int layer, int n_pages) {
     const size_t total = (size_t)n_tokens * H * dh;
@@ -85,7 +85,7 @@ extern "C" int laser_kv_create(const laser_kv_desc* desc, void* stream_, laser_k
     auto fail = [&](int rc) { laser_kv_destroy(reinterpret_cast<laser_kv*>(kv)); return rc; };
 #define KV_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) { set_error("%s: %s", #expr, hipGetErrorString(e_)); return fail(LASER_E_HIP); } } while (0)
     KV_TRY(hipMalloc((void**)&kv->kpages, pool_elems * 2));
-    KV_TRY(hipMalloc((void**)&kv->klpages, pool_elems * 2));
+    KV_TRY(hipMalloc((void**)&kv->klpages, pool_elems));
     KV_TRY(hipMalloc((void**)&kv->vpages, pool_elems * 2));
     KV_TRY(hipMalloc((void**)&kv->block_table, bt * 4));
     KV_TRY(hipMalloc((void**)&kv->len, (size_t)d.max_seqs * 4));
@@ -95,7 +95,7 @@ extern "C" int laser_kv_create(const laser_kv_desc* desc, void* stream_, laser_k
     // Pages start as zeros: masked-out cache slots are multiplied by probability 0 in the value
     // product, which must not meet NaN/Inf bit patterns left in fresh memory.
     KV_TRY(hipMemsetAsync(kv->kpages, 0, pool_elems * 2, stream));
-    KV_TRY(hipMemsetAsync(kv->klpages, 0, pool_elems * 2, stream));
+    KV_TRY(hipMemsetAsync(kv->klpages, 0, pool_elems, stream));
     KV_TRY(hipMemsetAsync(kv->vpages, 0, pool_elems * 2, stream));
     KV_TRY(hipMemsetAsync(kv->block_table, 0, bt * 4, stream));
     KV_TRY(hipMemsetAsync(kv->len, 0, (size_t)d.max_seqs * 4, stream));

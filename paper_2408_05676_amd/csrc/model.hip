@@ -248,7 +248,7 @@ static int launch_gemm(const GemmArgs& a0, hipStream_t stream) {
 // One block per row: rotate q and k, store q (fp16) and the row's k, v into its cache slot.
 struct RopeArgs {
     const float* qkv; const int32_t* row_pos; const int32_t* seq_ids; const int32_t* block_table;
-    const float2* rope; uint16_t* q; uint16_t* q_lo; uint16_t* kpages; uint16_t* klpages; uint16_t* vpages;
+    const float2* rope; uint16_t* q; uint16_t* q_lo; uint16_t* kpages; uint8_t* klpages; uint16_t* vpages;
     int R, d, H, dh, mpps, layer, n_pages;
 };
 
@@ -286,8 +286,11 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a) {
         const size_t base = (((size_t)a.layer * a.n_pages + pg) * a.H + h) * kPageSize * a.dh;
         *reinterpret_cast<uint2*>(a.kpages + base + (size_t)tp * a.dh + i) = ok0.u;
         *reinterpret_cast<uint2*>(a.kpages + base + (size_t)tp * a.dh + i + half) = ok1.u;
-        *reinterpret_cast<uint2*>(a.klpages + base + (size_t)tp * a.dh + i) = lk0.u;
-        *reinterpret_cast<uint2*>(a.klpages + base + (size_t)tp * a.dh + i + half) = lk1.u;
+        // the keys' low plane is kept in 8 bits
+        *reinterpret_cast<uint32_t*>(a.klpages + base + (size_t)tp * a.dh + i) =
+            f16_to_b8(lk0.h[0]) | (f16_to_b8(lk0.h[1]) << 8) | (f16_to_b8(lk0.h[2]) << 16) | (f16_to_b8(lk0.h[3]) << 24);
+        *reinterpret_cast<uint32_t*>(a.klpages + base + (size_t)tp * a.dh + i + half) =
+            f16_to_b8(lk1.h[0]) | (f16_to_b8(lk1.h[1]) << 8) | (f16_to_b8(lk1.h[2]) << 16) | (f16_to_b8(lk1.h[3]) << 24);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             a.vpages[base + (size_t)(i + j) * kPageSize + tp] = f32_to_f16(v0[j]);
@@ -300,7 +303,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a) {
 // Attention of the R new rows of one (sequence, head) over cache + new slots, one 16-token page per
 // wave step, online softmax, optional split over the context (partials merged by attn_combine).
 struct AttnArgs {
-    const uint16_t* q; const uint16_t* q_lo; const uint16_t* kpages; const uint16_t* klpages; const uint16_t* vpages;
+    const uint16_t* q; const uint16_t* q_lo; const uint16_t* kpages; const uint8_t* klpages; const uint16_t* vpages;
     const int32_t* seq_ids; const int32_t* lens; const int32_t* block_table;
     uint16_t* out; uint16_t* out_lo; float* part;
     int R, d, H, mpps, layer, n_pages, nsplit, nqt;
@@ -347,20 +350,21 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     // Pages p0 + wave, + 4, ..: the K and V fragments of the next page are requested before the current
     // one is multiplied (unconditionally: past the wave's last page the current page is requested again,
     // a cache hit), so a wave always has one page in flight.
-    auto load_page = [&](int p, Frag8 (&ak)[NC32], Frag8 (&akl)[NC32], Frag4 (&bv)[NC16]) {
+    auto load_page = [&](int p, Frag8 (&ak)[NC32], u32x2 (&akl)[NC32], Frag4 (&bv)[NC16]) {
         const int pg = bt[p];
         const size_t base = (((size_t)a.layer * a.n_pages + pg) * a.H + h) * kPageSize * DH;
         const uint16_t* kp = a.kpages + base + (size_t)r * DH + g * 8;
-        const uint16_t* klp = a.klpages + base + (size_t)r * DH + g * 8;
+        const uint8_t* klp = a.klpages + base + (size_t)r * DH + g * 8;
 #pragma unroll
         for (int c = 0; c < NC32; ++c) ak[c].v4 = *reinterpret_cast<const u32x4*>(kp + c * 32);
 #pragma unroll
-        for (int c = 0; c < NC32; ++c) akl[c].v4 = *reinterpret_cast<const u32x4*>(klp + c * 32);
+        for (int c = 0; c < NC32; ++c) akl[c] = *reinterpret_cast<const u32x2*>(klp + c * 32);
         const uint16_t* vp = a.vpages + base + (size_t)r * kPageSize + 4 * g;
 #pragma unroll
         for (int c = 0; c < NC16; ++c) bv[c].v2 = *reinterpret_cast<const u32x2*>(vp + (size_t)c * 16 * kPageSize);
     };
-    Frag8 ak[NC32], akn[NC32], akl[NC32], akln[NC32];
+    Frag8 ak[NC32], akn[NC32];
+    u32x2 akl[NC32], akln[NC32];        // 8-bit low plane of the keys, widened right before use
     Frag4 bv[NC16], bvn[NC16];
     int p = p0 + wave;
     if (p < p1) load_page(p, ak, akl, bv);
@@ -373,7 +377,11 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
 #pragma unroll
         for (int c = 0; c < NC32; ++c) sl = mfma_16x16x32(ak[c], bql[c], sl);
 #pragma unroll
-        for (int c = 0; c < NC32; ++c) sl = mfma_16x16x32(akl[c], bq[c], sl);
+        for (int c = 0; c < NC32; ++c) {
+            Frag8 kl;
+            b8x8_to_f16x8(akl[c][0], akl[c][1], kl);
+            sl = mfma_16x16x32(kl, bq[c], sl);
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) s[i] += sl[i] * kLoInv;
         float sv[4], mx = -INFINITY;

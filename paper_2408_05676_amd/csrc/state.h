@@ -15,11 +15,11 @@ constexpr int kIdSlots = 64;      // ring of staged seq-id vectors
 //   vpages[((l * n_pages + g) * H + h) * dh * 16 + c * 16 + t]     channel-major (transposed)
 // so that a 16-token page of one head is one contiguous 4 KiB block (dh = 128) in either pool and
 // both feed the matrix cores without an in-kernel transpose. Keys are stored split (see mfma.h):
-// klpages holds the low plane in the kpages layout.
+// klpages holds their 8-bit low plane, one byte per element, indexed like kpages.
 struct KV {
     laser_kv_desc d{};
     uint16_t* kpages = nullptr;
-    uint16_t* klpages = nullptr;      // low plane of the split keys, same layout as kpages: k = kpages + klpages / 4096
+    uint8_t* klpages = nullptr;       // 8-bit low plane of the split keys, indexed like kpages: k = kpages + klpages / 4096
     uint16_t* vpages = nullptr;
     int32_t* block_table = nullptr;   // [dev] [max_seqs][max_pages_per_seq]
     int32_t* len = nullptr;           // [dev] [max_seqs] committed tokens
