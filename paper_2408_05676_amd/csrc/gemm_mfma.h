@@ -2,10 +2,10 @@
 //   Y[M][N] = X[M][Kd] * W[N][Kd]^T,  X fp16, W bf16 (widened to fp16 on its way into LDS), fp32 accumulate.
 //
 // Workgroup tile 128 x 128, 256 threads = 2 x 2 waves of 64 x 64, each wave 2 x 2
-// v_mfma_f32_32x32x16_f16 tiles (64 accumulator registers). Reduction step 64; a thread keeps the
-// global loads of the next step in flight in registers while the current one is written to one of two
-// LDS buffers (36 KiB each pair, rows padded 128 -> 144 bytes against bank conflicts) and multiplied;
-// one workgroup barrier per step; two workgroups per CU. Measured at M = 704, N = 12288, K = 4096:
+// v_mfma_f32_32x32x16_f16 tiles (64 accumulator registers). Reduction step 64; three stages in flight: the
+// global loads of step kt + 2 (registers), the conversion and LDS write of step kt + 1 (interleaved with the
+// matrix instructions), the multiplication of step kt out of one of two LDS buffers (36 KiB each pair, rows
+// padded 128 -> 144 bytes against bank conflicts); one workgroup barrier per step; two workgroups per CU. Measured at M = 704, N = 12288, K = 4096:
 // 108-114 us = 25 % of the fp16 matrix peak (reduction step 32: 115-120 us, 16: 170 us, 128: 151 us).
 // Counters show 89 % L2 hits and the weights fetched from HBM once per launch, i.e. the XCD-aware tile
 // order works; what is left is the quantisation of 576 tiles over 256 CUs (75 %) and the L2 -> LDS ->
@@ -144,59 +144,82 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
 #pragma unroll
         for (int i = 0; i < STB; ++i) rb[slot][i] = *reinterpret_cast<const u32x4*>(wb[i] + kt * GM_BK);
     };
-    static_for<0, D - 1>([&](auto sc) { gload(sc, decltype(sc)::value); });
-    for (int kt0 = 0; kt0 < nk; kt0 += D) {
-        static_for<0, D>([&](auto jc) {
-            constexpr int j = decltype(jc)::value;
-            constexpr int buf = j & 1;       // D is even
-            const int kt = kt0 + j;
-            gload(std::integral_constant<int, (j + D - 1) % D>{}, kt + D - 1);
-            __builtin_amdgcn_sched_barrier(0);
-            const unsigned keep = kt < nk ? 0xFFFFFFFFu : 0u;     // steps past the end contribute zeros (no branch)
+    // Software pipeline over k-steps: while step kt is multiplied out of LDS buffer kt % 2, the registers that
+    // hold step kt + 1 are converted and written to the other buffer in pieces BETWEEN the matrix instructions
+    // of the same basic block (so the vector ALU and LDS-write work hides behind the matrix pipe instead of
+    // preceding it), and the global loads of step kt + 2 are in flight. One workgroup barrier per step: it
+    // publishes buffer (kt + 1) % 2 and guarantees that every wave has finished reading buffer kt % 2 before
+    // the next step overwrites it.
+    constexpr int NKK = GM_BK / 16;
+    auto stage_piece = [&](auto slot_c, int buf, int kk, unsigned keep) {       // piece kk (of NKK) of one k-step
+        constexpr int slot = decltype(slot_c)::value;
 #pragma unroll
-            for (int i = 0; i < ST; ++i) *reinterpret_cast<u32x4*>(&sA[buf][srow + RPT * i][sk]) = ra[j][i] & keep;
-            if constexpr (SPLIT) {
-#pragma unroll
-                for (int i = 0; i < ST; ++i) *reinterpret_cast<u32x4*>(&sAl[buf][srow + RPT * i][sk]) = rl[j][i] & keep;
+        for (int i = 0; i < ST; ++i)
+            if (i * NKK / ST == kk) {
+                *reinterpret_cast<u32x4*>(&sA[buf][srow + RPT * i][sk]) = ra[slot][i] & keep;
+                if constexpr (SPLIT) *reinterpret_cast<u32x4*>(&sAl[buf][srow + RPT * i][sk]) = rl[slot][i] & keep;
             }
 #pragma unroll
-            for (int i = 0; i < STB; ++i) {
+        for (int i = 0; i < STB; ++i)
+            if (i * NKK / STB == kk) {
                 Frag8 fw;
-                fw.v4 = rb[j][i];
+                fw.v4 = rb[slot][i];
                 bf16x8_to_f16x8(fw);
                 *reinterpret_cast<u32x4*>(&sB[buf][srow + RPT * i][sk]) = fw.v4;
             }
-            // One barrier per step: a wave may run one step ahead (into the other buffer); it cannot
-            // overwrite this buffer before every wave has passed the next step's barrier, i.e. has
-            // finished reading it.
-            __syncthreads();
-            if (!dead)
+    };
+    auto multiply_piece = [&](int buf, int kk) {
+        Frag8 fa[2], fb[NJ];
 #pragma unroll
-            for (int kk = 0; kk < GM_BK / 16; ++kk) {
-                Frag8 fa[2], fb[NJ];
+        for (int i = 0; i < 2; ++i)
+            fa[i].v4 = *reinterpret_cast<const u32x4*>(&sA[buf][wm * 64 + i * 32 + lr][kk * 16 + lg * 8]);
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
-                    fa[i].v4 = *reinterpret_cast<const u32x4*>(&sA[buf][wm * 64 + i * 32 + lr][kk * 16 + lg * 8]);
+        for (int i = 0; i < NJ; ++i)
+            fb[i].v4 = *reinterpret_cast<const u32x4*>(&sB[buf][wn * WN + i * 32 + lr][kk * 16 + lg * 8]);
 #pragma unroll
-                for (int i = 0; i < NJ; ++i)
-                    fb[i].v4 = *reinterpret_cast<const u32x4*>(&sB[buf][wn * WN + i * 32 + lr][kk * 16 + lg * 8]);
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
+            for (int jj = 0; jj < NJ; ++jj) acc[i][jj] = mfma_32x32x16(fa[i], fb[jj], acc[i][jj]);
+        if constexpr (SPLIT) {
+            Frag8 fl[2];
 #pragma unroll
-                    for (int jj = 0; jj < NJ; ++jj) acc[i][jj] = mfma_32x32x16(fa[i], fb[jj], acc[i][jj]);
-                if constexpr (SPLIT) {
-                    Frag8 fl[2];
+            for (int i = 0; i < 2; ++i)
+                fl[i].v4 = *reinterpret_cast<const u32x4*>(&sAl[buf][wm * 64 + i * 32 + lr][kk * 16 + lg * 8]);
 #pragma unroll
-                    for (int i = 0; i < 2; ++i)
-                        fl[i].v4 = *reinterpret_cast<const u32x4*>(&sAl[buf][wm * 64 + i * 32 + lr][kk * 16 + lg * 8]);
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
-                    for (int i = 0; i < 2; ++i)
+                for (int jj = 0; jj < NJ; ++jj) acl[i][jj] = mfma_32x32x16(fl[i], fb[jj], acl[i][jj]);
+        }
+    };
+    static_assert(D == 2, "the pipeline below alternates two register slots and two LDS buffers");
+    gload(std::integral_constant<int, 0>{}, 0);
+    gload(std::integral_constant<int, 1>{}, 1);
 #pragma unroll
-                        for (int jj = 0; jj < NJ; ++jj) acl[i][jj] = mfma_32x32x16(fl[i], fb[jj], acl[i][jj]);
+    for (int kk = 0; kk < NKK; ++kk) stage_piece(std::integral_constant<int, 0>{}, 0, kk, 0xFFFFFFFFu);
+    __syncthreads();
+    // The whole loop exists twice (live and dead waves) so that neither body contains a branch: with a branch
+    // inside, the conversions common to both arms are hoisted in front of it and run before, not between, the
+    // matrix instructions.
+    auto run = [&](auto dead_c) {
+        constexpr bool kDead = decltype(dead_c)::value;
+        for (int kt0 = 0; kt0 < nk; kt0 += D) {
+            static_for<0, D>([&](auto jc) {
+                constexpr int j = decltype(jc)::value;      // step kt lives in LDS buffer j; registers slot j are free
+                const int kt = kt0 + j;
+                gload(jc, kt + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                const unsigned keep = kt + 1 < nk ? 0xFFFFFFFFu : 0u;     // a step past the end is staged as zeros (no branch)
+#pragma unroll
+                for (int kk = 0; kk < NKK; ++kk) {
+                    if constexpr (!kDead) multiply_piece(j, kk);
+                    stage_piece(std::integral_constant<int, 1 - j>{}, 1 - j, kk, keep);
                 }
-            }
-        });
-    }
+                __syncthreads();
+            });
+        }
+    };
+    if (dead) run(std::true_type{});
+    else run(std::false_type{});
     if constexpr (SPLIT) {
 #pragma unroll
         for (int i = 0; i < 2; ++i)

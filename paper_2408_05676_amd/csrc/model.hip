@@ -223,7 +223,7 @@ static int launch_gemm(const GemmArgs& a0, hipStream_t stream) {
     a.S = S;
     dim3 grid((unsigned)((ntiles * S + 3) / 4), (unsigned)passes);
     // the down projection (EPI_RESID without a low plane) is the only unsplit product
-    constexpr bool kMaySplit = true, kMayPlain = EPI == EPI_RESID;
+    constexpr bool kMaySplit = true, kMayPlain = EPI == EPI_RESID;      // few rows: gate/up and QKV are always split
     auto go = [&](auto mbc) {
         constexpr int mb = decltype(mbc)::value;
         if (a.Xlo) {
@@ -525,7 +525,10 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
         GemmArgs go{d.wo + (size_t)l * dm * dm, m->attn, m->attn_lo, M, dm, dm, 1, m->x, nullptr};
         if ((rc = launch_gemm<EPI_RESID>(go, stream))) return rc;
         hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.g2 + (size_t)l * dm, dm, d.eps, m->xn, m->xn_lo);
-        GemmArgs gg{d.wgu + (size_t)l * 2 * F * dm, m->xn, m->xn_lo, M, F, dm, 1, nullptr, m->act};
+        // On the tiled many-row path a split operand doubles the matrix work; gate/up (45 % of the layer's
+        // flops) takes the single fp16 rows there unless option "split_ffn" asks for the split (see set_option).
+        const bool split_gu = M <= kSkinnyMaxRows || m->split_ffn;
+        GemmArgs gg{d.wgu + (size_t)l * 2 * F * dm, m->xn, split_gu ? m->xn_lo : nullptr, M, F, dm, 1, nullptr, m->act};
         const bool prof = m->prof_on && m->prof_n < m->prof_cap;
         if (prof) LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n], stream));
         if ((rc = launch_gemm<EPI_SWIGLU>(gg, stream))) return rc;
@@ -711,6 +714,7 @@ extern "C" int laser_model_set_option(laser_model* mh, const char* name, int val
     LASER_REQUIRE(m != nullptr && name != nullptr, LASER_E_INVALID_ARG, "NULL argument");
     if (std::string(name) == "fused") { m->use_fused = value; return LASER_OK; }
     if (std::string(name) == "fused_trace") { m->fused_trace = value; return LASER_OK; }
+    if (std::string(name) == "split_ffn") { m->split_ffn = value; return LASER_OK; }
     set_error("unknown option %s", name);
     return LASER_E_INVALID_ARG;
 }

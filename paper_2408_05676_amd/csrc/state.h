@@ -74,6 +74,7 @@ struct Model {
     void* fused_ws = nullptr;          // workspace of the persistent few-row kernel (fused.hip)
     int use_fused = 1;                 // 0 forces the generic multi-kernel path
     int fused_trace = 0;               // 1: thread 0 of every workgroup stamps the wall clock at phase edges
+    int split_ffn = 0;                 // 1: the many-row (tiled) gate/up product also takes split activations
 };
 
 }  // namespace laser
