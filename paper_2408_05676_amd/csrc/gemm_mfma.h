@@ -29,10 +29,12 @@ namespace laser {
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
 constexpr int GM_BM = 128, GM_BN = 128;
-constexpr int GM_DEPTH = 2;         // k-steps of global loads in flight per thread (even)
+constexpr int GM_BK_PLAIN = 64, GM_WGS = 2;   // unsplit kernels: reduction step, workgroups per CU
+constexpr int GM_DEPTH = 2;         // register slots per thread: GM_DEPTH - 1 k-steps of global loads in flight (even)
 
 struct GemmTileArgs {
-    const uint16_t* W;      // [N][Kd] bf16   (SwiGLU: [2F][Kd], gate rows then up rows; N = F)
+    const uint16_t* W;      // [N][Kd] bf16, or the same values already widened to fp16 (WF16 kernels)
+                            // (SwiGLU: [2F][Kd], gate rows then up rows; N = F)
     const uint16_t* X;      // [M][Kd] fp16
     const uint16_t* Xlo;    // [M][Kd] low plane of split activations (x = X + Xlo / 4096), SPLIT kernels only
     int M, N, Kd;
@@ -68,10 +70,13 @@ __device__ inline void static_for(F&& f) {
 // SPLIT: the activations come as two fp16 planes; every weight fragment meets both (second accumulator
 // set, folded in with the factor 2^-12 at the end). The reduction step drops to 32 so that the third
 // LDS tile still leaves room for two workgroups per CU.
-template <int EPI, int BN, bool SPLIT>
-__global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
+// WF16: the weights were widened to fp16 beforehand (the model handle keeps such a copy for the many-row
+// path): the loop then has no conversion arithmetic, which otherwise competes with the matrix instructions
+// for issue slots (about 50 of the ~100 vector instructions per k-step).
+template <int EPI, int BN, bool SPLIT, bool WF16 = false>
+__global__ __launch_bounds__(256, SPLIT ? 2 : GM_WGS) void gemm_mfma_kernel(GemmTileArgs a) {
     static_assert(BN == 128 || (BN == 64 && EPI != GEPI_SWIGLU), "tile width");
-    constexpr int GM_BK = SPLIT ? 32 : 64;   // reduction step
+    constexpr int GM_BK = SPLIT ? 32 : GM_BK_PLAIN;   // reduction step
     constexpr int GM_LD = GM_BK + 8;         // halves per padded LDS row (16-byte reads of 8 rows fall into distinct banks)
     constexpr int CH = GM_BK / 8;            // 16-byte chunks per tile row and k-step
     constexpr int RPT = 256 / CH;            // rows staged per pass of the 256 threads
@@ -79,7 +84,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
     constexpr int STB = BN / RPT;            // passes over the weight rows
     constexpr int WN = BN / 2;               // columns per wave
     constexpr int NJ = WN / 32;              // 32-column MFMA tiles per wave
-    constexpr int D = GM_DEPTH;
+    constexpr int D = (SPLIT && BN == 128) ? 2 : (SPLIT ? 4 : GM_DEPTH);   // the split 128-column kernel has no registers for a deeper ring
     __shared__ __attribute__((aligned(16))) uint16_t sA[2][GM_BM][GM_LD];
     __shared__ __attribute__((aligned(16))) uint16_t sB[2][BN][GM_LD];
     __shared__ __attribute__((aligned(16))) uint16_t sAl[SPLIT ? 2 : 1][SPLIT ? GM_BM : 1][SPLIT ? GM_LD : 8];
@@ -164,7 +169,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
             if (i * NKK / STB == kk) {
                 Frag8 fw;
                 fw.v4 = rb[slot][i];
-                bf16x8_to_f16x8(fw);
+                if constexpr (!WF16) bf16x8_to_f16x8(fw);
                 *reinterpret_cast<u32x4*>(&sB[buf][srow + RPT * i][sk]) = fw.v4;
             }
     };
@@ -191,32 +196,41 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmTileArgs a) {
                 for (int jj = 0; jj < NJ; ++jj) acl[i][jj] = mfma_32x32x16(fl[i], fb[jj], acl[i][jj]);
         }
     };
-    static_assert(D == 2, "the pipeline below alternates two register slots and two LDS buffers");
-    gload(std::integral_constant<int, 0>{}, 0);
-    gload(std::integral_constant<int, 1>{}, 1);
+    static_assert(D % 2 == 0, "slot j of the unrolled loop must map to LDS buffer j & 1");
+    static_for<0, D>([&](auto sc) { gload(sc, decltype(sc)::value); });
 #pragma unroll
     for (int kk = 0; kk < NKK; ++kk) stage_piece(std::integral_constant<int, 0>{}, 0, kk, 0xFFFFFFFFu);
     __syncthreads();
     // The whole loop exists twice (live and dead waves) so that neither body contains a branch: with a branch
     // inside, the conversions common to both arms are hoisted in front of it and run before, not between, the
     // matrix instructions.
+    // Steps are taken in groups of D (D register slots, two LDS buffers). If the step count is not a multiple
+    // of D the last group multiplies steps that do not exist: they are staged as zeros, which only that
+    // group's code pays for (the mask costs a vector instruction per staged register).
     auto run = [&](auto dead_c) {
         constexpr bool kDead = decltype(dead_c)::value;
-        for (int kt0 = 0; kt0 < nk; kt0 += D) {
-            static_for<0, D>([&](auto jc) {
-                constexpr int j = decltype(jc)::value;      // step kt lives in LDS buffer j; registers slot j are free
-                const int kt = kt0 + j;
-                gload(jc, kt + 2);
-                __builtin_amdgcn_sched_barrier(0);
-                const unsigned keep = kt + 1 < nk ? 0xFFFFFFFFu : 0u;     // a step past the end is staged as zeros (no branch)
+        auto pairs = [&](int kt_begin, int kt_end, auto mask_c) {
+            constexpr bool kMask = decltype(mask_c)::value;
+            for (int kt0 = kt_begin; kt0 < kt_end; kt0 += D) {
+                static_for<0, D>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;      // step kt lives in LDS buffer j & 1; registers slot j are free
+                    constexpr int jn = (j + 1) % D;             // slot that holds step kt + 1
+                    const int kt = kt0 + j;
+                    gload(jc, kt + D);
+                    __builtin_amdgcn_sched_barrier(0);
+                    const unsigned keep = (!kMask || kt + 1 < nk) ? 0xFFFFFFFFu : 0u;
 #pragma unroll
-                for (int kk = 0; kk < NKK; ++kk) {
-                    if constexpr (!kDead) multiply_piece(j, kk);
-                    stage_piece(std::integral_constant<int, 1 - j>{}, 1 - j, kk, keep);
-                }
-                __syncthreads();
-            });
-        }
+                    for (int kk = 0; kk < NKK; ++kk) {
+                        if constexpr (!kDead) multiply_piece(j & 1, kk);
+                        stage_piece(std::integral_constant<int, jn>{}, jn & 1, kk, keep);
+                    }
+                    __syncthreads();
+                });
+            }
+        };
+        const int full_end = nk - nk % D;                // whole groups of D steps need no mask
+        pairs(0, full_end, std::false_type{});
+        if (nk % D) pairs(full_end, nk, std::true_type{});
     };
     if (dead) run(std::true_type{});
     else run(std::false_type{});

@@ -103,6 +103,7 @@ enum { EPI_F32 = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
 
 struct GemmArgs {
     const uint16_t* W;      // [N][Kd]  (EPI_SWIGLU: [2N][Kd], gate rows then up rows)
+    const uint16_t* W16;    // the same matrix widened to fp16 (many-row path only), or NULL
     const uint16_t* X;      // [M][Kd]
     const uint16_t* Xlo;    // [M][Kd] low plane of split activations, or NULL
     int M, N, Kd, S;
@@ -183,6 +184,16 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
 
 constexpr int kSkinnyMaxRows = 80;   // beyond this the weights would be streamed more than once
 
+// bf16 -> fp16 copy of a weight matrix, 8 elements per thread and iteration
+__global__ __launch_bounds__(256) void widen_weights_kernel(const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, size_t n8) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+        Frag8 f;
+        f.u = reinterpret_cast<const uint4*>(src)[i];
+        bf16x8_to_f16x8(f);
+        reinterpret_cast<uint4*>(dst)[i] = f.u;
+    }
+}
+
 template <int EPI>
 static int launch_gemm(const GemmArgs& a0, hipStream_t stream) {
     GemmArgs a = a0;
@@ -194,11 +205,14 @@ static int launch_gemm(const GemmArgs& a0, hipStream_t stream) {
         // narrow outputs: 128-column tiles would leave compute units without work; 64-column tiles double the count
         const bool narrow = EPI != EPI_SWIGLU && (long)tiles_m * ((a.N + 127) / 128) * 4 < (long)ncu * 5;
         const int bn = narrow ? 64 : 128;
-        GemmTileArgs t{a.W, a.X, a.Xlo, a.M, a.N, a.Kd, tiles_m, EPI == EPI_SWIGLU ? (a.N + 63) / 64 : (a.N + bn - 1) / bn, a.outf, a.outh};
+        GemmTileArgs t{a.W16 ? a.W16 : a.W, a.X, a.Xlo, a.M, a.N, a.Kd, tiles_m, EPI == EPI_SWIGLU ? (a.N + 63) / 64 : (a.N + bn - 1) / bn, a.outf, a.outh};
         const int total = t.tiles_m * t.tiles_n;
         dim3 grid((unsigned)(((total + 7) / 8) * 8));
         auto go = [&](auto bnc, auto splitc) {
-            hipLaunchKernelGGL((gemm_mfma_kernel<GE, decltype(bnc)::value, decltype(splitc)::value>), grid, dim3(256), 0, stream, t);
+            if (a.W16)
+                hipLaunchKernelGGL((gemm_mfma_kernel<GE, decltype(bnc)::value, decltype(splitc)::value, true>), grid, dim3(256), 0, stream, t);
+            else
+                hipLaunchKernelGGL((gemm_mfma_kernel<GE, decltype(bnc)::value, decltype(splitc)::value, false>), grid, dim3(256), 0, stream, t);
         };
         using std::integral_constant;
         if constexpr (EPI != EPI_SWIGLU) {
@@ -493,6 +507,17 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
     const int R = K + 1, M = B * R, dm = d.d_model, F = d.ffn;
     hipLaunchKernelGGL(embed_rmsnorm_kernel, dim3(M), dim3(256), 0, stream, d.emb, d.g1, pending, drafts, draft_len,
                        ids_dev, kv->len, R, dm, d.vocab, d.eps, m->x, m->xn, m->xn_lo, m->row_pos);
+    if (M > kSkinnyMaxRows && !m->w16[0]) {
+        // first many-row step: widen the four projection matrices to fp16 once (same rounding as the kernels' own)
+        const size_t n[4] = {(size_t)d.n_layers * 3 * dm * dm, (size_t)d.n_layers * dm * dm, (size_t)d.n_layers * 2 * F * dm,
+                             (size_t)d.n_layers * dm * F};
+        const uint16_t* src[4] = {d.wqkv, d.wo, d.wgu, d.wdown};
+        for (int i = 0; i < 4; ++i) {
+            LASER_HIP_CHECK(hipMalloc((void**)&m->w16[i], n[i] * 2));
+            hipLaunchKernelGGL(widen_weights_kernel, dim3(2048), dim3(256), 0, stream, src[i], m->w16[i], n[i] / 8);
+        }
+        LASER_HIP_CHECK(hipGetLastError());
+    }
     const int nqt = (R + 15) / 16;
     const int npages_ub = (max_len_ub + R + kPageSize - 1) / kPageSize;
     const int nsplit = std::max(1, (npages_ub + kSplitPages - 1) / kSplitPages);
@@ -507,7 +532,8 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
         int rc;
         if (l > 0)
             hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.g1 + (size_t)l * dm, dm, d.eps, m->xn, m->xn_lo);
-        GemmArgs g{d.wqkv + (size_t)l * 3 * dm * dm, m->xn, m->xn_lo, M, 3 * dm, dm, 1, m->qkv, nullptr};
+        const bool many = M > kSkinnyMaxRows;      // tiled path: weights from the fp16 copy
+        GemmArgs g{d.wqkv + (size_t)l * 3 * dm * dm, many ? m->w16[0] + (size_t)l * 3 * dm * dm : nullptr, m->xn, m->xn_lo, M, 3 * dm, dm, 1, m->qkv, nullptr};
         if ((rc = launch_gemm<EPI_F32>(g, stream))) return rc;
         RopeArgs ra{m->qkv, m->row_pos, ids_dev, kv->block_table, m->rope, m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages,
                     R, dm, d.n_heads, m->dh, kv->d.max_pages_per_seq, l, kv->d.n_pages};
@@ -522,18 +548,18 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
             if (m->dh == 128) hipLaunchKernelGGL(attn_combine_kernel<128>, cg, dim3(256), 0, stream, aa);
             else hipLaunchKernelGGL(attn_combine_kernel<64>, cg, dim3(256), 0, stream, aa);
         }
-        GemmArgs go{d.wo + (size_t)l * dm * dm, m->attn, m->attn_lo, M, dm, dm, 1, m->x, nullptr};
+        GemmArgs go{d.wo + (size_t)l * dm * dm, many ? m->w16[1] + (size_t)l * dm * dm : nullptr, m->attn, m->attn_lo, M, dm, dm, 1, m->x, nullptr};
         if ((rc = launch_gemm<EPI_RESID>(go, stream))) return rc;
         hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.g2 + (size_t)l * dm, dm, d.eps, m->xn, m->xn_lo);
         // On the tiled many-row path a split operand doubles the matrix work; gate/up (45 % of the layer's
         // flops) takes the single fp16 rows there unless option "split_ffn" asks for the split (see set_option).
         const bool split_gu = M <= kSkinnyMaxRows || m->split_ffn;
-        GemmArgs gg{d.wgu + (size_t)l * 2 * F * dm, m->xn, split_gu ? m->xn_lo : nullptr, M, F, dm, 1, nullptr, m->act};
+        GemmArgs gg{d.wgu + (size_t)l * 2 * F * dm, many ? m->w16[2] + (size_t)l * 2 * F * dm : nullptr, m->xn, split_gu ? m->xn_lo : nullptr, M, F, dm, 1, nullptr, m->act};
         const bool prof = m->prof_on && m->prof_n < m->prof_cap;
         if (prof) LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n], stream));
         if ((rc = launch_gemm<EPI_SWIGLU>(gg, stream))) return rc;
         if (prof) { LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n + 1], stream)); ++m->prof_n; }
-        GemmArgs gd{d.wdown + (size_t)l * dm * F, m->act, nullptr, M, dm, F, 1, m->x, nullptr};
+        GemmArgs gd{d.wdown + (size_t)l * dm * F, many ? m->w16[3] + (size_t)l * dm * F : nullptr, m->act, nullptr, M, dm, F, 1, m->x, nullptr};
         if ((rc = launch_gemm<EPI_RESID>(gd, stream))) return rc;
     }
     hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.gf, dm, d.eps, m->xn, (uint16_t*)nullptr);
@@ -548,7 +574,7 @@ using namespace laser;
 extern "C" int laser_model_destroy(laser_model* h) {
     if (!h) return LASER_OK;
     Model* m = reinterpret_cast<Model*>(h);
-    void* ptrs[] = {m->x, m->xn, m->xn_lo, m->q_lo, m->attn_lo, m->qkv, m->q, m->attn, m->act, m->row_pos, m->att_part, m->rope, m->hp_max,
+    void* ptrs[] = {m->w16[0], m->w16[1], m->w16[2], m->w16[3], m->x, m->xn, m->xn_lo, m->q_lo, m->attn_lo, m->qkv, m->q, m->attn, m->act, m->row_pos, m->att_part, m->rope, m->hp_max,
                     m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx, m->row_x, m->logits_ws};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     for (hipEvent_t e : m->prof_ev) (void)hipEventDestroy(e);

@@ -74,6 +74,8 @@ struct Model {
     void* fused_ws = nullptr;          // workspace of the persistent few-row kernel (fused.hip)
     int use_fused = 1;                 // 0 forces the generic multi-kernel path
     int fused_trace = 0;               // 1: thread 0 of every workgroup stamps the wall clock at phase edges
+    uint16_t* w16[4] = {nullptr, nullptr, nullptr, nullptr};   // fp16 copies of wqkv, wo, wgu, wdown for the tiled many-row
+                                                               // kernels, made at the first step with more than 80 rows
     int split_ffn = 0;                 // 1: the many-row (tiled) gate/up product also takes split activations
 };
 
