@@ -127,7 +127,8 @@ typedef struct laser_model_desc {
 
 /* Supported: head_dim 64 or 128; d_model, ffn multiples of 128; vocab multiple of 16 (else
  * LASER_E_SHAPE). Allocates workspace and the RoPE table; synchronises `stream`. n_layers may be 0
- * (head-only use). */
+ * (head-only use). The first verify step with more than 80 rows additionally allocates an fp16 copy
+ * of the four projection matrices (2 bytes per parameter) for the tiled many-row kernels. */
 int laser_model_create(const laser_model_desc* desc, void* stream, laser_model** out);
 int laser_model_destroy(laser_model* model);
 
@@ -135,6 +136,8 @@ int laser_model_destroy(laser_model* model);
  * Paged KV cache. A sequence slot owns a list of pages (page_size tokens each); `len` tokens are
  * committed, the next R slots are scratch for the step in flight. Pages are reserved from the host
  * without reading device state: the library keeps, per slot, an upper bound of `len`.
+ * Storage per token, layer and channel: key fp16 + an 8-bit low part (the key is kept to about 14
+ * significant bits, which the logit tolerance needs at 32 layers), value fp16: 5 bytes.
  */
 typedef struct laser_kv_desc {
     int32_t n_layers, n_heads, head_dim;
@@ -207,7 +210,10 @@ int laser_ctx_advance(int32_t* ctx_tail, int32_t* pending, const int32_t* out_to
                       const int32_t* accept_len, int B, int K, int n_max, void* stream);
 
 /* Options: "fused" = 1 (default) lets laser_verify_step use the persistent whole-step kernel when
- * B*(K+1) <= 16; 0 forces the general multi-kernel path. Both compute the same function. */
+ * B*(K+1) <= 16; 0 forces the general multi-kernel path. Both compute the same function.
+ * "split_ffn" = 1 makes the many-row (more than 80 rows) gate/up product take its input rows as two
+ * fp16 planes like the other products (default 0: single fp16 there, which halves that product's
+ * matrix work; with up to 80 rows the input is always split). */
 int laser_model_set_option(laser_model* model, const char* name, int value);
 /* Phase trace of the persistent kernel (option "fused_trace" = 1): thread 0 of every workgroup stamps
  * the 100 MHz wall clock before and after every grid barrier. Copies the stamps of the most recent

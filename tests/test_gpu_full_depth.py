@@ -88,5 +88,8 @@ def test_latency_configuration_full_depth(weights_7b, fused):
     _check("c3", weights_7b, fused)
 
 
-def test_many_row_path_full_depth(weights_7b):
-    _check("many", weights_7b, 0)
+@pytest.mark.parametrize("split_ffn", [0, 1])
+def test_many_row_path_full_depth(weights_7b, split_ffn):
+    """108 rows: tiled matrix-core GEMMs. By default the gate/up product takes single fp16 rows there
+    (option split_ffn = 0); both settings must stay inside the tolerance."""
+    _check("many", weights_7b, 0, options=(("split_ffn", split_ffn),))
