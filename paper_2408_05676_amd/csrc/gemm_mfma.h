@@ -45,6 +45,9 @@ struct GemmTileArgs {
 
 enum { GEPI_F32 = 0, GEPI_RESID = 1, GEPI_SWIGLU = 2 };
 
+// workgroups of a launch: 8 x the largest per-XCD tile count (n-tiles are dealt round-robin to the XCDs)
+inline unsigned gemm_mfma_grid(int tiles_m, int tiles_n) { return 8u * (unsigned)(((tiles_n + 7) / 8) * tiles_m); }
+
 __device__ inline float16_t mfma_32x32x16(const Frag8& a, const Frag8& b, float16_t c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(a.v, b.v, c, 0, 0, 0);
 }
@@ -88,12 +91,20 @@ __global__ __launch_bounds__(256, SPLIT ? 2 : GM_WGS) void gemm_mfma_kernel(Gemm
     __shared__ __attribute__((aligned(16))) uint16_t sA[2][GM_BM][GM_LD];
     __shared__ __attribute__((aligned(16))) uint16_t sB[2][BN][GM_LD];
     __shared__ __attribute__((aligned(16))) uint16_t sAl[SPLIT ? 2 : 1][SPLIT ? GM_BM : 1][SPLIT ? GM_LD : 8];
-    // ---- XCD-aware tile order ----
-    const int total = a.tiles_m * a.tiles_n;
-    const int per_xcd = (total + 7) / 8;
-    const int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (v >= total) return;
-    const int tn = v / a.tiles_m, tm = v % a.tiles_m;
+    // ---- XCD-aware tile order, longest tiles first ----
+    // n-tile tn belongs to XCD tn % 8 (consecutive workgroup ids go round-robin over the XCDs). Inside an XCD the
+    // workgroups come in dispatch order: first every FULL m-tile of every owned n-tile (m fastest, so the m-tiles
+    // that share a weight tile run together and hit it in L2), then the ragged last m-tiles, whose dead waves make
+    // them finish in about half the time: issued last they fill the tail of the launch instead of holding slots
+    // that full tiles are waiting for (704 rows: QKV 199 -> 189 us, gate/up 169 -> 167 us).
+    const int xcd = blockIdx.x % 8, li = blockIdx.x / 8;
+    const int nt_x = (a.tiles_n - xcd + 7) / 8;                 // n-tiles owned by this XCD
+    const bool ragged = a.M % GM_BM != 0 && a.tiles_m > 1;
+    const int full_m = ragged ? a.tiles_m - 1 : a.tiles_m;
+    if (li >= nt_x * a.tiles_m) return;
+    int tn, tm;
+    if (li < nt_x * full_m) { tn = xcd + 8 * (li / full_m); tm = li % full_m; }
+    else { tn = xcd + 8 * (li - nt_x * full_m); tm = a.tiles_m - 1; }
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = wave >> 1, wn = wave & 1;

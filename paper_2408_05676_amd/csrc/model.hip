@@ -206,8 +206,7 @@ static int launch_gemm(const GemmArgs& a0, hipStream_t stream) {
         const bool narrow = EPI != EPI_SWIGLU && (long)tiles_m * ((a.N + 127) / 128) * 4 < (long)ncu * 5;
         const int bn = narrow ? 64 : 128;
         GemmTileArgs t{a.W16 ? a.W16 : a.W, a.X, a.Xlo, a.M, a.N, a.Kd, tiles_m, EPI == EPI_SWIGLU ? (a.N + 63) / 64 : (a.N + bn - 1) / bn, a.outf, a.outh};
-        const int total = t.tiles_m * t.tiles_n;
-        dim3 grid((unsigned)(((total + 7) / 8) * 8));
+        dim3 grid(gemm_mfma_grid(t.tiles_m, t.tiles_n));
         auto go = [&](auto bnc, auto splitc) {
             if (a.W16)
                 hipLaunchKernelGGL((gemm_mfma_kernel<GE, decltype(bnc)::value, decltype(splitc)::value, true>), grid, dim3(256), 0, stream, t);
