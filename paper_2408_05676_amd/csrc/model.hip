@@ -320,6 +320,7 @@ struct AttnArgs {
     const int32_t* seq_ids; const int32_t* lens; const int32_t* block_table;
     uint16_t* out; uint16_t* out_lo; float* part;
     int R, d, H, mpps, layer, n_pages, nsplit, nqt;
+    int split_pages;       // pages per context split (kSplitPages, or "all" when the launch is not split)
     float scale;
 };
 
@@ -343,7 +344,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     // A split is always kSplitPages pages at fixed positions, so the order in which a row's scores are
     // reduced depends on the row's position only (not on the batch, the draft count or the host's
     // length bound): verifying a token as a draft reproduces its one-at-a-time logits bit for bit.
-    const int p0 = split * kSplitPages, p1 = min(npages, p0 + kSplitPages);
+    const int p0 = split * a.split_pages, p1 = min(npages, p0 + a.split_pages);
 
     Frag8 bq[NC32], bql[NC32];
     {
@@ -519,7 +520,14 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
     }
     const int nqt = (R + 15) / 16;
     const int npages_ub = (max_len_ub + R + kPageSize - 1) / kPageSize;
-    const int nsplit = std::max(1, (npages_ub + kSplitPages - 1) / kSplitPages);
+    // With enough (sequence, head, query tile) triples to fill the chip several times over, the context is not
+    // split: no partials, no combine kernel. (The split policy is a function of the launch shape only, so steps
+    // of one shape stay bit-identical to each other; different batch sizes may differ in the last bits.)
+    int ncu = 0;
+    LASER_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, 0));
+    const bool whole = (long)B * d.n_heads * nqt >= 4L * ncu;
+    const int split_pages = whole ? (1 << 20) : kSplitPages;
+    const int nsplit = whole ? 1 : std::max(1, (npages_ub + kSplitPages - 1) / kSplitPages);
     const size_t part_need = (size_t)B * d.n_heads * nqt * nsplit * (32 + 16 * m->dh);
     if (nsplit > 1 && part_need > m->att_part_floats) {
         if (m->att_part) LASER_HIP_CHECK(hipFree(m->att_part));
@@ -538,7 +546,7 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
                     R, dm, d.n_heads, m->dh, kv->d.max_pages_per_seq, l, kv->d.n_pages};
         hipLaunchKernelGGL(rope_kv_kernel, dim3(M), dim3(256), 0, stream, ra);
         AttnArgs aa{m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages, ids_dev, kv->len, kv->block_table, m->attn, m->attn_lo, m->att_part,
-                    R, dm, d.n_heads, kv->d.max_pages_per_seq, l, kv->d.n_pages, nsplit, nqt, 1.0f / sqrtf((float)m->dh)};
+                    R, dm, d.n_heads, kv->d.max_pages_per_seq, l, kv->d.n_pages, nsplit, nqt, split_pages, 1.0f / sqrtf((float)m->dh)};
         dim3 ag(d.n_heads, B, nsplit * nqt);
         if (m->dh == 128) hipLaunchKernelGGL(attn_kernel<128>, ag, dim3(256), 0, stream, aa);
         else hipLaunchKernelGGL(attn_kernel<64>, ag, dim3(256), 0, stream, aa);
