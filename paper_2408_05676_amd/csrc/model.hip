@@ -263,27 +263,59 @@ struct RopeArgs {
     const float* qkv; const int32_t* row_pos; const int32_t* seq_ids; const int32_t* block_table;
     const float2* rope; uint16_t* q; uint16_t* q_lo; uint16_t* kpages; uint8_t* klpages; uint16_t* vpages;
     int R, d, H, dh, mpps, layer, n_pages;
+    int M, ny, B;          // rows, blocks per row; blocks past M * ny write the values (see below)
 };
 
+// Values. The cache keeps them channel-major ([dh][16 tokens] per page and head), so one row's values are 2-byte
+// pieces 32 bytes apart: written row by row they cost a partial-sector write each (2.9 M of them at 704 rows).
+// Instead a thread owns one (sequence, head, channel): it reads that channel's 32-byte page row, replaces the
+// slots of the sequence's R new tokens and writes the row back, so all loads and stores are whole 16-byte pieces
+// and a wave covers 2 KiB of contiguous page memory.
+__device__ inline void write_values(const RopeArgs& a, int blk) {
+    const int per_blk = 256 / a.dh;                         // (sequence, head) items per block
+    const int item = blk * per_blk + (int)threadIdx.x / a.dh, c = (int)threadIdx.x % a.dh;
+    if (item >= a.B * a.H) return;
+    const int b = item / a.H, h = item % a.H;
+    const int pos0 = a.row_pos[b * a.R];                    // slot of the sequence's first row
+    const int32_t* bt = a.block_table + (size_t)a.seq_ids[b] * a.mpps;
+    const float* v = a.qkv + (size_t)b * a.R * 3 * a.d + 2 * a.d + (size_t)h * a.dh + c;
+    for (int pg = pos0 / kPageSize; pg <= (pos0 + a.R - 1) / kPageSize; ++pg) {
+        uint16_t* rowp = a.vpages + ((((size_t)a.layer * a.n_pages + bt[pg]) * a.H + h) * a.dh + c) * kPageSize;
+        Frag8 lo, hi;                                       // tokens 0..7 and 8..15 of the page
+        lo.u = reinterpret_cast<const uint4*>(rowp)[0];
+        hi.u = reinterpret_cast<const uint4*>(rowp)[1];
+#pragma unroll
+        for (int tp = 0; tp < kPageSize; ++tp) {
+            const int r = pg * kPageSize + tp - pos0;
+            if (r >= 0 && r < a.R) {
+                const uint16_t val = f32_to_f16(v[(size_t)r * 3 * a.d]);
+                if (tp < 8) lo.h[tp & 7] = val; else hi.h[tp & 7] = val;
+            }
+        }
+        reinterpret_cast<uint4*>(rowp)[0] = lo.u;
+        reinterpret_cast<uint4*>(rowp)[1] = hi.u;
+    }
+}
+
 __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a) {
-    const int m = blockIdx.x, b = m / a.R;
+    if ((int)blockIdx.x >= a.M * a.ny) { write_values(a, (int)blockIdx.x - a.M * a.ny); return; }
+    const int m = blockIdx.x / a.ny, by = blockIdx.x % a.ny, b = m / a.R;
     const int pos = a.row_pos[m];
     const int pg = a.block_table[(size_t)a.seq_ids[b] * a.mpps + pos / kPageSize], tp = pos % kPageSize;
     const int half = a.dh / 2;                            // a multiple of 4 (dh is 64 or 128)
     const float* row = a.qkv + (size_t)m * 3 * a.d;
     // a thread takes 4 consecutive rotary pairs (i .. i+3, partners at + half) of one head: 16-byte loads, 8-byte stores
-    for (int idx = threadIdx.x * 4; idx < a.d / 2; idx += 256 * 4) {
+    // ny blocks share a row (each takes every ny-th group of 1024 rotary pairs)
+    for (int idx = (by * 256 + threadIdx.x) * 4; idx < a.d / 2; idx += a.ny * 256 * 4) {
         const int h = idx / half, i = idx % half;
         const int c0 = h * a.dh + i, c1 = c0 + half;
         const float4 csa = *reinterpret_cast<const float4*>(a.rope + (size_t)pos * half + i);       // (cos, sin) x 2
         const float4 csb = *reinterpret_cast<const float4*>(a.rope + (size_t)pos * half + i + 2);
         const float4 qa = *reinterpret_cast<const float4*>(row + c0), qb = *reinterpret_cast<const float4*>(row + c1);
         const float4 ka = *reinterpret_cast<const float4*>(row + a.d + c0), kb = *reinterpret_cast<const float4*>(row + a.d + c1);
-        const float4 va = *reinterpret_cast<const float4*>(row + 2 * a.d + c0), vb = *reinterpret_cast<const float4*>(row + 2 * a.d + c1);
         const float co[4] = {csa.x, csa.z, csb.x, csb.z}, si[4] = {csa.y, csa.w, csb.y, csb.w};
         const float q0[4] = {qa.x, qa.y, qa.z, qa.w}, q1[4] = {qb.x, qb.y, qb.z, qb.w};
         const float k0[4] = {ka.x, ka.y, ka.z, ka.w}, k1[4] = {kb.x, kb.y, kb.z, kb.w};
-        const float v0[4] = {va.x, va.y, va.z, va.w}, v1[4] = {vb.x, vb.y, vb.z, vb.w};
         Frag4 oq0, oq1, ok0, ok1, lq0, lq1, lk0, lk1;     // queries and keys are split (hi, lo planes)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -304,11 +336,6 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a) {
             f16_to_b8(lk0.h[0]) | (f16_to_b8(lk0.h[1]) << 8) | (f16_to_b8(lk0.h[2]) << 16) | (f16_to_b8(lk0.h[3]) << 24);
         *reinterpret_cast<uint32_t*>(a.klpages + base + (size_t)tp * a.dh + i + half) =
             f16_to_b8(lk1.h[0]) | (f16_to_b8(lk1.h[1]) << 8) | (f16_to_b8(lk1.h[2]) << 16) | (f16_to_b8(lk1.h[3]) << 24);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            a.vpages[base + (size_t)(i + j) * kPageSize + tp] = f32_to_f16(v0[j]);
-            a.vpages[base + (size_t)(i + j + half) * kPageSize + tp] = f32_to_f16(v1[j]);
-        }
     }
 }
 
@@ -543,8 +570,10 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
         GemmArgs g{d.wqkv + (size_t)l * 3 * dm * dm, many ? m->w16[0] + (size_t)l * 3 * dm * dm : nullptr, m->xn, m->xn_lo, M, 3 * dm, dm, 1, m->qkv, nullptr};
         if ((rc = launch_gemm<EPI_F32>(g, stream))) return rc;
         RopeArgs ra{m->qkv, m->row_pos, ids_dev, kv->block_table, m->rope, m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages,
-                    R, dm, d.n_heads, m->dh, kv->d.max_pages_per_seq, l, kv->d.n_pages};
-        hipLaunchKernelGGL(rope_kv_kernel, dim3(M), dim3(256), 0, stream, ra);
+                    R, dm, d.n_heads, m->dh, kv->d.max_pages_per_seq, l, kv->d.n_pages,
+                    M, std::max(1, std::min(4, dm / 2048)), B};
+        const int v_blocks = (B * d.n_heads + 256 / m->dh - 1) / (256 / m->dh);
+        hipLaunchKernelGGL(rope_kv_kernel, dim3((unsigned)(M * ra.ny + v_blocks)), dim3(256), 0, stream, ra);
         AttnArgs aa{m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages, ids_dev, kv->len, kv->block_table, m->attn, m->attn_lo, m->att_part,
                     R, dm, d.n_heads, kv->d.max_pages_per_seq, l, kv->d.n_pages, nsplit, nqt, split_pages, 1.0f / sqrtf((float)m->dh)};
         dim3 ag(d.n_heads, B, nsplit * nqt);
