@@ -272,7 +272,7 @@ def run_workload(args, name, steps, warmup, weights_cache):
         "metric": "accepted tokens/s per verify step (7B shape, bs 1 & 64); % HBM / MFMA peak",
         "value": value, "unit": "accepted tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": elapsed * 1e3 / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 weights x fp16 activations, fp32 accumulate", "data": "synthetic",
+        "dtype": "bf16 weights x fp16 activations (two-plane split where single fp16 is too coarse), fp32 accumulate", "data": "synthetic",
         "config": {"workload": wl["label"], "batch": B, "context": ctx_len, "K": K, "regime": args.regime,
                    "topk": topk, "p": p, "lm_gain": gain, "replay_noise": replay_noise if args.regime != "floor" else None,
                    "tokens_per_step": tokens_per_step, "accepted_drafts_per_step": tokens_per_step - 1.0,

@@ -354,7 +354,7 @@ struct AttnArgs {
 constexpr int kSplitPages = 16;   // pages (of 16 tokens) per context split
 
 template <int DH>
-__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, 4) void attn_kernel(AttnArgs a) {
     constexpr int NC32 = DH / 32, NC16 = DH / 16;
     __shared__ float sm_m[4][16], sm_l[4][16];
     __shared__ float sm_o[4][16][DH];
