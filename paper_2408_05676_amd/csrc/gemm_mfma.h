@@ -38,7 +38,10 @@ struct GemmTileArgs {
     const uint16_t* X;      // [M][Kd] fp16
     const uint16_t* Xlo;    // [M][Kd] low plane of split activations (x = X + Xlo / 4096), SPLIT kernels only
     int M, N, Kd;
-    int tiles_m, tiles_n;   // tiles_n counts BN-column tiles (SwiGLU: 64-feature tiles)
+    int tiles_m, tiles_n;   // tiles_n counts BN-column tiles (SwiGLU: 64-feature tiles), times ksplit
+    int ksplit;             // > 1: the reduction is cut into ksplit equal parts, each a unit of its own that STORES its
+                            // partial result at outf + part * M * N (store epilogue only; the consumer adds the parts
+                            // in a fixed order). It evens out tile counts that do not fill the chip's slots.
     float* outf;            // EPI_F32: [M][N] store; EPI_RESID: [M][N] accumulate
     uint16_t* outh;         // EPI_SWIGLU: [M][N] fp16
 };
@@ -105,6 +108,8 @@ __global__ __launch_bounds__(256, SPLIT ? 2 : GM_WGS) void gemm_mfma_kernel(Gemm
     int tn, tm;
     if (li < nt_x * full_m) { tn = xcd + 8 * (li / full_m); tm = li % full_m; }
     else { tn = xcd + 8 * (li - nt_x * full_m); tm = a.tiles_m - 1; }
+    const int kpart = tn % a.ksplit;          // (n-tile, reduction part) pairs were dealt out as one index
+    tn /= a.ksplit;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = wave >> 1, wn = wave & 1;
@@ -147,7 +152,15 @@ __global__ __launch_bounds__(256, SPLIT ? 2 : GM_WGS) void gemm_mfma_kernel(Gemm
     // Register ring of D k-steps. The element type must be a native vector: an array of HIP's uint4
     // (a struct) that is only copied as a whole is not promoted to registers and lands in scratch.
     u32x4 ra[D][ST], rb[D][STB], rl[D][SPLIT ? ST : 1];
-    const int nk = a.Kd / GM_BK;             // the host guarantees Kd % GM_BK == 0
+    const int nk = a.Kd / GM_BK / a.ksplit;  // the host guarantees Kd % (GM_BK * ksplit) == 0
+    {
+        const int k0 = kpart * nk * GM_BK;
+#pragma unroll
+        for (int i = 0; i < ST; ++i) { xa[i] += k0; if constexpr (SPLIT) xl[i] += k0; }
+#pragma unroll
+        for (int i = 0; i < STB; ++i) wb[i] += k0;
+    }
+    float* const outf = a.outf ? a.outf + (size_t)kpart * a.M * a.N : nullptr;
     auto gload = [&](auto slot_c, int kt) {
         constexpr int slot = decltype(slot_c)::value;
         kt = kt < nk ? kt : nk - 1;          // unconditional, clamped: a load under a branch would be waited for at once
@@ -271,7 +284,7 @@ __global__ __launch_bounds__(256, SPLIT ? 2 : GM_WGS) void gemm_mfma_kernel(Gemm
                 for (int j = 0; j < NJ; ++j) {
                     const int col = tn * BN + wn * WN + j * 32 + lr;
                     if (col < a.N) {
-                        float* p = a.outf + (size_t)row * a.N + col;
+                        float* p = outf + (size_t)row * a.N + col;
                         if (EPI == GEPI_RESID) *p += acc[i][j][e];
                         else *p = acc[i][j][e];
                     }

@@ -314,7 +314,7 @@ int run_head(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* 
             logits = m->logits_ws;
         }
         const int tiles_m = (M + GM_BM - 1) / GM_BM, tiles_n = (m->d.vocab + 127) / 128;
-        GemmTileArgs t{m->d.wlm, h, nullptr, M, m->d.vocab, m->d.d_model, tiles_m, tiles_n, logits, nullptr};
+        GemmTileArgs t{m->d.wlm, h, nullptr, M, m->d.vocab, m->d.d_model, tiles_m, tiles_n, 1, logits, nullptr};
         hipLaunchKernelGGL((gemm_mfma_kernel<GEPI_F32, 128, false>), dim3(gemm_mfma_grid(tiles_m, tiles_n)), dim3(256), 0,
                            stream, t);
         int32_t* row_ok = m->hp_arg;                     // per-row scratch: the streaming path's buffers are free here

@@ -57,10 +57,25 @@ __global__ __launch_bounds__(256) void embed_rmsnorm_kernel(
 }
 
 // xn_lo may be NULL (the final norm feeds the output head, which takes single fp16 rows).
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
-                                                      int d, float eps, uint16_t* __restrict__ xn, uint16_t* __restrict__ xn_lo) {
+// n_part > 0: the projection before this norm left its result as n_part partial sums (part + p * part_stride, same
+// [row][d] layout): they are added to the residual row in order p = 0, 1, .. first, and the row is written back.
+__global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ gain,
+                                                      int d, float eps, uint16_t* __restrict__ xn, uint16_t* __restrict__ xn_lo,
+                                                      const float* __restrict__ part, int n_part, size_t part_stride) {
     __shared__ float sm[4];
     const size_t m = blockIdx.x;
+    if (n_part > 0) {
+        float4* xw = reinterpret_cast<float4*>(x + m * d);
+        for (int i = threadIdx.x; i < d / 4; i += 256) {
+            float4 t = xw[i];
+            for (int p = 0; p < n_part; ++p) {
+                const float4 q = reinterpret_cast<const float4*>(part + p * part_stride + m * d)[i];
+                t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+            }
+            xw[i] = t;
+        }
+        __syncthreads();       // the passes below read what other threads of this block have just written
+    }
     // the row stays in registers between the two passes (up to 8192 columns; d is a multiple of 128)
     constexpr int NV = 8;
     const int n4 = d / 4;
@@ -109,6 +124,10 @@ struct GemmArgs {
     int M, N, Kd, S;
     float* outf;            // EPI_F32: [M][N] store;  EPI_RESID: [M][N] accumulate
     uint16_t* outh;         // EPI_SWIGLU: [M][N] fp16
+    float* part = nullptr;  // many-row path: workspace for reduction-split partial results (store / accumulate epilogues)
+    size_t part_floats = 0;
+    int want_split = 0;     // 0: choose; 1, 2, 4: force this many reduction parts
+    int n_part = 0;         // out: parts left in `part` for the consumer to add up (0: the result is complete)
 };
 
 template <int MB, int EPI, bool SPLIT>
@@ -194,18 +213,61 @@ __global__ __launch_bounds__(256) void widen_weights_kernel(const uint16_t* __re
     }
 }
 
+// Reduction parts for a tiled launch of `tiles` 128 x 128 tiles. Two workgroups share a CU ("slots" = 2 x CUs) and a
+// launch takes ceil(units / slots) rounds; a lone workgroup on a CU runs at about 0.6 of the shared time. Cutting the
+// reduction into S parts makes S times as many units of 1/S the length, which evens out tile counts like 576 (2 rounds
+// for 1.1 rounds of work) or 192 (most slots empty); each part costs one more pass of the output through memory.
+static int choose_ksplit(long tiles, int ksteps, long out_elems, int slots) {
+    int best = 1;
+    double best_cost = 1e30;
+    for (int S = 1; S <= 4; S *= 2) {
+        if (ksteps % S || ksteps / S < 8) continue;
+        if (S > 2 && out_elems > (4L << 20)) continue;          // large outputs: the extra passes cost more than they save
+        const long units = tiles * S;
+        const double rounds = units <= slots / 2 ? 0.6 : (double)((units + slots - 1) / slots);
+        const double cost = rounds / S + 0.04 * (S - 1);
+        if (cost < best_cost - 1e-9) { best_cost = cost; best = S; }
+    }
+    return best;
+}
+
 template <int EPI>
-static int launch_gemm(const GemmArgs& a0, hipStream_t stream) {
-    GemmArgs a = a0;
+static int launch_gemm(GemmArgs& a_in, hipStream_t stream) {
+    GemmArgs& a = a_in;
+    a.n_part = 0;
     if (a.M > kSkinnyMaxRows) {
         constexpr int GE = EPI == EPI_F32 ? GEPI_F32 : (EPI == EPI_RESID ? GEPI_RESID : GEPI_SWIGLU);
         const int tiles_m = (a.M + GM_BM - 1) / GM_BM;
         int ncu = 0;
         LASER_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, 0));
+        using std::integral_constant;
+        if constexpr (EPI != EPI_SWIGLU) {
+            // store / accumulate epilogues may split the reduction: partial results go to the workspace and the
+            // next kernel (rotary + cache write, or the norm) adds them up in a fixed order
+            const int bk = a.Xlo ? 32 : 64;
+            const long tiles = (long)tiles_m * ((a.N + 127) / 128);
+            int S = a.want_split ? a.want_split : choose_ksplit(tiles, a.Kd / bk, (long)a.M * a.N, 2 * ncu);
+            if ((a.Kd / bk) % S || !a.part || (size_t)S * a.M * a.N > a.part_floats) S = 1;
+            if (S > 1) {
+                GemmTileArgs t{a.W16 ? a.W16 : a.W, a.X, a.Xlo, a.M, a.N, a.Kd, tiles_m, ((a.N + 127) / 128) * S, S, a.part, nullptr};
+                dim3 grid(gemm_mfma_grid(t.tiles_m, t.tiles_n));
+                auto gos = [&](auto splitc) {
+                    if (a.W16)
+                        hipLaunchKernelGGL((gemm_mfma_kernel<GEPI_F32, 128, decltype(splitc)::value, true>), grid, dim3(256), 0, stream, t);
+                    else
+                        hipLaunchKernelGGL((gemm_mfma_kernel<GEPI_F32, 128, decltype(splitc)::value, false>), grid, dim3(256), 0, stream, t);
+                };
+                if (a.Xlo) gos(integral_constant<bool, true>{});
+                else gos(integral_constant<bool, false>{});
+                LASER_HIP_CHECK(hipGetLastError());
+                a.n_part = S;
+                return LASER_OK;
+            }
+        }
         // narrow outputs: 128-column tiles would leave compute units without work; 64-column tiles double the count
         const bool narrow = EPI != EPI_SWIGLU && (long)tiles_m * ((a.N + 127) / 128) * 4 < (long)ncu * 5;
         const int bn = narrow ? 64 : 128;
-        GemmTileArgs t{a.W16 ? a.W16 : a.W, a.X, a.Xlo, a.M, a.N, a.Kd, tiles_m, EPI == EPI_SWIGLU ? (a.N + 63) / 64 : (a.N + bn - 1) / bn, a.outf, a.outh};
+        GemmTileArgs t{a.W16 ? a.W16 : a.W, a.X, a.Xlo, a.M, a.N, a.Kd, tiles_m, EPI == EPI_SWIGLU ? (a.N + 63) / 64 : (a.N + bn - 1) / bn, 1, a.outf, a.outh};
         dim3 grid(gemm_mfma_grid(t.tiles_m, t.tiles_n));
         auto go = [&](auto bnc, auto splitc) {
             if (a.W16)
@@ -213,7 +275,6 @@ static int launch_gemm(const GemmArgs& a0, hipStream_t stream) {
             else
                 hipLaunchKernelGGL((gemm_mfma_kernel<GE, decltype(bnc)::value, decltype(splitc)::value, false>), grid, dim3(256), 0, stream, t);
         };
-        using std::integral_constant;
         if constexpr (EPI != EPI_SWIGLU) {
             if (narrow) {
                 if (a.Xlo) go(integral_constant<int, 64>{}, integral_constant<bool, true>{});
@@ -264,7 +325,18 @@ struct RopeArgs {
     const float2* rope; uint16_t* q; uint16_t* q_lo; uint16_t* kpages; uint8_t* klpages; uint16_t* vpages;
     int R, d, H, dh, mpps, layer, n_pages;
     int M, ny, B;          // rows, blocks per row; blocks past M * ny write the values (see below)
+    int n_part;            // > 1: qkv holds that many partial results, n_part_stride floats apart, to be added in order
+    size_t part_stride;
 };
+
+__device__ inline float4 ld4_sum(const float* p, int n_part, size_t stride) {
+    float4 t = *reinterpret_cast<const float4*>(p);
+    for (int s = 1; s < n_part; ++s) {
+        const float4 q = *reinterpret_cast<const float4*>(p + s * stride);
+        t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+    }
+    return t;
+}
 
 // Values. The cache keeps them channel-major ([dh][16 tokens] per page and head), so one row's values are 2-byte
 // pieces 32 bytes apart: written row by row they cost a partial-sector write each (2.9 M of them at 704 rows).
@@ -288,7 +360,9 @@ __device__ inline void write_values(const RopeArgs& a, int blk) {
         for (int tp = 0; tp < kPageSize; ++tp) {
             const int r = pg * kPageSize + tp - pos0;
             if (r >= 0 && r < a.R) {
-                const uint16_t val = f32_to_f16(v[(size_t)r * 3 * a.d]);
+                float vs = v[(size_t)r * 3 * a.d];
+                for (int s = 1; s < a.n_part; ++s) vs += v[(size_t)r * 3 * a.d + s * a.part_stride];
+                const uint16_t val = f32_to_f16(vs);
                 if (tp < 8) lo.h[tp & 7] = val; else hi.h[tp & 7] = val;
             }
         }
@@ -311,8 +385,8 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a) {
         const int c0 = h * a.dh + i, c1 = c0 + half;
         const float4 csa = *reinterpret_cast<const float4*>(a.rope + (size_t)pos * half + i);       // (cos, sin) x 2
         const float4 csb = *reinterpret_cast<const float4*>(a.rope + (size_t)pos * half + i + 2);
-        const float4 qa = *reinterpret_cast<const float4*>(row + c0), qb = *reinterpret_cast<const float4*>(row + c1);
-        const float4 ka = *reinterpret_cast<const float4*>(row + a.d + c0), kb = *reinterpret_cast<const float4*>(row + a.d + c1);
+        const float4 qa = ld4_sum(row + c0, a.n_part, a.part_stride), qb = ld4_sum(row + c1, a.n_part, a.part_stride);
+        const float4 ka = ld4_sum(row + a.d + c0, a.n_part, a.part_stride), kb = ld4_sum(row + a.d + c1, a.n_part, a.part_stride);
         const float co[4] = {csa.x, csa.z, csb.x, csb.z}, si[4] = {csa.y, csa.w, csb.y, csb.w};
         const float q0[4] = {qa.x, qa.y, qa.z, qa.w}, q1[4] = {qb.x, qb.y, qb.z, qb.w};
         const float k0[4] = {ka.x, ka.y, ka.z, ka.w}, k1[4] = {kb.x, kb.y, kb.z, kb.w};
@@ -545,6 +619,12 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
         }
         LASER_HIP_CHECK(hipGetLastError());
     }
+    if (M > kSkinnyMaxRows && !m->kpart) {
+        // workspace for reduction-split partial results: up to 4 parts of [max_rows][d] or 2 of [max_rows][3 d]
+        m->kpart_floats = (size_t)d.max_rows * dm * 6;
+        LASER_HIP_CHECK(hipMalloc((void**)&m->kpart, m->kpart_floats * 4));
+    }
+    int pend = 0;              // partial results of the last down projection still to be added to the residual
     const int nqt = (R + 15) / 16;
     const int npages_ub = (max_len_ub + R + kPageSize - 1) / kPageSize;
     // With enough (sequence, head, query tile) triples to fill the chip several times over, the context is not
@@ -565,13 +645,16 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
     for (int l = 0; l < d.n_layers; ++l) {
         int rc;
         if (l > 0)
-            hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.g1 + (size_t)l * dm, dm, d.eps, m->xn, m->xn_lo);
+            hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.g1 + (size_t)l * dm, dm, d.eps, m->xn, m->xn_lo,
+                               (const float*)m->kpart, pend, (size_t)M * dm);
+        pend = 0;
         const bool many = M > kSkinnyMaxRows;      // tiled path: weights from the fp16 copy
         GemmArgs g{d.wqkv + (size_t)l * 3 * dm * dm, many ? m->w16[0] + (size_t)l * 3 * dm * dm : nullptr, m->xn, m->xn_lo, M, 3 * dm, dm, 1, m->qkv, nullptr};
+        g.part = m->kpart; g.part_floats = m->kpart_floats; g.want_split = m->ksplit_opt[0];
         if ((rc = launch_gemm<EPI_F32>(g, stream))) return rc;
-        RopeArgs ra{m->qkv, m->row_pos, ids_dev, kv->block_table, m->rope, m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages,
+        RopeArgs ra{g.n_part ? m->kpart : m->qkv, m->row_pos, ids_dev, kv->block_table, m->rope, m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages,
                     R, dm, d.n_heads, m->dh, kv->d.max_pages_per_seq, l, kv->d.n_pages,
-                    M, std::max(1, std::min(4, dm / 2048)), B};
+                    M, std::max(1, std::min(4, dm / 2048)), B, std::max(1, g.n_part), (size_t)M * 3 * dm};
         const int v_blocks = (B * d.n_heads + 256 / m->dh - 1) / (256 / m->dh);
         hipLaunchKernelGGL(rope_kv_kernel, dim3((unsigned)(M * ra.ny + v_blocks)), dim3(256), 0, stream, ra);
         AttnArgs aa{m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages, ids_dev, kv->len, kv->block_table, m->attn, m->attn_lo, m->att_part,
@@ -585,8 +668,10 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
             else hipLaunchKernelGGL(attn_combine_kernel<64>, cg, dim3(256), 0, stream, aa);
         }
         GemmArgs go{d.wo + (size_t)l * dm * dm, many ? m->w16[1] + (size_t)l * dm * dm : nullptr, m->attn, m->attn_lo, M, dm, dm, 1, m->x, nullptr};
+        go.part = m->kpart; go.part_floats = m->kpart_floats; go.want_split = m->ksplit_opt[1];
         if ((rc = launch_gemm<EPI_RESID>(go, stream))) return rc;
-        hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.g2 + (size_t)l * dm, dm, d.eps, m->xn, m->xn_lo);
+        hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.g2 + (size_t)l * dm, dm, d.eps, m->xn, m->xn_lo,
+                           (const float*)m->kpart, go.n_part, (size_t)M * dm);
         // On the tiled many-row path a split operand doubles the matrix work; gate/up (45 % of the layer's
         // flops) takes the single fp16 rows there unless option "split_ffn" asks for the split (see set_option).
         const bool split_gu = M <= kSkinnyMaxRows || m->split_ffn;
@@ -596,9 +681,12 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
         if ((rc = launch_gemm<EPI_SWIGLU>(gg, stream))) return rc;
         if (prof) { LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n + 1], stream)); ++m->prof_n; }
         GemmArgs gd{d.wdown + (size_t)l * dm * F, many ? m->w16[3] + (size_t)l * dm * F : nullptr, m->act, nullptr, M, dm, F, 1, m->x, nullptr};
+        gd.part = m->kpart; gd.part_floats = m->kpart_floats; gd.want_split = m->ksplit_opt[2];
         if ((rc = launch_gemm<EPI_RESID>(gd, stream))) return rc;
+        pend = gd.n_part;        // added to the residual by the next norm (next layer's, or the final one)
     }
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.gf, dm, d.eps, m->xn, (uint16_t*)nullptr);
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.gf, dm, d.eps, m->xn, (uint16_t*)nullptr,
+                       (const float*)m->kpart, pend, (size_t)M * dm);
     LASER_HIP_CHECK(hipGetLastError());
     return LASER_OK;
 }
@@ -610,7 +698,7 @@ using namespace laser;
 extern "C" int laser_model_destroy(laser_model* h) {
     if (!h) return LASER_OK;
     Model* m = reinterpret_cast<Model*>(h);
-    void* ptrs[] = {m->w16[0], m->w16[1], m->w16[2], m->w16[3], m->x, m->xn, m->xn_lo, m->q_lo, m->attn_lo, m->qkv, m->q, m->attn, m->act, m->row_pos, m->att_part, m->rope, m->hp_max,
+    void* ptrs[] = {m->kpart, m->w16[0], m->w16[1], m->w16[2], m->w16[3], m->x, m->xn, m->xn_lo, m->q_lo, m->attn_lo, m->qkv, m->q, m->attn, m->act, m->row_pos, m->att_part, m->rope, m->hp_max,
                     m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx, m->row_x, m->logits_ws};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     for (hipEvent_t e : m->prof_ev) (void)hipEventDestroy(e);
@@ -777,6 +865,12 @@ extern "C" int laser_model_set_option(laser_model* mh, const char* name, int val
     if (std::string(name) == "fused") { m->use_fused = value; return LASER_OK; }
     if (std::string(name) == "fused_trace") { m->fused_trace = value; return LASER_OK; }
     if (std::string(name) == "split_ffn") { m->split_ffn = value; return LASER_OK; }
+    for (int i = 0; i < 3; ++i)
+        if (std::string(name) == (i == 0 ? "ksplit_qkv" : i == 1 ? "ksplit_o" : "ksplit_down")) {
+            LASER_REQUIRE(value == 0 || value == 1 || value == 2 || value == 4, LASER_E_INVALID_ARG, "%s must be 0 (choose), 1, 2 or 4", name);
+            m->ksplit_opt[i] = value;
+            return LASER_OK;
+        }
     set_error("unknown option %s", name);
     return LASER_E_INVALID_ARG;
 }

@@ -76,6 +76,9 @@ struct Model {
     int fused_trace = 0;               // 1: thread 0 of every workgroup stamps the wall clock at phase edges
     uint16_t* w16[4] = {nullptr, nullptr, nullptr, nullptr};   // fp16 copies of wqkv, wo, wgu, wdown for the tiled many-row
                                                                // kernels, made at the first step with more than 80 rows
+    float* kpart = nullptr;            // partial results of reduction-split tiled GEMMs (many-row path), [parts][rows][N]
+    size_t kpart_floats = 0;
+    int ksplit_opt[3] = {0, 0, 0};     // forced reduction parts for QKV, O, down (0 = choose from the tile count)
     int split_ffn = 0;                 // 1: the many-row (tiled) gate/up product also takes split activations
 };
 
