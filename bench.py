@@ -251,7 +251,7 @@ def run_workload(args, name, steps, warmup, weights_cache):
         dom_name, dom_work, bound = "verify_fused_kernel (whole verify step)", step_bytes, "hbm"
     elif M <= 80:
         # dominant kernel: the gate/up projection (largest weight stream of every layer), weight-streaming form
-        dom_name, bound = "gemm_skinny_kernel<gate/up SwiGLU>", "hbm"
+        dom_name, bound = ("gemm_mid_kernel" if M > 16 else "gemm_skinny_kernel") + "<gate/up SwiGLU>", "hbm"
         dom_work = 2 * sh.ffn * sh.d * 2 + M * sh.d * 2 + M * sh.ffn * 2
     else:
         # many rows: the same projection runs as the LDS-tiled matrix-core GEMM and is compute-bound

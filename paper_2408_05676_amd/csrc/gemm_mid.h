@@ -1,0 +1,192 @@
+// Weight-streaming GEMM for 17..80 activation rows (MB = 2..5 row tiles of 16):
+//   Y[M][N] = X[M][Kd] * W[N][Kd]^T,  W bf16 (widened to fp16 in registers), X fp16 in one or two planes,
+//   fp32 accumulation on the matrix cores.
+//
+// The few-row kernel (gemm_skinny.h) re-reads the activation rows from L2 at every step: with MB row tiles in two
+// planes that is 2 MB x 64 bytes per lane and step against 64 bytes of weights, and at 72 rows it is bound by L2,
+// not by HBM. Here the four waves of a workgroup own four DIFFERENT 16-row weight tiles and walk the SAME
+// reduction range, so the activation chunk of a step (rows x 128 elements, both planes) is staged once in LDS by
+// the whole workgroup and read from there by every wave; the next chunk and the weight fragments of the next two
+// steps are in flight while the current ones are multiplied (three named fragment sets, the loop unrolled by
+// three: a register copy of a fragment still in flight would make the wave wait for it).
+//
+// blockIdx.y = part of the reduction: with more than one part each workgroup stores its partial result at
+// part + blockIdx.y * M * N and the consumer adds the parts in order (store / accumulate epilogues only).
+// SwiGLU: a gate tile and its up tile go to neighbouring waves (twice the waves, half the registers each); the up
+// wave hands its sums over through LDS at the end.
+#pragma once
+
+#include <type_traits>
+
+#include "gemm_skinny.h"
+
+namespace laser {
+
+enum { EPI_F32 = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
+
+struct GemmMidArgs {
+    const uint16_t* W;      // [N][Kd] bf16  (EPI_SWIGLU: [2N][Kd], gate rows then up rows)
+    const uint16_t* X;      // [M][Kd] fp16
+    const uint16_t* Xlo;    // [M][Kd] low plane of split activations (SPLIT only)
+    int M, N, Kd;           // 16 < M <= 80, N % 16 == 0, Kd % 128 == 0
+    float* outf;            // EPI_F32: [M][N] store;  EPI_RESID: [M][N] accumulate (one part only)
+    uint16_t* outh;         // EPI_SWIGLU: [M][N] fp16
+    float* part;            // gridDim.y > 1: [gridDim.y][M][N] partial results
+};
+
+template <int MB, int EPI, bool SPLIT>
+__global__ __launch_bounds__(256, 2) void gemm_mid_kernel(GemmMidArgs a) {
+    constexpr int ROWS = MB * 16, NP = SPLIT ? 2 : 1;
+    constexpr int LDH = kGemmKStep + 8;   // halves per LDS row: 272 bytes, the 16 rows of a 16-byte read hit distinct banks
+    __shared__ __attribute__((aligned(16))) uint16_t sx[NP * ROWS * LDH];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int r = lane & 15, g = lane >> 4;
+    const int ntiles = a.N / 16;
+    const int vt = blockIdx.x * 4 + wave;
+    const int tile_raw = EPI == EPI_SWIGLU ? vt >> 1 : vt;
+    const int sel = EPI == EPI_SWIGLU ? vt & 1 : 0;          // SwiGLU: 0 = gate rows, 1 = up rows
+    const bool active = tile_raw < ntiles;
+    const int tile = active ? tile_raw : ntiles - 1;        // idle waves stream a valid tile and drop the result
+    const int S = gridDim.y, ks = blockIdx.y;
+    const int ksteps = a.Kd / kGemmKStep, per = (ksteps + S - 1) / S;
+    const int sbeg = ks * per, send = min(ksteps, sbeg + per);
+
+    const uint16_t* const wp = a.W + ((size_t)sel * a.N + (size_t)tile * 16 + r) * a.Kd + g * 32;
+    // staging: piece p = tid + 256 i covers row p / 16, 16-byte column p % 16 of the chunk
+    const uint16_t* xsrc[MB];
+    const uint16_t* xlsrc[MB];
+    int xdst[MB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+        const int p = tid + 256 * i, row = p >> 4, c = p & 15;
+        const int grow = min(row, a.M - 1);
+        xsrc[i] = a.X + (size_t)grow * a.Kd + c * 8;
+        xlsrc[i] = SPLIT ? a.Xlo + (size_t)grow * a.Kd + c * 8 : nullptr;
+        xdst[i] = row * LDH + c * 8;
+    }
+    float4_t acc[MB], acl[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) { acc[mb] = float4_t{0.f, 0.f, 0.f, 0.f}; acl[mb] = float4_t{0.f, 0.f, 0.f, 0.f}; }
+
+    Frag8 w0[4], w1[4], w2[4];
+    u32x4 xr[NP][MB];
+    auto load_w = [&](int st, Frag8 (&w)[4]) {              // clamped: always in bounds, surplus loads are dropped
+        const int k0 = min(st, ksteps - 1) * kGemmKStep;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) w[c].v4 = *reinterpret_cast<const u32x4*>(wp + k0 + c * 8);
+    };
+    auto load_x = [&](int st) {
+        const int k0 = min(st, ksteps - 1) * kGemmKStep;
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            xr[0][i] = *reinterpret_cast<const u32x4*>(xsrc[i] + k0);
+            if constexpr (SPLIT) xr[NP - 1][i] = *reinterpret_cast<const u32x4*>(xlsrc[i] + k0);
+        }
+    };
+    // one step: multiply the fragments in `cur`, refill `fill` (free since the step before) two steps ahead
+    auto step = [&](int st, Frag8 (&cur)[4], Frag8 (&fill)[4]) {
+        load_w(st + 2, fill);
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            *reinterpret_cast<u32x4*>(sx + xdst[i]) = xr[0][i];
+            if constexpr (SPLIT) *reinterpret_cast<u32x4*>(sx + ROWS * LDH + xdst[i]) = xr[NP - 1][i];
+        }
+        __syncthreads();
+        load_x(st + 1);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) bf16x8_to_f16x8(cur[c]);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            Frag8 b[4], bl[4];
+            const uint16_t* row = sx + (mb * 16 + r) * LDH + g * 32;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) b[c].v4 = *reinterpret_cast<const u32x4*>(row + c * 8);
+            if constexpr (SPLIT) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) bl[c].v4 = *reinterpret_cast<const u32x4*>(row + ROWS * LDH + c * 8);
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[mb] = mfma_16x16x32(cur[c], b[c], acc[mb]);
+            if constexpr (SPLIT) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acl[mb] = mfma_16x16x32(cur[c], bl[c], acl[mb]);
+            }
+        }
+        __syncthreads();                                     // the chunk is free for the next step's pieces
+    };
+    load_x(sbeg);
+    load_w(sbeg, w0);
+    load_w(sbeg + 1, w1);
+    for (int st = sbeg; st < send; st += 3) {                // sbeg, send are the same for every wave of the workgroup
+        step(st, w0, w2);
+        if (st + 1 >= send) break;
+        step(st + 1, w1, w0);
+        if (st + 2 >= send) break;
+        step(st + 2, w2, w1);
+    }
+    float v[MB][4];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[mb][i] = SPLIT ? acc[mb][i] + acl[mb][i] * kLoInv : acc[mb][i];
+    const int n = tile * 16 + 4 * g;
+    if constexpr (EPI == EPI_SWIGLU) {
+        float* ex = reinterpret_cast<float*>(sx);             // [pair 0..1][mb][i][lane]; the loop's last barrier freed sx
+        if (sel == 1) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) ex[(((wave >> 1) * MB + mb) * 4 + i) * 64 + lane] = v[mb][i];
+        }
+        __syncthreads();
+        if (sel == 1 || !active) return;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const int row = mb * 16 + r;
+            if (row >= a.M) continue;
+            Frag4 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float up = ex[(((wave >> 1) * MB + mb) * 4 + i) * 64 + lane];
+                o.h[i] = f32_to_f16(v[mb][i] / (1.f + __expf(-v[mb][i])) * up);
+            }
+            *reinterpret_cast<uint2*>(a.outh + (size_t)row * a.N + n) = o.u;
+        }
+    } else {
+        if (!active) return;
+        float* const outf = S > 1 ? a.part + (size_t)ks * a.M * a.N : a.outf;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const int row = mb * 16 + r;
+            if (row >= a.M) continue;
+            float4* p = reinterpret_cast<float4*>(outf + (size_t)row * a.N + n);
+            float4 t = make_float4(v[mb][0], v[mb][1], v[mb][2], v[mb][3]);
+            if (EPI == EPI_RESID && S == 1) { const float4 o = *p; t.x += o.x; t.y += o.y; t.z += o.z; t.w += o.w; }
+            *p = t;
+        }
+    }
+}
+
+// Reduction parts for a store / accumulate projection: doubled while the launch would leave compute units idle,
+// each part keeps at least two steps and the partial results fit the workspace. A function of the shape only.
+inline int gemm_mid_parts(int M, int N, int Kd, size_t part_floats) {
+    const int groups = (N / 16 + 3) / 4, ksteps = Kd / kGemmKStep;
+    int S = 1;
+    while (S < 8 && groups * S < 256 && ksteps / (2 * S) >= 2 && (size_t)(2 * S) * M * N <= part_floats) S *= 2;
+    return S;
+}
+
+// Caller guarantees 16 < M <= 80, N % 16 == 0, Kd % 128 == 0, and S == 1 for EPI_SWIGLU.
+template <int EPI, bool SPLIT>
+inline void launch_gemm_mid(const GemmMidArgs& a, int S, hipStream_t stream) {
+    const int ntiles = a.N / 16, mblocks = (a.M + 15) / 16;
+    dim3 grid((unsigned)(((EPI == EPI_SWIGLU ? 2 : 1) * ntiles + 3) / 4), (unsigned)S);
+    switch (mblocks) {
+        case 2: hipLaunchKernelGGL((gemm_mid_kernel<2, EPI, SPLIT>), grid, dim3(256), 0, stream, a); break;
+        case 3: hipLaunchKernelGGL((gemm_mid_kernel<3, EPI, SPLIT>), grid, dim3(256), 0, stream, a); break;
+        case 4: hipLaunchKernelGGL((gemm_mid_kernel<4, EPI, SPLIT>), grid, dim3(256), 0, stream, a); break;
+        default: hipLaunchKernelGGL((gemm_mid_kernel<5, EPI, SPLIT>), grid, dim3(256), 0, stream, a); break;
+    }
+}
+
+}  // namespace laser

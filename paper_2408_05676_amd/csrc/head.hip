@@ -10,20 +10,24 @@
 // draft, that chunk already contributes >= LASER_MAX_TOPK >= k listed ones, so "rank < k" is exact.
 // The block then scans the rows left to right and emits accepted drafts plus the correction token.
 //
-// Many rows (M > 80): streaming the head matrix once per 64 rows would read it M/64 times. Instead the
-// logits go through the LDS-tiled matrix-core GEMM into an fp32 workspace (written and read once:
-// 8 bytes per logit against the 2 * d flops it costs), head_stats_kernel reduces each row (max, sum of
-// exp, arg-max, the draft's logit and its exact rank) and decides it, head_scan_kernel scans the rows.
+// More than 16 rows: the per-lane running statistics of pass 1 (one set per row tile) and the serial merge of
+// pass 2 cost more than they save. Instead the logits are written to an fp32 workspace by a GEMM (17..80 rows:
+// the weight-streaming kernel of gemm_mid.h, the head matrix read once; more: the LDS-tiled matrix-core GEMM;
+// the logits are written and read once, 8 bytes each against the 2 * d flops they cost), head_stats_kernel
+// reduces each row (max, sum of exp, arg-max, the draft's logit and its exact rank) and decides it,
+// head_scan_kernel scans the rows.
 #include <cmath>
 
 #include "gemm_mfma.h"
 #include "gemm_skinny.h"
+#include "gemm_mid.h"
 #include "state.h"
 
 namespace laser {
 
 constexpr int KT = LASER_MAX_TOPK;
-constexpr int kHeadStreamMaxRows = 80;   // beyond this the head matrix goes through the tiled GEMM
+constexpr int kHeadStreamMaxRows = 16;   // beyond this the logits are written out by a GEMM and reduced row by row
+constexpr int kHeadMidMaxRows = 80;      // up to here that GEMM streams the head matrix once; beyond, the tiled one
 
 struct HeadArgs {
     const uint16_t* W; const uint16_t* H; int M, V, d, tiles_per_wave, chunks;
@@ -313,10 +317,15 @@ int run_head(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* 
             }
             logits = m->logits_ws;
         }
-        const int tiles_m = (M + GM_BM - 1) / GM_BM, tiles_n = (m->d.vocab + 127) / 128;
-        GemmTileArgs t{m->d.wlm, h, nullptr, M, m->d.vocab, m->d.d_model, tiles_m, tiles_n, 1, logits, nullptr};
-        hipLaunchKernelGGL((gemm_mfma_kernel<GEPI_F32, 128, false>), dim3(gemm_mfma_grid(tiles_m, tiles_n)), dim3(256), 0,
-                           stream, t);
+        if (M <= kHeadMidMaxRows && m->d.d_model % kGemmKStep == 0 && m->d.vocab % 16 == 0) {
+            GemmMidArgs t{m->d.wlm, h, nullptr, M, m->d.vocab, m->d.d_model, logits, nullptr, nullptr};
+            launch_gemm_mid<EPI_F32, false>(t, 1, stream);
+        } else {
+            const int tiles_m = (M + GM_BM - 1) / GM_BM, tiles_n = (m->d.vocab + 127) / 128;
+            GemmTileArgs t{m->d.wlm, h, nullptr, M, m->d.vocab, m->d.d_model, tiles_m, tiles_n, 1, logits, nullptr};
+            hipLaunchKernelGGL((gemm_mfma_kernel<GEPI_F32, 128, false>), dim3(gemm_mfma_grid(tiles_m, tiles_n)), dim3(256), 0,
+                               stream, t);
+        }
         int32_t* row_ok = m->hp_arg;                     // per-row scratch: the streaming path's buffers are free here
         int32_t* row_arg = m->hp_arg + M;
         StatsArgs sa{logits, m->row_x, m->d.vocab, topk, mode, p, row_ok, row_arg};
@@ -330,16 +339,8 @@ int run_head(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* 
     const int tpw = (ntiles + 1023) / 1024;
     HeadArgs a{m->d.wlm, h, M, m->d.vocab, m->d.d_model, tpw, m->head_chunks, m->row_x,
                m->hp_max, m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx, logits_dbg};
-    const int mblocks = (M + 15) / 16;
-    const int MB = mblocks >= 4 ? 4 : mblocks;
-    const int passes = (mblocks + MB - 1) / MB;
-    dim3 grid((unsigned)((m->head_chunks + 3) / 4), (unsigned)passes);
-    switch (MB) {
-        case 1: hipLaunchKernelGGL(lm_head_kernel<1>, grid, dim3(256), 0, stream, a); break;
-        case 2: hipLaunchKernelGGL(lm_head_kernel<2>, grid, dim3(256), 0, stream, a); break;
-        case 3: hipLaunchKernelGGL(lm_head_kernel<3>, grid, dim3(256), 0, stream, a); break;
-        default: hipLaunchKernelGGL(lm_head_kernel<4>, grid, dim3(256), 0, stream, a); break;
-    }
+    dim3 grid((unsigned)((m->head_chunks + 3) / 4), 1u);         // at most 16 rows: one row tile
+    hipLaunchKernelGGL(lm_head_kernel<1>, grid, dim3(256), 0, stream, a);
     AcceptArgs aa{m->hp_max, m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx, m->row_x, drafts, draft_len,
                   K, m->head_chunks, topk, mode, p, accept_len, out_tokens};
     hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(256), 0, stream, aa);

@@ -7,6 +7,7 @@
 
 #include "gemm_mfma.h"
 #include "gemm_skinny.h"
+#include "gemm_mid.h"
 #include "state.h"
 
 namespace laser {
@@ -114,7 +115,6 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, con
 }
 
 // ------------------------------------------------------------------------------------------------
-enum { EPI_F32 = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
 
 struct GemmArgs {
     const uint16_t* W;      // [N][Kd]  (EPI_SWIGLU: [2N][Kd], gate rows then up rows)
@@ -202,143 +202,6 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
 }
 
 constexpr int kSkinnyMaxRows = 80;   // beyond this the weights would be streamed more than once
-
-// Weight-streaming GEMM for 17..80 activation rows (MB = 2..5 row tiles). gemm_skinny_kernel re-reads the
-// activation rows from L2 at every step: with MB row tiles in two planes that is 2 MB x 64 bytes per lane and step
-// against 64 bytes of weights, and the kernel is bound by L2 (the 1B shape's gate/up ran at 0.6 TB/s). Here the four
-// waves of a workgroup own four DIFFERENT 16-row weight tiles and walk the SAME reduction range, so the
-// activation chunk of a step (rows x 128 elements, both planes) is staged once in LDS by the whole workgroup and
-// read from there by every wave; the next chunk and the weight fragments of the next two steps are in flight
-// while the current ones are multiplied. blockIdx.y = part of the reduction: with more than one part each
-// workgroup stores its partial result at part + blockIdx.y * M * N and the consumer (rotary kernel or norm) adds
-// the parts in order (store / accumulate epilogues only). SwiGLU: a gate tile and its up tile go to neighbouring
-// waves (twice the waves, half the registers), the up wave hands its sums over through LDS at the end.
-template <int MB, int EPI, bool SPLIT>
-__global__ __launch_bounds__(256, 2) void gemm_mid_kernel(GemmArgs a) {
-    constexpr int ROWS = MB * 16, NP = SPLIT ? 2 : 1;
-    constexpr int LDH = kGemmKStep + 8;                     // halves per LDS row: 272 bytes, the 16 rows of a 16-byte read hit distinct banks
-    __shared__ __attribute__((aligned(16))) uint16_t sx[NP * ROWS * LDH];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int r = lane & 15, g = lane >> 4;
-    const int ntiles = a.N / 16;
-    const int vt = blockIdx.x * 4 + wave;
-    const int tile_raw = EPI == EPI_SWIGLU ? vt >> 1 : vt;
-    const int sel = EPI == EPI_SWIGLU ? vt & 1 : 0;          // SwiGLU: 0 = gate rows, 1 = up rows
-    const bool active = tile_raw < ntiles;
-    const int tile = active ? tile_raw : ntiles - 1;        // idle waves stream a valid tile and drop the result
-    const int S = gridDim.y, ks = blockIdx.y;
-    const int ksteps = a.Kd / kGemmKStep, per = (ksteps + S - 1) / S;
-    const int sbeg = ks * per, send = min(ksteps, sbeg + per);
-
-    const uint16_t* const wp = a.W + ((size_t)sel * a.N + (size_t)tile * 16 + r) * a.Kd + g * 32;
-    // staging: piece p = tid + 256 i covers row p / 16, 16-byte column p % 16 of the chunk
-    const uint16_t* xsrc[MB];
-    const uint16_t* xlsrc[MB];
-    int xdst[MB];
-#pragma unroll
-    for (int i = 0; i < MB; ++i) {
-        const int p = tid + 256 * i, row = p >> 4, c = p & 15;
-        const int grow = min(row, a.M - 1);
-        xsrc[i] = a.X + (size_t)grow * a.Kd + c * 8;
-        xlsrc[i] = SPLIT ? a.Xlo + (size_t)grow * a.Kd + c * 8 : nullptr;
-        xdst[i] = row * LDH + c * 8;
-    }
-    float4_t acc[MB], acl[MB];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) { acc[mb] = float4_t{0.f, 0.f, 0.f, 0.f}; acl[mb] = float4_t{0.f, 0.f, 0.f, 0.f}; }
-
-    Frag8 w0[4], w1[4], w2[4];
-    u32x4 xr[NP][MB];
-    auto load_w = [&](int st, Frag8 (&w)[4]) {              // clamped: always in bounds, surplus loads are dropped
-        const int k0 = min(st, ksteps - 1) * kGemmKStep;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) w[c].v4 = *reinterpret_cast<const u32x4*>(wp + k0 + c * 8);
-    };
-    auto load_x = [&](int st) {
-        const int k0 = min(st, ksteps - 1) * kGemmKStep;
-#pragma unroll
-        for (int i = 0; i < MB; ++i) {
-            xr[0][i] = *reinterpret_cast<const u32x4*>(xsrc[i] + k0);
-            if constexpr (SPLIT) xr[NP - 1][i] = *reinterpret_cast<const u32x4*>(xlsrc[i] + k0);
-        }
-    };
-    load_x(sbeg);
-    load_w(sbeg, w0);
-    load_w(sbeg + 1, w1);
-    for (int st = sbeg; st < send; ++st) {
-#pragma unroll
-        for (int i = 0; i < MB; ++i) {
-            *reinterpret_cast<u32x4*>(sx + xdst[i]) = xr[0][i];
-            if constexpr (SPLIT) *reinterpret_cast<u32x4*>(sx + ROWS * LDH + xdst[i]) = xr[NP - 1][i];
-        }
-        __syncthreads();
-        load_w(st + 2, w2);                                  // in flight during this step's and the next step's matrix work
-        load_x(st + 1);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) bf16x8_to_f16x8(w0[c]);
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            Frag8 b[4], bl[4];
-            const uint16_t* row = sx + (mb * 16 + r) * LDH + g * 32;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) b[c].v4 = *reinterpret_cast<const u32x4*>(row + c * 8);
-            if constexpr (SPLIT) {
-#pragma unroll
-                for (int c = 0; c < 4; ++c) bl[c].v4 = *reinterpret_cast<const u32x4*>(row + ROWS * LDH + c * 8);
-            }
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc[mb] = mfma_16x16x32(w0[c], b[c], acc[mb]);
-            if constexpr (SPLIT) {
-#pragma unroll
-                for (int c = 0; c < 4; ++c) acl[mb] = mfma_16x16x32(w0[c], bl[c], acl[mb]);
-            }
-        }
-        __syncthreads();                                     // the chunk is free for the next step's pieces
-#pragma unroll
-        for (int c = 0; c < 4; ++c) { w0[c] = w1[c]; w1[c] = w2[c]; }
-    }
-    float v[MB][4];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) v[mb][i] = SPLIT ? acc[mb][i] + acl[mb][i] * kLoInv : acc[mb][i];
-    const int n = tile * 16 + 4 * g;
-    if constexpr (EPI == EPI_SWIGLU) {
-        float* ex = reinterpret_cast<float*>(sx);             // [pair 0..1][mb][i][lane]; the loop's last barrier freed sx
-        if (sel == 1) {
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) ex[(((wave >> 1) * MB + mb) * 4 + i) * 64 + lane] = v[mb][i];
-        }
-        __syncthreads();
-        if (sel == 1 || !active) return;
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            const int row = mb * 16 + r;
-            if (row >= a.M) continue;
-            Frag4 o;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float up = ex[(((wave >> 1) * MB + mb) * 4 + i) * 64 + lane];
-                o.h[i] = f32_to_f16(v[mb][i] / (1.f + __expf(-v[mb][i])) * up);
-            }
-            *reinterpret_cast<uint2*>(a.outh + (size_t)row * a.N + n) = o.u;
-        }
-    } else {
-        if (!active) return;
-        float* const outf = S > 1 ? a.part + (size_t)ks * a.M * a.N : a.outf;
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            const int row = mb * 16 + r;
-            if (row >= a.M) continue;
-            float4* p = reinterpret_cast<float4*>(outf + (size_t)row * a.N + n);
-            float4 t = make_float4(v[mb][0], v[mb][1], v[mb][2], v[mb][3]);
-            if (EPI == EPI_RESID && S == 1) { const float4 o = *p; t.x += o.x; t.y += o.y; t.z += o.z; t.w += o.w; }
-            *p = t;
-        }
-    }
-}
 
 // bf16 -> fp16 copy of a weight matrix, 8 elements per thread and iteration
 __global__ __launch_bounds__(256) void widen_weights_kernel(const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, size_t n8) {
@@ -429,22 +292,10 @@ static int launch_gemm(GemmArgs& a_in, hipStream_t stream) {
     const int mblocks = (a.M + 15) / 16;
     if (mblocks >= 2 && (a.Xlo || EPI == EPI_RESID) && a.Kd % kGemmKStep == 0) {
         // 17..80 rows: activations staged in LDS and shared by the workgroup's four weight tiles
-        const int groups = ((EPI == EPI_SWIGLU ? 2 : 1) * ntiles + 3) / 4, ksteps = a.Kd / kGemmKStep;
-        int S = 1;
-        if (EPI != EPI_SWIGLU && a.part)
-            while (S < 8 && groups * S < 256 && ksteps / (2 * S) >= 2 && (size_t)(2 * S) * a.M * a.N <= a.part_floats) S *= 2;
-        dim3 grid((unsigned)groups, (unsigned)S);
-        auto gom = [&](auto mbc) {
-            constexpr int mb = decltype(mbc)::value;
-            if (a.Xlo) hipLaunchKernelGGL((gemm_mid_kernel<mb, EPI, true>), grid, dim3(256), 0, stream, a);
-            else if constexpr (EPI == EPI_RESID) hipLaunchKernelGGL((gemm_mid_kernel<mb, EPI, false>), grid, dim3(256), 0, stream, a);
-        };
-        switch (mblocks) {
-            case 2: gom(std::integral_constant<int, 2>{}); break;
-            case 3: gom(std::integral_constant<int, 3>{}); break;
-            case 4: gom(std::integral_constant<int, 4>{}); break;
-            default: gom(std::integral_constant<int, 5>{}); break;
-        }
+        GemmMidArgs t{a.W, a.X, a.Xlo, a.M, a.N, a.Kd, a.outf, a.outh, a.part};
+        const int S = EPI == EPI_SWIGLU || !a.part ? 1 : gemm_mid_parts(a.M, a.N, a.Kd, a.part_floats);
+        if (a.Xlo) launch_gemm_mid<EPI, true>(t, S, stream);
+        else if constexpr (EPI == EPI_RESID) launch_gemm_mid<EPI, false>(t, S, stream);
         LASER_HIP_CHECK(hipGetLastError());
         a.n_part = S > 1 ? S : 0;
         return LASER_OK;
