@@ -6,9 +6,11 @@
 // planes that is 2 MB x 64 bytes per lane and step against 64 bytes of weights, and at 72 rows it is bound by L2,
 // not by HBM. Here the four waves of a workgroup own four DIFFERENT 16-row weight tiles and walk the SAME
 // reduction range, so the activation chunk of a step (rows x 128 elements, both planes) is staged once in LDS by
-// the whole workgroup and read from there by every wave; the next chunk and the weight fragments of the next two
-// steps are in flight while the current ones are multiplied (three named fragment sets, the loop unrolled by
-// three: a register copy of a fragment still in flight would make the wave wait for it).
+// the whole workgroup and read from there by every wave; the next chunk and the next step's weight fragments are
+// in flight while the current ones are multiplied (two named fragment sets, the loop unrolled by two: a register
+// copy of a fragment still in flight would make the wave wait for it). Register pressure is kept below the
+// point of scratch spills on purpose: a reload from scratch waits, in order, behind every global load issued
+// before it, which puts a full HBM latency into each step.
 //
 // blockIdx.y = part of the reduction: with more than one part each workgroup stores its partial result at
 // part + blockIdx.y * M * N and the consumer adds the parts in order (store / accumulate epilogues only).
@@ -53,22 +55,20 @@ __global__ __launch_bounds__(256, 2) void gemm_mid_kernel(GemmMidArgs a) {
 
     const uint16_t* const wp = a.W + ((size_t)sel * a.N + (size_t)tile * 16 + r) * a.Kd + g * 32;
     // staging: piece p = tid + 256 i covers row p / 16, 16-byte column p % 16 of the chunk
-    const uint16_t* xsrc[MB];
-    const uint16_t* xlsrc[MB];
+    // (32-bit element offsets from the uniform plane bases: M * Kd is far below 2^31 here)
+    unsigned xoff[MB];
     int xdst[MB];
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
         const int p = tid + 256 * i, row = p >> 4, c = p & 15;
-        const int grow = min(row, a.M - 1);
-        xsrc[i] = a.X + (size_t)grow * a.Kd + c * 8;
-        xlsrc[i] = SPLIT ? a.Xlo + (size_t)grow * a.Kd + c * 8 : nullptr;
+        xoff[i] = (unsigned)min(row, a.M - 1) * (unsigned)a.Kd + c * 8;
         xdst[i] = row * LDH + c * 8;
     }
     float4_t acc[MB], acl[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) { acc[mb] = float4_t{0.f, 0.f, 0.f, 0.f}; acl[mb] = float4_t{0.f, 0.f, 0.f, 0.f}; }
 
-    Frag8 w0[4], w1[4], w2[4];
+    Frag8 w0[4], w1[4];
     u32x4 xr[NP][MB];
     auto load_w = [&](int st, Frag8 (&w)[4]) {              // clamped: always in bounds, surplus loads are dropped
         const int k0 = min(st, ksteps - 1) * kGemmKStep;
@@ -77,15 +77,17 @@ __global__ __launch_bounds__(256, 2) void gemm_mid_kernel(GemmMidArgs a) {
     };
     auto load_x = [&](int st) {
         const int k0 = min(st, ksteps - 1) * kGemmKStep;
+        const uint16_t* const xb = a.X + k0;
+        const uint16_t* const xlb = SPLIT ? a.Xlo + k0 : nullptr;
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
-            xr[0][i] = *reinterpret_cast<const u32x4*>(xsrc[i] + k0);
-            if constexpr (SPLIT) xr[NP - 1][i] = *reinterpret_cast<const u32x4*>(xlsrc[i] + k0);
+            xr[0][i] = *reinterpret_cast<const u32x4*>(xb + xoff[i]);
+            if constexpr (SPLIT) xr[NP - 1][i] = *reinterpret_cast<const u32x4*>(xlb + xoff[i]);
         }
     };
-    // one step: multiply the fragments in `cur`, refill `fill` (free since the step before) two steps ahead
+    // one step: multiply the fragments in `cur` while `fill` (free since the step before) takes the next step's
     auto step = [&](int st, Frag8 (&cur)[4], Frag8 (&fill)[4]) {
-        load_w(st + 2, fill);
+        load_w(st + 1, fill);
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
             *reinterpret_cast<u32x4*>(sx + xdst[i]) = xr[0][i];
@@ -95,34 +97,40 @@ __global__ __launch_bounds__(256, 2) void gemm_mid_kernel(GemmMidArgs a) {
         load_x(st + 1);
 #pragma unroll
         for (int c = 0; c < 4; ++c) bf16x8_to_f16x8(cur[c]);
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            Frag8 b[4], bl[4];
+        // The row tiles' fragments are read from LDS one tile ahead of the matrix instructions that use them (two
+        // fragment sets; the scheduling fences keep the compiler from sinking the reads back to their uses: with
+        // about one wave per SIMD nothing else would cover the LDS latency of 8 reads per tile).
+        Frag8 b[2][NP * 4];
+        auto read_b = [&](int mb, Frag8 (&f)[NP * 4]) {
             const uint16_t* row = sx + (mb * 16 + r) * LDH + g * 32;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) b[c].v4 = *reinterpret_cast<const u32x4*>(row + c * 8);
+            for (int c = 0; c < 4; ++c) f[c].v4 = *reinterpret_cast<const u32x4*>(row + c * 8);
             if constexpr (SPLIT) {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) bl[c].v4 = *reinterpret_cast<const u32x4*>(row + ROWS * LDH + c * 8);
+                for (int c = 0; c < 4; ++c) f[4 + c].v4 = *reinterpret_cast<const u32x4*>(row + ROWS * LDH + c * 8);
             }
+        };
+        read_b(0, b[0]);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) acc[mb] = mfma_16x16x32(cur[c], b[c], acc[mb]);
+        for (int mb = 0; mb < MB; ++mb) {
+            if (mb + 1 < MB) read_b(mb + 1, b[(mb + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[mb] = mfma_16x16x32(cur[c], b[mb & 1][c], acc[mb]);
             if constexpr (SPLIT) {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) acl[mb] = mfma_16x16x32(cur[c], bl[c], acl[mb]);
+                for (int c = 0; c < 4; ++c) acl[mb] = mfma_16x16x32(cur[c], b[mb & 1][NP * 4 - 4 + c], acl[mb]);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();                                     // the chunk is free for the next step's pieces
     };
     load_x(sbeg);
     load_w(sbeg, w0);
-    load_w(sbeg + 1, w1);
-    for (int st = sbeg; st < send; st += 3) {                // sbeg, send are the same for every wave of the workgroup
-        step(st, w0, w2);
+    for (int st = sbeg; st < send; st += 2) {                // sbeg, send are the same for every wave of the workgroup
+        step(st, w0, w1);
         if (st + 1 >= send) break;
         step(st + 1, w1, w0);
-        if (st + 2 >= send) break;
-        step(st + 2, w2, w1);
     }
     float v[MB][4];
 #pragma unroll
