@@ -225,6 +225,15 @@ def test_1b_width_three_layers_generic_row_tiles():
     _run_steps(sh, B=8, ctx_len=40, K=8, n_steps=2, k=2, p=0.0, seed=21)
 
 
+@pytest.mark.parametrize("B,K", [(3, 5), (4, 8), (7, 6), (5, 15), (8, 9)])
+def test_mid_row_counts_stage_activations_in_lds(B, K):
+    """17..80 rows (M = 18, 36, 49, 80, 80): the weight-streaming kernel that stages the activation chunk in
+    LDS, with 2, 3, 4 and 5 row tiles, ragged last tiles, reduction parts summed by the rotary kernel and the
+    norms, and the head through the same kernel plus per-row statistics. Ragged draft lengths on one case."""
+    sh = synth.SHAPES["tiny128"].with_(lm_gain=4.0)
+    _run_steps(sh, B=B, ctx_len=21, K=K, n_steps=2, k=2, p=0.05, seed=40 + B, ragged=(B == 7), fused=0)
+
+
 def test_7b_throughput_launch_shape_sampled():
     """The throughput workload's launch configuration (7B width, B = 64, K = 10: M = 704 rows on the
     tiled matrix-core GEMMs, paged cache) with two layers; the oracle follows three of the 64 sequences."""
