@@ -213,7 +213,13 @@ int laser_ctx_advance(int32_t* ctx_tail, int32_t* pending, const int32_t* out_to
  * B*(K+1) <= 16; 0 forces the general multi-kernel path. Both compute the same function.
  * "split_ffn" = 1 makes the many-row (more than 80 rows) gate/up product take its input rows as two
  * fp16 planes like the other products (default 0: single fp16 there, which halves that product's
- * matrix work; with up to 80 rows the input is always split). */
+ * matrix work; with up to 80 rows the input is always split).
+ * "ksplit_qkv", "ksplit_o", "ksplit_down" = 0 (default), 1, 2 or 4: number of parts the reduction of
+ * that projection is cut into on the many-row path (0: chosen from the launch shape; a value the
+ * shape or the workspace cannot take falls back to 1). The parts are added in a fixed order by the
+ * kernel that follows, so a given setting is deterministic; different settings may differ in the
+ * last bits. Tuning and test knobs: the default is what the benchmark measures.
+ * Unknown names and out-of-range values return LASER_E_INVALID_ARG. */
 int laser_model_set_option(laser_model* model, const char* name, int value);
 /* Phase trace of the persistent kernel (option "fused_trace" = 1): thread 0 of every workgroup stamps
  * the 100 MHz wall clock before and after every grid barrier. Copies the stamps of the most recent
