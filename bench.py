@@ -265,6 +265,13 @@ def run_workload(args, name, steps, warmup, weights_cache):
     else:
         peak, unit, achieved = MFMA_F16_PEAK_TFLOPS, "TFLOP/s", (dom_work / dom_avg_s / 1e12 if dom_n else 0.0)
         work_key = "flops_per_launch"
+    # measured peaks of this chip in this process (a streaming read / copy over 1 GiB, a register-resident fp16
+    # matrix-instruction loop), beside the datasheet peak the fraction is quoted against
+    scratch = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    read_gbs, copy_gbs = laser.probe_hbm(scratch, reps=10)
+    mfma_tflops = laser.probe_mfma_f16(scratch, reps=5)
+    del scratch
+    measured_peak = max(read_gbs, copy_gbs) if bound == "hbm" else mfma_tflops
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{name}_{path}.json")
     if os.path.exists(tpath):
@@ -288,7 +295,9 @@ def run_workload(args, name, steps, warmup, weights_cache):
                    "step_hbm_frac": step_bytes / (gpu_ms / 1e3 / steps) / 1e9 / HBM_PEAK_GBS},
         "roofline": {"bound": bound, "kernel": dom_name, "achieved": achieved,
                      "peak": peak, "unit": unit, "frac": achieved / peak, "traffic": traffic,
-                     work_key: dom_work, "avg_launch_us": dom_avg_s * 1e6, "launches": dom_n},
+                     work_key: dom_work, "avg_launch_us": dom_avg_s * 1e6, "launches": dom_n,
+                     "measured_peak": measured_peak, "frac_of_measured_peak": achieved / measured_peak if measured_peak else None,
+                     "measured": {"hbm_read_GBs": read_gbs, "hbm_copy_GBs": copy_gbs, "mfma_f16_TFLOPs": mfma_tflops}},
     }
     eng.close()
     pool.close()

@@ -236,6 +236,18 @@ int laser_model_status(laser_model* model, void* stream, int* aborted);
 int laser_profile_begin(laser_model* model, int max_records);
 int laser_profile_end(laser_model* model, void* stream, float* total_ms, int* n_launches);
 
+/* Measured peaks of the device, so that roofline fractions can be quoted against what the chip delivers as well
+ * as against its datasheet. Neither touches any model state; both synchronise `stream` before they return.
+ * laser_probe_hbm: buf [dev] is caller-owned scratch of `bytes` bytes (a multiple of 32, at least 1 MiB; use
+ *   more than the 256 MiB last-level cache). The read probe streams all of it `reps` times (read_gbs = bytes
+ *   read per second / 1e9); the copy probe copies its first half onto its second half `reps` times
+ *   (copy_gbs = bytes read + written per second / 1e9). The buffer's second half is overwritten.
+ * laser_probe_mfma_f16: a register-resident loop of 32x32x16 fp16 matrix instructions on every SIMD (16 waves per
+ *   compute unit, four independent accumulators each); scratch [dev] is any device buffer of at least 4 bytes
+ *   (not written); tflops = executed flops per second / 1e12. */
+int laser_probe_hbm(void* buf, size_t bytes, int reps, void* stream, float* read_gbs, float* copy_gbs);
+int laser_probe_mfma_f16(void* scratch, int reps, void* stream, float* tflops);
+
 #ifdef __cplusplus
 }
 #endif

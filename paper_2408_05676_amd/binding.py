@@ -74,6 +74,8 @@ def lib():
         "laser_model_status": [vp, vp, C.POINTER(C.c_int)],
         "laser_model_read_trace": [vp, vp, vp, i32, C.POINTER(C.c_int), C.POINTER(C.c_int)],
         "laser_profile_end": [vp, vp, C.POINTER(C.c_float), C.POINTER(C.c_int)],
+        "laser_probe_hbm": [vp, C.c_size_t, i32, vp, C.POINTER(C.c_float), C.POINTER(C.c_float)],
+        "laser_probe_mfma_f16": [vp, i32, vp, C.POINTER(C.c_float)],
     }
     for name, args in protos.items():
         fn = getattr(L, name)
@@ -325,3 +327,23 @@ def ctx_advance(ctx_tail: torch.Tensor, pending: torch.Tensor, out_tokens: torch
     _check(lib().laser_ctx_advance(_dev(ctx_tail, torch.int32, "ctx_tail"), _dev(pending, torch.int32, "pending"),
                                    _dev(out_tokens, torch.int32, "out_tokens"), _dev(accept_len, torch.int32, "accept_len"),
                                    B, K, n_max, _stream(stream)), "laser_ctx_advance")
+
+
+def probe_hbm(buf: torch.Tensor, reps: int = 10, stream=None):
+    """laser_probe_hbm on a caller-owned CUDA scratch tensor: (read GB/s, copy GB/s)."""
+    if not (isinstance(buf, torch.Tensor) and buf.is_cuda and buf.is_contiguous()):
+        raise LaserError("buf must be a contiguous CUDA tensor")
+    nbytes = buf.numel() * buf.element_size()
+    r, c = C.c_float(), C.c_float()
+    _check(lib().laser_probe_hbm(buf.data_ptr(), nbytes - nbytes % 32, reps, _stream(stream), C.byref(r), C.byref(c)),
+           "laser_probe_hbm")
+    return r.value, c.value
+
+
+def probe_mfma_f16(scratch: torch.Tensor, reps: int = 10, stream=None) -> float:
+    """laser_probe_mfma_f16: executed TFLOP/s of a register-resident fp16 matrix-instruction loop."""
+    if not (isinstance(scratch, torch.Tensor) and scratch.is_cuda and scratch.numel() * scratch.element_size() >= 4):
+        raise LaserError("scratch must be a CUDA tensor of at least 4 bytes")
+    t = C.c_float()
+    _check(lib().laser_probe_mfma_f16(scratch.data_ptr(), reps, _stream(stream), C.byref(t)), "laser_probe_mfma_f16")
+    return t.value

@@ -1,0 +1,126 @@
+// Measured peaks of the device, reported beside the datasheet figures: a streaming read, a streaming copy and a
+// register-resident matrix-core loop. They share nothing with the decoding path; the benchmark runs them in the
+// same process so that a roofline fraction can also be quoted against what this chip delivered that day.
+#include "common.h"
+#include "mfma.h"
+
+namespace laser {
+
+typedef unsigned u32x4_p __attribute__((ext_vector_type(4)));
+
+// Grid-stride over 16-byte pieces, four loads in flight per thread; the XOR of everything read is stored only if
+// it matches an impossible pattern, so the loads cannot be dropped.
+__global__ __launch_bounds__(256) void probe_read_kernel(const u32x4_p* __restrict__ src, size_t n16, unsigned* sink) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    u32x4_p x = {0u, 0u, 0u, 0u};
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const u32x4_p a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        x ^= a ^ b ^ c ^ d;
+    }
+    for (; i < n16; i += stride) x ^= src[i];
+    if ((x[0] ^ x[1]) == 0x9E3779B9u && (x[2] ^ x[3]) == 0x7F4A7C15u) sink[0] = x[0];
+}
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4_p* __restrict__ src, u32x4_p* __restrict__ dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const u32x4_p a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+typedef float f32x16_p __attribute__((ext_vector_type(16)));
+
+// Four independent 32x32x16 fp16 accumulation chains per wave, operands fixed in registers: nothing but the
+// matrix pipe is exercised. 4 * iters instructions of 32768 flops per wave.
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* sink) {
+    Frag8 a, b;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { a.v4[i] = 0x3C003C00u + threadIdx.x; b.v4[i] = 0x38003800u + (threadIdx.x >> 3); }
+    f32x16_p c0, c1, c2, c3;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { c0[e] = 0.f; c1[e] = 1.f; c2[e] = 2.f; c3[e] = 3.f; }
+    for (int it = 0; it < iters; ++it) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a.v, b.v, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a.v, b.v, c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a.v, b.v, c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a.v, b.v, c3, 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s += c0[e] + c1[e] + c2[e] + c3[e];
+    if (s == 12345.678f) sink[0] = s;
+}
+
+}  // namespace laser
+
+using namespace laser;
+
+extern "C" int laser_probe_hbm(void* buf, size_t bytes, int reps, void* stream_v, float* read_gbs, float* copy_gbs) {
+    LASER_REQUIRE(buf != nullptr && read_gbs != nullptr && copy_gbs != nullptr, LASER_E_INVALID_ARG, "NULL argument");
+    LASER_REQUIRE(bytes >= (1u << 20) && bytes % 32 == 0 && reps >= 1 && reps <= 1000, LASER_E_INVALID_ARG,
+                  "bytes must be a multiple of 32 and at least 1 MiB, reps 1..1000");
+    hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
+    int ncu = 0;
+    LASER_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, 0));
+    hipEvent_t e0, e1;
+    LASER_HIP_CHECK(hipEventCreate(&e0));
+    LASER_HIP_CHECK(hipEventCreate(&e1));
+    const unsigned grid = (unsigned)ncu * 16u;
+    u32x4_p* lo = reinterpret_cast<u32x4_p*>(buf);
+    u32x4_p* hi = lo + bytes / 32;
+    unsigned* sink = reinterpret_cast<unsigned*>(buf);     // never written: the pattern cannot match
+    float ms = 0.f;
+    // read: the whole buffer
+    hipLaunchKernelGGL(probe_read_kernel, dim3(grid), dim3(256), 0, stream, (const u32x4_p*)lo, bytes / 16, sink);
+    LASER_HIP_CHECK(hipEventRecord(e0, stream));
+    for (int i = 0; i < reps; ++i)
+        hipLaunchKernelGGL(probe_read_kernel, dim3(grid), dim3(256), 0, stream, (const u32x4_p*)lo, bytes / 16, sink);
+    LASER_HIP_CHECK(hipEventRecord(e1, stream));
+    LASER_HIP_CHECK(hipEventSynchronize(e1));
+    LASER_HIP_CHECK(hipEventElapsedTime(&ms, e0, e1));
+    *read_gbs = (float)((double)bytes * reps / (ms * 1e-3) / 1e9);
+    // copy: first half to second half; bytes moved = read + written
+    hipLaunchKernelGGL(probe_copy_kernel, dim3(grid), dim3(256), 0, stream, (const u32x4_p*)lo, hi, bytes / 32);
+    LASER_HIP_CHECK(hipEventRecord(e0, stream));
+    for (int i = 0; i < reps; ++i)
+        hipLaunchKernelGGL(probe_copy_kernel, dim3(grid), dim3(256), 0, stream, (const u32x4_p*)lo, hi, bytes / 32);
+    LASER_HIP_CHECK(hipEventRecord(e1, stream));
+    LASER_HIP_CHECK(hipEventSynchronize(e1));
+    LASER_HIP_CHECK(hipEventElapsedTime(&ms, e0, e1));
+    *copy_gbs = (float)((double)bytes * reps / (ms * 1e-3) / 1e9);
+    LASER_HIP_CHECK(hipGetLastError());
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return LASER_OK;
+}
+
+extern "C" int laser_probe_mfma_f16(void* scratch, int reps, void* stream_v, float* tflops) {
+    LASER_REQUIRE(scratch != nullptr && tflops != nullptr && reps >= 1 && reps <= 1000, LASER_E_INVALID_ARG,
+                  "NULL argument or reps outside 1..1000");
+    hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
+    int ncu = 0;
+    LASER_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, 0));
+    hipEvent_t e0, e1;
+    LASER_HIP_CHECK(hipEventCreate(&e0));
+    LASER_HIP_CHECK(hipEventCreate(&e1));
+    const int iters = 4096;
+    const unsigned grid = (unsigned)ncu * 4u;               // 16 waves per compute unit, 4 per SIMD
+    float* sink = reinterpret_cast<float*>(scratch);       // never written: the sum cannot match
+    float ms = 0.f;
+    hipLaunchKernelGGL(probe_mfma_kernel, dim3(grid), dim3(256), 0, stream, iters, sink);
+    LASER_HIP_CHECK(hipEventRecord(e0, stream));
+    for (int i = 0; i < reps; ++i) hipLaunchKernelGGL(probe_mfma_kernel, dim3(grid), dim3(256), 0, stream, iters, sink);
+    LASER_HIP_CHECK(hipEventRecord(e1, stream));
+    LASER_HIP_CHECK(hipEventSynchronize(e1));
+    LASER_HIP_CHECK(hipEventElapsedTime(&ms, e0, e1));
+    const double flops = (double)grid * 4.0 * 4.0 * iters * 32768.0 * reps;   // workgroups x waves x chains x iters x flops
+    *tflops = (float)(flops / (ms * 1e-3) / 1e12);
+    LASER_HIP_CHECK(hipGetLastError());
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return LASER_OK;
+}
