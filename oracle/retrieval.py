@@ -23,6 +23,13 @@ structure:
 
 This equals greedy descent of the paper's trie from the node the suffix reaches, always
 into the child with the highest frequency (frequency = number of occurrences of the path).
+
+Temporary branch (Sec. 3.2: the current prompt and the text generated so far are added to the
+group's trie for the duration of this generation only): `own`, the sequence's own text, counts
+as ONE MORE SEQUENCE of the key's sub-pool, placed after all of the key's pool sequences. The
+rules above are unchanged (its last position, which the context suffix itself ends at, has no
+successor and is therefore never an occurrence). A result whose smallest surviving position
+lies in the own text is reported as pool_index = -2 - (position in the own text).
 """
 from __future__ import annotations
 
@@ -83,10 +90,32 @@ def _greedy_chain(pool: RegroupedPool, M: np.ndarray, K: int):
     return chain, M
 
 
+class _SubPoolWithOwnText:
+    """The key's sub-pool [lo, hi) followed by the sequence's own text, as one position space."""
+
+    def __init__(self, pool: RegroupedPool, lo: int, hi: int, own):
+        own = np.asarray(own, dtype=np.int32)
+        n = hi - lo
+        self.P = np.concatenate([pool.P[lo:hi], own])
+        self.seq_begin = np.concatenate([pool.seq_begin[lo:hi] - lo, np.full(own.size, n, dtype=np.int64)])
+        self.seq_end = np.concatenate([pool.seq_end[lo:hi] - lo, np.full(own.size, n + own.size, dtype=np.int64)])
+        self.n_pool, self.lo = n, lo
+
+    def report(self, idx: int) -> int:
+        return self.lo + idx if idx < self.n_pool else -2 - (idx - self.n_pool)
+
+
 def retrieve_one(pool: RegroupedPool, key: int, ctx_tail, n_min: int, n_max: int, K: int,
-                 min_tokens: int = 1):
+                 min_tokens: int = 1, own=None):
     """ctx_tail: the last tokens of the context, right-aligned; entries < 0 are left padding.
+    own: the sequence's own text so far (temporary branch), or None.
     Returns (drafts list, match_n, pool_index)."""
+    if own is not None and len(own) > 0:
+        lo, hi = pool.key_range.get(int(key), (0, 0))
+        q = _SubPoolWithOwnText(pool, lo, hi, own)
+        q.key_range = {int(key): (0, q.P.size)}
+        chain, n, idx = retrieve_one(q, key, ctx_tail, n_min, n_max, K, min_tokens)
+        return chain, n, (q.report(idx) if idx >= 0 else -1)
     ctx = np.asarray(ctx_tail, dtype=np.int64)
     valid = 0
     while valid < ctx.size and ctx[ctx.size - 1 - valid] >= 0:
@@ -110,16 +139,17 @@ def retrieve_one(pool: RegroupedPool, key: int, ctx_tail, n_min: int, n_max: int
     return best
 
 
-def retrieve(pool: RegroupedPool, keys, ctx_tails, n_min: int, n_max: int, K: int, min_tokens: int = 1):
-    """Batched form.  Returns drafts int32[B][K] (-1 padded), draft_len int32[B],
-    match_n int32[B], pool_index int64[B]."""
+def retrieve(pool: RegroupedPool, keys, ctx_tails, n_min: int, n_max: int, K: int, min_tokens: int = 1, own=None):
+    """Batched form; own: per sequence its own text (list of arrays) or None.  Returns drafts int32[B][K]
+    (-1 padded), draft_len int32[B], match_n int32[B], pool_index int64[B]."""
     B = len(keys)
     drafts = np.full((B, K), -1, dtype=np.int32)
     dl = np.zeros(B, dtype=np.int32)
     mn = np.zeros(B, dtype=np.int32)
     pi = np.full(B, -1, dtype=np.int64)
     for b in range(B):
-        c, n, idx = retrieve_one(pool, keys[b], ctx_tails[b], n_min, n_max, K, min_tokens)
+        c, n, idx = retrieve_one(pool, keys[b], ctx_tails[b], n_min, n_max, K, min_tokens,
+                                 None if own is None else own[b])
         drafts[b, :len(c)] = c
         dl[b], mn[b], pi[b] = len(c), n, idx
     return drafts, dl, mn, pi

@@ -172,3 +172,58 @@ def test_batched_form_and_padding():
     assert drafts.tolist() == [[5, -1, -1], [-1, -1, -1], [3, 5, -1]]
     assert dl.tolist() == [1, 0, 2] and mn.tolist() == [2, 0, 2] and pi.tolist() == [6, -1, 9]
     assert drafts.dtype == np.int32 and pi.dtype == np.int64
+
+
+# ------------------------------------------------------------------ temporary branch (the sequence's own text)
+def test_temporary_branch_hand_worked():
+    """Sec. 3.2: prompt + generated text join the key's trie for the current generation only."""
+    pool = RegroupedPool(*_flatten([[1, 2, 3, 4]], [7]))
+    # pool occurrence of (2, 3) at position 2 -> 4; own text has (2, 3) at positions 2 (-> 9) and 6 (its end, no
+    # successor: not an occurrence). Votes 4:1, 9:1 -> smaller id 4; the pool sequence ends there.
+    own = [7, 2, 3, 9, 5, 2, 3]
+    assert retrieve_one(pool, 7, [5, 2, 3], 1, 2, 3, own=own) == ([4], 2, 2)
+    # two own occurrences outvote the pool: (2, 3) -> 9 twice
+    own = [2, 3, 9, 8, 2, 3, 9, 6, 2, 3]
+    assert retrieve_one(pool, 7, [6, 2, 3], 1, 2, 2, own=own) == ([9, 6], 2, -2 - 5)      # 9 then {8, 6} tie -> 6
+    # nothing in the pool: the draft comes from the own text alone, index = -2 - position
+    pool2 = RegroupedPool(*_flatten([[1, 1, 1]], [7]))
+    assert retrieve_one(pool2, 7, [5, 6], 1, 2, 3, own=[5, 6, 7, 5, 6]) == ([7, 5, 6], 2, -3)
+    # unknown key: only the own text is searched
+    assert retrieve_one(pool2, 99, [5, 6], 1, 2, 3, own=[5, 6, 7, 5, 6]) == ([7, 5, 6], 2, -3)
+    # an own text that repeats nothing changes nothing; None and [] are the plain lookup
+    plain = retrieve_one(pool, 7, [5, 2, 3], 1, 2, 3)
+    assert plain == ([4], 2, 2)
+    assert retrieve_one(pool, 7, [5, 2, 3], 1, 2, 3, own=[]) == plain
+    assert retrieve_one(pool, 7, [5, 2, 3], 1, 2, 3, own=[8, 8, 5, 2, 3]) == plain
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_temporary_branch_against_explicit_trie(seed):
+    """The own text is one more sequence of the key's trie, inserted after the key's pool sequences."""
+    r = np.random.default_rng(100 + seed)
+    for trial in range(120):
+        vocab = int(r.integers(2, 6))
+        n_keys = int(r.integers(1, 3))
+        n_seq = int(r.integers(1, 7))
+        seqs = [r.integers(0, vocab, size=int(r.integers(1, 20))).tolist() for _ in range(n_seq)]
+        keys = r.integers(0, n_keys, size=n_seq).tolist()
+        pool = RegroupedPool(*_flatten(seqs, keys))
+        n_max = int(r.integers(1, 5))
+        n_min = int(r.integers(1, n_max + 1))
+        K = int(r.integers(1, 7))
+        mt = int(r.integers(1, 4))
+        for q in range(6):
+            key = int(r.integers(0, n_keys + 1))
+            own = r.integers(0, vocab, size=int(r.integers(1, 30))).tolist()
+            ctx = ([-1] * n_max + own)[-n_max:]                    # the context is the own text's tail
+            got = retrieve_one(pool, key, ctx, n_min, n_max, K, mt, own=own)
+            grouped = [s for s, k in zip(seqs, keys) if k == key]
+            n_pool = sum(len(s) for s in grouped)
+            base = pool.key_range.get(key, (0, 0))[0]
+            chain, n, idx = trie_retrieve(grouped + [own], 0, ctx, n_min, n_max, K, mt)
+            want = (chain, n, (base + idx if idx < n_pool else -2 - (idx - n_pool)) if idx >= 0 else -1)
+            assert got == want, (seed, trial, q, seqs, keys, key, own, n_min, n_max, K, mt)
+            d, n, idx = got
+            if d and idx <= -2:                                    # the draft literally follows that own-text position
+                pos = -2 - idx
+                assert own[pos + 1: pos + 1 + len(d)] == d and own[pos - n + 1: pos + 1] == ctx[len(ctx) - n:]
