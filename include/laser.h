@@ -40,6 +40,7 @@ extern "C" {
 #define LASER_MAX_NGRAM   8      /* longest context suffix that can be indexed (n_max)            */
 #define LASER_MAX_DRAFT   63     /* largest K (drafts per sequence per step); R = K+1 <= 64 rows    */
 #define LASER_MAX_TOPK    8      /* largest k of the top-k condition                                */
+#define LASER_MAX_OWN_TEXT 4096  /* tokens of a sequence's own text a temporary-branch lookup takes */
 
 /* acceptance rule selector (Sec. 3.4). rank = number of vocabulary entries ordered before the draft
  * (higher logit first, smaller id on ties); q = softmax probability of the draft at temperature 1. */
@@ -99,6 +100,31 @@ int laser_retrieve_drafts(const laser_pool* pool, const int64_t* keys, const int
                           int B, int n_min, int n_max, int K, int min_tokens,
                           int32_t* drafts, int32_t* draft_len, int32_t* match_n,
                           int64_t* pool_index, void* stream);
+
+/* laser_retrieve_drafts_temp: the same lookup with the temporary branch of Sec. 3.2 (the current prompt and
+ * the text generated so far join the group's trie while this text is being generated, and leave it afterwards).
+ * Row b of own_tokens counts as ONE MORE SEQUENCE of keys[b]'s sub-pool, placed after all of its pool sequences;
+ * every rule of laser_retrieve_drafts applies unchanged to the enlarged sub-pool (occurrences need a successor
+ * inside their sequence, so the context suffix at the very end of the own text is not one). Nothing is added to
+ * the pool itself: the "branch" lives in the caller's buffer and ends with it. An unknown key searches the own
+ * text alone.
+ *   own_tokens [dev] int32[B][own_cap]  the sequence's text, oldest token first, left-aligned; normally its
+ *                                       last tokens are ctx_tail
+ *   own_len    [dev] int32[B]           tokens in each row (clamped to 0..own_cap)
+ *   own_cap    1..LASER_MAX_OWN_TEXT    (longer texts: keep the most recent tokens, see laser_own_text_append)
+ *   pool_index out: as above; if no surviving occurrence lies in the pool, -2 - (position in the own text row)
+ * The own text is scanned by the lookup (no index): O(own_len * n) token compares per tried n. */
+int laser_retrieve_drafts_temp(const laser_pool* pool, const int64_t* keys, const int32_t* ctx_tail,
+                               const int32_t* own_tokens, const int32_t* own_len, int own_cap,
+                               int B, int n_min, int n_max, int K, int min_tokens,
+                               int32_t* drafts, int32_t* draft_len, int32_t* match_n,
+                               int64_t* pool_index, void* stream);
+
+/* Device-side bookkeeping for the own text: appends the tokens a step emitted,
+ * out_tokens[b][0..accept_len[b]] (as written by laser_verify_step), to row b; a row that would overflow drops
+ * its oldest tokens first (sliding window of own_cap tokens). own_tokens / own_len [dev] in/out. */
+int laser_own_text_append(int32_t* own_tokens, int32_t* own_len, int own_cap, const int32_t* out_tokens,
+                          const int32_t* accept_len, int B, int K, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Target model (Sec. 2.1 Eq. 1/3, Sec. 3.4 Eq. 6: the LLM that yields K+1 distributions per pass).

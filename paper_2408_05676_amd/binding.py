@@ -56,6 +56,8 @@ def lib():
         "laser_pool_info": [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)],
         "laser_pool_read_tokens": [vp, i64, i64, vp],
         "laser_retrieve_drafts": [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp],
+        "laser_retrieve_drafts_temp": [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp],
+        "laser_own_text_append": [vp, vp, i32, vp, vp, i32, i32, vp],
         "laser_model_create": [C.POINTER(_ModelDesc), vp, C.POINTER(vp)],
         "laser_model_destroy": [vp],
         "laser_kv_create": [C.POINTER(_KVDesc), vp, C.POINTER(vp)],
@@ -165,6 +167,39 @@ def retrieve_drafts(pool: Pool, keys: torch.Tensor, ctx_tail: torch.Tensor, n_mi
                                        _dev(pi, torch.int64, "pool_index"), _stream(stream)),
            "laser_retrieve_drafts")
     return drafts, dl, mn, pi
+
+
+def retrieve_drafts_temp(pool: Pool, keys: torch.Tensor, ctx_tail: torch.Tensor, own_tokens: torch.Tensor,
+                         own_len: torch.Tensor, n_min: int, n_max: int, K: int, min_tokens: int = 1, out=None, stream=None):
+    """laser_retrieve_drafts_temp: the lookup with each sequence's own text [B][own_cap] as a temporary branch."""
+    B = keys.shape[0]
+    if ctx_tail.shape != (B, n_max):
+        raise LaserError("ctx_tail must be [B][n_max]")
+    if own_tokens.dim() != 2 or own_tokens.shape[0] != B or own_len.shape != (B,):
+        raise LaserError("own_tokens must be [B][own_cap] and own_len [B]")
+    dev = keys.device
+    if out is None:
+        out = (torch.empty((B, K), dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+               torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int64, device=dev))
+    drafts, dl, mn, pi = out
+    _check(lib().laser_retrieve_drafts_temp(pool._h, _dev(keys, torch.int64, "keys"), _dev(ctx_tail, torch.int32, "ctx_tail"),
+                                            _dev(own_tokens, torch.int32, "own_tokens"), _dev(own_len, torch.int32, "own_len"),
+                                            own_tokens.shape[1], B, n_min, n_max, K, min_tokens,
+                                            _dev(drafts, torch.int32, "drafts") if K > 0 else None,
+                                            _dev(dl, torch.int32, "draft_len"), _dev(mn, torch.int32, "match_n"),
+                                            _dev(pi, torch.int64, "pool_index"), _stream(stream)),
+           "laser_retrieve_drafts_temp")
+    return drafts, dl, mn, pi
+
+
+def own_text_append(own_tokens: torch.Tensor, own_len: torch.Tensor, out_tokens: torch.Tensor, accept_len: torch.Tensor,
+                    stream=None):
+    """laser_own_text_append."""
+    B, cap = own_tokens.shape
+    K = out_tokens.shape[1] - 1
+    _check(lib().laser_own_text_append(_dev(own_tokens, torch.int32, "own_tokens"), _dev(own_len, torch.int32, "own_len"), cap,
+                                       _dev(out_tokens, torch.int32, "out_tokens"), _dev(accept_len, torch.int32, "accept_len"),
+                                       B, K, _stream(stream)), "laser_own_text_append")
 
 
 class Model:

@@ -37,6 +37,7 @@ constexpr int kCand = 2048;        // occurrences a wave keeps in LDS
 constexpr int kVote = 1024;        // vote-table slots (power of two)
 constexpr int kVoteFill = 768;     // distinct tokens beyond which a vote pass is split
 constexpr int kEmptyTok = -1;
+constexpr int kOwnMax = LASER_MAX_OWN_TEXT;   // tokens of a sequence's own text (temporary branch) a lookup can take
 
 __device__ inline uint32_t fmix32(uint32_t h) {   // bijective 32-bit mixer
     h ^= h >> 16; h *= 0x85EBCA6Bu; h ^= h >> 13; h *= 0xC2B2AE35u; h ^= h >> 16;
@@ -49,11 +50,18 @@ struct RetrieveArgs {
     const int64_t* keys; const int32_t* ctx_tail;
     int B, n_min, n_max, K, min_tokens;
     int32_t* drafts; int32_t* draft_len; int32_t* match_n; int64_t* pool_index;
+    // temporary branch (Sec. 3.2): the sequence's own text, searched as one more sequence of its key's sub-pool,
+    // placed after the pool's sequences; NULL = none
+    const int32_t* own; const int32_t* own_len; int own_cap;
 };
 
-// One wavefront (= one workgroup of 64 lanes) per context.
+// One wavefront (= one workgroup of 64 lanes) per context. OWN: with the temporary branch. Occurrences in the own
+// text are found by a scan of it (it is at most kOwnMax tokens and the wave has it in L2 anyway), always kept
+// in LDS (own_cand, position-ascending) and take part in every vote and filter next to the pool's.
+template <bool OWN>
 __global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
     __shared__ uint32_t cand[kCand];
+    __shared__ uint32_t own_cand[OWN ? kOwnMax : 1];
     __shared__ int vote_tok[kVote];
     __shared__ int vote_cnt[kVote];
     __shared__ int chain[LASER_MAX_DRAFT + 1];
@@ -67,6 +75,8 @@ __global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
 
     int valid = 0;
     while (valid < a.n_max && tail[a.n_max - 1 - valid] >= 0) ++valid;
+    const int32_t* own = OWN ? a.own + (size_t)b * a.own_cap : nullptr;
+    const uint32_t own_len = OWN ? (uint32_t)min(max(a.own_len[b], 0), a.own_cap) : 0u;
 
     int best_len = 0, best_n = 0;
     long long best_idx = -1;
@@ -91,7 +101,20 @@ __global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
             }
             slot = (slot + 1) & a.cap_mask;
         }
-        if (count == 0) continue;
+        // ---- occurrences in the own text: positions e with own[e-n+1..e] == w and a successor e+1 < own_len ----
+        uint32_t mo = 0;
+        if constexpr (OWN) {
+            for (uint32_t e0 = (uint32_t)(n - 1); e0 + 1 < own_len; e0 += 64) {
+                const uint32_t e = e0 + lane;
+                bool hit = e + 1 < own_len;
+                for (int i = 0; i < n && hit; ++i) hit = own[e - (n - 1) + i] == w[i];
+                const uint64_t mask = __ballot(hit);
+                if (hit) own_cand[mo + __popcll(mask & ((1ull << lane) - 1ull))] = e;
+                mo += __popcll(mask);
+            }
+            __syncthreads();
+        }
+        if (count == 0 && mo == 0) continue;
 
         // ---- frequency-greedy chain over the occurrences sa[start .. start+count) ----
         // Survivors are either materialised in LDS (m <= kCand) or, while there are too many,
@@ -113,16 +136,25 @@ __global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
                     for (int i = lane; i < kVote; i += 64) { vote_tok[i] = kEmptyTok; vote_cnt[i] = 0; }
                     if (lane == 0) sh_distinct = 0;
                     __syncthreads();
-                    const uint32_t total = in_lds ? m : count;
+                    const uint32_t total_pool = in_lds ? m : count;
+                    const uint32_t total = total_pool + mo;
                     for (uint32_t i0 = 0; i0 < total; i0 += 64) {
                         uint32_t i = i0 + lane;
                         if (i < total) {
-                            uint32_t e = in_lds ? cand[i] : a.sa[start + i];
-                            bool ok = (e + (uint32_t)j) < a.seq_end[e];
-                            if (ok && !in_lds)
-                                for (int c = 1; c < j; ++c) ok = ok && (a.P[e + c] == chain[c - 1]);
+                            bool ok;
+                            int tok = 0;
+                            if (i < total_pool) {
+                                uint32_t e = in_lds ? cand[i] : a.sa[start + i];
+                                ok = (e + (uint32_t)j) < a.seq_end[e];
+                                if (ok && !in_lds)
+                                    for (int c = 1; c < j; ++c) ok = ok && (a.P[e + c] == chain[c - 1]);
+                                if (ok) tok = a.P[e + j];
+                            } else {
+                                const uint32_t e = own_cand[OWN ? i - total_pool : 0];
+                                ok = e + (uint32_t)j < own_len;
+                                if (ok) tok = own[e + j];
+                            }
                             if (ok) {
-                                int tok = a.P[e + j];
                                 uint32_t hh = fmix32((uint32_t)tok);
                                 if (nparts == 1 || (hh / kVote) % nparts == part) {
                                     uint32_t s = hh & (kVote - 1);
@@ -207,6 +239,24 @@ __global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
                     __syncthreads();
                 }
             }
+            if constexpr (OWN) {
+                uint32_t out = 0;
+                for (uint32_t i0 = 0; i0 < mo; i0 += 64) {
+                    const uint32_t i = i0 + lane;
+                    uint32_t e = 0; bool keep = false;
+                    if (i < mo) {
+                        e = own_cand[i];
+                        keep = e + (uint32_t)j < own_len && own[e + j] == win_tok;
+                    }
+                    const uint64_t mask = __ballot(keep);
+                    const uint32_t pos = out + __popcll(mask & ((1ull << lane) - 1ull));
+                    __syncthreads();               // all reads of this chunk precede the writes
+                    if (keep) own_cand[pos] = e;   // pos <= i: never overtakes unread entries
+                    out += __popcll(mask);
+                }
+                mo = out;
+                __syncthreads();
+            }
         }
         // ---- smallest surviving position ----
         uint32_t mn = 0xFFFFFFFFu;
@@ -222,11 +272,15 @@ __global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
         }
         for (int off = 32; off > 0; off >>= 1) mn = min(mn, (uint32_t)__shfl_xor((int)mn, off));
         __syncthreads();
+        // pool positions precede the own text's; a result that survives only there is reported as -2 - position
+        // (own_cand stays position-ascending through the filters, so its first entry is the smallest)
+        long long idx = (long long)mn;
+        if (OWN && mn == 0xFFFFFFFFu) idx = mo > 0 ? -2ll - (long long)own_cand[0] : -1ll;
 
         if (len >= a.min_tokens) {
-            res_len = len; res_n = n; res_idx = (long long)mn; done = true;
+            res_len = len; res_n = n; res_idx = idx; done = true;
         } else if (len > best_len) {
-            best_len = len; best_n = n; best_idx = (long long)mn;
+            best_len = len; best_n = n; best_idx = idx;
             for (int i = lane; i < len; i += 64) best_chain[i] = chain[i];
             __syncthreads();
         }
@@ -240,6 +294,32 @@ __global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
         a.match_n[b] = res_len > 0 ? res_n : 0;
         a.pool_index[b] = res_len > 0 ? res_idx : -1;
     }
+}
+
+// Appends the tokens a step emitted (out_tokens[b][0 .. accept_len[b]]) to row b of the own-text buffer; a full row
+// drops its oldest tokens (sliding window of `cap`). One workgroup per sequence.
+__global__ __launch_bounds__(256) void own_text_append_kernel(int32_t* own, int32_t* own_len, int cap, const int32_t* out_tokens,
+                                                              const int32_t* accept_len, int K) {
+    const int b = blockIdx.x, tid = threadIdx.x;
+    int32_t* row = own + (size_t)b * cap;
+    const int32_t* nw = out_tokens + (size_t)b * (K + 1);
+    int n_new = min(max(accept_len[b], 0), K) + 1;
+    int len = min(max(own_len[b], 0), cap);
+    const int skip = max(n_new - cap, 0);              // more new tokens than the row holds: keep the newest
+    n_new -= skip;
+    const int shift = max(len + n_new - cap, 0);
+    if (shift > 0) {
+        const int keep = len - shift;                  // row[shift .. len) moves to row[0 .. keep)
+        for (int base = 0; base < keep; base += 256) {
+            const int i = base + tid;
+            const int32_t v = i < keep ? row[i + shift] : 0;
+            __syncthreads();                           // every read of this chunk precedes its writes; later chunks read beyond them
+            if (i < keep) row[i] = v;
+        }
+        len = max(keep, 0);
+    }
+    for (int i = tid; i < n_new; i += 256) row[len + i] = nw[skip + i];
+    if (tid == 0) own_len[b] = len + n_new;
 }
 
 // ------------------------------------------------------------------------------------ host build
@@ -443,10 +523,9 @@ extern "C" int laser_pool_read_tokens(const laser_pool* pool, int64_t start, int
     return LASER_OK;
 }
 
-extern "C" int laser_retrieve_drafts(const laser_pool* pool, const int64_t* keys, const int32_t* ctx_tail,
-                                     int B, int n_min, int n_max, int K, int min_tokens,
-                                     int32_t* drafts, int32_t* draft_len, int32_t* match_n,
-                                     int64_t* pool_index, void* stream) {
+static int retrieve_impl(const laser_pool* pool, const int64_t* keys, const int32_t* ctx_tail, const int32_t* own,
+                         const int32_t* own_len, int own_cap, int B, int n_min, int n_max, int K, int min_tokens,
+                         int32_t* drafts, int32_t* draft_len, int32_t* match_n, int64_t* pool_index, void* stream) {
     LASER_REQUIRE(pool != nullptr, LASER_E_INVALID_ARG, "pool is NULL");
     const Pool* p = reinterpret_cast<const Pool*>(pool);
     LASER_REQUIRE(B >= 0, LASER_E_INVALID_ARG, "B < 0");
@@ -457,8 +536,43 @@ extern "C" int laser_retrieve_drafts(const laser_pool* pool, const int64_t* keys
     LASER_REQUIRE(keys && ctx_tail && draft_len && match_n && pool_index && (drafts || K == 0),
                   LASER_E_INVALID_ARG, "NULL device buffer");
     RetrieveArgs a{p->P, p->seq_end, p->sa, p->table, p->cap_mask, keys, ctx_tail,
-                   B, n_min, n_max, K, min_tokens < 1 ? 1 : min_tokens, drafts, draft_len, match_n, pool_index};
-    hipLaunchKernelGGL(retrieve_kernel, dim3(B), dim3(64), 0, (hipStream_t)stream, a);
+                   B, n_min, n_max, K, min_tokens < 1 ? 1 : min_tokens, drafts, draft_len, match_n, pool_index,
+                   own, own_len, own_cap};
+    if (own) hipLaunchKernelGGL(retrieve_kernel<true>, dim3(B), dim3(64), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL(retrieve_kernel<false>, dim3(B), dim3(64), 0, (hipStream_t)stream, a);
+    LASER_HIP_CHECK(hipGetLastError());
+    return LASER_OK;
+}
+
+extern "C" int laser_retrieve_drafts(const laser_pool* pool, const int64_t* keys, const int32_t* ctx_tail,
+                                     int B, int n_min, int n_max, int K, int min_tokens,
+                                     int32_t* drafts, int32_t* draft_len, int32_t* match_n,
+                                     int64_t* pool_index, void* stream) {
+    return retrieve_impl(pool, keys, ctx_tail, nullptr, nullptr, 0, B, n_min, n_max, K, min_tokens, drafts, draft_len,
+                         match_n, pool_index, stream);
+}
+
+extern "C" int laser_retrieve_drafts_temp(const laser_pool* pool, const int64_t* keys, const int32_t* ctx_tail,
+                                          const int32_t* own_tokens, const int32_t* own_len, int own_cap,
+                                          int B, int n_min, int n_max, int K, int min_tokens,
+                                          int32_t* drafts, int32_t* draft_len, int32_t* match_n,
+                                          int64_t* pool_index, void* stream) {
+    LASER_REQUIRE(own_cap >= 1 && own_cap <= LASER_MAX_OWN_TEXT, LASER_E_INVALID_ARG, "own_cap %d outside 1..%d", own_cap,
+                  LASER_MAX_OWN_TEXT);
+    LASER_REQUIRE(B <= 0 || (own_tokens && own_len), LASER_E_INVALID_ARG, "NULL own-text buffer");
+    return retrieve_impl(pool, keys, ctx_tail, own_tokens, own_len, own_cap, B, n_min, n_max, K, min_tokens, drafts,
+                         draft_len, match_n, pool_index, stream);
+}
+
+extern "C" int laser_own_text_append(int32_t* own_tokens, int32_t* own_len, int own_cap, const int32_t* out_tokens,
+                                     const int32_t* accept_len, int B, int K, void* stream) {
+    LASER_REQUIRE(B >= 0 && K >= 0 && K <= LASER_MAX_DRAFT, LASER_E_INVALID_ARG, "B < 0 or K outside 0..%d", LASER_MAX_DRAFT);
+    LASER_REQUIRE(own_cap >= 1 && own_cap <= LASER_MAX_OWN_TEXT, LASER_E_INVALID_ARG, "own_cap %d outside 1..%d", own_cap,
+                  LASER_MAX_OWN_TEXT);
+    if (B == 0) return LASER_OK;
+    LASER_REQUIRE(own_tokens && own_len && out_tokens && accept_len, LASER_E_INVALID_ARG, "NULL device buffer");
+    hipLaunchKernelGGL(own_text_append_kernel, dim3(B), dim3(256), 0, (hipStream_t)stream, own_tokens, own_len, own_cap,
+                       out_tokens, accept_len, K);
     LASER_HIP_CHECK(hipGetLastError());
     return LASER_OK;
 }
