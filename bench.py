@@ -155,7 +155,8 @@ def run_workload(args, name, steps, warmup, weights_cache):
     weights = weights_cache[wkey]
     n_gen = (steps + warmup) * R + 16                       # tokens the replayed continuation must cover
     max_len = ctx_len + 2 * n_gen + R + 32
-    eng = Engine(sh, weights, B, K, max_len, n_max)
+    own_cap = min(4096, max_len) if args.temp_branch else 0   # temporary branch: the sequence's own text is searched too
+    eng = Engine(sh, weights, B, K, max_len, n_max, own_text_cap=own_cap)
     path = "generic" if args.no_fused else args.path
     fused_possible = B * R <= 16 and sh.n_layers > 0
     if not fused_possible:
@@ -169,6 +170,10 @@ def run_workload(args, name, steps, warmup, weights_cache):
             eng.kv.set_len(b, ctx_len - 1)
         eng.pending.copy_(torch.as_tensor(np.ascontiguousarray(ctx["ctx"][:, -1]), dtype=torch.int32))
         eng.ctx_tail.copy_(torch.as_tensor(np.ascontiguousarray(ctx["ctx"][:, -n_max:]), dtype=torch.int32))
+        if eng.own_text is not None:
+            t = min(ctx_len, own_cap)
+            eng.own_text[:, :t] = torch.as_tensor(np.ascontiguousarray(ctx["ctx"][:, ctx_len - t:]), dtype=torch.int32).cuda()
+            eng.own_len.fill_(t)
 
     # Few-row workloads have two verify paths; time a few steps of each (no pool yet: rows without drafts
     # cost the same) and keep the faster for everything that follows, the replayed continuation included.
@@ -283,7 +288,7 @@ def run_workload(args, name, steps, warmup, weights_cache):
         "ms_per_step": elapsed * 1e3 / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 weights x fp16 activations (two-plane split where single fp16 is too coarse), fp32 accumulate", "data": "synthetic",
         "config": {"workload": wl["label"], "batch": B, "context": ctx_len, "K": K, "regime": args.regime,
-                   "topk": topk, "p": p, "lm_gain": gain, "replay_noise": replay_noise if args.regime != "floor" else None,
+                   "topk": topk, "p": p, "lm_gain": gain, "temporary_branch": bool(args.temp_branch), "replay_noise": replay_noise if args.regime != "floor" else None,
                    "tokens_per_step": tokens_per_step, "accepted_drafts_per_step": tokens_per_step - 1.0,
                    # context: the same library decoding one token per step (K = 0), and the floor of this step shape
                    # (no draft ever accepted); the paper reports 3-5x over its own autoregressive decoding on an RTX 4090
@@ -317,6 +322,9 @@ def main():
                     help="substitution rate of the replayed copy of the model's own continuation that is added to the "
                          "pool (default: the rate that puts the accepted length per step into the band the paper reports)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--temp-branch", action="store_true",
+                    help="search each sequence's own text (prompt + emitted tokens, last 4096) as a temporary branch "
+                         "of its pool at every retrieval (laser_retrieve_drafts_temp)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 1 GiB device copy before the timed region (a kernel of known "
                          "traffic against which hardware byte counters are scaled)")

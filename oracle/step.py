@@ -64,13 +64,17 @@ def verify_step(dec: Decoder, seqs, drafts, draft_len, k: int, p: float, mode: i
 
 
 def laser_step(dec: Decoder, pool: retrieval.RegroupedPool, seqs, n_min: int, n_max: int, K: int,
-               k: int, p: float, mode: int = 0, min_tokens: int = 1, return_logits: bool = False):
-    """retrieve -> verify -> accept -> commit for a batch of sequences."""
+               k: int, p: float, mode: int = 0, min_tokens: int = 1, return_logits: bool = False,
+               temporary_branch: int = 0):
+    """retrieve -> verify -> accept -> commit for a batch of sequences.
+    temporary_branch = W > 0: each sequence's own text (its last W tokens: prompt and everything emitted so far)
+    is searched as one more sequence of its key's sub-pool (Sec. 3.2)."""
     tails = []
     for s in seqs:
         t = s.tokens[-n_max:]
         tails.append([-1] * (n_max - len(t)) + t)
-    drafts, dl, mn, pi = retrieval.retrieve(pool, [s.key for s in seqs], tails, n_min, n_max, K, min_tokens)
+    own = [s.tokens[-temporary_branch:] for s in seqs] if temporary_branch > 0 else None
+    drafts, dl, mn, pi = retrieval.retrieve(pool, [s.key for s in seqs], tails, n_min, n_max, K, min_tokens, own=own)
     res = verify_step(dec, seqs, drafts, dl, k, p, mode, return_logits)
     res.update({"drafts": drafts, "draft_len": dl, "match_n": mn, "pool_index": pi})
     return res

@@ -32,7 +32,9 @@ class Engine:
     state (pending token, context tail) lives on the device."""
 
     def __init__(self, shape, weights: dict, batch: int, K: int, max_len: int, n_max: int = 3,
-                 prefill_chunk: int = 16):
+                 prefill_chunk: int = 16, own_text_cap: int = 0):
+        """own_text_cap > 0: keep each sequence's own text (prompt + emitted tokens, the most recent own_text_cap of
+        them) on the device and search it as a temporary branch at every retrieval (Sec. 3.2)."""
         self.shape, self.B, self.K, self.n_max = shape, batch, K, n_max
         R = max(K + 1, prefill_chunk)
         pages_per_seq = (max_len + 15) // 16 + 1
@@ -56,6 +58,10 @@ class Engine:
         self.accept_len = torch.zeros(batch, dtype=torch.int32, device=dev)
         self.out_tokens = torch.full((batch, K + 1), -1, dtype=torch.int32, device=dev)
         self.pool = None
+        self.own_text = self.own_len = None
+        if own_text_cap > 0:
+            self.own_text = torch.zeros((batch, own_text_cap), dtype=torch.int32, device=dev)
+            self.own_len = torch.zeros(batch, dtype=torch.int32, device=dev)
 
     def set_pool(self, pool: L.Pool, keys):
         self.pool = pool
@@ -80,16 +86,27 @@ class Engine:
         t = min(T, self.n_max)
         tail[:, self.n_max - t:] = prompts[:, T - t:]
         self.ctx_tail.copy_(torch.as_tensor(tail))
+        if self.own_text is not None:
+            cap = self.own_text.shape[1]
+            t = min(T, cap)
+            self.own_text[:, :t] = torch.as_tensor(np.ascontiguousarray(prompts[:, T - t:]), dtype=torch.int32).cuda()
+            self.own_len.fill_(t)
 
     def step(self, topk: int, p: float, mode: int = L.MODE_RV, n_min: int = 1, retrieve: bool = True):
         """retrieve -> verify -> commit -> context update; all asynchronous."""
         if retrieve and self.pool is not None and self.K > 0:
-            L.retrieve_drafts(self.pool, self.keys, self.ctx_tail, n_min, self.n_max, self.K, 1,
-                              out=(self.drafts, self.draft_len, self.match_n, self.pool_index))
+            out = (self.drafts, self.draft_len, self.match_n, self.pool_index)
+            if self.own_text is not None:
+                L.retrieve_drafts_temp(self.pool, self.keys, self.ctx_tail, self.own_text, self.own_len, n_min, self.n_max,
+                                       self.K, 1, out=out)
+            else:
+                L.retrieve_drafts(self.pool, self.keys, self.ctx_tail, n_min, self.n_max, self.K, 1, out=out)
         L.verify_step(self.model, self.kv, self.seq_ids, self.pending, self.drafts, self.draft_len, topk, p, mode,
                       out=(self.accept_len, self.out_tokens))
         L.kv_commit(self.kv, self.seq_ids, self.accept_len)
         L.ctx_advance(self.ctx_tail, self.pending, self.out_tokens, self.accept_len)
+        if self.own_text is not None:
+            L.own_text_append(self.own_text, self.own_len, self.out_tokens, self.accept_len)
 
     def generate_greedy(self, n_tokens: int) -> np.ndarray:
         """Plain autoregressive greedy decoding (K = 0: one row per sequence): int32[B][n_tokens]."""
@@ -101,6 +118,8 @@ class Engine:
             L.verify_step(self.model, self.kv, self.seq_ids, self.pending, no_drafts, zero, 1, -1.0, out=(self.accept_len, tok))
             L.kv_commit(self.kv, self.seq_ids, self.accept_len)
             L.ctx_advance(self.ctx_tail, self.pending, tok, self.accept_len)
+            if self.own_text is not None:
+                L.own_text_append(self.own_text, self.own_len, tok, self.accept_len)
             out[:, i] = tok[:, 0]
         return out.cpu().numpy()
 

@@ -20,6 +20,16 @@ pytestmark = pytest.mark.gpu
 @pytest.mark.parametrize("fused", [1, 0])
 @pytest.mark.parametrize("k,p", [(1, -1.0), (2, 0.004)])
 def test_tiny_configuration_full_loop(fused, k, p):
+    _full_loop(fused, k, p, own_cap=0)
+
+
+def test_tiny_configuration_full_loop_with_temporary_branch():
+    """The same loop with every sequence's own text (a window of its last 70 tokens, so that it slides during
+    the run) searched as a temporary branch at every retrieval; the pool index of a hit there is negative."""
+    _full_loop(1, 2, 0.004, own_cap=70)
+
+
+def _full_loop(fused, k, p, own_cap):
     import paper_2408_05676_amd as laser
     from paper_2408_05676_amd.harness import Engine, stacked_weights
     sh = synth.SHAPES["tiny"].with_(lm_gain=4.0)
@@ -49,7 +59,7 @@ def test_tiny_configuration_full_loop(fused, k, p):
     seqs = [step.Sequence(dec, int(ctx["keys"][b]), ctx["ctx"][b], cap) for b in range(B)]
 
     weights = stacked_weights(lambda n, l: torch_gen_weight(sh, n, l, "cuda"), sh)
-    eng = Engine(sh, weights, B, K, cap, n_max)
+    eng = Engine(sh, weights, B, K, cap, n_max, own_text_cap=own_cap)
     eng.model.set_option("fused", fused)
     eng.prefill(ctx["ctx"])
     pool = laser.Pool(toks, off, keys, n_max)
@@ -59,7 +69,7 @@ def test_tiny_configuration_full_loop(fused, k, p):
     for it in range(n_steps):
         eng.step(k, p)
         torch.cuda.synchronize()
-        ora = step.laser_step(dec, opool, seqs, 1, n_max, K, k, p, 0, return_logits=True)
+        ora = step.laser_step(dec, opool, seqs, 1, n_max, K, k, p, 0, return_logits=True, temporary_branch=own_cap)
         d, dl = eng.drafts.cpu().numpy(), eng.draft_len.cpu().numpy()
         assert (dl == ora["draft_len"]).all() and (d == ora["drafts"]).all(), it
         assert (eng.match_n.cpu().numpy() == ora["match_n"]).all() and (eng.pool_index.cpu().numpy() == ora["pool_index"]).all(), it
@@ -74,6 +84,9 @@ def test_tiny_configuration_full_loop(fused, k, p):
         assert eng.pending.cpu().tolist() == [s.pending for s in seqs]
         tails = [([-1] * n_max + list(s.tokens))[-n_max:] for s in seqs]
         assert eng.ctx_tail.cpu().tolist() == tails
+        if own_cap:
+            ol, ot = eng.own_len.cpu().numpy(), eng.own_text.cpu().numpy()
+            assert [ot[b, :ol[b]].tolist() for b in range(B)] == [list(s.tokens)[-own_cap:] for s in seqs]
     print(f"[tiny loop fused={fused} k={k} p={p}] {it + 1} steps, {emitted} tokens emitted "
           f"({emitted / max(1, (it + 1) * B):.2f} per step and sequence), in-tolerance flips {flips}")
     assert emitted > (it + 1) * B or flips, "no draft was ever accepted: the replayed continuation is not being found"
