@@ -36,15 +36,20 @@ struct GemmMidArgs {
     float* part;            // gridDim.y > 1: [gridDim.y][M][N] partial results
 };
 
-template <int MB, int EPI, bool SPLIT>
-__global__ __launch_bounds__(256, 2) void gemm_mid_kernel(GemmMidArgs a) {
+// NW = waves (weight tiles) per workgroup, 4 or 8: what enters a compute unit per step is NW x 4 KB of weights
+// plus ONE activation chunk, so more waves per workgroup mean fewer chunk bytes per weight byte but fewer
+// workgroups to spread over the chip; gemm_mid_plan picks per launch shape.
+template <int MB, int EPI, bool SPLIT, int NW>
+__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void gemm_mid_kernel(GemmMidArgs a) {
     constexpr int ROWS = MB * 16, NP = SPLIT ? 2 : 1;
+    constexpr int NT = NW * 64;                              // threads
+    constexpr int NPIECE = (ROWS * 16 + NT - 1) / NT;        // 16-byte pieces of a plane's chunk per thread
     constexpr int LDH = kGemmKStep + 8;   // halves per LDS row: 272 bytes, the 16 rows of a 16-byte read hit distinct banks
     __shared__ __attribute__((aligned(16))) uint16_t sx[NP * ROWS * LDH];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int r = lane & 15, g = lane >> 4;
     const int ntiles = a.N / 16;
-    const int vt = blockIdx.x * 4 + wave;
+    const int vt = blockIdx.x * NW + wave;
     const int tile_raw = EPI == EPI_SWIGLU ? vt >> 1 : vt;
     const int sel = EPI == EPI_SWIGLU ? vt & 1 : 0;          // SwiGLU: 0 = gate rows, 1 = up rows
     const bool active = tile_raw < ntiles;
@@ -54,13 +59,14 @@ __global__ __launch_bounds__(256, 2) void gemm_mid_kernel(GemmMidArgs a) {
     const int sbeg = ks * per, send = min(ksteps, sbeg + per);
 
     const uint16_t* const wp = a.W + ((size_t)sel * a.N + (size_t)tile * 16 + r) * a.Kd + g * 32;
-    // staging: piece p = tid + 256 i covers row p / 16, 16-byte column p % 16 of the chunk
+    // staging: piece p = tid + NT i covers row p / 16, 16-byte column p % 16 of the chunk; where the pieces do not
+    // divide evenly the last ones are staged twice (same bytes to the same place)
     // (32-bit element offsets from the uniform plane bases: M * Kd is far below 2^31 here)
-    unsigned xoff[MB];
-    int xdst[MB];
+    unsigned xoff[NPIECE];
+    int xdst[NPIECE];
 #pragma unroll
-    for (int i = 0; i < MB; ++i) {
-        const int p = tid + 256 * i, row = p >> 4, c = p & 15;
+    for (int i = 0; i < NPIECE; ++i) {
+        const int p = min(tid + NT * i, ROWS * 16 - 1), row = p >> 4, c = p & 15;
         xoff[i] = (unsigned)min(row, a.M - 1) * (unsigned)a.Kd + c * 8;
         xdst[i] = row * LDH + c * 8;
     }
@@ -69,7 +75,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mid_kernel(GemmMidArgs a) {
     for (int mb = 0; mb < MB; ++mb) { acc[mb] = float4_t{0.f, 0.f, 0.f, 0.f}; acl[mb] = float4_t{0.f, 0.f, 0.f, 0.f}; }
 
     Frag8 w0[4], w1[4];
-    u32x4 xr[NP][MB];
+    u32x4 xr[NP][NPIECE];
     auto load_w = [&](int st, Frag8 (&w)[4]) {              // clamped: always in bounds, surplus loads are dropped
         const int k0 = min(st, ksteps - 1) * kGemmKStep;
 #pragma unroll
@@ -80,7 +86,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mid_kernel(GemmMidArgs a) {
         const uint16_t* const xb = a.X + k0;
         const uint16_t* const xlb = SPLIT ? a.Xlo + k0 : nullptr;
 #pragma unroll
-        for (int i = 0; i < MB; ++i) {
+        for (int i = 0; i < NPIECE; ++i) {
             xr[0][i] = *reinterpret_cast<const u32x4*>(xb + xoff[i]);
             if constexpr (SPLIT) xr[NP - 1][i] = *reinterpret_cast<const u32x4*>(xlb + xoff[i]);
         }
@@ -89,7 +95,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mid_kernel(GemmMidArgs a) {
     auto step = [&](int st, Frag8 (&cur)[4], Frag8 (&fill)[4]) {
         load_w(st + 1, fill);
 #pragma unroll
-        for (int i = 0; i < MB; ++i) {
+        for (int i = 0; i < NPIECE; ++i) {
             *reinterpret_cast<u32x4*>(sx + xdst[i]) = xr[0][i];
             if constexpr (SPLIT) *reinterpret_cast<u32x4*>(sx + ROWS * LDH + xdst[i]) = xr[NP - 1][i];
         }
@@ -139,7 +145,8 @@ __global__ __launch_bounds__(256, 2) void gemm_mid_kernel(GemmMidArgs a) {
         for (int i = 0; i < 4; ++i) v[mb][i] = SPLIT ? acc[mb][i] + acl[mb][i] * kLoInv : acc[mb][i];
     const int n = tile * 16 + 4 * g;
     if constexpr (EPI == EPI_SWIGLU) {
-        float* ex = reinterpret_cast<float*>(sx);             // [pair 0..1][mb][i][lane]; the loop's last barrier freed sx
+        static_assert((NW / 2) * MB * 4 * 64 * sizeof(float) <= sizeof(sx), "the exchange area must fit the staging area");
+        float* ex = reinterpret_cast<float*>(sx);             // [pair][mb][i][lane]; the loop's last barrier freed sx
         if (sel == 1) {
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
@@ -175,25 +182,54 @@ __global__ __launch_bounds__(256, 2) void gemm_mid_kernel(GemmMidArgs a) {
     }
 }
 
-// Reduction parts for a store / accumulate projection: doubled while the launch would leave compute units idle,
-// each part keeps at least two steps and the partial results fit the workspace. A function of the shape only.
-inline int gemm_mid_parts(int M, int N, int Kd, size_t part_floats) {
-    const int groups = (N / 16 + 3) / 4, ksteps = Kd / kGemmKStep;
-    int S = 1;
-    while (S < 8 && groups * S < 256 && ksteps / (2 * S) >= 2 && (size_t)(2 * S) * M * N <= part_floats) S *= 2;
-    return S;
+// Compute units of the device (asked once).
+inline int gemm_mid_cu_count() {
+    static const int n = [] {
+        int v = 0;
+        return hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, 0) == hipSuccess && v > 0 ? v : 256;
+    }();
+    return n;
 }
 
-// Caller guarantees 16 < M <= 80, N % 16 == 0, Kd % 128 == 0, and S == 1 for EPI_SWIGLU.
+struct GemmMidPlan { int NW, S; };
+
+// Waves per workgroup and reduction parts for one launch: the pair with the fewest kilobytes entering the busiest
+// compute unit (weights + activation chunks over its workgroups' steps, two steps' worth of start-up per
+// workgroup, plus its share of writing and re-reading the partial results). Parts only for store / accumulate
+// epilogues with a workspace, each part at least two steps. A function of the launch shape only.
+inline GemmMidPlan gemm_mid_plan(int M, int N, int Kd, int planes, bool swiglu, size_t part_floats) {
+    const int n_cu = gemm_mid_cu_count();
+    const long vtiles = (long)(N / 16) * (swiglu ? 2 : 1), ksteps = Kd / kGemmKStep;
+    const long xkb = (long)((M + 15) / 16) * 4 * planes;
+    GemmMidPlan best{4, 1};
+    double best_cost = 1e300;
+    for (int nw = 4; nw <= 8; nw *= 2)
+        for (int S = 1; S <= 8; S *= 2) {
+            if (S > 1 && (swiglu || ksteps / S < 2 || (size_t)S * M * N > part_floats)) break;
+            const long n_wg = (vtiles + nw - 1) / nw * S;
+            const long per_cu = (n_wg + n_cu - 1) / n_cu, steps = (ksteps + S - 1) / S;
+            const double cost = (double)per_cu * (steps + 2) * (nw * 4 + xkb) +
+                                (S > 1 ? 2.0 * S * M * N * 4 / 1024 / n_cu : 0.0);
+            if (cost < best_cost) { best_cost = cost; best = {nw, S}; }
+        }
+    return best;
+}
+
+// Caller guarantees 16 < M <= 80, N % 16 == 0, Kd % 128 == 0, and a plan made for this shape.
 template <int EPI, bool SPLIT>
-inline void launch_gemm_mid(const GemmMidArgs& a, int S, hipStream_t stream) {
-    const int ntiles = a.N / 16, mblocks = (a.M + 15) / 16;
-    dim3 grid((unsigned)(((EPI == EPI_SWIGLU ? 2 : 1) * ntiles + 3) / 4), (unsigned)S);
+inline void launch_gemm_mid(const GemmMidArgs& a, GemmMidPlan pl, hipStream_t stream) {
+    const int vtiles = (EPI == EPI_SWIGLU ? 2 : 1) * (a.N / 16), mblocks = (a.M + 15) / 16;
+    dim3 grid((unsigned)((vtiles + pl.NW - 1) / pl.NW), (unsigned)pl.S);
+    auto go = [&](auto mbc) {
+        constexpr int mb = decltype(mbc)::value;
+        if (pl.NW == 8) hipLaunchKernelGGL((gemm_mid_kernel<mb, EPI, SPLIT, 8>), grid, dim3(512), 0, stream, a);
+        else hipLaunchKernelGGL((gemm_mid_kernel<mb, EPI, SPLIT, 4>), grid, dim3(256), 0, stream, a);
+    };
     switch (mblocks) {
-        case 2: hipLaunchKernelGGL((gemm_mid_kernel<2, EPI, SPLIT>), grid, dim3(256), 0, stream, a); break;
-        case 3: hipLaunchKernelGGL((gemm_mid_kernel<3, EPI, SPLIT>), grid, dim3(256), 0, stream, a); break;
-        case 4: hipLaunchKernelGGL((gemm_mid_kernel<4, EPI, SPLIT>), grid, dim3(256), 0, stream, a); break;
-        default: hipLaunchKernelGGL((gemm_mid_kernel<5, EPI, SPLIT>), grid, dim3(256), 0, stream, a); break;
+        case 2: go(std::integral_constant<int, 2>{}); break;
+        case 3: go(std::integral_constant<int, 3>{}); break;
+        case 4: go(std::integral_constant<int, 4>{}); break;
+        default: go(std::integral_constant<int, 5>{}); break;
     }
 }
 

@@ -319,7 +319,7 @@ int run_head(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* 
         }
         if (M <= kHeadMidMaxRows && m->d.d_model % kGemmKStep == 0 && m->d.vocab % 16 == 0) {
             GemmMidArgs t{m->d.wlm, h, nullptr, M, m->d.vocab, m->d.d_model, logits, nullptr, nullptr};
-            launch_gemm_mid<EPI_F32, false>(t, 1, stream);
+            launch_gemm_mid<EPI_F32, false>(t, gemm_mid_plan(M, m->d.vocab, m->d.d_model, 1, false, 0), stream);
         } else {
             const int tiles_m = (M + GM_BM - 1) / GM_BM, tiles_n = (m->d.vocab + 127) / 128;
             GemmTileArgs t{m->d.wlm, h, nullptr, M, m->d.vocab, m->d.d_model, tiles_m, tiles_n, 1, logits, nullptr};

@@ -293,11 +293,11 @@ static int launch_gemm(GemmArgs& a_in, hipStream_t stream) {
     if (mblocks >= 2 && (a.Xlo || EPI == EPI_RESID) && a.Kd % kGemmKStep == 0) {
         // 17..80 rows: activations staged in LDS and shared by the workgroup's four weight tiles
         GemmMidArgs t{a.W, a.X, a.Xlo, a.M, a.N, a.Kd, a.outf, a.outh, a.part};
-        const int S = EPI == EPI_SWIGLU || !a.part ? 1 : gemm_mid_parts(a.M, a.N, a.Kd, a.part_floats);
-        if (a.Xlo) launch_gemm_mid<EPI, true>(t, S, stream);
-        else if constexpr (EPI == EPI_RESID) launch_gemm_mid<EPI, false>(t, S, stream);
+        const GemmMidPlan pl = gemm_mid_plan(a.M, a.N, a.Kd, a.Xlo ? 2 : 1, EPI == EPI_SWIGLU, a.part ? a.part_floats : 0);
+        if (a.Xlo) launch_gemm_mid<EPI, true>(t, pl, stream);
+        else if constexpr (EPI == EPI_RESID) launch_gemm_mid<EPI, false>(t, pl, stream);
         LASER_HIP_CHECK(hipGetLastError());
-        a.n_part = S > 1 ? S : 0;
+        a.n_part = pl.S > 1 ? pl.S : 0;
         return LASER_OK;
     }
     const int MB = mblocks >= 5 ? 5 : mblocks;
