@@ -59,38 +59,41 @@ __global__ __launch_bounds__(256) void embed_rmsnorm_kernel(
 
 // xn_lo may be NULL (the final norm feeds the output head, which takes single fp16 rows).
 // n_part > 0: the projection before this norm left its result as n_part partial sums (part + p * part_stride, same
-// [row][d] layout): they are added to the residual row in order p = 0, 1, .. first, and the row is written back.
+// [row][d] layout): they are added to the residual row in order p = 0, 1, .. and the row is written back, in the
+// same pass that takes the row into registers and sums its squares (every thread touches only its own columns).
 __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ gain,
                                                       int d, float eps, uint16_t* __restrict__ xn, uint16_t* __restrict__ xn_lo,
                                                       const float* __restrict__ part, int n_part, size_t part_stride) {
     __shared__ float sm[4];
     const size_t m = blockIdx.x;
-    if (n_part > 0) {
-        float4* xw = reinterpret_cast<float4*>(x + m * d);
-        for (int i = threadIdx.x; i < d / 4; i += 256) {
-            float4 t = xw[i];
+    // the row stays in registers between the two passes (up to 8192 columns; d is a multiple of 128)
+    constexpr int NV = 8;
+    const int n4 = d / 4;
+    float4* xw = reinterpret_cast<float4*>(x + m * d);
+    const float4* xr = xw;
+    auto take = [&](int i) {                     // column group i of the row, partial sums added and stored back
+        float4 t = xr[i];
+        if (n_part > 0) {
             for (int p = 0; p < n_part; ++p) {
                 const float4 q = reinterpret_cast<const float4*>(part + p * part_stride + m * d)[i];
                 t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
             }
             xw[i] = t;
         }
-        __syncthreads();       // the passes below read what other threads of this block have just written
-    }
-    // the row stays in registers between the two passes (up to 8192 columns; d is a multiple of 128)
-    constexpr int NV = 8;
-    const int n4 = d / 4;
-    const float4* xr = reinterpret_cast<const float4*>(x + m * d);
+        return t;
+    };
     float4 v[NV];
     float ss = 0.f;
 #pragma unroll
     for (int c = 0; c < NV; ++c) {
         const int i = c * 256 + threadIdx.x;
-        v[c] = xr[i < n4 ? i : 0];
-        if (i < n4) ss += v[c].x * v[c].x + v[c].y * v[c].y + v[c].z * v[c].z + v[c].w * v[c].w;
+        if (i < n4) {
+            v[c] = take(i);
+            ss += v[c].x * v[c].x + v[c].y * v[c].y + v[c].z * v[c].z + v[c].w * v[c].w;
+        }
     }
-    for (int i = NV * 256 + threadIdx.x; i < n4; i += 256) {
-        const float4 t = xr[i];
+    for (int i = NV * 256 + threadIdx.x; i < n4; i += 256) {      // wider rows: re-read below by the same thread
+        const float4 t = take(i);
         ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
     }
     ss = block_sum_256(ss, sm);
