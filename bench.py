@@ -192,6 +192,8 @@ def run_workload(args, name, steps, warmup, weights_cache):
             rollback()
         path = min(path_ms, key=path_ms.get)
     eng.model.set_option("fused", 1 if path == "fused" else 0)
+    for kv_ in args.model_option:
+        eng.model.set_option(kv_.split("=")[0], int(kv_.split("=")[1]))
 
     pool_data = synth.gen_pool(spec)
     toks, off, keys = pool_data["tokens"], pool_data["seq_off"], pool_data["seq_key"]
@@ -322,6 +324,8 @@ def main():
                     help="substitution rate of the replayed copy of the model's own continuation that is added to the "
                          "pool (default: the rate that puts the accepted length per step into the band the paper reports)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--model-option", action="append", default=[], metavar="NAME=VALUE",
+                    help="laser_model_set_option before the run (tuning knobs such as attn_whole_mult=1)")
     ap.add_argument("--temp-branch", action="store_true",
                     help="search each sequence's own text (prompt + emitted tokens, last 4096) as a temporary branch "
                          "of its pool at every retrieval (laser_retrieve_drafts_temp)")

@@ -640,12 +640,14 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
     int pend = 0;              // partial results of the last down projection still to be added to the residual
     const int nqt = (R + 15) / 16;
     const int npages_ub = (max_len_ub + R + kPageSize - 1) / kPageSize;
-    // With enough (sequence, head, query tile) triples to fill the chip several times over, the context is not
-    // split: no partials, no combine kernel. (The split policy is a function of the launch shape only, so steps
+    // With a (sequence, head, query tile) triple for every second compute unit the context is not split: no
+    // partials, no combine kernel; the four waves of a workgroup still share a context's pages. Measured: 128 triples
+    // (1B shape, 8 sequences, context 512) 2.02 -> 1.99 ms per step unsplit, 256 triples (7B, 8 sequences, context
+    // 1024) 8.17 -> 7.71 ms, 32 triples (7B, one sequence) slower unsplit. Option "attn_whole_min" moves the threshold. (The split policy is a function of the launch shape only, so steps
     // of one shape stay bit-identical to each other; different batch sizes may differ in the last bits.)
     int ncu = 0;
     LASER_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, 0));
-    const bool whole = (long)B * d.n_heads * nqt >= 4L * ncu;
+    const bool whole = (long)B * d.n_heads * nqt >= (long)(m->attn_whole_min > 0 ? m->attn_whole_min : ncu / 2);
     const int split_pages = whole ? (1 << 20) : kSplitPages;
     const int nsplit = whole ? 1 : std::max(1, (npages_ub + kSplitPages - 1) / kSplitPages);
     const size_t part_need = (size_t)B * d.n_heads * nqt * nsplit * (32 + 16 * m->dh);
@@ -878,6 +880,11 @@ extern "C" int laser_model_set_option(laser_model* mh, const char* name, int val
     if (std::string(name) == "fused") { m->use_fused = value; return LASER_OK; }
     if (std::string(name) == "fused_trace") { m->fused_trace = value; return LASER_OK; }
     if (std::string(name) == "split_ffn") { m->split_ffn = value; return LASER_OK; }
+    if (std::string(name) == "attn_whole_min") {
+        LASER_REQUIRE(value >= 0, LASER_E_INVALID_ARG, "attn_whole_min must be >= 0");
+        m->attn_whole_min = value;
+        return LASER_OK;
+    }
     for (int i = 0; i < 3; ++i)
         if (std::string(name) == (i == 0 ? "ksplit_qkv" : i == 1 ? "ksplit_o" : "ksplit_down")) {
             LASER_REQUIRE(value == 0 || value == 1 || value == 2 || value == 4, LASER_E_INVALID_ARG, "%s must be 0 (choose), 1, 2 or 4", name);
