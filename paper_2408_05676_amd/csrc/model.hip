@@ -61,9 +61,12 @@ __global__ __launch_bounds__(256) void embed_rmsnorm_kernel(
 // n_part > 0: the projection before this norm left its result as n_part partial sums (part + p * part_stride, same
 // [row][d] layout): they are added to the residual row in order p = 0, 1, .. and the row is written back, in the
 // same pass that takes the row into registers and sums its squares (every thread touches only its own columns).
+// NPART is a template argument (0, 2, 4 or 8) so that the parts' loads are all issued before the first is added: with
+// a run-time trip count they were waited for one after the other, a memory round trip each.
+template <int NPART>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ gain,
                                                       int d, float eps, uint16_t* __restrict__ xn, uint16_t* __restrict__ xn_lo,
-                                                      const float* __restrict__ part, int n_part, size_t part_stride) {
+                                                      const float* __restrict__ part, size_t part_stride) {
     __shared__ float sm[4];
     const size_t m = blockIdx.x;
     // the row stays in registers between the two passes (up to 8192 columns; d is a multiple of 128)
@@ -73,11 +76,12 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, con
     const float4* xr = xw;
     auto take = [&](int i) {                     // column group i of the row, partial sums added and stored back
         float4 t = xr[i];
-        if (n_part > 0) {
-            for (int p = 0; p < n_part; ++p) {
-                const float4 q = reinterpret_cast<const float4*>(part + p * part_stride + m * d)[i];
-                t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
-            }
+        if constexpr (NPART > 0) {
+            float4 q[NPART];
+#pragma unroll
+            for (int p = 0; p < NPART; ++p) q[p] = reinterpret_cast<const float4*>(part + p * part_stride + m * d)[i];
+#pragma unroll
+            for (int p = 0; p < NPART; ++p) { t.x += q[p].x; t.y += q[p].y; t.z += q[p].z; t.w += q[p].w; }
             xw[i] = t;
         }
         return t;
@@ -115,6 +119,16 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, con
         if (i < n4) emit(i, v[c]);
     }
     for (int i = NV * 256 + threadIdx.x; i < n4; i += 256) emit(i, xr[i]);
+}
+
+static void launch_rmsnorm(int M, hipStream_t stream, float* x, const float* gain, int d, float eps, uint16_t* xn, uint16_t* xn_lo,
+                           const float* part, int n_part, size_t part_stride) {
+    switch (n_part) {
+        case 0: hipLaunchKernelGGL(rmsnorm_kernel<0>, dim3(M), dim3(256), 0, stream, x, gain, d, eps, xn, xn_lo, part, part_stride); break;
+        case 2: hipLaunchKernelGGL(rmsnorm_kernel<2>, dim3(M), dim3(256), 0, stream, x, gain, d, eps, xn, xn_lo, part, part_stride); break;
+        case 4: hipLaunchKernelGGL(rmsnorm_kernel<4>, dim3(M), dim3(256), 0, stream, x, gain, d, eps, xn, xn_lo, part, part_stride); break;
+        default: hipLaunchKernelGGL(rmsnorm_kernel<8>, dim3(M), dim3(256), 0, stream, x, gain, d, eps, xn, xn_lo, part, part_stride); break;
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -342,12 +356,15 @@ struct RopeArgs {
     size_t part_stride;
 };
 
-__device__ inline float4 ld4_sum(const float* p, int n_part, size_t stride) {
-    float4 t = *reinterpret_cast<const float4*>(p);
-    for (int s = 1; s < n_part; ++s) {
-        const float4 q = *reinterpret_cast<const float4*>(p + s * stride);
-        t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
-    }
+// NPART (1, 2, 4 or 8) is a template argument so that all parts are requested before the first is added.
+template <int NPART>
+__device__ inline float4 ld4_sum(const float* p, size_t stride) {
+    float4 q[NPART];
+#pragma unroll
+    for (int s = 0; s < NPART; ++s) q[s] = *reinterpret_cast<const float4*>(p + s * stride);
+    float4 t = q[0];
+#pragma unroll
+    for (int s = 1; s < NPART; ++s) { t.x += q[s].x; t.y += q[s].y; t.z += q[s].z; t.w += q[s].w; }
     return t;
 }
 
@@ -356,6 +373,7 @@ __device__ inline float4 ld4_sum(const float* p, int n_part, size_t stride) {
 // Instead a thread owns one (sequence, head, channel): it reads that channel's 32-byte page row, replaces the
 // slots of the sequence's R new tokens and writes the row back, so all loads and stores are whole 16-byte pieces
 // and a wave covers 2 KiB of contiguous page memory.
+template <int NPART>
 __device__ inline void write_values(const RopeArgs& a, int blk) {
     const int per_blk = 256 / a.dh;                         // (sequence, head) items per block
     const int item = blk * per_blk + (int)threadIdx.x / a.dh, c = (int)threadIdx.x % a.dh;
@@ -373,8 +391,12 @@ __device__ inline void write_values(const RopeArgs& a, int blk) {
         for (int tp = 0; tp < kPageSize; ++tp) {
             const int r = pg * kPageSize + tp - pos0;
             if (r >= 0 && r < a.R) {
-                float vs = v[(size_t)r * 3 * a.d];
-                for (int s = 1; s < a.n_part; ++s) vs += v[(size_t)r * 3 * a.d + s * a.part_stride];
+                float vp[NPART];
+#pragma unroll
+                for (int s = 0; s < NPART; ++s) vp[s] = v[(size_t)r * 3 * a.d + s * a.part_stride];
+                float vs = vp[0];
+#pragma unroll
+                for (int s = 1; s < NPART; ++s) vs += vp[s];
                 const uint16_t val = f32_to_f16(vs);
                 if (tp < 8) lo.h[tp & 7] = val; else hi.h[tp & 7] = val;
             }
@@ -384,8 +406,9 @@ __device__ inline void write_values(const RopeArgs& a, int blk) {
     }
 }
 
+template <int NPART>
 __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a) {
-    if ((int)blockIdx.x >= a.M * a.ny) { write_values(a, (int)blockIdx.x - a.M * a.ny); return; }
+    if ((int)blockIdx.x >= a.M * a.ny) { write_values<NPART>(a, (int)blockIdx.x - a.M * a.ny); return; }
     const int m = blockIdx.x / a.ny, by = blockIdx.x % a.ny, b = m / a.R;
     const int pos = a.row_pos[m];
     const int pg = a.block_table[(size_t)a.seq_ids[b] * a.mpps + pos / kPageSize], tp = pos % kPageSize;
@@ -398,8 +421,8 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a) {
         const int c0 = h * a.dh + i, c1 = c0 + half;
         const float4 csa = *reinterpret_cast<const float4*>(a.rope + (size_t)pos * half + i);       // (cos, sin) x 2
         const float4 csb = *reinterpret_cast<const float4*>(a.rope + (size_t)pos * half + i + 2);
-        const float4 qa = ld4_sum(row + c0, a.n_part, a.part_stride), qb = ld4_sum(row + c1, a.n_part, a.part_stride);
-        const float4 ka = ld4_sum(row + a.d + c0, a.n_part, a.part_stride), kb = ld4_sum(row + a.d + c1, a.n_part, a.part_stride);
+        const float4 qa = ld4_sum<NPART>(row + c0, a.part_stride), qb = ld4_sum<NPART>(row + c1, a.part_stride);
+        const float4 ka = ld4_sum<NPART>(row + a.d + c0, a.part_stride), kb = ld4_sum<NPART>(row + a.d + c1, a.part_stride);
         const float co[4] = {csa.x, csa.z, csb.x, csb.z}, si[4] = {csa.y, csa.w, csb.y, csb.w};
         const float q0[4] = {qa.x, qa.y, qa.z, qa.w}, q1[4] = {qb.x, qb.y, qb.z, qb.w};
         const float k0[4] = {ka.x, ka.y, ka.z, ka.w}, k1[4] = {kb.x, kb.y, kb.z, kb.w};
@@ -660,8 +683,7 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
     for (int l = 0; l < d.n_layers; ++l) {
         int rc;
         if (l > 0)
-            hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.g1 + (size_t)l * dm, dm, d.eps, m->xn, m->xn_lo,
-                               (const float*)m->kpart, pend, (size_t)M * dm);
+            launch_rmsnorm(M, stream, m->x, d.g1 + (size_t)l * dm, dm, d.eps, m->xn, m->xn_lo, (const float*)m->kpart, pend, (size_t)M * dm);
         pend = 0;
         const bool many = M > kSkinnyMaxRows;      // tiled path: weights from the fp16 copy
         GemmArgs g{d.wqkv + (size_t)l * 3 * dm * dm, many ? m->w16[0] + (size_t)l * 3 * dm * dm : nullptr, m->xn, m->xn_lo, M, 3 * dm, dm, 1, m->qkv, nullptr};
@@ -671,7 +693,13 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
                     R, dm, d.n_heads, m->dh, kv->d.max_pages_per_seq, l, kv->d.n_pages,
                     M, std::max(1, std::min(4, dm / 2048)), B, std::max(1, g.n_part), (size_t)M * 3 * dm};
         const int v_blocks = (B * d.n_heads + 256 / m->dh - 1) / (256 / m->dh);
-        hipLaunchKernelGGL(rope_kv_kernel, dim3((unsigned)(M * ra.ny + v_blocks)), dim3(256), 0, stream, ra);
+        const dim3 rg((unsigned)(M * ra.ny + v_blocks));
+        switch (ra.n_part) {
+            case 1: hipLaunchKernelGGL(rope_kv_kernel<1>, rg, dim3(256), 0, stream, ra); break;
+            case 2: hipLaunchKernelGGL(rope_kv_kernel<2>, rg, dim3(256), 0, stream, ra); break;
+            case 4: hipLaunchKernelGGL(rope_kv_kernel<4>, rg, dim3(256), 0, stream, ra); break;
+            default: hipLaunchKernelGGL(rope_kv_kernel<8>, rg, dim3(256), 0, stream, ra); break;
+        }
         AttnArgs aa{m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages, ids_dev, kv->len, kv->block_table, m->attn, m->attn_lo, m->att_part,
                     R, dm, d.n_heads, kv->d.max_pages_per_seq, l, kv->d.n_pages, nsplit, nqt, split_pages, 1.0f / sqrtf((float)m->dh)};
         dim3 ag(d.n_heads, B, nsplit * nqt);
@@ -685,8 +713,7 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
         GemmArgs go{d.wo + (size_t)l * dm * dm, many ? m->w16[1] + (size_t)l * dm * dm : nullptr, m->attn, m->attn_lo, M, dm, dm, 1, m->x, nullptr};
         go.part = m->kpart; go.part_floats = m->kpart_floats; go.want_split = m->ksplit_opt[1];
         if ((rc = launch_gemm<EPI_RESID>(go, stream))) return rc;
-        hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.g2 + (size_t)l * dm, dm, d.eps, m->xn, m->xn_lo,
-                           (const float*)m->kpart, go.n_part, (size_t)M * dm);
+        launch_rmsnorm(M, stream, m->x, d.g2 + (size_t)l * dm, dm, d.eps, m->xn, m->xn_lo, (const float*)m->kpart, go.n_part, (size_t)M * dm);
         // On the tiled many-row path a split operand doubles the matrix work; gate/up (45 % of the layer's
         // flops) takes the single fp16 rows there unless option "split_ffn" asks for the split (see set_option).
         const bool split_gu = M <= kSkinnyMaxRows || m->split_ffn;
@@ -700,8 +727,7 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
         if ((rc = launch_gemm<EPI_RESID>(gd, stream))) return rc;
         pend = gd.n_part;        // added to the residual by the next norm (next layer's, or the final one)
     }
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, stream, m->x, d.gf, dm, d.eps, m->xn, (uint16_t*)nullptr,
-                       (const float*)m->kpart, pend, (size_t)M * dm);
+    launch_rmsnorm(M, stream, m->x, d.gf, dm, d.eps, m->xn, nullptr, (const float*)m->kpart, pend, (size_t)M * dm);
     LASER_HIP_CHECK(hipGetLastError());
     return LASER_OK;
 }
