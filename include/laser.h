@@ -153,8 +153,10 @@ typedef struct laser_model_desc {
 
 /* Supported: head_dim 64 or 128; d_model, ffn multiples of 128; vocab multiple of 16 (else
  * LASER_E_SHAPE). Allocates workspace and the RoPE table; synchronises `stream`. n_layers may be 0
- * (head-only use). The first verify step with more than 80 rows additionally allocates an fp16 copy
- * of the four projection matrices (2 bytes per parameter) for the tiled many-row kernels. */
+ * (head-only use). Two further allocations happen lazily, inside the first verify step that needs them:
+ * with more than 16 rows a workspace for reduction-split partial results (max_rows * d_model * 32 bytes),
+ * with more than 80 rows an fp16 copy of the four projection matrices (2 bytes per parameter) for the tiled
+ * many-row kernels. */
 int laser_model_create(const laser_model_desc* desc, void* stream, laser_model** out);
 int laser_model_destroy(laser_model* model);
 
@@ -193,7 +195,7 @@ int laser_kv_read_lens(laser_kv* kv, const int32_t* seq_ids /*[host] B*/, int B,
 /* laser_verify_step (Eq. 3 / Eq. 6 forward, Eq. 4 / 7 / 8 acceptance, correction rule of Sec. 2.1).
  * For sequence b, rows r = 0..K hold the tokens [pending[b], drafts[b][0..K-1]] at positions
  * len+r; their keys/values go to cache slots len..len+K; row r attends to slots 0..len+r. The
- * output head and the acceptance rule are fused: with up to 80 rows (B*(K+1)) logits are never
+ * output head and the acceptance rule are fused: with up to 16 rows (B*(K+1)) logits are never
  * stored unless logits_dbg is given; with more rows they pass once through an fp32 workspace of
  * max_rows * vocab floats that the model handle allocates at the first such call (that call
  * synchronises; LASER_E_HIP if the allocation fails). With B*(K+1) <= 16 the whole step is one
