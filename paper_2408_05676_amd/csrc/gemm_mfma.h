@@ -66,10 +66,6 @@ __device__ inline int w_row(const GemmTileArgs& a, int tn, int j) {
     return tn * BN + j;
 }
 
-template <int J, int N, class F>
-__device__ inline void static_for(F&& f) {
-    if constexpr (J < N) { f(std::integral_constant<int, J>{}); static_for<J + 1, N>(f); }
-}
 
 // BN = 128: 2 x 2 waves of 64 x 64. BN = 64 (narrow outputs, where 128-column tiles would leave CUs
 // without work): 2 x 2 waves of 64 x 32. The SwiGLU epilogue needs BN = 128.

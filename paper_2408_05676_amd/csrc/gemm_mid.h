@@ -41,6 +41,7 @@ struct GemmMidArgs {
 // workgroups to spread over the chip; gemm_mid_plan picks per launch shape.
 template <int MB, int EPI, bool SPLIT, int NW>
 __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void gemm_mid_kernel(GemmMidArgs a) {
+    constexpr bool DEEP = NW == 8;
     constexpr int ROWS = MB * 16, NP = SPLIT ? 2 : 1;
     constexpr int NT = NW * 64;                              // threads
     constexpr int NPIECE = (ROWS * 16 + NT - 1) / NT;        // 16-byte pieces of a plane's chunk per thread
@@ -74,38 +75,52 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void gemm_mid_kernel(Gemm
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) { acc[mb] = float4_t{0.f, 0.f, 0.f, 0.f}; acl[mb] = float4_t{0.f, 0.f, 0.f, 0.f}; }
 
-    Frag8 w0[4], w1[4];
-    u32x4 xr[NP][NPIECE];
-    auto load_w = [&](int st, Frag8 (&w)[4]) {              // clamped: always in bounds, surplus loads are dropped
-        const int k0 = min(st, ksteps - 1) * kGemmKStep;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) w[c].v4 = *reinterpret_cast<const u32x4*>(wp + k0 + c * 8);
-    };
-    auto load_x = [&](int st) {
-        const int k0 = min(st, ksteps - 1) * kGemmKStep;
-        const uint16_t* const xb = a.X + k0;
-        const uint16_t* const xlb = SPLIT ? a.Xlo + k0 : nullptr;
-#pragma unroll
-        for (int i = 0; i < NPIECE; ++i) {
-            xr[0][i] = *reinterpret_cast<const u32x4*>(xb + xoff[i]);
-            if constexpr (SPLIT) xr[NP - 1][i] = *reinterpret_cast<const u32x4*>(xlb + xoff[i]);
+    // Register rings. DEEP = false: the activation pieces and the weight fragments of step s + 1 are requested during
+    // step s, all at once (pieces right after the first barrier, fragments at the top). DEEP = true (the 8-wave form,
+    // whose staging pieces per thread are few): pieces two steps ahead, fragments three, and the requests are spread
+    // over the step's row tiles between the matrix instructions -- issued in one burst, the 80 vector loads of a
+    // workgroup-step occupy the compute unit's one address unit for about as long as the matrix work takes, and every
+    // wave sits behind its own burst before it reaches its LDS reads. Ring slots are indexed by the step's number
+    // within the unrolled body, so they stay named registers (a register copy of a fragment in flight would wait for
+    // it); the main loop has no branch between steps (at a join the compiler's wait counters fall back to
+    // "everything", which would undo the prefetch), the last few steps run one by one.
+    constexpr int XD = DEEP ? 2 : 1, WD = DEEP ? 3 : 1;
+    constexpr int XR = XD, WR = WD + 1, UNROLL = DEEP ? 4 : 2;   // a common multiple of XR and WR
+    constexpr int NLOAD = 4 + NP * NPIECE;                        // vector loads per thread and step
+    Frag8 w[WR][4];
+    u32x4 xr[XR][NP][NPIECE];
+    // load l of a step: 0..3 = weight fragment l, then the activation pieces plane by plane. GUARD: requests for
+    // steps past the part's end are skipped (a uniform branch; the main loop never asks for such a step and is
+    // instantiated without it).
+    auto load_one = [&](auto guard_c, int st_w, int st_x, auto l_c, auto ws_c, auto xs_c) {
+        constexpr bool GUARD = decltype(guard_c)::value;
+        constexpr int l = decltype(l_c)::value, WS = decltype(ws_c)::value, XS = decltype(xs_c)::value;
+        if constexpr (l < 4) {
+            if (!GUARD || st_w < send) w[WS][l].v4 = *reinterpret_cast<const u32x4*>(wp + st_w * kGemmKStep + l * 8);
+        } else {
+            constexpr int pl = (l - 4) / NPIECE, i = (l - 4) % NPIECE;
+            if (!GUARD || st_x < send) xr[XS][pl][i] = *reinterpret_cast<const u32x4*>((pl == 0 ? a.X : a.Xlo) + st_x * kGemmKStep + xoff[i]);
         }
     };
-    // one step: multiply the fragments in `cur` while `fill` (free since the step before) takes the next step's
-    auto step = [&](int st, Frag8 (&cur)[4], Frag8 (&fill)[4]) {
-        load_w(st + 1, fill);
+    // one step, J = its number within the unrolled body: ring slots J % XR (chunk) and J % WR (fragments)
+    auto step = [&](auto guard_c, int st, auto j_c) {
+        constexpr int J = decltype(j_c)::value, XS = J % XR, WS = J % WR, WF = (J + WD) % WR;
+        using WFc = std::integral_constant<int, WF>;
+        using XSc = std::integral_constant<int, XS>;
+        if constexpr (!DEEP) static_for<0, 4>([&](auto l) { load_one(guard_c, st + WD, send, l, WFc{}, XSc{}); });
 #pragma unroll
         for (int i = 0; i < NPIECE; ++i) {
-            *reinterpret_cast<u32x4*>(sx + xdst[i]) = xr[0][i];
-            if constexpr (SPLIT) *reinterpret_cast<u32x4*>(sx + ROWS * LDH + xdst[i]) = xr[NP - 1][i];
+            *reinterpret_cast<u32x4*>(sx + xdst[i]) = xr[XS][0][i];
+            if constexpr (SPLIT) *reinterpret_cast<u32x4*>(sx + ROWS * LDH + xdst[i]) = xr[XS][NP - 1][i];
         }
         __syncthreads();
-        load_x(st + 1);
+        if constexpr (!DEEP) static_for<4, NLOAD>([&](auto l) { load_one(guard_c, send, st + XD, l, WFc{}, XSc{}); });
+        Frag8 (&cur)[4] = w[WS];
 #pragma unroll
         for (int c = 0; c < 4; ++c) bf16x8_to_f16x8(cur[c]);
         // The row tiles' fragments are read from LDS one tile ahead of the matrix instructions that use them (two
         // fragment sets; the scheduling fences keep the compiler from sinking the reads back to their uses: with
-        // about one wave per SIMD nothing else would cover the LDS latency of 8 reads per tile).
+        // one or two waves per SIMD nothing else would cover the LDS latency of 8 reads per tile).
         Frag8 b[2][NP * 4];
         auto read_b = [&](int mb, Frag8 (&f)[NP * 4]) {
             const uint16_t* row = sx + (mb * 16 + r) * LDH + g * 32;
@@ -117,9 +132,11 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void gemm_mid_kernel(Gemm
             }
         };
         read_b(0, b[0]);
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            if (mb + 1 < MB) read_b(mb + 1, b[(mb + 1) & 1]);
+        static_for<0, MB>([&](auto mb_c) {
+            constexpr int mb = decltype(mb_c)::value;
+            if constexpr (mb + 1 < MB) read_b(mb + 1, b[(mb + 1) & 1]);
+            if constexpr (DEEP)          // this row tile's share of the step's requests: loads [mb, mb + 1) * NLOAD / MB
+                static_for<mb * NLOAD / MB, (mb + 1) * NLOAD / MB>([&](auto l) { load_one(guard_c, st + WD, st + XD, l, WFc{}, XSc{}); });
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int c = 0; c < 4; ++c) acc[mb] = mfma_16x16x32(cur[c], b[mb & 1][c], acc[mb]);
@@ -128,16 +145,36 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void gemm_mid_kernel(Gemm
                 for (int c = 0; c < 4; ++c) acl[mb] = mfma_16x16x32(cur[c], b[mb & 1][NP * 4 - 4 + c], acl[mb]);
             }
             __builtin_amdgcn_sched_barrier(0);
-        }
+        });
         __syncthreads();                                     // the chunk is free for the next step's pieces
     };
-    load_x(sbeg);
-    load_w(sbeg, w0);
-    for (int st = sbeg; st < send; st += 2) {                // sbeg, send are the same for every wave of the workgroup
-        step(st, w0, w1);
-        if (st + 1 >= send) break;
-        step(st + 1, w1, w0);
+    // prologue: the first XD chunks and WD fragment sets
+    // (in the order of first use, pinned by scheduling fences: loads complete in issue order, and the loop header's
+    // wait for the first chunk must not find a later request ahead of it)
+    auto prologue = [&](auto guard_c) {
+        static_for<0, XD>([&](auto d) {
+            static_for<4, NLOAD>([&](auto l) { load_one(guard_c, send, sbeg + decltype(d)::value, l, std::integral_constant<int, 0>{}, d); });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        static_for<0, WD>([&](auto d) {
+            static_for<0, 4>([&](auto l) { load_one(guard_c, sbeg + decltype(d)::value, send, l, d, std::integral_constant<int, 0>{}); });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    // main loop: groups of UNROLL steps all of whose requests lie inside the part, entered through a prologue without
+    // guards (so that the loop header sees known wait-counter states on both of its edges); then up to
+    // UNROLL + WD - 1 steps one by one (the ring positions carry on: every group starts at position 0)
+    int st = sbeg;                                           // sbeg, send are the same for every wave of the workgroup
+    if (st + UNROLL + WD <= send) {
+        prologue(std::false_type{});
+        for (; st + UNROLL + WD <= send; st += UNROLL)
+            static_for<0, UNROLL>([&](auto j) { step(std::false_type{}, st + decltype(j)::value, j); });
+    } else {
+        prologue(std::true_type{});
     }
+    static_for<0, UNROLL + WD - 1>([&](auto j) {
+        if (st + decltype(j)::value < send) step(std::true_type{}, st + decltype(j)::value, j);
+    });
     float v[MB][4];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
@@ -195,9 +232,10 @@ struct GemmMidPlan { int NW, S; };
 
 // Waves per workgroup and reduction parts for one launch: the pair with the fewest kilobytes entering the busiest
 // compute unit (weights + activation chunks over its workgroups' steps, two steps' worth of start-up per
-// workgroup, plus its share of writing and re-reading the partial results). Parts only for store / accumulate
+// workgroup -- five for the 8-wave form, whose deeper rings take longer to fill and drain --, plus its share of
+// writing and re-reading the partial results). Parts only for store / accumulate
 // epilogues with a workspace, each part at least two steps. A function of the launch shape only.
-inline GemmMidPlan gemm_mid_plan(int M, int N, int Kd, int planes, bool swiglu, size_t part_floats) {
+inline GemmMidPlan gemm_mid_plan(int M, int N, int Kd, int planes, bool swiglu, size_t part_floats, int force_nw = 0) {
     const int n_cu = gemm_mid_cu_count();
     const long vtiles = (long)(N / 16) * (swiglu ? 2 : 1), ksteps = Kd / kGemmKStep;
     const long xkb = (long)((M + 15) / 16) * 4 * planes;
@@ -205,10 +243,11 @@ inline GemmMidPlan gemm_mid_plan(int M, int N, int Kd, int planes, bool swiglu, 
     double best_cost = 1e300;
     for (int nw = 4; nw <= 8; nw *= 2)
         for (int S = 1; S <= 8; S *= 2) {
+            if (force_nw && nw != force_nw) break;
             if (S > 1 && (swiglu || ksteps / S < 2 || (size_t)S * M * N > part_floats)) break;
             const long n_wg = (vtiles + nw - 1) / nw * S;
             const long per_cu = (n_wg + n_cu - 1) / n_cu, steps = (ksteps + S - 1) / S;
-            const double cost = (double)per_cu * (steps + 2) * (nw * 4 + xkb) +
+            const double cost = (double)per_cu * (steps + (nw == 8 ? 5 : 2)) * (nw * 4 + xkb) +
                                 (S > 1 ? 2.0 * S * M * N * 4 / 1024 / n_cu : 0.0);
             if (cost < best_cost) { best_cost = cost; best = {nw, S}; }
         }

@@ -31,7 +31,16 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace laser {
+
+// f(integral_constant<int, J>) for J = J0 .. N-1, unrolled at compile time: ring slots and fragment sets indexed
+// by J stay in named registers.
+template <int J, int N, class F>
+__device__ inline void static_for(F&& f) {
+    if constexpr (J < N) { f(std::integral_constant<int, J>{}); static_for<J + 1, N>(f); }
+}
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));

@@ -145,6 +145,7 @@ struct GemmArgs {
     size_t part_floats = 0;
     int want_split = 0;     // 0: choose; 1, 2, 4: force this many reduction parts
     int n_part = 0;         // out: parts left in `part` for the consumer to add up (0: the result is complete)
+    int mid_waves = 0;      // 17..80 rows: 0 = choose the waves per workgroup, 4 or 8 = force
 };
 
 template <int MB, int EPI, bool SPLIT>
@@ -310,7 +311,7 @@ static int launch_gemm(GemmArgs& a_in, hipStream_t stream) {
     if (mblocks >= 2 && (a.Xlo || EPI == EPI_RESID) && a.Kd % kGemmKStep == 0) {
         // 17..80 rows: activations staged in LDS and shared by the workgroup's four weight tiles
         GemmMidArgs t{a.W, a.X, a.Xlo, a.M, a.N, a.Kd, a.outf, a.outh, a.part};
-        const GemmMidPlan pl = gemm_mid_plan(a.M, a.N, a.Kd, a.Xlo ? 2 : 1, EPI == EPI_SWIGLU, a.part ? a.part_floats : 0);
+        const GemmMidPlan pl = gemm_mid_plan(a.M, a.N, a.Kd, a.Xlo ? 2 : 1, EPI == EPI_SWIGLU, a.part ? a.part_floats : 0, a.mid_waves);
         if (a.Xlo) launch_gemm_mid<EPI, true>(t, pl, stream);
         else if constexpr (EPI == EPI_RESID) launch_gemm_mid<EPI, false>(t, pl, stream);
         LASER_HIP_CHECK(hipGetLastError());
@@ -687,7 +688,7 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
         pend = 0;
         const bool many = M > kSkinnyMaxRows;      // tiled path: weights from the fp16 copy
         GemmArgs g{d.wqkv + (size_t)l * 3 * dm * dm, many ? m->w16[0] + (size_t)l * 3 * dm * dm : nullptr, m->xn, m->xn_lo, M, 3 * dm, dm, 1, m->qkv, nullptr};
-        g.part = m->kpart; g.part_floats = m->kpart_floats; g.want_split = m->ksplit_opt[0];
+        g.part = m->kpart; g.part_floats = m->kpart_floats; g.want_split = m->ksplit_opt[0]; g.mid_waves = m->mid_waves;
         if ((rc = launch_gemm<EPI_F32>(g, stream))) return rc;
         RopeArgs ra{g.n_part ? m->kpart : m->qkv, m->row_pos, ids_dev, kv->block_table, m->rope, m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages,
                     R, dm, d.n_heads, m->dh, kv->d.max_pages_per_seq, l, kv->d.n_pages,
@@ -711,19 +712,20 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
             else hipLaunchKernelGGL(attn_combine_kernel<64>, cg, dim3(256), 0, stream, aa);
         }
         GemmArgs go{d.wo + (size_t)l * dm * dm, many ? m->w16[1] + (size_t)l * dm * dm : nullptr, m->attn, m->attn_lo, M, dm, dm, 1, m->x, nullptr};
-        go.part = m->kpart; go.part_floats = m->kpart_floats; go.want_split = m->ksplit_opt[1];
+        go.part = m->kpart; go.part_floats = m->kpart_floats; go.want_split = m->ksplit_opt[1]; go.mid_waves = m->mid_waves;
         if ((rc = launch_gemm<EPI_RESID>(go, stream))) return rc;
         launch_rmsnorm(M, stream, m->x, d.g2 + (size_t)l * dm, dm, d.eps, m->xn, m->xn_lo, (const float*)m->kpart, go.n_part, (size_t)M * dm);
         // On the tiled many-row path a split operand doubles the matrix work; gate/up (45 % of the layer's
         // flops) takes the single fp16 rows there unless option "split_ffn" asks for the split (see set_option).
         const bool split_gu = M <= kSkinnyMaxRows || m->split_ffn;
         GemmArgs gg{d.wgu + (size_t)l * 2 * F * dm, many ? m->w16[2] + (size_t)l * 2 * F * dm : nullptr, m->xn, split_gu ? m->xn_lo : nullptr, M, F, dm, 1, nullptr, m->act};
+        gg.mid_waves = m->mid_waves;
         const bool prof = m->prof_on && m->prof_n < m->prof_cap;
         if (prof) LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n], stream));
         if ((rc = launch_gemm<EPI_SWIGLU>(gg, stream))) return rc;
         if (prof) { LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n + 1], stream)); ++m->prof_n; }
         GemmArgs gd{d.wdown + (size_t)l * dm * F, many ? m->w16[3] + (size_t)l * dm * F : nullptr, m->act, nullptr, M, dm, F, 1, m->x, nullptr};
-        gd.part = m->kpart; gd.part_floats = m->kpart_floats; gd.want_split = m->ksplit_opt[2];
+        gd.part = m->kpart; gd.part_floats = m->kpart_floats; gd.want_split = m->ksplit_opt[2]; gd.mid_waves = m->mid_waves;
         if ((rc = launch_gemm<EPI_RESID>(gd, stream))) return rc;
         pend = gd.n_part;        // added to the residual by the next norm (next layer's, or the final one)
     }
@@ -906,6 +908,11 @@ extern "C" int laser_model_set_option(laser_model* mh, const char* name, int val
     if (std::string(name) == "fused") { m->use_fused = value; return LASER_OK; }
     if (std::string(name) == "fused_trace") { m->fused_trace = value; return LASER_OK; }
     if (std::string(name) == "split_ffn") { m->split_ffn = value; return LASER_OK; }
+    if (std::string(name) == "mid_waves") {
+        LASER_REQUIRE(value == 0 || value == 4 || value == 8, LASER_E_INVALID_ARG, "mid_waves must be 0 (choose), 4 or 8");
+        m->mid_waves = value;
+        return LASER_OK;
+    }
     if (std::string(name) == "attn_whole_min") {
         LASER_REQUIRE(value >= 0, LASER_E_INVALID_ARG, "attn_whole_min must be >= 0");
         m->attn_whole_min = value;
