@@ -247,6 +247,8 @@ int laser_ctx_advance(int32_t* ctx_tail, int32_t* pending, const int32_t* out_to
  * shape or the workspace cannot take falls back to 1). The parts are added in a fixed order by the
  * kernel that follows, so a given setting is deterministic; different settings may differ in the
  * last bits. Tuning and test knobs: the default is what the benchmark measures.
+ * "mid_waves" = 0 (default: chosen per launch shape), 4 or 8: waves per workgroup of the weight-streaming
+ * GEMM used with 17..80 rows.
  * "attn_whole_min" = 0 (default: half the number of compute units) or a count: from this many (sequence, head,
  * 16-row query tile) triples on, the general path's attention walks a context in one workgroup instead of
  * splitting it into 256-token parts that a second kernel merges.
