@@ -6,6 +6,8 @@ verify steps (Eq. 3 / Eq. 6 forward, Eq. 8 acceptance with k = 2, p = 0):
   c3    the latency configuration itself: one sequence, context 1024, K = 8
   many  12 sequences, context 24, K = 8 (108 rows: the many-row launch shape); the oracle follows
         sequences 0 and 7
+  mid   6 sequences, context 24, K = 8 (54 rows: the 17..80-row launch shape); the oracle follows
+        sequences 1 and 4
 
 It calls only oracle/ and synth/ (never the HIP library). The oracle needs the 7B weights on the host
 (26 GB as float32) and a quarter of an hour on 8 cores, more than a GPU test may take, so the GPU tests
@@ -13,7 +15,8 @@ compare against this file instead. Stored per followed sequence: the prompt, the
 logit column plus the 64 largest logits of every row (float32), the accepted length, the emitted tokens
 and the oracle's deciding margins.
 
-    python tests/golden/make_full_depth.py
+    python tests/golden/make_full_depth.py            # all cases
+    python tests/golden/make_full_depth.py mid        # only the named cases; the others are kept from the file
 """
 from __future__ import annotations
 
@@ -36,6 +39,7 @@ CASES = {
     #        B   ctx   K  followed  seed  right drafts
     "c3": (1, 1024, 8, [0], 41, 5),
     "many": (12, 24, 8, [0, 7], 13, 3),
+    "mid": (6, 24, 8, [1, 4], 17, 3),
 }
 
 
@@ -45,7 +49,14 @@ def main():
     dec = Decoder(sh.n_layers, sh.d, sh.n_heads, sh.ffn, sh.vocab, synth.gen_all_weights(sh), sh.eps, sh.rope_base)
     print(f"weights ready {time.time() - t0:.0f} s", flush=True)
     out = {}
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "full_depth_7b.npz")
+    only = sys.argv[1:]
+    if only:                                       # keep what the file (written by this script) holds for the other cases
+        with np.load(path) as old:
+            out.update({k: old[k] for k in old.files if k != "params" and k.split("_")[0] not in only})
     for name, (B, ctx, K, follow, seed, n_right) in CASES.items():
+        if only and name not in only:
+            continue
         prompts = synth.uniform_tokens(seed, 50, 0, B * ctx, sh.vocab).reshape(B, ctx)
         drafts = synth.uniform_tokens(seed, 51, 0, B * K, sh.vocab).reshape(B, K).copy()
         dl = np.full(B, K, dtype=np.int32)
@@ -82,7 +93,6 @@ def main():
         print(f"{name}: accepted {res['accept_len'].tolist()}, emitted {res['out_tokens'].tolist()}, "
               f"logit std {lg.std():.3f}, {time.time() - t0:.0f} s", flush=True)
     out["params"] = np.array([K_TOP, P_THR, MODE], dtype=np.float64)
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "full_depth_7b.npz")
     np.savez(path, **out)
     print(f"wrote {path} ({os.path.getsize(path) / 1e6:.2f} MB) in {time.time() - t0:.0f} s")
 

@@ -5,8 +5,9 @@ The oracle cannot run a 32-layer 7B forward inside a GPU test (26 GB of host wei
 so its results were written once by tests/golden/make_full_depth.py, which calls only oracle/ and synth/,
 into tests/golden/full_depth_7b.npz: every fourth logit column and the 64 largest logits of every row, the
 accepted length, the emitted tokens and the deciding margins. Two cases: the latency configuration itself
-(one sequence, context 1024, K = 8; both the persistent kernel and the general path) and a 108-row batch on
-the tiled many-row path (the oracle follows two of its twelve sequences)."""
+(one sequence, context 1024, K = 8; both the persistent kernel and the general path), a 108-row batch on
+the tiled many-row path (the oracle follows two of its twelve sequences) and a 54-row batch on the 17..80-row
+path (two of six sequences)."""
 import os
 
 import numpy as np
@@ -93,3 +94,9 @@ def test_many_row_path_full_depth(weights_7b, split_ffn):
     """108 rows: tiled matrix-core GEMMs. By default the gate/up product takes single fp16 rows there
     (option split_ffn = 0); both settings must stay inside the tolerance."""
     _check("many", weights_7b, 0, options=(("split_ffn", split_ffn),))
+
+
+def test_mid_row_path_full_depth(weights_7b):
+    """54 rows: the weight-streaming kernels that stage the activation chunk in LDS (four row tiles, reduction
+    parts added by the rotary kernel and the norms), the head through the same kernel plus row statistics."""
+    _check("mid", weights_7b, 0)
