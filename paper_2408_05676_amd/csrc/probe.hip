@@ -55,6 +55,19 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* sink)
     if (s == 12345.678f) sink[0] = s;
 }
 
+// A pair of timing events that is destroyed on every way out of a probe.
+struct EventPair {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t create() {
+        hipError_t e = hipEventCreate(&e0);
+        return e != hipSuccess ? e : hipEventCreate(&e1);
+    }
+    ~EventPair() {
+        if (e0) (void)hipEventDestroy(e0);
+        if (e1) (void)hipEventDestroy(e1);
+    }
+};
+
 }  // namespace laser
 
 using namespace laser;
@@ -66,9 +79,9 @@ extern "C" int laser_probe_hbm(void* buf, size_t bytes, int reps, void* stream_v
     hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
     int ncu = 0;
     LASER_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, 0));
-    hipEvent_t e0, e1;
-    LASER_HIP_CHECK(hipEventCreate(&e0));
-    LASER_HIP_CHECK(hipEventCreate(&e1));
+    EventPair ev;
+    LASER_HIP_CHECK(ev.create());
+    hipEvent_t e0 = ev.e0, e1 = ev.e1;
     const unsigned grid = (unsigned)ncu * 16u;
     u32x4_p* lo = reinterpret_cast<u32x4_p*>(buf);
     u32x4_p* hi = lo + bytes / 32;
@@ -93,8 +106,6 @@ extern "C" int laser_probe_hbm(void* buf, size_t bytes, int reps, void* stream_v
     LASER_HIP_CHECK(hipEventElapsedTime(&ms, e0, e1));
     *copy_gbs = (float)((double)bytes * reps / (ms * 1e-3) / 1e9);
     LASER_HIP_CHECK(hipGetLastError());
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
     return LASER_OK;
 }
 
@@ -104,9 +115,9 @@ extern "C" int laser_probe_mfma_f16(void* scratch, int reps, void* stream_v, flo
     hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
     int ncu = 0;
     LASER_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, 0));
-    hipEvent_t e0, e1;
-    LASER_HIP_CHECK(hipEventCreate(&e0));
-    LASER_HIP_CHECK(hipEventCreate(&e1));
+    EventPair ev;
+    LASER_HIP_CHECK(ev.create());
+    hipEvent_t e0 = ev.e0, e1 = ev.e1;
     const int iters = 4096;
     const unsigned grid = (unsigned)ncu * 4u;               // 16 waves per compute unit, 4 per SIMD
     float* sink = reinterpret_cast<float*>(scratch);       // never written: the sum cannot match
@@ -120,7 +131,5 @@ extern "C" int laser_probe_mfma_f16(void* scratch, int reps, void* stream_v, flo
     const double flops = (double)grid * 4.0 * 4.0 * iters * 32768.0 * reps;   // workgroups x waves x chains x iters x flops
     *tflops = (float)(flops / (ms * 1e-3) / 1e12);
     LASER_HIP_CHECK(hipGetLastError());
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
     return LASER_OK;
 }
