@@ -340,7 +340,8 @@ def main():
                     help="with the default (batch 1) workload, skip the batch-64 workload that is otherwise measured as well")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (the path needs no collectives; see DESIGN.md on sharding). "
+        print("bench.py: this build runs on ONE GPU (sequences are independent, so more GPUs would each run this same "
+              "path on their share of the batch, without collectives). "
               "--gpus N with N > 1 is not supported.", file=sys.stderr)
         sys.exit(2)
 
