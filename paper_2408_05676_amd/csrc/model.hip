@@ -464,8 +464,10 @@ struct AttnArgs {
 
 constexpr int kSplitPages = 16;   // pages (of 16 tokens) per context split
 
-template <int DH>
-__global__ __launch_bounds__(256, 4) void attn_kernel(AttnArgs a) {
+// NWV = waves per workgroup that share a context's pages (4, or 8 for unsplit launches of few workgroups: half
+// the pages per wave; waves 4..7 hand their partial results to waves 0..3 before the four-way merge).
+template <int DH, int NWV>
+__global__ __launch_bounds__(NWV * 64, NWV == 4 ? 4 : 2) void attn_kernel(AttnArgs a) {
     constexpr int NC32 = DH / 32, NC16 = DH / 16;
     __shared__ float sm_m[4][16], sm_l[4][16];
     __shared__ float sm_o[4][16][DH];
@@ -499,7 +501,7 @@ __global__ __launch_bounds__(256, 4) void attn_kernel(AttnArgs a) {
     for (int c = 0; c < NC16; ++c) acc[c] = float4_t{0.f, 0.f, 0.f, 0.f};
     const int32_t* bt = a.block_table + (size_t)slot * a.mpps;
 
-    // Pages p0 + wave, + 4, ..: the K and V fragments of the next page are requested before the current
+    // Pages p0 + wave, + NWV, ..: the K and V fragments of the next page are requested before the current
     // one is multiplied (unconditionally: past the wave's last page the current page is requested again,
     // a cache hit), so a wave always has one page in flight.
     auto load_page = [&](int p, Frag8 (&ak)[NC32], u32x2 (&akl)[NC32], Frag4 (&bv)[NC16]) {
@@ -520,8 +522,8 @@ __global__ __launch_bounds__(256, 4) void attn_kernel(AttnArgs a) {
     Frag4 bv[NC16], bvn[NC16];
     int p = p0 + wave;
     if (p < p1) load_page(p, ak, akl, bv);
-    for (; p < p1; p += 4) {
-        load_page(p + 4 < p1 ? p + 4 : p, akn, akln, bvn);
+    for (; p < p1; p += NWV) {
+        load_page(p + NWV < p1 ? p + NWV : p, akn, akln, bvn);
         // s[i] = K[tok 4g+i] . Q[row r] with both operands split: hi.hi + 2^-12 (hi.lo + lo.hi)
         float4_t s = float4_t{0.f, 0.f, 0.f, 0.f}, sl = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -574,15 +576,43 @@ __global__ __launch_bounds__(256, 4) void attn_kernel(AttnArgs a) {
 #pragma unroll
         for (int c = 0; c < NC16; ++c) bv[c] = bvn[c];
     }
-    // ---- merge the four waves ----
-    if (g == 0) { sm_m[wave][r] = m_run; sm_l[wave][r] = l_run; }
+    if constexpr (NWV == 8) {
+        // ---- waves 4..7 hand over to waves 0..3 (same lane layout on both sides) ----
+        if (wave >= 4) {
+            if (g == 0) { sm_m[wave - 4][r] = m_run; sm_l[wave - 4][r] = l_run; }
 #pragma unroll
-    for (int c = 0; c < NC16; ++c)
+            for (int c = 0; c < NC16; ++c)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sm_o[wave][4 * g + i][c * 16 + r] = acc[c][i];
+                for (int i = 0; i < 4; ++i) sm_o[wave - 4][4 * g + i][c * 16 + r] = acc[c][i];
+        }
+        __syncthreads();
+        if (wave < 4) {
+            const float pm = sm_m[wave][r], pl = sm_l[wave][r];
+            const float m_new = fmaxf(m_run, pm);
+            const float f = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
+            const float fp = (pm == -INFINITY) ? 0.f : __expf(pm - m_new);
+            l_run = l_run * f + pl * fp;
+            m_run = m_new;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float fi = __shfl(f, 4 * g + i), fpi = __shfl(fp, 4 * g + i);     // accumulator rows are q = 4g+i
+#pragma unroll
+                for (int c = 0; c < NC16; ++c) acc[c][i] = acc[c][i] * fi + sm_o[wave][4 * g + i][c * 16 + r] * fpi;
+            }
+        }
+        __syncthreads();               // waves 0..3 have read what they now overwrite
+    }
+    // ---- merge the four waves (all threads of the workgroup share the final pass) ----
+    if (NWV == 4 || wave < 4) {
+        if (g == 0) { sm_m[wave][r] = m_run; sm_l[wave][r] = l_run; }
+#pragma unroll
+        for (int c = 0; c < NC16; ++c)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sm_o[wave][4 * g + i][c * 16 + r] = acc[c][i];
+    }
     __syncthreads();
     float* part = a.part + ((((size_t)b * a.H + h) * a.nqt + qt) * a.nsplit + split) * (32 + 16 * DH);
-    for (int idx = threadIdx.x; idx < 16 * DH; idx += 256) {
+    for (int idx = threadIdx.x; idx < 16 * DH; idx += NWV * 64) {
         const int q = idx / DH, c = idx % DH;
         float M = fmaxf(fmaxf(sm_m[0][q], sm_m[1][q]), fmaxf(sm_m[2][q], sm_m[3][q]));
         float L = 0.f, O = 0.f;
@@ -704,8 +734,15 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
         AttnArgs aa{m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages, ids_dev, kv->len, kv->block_table, m->attn, m->attn_lo, m->att_part,
                     R, dm, d.n_heads, kv->d.max_pages_per_seq, l, kv->d.n_pages, nsplit, nqt, split_pages, 1.0f / sqrtf((float)m->dh)};
         dim3 ag(d.n_heads, B, nsplit * nqt);
-        if (m->dh == 128) hipLaunchKernelGGL(attn_kernel<128>, ag, dim3(256), 0, stream, aa);
-        else hipLaunchKernelGGL(attn_kernel<64>, ag, dim3(256), 0, stream, aa);
+        // unsplit contexts in a launch of fewer than two workgroups per compute unit: eight waves share the pages
+        const bool wide = whole && (long)B * d.n_heads * nqt < 2L * ncu;
+        if (m->dh == 128) {
+            if (wide) hipLaunchKernelGGL((attn_kernel<128, 8>), ag, dim3(512), 0, stream, aa);
+            else hipLaunchKernelGGL((attn_kernel<128, 4>), ag, dim3(256), 0, stream, aa);
+        } else {
+            if (wide) hipLaunchKernelGGL((attn_kernel<64, 8>), ag, dim3(512), 0, stream, aa);
+            else hipLaunchKernelGGL((attn_kernel<64, 4>), ag, dim3(256), 0, stream, aa);
+        }
         if (nsplit > 1) {
             dim3 cg(d.n_heads, B * nqt);
             if (m->dh == 128) hipLaunchKernelGGL(attn_combine_kernel<128>, cg, dim3(256), 0, stream, aa);
