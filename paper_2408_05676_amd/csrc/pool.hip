@@ -35,7 +35,6 @@ struct Pool {
 // ------------------------------------------------------------------------------------ kernel
 constexpr int kCand = 2048;        // occurrences a wave keeps in LDS
 constexpr int kVote = 1024;        // vote-table slots (power of two)
-constexpr int kVoteFill = 768;     // distinct tokens beyond which a vote pass is split
 constexpr int kEmptyTok = -1;
 constexpr int kOwnMax = LASER_MAX_OWN_TEXT;   // tokens of a sequence's own text (temporary branch) a lookup can take
 
@@ -61,6 +60,11 @@ struct RetrieveArgs {
 template <bool OWN>
 __global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
     __shared__ uint32_t cand[kCand];
+    // Beside each occurrence kept in LDS: the end of its sequence, and the successor token the current vote read for
+    // it (-1: none). The filter that follows a vote then needs no memory round trip at all, the vote one instead of
+    // two -- the lookup is a chain of dependent round trips, and these were three of the four per chain step.
+    __shared__ uint32_t cand_end[kCand];
+    __shared__ int cand_tok[kCand];
     __shared__ uint32_t own_cand[OWN ? kOwnMax : 1];
     __shared__ int vote_tok[kVote];
     __shared__ int vote_cnt[kVote];
@@ -122,18 +126,28 @@ __global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
         bool in_lds = count <= (uint32_t)kCand;
         uint32_t m = count;
         if (in_lds)
-            for (uint32_t i = lane; i < count; i += 64) cand[i] = a.sa[start + i];
+            for (uint32_t i = lane; i < count; i += 64) {
+                const uint32_t e = a.sa[start + i];
+                cand[i] = e;
+                cand_end[i] = a.seq_end[e];
+            }
         __syncthreads();
 
         int len = 0;
         for (int j = 1; j <= a.K; ++j) {
             int win_tok = -1, win_cnt = 0;
+            // The table is only as large as this vote can need (4 slots per voter, 64..kVote): clearing and scanning
+            // 1024 slots with one wave cost more than the votes of the few dozen occurrences a typical lookup has.
+            const uint32_t voters = (in_lds ? m : count) + mo;
+            int vsz = 64;
+            while (vsz < kVote && (uint32_t)vsz < 4u * voters) vsz *= 2;
+            const int vfill = vsz / 4 * 3;             // distinct tokens beyond which a vote pass is split
             // The vote may need several passes when too many distinct successors show up.
             for (uint32_t nparts = 1;; nparts *= 2) {
                 win_tok = -1; win_cnt = 0;
                 bool overflow = false;
                 for (uint32_t part = 0; part < nparts && !overflow; ++part) {
-                    for (int i = lane; i < kVote; i += 64) { vote_tok[i] = kEmptyTok; vote_cnt[i] = 0; }
+                    for (int i = lane; i < vsz; i += 64) { vote_tok[i] = kEmptyTok; vote_cnt[i] = 0; }
                     if (lane == 0) sh_distinct = 0;
                     __syncthreads();
                     const uint32_t total_pool = in_lds ? m : count;
@@ -145,10 +159,11 @@ __global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
                             int tok = 0;
                             if (i < total_pool) {
                                 uint32_t e = in_lds ? cand[i] : a.sa[start + i];
-                                ok = (e + (uint32_t)j) < a.seq_end[e];
+                                ok = (e + (uint32_t)j) < (in_lds ? cand_end[i] : a.seq_end[e]);
                                 if (ok && !in_lds)
                                     for (int c = 1; c < j; ++c) ok = ok && (a.P[e + c] == chain[c - 1]);
                                 if (ok) tok = a.P[e + j];
+                                if (in_lds) cand_tok[i] = ok ? tok : -1;
                             } else {
                                 const uint32_t e = own_cand[OWN ? i - total_pool : 0];
                                 ok = e + (uint32_t)j < own_len;
@@ -157,8 +172,8 @@ __global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
                             if (ok) {
                                 uint32_t hh = fmix32((uint32_t)tok);
                                 if (nparts == 1 || (hh / kVote) % nparts == part) {
-                                    uint32_t s = hh & (kVote - 1);
-                                    for (int probe = 0; probe < kVote; ++probe) {
+                                    uint32_t s = hh & (vsz - 1);
+                                    for (int probe = 0; probe < vsz; ++probe) {
                                         int cur = vote_tok[s];
                                         if (cur == kEmptyTok) {
                                             int prev = atomicCAS(&vote_tok[s], kEmptyTok, tok);
@@ -166,7 +181,7 @@ __global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
                                             else cur = prev;
                                         }
                                         if (cur == tok) { atomicAdd(&vote_cnt[s], 1); break; }
-                                        s = (s + 1) & (kVote - 1);
+                                        s = (s + 1) & (vsz - 1);
                                     }
                                 }
                             }
@@ -174,16 +189,16 @@ __global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
                         // stop feeding a table that is getting too full; the pass will be split
                         if ((i0 & 1023u) == 960u) {
                             __syncthreads();
-                            if (sh_distinct > kVoteFill) break;
+                            if (sh_distinct > vfill) break;
                         }
                     }
                     __syncthreads();
-                    overflow = sh_distinct > kVoteFill;
+                    overflow = sh_distinct > vfill;
                     __syncthreads();               // everyone has read the counter before it is reset
                     if (overflow) break;
                     // best of this part: larger count, then smaller token id
                     int bt = -1, bc = 0;
-                    for (int i = lane; i < kVote; i += 64) {
+                    for (int i = lane; i < vsz; i += 64) {
                         int c = vote_cnt[i], t = vote_tok[i];
                         if (c > bc || (c == bc && c > 0 && t < bt)) { bc = c; bt = t; }
                     }
@@ -204,15 +219,16 @@ __global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
                 uint32_t out = 0;
                 for (uint32_t i0 = 0; i0 < m; i0 += 64) {
                     uint32_t i = i0 + lane;
-                    uint32_t e = 0; bool keep = false;
+                    uint32_t e = 0, end = 0; bool keep = false;
                     if (i < m) {
                         e = cand[i];
-                        keep = (e + (uint32_t)j) < a.seq_end[e] && a.P[e + j] == win_tok;
+                        end = cand_end[i];
+                        keep = cand_tok[i] == win_tok;     // what the vote just read for this occurrence (tokens are >= 0)
                     }
                     uint64_t mask = __ballot(keep);
                     uint32_t pos = out + __popcll(mask & ((1ull << lane) - 1ull));
                     __syncthreads();               // all reads of this chunk precede the writes
-                    if (keep) cand[pos] = e;       // pos <= i: never overtakes unread entries
+                    if (keep) { cand[pos] = e; cand_end[pos] = end; }   // pos <= i: never overtakes unread entries
                     out += __popcll(mask);
                 }
                 m = out;
@@ -223,15 +239,16 @@ __global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
                     uint32_t out = 0;
                     for (uint32_t i0 = 0; i0 < count; i0 += 64) {
                         uint32_t i = i0 + lane;
-                        uint32_t e = 0; bool keep = false;
+                        uint32_t e = 0, end = 0; bool keep = false;
                         if (i < count) {
                             e = a.sa[start + i];
-                            keep = (e + (uint32_t)j) < a.seq_end[e];
+                            end = a.seq_end[e];
+                            keep = (e + (uint32_t)j) < end;
                             for (int c = 1; c <= j && keep; ++c) keep = (a.P[e + c] == chain[c - 1]);
                         }
                         uint64_t mask = __ballot(keep);
                         uint32_t pos = out + __popcll(mask & ((1ull << lane) - 1ull));
-                        if (keep) cand[pos] = e;
+                        if (keep) { cand[pos] = e; cand_end[pos] = end; }
                         out += __popcll(mask);
                     }
                     m = out;
