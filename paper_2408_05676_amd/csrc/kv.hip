@@ -8,6 +8,13 @@
 namespace laser {
 
 int KV::stage_ids(const int32_t* host_ids, int B, hipStream_t stream, const int32_t** dev_out) {
+    // The same ids on the same stream as the staging before (the steady state of a decoding loop, where verify and
+    // commit alternate over one batch): that device copy is still intact and ordered before this call.
+    if (ids_last >= 0 && ids_last_n == B && ids_last_stream == stream &&
+        std::memcmp(ids_pinned + (size_t)ids_last * d.max_seqs, host_ids, (size_t)B * sizeof(int32_t)) == 0) {
+        *dev_out = ids_dev + (size_t)ids_last * d.max_seqs;
+        return LASER_OK;
+    }
     const int s = ids_next;
     ids_next = (ids_next + 1) % kIdSlots;
     if (ids_used[s]) LASER_HIP_CHECK(hipEventSynchronize(ids_ev[s]));   // slot's last copy has been consumed
@@ -17,6 +24,7 @@ int KV::stage_ids(const int32_t* host_ids, int B, hipStream_t stream, const int3
     LASER_HIP_CHECK(hipMemcpyAsync(dev, pin, (size_t)B * sizeof(int32_t), hipMemcpyHostToDevice, stream));
     LASER_HIP_CHECK(hipEventRecord(ids_ev[s], stream));
     ids_used[s] = true;
+    ids_last = s; ids_last_n = B; ids_last_stream = stream;
     *dev_out = dev;
     return LASER_OK;
 }

@@ -34,6 +34,8 @@ struct KV {
     int32_t* ids_dev = nullptr;       // [kIdSlots][max_seqs]
     hipEvent_t ids_ev[kIdSlots]{};
     bool ids_used[kIdSlots]{};
+    int ids_last = -1, ids_last_n = 0;            // most recently staged slot, its id count and stream
+    hipStream_t ids_last_stream = nullptr;
     int ids_next = 0;
 
     int stage_ids(const int32_t* host_ids, int B, hipStream_t stream, const int32_t** dev_out);
