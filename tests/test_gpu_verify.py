@@ -196,6 +196,14 @@ def test_argument_errors_and_capacity():
     al = torch.tensor([2, 0], dtype=torch.int32, device="cuda")
     laser.ctx_advance(tail, pend, outt, al)
     assert tail.cpu().tolist() == [[7, 8, 9], [2, 3, 4]] and pend.cpu().tolist() == [9, 4]
+    # options: known names take their documented values only; unknown names are refused
+    for name, good, bad in (("ksplit_qkv", 2, 3), ("ksplit_down", 4, 8), ("mid_waves", 8, 3), ("attn_whole_min", 128, -1)):
+        model.set_option(name, good)
+        with pytest.raises(laser.LaserError):
+            model.set_option(name, bad)
+        model.set_option(name, 0)
+    with pytest.raises(laser.LaserError, match="unknown option"):
+        model.set_option("no_such_option", 1)
     model.close(); kv.close()
 
 
