@@ -4,13 +4,15 @@
 //
 // The few-row kernel (gemm_skinny.h) re-reads the activation rows from L2 at every step: with MB row tiles in two
 // planes that is 2 MB x 64 bytes per lane and step against 64 bytes of weights, and at 72 rows it is bound by L2,
-// not by HBM. Here the four waves of a workgroup own four DIFFERENT 16-row weight tiles and walk the SAME
-// reduction range, so the activation chunk of a step (rows x 128 elements, both planes) is staged once in LDS by
-// the whole workgroup and read from there by every wave; the next chunk and the next step's weight fragments are
-// in flight while the current ones are multiplied (two named fragment sets, the loop unrolled by two: a register
-// copy of a fragment still in flight would make the wave wait for it). Register pressure is kept below the
-// point of scratch spills on purpose: a reload from scratch waits, in order, behind every global load issued
-// before it, which puts a full HBM latency into each step.
+// not by HBM. Here the waves of a workgroup own DIFFERENT 16-row weight tiles and walk the SAME reduction range,
+// so the activation chunk of a step (rows x 128 elements, both planes) is staged once in LDS by the whole
+// workgroup and read from there by every wave, while the next chunk(s) and weight fragments are in flight in
+// named register sets (the loops are unrolled by the ring sizes: a register copy of a fragment still in flight
+// would make the wave wait for it). 4-wave form: two chunk buffers, chunk s + 1 written in the middle of step s,
+// one barrier per step. 8-wave form: one buffer, two barriers, chunk two steps and fragments three steps ahead,
+// requests spread over the step. Register pressure is kept below the point of scratch spills inside the loops on
+// purpose: a reload from scratch waits, in order, behind every global load issued before it, which puts a full
+// HBM latency into each step.
 //
 // blockIdx.y = part of the reduction: with more than one part each workgroup stores its partial result at
 // part + blockIdx.y * M * N and the consumer adds the parts in order (store / accumulate epilogues only).
@@ -46,7 +48,9 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void gemm_mid_kernel(Gemm
     constexpr int NT = NW * 64;                              // threads
     constexpr int NPIECE = (ROWS * 16 + NT - 1) / NT;        // 16-byte pieces of a plane's chunk per thread
     constexpr int LDH = kGemmKStep + 8;   // halves per LDS row: 272 bytes, the 16 rows of a 16-byte read hit distinct banks
-    __shared__ __attribute__((aligned(16))) uint16_t sx[NP * ROWS * LDH];
+    constexpr int BUFH = NP * ROWS * LDH; // halves per chunk buffer
+    // dynamic LDS: one chunk buffer for the 8-wave form, two for the 4-wave form (gemm_mid_lds_bytes)
+    extern __shared__ __attribute__((aligned(16))) uint16_t sx[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int r = lane & 15, g = lane >> 4;
     const int ntiles = a.N / 16;
@@ -148,33 +152,106 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void gemm_mid_kernel(Gemm
         });
         __syncthreads();                                     // the chunk is free for the next step's pieces
     };
-    // prologue: the first XD chunks and WD fragment sets
-    // (in the order of first use, pinned by scheduling fences: loads complete in issue order, and the loop header's
-    // wait for the first chunk must not find a later request ahead of it)
-    auto prologue = [&](auto guard_c) {
-        static_for<0, XD>([&](auto d) {
-            static_for<4, NLOAD>([&](auto l) { load_one(guard_c, send, sbeg + decltype(d)::value, l, std::integral_constant<int, 0>{}, d); });
-            __builtin_amdgcn_sched_barrier(0);
+    if constexpr (DEEP) {
+        // prologue: the first XD chunks and WD fragment sets
+        // (in the order of first use, pinned by scheduling fences: loads complete in issue order, and the loop header's
+        // wait for the first chunk must not find a later request ahead of it)
+        auto prologue = [&](auto guard_c) {
+            static_for<0, XD>([&](auto d) {
+                static_for<4, NLOAD>([&](auto l) { load_one(guard_c, send, sbeg + decltype(d)::value, l, std::integral_constant<int, 0>{}, d); });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            static_for<0, WD>([&](auto d) {
+                static_for<0, 4>([&](auto l) { load_one(guard_c, sbeg + decltype(d)::value, send, l, d, std::integral_constant<int, 0>{}); });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        };
+        // main loop: groups of UNROLL steps all of whose requests lie inside the part, entered through a prologue without
+        // guards (so that the loop header sees known wait-counter states on both of its edges); then up to
+        // UNROLL + WD - 1 steps one by one (the ring positions carry on: every group starts at position 0)
+        int st = sbeg;                                           // sbeg, send are the same for every wave of the workgroup
+        if (st + UNROLL + WD <= send) {
+            prologue(std::false_type{});
+            for (; st + UNROLL + WD <= send; st += UNROLL)
+                static_for<0, UNROLL>([&](auto j) { step(std::false_type{}, st + decltype(j)::value, j); });
+        } else {
+            prologue(std::true_type{});
+        }
+        static_for<0, UNROLL + WD - 1>([&](auto j) {
+            if (st + decltype(j)::value < send) step(std::true_type{}, st + decltype(j)::value, j);
         });
-        static_for<0, WD>([&](auto d) {
-            static_for<0, 4>([&](auto l) { load_one(guard_c, sbeg + decltype(d)::value, send, l, d, std::integral_constant<int, 0>{}); });
-            __builtin_amdgcn_sched_barrier(0);
-        });
-    };
-    // main loop: groups of UNROLL steps all of whose requests lie inside the part, entered through a prologue without
-    // guards (so that the loop header sees known wait-counter states on both of its edges); then up to
-    // UNROLL + WD - 1 steps one by one (the ring positions carry on: every group starts at position 0)
-    int st = sbeg;                                           // sbeg, send are the same for every wave of the workgroup
-    if (st + UNROLL + WD <= send) {
-        prologue(std::false_type{});
-        for (; st + UNROLL + WD <= send; st += UNROLL)
-            static_for<0, UNROLL>([&](auto j) { step(std::false_type{}, st + decltype(j)::value, j); });
     } else {
-        prologue(std::true_type{});
+        // 4-wave form: two chunk buffers. The pieces of chunk s + 1 (requested half a step or more earlier) are
+        // written into the other buffer in the MIDDLE of step s, between the matrix instructions of two row tiles,
+        // and the request for chunk s + 2 follows them: the write, its wait and the requests' issue time hide behind
+        // the matrix work, and a step needs ONE workgroup barrier instead of two.
+        auto write_chunk = [&](int buf) {
+#pragma unroll
+            for (int i = 0; i < NPIECE; ++i) {
+                *reinterpret_cast<u32x4*>(sx + buf * BUFH + xdst[i]) = xr[0][0][i];
+                if constexpr (SPLIT) *reinterpret_cast<u32x4*>(sx + buf * BUFH + ROWS * LDH + xdst[i]) = xr[0][NP - 1][i];
+            }
+        };
+        using X0 = std::integral_constant<int, 0>;
+        auto step2 = [&](auto guard_c, int st, auto j_c) {
+            constexpr bool GUARD = decltype(guard_c)::value;
+            constexpr int J = decltype(j_c)::value, CB = J % 2, NB = (J + 1) % 2, WS = J % WR, WF = (J + WD) % WR;
+            using WFc = std::integral_constant<int, WF>;
+            static_for<0, 4>([&](auto l) { load_one(guard_c, st + WD, send, l, WFc{}, X0{}); });
+            Frag8 (&cur)[4] = w[WS];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) bf16x8_to_f16x8(cur[c]);
+            Frag8 b[2][NP * 4];
+            auto read_b = [&](int mb, Frag8 (&f)[NP * 4]) {
+                const uint16_t* row = sx + CB * BUFH + (mb * 16 + r) * LDH + g * 32;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) f[c].v4 = *reinterpret_cast<const u32x4*>(row + c * 8);
+                if constexpr (SPLIT) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) f[4 + c].v4 = *reinterpret_cast<const u32x4*>(row + ROWS * LDH + c * 8);
+                }
+            };
+            read_b(0, b[0]);
+            static_for<0, MB>([&](auto mb_c) {
+                constexpr int mb = decltype(mb_c)::value;
+                if constexpr (mb + 1 < MB) read_b(mb + 1, b[(mb + 1) & 1]);
+                if constexpr (mb == MB / 2) {
+                    if (!GUARD || st + 1 < send) write_chunk(NB);
+                    static_for<4, NLOAD>([&](auto l) { load_one(guard_c, send, st + 2, l, WFc{}, X0{}); });
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[mb] = mfma_16x16x32(cur[c], b[mb & 1][c], acc[mb]);
+                if constexpr (SPLIT) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acl[mb] = mfma_16x16x32(cur[c], b[mb & 1][NP * 4 - 4 + c], acl[mb]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            __syncthreads();         // chunk s + 1 is complete for everyone, chunk s is free
+        };
+        // prologue: chunk sbeg into buffer 0, chunk sbeg + 1 requested, the first fragment set
+        auto prologue2 = [&](auto guard_c) {
+            static_for<4, NLOAD>([&](auto l) { load_one(std::false_type{}, send, sbeg, l, X0{}, X0{}); });   // sbeg < send always
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<0, 4>([&](auto l) { load_one(std::false_type{}, sbeg, send, l, X0{}, X0{}); });
+            __builtin_amdgcn_sched_barrier(0);
+            write_chunk(0);
+            static_for<4, NLOAD>([&](auto l) { load_one(guard_c, send, sbeg + 1, l, X0{}, X0{}); });
+            __syncthreads();
+        };
+        int st = sbeg;                                       // sbeg, send are the same for every wave of the workgroup
+        if (st + UNROLL + 2 <= send) {
+            prologue2(std::false_type{});
+            for (; st + UNROLL + 2 <= send; st += UNROLL)
+                static_for<0, UNROLL>([&](auto j) { step2(std::false_type{}, st + decltype(j)::value, j); });
+        } else {
+            prologue2(std::true_type{});
+        }
+        static_for<0, UNROLL + 1>([&](auto j) {
+            if (st + decltype(j)::value < send) step2(std::true_type{}, st + decltype(j)::value, j);
+        });
     }
-    static_for<0, UNROLL + WD - 1>([&](auto j) {
-        if (st + decltype(j)::value < send) step(std::true_type{}, st + decltype(j)::value, j);
-    });
     float v[MB][4];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
@@ -182,7 +259,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void gemm_mid_kernel(Gemm
         for (int i = 0; i < 4; ++i) v[mb][i] = SPLIT ? acc[mb][i] + acl[mb][i] * kLoInv : acc[mb][i];
     const int n = tile * 16 + 4 * g;
     if constexpr (EPI == EPI_SWIGLU) {
-        static_assert((NW / 2) * MB * 4 * 64 * sizeof(float) <= sizeof(sx), "the exchange area must fit the staging area");
+        static_assert((NW / 2) * MB * 4 * 64 * sizeof(float) <= BUFH * sizeof(uint16_t), "the exchange area must fit a chunk buffer");
         float* ex = reinterpret_cast<float*>(sx);             // [pair][mb][i][lane]; the loop's last barrier freed sx
         if (sel == 1) {
 #pragma unroll
@@ -254,6 +331,11 @@ inline GemmMidPlan gemm_mid_plan(int M, int N, int Kd, int planes, bool swiglu, 
     return best;
 }
 
+// Dynamic LDS of a launch: one chunk buffer (both planes, padded rows) for the 8-wave form, two for the 4-wave form.
+constexpr size_t gemm_mid_lds_bytes(int mb, bool split, int nw) {
+    return (size_t)(nw == 8 ? 1 : 2) * (split ? 2 : 1) * mb * 16 * (kGemmKStep + 8) * sizeof(uint16_t);
+}
+
 // Caller guarantees 16 < M <= 80, N % 16 == 0, Kd % 128 == 0, and a plan made for this shape.
 template <int EPI, bool SPLIT>
 inline void launch_gemm_mid(const GemmMidArgs& a, GemmMidPlan pl, hipStream_t stream) {
@@ -261,8 +343,19 @@ inline void launch_gemm_mid(const GemmMidArgs& a, GemmMidPlan pl, hipStream_t st
     dim3 grid((unsigned)((vtiles + pl.NW - 1) / pl.NW), (unsigned)pl.S);
     auto go = [&](auto mbc) {
         constexpr int mb = decltype(mbc)::value;
-        if (pl.NW == 8) hipLaunchKernelGGL((gemm_mid_kernel<mb, EPI, SPLIT, 8>), grid, dim3(512), 0, stream, a);
-        else hipLaunchKernelGGL((gemm_mid_kernel<mb, EPI, SPLIT, 4>), grid, dim3(256), 0, stream, a);
+        // more than 64 KB of dynamic LDS has to be allowed per kernel, once
+        static const bool allowed = [] {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mid_kernel<mb, EPI, SPLIT, 8>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_mid_lds_bytes(mb, SPLIT, 8));
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mid_kernel<mb, EPI, SPLIT, 4>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_mid_lds_bytes(mb, SPLIT, 4));
+            return true;
+        }();
+        (void)allowed;
+        if (pl.NW == 8)
+            hipLaunchKernelGGL((gemm_mid_kernel<mb, EPI, SPLIT, 8>), grid, dim3(512), gemm_mid_lds_bytes(mb, SPLIT, 8), stream, a);
+        else
+            hipLaunchKernelGGL((gemm_mid_kernel<mb, EPI, SPLIT, 4>), grid, dim3(256), gemm_mid_lds_bytes(mb, SPLIT, 4), stream, a);
     };
     switch (mblocks) {
         case 2: go(std::integral_constant<int, 2>{}); break;
