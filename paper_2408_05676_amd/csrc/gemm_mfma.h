@@ -79,7 +79,13 @@ template <int EPI, int BN, bool SPLIT, bool WF16 = false>
 __global__ __launch_bounds__(256, SPLIT ? 2 : GM_WGS) void gemm_mfma_kernel(GemmTileArgs a) {
     static_assert(BN == 128 || (BN == 64 && EPI != GEPI_SWIGLU), "tile width");
     constexpr int GM_BK = SPLIT ? 32 : GM_BK_PLAIN;   // reduction step
-    constexpr int GM_LD = GM_BK + 8;         // halves per padded LDS row (16-byte reads of 8 rows fall into distinct banks)
+    // LDS rows. Single-plane kernel: 64 + 8 halves, the padding spreads 16-byte reads of consecutive rows over the banks.
+    // Split kernel (step 32): padded 80-byte rows left a third of the LDS-active cycles in bank conflicts (hardware
+    // counter), so its rows are unpadded 64 bytes and the four 16-byte chunks of row r sit at chunk ^ ((r >> 2) & 3):
+    // 16 consecutive rows at one logical chunk, and 4 rows x 4 chunks of a staging write, each touch 16 distinct
+    // 16-byte bank groups.
+    constexpr bool SWZ = SPLIT;
+    constexpr int GM_LD = SWZ ? GM_BK : GM_BK + 8;
     constexpr int CH = GM_BK / 8;            // 16-byte chunks per tile row and k-step
     constexpr int RPT = 256 / CH;            // rows staged per pass of the 256 threads
     constexpr int ST = GM_BM / RPT;          // passes over the activation rows
@@ -113,6 +119,7 @@ __global__ __launch_bounds__(256, SPLIT ? 2 : GM_WGS) void gemm_mfma_kernel(Gemm
 
     // global -> LDS staging: thread t moves chunk t % CH of rows t / CH + RPT i of both operands
     const int srow = tid / CH, sk = (tid % CH) * 8;
+    const int skw = SWZ ? ((tid % CH) ^ ((srow >> 2) & 3)) * 8 : sk;       // LDS column of this thread's chunk (RPT is a multiple of 16)
     const uint16_t* xa[ST];
     const uint16_t* xl[ST];
     const uint16_t* wb[STB];
@@ -181,8 +188,8 @@ __global__ __launch_bounds__(256, SPLIT ? 2 : GM_WGS) void gemm_mfma_kernel(Gemm
 #pragma unroll
         for (int i = 0; i < ST; ++i)
             if (i * NKK / ST == kk) {
-                *reinterpret_cast<u32x4*>(&sA[buf][srow + RPT * i][sk]) = ra[slot][i] & keep;
-                if constexpr (SPLIT) *reinterpret_cast<u32x4*>(&sAl[buf][srow + RPT * i][sk]) = rl[slot][i] & keep;
+                *reinterpret_cast<u32x4*>(&sA[buf][srow + RPT * i][skw]) = ra[slot][i] & keep;
+                if constexpr (SPLIT) *reinterpret_cast<u32x4*>(&sAl[buf][srow + RPT * i][skw]) = rl[slot][i] & keep;
             }
 #pragma unroll
         for (int i = 0; i < STB; ++i)
@@ -190,17 +197,19 @@ __global__ __launch_bounds__(256, SPLIT ? 2 : GM_WGS) void gemm_mfma_kernel(Gemm
                 Frag8 fw;
                 fw.v4 = rb[slot][i];
                 if constexpr (!WF16) bf16x8_to_f16x8(fw);
-                *reinterpret_cast<u32x4*>(&sB[buf][srow + RPT * i][sk]) = fw.v4;
+                *reinterpret_cast<u32x4*>(&sB[buf][srow + RPT * i][skw]) = fw.v4;
             }
     };
     auto multiply_piece = [&](int buf, int kk) {
         Frag8 fa[2], fb[NJ];
+        // LDS column of this lane's fragment (every row offset above lr is a multiple of 32)
+        const int fc = SWZ ? ((kk * 2 + lg) ^ ((lr >> 2) & 3)) * 8 : kk * 16 + lg * 8;
 #pragma unroll
         for (int i = 0; i < 2; ++i)
-            fa[i].v4 = *reinterpret_cast<const u32x4*>(&sA[buf][wm * 64 + i * 32 + lr][kk * 16 + lg * 8]);
+            fa[i].v4 = *reinterpret_cast<const u32x4*>(&sA[buf][wm * 64 + i * 32 + lr][fc]);
 #pragma unroll
         for (int i = 0; i < NJ; ++i)
-            fb[i].v4 = *reinterpret_cast<const u32x4*>(&sB[buf][wn * WN + i * 32 + lr][kk * 16 + lg * 8]);
+            fb[i].v4 = *reinterpret_cast<const u32x4*>(&sB[buf][wn * WN + i * 32 + lr][fc]);
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -209,7 +218,7 @@ __global__ __launch_bounds__(256, SPLIT ? 2 : GM_WGS) void gemm_mfma_kernel(Gemm
             Frag8 fl[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i)
-                fl[i].v4 = *reinterpret_cast<const u32x4*>(&sAl[buf][wm * 64 + i * 32 + lr][kk * 16 + lg * 8]);
+                fl[i].v4 = *reinterpret_cast<const u32x4*>(&sAl[buf][wm * 64 + i * 32 + lr][fc]);
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
