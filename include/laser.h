@@ -252,6 +252,8 @@ int laser_ctx_advance(int32_t* ctx_tail, int32_t* pending, const int32_t* out_to
  * "attn_whole_min" = 0 (default: half the number of compute units) or a count: from this many (sequence, head,
  * 16-row query tile) triples on, the general path's attention walks a context in one workgroup instead of
  * splitting it into 256-token parts that a second kernel merges.
+ * "attn_waves" = 0 (default: eight when an unsplit launch has fewer than two workgroups per compute unit, else four),
+ * 4 or 8: waves of a workgroup that share the pages of an unsplit context.
  * Unknown names and out-of-range values return LASER_E_INVALID_ARG. */
 int laser_model_set_option(laser_model* model, const char* name, int value);
 /* Phase trace of the persistent kernel (option "fused_trace" = 1): thread 0 of every workgroup stamps

@@ -8,9 +8,7 @@ decoder blocks, RMSNorm (eps 1e-6), rotary positions (base 10000, element i pair
 i + head_dim/2), multi-head causal attention with scale 1/sqrt(head_dim), SwiGLU FFN,
 no biases, untied embedding and output head.  Everything is evaluated in float64 (or the
 dtype asked for) on the weight values handed in; activations and the KV cache are never
-rounded.  (A diagnostic switch, `act_round`, applies a caller-supplied rounding function
-to the matrix-product inputs and to cached keys/values; it exists only to attribute a
-discrepancy to reduced-precision storage and is never the pass criterion.)
+rounded.
 
 Rows r = 0..R-1 of one sequence hold the tokens [pending, draft_1 .. draft_{R-1}] at
 positions len+r; row r's output is the distribution of the token after it (q_{r+1}).  Keys
@@ -56,14 +54,13 @@ class KVCache:
 
 class Decoder:
     def __init__(self, n_layers, d, n_heads, ffn, vocab, weights, eps=1e-6, rope_base=10000.0,
-                 dtype=np.float64, act_round=None):
+                 dtype=np.float64):
         """weights[(name, layer)] -> array in the layouts of the data spec:
         wqkv [3d][d], wo [d][d], wgu [2F][d], wdown [d][F], g1, g2 [d]; ('emb',-1) [V][d],
         ('wlm',-1) [V][d], ('gf',-1) [d]."""
         self.L, self.d, self.H, self.F, self.V = n_layers, d, n_heads, ffn, vocab
         self.dh = d // n_heads
         self.w, self.eps, self.base, self.dt = weights, eps, rope_base, dtype
-        self.rnd = (lambda a: a) if act_round is None else (lambda a: act_round(a).astype(dtype))
 
     def _w(self, name, layer=-1):
         return np.asarray(self.w[(name, layer)], dtype=self.dt)
@@ -79,11 +76,11 @@ class Decoder:
         pos = np.arange(t0, t0 + R)
         x = self._w("emb")[tokens].copy()                                   # [R][d]
         for l in range(self.L):
-            n1 = self.rnd(rmsnorm(x, self._w("g1", l), self.eps))
+            n1 = rmsnorm(x, self._w("g1", l), self.eps)
             qkv = n1 @ self._w("wqkv", l).T                                  # [R][3d]
-            q = self.rnd(rope(qkv[:, :d].reshape(R, H, dh), pos, self.base))
-            k = self.rnd(rope(qkv[:, d:2 * d].reshape(R, H, dh), pos, self.base))
-            v = self.rnd(qkv[:, 2 * d:].reshape(R, H, dh))
+            q = rope(qkv[:, :d].reshape(R, H, dh), pos, self.base)
+            k = rope(qkv[:, d:2 * d].reshape(R, H, dh), pos, self.base)
+            v = qkv[:, 2 * d:].reshape(R, H, dh)
             cache.k[l, t0:t0 + R] = k
             cache.v[l, t0:t0 + R] = v
             att = np.empty((R, H, dh), dtype=self.dt)
@@ -95,11 +92,11 @@ class Decoder:
                 p = np.exp(s)
                 p = p / p.sum(axis=1, keepdims=True)
                 att[r] = np.einsum("ht,thd->hd", p, vv)
-            x = x + self.rnd(att.reshape(R, d)) @ self._w("wo", l).T
-            n2 = self.rnd(rmsnorm(x, self._w("g2", l), self.eps))
+            x = x + att.reshape(R, d) @ self._w("wo", l).T
+            n2 = rmsnorm(x, self._w("g2", l), self.eps)
             gu = n2 @ self._w("wgu", l).T                                    # [R][2F]
-            x = x + self.rnd(silu(gu[:, :self.F]) * gu[:, self.F:]) @ self._w("wdown", l).T
-        return self.rnd(rmsnorm(x, self._w("gf"), self.eps))
+            x = x + (silu(gu[:, :self.F]) * gu[:, self.F:]) @ self._w("wdown", l).T
+        return rmsnorm(x, self._w("gf"), self.eps)
 
     def head(self, h: np.ndarray) -> np.ndarray:
         return h @ self._w("wlm").T

@@ -1241,10 +1241,19 @@ struct FusedWS {
     int trace_cap = 0;
 };
 
-bool fused_supported(const Model* m, int B, int K) {
+// context splits of a launch: a fixed AW * PPW pages (256 tokens) each, enough to cover the longest sequence
+static int fused_splits(int max_len_ub, int R) {
+    const int pages_ub = (max_len_ub + R + kPageSize - 1) / kPageSize;
+    return std::max(1, (pages_ub + AW * PPW - 1) / (AW * PPW));
+}
+
+// max_len_ub: the host's bound of the longest committed context of the batch. A batch whose (sequence, head, context
+// split) triples exceed what the partial buffer holds takes the general path instead.
+bool fused_supported(const Model* m, int B, int K, int max_len_ub) {
     const laser_model_desc& d = m->d;
     if (!query_device()) return false;
     const int nwg = g_num_cu, M = B * (K + 1);
+    if ((long)B * d.n_heads * fused_splits(max_len_ub, K + 1) > 16L * nwg) return false;
     auto per = [](int n, int lanes) { return (n + lanes - 1) / lanes; };
     // every wave slot accumulates at most MAX_UNITS tiles per phase; the norm reduction reads <= 256 partials
     return d.n_layers > 0 && M >= 1 && M <= 16 && d.d_model % 128 == 0 && d.ffn % 128 == 0 && d.vocab % 16 == 0 &&
@@ -1320,12 +1329,10 @@ int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, 
     if (rc) return rc;
     const laser_model_desc& d = m->d;
     const int R = K + 1;
-    // context splits: a fixed AW * PPW pages (256 tokens) each, enough to cover the longest sequence
-    const int pages_ub = (max_len_ub + R + kPageSize - 1) / kPageSize;
-    const int S = std::max(1, (pages_ub + AW * PPW - 1) / (AW * PPW));
+    const int S = fused_splits(max_len_ub, R);
     LASER_REQUIRE(B * d.n_heads * S <= ws->bh_cap, LASER_E_LIMIT,
-                  "context of %d tokens needs %d attention splits; the persistent kernel holds %d (use option fused = 0)",
-                  max_len_ub + R, B * d.n_heads * S, ws->bh_cap);
+                  "context of %d tokens needs %d attention splits; the persistent kernel holds %d",
+                  max_len_ub + R, B * d.n_heads * S, ws->bh_cap);      // fused_supported() has already ruled this out
     FusedArgs a{};
     a.wqkv = d.wqkv; a.wo = d.wo; a.wgu = d.wgu; a.wdown = d.wdown; a.emb = d.emb; a.wlm = d.wlm;
     a.g1 = d.g1; a.g2 = d.g2; a.gf = d.gf;
@@ -1347,7 +1354,6 @@ int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, 
     a.epoch0 = ws->epoch;
     a.trace = m->fused_trace ? ws->trace : nullptr;
     a.trace_cap = ws->trace_cap;
-    ws->epoch += 5ull * d.n_layers + 2ull;
     void* args[] = {&a};
     const bool tr = a.trace != nullptr;
     const void* fn = m->dh == 128 ? (tr ? (const void*)verify_fused_kernel<128, true> : (const void*)verify_fused_kernel<128, false>)
@@ -1355,6 +1361,7 @@ int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, 
     const bool prof = m->prof_on && m->prof_n < m->prof_cap;
     if (prof) LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n], stream));
     LASER_HIP_CHECK(hipLaunchCooperativeKernel(fn, dim3(ws->nwg), dim3(FT), args, (size_t)g_lds_max, stream));
+    ws->epoch += 5ull * d.n_layers + 2ull;       // barriers this launch passes; advanced only once it is enqueued
     if (prof) { LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n + 1], stream)); ++m->prof_n; }
     return LASER_OK;
 }

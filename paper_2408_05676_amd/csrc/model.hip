@@ -12,7 +12,7 @@
 
 namespace laser {
 
-bool fused_supported(const Model* m, int B, int K);
+bool fused_supported(const Model* m, int B, int K, int max_len_ub);
 void fused_free(Model* m);
 int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, const int32_t* drafts,
               const int32_t* draft_len, int B, int K, int topk, float p, int mode, int32_t* accept_len,
@@ -481,9 +481,11 @@ __global__ __launch_bounds__(NWV * 64, NWV == 4 ? 4 : 2) void attn_kernel(AttnAr
     const int rows_here = min(a.R - qt * 16, 16);
     const int last_tok = len + qt * 16 + rows_here - 1;  // last slot any row of this tile may see
     const int npages = last_tok / kPageSize + 1;
-    // A split is always kSplitPages pages at fixed positions, so the order in which a row's scores are
-    // reduced depends on the row's position only (not on the batch, the draft count or the host's
-    // length bound): verifying a token as a draft reproduces its one-at-a-time logits bit for bit.
+    // A split is always kSplitPages pages at fixed positions and its pages go round-robin over the waves, so within
+    // one launch shape (same split policy and waves per workgroup) the order in which a row's scores are reduced
+    // depends on the row's position only, not on the draft count or the host's length bound: verifying a token as
+    // a draft reproduces its one-at-a-time logits bit for bit. Launch shapes that take the context unsplit, or
+    // with eight waves, reduce in a different order and may differ from the split form in the last bits.
     const int p0 = split * a.split_pages, p1 = min(npages, p0 + a.split_pages);
 
     Frag8 bq[NC32], bql[NC32];
@@ -680,9 +682,18 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
         const size_t n[4] = {(size_t)d.n_layers * 3 * dm * dm, (size_t)d.n_layers * dm * dm, (size_t)d.n_layers * 2 * F * dm,
                              (size_t)d.n_layers * dm * F};
         const uint16_t* src[4] = {d.wqkv, d.wo, d.wgu, d.wdown};
+        uint16_t* cp[4] = {nullptr, nullptr, nullptr, nullptr};      // published only when all four exist
         for (int i = 0; i < 4; ++i) {
-            LASER_HIP_CHECK(hipMalloc((void**)&m->w16[i], n[i] * 2));
-            hipLaunchKernelGGL(widen_weights_kernel, dim3(2048), dim3(256), 0, stream, src[i], m->w16[i], n[i] / 8);
+            const hipError_t e = hipMalloc((void**)&cp[i], n[i] * 2);
+            if (e != hipSuccess) {
+                for (int j = 0; j < i; ++j) (void)hipFree(cp[j]);
+                set_error("hipMalloc of the %zu-byte fp16 weight copy failed: %s", n[i] * 2, hipGetErrorString(e));
+                return LASER_E_HIP;
+            }
+        }
+        for (int i = 0; i < 4; ++i) {
+            hipLaunchKernelGGL(widen_weights_kernel, dim3(2048), dim3(256), 0, stream, src[i], cp[i], n[i] / 8);
+            m->w16[i] = cp[i];
         }
         LASER_HIP_CHECK(hipGetLastError());
     }
@@ -735,7 +746,7 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
                     R, dm, d.n_heads, kv->d.max_pages_per_seq, l, kv->d.n_pages, nsplit, nqt, split_pages, 1.0f / sqrtf((float)m->dh)};
         dim3 ag(d.n_heads, B, nsplit * nqt);
         // unsplit contexts in a launch of fewer than two workgroups per compute unit: eight waves share the pages
-        const bool wide = whole && (long)B * d.n_heads * nqt < 2L * ncu;
+        const bool wide = whole && (m->attn_waves ? m->attn_waves == 8 : (long)B * d.n_heads * nqt < 2L * ncu);
         if (m->dh == 128) {
             if (wide) hipLaunchKernelGGL((attn_kernel<128, 8>), ag, dim3(512), 0, stream, aa);
             else hipLaunchKernelGGL((attn_kernel<128, 4>), ag, dim3(256), 0, stream, aa);
@@ -890,12 +901,17 @@ extern "C" int laser_verify_step(laser_model* mh, laser_kv* kh, const int32_t* s
     }
     const int32_t* ids_dev = nullptr;
     if ((rc = kv->stage_ids(seq_ids, B, stream, &ids_dev))) return rc;
-    for (int b = 0; b < B; ++b) kv->h_last_rows[seq_ids[b]] = R;
-    if (m->use_fused && fused_supported(m, B, K))
-        return run_fused(m, kv, ids_dev, pending, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens,
-                         logits_dbg, max_ub, stream);
-    if ((rc = forward(m, kv, ids_dev, pending, drafts, draft_len, B, K, max_ub, stream))) return rc;
-    return run_head(m, m->xn, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens, logits_dbg, stream);
+    if (m->use_fused && fused_supported(m, B, K, max_ub)) {
+        rc = run_fused(m, kv, ids_dev, pending, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens,
+                       logits_dbg, max_ub, stream);
+    } else {
+        if ((rc = forward(m, kv, ids_dev, pending, drafts, draft_len, B, K, max_ub, stream))) return rc;
+        rc = run_head(m, m->xn, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens, logits_dbg, stream);
+    }
+    // only a step that has been enqueued may be committed
+    if (rc == LASER_OK)
+        for (int b = 0; b < B; ++b) kv->h_last_rows[seq_ids[b]] = R;
+    return rc;
 }
 
 extern "C" int laser_verify_head(laser_model* mh, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len,
@@ -953,6 +969,11 @@ extern "C" int laser_model_set_option(laser_model* mh, const char* name, int val
     if (std::string(name) == "attn_whole_min") {
         LASER_REQUIRE(value >= 0, LASER_E_INVALID_ARG, "attn_whole_min must be >= 0");
         m->attn_whole_min = value;
+        return LASER_OK;
+    }
+    if (std::string(name) == "attn_waves") {
+        LASER_REQUIRE(value == 0 || value == 4 || value == 8, LASER_E_INVALID_ARG, "attn_waves must be 0 (choose), 4 or 8");
+        m->attn_waves = value;
         return LASER_OK;
     }
     for (int i = 0; i < 3; ++i)

@@ -7,8 +7,10 @@
 //   sa[Ne]      uint32  every position that has an in-sequence successor, sorted inside its
 //                       sub-pool by the text read backwards from it (P[e], P[e-1], ... up to n_max
 //                       tokens, "before the sequence start" ordering first), then by position.
-//                       All occurrences of any n-gram (n <= n_max) are therefore one contiguous,
-//                       position-ascending run of sa.
+//                       All occurrences of any n-gram (n <= n_max) are therefore one contiguous run of
+//                       sa. Only the runs of n_max-grams are position-ascending: inside the run of a shorter
+//                       n-gram the order is set by the tokens further back first, so the smallest position
+//                       of a run has to be searched for (the lookup takes an explicit minimum).
 //   table[cap]  16 B    open addressing (linear probing, load <= 0.5): (key, n, n-gram) -> run in sa
 // A lookup hashes (key, n, suffix), probes, and confirms a hit by comparing key, n and the actual
 // tokens at the run's first occurrence, so hash collisions cannot produce a false match.

@@ -83,6 +83,7 @@ struct Model {
     int ksplit_opt[3] = {0, 0, 0};     // forced reduction parts for QKV, O, down (0 = choose from the tile count)
     int mid_waves = 0;                 // 17..80 rows: waves per workgroup of the weight-streaming GEMM, 0 = chosen per launch shape
     int attn_whole_min = 0;            // attention takes a context unsplit from this many (sequence, head, query tile) triples on; 0: half the number of compute units
+    int attn_waves = 0;                // unsplit attention: waves per workgroup that share a context's pages (4 or 8), 0 = chosen per launch shape
     int split_ffn = 0;                 // 1: the many-row (tiled) gate/up product also takes split activations
 };
 

@@ -35,23 +35,31 @@ def make_kv(sh: synth.ModelShape, n_pages: int, max_seqs: int, max_pages_per_seq
     return laser.KVCache(sh.n_layers, sh.n_heads, sh.head_dim, n_pages, max_seqs, max_pages_per_seq)
 
 
-def prefill(model, kv, seq_ids, prompts: np.ndarray, chunk: int = 16):
-    """Feed prompts[:, :-1] through laser_verify_step in chunks, forcing acceptance at commit.
-    Returns the pending tokens (last prompt token of each sequence) as a CUDA tensor."""
+def prefill(model, kv, seq_ids, prompts, chunk: int = 16):
+    """Feed every prompt but its last token through laser_verify_step in chunks, forcing acceptance at commit.
+    prompts: int[B][T], or a list of B arrays of different lengths (each chunk then runs the sequences that
+    still have tokens left, with ragged draft lengths). Returns the pending tokens (last prompt token of each
+    sequence) as a CUDA tensor."""
     import paper_2408_05676_amd as laser
-    B, T = prompts.shape
-    body = prompts[:, :-1]
+    prompts = [np.asarray(p) for p in prompts]
+    B = len(prompts)
     pos = 0
-    while pos < T - 1:
-        n = min(chunk, T - 1 - pos)
-        pend = torch.tensor(body[:, pos], dtype=torch.int32, device="cuda")
-        K = n - 1
-        dr = torch.tensor(body[:, pos + 1:pos + n].reshape(B, K), dtype=torch.int32, device="cuda")
-        dl = torch.full((B,), K, dtype=torch.int32, device="cuda")
-        laser.verify_step(model, kv, seq_ids, pend, dr, dl, 1, -1.0)
-        laser.kv_commit(kv, seq_ids, dl)          # accept_len := K -> all n rows become permanent
-        pos += n
-    return torch.tensor(prompts[:, -1], dtype=torch.int32, device="cuda")
+    while True:
+        act = [b for b in range(B) if pos < len(prompts[b]) - 1]
+        if not act:
+            break
+        n = [min(chunk, len(prompts[b]) - 1 - pos) for b in act]
+        K = max(n) - 1
+        dr = np.zeros((len(act), K), dtype=np.int32)
+        for i, b in enumerate(act):
+            dr[i, :n[i] - 1] = prompts[b][pos + 1:pos + n[i]]
+        pend = torch.tensor([int(prompts[b][pos]) for b in act], dtype=torch.int32, device="cuda")
+        dl = torch.tensor([v - 1 for v in n], dtype=torch.int32, device="cuda")
+        ids = [seq_ids[b] for b in act]
+        laser.verify_step(model, kv, ids, pend, torch.tensor(dr, device="cuda"), dl, 1, -1.0)
+        laser.kv_commit(kv, ids, dl)              # accept_len := rows - 1 -> all fed rows become permanent
+        pos += chunk
+    return torch.tensor([int(p[-1]) for p in prompts], dtype=torch.int32, device="cuda")
 
 
 def logits_close(g: np.ndarray, o: np.ndarray):

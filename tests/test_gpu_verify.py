@@ -33,24 +33,31 @@ def _oracle(sh):
     return _ORACLES[key]
 
 
-def _run_steps(sh, B, ctx_len, K, n_steps, k, p, mode=0, seed=1, ragged=False, fused=1, sample=None):
+def _run_steps(sh, B, ctx_len, K, n_steps, k, p, mode=0, seed=1, ragged=False, fused=1, sample=None, options=()):
     """Runs n_steps verify steps of B sequences on the GPU and compares with the oracle. `sample`: the
     sequences the oracle follows (default all); the GPU always runs the whole batch, so a sampled run
-    checks the full launch configuration at a cost the oracle can afford."""
+    checks the full launch configuration at a cost the oracle can afford. ctx_len: one context length, or
+    a list with one per sequence. options: (name, value) pairs for laser_model_set_option."""
     laser = _laser()
     dec = _oracle(sh)
     S = list(range(B)) if sample is None else list(sample)
-    cap = ctx_len + (K + 1) * (n_steps + 1) + 16
+    ctx_lens = [ctx_len] * B if np.isscalar(ctx_len) else [int(c) for c in ctx_len]
+    assert len(ctx_lens) == B
+    cap = max(ctx_lens) + (K + 1) * (n_steps + 1) + 16
     model = gu.make_model(sh, max_rows=B * max(K + 1, 16), max_batch=B, max_pos=cap + 16)
     model.set_option("fused", fused)
+    for name, value in options:
+        model.set_option(name, value)
     kv = gu.make_kv(sh, n_pages=B * (cap // 16 + 2), max_seqs=B + 3, max_pages_per_seq=cap // 16 + 2)
     seq_ids = [B + 2 - b for b in range(B)]                             # non-trivial slot numbers
-    prompts = synth.uniform_tokens(seed, 50, 0, B * ctx_len, sh.vocab).reshape(B, ctx_len)
+    flat = synth.uniform_tokens(seed, 50, 0, sum(ctx_lens), sh.vocab)
+    cuts = np.cumsum([0] + ctx_lens)
+    prompts = [flat[cuts[b]:cuts[b + 1]] for b in range(B)]
     for s in seq_ids:
         kv.reserve(s, cap)
     pend = gu.prefill(model, kv, seq_ids, prompts, chunk=16 if not ragged else 7)
     seqs = [step.Sequence(dec, 0, prompts[b], cap) for b in S]
-    assert kv.read_lens(seq_ids).tolist() == [ctx_len - 1] * B
+    assert kv.read_lens(seq_ids).tolist() == [c - 1 for c in ctx_lens]
     r = np.random.default_rng(seed)
     flips_total, worst = 0, 0.0
     for it in range(n_steps):
@@ -98,8 +105,8 @@ def _run_steps(sh, B, ctx_len, K, n_steps, k, p, mode=0, seed=1, ragged=False, f
         if sample is None:
             pend = torch.tensor([s.pending for s in seqs], dtype=torch.int32, device="cuda")
         assert kv.read_lens(seq_ids)[S].tolist() == [s.cache.length for s in seqs]
-    print(f"[{sh.name} B={B} K={K} k={k} p={p} mode={mode}] worst logit error {worst:.3f} of bound, "
-          f"in-tolerance flips {flips_total}")
+    print(f"[{sh.name} B={B} ctx={ctx_len if np.isscalar(ctx_len) else (min(ctx_lens), max(ctx_lens))} K={K} k={k} p={p} "
+          f"mode={mode} {dict(options)}] worst logit error {worst:.3f} of bound, in-tolerance flips {flips_total}")
     model.close(); kv.close()
     return flips_total
 
@@ -259,3 +266,30 @@ def test_persistent_kernel_edge_shapes(fused):
     _run_steps(sh, B=2, ctx_len=49, K=7, n_steps=3, k=2, p=0.05, seed=32, ragged=True, fused=fused)     # M = 16
     _run_steps(sh, B=1, ctx_len=2200, K=8, n_steps=2, k=2, p=0.05, seed=33, fused=fused)                # 9+ splits
     _run_steps(sh, B=3, ctx_len=17, K=4, n_steps=4, k=2, p=0.05, seed=34, fused=fused)                  # len = 16: page edge
+
+
+@pytest.mark.parametrize("waves", [4, 8])
+def test_unsplit_attention_long_contexts(waves):
+    """The general path's attention with the context walked UNSPLIT by one workgroup (what the 72-row and the
+    704-row workloads run: many pages per wave, the prefetch of the next page, a long online-softmax chain, and with
+    eight waves the hand-over of waves 4..7 to waves 0..3), forced on small batches by the options
+    attn_whole_min = 1 and attn_waves: contexts of about 300 and 640 tokens, ragged over the batch, one ending on
+    a page boundary (len = 304) and one whose new rows cross one."""
+    opts = (("attn_whole_min", 1), ("attn_waves", waves))
+    sh = synth.SHAPES["tiny128"].with_(lm_gain=4.0)                       # head_dim 128
+    _run_steps(sh, B=3, ctx_len=[305, 640, 171], K=5, n_steps=2, k=2, p=0.05, seed=51, fused=0, options=opts)
+    sh = synth.SHAPES["tiny"].with_(lm_gain=4.0)                          # head_dim 64, two query tiles (R = 21)
+    _run_steps(sh, B=2, ctx_len=[333, 590], K=20, n_steps=1, k=2, p=0.05, seed=52, fused=0, options=opts)
+    sh7 = synth.SHAPES["7b"].with_(n_layers=2)                            # 7B width, 18 rows
+    _run_steps(sh7, B=2, ctx_len=[640, 300], K=8, n_steps=1, k=2, p=0.0, seed=53, fused=0, options=opts)
+
+
+def test_7b_throughput_launch_shape_at_real_contexts_sampled():
+    """The throughput workload at its real launch configuration AND contexts: 7B width, B = 64, K = 10 (704 rows,
+    tiled GEMMs), contexts of 512..768 tokens mixed over the batch (unsplit attention, 32..48 pages per workgroup,
+    four waves), two layers; the oracle follows three sequences: one whose cache ends on a page boundary
+    (len = 512), one in the middle, the longest one."""
+    sh = synth.SHAPES["7b"].with_(n_layers=2)
+    lens = [512 + (b * 37) % 257 for b in range(64)]
+    lens[0], lens[29], lens[63] = 513, 651, 768
+    _run_steps(sh, B=64, ctx_len=lens, K=10, n_steps=1, k=2, p=0.0, seed=54, sample=[0, 29, 63], fused=0)

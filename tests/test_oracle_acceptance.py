@@ -194,3 +194,52 @@ def test_laser_step_uses_pool_and_matches_greedy_under_strict(tiny):
         steps += 1
     assert s.tokens[len(prompt):len(prompt) + 30] == ref
     assert steps <= 8                      # ~6 tokens per step when the pool holds the answer
+
+
+def test_laser_step_temporary_branch_is_the_last_w_tokens_of_the_own_text(tiny):
+    """Sec. 3.2: the current prompt and the text generated so far join the key's trie while the text is being
+    generated. laser_step(temporary_branch=W) must hand retrieval exactly the last W tokens the sequence holds
+    (prompt + everything emitted so far), per sequence. Pinned by (1) a hand-worked window, (2) an explicit trie
+    built independently over pool + own text at every step of a generation, (3) strict == greedy."""
+    from tests.test_oracle_retrieval import trie_retrieve
+    sh, dec = tiny
+    empty = RegroupedPool(np.zeros(0, dtype=np.int32), np.array([0]), np.zeros(0, dtype=np.int64))
+    # (1) own text 5 6 7 8 9 1 2 3 5 6: the suffix (5, 6) occurred at its start, followed by 7 8 9 1.
+    #     A window of 10 tokens sees that occurrence, a window of 4 tokens (2 3 5 6) does not.
+    prompt = [5, 6, 7, 8, 9, 1, 2, 3, 5, 6]
+    for W, want_drafts, want_idx in ((10, [7, 8, 9, 1], -2 - 1), (8, [], -1), (4, [], -1)):
+        s = step.Sequence(dec, 3, prompt, 64)
+        res = step.laser_step(dec, empty, [s], 1, 2, 4, 1, -1.0, temporary_branch=W)
+        assert res["drafts"][0, :res["draft_len"][0]].tolist() == want_drafts, W
+        assert int(res["pool_index"][0]) == want_idx and int(res["match_n"][0]) == (2 if want_drafts else 0)
+    # without the branch nothing is found at all
+    s = step.Sequence(dec, 3, prompt, 64)
+    assert int(step.laser_step(dec, empty, [s], 1, 2, 4, 1, -1.0)["draft_len"][0]) == 0
+    # (2) + (3): two sequences of different keys generate 20 tokens each; every step's drafts equal the greedy
+    # descent of an explicit trie over [pool sequences of the key] + [last W tokens of that sequence]
+    pool_seqs = [[9, 4, 4, 7, 1, 2], [4, 4, 8, 3], [1, 2, 3, 4, 4, 7]]
+    pool_keys = [1, 2, 1]
+    toks = np.array([t for q in pool_seqs for t in q], dtype=np.int32)
+    off = np.cumsum([0] + [len(q) for q in pool_seqs]).astype(np.int64)
+    pool = RegroupedPool(toks, off, np.array(pool_keys, dtype=np.int64))
+    prompts = {1: synth.uniform_tokens(21, 1, 0, 9, sh.vocab).tolist() + [4, 4], 2: [4, 4, 8, 4, 4]}
+    refs = {k: step.autoregressive_greedy(dec, step.Sequence(dec, k, pr, 96), 20) for k, pr in prompts.items()}
+    W, n_max, K = 7, 2, 3
+    seqs = [step.Sequence(dec, k, prompts[k], 96) for k in (1, 2)]
+    base = {1: 0, 2: sum(len(q) for q, k in zip(pool_seqs, pool_keys) if k == 1)}
+    n_pool = {k: sum(len(q) for q, kk in zip(pool_seqs, pool_keys) if kk == k) for k in (1, 2)}
+    for _ in range(12):
+        before = [list(s.tokens) for s in seqs]
+        res = step.laser_step(dec, pool, seqs, 1, n_max, K, 1, -1.0, temporary_branch=W)
+        for i, s in enumerate(seqs):
+            own = before[i][-W:]
+            of_key = [q for q, k in zip(pool_seqs, pool_keys) if k == s.key]
+            chain, n, idx = trie_retrieve(of_key + [own], base[s.key], before[i][-n_max:], 1, n_max, K)
+            assert res["drafts"][i, :res["draft_len"][i]].tolist() == chain
+            if chain:
+                # positions past the key's pool text lie in the own text and are reported as -2 - position
+                want = idx if idx - base[s.key] < n_pool[s.key] else -2 - (idx - base[s.key] - n_pool[s.key])
+                assert int(res["pool_index"][i]) == want and int(res["match_n"][i]) == n
+    for s in seqs:
+        n = min(20, len(s.tokens) - len(prompts[s.key]))
+        assert n >= 12 and s.tokens[len(prompts[s.key]):len(prompts[s.key]) + n] == refs[s.key][:n]
