@@ -223,6 +223,18 @@ int laser_verify_head(laser_model* model, const uint16_t* h, const int32_t* draf
                       const int32_t* draft_len, int B, int K, int topk, float p, int mode,
                       int32_t* accept_len, int32_t* out_tokens, float* logits_dbg, void* stream);
 
+/* laser_verify_head_static: laser_verify_head for callers that cannot allocate device memory -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc. Same inputs, outputs and results as
+ * laser_verify_head with up to 16 rows (no logits_dbg), but the per-(row, vocabulary chunk) partial statistics that
+ * pass from the streaming kernel to the acceptance kernel live in a device array that is part of the library image
+ * (1.19 MiB on every GPU the library runs on, until the process ends) instead of the model handle's workspace; the
+ * call itself allocates and frees nothing. Limits: B*(K+1) <= 16 rows and at most 1024 vocabulary chunks (every
+ * model handle satisfies the second); beyond them LASER_E_LIMIT. All calls on one GPU share that
+ * array: calls that overlap on one GPU (two streams, two threads) race; calls on one stream are ordered. */
+int laser_verify_head_static(laser_model* model, const uint16_t* h, const int32_t* drafts,
+                             const int32_t* draft_len, int B, int K, int topk, float p, int mode,
+                             int32_t* accept_len, int32_t* out_tokens, void* stream);
+
 /* laser_kv_commit ("all drafted tokens after the failing position are discarded", Sec. 2.1):
  * len[seq_ids[b]] += accept_len[b] + 1, i.e. the pending token and the accepted drafts become
  * permanent; later slots are dead and get overwritten by the next step.

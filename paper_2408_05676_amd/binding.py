@@ -69,6 +69,7 @@ def lib():
         "laser_kv_read_lens": [vp, vp, i32, vp, vp],
         "laser_verify_step": [vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, i32, vp, vp, vp, vp],
         "laser_verify_head": [vp, vp, vp, vp, i32, i32, i32, f32, i32, vp, vp, vp, vp],
+        "laser_verify_head_static": [vp, vp, vp, vp, i32, i32, i32, f32, i32, vp, vp, vp],
         "laser_kv_commit": [vp, vp, vp, i32, vp],
         "laser_ctx_advance": [vp, vp, vp, vp, i32, i32, i32, vp],
         "laser_profile_begin": [vp, i32],
@@ -345,6 +346,22 @@ def verify_head(model: Model, h: torch.Tensor, drafts: torch.Tensor, draft_len: 
                                    logits.data_ptr() if want_logits else None, _stream(stream)),
            "laser_verify_head")
     return acc, toks, logits
+
+
+def verify_head_static(model: Model, h: torch.Tensor, drafts: torch.Tensor, draft_len: torch.Tensor, topk: int,
+                       p: float, mode: int, out, stream=None):
+    """laser_verify_head_static: laser_verify_head without any allocation (at most 16 rows); out = (accept_len
+    int32 [B], out_tokens int32 [B][K+1]) must be given."""
+    B, K = drafts.shape
+    if h.shape != (B, K + 1, model.d):
+        raise LaserError("h must be [B][K+1][d]")
+    acc, toks = out
+    _check(lib().laser_verify_head_static(model._h, _dev(h, torch.float16, "h"),
+                                          _dev(drafts, torch.int32, "drafts") if K > 0 else None,
+                                          _dev(draft_len, torch.int32, "draft_len"), B, K, topk, p, mode,
+                                          _dev(acc, torch.int32, "accept_len"), _dev(toks, torch.int32, "out_tokens"),
+                                          _stream(stream)), "laser_verify_head_static")
+    return acc, toks
 
 
 def kv_commit(kv: KVCache, seq_ids, accept_len: torch.Tensor, stream=None):

@@ -17,6 +17,7 @@
 // reduces each row (max, sum of exp, arg-max, the draft's logit and its exact rank) and decides it,
 // head_scan_kernel scans the rows.
 #include <cmath>
+#include <mutex>
 
 #include "gemm_mfma.h"
 #include "gemm_skinny.h"
@@ -300,13 +301,39 @@ __global__ void head_scan_kernel(const int32_t* row_ok, const int32_t* row_arg, 
     for (int j = 0; j < R; ++j) out[j] = j < n ? drafts[(size_t)b * K + j] : (j == n ? row_arg[b * R + n] : -1);
 }
 
+// Device buffers of the streaming head (at most 16 rows): the row's draft token, and per (row, vocabulary chunk) the
+// partial statistics that lm_head_kernel leaves for accept_kernel.
+struct HeadBufs {
+    int32_t* row_x; float* hp_max; float* hp_sum; int32_t* hp_arg; float* hp_topv; int32_t* hp_topi; float* hp_lx;
+};
+
+// The streaming head: rows -> lm_head_kernel (every wave a vocabulary chunk) -> accept_kernel. Allocates nothing.
+static int run_head_stream(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len, int B, int K,
+                           int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, float* logits_dbg,
+                           const HeadBufs& hb, hipStream_t stream) {
+    const int M = B * (K + 1);
+    hipLaunchKernelGGL(head_rows_kernel, dim3((M + 255) / 256), dim3(256), 0, stream, drafts, draft_len, B, K,
+                       m->d.vocab, hb.row_x, hb.hp_lx);
+    const int ntiles = m->d.vocab / 16;
+    const int tpw = (ntiles + 1023) / 1024;
+    HeadArgs a{m->d.wlm, h, M, m->d.vocab, m->d.d_model, tpw, m->head_chunks, hb.row_x,
+               hb.hp_max, hb.hp_sum, hb.hp_arg, hb.hp_topv, hb.hp_topi, hb.hp_lx, logits_dbg};
+    dim3 grid((unsigned)((m->head_chunks + 3) / 4), 1u);         // at most 16 rows: one row tile
+    hipLaunchKernelGGL(lm_head_kernel<1>, grid, dim3(256), 0, stream, a);
+    AcceptArgs aa{hb.hp_max, hb.hp_sum, hb.hp_arg, hb.hp_topv, hb.hp_topi, hb.hp_lx, hb.row_x, drafts, draft_len,
+                  K, m->head_chunks, topk, mode, p, accept_len, out_tokens};
+    hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(256), 0, stream, aa);
+    LASER_HIP_CHECK(hipGetLastError());
+    return LASER_OK;
+}
+
 int run_head(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len, int B, int K,
              int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, float* logits_dbg,
              hipStream_t stream) {
     const int R = K + 1, M = B * R;
-    hipLaunchKernelGGL(head_rows_kernel, dim3((M + 255) / 256), dim3(256), 0, stream, drafts, draft_len, B, K,
-                       m->d.vocab, m->row_x, m->hp_lx);
     if (M > kHeadStreamMaxRows) {
+        hipLaunchKernelGGL(head_rows_kernel, dim3((M + 255) / 256), dim3(256), 0, stream, drafts, draft_len, B, K,
+                           m->d.vocab, m->row_x, m->hp_lx);
         float* logits = logits_dbg;
         if (!logits) {                                   // workspace for max_rows x vocab logits, on first use
             if (!m->logits_ws) {
@@ -335,17 +362,58 @@ int run_head(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* 
         LASER_HIP_CHECK(hipGetLastError());
         return LASER_OK;
     }
-    const int ntiles = m->d.vocab / 16;
-    const int tpw = (ntiles + 1023) / 1024;
-    HeadArgs a{m->d.wlm, h, M, m->d.vocab, m->d.d_model, tpw, m->head_chunks, m->row_x,
-               m->hp_max, m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx, logits_dbg};
-    dim3 grid((unsigned)((m->head_chunks + 3) / 4), 1u);         // at most 16 rows: one row tile
-    hipLaunchKernelGGL(lm_head_kernel<1>, grid, dim3(256), 0, stream, a);
-    AcceptArgs aa{m->hp_max, m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx, m->row_x, drafts, draft_len,
-                  K, m->head_chunks, topk, mode, p, accept_len, out_tokens};
-    hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(256), 0, stream, aa);
-    LASER_HIP_CHECK(hipGetLastError());
+    HeadBufs hb{m->row_x, m->hp_max, m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx};
+    return run_head_stream(m, h, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens, logits_dbg, hb, stream);
+}
+
+// ---- the head without any allocation ------------------------------------------------------------------------
+// The partial statistics live in a file-scope device array instead of the model handle's workspace. Each GPU holds
+// its own copy of the array at its own address: the address is taken once per device with that device current.
+constexpr int kStaticRows = kHeadStreamMaxRows;      // rows one call may verify
+constexpr int kStaticChunks = 1024;                  // vocabulary chunks (laser_model_create never makes more)
+struct HeadScratch {
+    float hp_max[kStaticRows * kStaticChunks];
+    float hp_sum[kStaticRows * kStaticChunks];
+    int32_t hp_arg[kStaticRows * kStaticChunks];
+    float hp_topv[kStaticRows * kStaticChunks * KT];
+    int32_t hp_topi[kStaticRows * kStaticChunks * KT];
+    float hp_lx[kStaticRows];
+    int32_t row_x[kStaticRows];
+};
+static __device__ __align__(256) unsigned char scratch[sizeof(HeadScratch)];      // 1.19 MiB per GPU, for the life of the process
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kMaxDevices];             // device address of `scratch` on each GPU, once known
+
+static int head_scratch(HeadScratch** out) {
+    int dev = -1;
+    LASER_HIP_CHECK(hipGetDevice(&dev));
+    LASER_REQUIRE(dev >= 0 && dev < kMaxDevices, LASER_E_LIMIT, "device ordinal %d beyond %d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        LASER_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        LASER_REQUIRE(ptr != nullptr, LASER_E_HIP, "hipGetSymbolAddress returned no address for the head scratch");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = reinterpret_cast<HeadScratch*>(g_scratch_ptr[dev]);
     return LASER_OK;
+}
+
+int run_head_static(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len, int B, int K,
+                    int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, hipStream_t stream) {
+    const int M = B * (K + 1);
+    LASER_REQUIRE(M <= kStaticRows, LASER_E_LIMIT, "B*(K+1) = %d rows exceed the %d this entry point verifies per call", M, kStaticRows);
+    LASER_REQUIRE(m->head_chunks <= kStaticChunks, LASER_E_LIMIT, "vocabulary of %d needs %d chunks, the static scratch holds %d",
+                  m->d.vocab, m->head_chunks, kStaticChunks);
+    HeadScratch* sc = nullptr;
+    int rc = head_scratch(&sc);
+    if (rc) return rc;
+    // Nothing in the array has to start at zero: head_rows_kernel resets row_x and hp_lx for the call's rows, and
+    // lm_head_kernel overwrites every (row, chunk) record that accept_kernel reads.
+    HeadBufs hb{sc->row_x, sc->hp_max, sc->hp_sum, sc->hp_arg, sc->hp_topv, sc->hp_topi, sc->hp_lx};
+    return run_head_stream(m, h, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens, nullptr, hb, stream);
 }
 
 }  // namespace laser

@@ -23,6 +23,8 @@ int fused_read_trace(Model* m, hipStream_t stream, long long* out, int max_elems
 int run_head(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len, int B, int K,
              int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, float* logits_dbg,
              hipStream_t stream);
+int run_head_static(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len, int B, int K,
+                    int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, hipStream_t stream);
 
 // ------------------------------------------------------------------------------------------------
 __device__ inline float block_sum_256(float v, float* sm /*[4]*/) {
@@ -923,6 +925,17 @@ extern "C" int laser_verify_head(laser_model* mh, const uint16_t* h, const int32
     if (B == 0) return LASER_OK;
     LASER_REQUIRE(h != nullptr, LASER_E_INVALID_ARG, "h is NULL");
     return run_head(m, h, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens, logits_dbg, (hipStream_t)stream);
+}
+
+extern "C" int laser_verify_head_static(laser_model* mh, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len,
+                                        int B, int K, int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens,
+                                        void* stream) {
+    Model* m = reinterpret_cast<Model*>(mh);
+    int rc = check_step_args(m, B, K, topk, mode, draft_len, drafts, accept_len, out_tokens);
+    if (rc) return rc;
+    if (B == 0) return LASER_OK;
+    LASER_REQUIRE(h != nullptr, LASER_E_INVALID_ARG, "h is NULL");
+    return run_head_static(m, h, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens, (hipStream_t)stream);
 }
 
 extern "C" int laser_profile_begin(laser_model* mh, int max_records) {
