@@ -17,6 +17,13 @@ Greedy verification (Eq. 4) is mode 0 with k = 1 and p < 0.
 Rows are examined from the first; the scan stops at the first rejected draft or after
 draft_len drafts.  With a accepted drafts the step emits x~_1..x~_a followed by
 argmax q_{a+1} (the correction when a draft failed, the bonus token when all passed).
+
+Token trees (Sec. 3.4: "if a predecessor node in the token tree is rejected, all of its successor nodes will be
+skipped ... ultimately accepting the verified branch with the maximum length"): node i with token x_i and parent
+node parent[i] (-1: child of the root) is examined against the distribution of its parent's row (row parent[i] + 1;
+row 0 belongs to the pending token).  It is verified iff its parent is (the root always is) and x_i passes the rule.
+The accepted branch is the deepest verified node's path; among equally deep ones the first in the pseudo-sequence.
+The step emits that path's tokens followed by the argmax of its last node's row.
 """
 from __future__ import annotations
 
@@ -93,3 +100,35 @@ def verify_batch(logits: np.ndarray, drafts: np.ndarray, draft_len, k: int, p: f
         all_stats.append(st)
         gaps[b] = gap
     return acc, out, all_stats, gaps
+
+
+def verify_tree(logits: np.ndarray, tokens, parent, n_nodes: int, k: int, p: float, mode: int = 0):
+    """logits [R][V] (R >= n_nodes + 1); tokens[i], parent[i] for the nodes of the pseudo-sequence.
+    Returns (path: accepted node indices root-side first, emitted tokens (path tokens + one more), per-node stats
+    of the examined nodes {node: stats}, top-1/top-2 gap of the emitting row)."""
+    verified, depth, stats = {}, {}, {}
+    best, best_depth = -1, 0
+    for i in range(int(n_nodes)):
+        par = int(parent[i])
+        assert -1 <= par < i
+        if par >= 0 and not verified[par]:
+            verified[i] = False                   # skipped: a predecessor was rejected
+            continue
+        st = row_stats(logits[par + 1], int(tokens[i]), k, p)
+        st["accepted"] = accepts(st["rank"], st["q"], k, p, mode)
+        stats[i] = st
+        verified[i] = st["accepted"]
+        if verified[i]:
+            depth[i] = (depth[par] if par >= 0 else 0) + 1
+            if depth[i] > best_depth:
+                best, best_depth = i, depth[i]
+    path = []
+    i = best
+    while i >= 0:
+        path.append(i)
+        i = int(parent[i])
+    path.reverse()
+    l = np.asarray(logits[best + 1], dtype=np.float64)
+    srt = np.partition(l, l.size - 2)[l.size - 2:]
+    out = [int(tokens[i]) for i in path] + [int(np.argmax(l))]
+    return path, out, stats, float(srt[1] - srt[0])

@@ -14,6 +14,12 @@ Rows r = 0..R-1 of one sequence hold the tokens [pending, draft_1 .. draft_{R-1}
 positions len+r; row r's output is the distribution of the token after it (q_{r+1}).  Keys
 and values of all R rows are written behind the cache speculatively; `commit` keeps the
 pending token plus the accepted drafts.
+
+Token trees (Sec. 3.3, tree attention): the rows after the first may form a tree instead of a chain. parent_row[r]
+(r >= 1) names the row whose token precedes row r's token (0 = the pending token); the pseudo-sequence lists parents
+before children.  Row r then sits at position len + depth(r) and sees the committed cache, its ancestors and itself --
+never a row of another branch.  Keys and values still go to slots len + r in row order; `compact` moves the
+rows of an accepted branch to the slots right behind the pending token before they are committed.
 """
 from __future__ import annotations
 
@@ -51,6 +57,15 @@ class KVCache:
     def commit(self, n_tokens: int) -> None:
         self.length += n_tokens
 
+    def compact(self, rows) -> None:
+        """rows: the row numbers (1-based behind the pending token's row 0, ascending) of an accepted branch.
+        Their keys/values move from slots length + row to slots length + 1, length + 2, ..."""
+        t0 = self.length
+        for j, r in enumerate(rows):
+            assert r >= j + 1
+            self.k[:, t0 + 1 + j] = self.k[:, t0 + r]
+            self.v[:, t0 + 1 + j] = self.v[:, t0 + r]
+
 
 class Decoder:
     def __init__(self, n_layers, d, n_heads, ffn, vocab, weights, eps=1e-6, rope_base=10000.0,
@@ -68,12 +83,22 @@ class Decoder:
     def new_cache(self, capacity: int) -> KVCache:
         return KVCache(self.L, self.H, self.dh, capacity, self.dt)
 
-    def hidden(self, cache: KVCache, tokens) -> np.ndarray:
-        """Final-normed hidden states [R][d] for rows `tokens` placed after the committed cache."""
+    def hidden(self, cache: KVCache, tokens, parent_row=None) -> np.ndarray:
+        """Final-normed hidden states [R][d] for rows `tokens` placed after the committed cache.
+        parent_row: None for a chain (row r follows row r - 1), else parent_row[r] < r for r >= 1 (entry 0 unused)."""
         tokens = np.asarray(tokens, dtype=np.int64)
         R, H, dh, d = tokens.size, self.H, self.dh, self.d
         t0 = cache.length
-        pos = np.arange(t0, t0 + R)
+        if parent_row is None:
+            parent_row = [-1] + list(range(R - 1))
+        depth = np.zeros(R, dtype=np.int64)
+        sees = [[0]] * R                        # rows of this pass a row attends to: its ancestors and itself
+        for r in range(1, R):
+            pr = int(parent_row[r])
+            assert 0 <= pr < r
+            depth[r] = depth[pr] + 1
+            sees[r] = sees[pr] + [r]
+        pos = t0 + depth
         x = self._w("emb")[tokens].copy()                                   # [R][d]
         for l in range(self.L):
             n1 = rmsnorm(x, self._w("g1", l), self.eps)
@@ -84,9 +109,10 @@ class Decoder:
             cache.k[l, t0:t0 + R] = k
             cache.v[l, t0:t0 + R] = v
             att = np.empty((R, H, dh), dtype=self.dt)
-            for r in range(R):                                               # row r sees slots 0 .. t0+r
-                kk = cache.k[l, :t0 + r + 1]                                 # [T][H][dh]
-                vv = cache.v[l, :t0 + r + 1]
+            for r in range(R):                                               # row r sees slots 0 .. t0-1 and its branch
+                mine = [t0 + j for j in sees[r]]
+                kk = np.concatenate([cache.k[l, :t0], cache.k[l, mine]])     # [T][H][dh]
+                vv = np.concatenate([cache.v[l, :t0], cache.v[l, mine]])
                 s = np.einsum("hd,thd->ht", q[r], kk) / np.sqrt(dh)          # [H][T]
                 s = s - s.max(axis=1, keepdims=True)
                 p = np.exp(s)
@@ -101,6 +127,7 @@ class Decoder:
     def head(self, h: np.ndarray) -> np.ndarray:
         return h @ self._w("wlm").T
 
-    def verify_forward(self, cache: KVCache, tokens) -> np.ndarray:
-        """logits [R][V]; row r is the unnormalised log-distribution q_{r+1} of Eq. 3 / Eq. 6."""
-        return self.head(self.hidden(cache, tokens))
+    def verify_forward(self, cache: KVCache, tokens, parent_row=None) -> np.ndarray:
+        """logits [R][V]; row r is the unnormalised log-distribution of the token that follows row r's token
+        (q_{r+1} of Eq. 3 / Eq. 6 for a chain)."""
+        return self.head(self.hidden(cache, tokens, parent_row))

@@ -30,6 +30,18 @@ as ONE MORE SEQUENCE of the key's sub-pool, placed after all of the key's pool s
 rules above are unchanged (its last position, which the context suffix itself ends at, has no
 successor and is therefore never an occurrence). A result whose smallest surviving position
 lies in the own text is reported as pool_index = -2 - (position in the own text).
+
+Tree drafts (Sec. 3.3, "tree-based drafting"): instead of one chain, the sub-tree of the trie below the node
+the suffix reaches is retrieved, cut to at most K nodes. A node is a path of successor tokens; its frequency is
+the number of occurrences whose continuation starts with that path. "If the number of retrieved tokens exceeds
+K, the tokens with the highest frequency are selected": nodes are taken one at a time, always the best node not
+yet taken whose parent is taken (the root's children at the start), best = higher frequency, then smaller
+depth, then the parent that was taken earlier, then the smaller token id. (A child never has a higher frequency
+than its parent, so this yields the K best nodes of the whole sub-tree in that order, and the result is a tree.)
+The pseudo-sequence lists the nodes depth-first, the children of a node in the order they were taken (higher
+frequency first, smaller token id on ties); parent[i] is the pseudo-sequence index of node i's parent, -1 for
+children of the root. n is chosen as for chains: the first n (from n_max down) whose tree has >= min_tokens
+nodes, else the largest tree seen (ties -> larger n).
 """
 from __future__ import annotations
 
@@ -88,6 +100,90 @@ def _greedy_chain(pool: RegroupedPool, M: np.ndarray, K: int):
         chain.append(int(tok))
         M = alive[succ == tok]
     return chain, M
+
+
+def _best_first_tree(pool: RegroupedPool, M0: np.ndarray, K: int):
+    """Nodes of the continuation trie below the occurrences M0, taken best first (see the module text).
+    Returns the taken nodes in the order taken: (token, index of the parent among the taken nodes or -1, depth, frequency)."""
+    taken, frontier = [], []          # frontier entries: (-frequency, depth, parent index, token, occurrences)
+
+    def grow(parent_idx: int, occ: np.ndarray, depth: int):
+        """children of a taken node (or of the root): successors at offset depth + 1 of its occurrences"""
+        alive = occ[occ + depth + 1 < pool.seq_end[occ]]
+        if alive.size == 0:
+            return
+        succ = pool.P[alive + depth + 1]
+        for tok in np.unique(succ):
+            sel = alive[succ == tok]
+            frontier.append((-int(sel.size), depth + 1, parent_idx, int(tok), sel))
+
+    grow(-1, M0, 0)
+    while frontier and len(taken) < K:
+        j = min(range(len(frontier)), key=lambda i: frontier[i][:4])
+        negf, depth, parent_idx, tok, occ = frontier.pop(j)
+        taken.append((tok, parent_idx, depth, -negf))
+        grow(len(taken) - 1, occ, depth)
+    return taken
+
+
+def _depth_first(taken):
+    """Pseudo-sequence of the taken nodes: depth-first, siblings in the order they were taken.
+    Returns (tokens, parents as pseudo-sequence indices (-1 = root), frequencies)."""
+    kids = {}
+    for i, (_, parent_idx, _, _) in enumerate(taken):
+        kids.setdefault(parent_idx, []).append(i)              # ascending i = order taken
+    tokens, parents, freqs = [], [], []
+
+    def visit(i: int, parent_pos: int):
+        pos = len(tokens)
+        tokens.append(taken[i][0]); parents.append(parent_pos); freqs.append(taken[i][3])
+        for c in kids.get(i, []):
+            visit(c, pos)
+
+    for c in kids.get(-1, []):
+        visit(c, -1)
+    return tokens, parents, freqs
+
+
+def retrieve_tree_one(pool: RegroupedPool, key: int, ctx_tail, n_min: int, n_max: int, K: int, min_tokens: int = 1):
+    """Tree form of retrieve_one.  Returns (tokens list, parents list, frequencies list, match_n)."""
+    ctx = np.asarray(ctx_tail, dtype=np.int64)
+    valid = 0
+    while valid < ctx.size and ctx[ctx.size - 1 - valid] >= 0:
+        valid += 1
+    min_tokens = max(1, min_tokens)
+    rng_ = pool.key_range.get(int(key))
+    if rng_ is None or K <= 0:
+        return [], [], [], 0
+    lo, hi = rng_
+    best = ([], [], [], 0)
+    for n in range(min(n_max, valid), max(n_min, 1) - 1, -1):
+        M0 = _occurrences(pool, lo, hi, ctx[ctx.size - n:])
+        if M0.size == 0:
+            continue
+        tokens, parents, freqs = _depth_first(_best_first_tree(pool, M0, K))
+        cand = (tokens, parents, freqs, n)
+        if len(tokens) >= min_tokens:
+            return cand
+        if len(tokens) > len(best[0]):
+            best = cand
+    return best
+
+
+def retrieve_tree(pool: RegroupedPool, keys, ctx_tails, n_min: int, n_max: int, K: int, min_tokens: int = 1):
+    """Batched form.  Returns tokens int32[B][K] (-1 padded), parents int32[B][K] (-1 padded and for children of
+    the root), n_nodes int32[B], match_n int32[B]."""
+    B = len(keys)
+    tokens = np.full((B, K), -1, dtype=np.int32)
+    parents = np.full((B, K), -1, dtype=np.int32)
+    nn = np.zeros(B, dtype=np.int32)
+    mn = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        t, par, _, n = retrieve_tree_one(pool, keys[b], ctx_tails[b], n_min, n_max, K, min_tokens)
+        tokens[b, :len(t)] = t
+        parents[b, :len(t)] = par
+        nn[b], mn[b] = len(t), n
+    return tokens, parents, nn, mn
 
 
 class _SubPoolWithOwnText:

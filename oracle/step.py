@@ -78,3 +78,48 @@ def laser_step(dec: Decoder, pool: retrieval.RegroupedPool, seqs, n_min: int, n_
     res = verify_step(dec, seqs, drafts, dl, k, p, mode, return_logits)
     res.update({"drafts": drafts, "draft_len": dl, "match_n": mn, "pool_index": pi})
     return res
+
+
+def verify_tree_step(dec: Decoder, seqs, tokens, parents, n_nodes, k: int, p: float, mode: int = 0,
+                     return_logits: bool = False):
+    """Verify a token tree per sequence in one forward (tree attention), accept the longest verified branch, move
+    its keys/values behind the pending token and commit them.  tokens, parents int[B][K] (pseudo-sequence order,
+    parents = node index or -1; entries past n_nodes[b] are padding: fed as token 0 hanging off the previous row)."""
+    tokens, parents = np.asarray(tokens), np.asarray(parents)
+    B, K = tokens.shape
+    logits = np.empty((B, K + 1, dec.V), dtype=np.float64)
+    acc = np.zeros(B, dtype=np.int32)
+    out = np.full((B, K + 1), -1, dtype=np.int32)
+    paths = np.full((B, K), -1, dtype=np.int32)
+    all_stats, gaps = [], np.zeros(B)
+    for b, s in enumerate(seqs):
+        nn = int(n_nodes[b])
+        row_tokens = [s.pending] + [int(tokens[b, j]) if j < nn else 0 for j in range(K)]
+        parent_row = [-1] + [int(parents[b, j]) + 1 if j < nn else j for j in range(K)]
+        logits[b] = dec.verify_forward(s.cache, row_tokens, parent_row)
+        path, toks, st, gap = acceptance.verify_tree(logits[b], tokens[b], parents[b], nn, k, p, mode)
+        s.cache.compact([i + 1 for i in path])
+        s.cache.commit(len(path) + 1)
+        s.tokens.extend(toks)
+        acc[b] = len(path)
+        out[b, :len(toks)] = toks
+        paths[b, :len(path)] = path
+        all_stats.append(st)
+        gaps[b] = gap
+    res = {"accept_len": acc, "out_tokens": out, "accept_path": paths, "stats": all_stats, "argmax_gap": gaps}
+    if return_logits:
+        res["logits"] = logits
+    return res
+
+
+def laser_tree_step(dec: Decoder, pool: retrieval.RegroupedPool, seqs, n_min: int, n_max: int, K: int,
+                    k: int, p: float, mode: int = 0, min_tokens: int = 1, return_logits: bool = False):
+    """retrieve a token tree -> verify with tree attention -> accept the longest verified branch -> commit."""
+    tails = []
+    for s in seqs:
+        t = s.tokens[-n_max:]
+        tails.append([-1] * (n_max - len(t)) + t)
+    tokens, parents, nn, mn = retrieval.retrieve_tree(pool, [s.key for s in seqs], tails, n_min, n_max, K, min_tokens)
+    res = verify_tree_step(dec, seqs, tokens, parents, nn, k, p, mode, return_logits)
+    res.update({"tree_tokens": tokens, "tree_parent": parents, "tree_len": nn, "match_n": mn})
+    return res
