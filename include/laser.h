@@ -40,6 +40,7 @@ extern "C" {
 #define LASER_MAX_NGRAM   8      /* longest context suffix that can be indexed (n_max)            */
 #define LASER_MAX_DRAFT   63     /* largest K (drafts per sequence per step); R = K+1 <= 64 rows    */
 #define LASER_MAX_TOPK    8      /* largest k of the top-k condition                                */
+#define LASER_MAX_TREE    32     /* largest K of laser_retrieve_tree (nodes of one retrieved token tree)           */
 #define LASER_MAX_OWN_TEXT 4096  /* tokens of a sequence's own text a temporary-branch lookup takes */
 
 /* acceptance rule selector (Sec. 3.4). rank = number of vocabulary entries ordered before the draft
@@ -120,6 +121,26 @@ int laser_retrieve_drafts_temp(const laser_pool* pool, const int64_t* keys, cons
                                int32_t* drafts, int32_t* draft_len, int32_t* match_n,
                                int64_t* pool_index, void* stream);
 
+/* laser_retrieve_tree (Sec. 3.3, tree-based drafting): like laser_retrieve_drafts, but instead of one chain the
+ * sub-tree of the key's trie below the node the suffix reaches is returned, cut to its K most frequent nodes ("if the
+ * number of retrieved tokens exceeds K, the tokens with the highest frequency are selected"). A node is a path of
+ * successor tokens; its frequency is the number of occurrences of the suffix that continue with that path. Nodes are
+ * taken best first among those whose parent is taken: higher frequency, then smaller depth, then the parent taken
+ * earlier, then the smaller token id. The pseudo-sequence lists the taken nodes depth-first, the children of a node
+ * in the order taken (higher frequency first).
+ *   tree_tokens [dev] int32[B][K]  out: token of node i, -1 padded
+ *   tree_parent [dev] int32[B][K]  out: pseudo-sequence index of node i's parent (< i), -1 for a child of the root
+ *                                       (it follows the pending token) and for padding
+ *   tree_freq   [dev] int32[B][K]  out, may be NULL: frequency of node i
+ *   tree_len    [dev] int32[B]     out: nodes 0..K
+ *   match_n     [dev] int32[B]     out: suffix length used (the first n from n_max down whose tree has >= min_tokens
+ *                                       nodes, else the n of the largest tree seen), 0 if nothing was found
+ * 0 <= K <= LASER_MAX_TREE; other arguments and limits as for laser_retrieve_drafts. */
+int laser_retrieve_tree(const laser_pool* pool, const int64_t* keys, const int32_t* ctx_tail,
+                        int B, int n_min, int n_max, int K, int min_tokens,
+                        int32_t* tree_tokens, int32_t* tree_parent, int32_t* tree_freq,
+                        int32_t* tree_len, int32_t* match_n, void* stream);
+
 /* Device-side bookkeeping for the own text: appends the tokens a step emitted,
  * out_tokens[b][0..accept_len[b]] (as written by laser_verify_step), to row b; a row that would overflow drops
  * its oldest tokens first (sliding window of own_cap tokens). own_tokens / own_len [dev] in/out. */
@@ -153,10 +174,12 @@ typedef struct laser_model_desc {
 
 /* Supported: head_dim 64 or 128; d_model, ffn multiples of 128; vocab multiple of 16 (else
  * LASER_E_SHAPE). Allocates workspace and the RoPE table; synchronises `stream`. n_layers may be 0
- * (head-only use). Two further allocations happen lazily, inside the first verify step that needs them:
- * with more than 16 rows a workspace for reduction-split partial results (max_rows * d_model * 32 bytes),
- * with more than 80 rows an fp16 copy of the four projection matrices (2 bytes per parameter) for the tiled
- * many-row kernels. */
+ * (head-only use). Further allocations happen lazily, inside the first call that needs them:
+ * with more than 16 rows a workspace for reduction-split partial results (max_rows * d_model * 32 bytes);
+ * with more than 80 rows fp16 copies of the four projection matrices and of the head matrix (2 bytes per parameter:
+ * the weight memory doubles) for the tiled many-row kernels. That call synchronises the stream; it fails with
+ * LASER_E_HIP if the memory is not there and with LASER_E_LIMIT if a weight exceeds the fp16 range (|w| > 65280).
+ * Option "f16_copies" = 0 makes no copies: the tiled kernels then widen the bf16 weights on the fly (slower). */
 int laser_model_create(const laser_model_desc* desc, void* stream, laser_model** out);
 int laser_model_destroy(laser_model* model);
 
@@ -195,10 +218,9 @@ int laser_kv_read_lens(laser_kv* kv, const int32_t* seq_ids /*[host] B*/, int B,
 /* laser_verify_step (Eq. 3 / Eq. 6 forward, Eq. 4 / 7 / 8 acceptance, correction rule of Sec. 2.1).
  * For sequence b, rows r = 0..K hold the tokens [pending[b], drafts[b][0..K-1]] at positions
  * len+r; their keys/values go to cache slots len..len+K; row r attends to slots 0..len+r. The
- * output head and the acceptance rule are fused: with up to 16 rows (B*(K+1)) logits are never
- * stored unless logits_dbg is given; with more rows they pass once through an fp32 workspace of
- * max_rows * vocab floats that the model handle allocates at the first such call (that call
- * synchronises; LASER_E_HIP if the allocation fails). With B*(K+1) <= 16 the whole step is one
+ * output head and the acceptance rule are fused for every row count: logits are reduced to per-(row, vocabulary
+ * chunk) partial statistics by the kernel that produces them and are never stored unless logits_dbg is given.
+ * With B*(K+1) <= 16 the whole step is one
  * persistent cooperative kernel (see laser_model_set_option). Drafts j >= draft_len[b] are padding
  * (fed as token 0, never accepted).
  *   seq_ids    [host] int32[B]      KV slots, all different
@@ -217,6 +239,26 @@ int laser_verify_step(laser_model* model, laser_kv* kv, const int32_t* seq_ids,
                       const int32_t* pending, const int32_t* drafts, const int32_t* draft_len,
                       int B, int K, int topk, float p, int mode,
                       int32_t* accept_len, int32_t* out_tokens, float* logits_dbg, void* stream);
+
+/* laser_verify_tree (Sec. 3.3 tree attention, Sec. 3.4 "accepting the verified branch with the maximum length"):
+ * laser_verify_step for a token tree. Rows r = 1..K hold the nodes of the pseudo-sequence in order (row 0 the pending
+ * token); node i sits at position len + depth(i), its key/value go to cache slot len + 1 + i, and it attends to the
+ * committed cache, the pending token, its ancestors and itself -- never to a node of another branch. Node i is verified
+ * iff its parent is (children of the root: always) and its token passes the acceptance rule against the distribution
+ * of its parent's row; the accepted branch ends at the deepest verified node (the first in the pseudo-sequence among
+ * equally deep ones).
+ *   tree_tokens, tree_parent, tree_len  [dev] as written by laser_retrieve_tree (an entry of tree_parent that does
+ *                not name an earlier node counts as -1; nodes past tree_len[b] are padding)
+ *   accept_len  [dev] int32[B]      out: a = nodes on the accepted branch
+ *   out_tokens  [dev] int32[B][K+1] out: the branch's tokens, then argmax of its last node's row (of row 0 if a = 0), then -1
+ *   accept_path [dev] int32[B][K]   out: pseudo-sequence indices of the branch's nodes, root side first, then -1
+ * A tree whose parent[i] = i - 1 is a chain and gives the results of laser_verify_step on its general path bit for
+ * bit. Always runs the general (multi-kernel) path. Follow with laser_kv_commit_tree. */
+int laser_verify_tree(laser_model* model, laser_kv* kv, const int32_t* seq_ids,
+                      const int32_t* pending, const int32_t* tree_tokens, const int32_t* tree_parent,
+                      const int32_t* tree_len, int B, int K, int topk, float p, int mode,
+                      int32_t* accept_len, int32_t* out_tokens, int32_t* accept_path,
+                      float* logits_dbg, void* stream);
 
 /* Output head + acceptance alone, on given final-normed hidden states h [dev] fp16 [B][K+1][d]. */
 int laser_verify_head(laser_model* model, const uint16_t* h, const int32_t* drafts,
@@ -243,6 +285,12 @@ int laser_verify_head_static(laser_model* model, const uint16_t* h, const int32_
 int laser_kv_commit(laser_kv* kv, const int32_t* seq_ids, const int32_t* accept_len, int B,
                     void* stream);
 
+/* laser_kv_commit_tree: laser_kv_commit after laser_verify_tree. The keys/values of the accepted branch's nodes are
+ * moved from their slots len + 1 + accept_path[b][j] to len + 1 + j (every layer and head) -- their rotary positions
+ * already are len + 1 + j --, then len[seq_ids[b]] += accept_len[b] + 1. K must be the K of that verify call. */
+int laser_kv_commit_tree(laser_kv* kv, const int32_t* seq_ids, const int32_t* accept_len,
+                         const int32_t* accept_path, int B, int K, void* stream);
+
 /* Device-side bookkeeping between steps: append the emitted tokens out_tokens[b][0..accept_len[b]]
  * to the context tail (keeping the last n_max tokens) and make the last of them the new pending
  * token.  ctx_tail [dev] int32[B][n_max] in/out, pending [dev] int32[B] out. */
@@ -259,6 +307,7 @@ int laser_ctx_advance(int32_t* ctx_tail, int32_t* pending, const int32_t* out_to
  * shape or the workspace cannot take falls back to 1). The parts are added in a fixed order by the
  * kernel that follows, so a given setting is deterministic; different settings may differ in the
  * last bits. Tuning and test knobs: the default is what the benchmark measures.
+ * "f16_copies" = 1 (default) or 0: see laser_model_create.
  * "mid_waves" = 0 (default: chosen per launch shape), 4 or 8: waves per workgroup of the weight-streaming
  * GEMM used with 17..80 rows.
  * "attn_whole_min" = 0 (default: half the number of compute units) or a count: from this many (sequence, head,

@@ -71,6 +71,9 @@ def lib():
         "laser_verify_head": [vp, vp, vp, vp, i32, i32, i32, f32, i32, vp, vp, vp, vp],
         "laser_verify_head_static": [vp, vp, vp, vp, i32, i32, i32, f32, i32, vp, vp, vp],
         "laser_kv_commit": [vp, vp, vp, i32, vp],
+        "laser_kv_commit_tree": [vp, vp, vp, vp, i32, i32, vp],
+        "laser_retrieve_tree": [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp],
+        "laser_verify_tree": [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, i32, vp, vp, vp, vp, vp],
         "laser_ctx_advance": [vp, vp, vp, vp, i32, i32, i32, vp],
         "laser_profile_begin": [vp, i32],
         "laser_model_set_option": [vp, C.c_char_p, i32],
@@ -346,6 +349,57 @@ def verify_head(model: Model, h: torch.Tensor, drafts: torch.Tensor, draft_len: 
                                    logits.data_ptr() if want_logits else None, _stream(stream)),
            "laser_verify_head")
     return acc, toks, logits
+
+
+def retrieve_tree(pool: "Pool", keys: torch.Tensor, ctx_tail: torch.Tensor, n_min: int, n_max: int, K: int,
+                  min_tokens: int = 1, out=None, stream=None):
+    """laser_retrieve_tree. Returns (tree_tokens [B][K], tree_parent [B][K], tree_freq [B][K], tree_len [B], match_n [B])."""
+    B = keys.shape[0]
+    dev = keys.device
+    if out is None:
+        out = (torch.empty((B, K), dtype=torch.int32, device=dev), torch.empty((B, K), dtype=torch.int32, device=dev),
+               torch.empty((B, K), dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+               torch.empty(B, dtype=torch.int32, device=dev))
+    tok, par, freq, tl, mn = out
+    _check(lib().laser_retrieve_tree(pool._h, _dev(keys, torch.int64, "keys"), _dev(ctx_tail, torch.int32, "ctx_tail"),
+                                     B, n_min, n_max, K, min_tokens,
+                                     _dev(tok, torch.int32, "tree_tokens") if K > 0 else None,
+                                     _dev(par, torch.int32, "tree_parent") if K > 0 else None,
+                                     (_dev(freq, torch.int32, "tree_freq") if K > 0 else None) if freq is not None else None,
+                                     _dev(tl, torch.int32, "tree_len"), _dev(mn, torch.int32, "match_n"), _stream(stream)),
+           "laser_retrieve_tree")
+    return tok, par, freq, tl, mn
+
+
+def verify_tree(model: "Model", kv: "KVCache", seq_ids, pending: torch.Tensor, tree_tokens: torch.Tensor,
+                tree_parent: torch.Tensor, tree_len: torch.Tensor, topk: int, p: float, mode: int = MODE_RV,
+                want_logits: bool = False, out=None, stream=None):
+    """laser_verify_tree. Returns (accept_len [B], out_tokens [B][K+1], accept_path [B][K], logits or None)."""
+    ids = _host_i32(seq_ids, "seq_ids")
+    B, K = tree_tokens.shape
+    dev = pending.device
+    if out is None:
+        out = (torch.empty(B, dtype=torch.int32, device=dev), torch.empty((B, K + 1), dtype=torch.int32, device=dev),
+               torch.empty((B, K), dtype=torch.int32, device=dev))
+    acc, toks, path = out
+    logits = torch.empty((B, K + 1, model.vocab), dtype=torch.float32, device=dev) if want_logits else None
+    _check(lib().laser_verify_tree(model._h, kv._h, ids.ctypes.data, _dev(pending, torch.int32, "pending"),
+                                   _dev(tree_tokens, torch.int32, "tree_tokens") if K > 0 else None,
+                                   _dev(tree_parent, torch.int32, "tree_parent") if K > 0 else None,
+                                   _dev(tree_len, torch.int32, "tree_len"), B, K, topk, p, mode,
+                                   _dev(acc, torch.int32, "accept_len"), _dev(toks, torch.int32, "out_tokens"),
+                                   _dev(path, torch.int32, "accept_path") if K > 0 else None,
+                                   logits.data_ptr() if want_logits else None, _stream(stream)), "laser_verify_tree")
+    return acc, toks, path, logits
+
+
+def kv_commit_tree(kv: "KVCache", seq_ids, accept_len: torch.Tensor, accept_path: torch.Tensor, stream=None):
+    """laser_kv_commit_tree."""
+    ids = _host_i32(seq_ids, "seq_ids")
+    K = accept_path.shape[1]
+    _check(lib().laser_kv_commit_tree(kv._h, ids.ctypes.data, _dev(accept_len, torch.int32, "accept_len"),
+                                      _dev(accept_path, torch.int32, "accept_path") if K > 0 else None, ids.size, K,
+                                      _stream(stream)), "laser_kv_commit_tree")
 
 
 def verify_head_static(model: Model, h: torch.Tensor, drafts: torch.Tensor, draft_len: torch.Tensor, topk: int,

@@ -22,6 +22,7 @@
 
 #include <type_traits>
 
+#include "head_part.h"
 #include "mfma.h"
 
 namespace laser {
@@ -44,9 +45,12 @@ struct GemmTileArgs {
                             // in a fixed order). It evens out tile counts that do not fill the chip's slots.
     float* outf;            // EPI_F32: [M][N] store; EPI_RESID: [M][N] accumulate
     uint16_t* outh;         // EPI_SWIGLU: [M][N] fp16
+    HeadPart hp{};          // GEPI_HEAD: where the per-(row, n-tile) statistics go (chunk = n-tile)
 };
 
-enum { GEPI_F32 = 0, GEPI_RESID = 1, GEPI_SWIGLU = 2 };
+// GEPI_HEAD: the output head. The tile's logits are not stored: each row's 128 columns are reduced to one record of
+// partial statistics (head_part.h).
+enum { GEPI_F32 = 0, GEPI_RESID = 1, GEPI_SWIGLU = 2, GEPI_HEAD = 3 };
 
 // workgroups of a launch: 8 x the largest per-XCD tile count (n-tiles are dealt round-robin to the XCDs)
 inline unsigned gemm_mfma_grid(int tiles_m, int tiles_n) { return 8u * (unsigned)(((tiles_n + 7) / 8) * tiles_m); }
@@ -270,6 +274,76 @@ __global__ __launch_bounds__(256, SPLIT ? 2 : GM_WGS) void gemm_mfma_kernel(Gemm
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] += acl[i][j][e] * kLoInv;
+    }
+    if constexpr (EPI == GEPI_HEAD) {
+        // ---- output-head epilogue: the tile goes through LDS in two halves of 64 columns (the staging buffer of the
+        // activations is free after the loop's last barrier and holds 128 rows x 65 floats), where thread t owns half a
+        // row (row t / 2, 32 of the 64 columns) and folds it into its running statistics; ids ascend per thread.
+        static_assert(BN == 128 && !SPLIT, "the head epilogue is written for 128-column single-plane tiles");
+        static_assert(sizeof(sA) >= GM_BM * 65 * sizeof(float), "the activation staging buffer must hold half a tile of floats");
+        float* sC = reinterpret_cast<float*>(&sA[0][0][0]);
+        const int trow = tid >> 1, part = tid & 1;
+        const int grow = tm * GM_BM + trow;
+        RowStat st;
+        st.init();
+        const int kt = a.hp.topk;                       // 1..KT
+        float thr_v = -INFINITY;                        // the list's kt-th entry: what a value has to beat to enter
+        int thr_i = 0x7FFFFFFF;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            if (wn == h) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e)
+                            sC[(wm * 64 + i * 32 + 8 * (e >> 2) + 4 * lg + (e & 3)) * 65 + j * 32 + lr] = acc[i][j][e];
+            }
+            __syncthreads();
+            const int n0 = tn * BN + h * 64 + part * 32;
+            const float* src = sC + trow * 65 + part * 32;
+            if (grow < a.M) {
+                // 32 columns at once, without data-dependent branches on the common path: their maximum and its first
+                // position, the sum of exponentials against the new running maximum, and the few values that beat the
+                // list's kt-th entry (kt = the call's k: deeper list entries are never needed for "rank < k")
+                float vals[32];
+#pragma unroll
+                for (int c = 0; c < 32; ++c) vals[c] = (n0 + c < a.N) ? src[c] : -INFINITY;
+                float mloc = vals[0];
+#pragma unroll
+                for (int c = 1; c < 32; ++c) mloc = fmaxf(mloc, vals[c]);
+                int cloc = 31;
+#pragma unroll
+                for (int c = 30; c >= 0; --c) cloc = vals[c] == mloc ? c : cloc;
+                const float m_new = fmaxf(st.mx, mloc);
+                float ssum = 0.f;
+                if (m_new != -INFINITY) {
+#pragma unroll
+                    for (int c = 0; c < 32; ++c) ssum += __expf(vals[c] - m_new);          // exp(-inf) = 0 for columns past N
+                    st.sum = st.sum * __expf(st.mx - m_new) + ssum;
+                }
+                if (mloc > st.mx) st.arg = n0 + cloc;                                      // ids ascend per thread: earlier ties stay
+                st.mx = m_new;
+                store_candidates(a.hp, grow, n0, 32, [&](int c) { return src[c]; });
+#pragma unroll
+                for (int c = 0; c < 32; ++c) {
+                    if (n0 + c < a.N && before(vals[c], n0 + c, thr_v, thr_i)) {
+                        st.push_top(vals[c], n0 + c);
+#pragma unroll
+                        for (int j = 0; j < KT; ++j) if (j == kt - 1) { thr_v = st.tv[j]; thr_i = st.ti[j]; }
+                    }
+                }
+                if (a.hp.logits_dbg) {
+#pragma unroll
+                    for (int c = 0; c < 32; ++c) if (n0 + c < a.N) a.hp.logits_dbg[(size_t)grow * a.N + n0 + c] = vals[c];
+                }
+            }
+            __syncthreads();
+        }
+        st.merge_from_lane(1);
+        if (part == 0 && grow < a.M) st.store(a.hp, grow, tn);
+        return;
     }
     // ---- epilogue: lane holds column lr of each 32-wide tile, rows 8 (e / 4) + 4 lg + e % 4 ----
 #pragma unroll

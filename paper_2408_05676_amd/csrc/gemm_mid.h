@@ -23,10 +23,13 @@
 #include <type_traits>
 
 #include "gemm_skinny.h"
+#include "head_part.h"
 
 namespace laser {
 
-enum { EPI_F32 = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
+// EPI_HEAD: the output head; a workgroup keeps one record of partial statistics per row (head_part.h) instead of
+// its logits (chunk = workgroup: NW x 16 vocabulary entries).
+enum { EPI_F32 = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3 };
 
 struct GemmMidArgs {
     const uint16_t* W;      // [N][Kd] bf16  (EPI_SWIGLU: [2N][Kd], gate rows then up rows)
@@ -36,6 +39,7 @@ struct GemmMidArgs {
     float* outf;            // EPI_F32: [M][N] store;  EPI_RESID: [M][N] accumulate (one part only)
     uint16_t* outh;         // EPI_SWIGLU: [M][N] fp16
     float* part;            // gridDim.y > 1: [gridDim.y][M][N] partial results
+    HeadPart hp{};          // EPI_HEAD: where the per-(row, workgroup) statistics go
 };
 
 // NW = waves (weight tiles) per workgroup, 4 or 8: what enters a compute unit per step is NW x 4 KB of weights
@@ -258,7 +262,35 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void gemm_mid_kernel(Gemm
 #pragma unroll
         for (int i = 0; i < 4; ++i) v[mb][i] = SPLIT ? acc[mb][i] + acl[mb][i] * kLoInv : acc[mb][i];
     const int n = tile * 16 + 4 * g;
-    if constexpr (EPI == EPI_SWIGLU) {
+    if constexpr (EPI == EPI_HEAD) {
+        // per wave 16 vocabulary entries of every row: lane statistics, merged over the four lane groups, then over
+        // the workgroup's waves in wave order through LDS (the loop's last barrier freed sx)
+        float* ex = reinterpret_cast<float*>(sx);             // [NW][ROWS][RowStat::kWords]
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const int row = mb * 16 + r;
+            RowStat st;
+            st.init();
+            if (active) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) st.add(v[mb][i], n + i);
+                if (row < a.M)
+                    store_candidates(a.hp, row, n, 4, [&](int c) { return c == 0 ? v[mb][0] : c == 1 ? v[mb][1] : c == 2 ? v[mb][2] : v[mb][3]; });
+                if (a.hp.logits_dbg && row < a.M)
+                    *reinterpret_cast<float4*>(a.hp.logits_dbg + (size_t)row * a.N + n) = make_float4(v[mb][0], v[mb][1], v[mb][2], v[mb][3]);
+            }
+            st.merge_from_lane(16);
+            st.merge_from_lane(32);
+            if (g == 0) st.to_lds(ex + ((size_t)wave * ROWS + row) * RowStat::kWords);
+        }
+        __syncthreads();
+        if (tid < ROWS && tid < a.M) {
+            RowStat m;
+            m.init();
+            for (int w = 0; w < NW; ++w) m.merge_lds(ex + ((size_t)w * ROWS + tid) * RowStat::kWords);
+            m.store(a.hp, tid, (int)blockIdx.x);
+        }
+    } else if constexpr (EPI == EPI_SWIGLU) {
         static_assert((NW / 2) * MB * 4 * 64 * sizeof(float) <= BUFH * sizeof(uint16_t), "the exchange area must fit a chunk buffer");
         float* ex = reinterpret_cast<float*>(sx);             // [pair][mb][i][lane]; the loop's last barrier freed sx
         if (sel == 1) {
@@ -332,8 +364,10 @@ inline GemmMidPlan gemm_mid_plan(int M, int N, int Kd, int planes, bool swiglu, 
 }
 
 // Dynamic LDS of a launch: one chunk buffer (both planes, padded rows) for the 8-wave form, two for the 4-wave form.
-constexpr size_t gemm_mid_lds_bytes(int mb, bool split, int nw) {
-    return (size_t)(nw == 8 ? 1 : 2) * (split ? 2 : 1) * mb * 16 * (kGemmKStep + 8) * sizeof(uint16_t);
+constexpr size_t gemm_mid_lds_bytes(int mb, bool split, int nw, bool head = false) {
+    const size_t chunks = (size_t)(nw == 8 ? 1 : 2) * (split ? 2 : 1) * mb * 16 * (kGemmKStep + 8) * sizeof(uint16_t);
+    const size_t records = head ? (size_t)nw * mb * 16 * RowStat::kWords * sizeof(float) : 0;   // the head's merge over the waves
+    return chunks > records ? chunks : records;
 }
 
 // Caller guarantees 16 < M <= 80, N % 16 == 0, Kd % 128 == 0, and a plan made for this shape.
@@ -341,21 +375,22 @@ template <int EPI, bool SPLIT>
 inline void launch_gemm_mid(const GemmMidArgs& a, GemmMidPlan pl, hipStream_t stream) {
     const int vtiles = (EPI == EPI_SWIGLU ? 2 : 1) * (a.N / 16), mblocks = (a.M + 15) / 16;
     dim3 grid((unsigned)((vtiles + pl.NW - 1) / pl.NW), (unsigned)pl.S);
+    constexpr bool kHead = EPI == EPI_HEAD;
     auto go = [&](auto mbc) {
         constexpr int mb = decltype(mbc)::value;
         // more than 64 KB of dynamic LDS has to be allowed per kernel, once
         static const bool allowed = [] {
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mid_kernel<mb, EPI, SPLIT, 8>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_mid_lds_bytes(mb, SPLIT, 8));
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_mid_lds_bytes(mb, SPLIT, 8, kHead));
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mid_kernel<mb, EPI, SPLIT, 4>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_mid_lds_bytes(mb, SPLIT, 4));
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_mid_lds_bytes(mb, SPLIT, 4, kHead));
             return true;
         }();
         (void)allowed;
         if (pl.NW == 8)
-            hipLaunchKernelGGL((gemm_mid_kernel<mb, EPI, SPLIT, 8>), grid, dim3(512), gemm_mid_lds_bytes(mb, SPLIT, 8), stream, a);
+            hipLaunchKernelGGL((gemm_mid_kernel<mb, EPI, SPLIT, 8>), grid, dim3(512), gemm_mid_lds_bytes(mb, SPLIT, 8, kHead), stream, a);
         else
-            hipLaunchKernelGGL((gemm_mid_kernel<mb, EPI, SPLIT, 4>), grid, dim3(256), gemm_mid_lds_bytes(mb, SPLIT, 4), stream, a);
+            hipLaunchKernelGGL((gemm_mid_kernel<mb, EPI, SPLIT, 4>), grid, dim3(256), gemm_mid_lds_bytes(mb, SPLIT, 4, kHead), stream, a);
     };
     switch (mblocks) {
         case 2: go(std::integral_constant<int, 2>{}); break;

@@ -1,21 +1,19 @@
-// Fused output head + acceptance (Sec. 3.4 Eq. 7-8; greedy Eq. 4; correction rule of Sec. 2.1).
+// Fused output head + acceptance (Sec. 3.4 Eq. 7-8; greedy Eq. 4; correction rule of Sec. 2.1). Logits are never
+// stored (unless a debug buffer is passed): every kernel that produces them reduces them at once to per-(row,
+// vocabulary chunk) partial statistics (head_part.h), and accept_kernel merges a row's chunks, decides the row and
+// scans the rows of a sequence.
 //
-// Pass 1 (lm_head_kernel): every wavefront owns a contiguous chunk of the vocabulary, streams those
-// rows of the head matrix once through the matrix cores against all verified rows, and keeps, per
-// row, running softmax statistics (max, sum of exp), the arg-max (smaller id on ties), the logit of
-// the row's draft token, and its chunk's best LASER_MAX_TOPK (logit, id) pairs -- all in registers.
-// Logits are never written unless a debug buffer is passed.
-// Pass 2 (accept_kernel): one block per sequence merges the per-chunk partials. The draft's rank is
-// the number of partial-list entries ordered before it; if a chunk hides an entry that precedes the
-// draft, that chunk already contributes >= LASER_MAX_TOPK >= k listed ones, so "rank < k" is exact.
-// The block then scans the rows left to right and emits accepted drafts plus the correction token.
-//
-// More than 16 rows: the per-lane running statistics of pass 1 (one set per row tile) and the serial merge of
-// pass 2 cost more than they save. Instead the logits are written to an fp32 workspace by a GEMM (17..80 rows:
-// the weight-streaming kernel of gemm_mid.h, the head matrix read once; more: the LDS-tiled matrix-core GEMM;
-// the logits are written and read once, 8 bytes each against the 2 * d flops they cost), head_stats_kernel
-// reduces each row (max, sum of exp, arg-max, the draft's logit and its exact rank) and decides it,
-// head_scan_kernel scans the rows.
+// Pass 1, by row count M = B*(K+1):
+//   M <= 16   lm_head_kernel: every wavefront owns a contiguous chunk of the vocabulary, streams those rows of the
+//             head matrix once through the matrix cores against all verified rows and keeps the running statistics
+//             in registers (chunk = wavefront).
+//   M <= 80   the weight-streaming kernel of gemm_mid.h with its head epilogue (chunk = workgroup, 64 or 128
+//             vocabulary entries): the head matrix is read once.
+//   more      the LDS-tiled matrix-core GEMM of gemm_mfma.h with its head epilogue (chunk = 128-column tile).
+// Pass 2 (accept_kernel): one block per sequence merges the per-chunk partials. The draft's rank is the number of
+// partial-list entries ordered before it; if a chunk hides an entry that precedes the draft, that chunk already
+// contributes >= LASER_MAX_TOPK >= k listed ones, so "rank < k" is exact. The block then scans the rows left to
+// right and emits accepted drafts plus the correction token.
 #include <cmath>
 #include <mutex>
 
@@ -26,90 +24,65 @@
 
 namespace laser {
 
-constexpr int KT = LASER_MAX_TOPK;
-constexpr int kHeadStreamMaxRows = 16;   // beyond this the logits are written out by a GEMM and reduced row by row
+int widen_copies(const uint16_t* const* src, const size_t* elems, int n, uint16_t** dst, hipStream_t stream);
+
+constexpr int kHeadStreamMaxRows = 16;   // up to here lm_head_kernel; beyond, a GEMM with the head epilogue
 constexpr int kHeadMidMaxRows = 80;      // up to here that GEMM streams the head matrix once; beyond, the tiled one
 
 struct HeadArgs {
-    const uint16_t* W; const uint16_t* H; int M, V, d, tiles_per_wave, chunks;
-    const int32_t* row_x;
-    float* hp_max; float* hp_sum; int32_t* hp_arg; float* hp_topv; int32_t* hp_topi; float* hp_lx;
-    float* logits_dbg;
+    const uint16_t* W; const uint16_t* H; int M, V, d, tiles_per_wave;
+    HeadPart hp;
 };
 
-__global__ void head_rows_kernel(const int32_t* drafts, const int32_t* draft_len, int B, int K, int vocab,
-                                 int32_t* row_x, float* hp_lx) {
-    const int m = blockIdx.x * blockDim.x + threadIdx.x, R = K + 1;
-    if (m >= B * R) return;
-    const int b = m / R, r = m % R;
-    int x = (r < K && r < draft_len[b]) ? drafts[(size_t)b * K + r] : -1;
-    if (x >= vocab) x = -1;
-    row_x[m] = x;
-    hp_lx[m] = -INFINITY;
-}
-
-// ordering of (logit, id): larger logit first, smaller id on ties
-__device__ inline bool before(float v, int i, float w, int j) { return v > w || (v == w && i < j); }
-
-struct RowStat {
-    float mx, sum, lx;
-    int arg;
-    float tv[KT];
-    int ti[KT];
-    __device__ void init() {
-        mx = -INFINITY; sum = 0.f; lx = -INFINITY; arg = 0x7FFFFFFF;
-#pragma unroll
-        for (int j = 0; j < KT; ++j) { tv[j] = -INFINITY; ti[j] = 0x7FFFFFFF; }
-    }
-    __device__ void push_top(float v, int n) {
-        if (!before(v, n, tv[KT - 1], ti[KT - 1])) return;
-        tv[KT - 1] = v; ti[KT - 1] = n;
-#pragma unroll
-        for (int j = KT - 1; j > 0; --j) {
-            if (before(tv[j], ti[j], tv[j - 1], ti[j - 1])) {
-                float fv = tv[j]; tv[j] = tv[j - 1]; tv[j - 1] = fv;
-                int fi = ti[j]; ti[j] = ti[j - 1]; ti[j - 1] = fi;
-            }
+// One thread per sequence: the candidates of every row. Node i of the pseudo-sequence (token tokens[b][i]) is a
+// candidate of its parent's row (row parent + 1; row 0 is the pending token's): for a chain, node i of row i.
+// Candidates of a row are stored next to each other, in pseudo-sequence order; nodes past n_nodes[b] and tokens
+// outside the vocabulary are no candidates (node_cand = -1: never accepted).
+__global__ void head_cands_kernel(const int32_t* tokens, const int32_t* parent, const int32_t* n_nodes, int B, int K, int vocab,
+                                  int32_t* cand_beg, int32_t* cand_cnt, int32_t* cand_x, int32_t* node_cand, float* cand_lx) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x, R = K + 1;
+    if (b >= B) return;
+    int nn = n_nodes[b];
+    nn = nn < 0 ? 0 : (nn > K ? K : nn);
+    int32_t* cnt = cand_cnt + (size_t)b * R;
+    int32_t* beg = cand_beg + (size_t)b * R;
+    for (int r = 0; r < R; ++r) cnt[r] = 0;
+    auto valid = [&](int i) { const int x = tokens[(size_t)b * K + i]; return i < nn && x >= 0 && x < vocab; };
+    for (int i = 0; i < nn; ++i)
+        if (valid(i)) ++cnt[tree_parent_of(parent, b, K, i, nn) + 1];
+    int off = b * K;
+    for (int r = 0; r < R; ++r) { beg[r] = off; off += cnt[r]; cnt[r] = 0; }
+    for (int i = 0; i < K; ++i) {
+        int c = -1;
+        if (valid(i)) {
+            const int prow = tree_parent_of(parent, b, K, i, nn) + 1;
+            c = beg[prow] + cnt[prow]++;
+            cand_x[c] = tokens[(size_t)b * K + i];
+            cand_lx[c] = -INFINITY;
         }
+        node_cand[(size_t)b * K + i] = c;
     }
-    __device__ void add(float v, int n) {
-        if (v > mx) { sum = sum * __expf(mx - v) + 1.f; mx = v; arg = n; }   // ids arrive ascending per lane
-        else sum += __expf(v - mx);
-        push_top(v, n);
-    }
-    __device__ void merge_from_lane(int src_xor) {
-        const float omx = __shfl_xor(mx, src_xor), osum = __shfl_xor(sum, src_xor), olx = __shfl_xor(lx, src_xor);
-        const int oarg = __shfl_xor(arg, src_xor);
-        float otv[KT]; int oti[KT];
-#pragma unroll
-        for (int j = 0; j < KT; ++j) { otv[j] = __shfl_xor(tv[j], src_xor); oti[j] = __shfl_xor(ti[j], src_xor); }
-        const float M = fmaxf(mx, omx);
-        if (M != -INFINITY) sum = sum * __expf(mx - M) + osum * __expf(omx - M);
-        if (before(omx, oarg, mx, arg)) arg = oarg;
-        mx = M;
-        lx = fmaxf(lx, olx);
-#pragma unroll
-        for (int j = 0; j < KT; ++j) push_top(otv[j], oti[j]);
-    }
-};
+}
 
 template <int MB>
 __global__ __launch_bounds__(256) void lm_head_kernel(HeadArgs a) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
     const int chunk = blockIdx.x * 4 + wave;
-    if (chunk >= a.chunks) return;
+    if (chunk >= a.hp.chunks) return;
     const int ntiles = a.V / 16;
     const int t0 = chunk * a.tiles_per_wave, t1 = min(ntiles, t0 + a.tiles_per_wave);
     const int row0 = blockIdx.y * MB * 16;
 
     RowStat st[MB];
-    int x[MB];
+    int cb[MB], cn[MB], x0[MB];           // the row's candidates; the first one's token is kept in a register
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         st[mb].init();
         const int row = row0 + mb * 16 + r;
-        x[mb] = row < a.M ? a.row_x[row] : -1;
+        cb[mb] = row < a.M ? a.hp.cand_beg[row] : 0;
+        cn[mb] = row < a.M ? a.hp.cand_cnt[row] : 0;
+        x0[mb] = cn[mb] > 0 ? a.hp.cand_x[cb[mb]] : -1;
     }
     for (int t = t0; t < t1; ++t) {
         float4_t acc[MB];
@@ -120,13 +93,16 @@ __global__ __launch_bounds__(256) void lm_head_kernel(HeadArgs a) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                st[mb].add(acc[mb][i], n + i);
-                if (n + i == x[mb]) st[mb].lx = acc[mb][i];
+            for (int i = 0; i < 4; ++i) st[mb].add(acc[mb][i], n + i);
+            auto pick = [&](int c) { return c == 0 ? acc[mb][0] : c == 1 ? acc[mb][1] : c == 2 ? acc[mb][2] : acc[mb][3]; };
+            if (x0[mb] >= n && x0[mb] < n + 4) a.hp.cand_lx[cb[mb]] = pick(x0[mb] - n);
+            for (int c = 1; c < cn[mb]; ++c) {                   // further children of a tree node
+                const int x = a.hp.cand_x[cb[mb] + c];
+                if (x >= n && x < n + 4) a.hp.cand_lx[cb[mb] + c] = pick(x - n);
             }
             const int row = row0 + mb * 16 + r;
-            if (a.logits_dbg && row < a.M)
-                *reinterpret_cast<float4*>(a.logits_dbg + (size_t)row * a.V + n) =
+            if (a.hp.logits_dbg && row < a.M)
+                *reinterpret_cast<float4*>(a.hp.logits_dbg + (size_t)row * a.V + n) =
                     make_float4(acc[mb][0], acc[mb][1], acc[mb][2], acc[mb][3]);
         }
     }
@@ -135,235 +111,203 @@ __global__ __launch_bounds__(256) void lm_head_kernel(HeadArgs a) {
         st[mb].merge_from_lane(16);
         st[mb].merge_from_lane(32);
         const int row = row0 + mb * 16 + r;
-        if (g == 0 && row < a.M) {
-            const size_t o = (size_t)row * a.chunks + chunk;
-            a.hp_max[o] = st[mb].mx; a.hp_sum[o] = st[mb].sum; a.hp_arg[o] = st[mb].arg;
-#pragma unroll
-            for (int j = 0; j < KT; ++j) { a.hp_topv[o * KT + j] = st[mb].tv[j]; a.hp_topi[o * KT + j] = st[mb].ti[j]; }
-            if (st[mb].lx != -INFINITY) a.hp_lx[row] = st[mb].lx;
-        }
+        if (g == 0 && row < a.M) st[mb].store(a.hp, row, chunk);
     }
 }
 
 struct AcceptArgs {
     const float* hp_max; const float* hp_sum; const int32_t* hp_arg; const float* hp_topv; const int32_t* hp_topi;
-    const float* hp_lx; const int32_t* row_x; const int32_t* drafts; const int32_t* draft_len;
+    const int32_t* cand_beg; const int32_t* cand_cnt; const int32_t* cand_x; const float* cand_lx; const int32_t* node_cand;
+    const int32_t* tokens; const int32_t* parent; const int32_t* n_nodes;      // parent == NULL: a chain
     int K, chunks, topk, mode; float p;
-    int32_t* accept_len; int32_t* out_tokens;
+    int32_t* accept_len; int32_t* out_tokens; int32_t* accept_path;            // accept_path may be NULL
 };
 
+// One block per sequence. Part 1: every row's chunks are merged (softmax statistics, arg-max) and every candidate
+// of the row gets its rank; part 2: the nodes are examined in pseudo-sequence order (a node is verified iff its
+// parent is and its token passes the rule against its parent's row), the deepest verified node -- the first one
+// among equally deep -- ends the accepted branch, and the branch's tokens plus the arg-max of its last row are
+// emitted (Sec. 3.4; Sec. 2.1 for the correction token). For a chain this is the longest accepted prefix.
+constexpr int kCandPass = 4;          // candidates ranked per pass over a row's chunks
 __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
-    __shared__ float s_f[4][3];
-    __shared__ int s_i[4][2];
-    __shared__ int row_ok[LASER_MAX_DRAFT + 1], row_arg[LASER_MAX_DRAFT + 1];
+    __shared__ float s_f[4][2];
+    __shared__ int s_i[4][1 + kCandPass];
+    __shared__ float row_mx[LASER_MAX_DRAFT + 1], row_sum[LASER_MAX_DRAFT + 1];
+    __shared__ int row_arg[LASER_MAX_DRAFT + 1];
+    __shared__ int rank_of[LASER_MAX_DRAFT + 1];          // by candidate number within the sequence
     const int b = blockIdx.x, R = a.K + 1;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     for (int r = 0; r < R; ++r) {
         const int row = b * R + r;
-        const int x = a.row_x[row];
-        const float lx = a.hp_lx[row];
-        float mx = -INFINITY, sum = 0.f;
-        int arg = 0x7FFFFFFF, ahead = 0;
-        for (int c = threadIdx.x; c < a.chunks; c += 256) {
-            const size_t o = (size_t)row * a.chunks + c;
-            const float cm = a.hp_max[o], cs = a.hp_sum[o];
-            const int ca = a.hp_arg[o];
-            const float M = fmaxf(mx, cm);
-            sum = sum * __expf(mx - M) + cs * __expf(cm - M);
-            if (before(cm, ca, mx, arg)) arg = ca;
-            mx = M;
-            if (x >= 0)
+        const int cb = a.cand_beg[row], cn = a.cand_cnt[row];
+        for (int c0 = 0; c0 < (cn > 0 ? cn : 1); c0 += kCandPass) {
+            int x[kCandPass];
+            float lx[kCandPass];
 #pragma unroll
-                for (int j = 0; j < KT; ++j) {
-                    const float v = a.hp_topv[o * KT + j];
-                    const int i = a.hp_topi[o * KT + j];
-                    ahead += (i != x && before(v, i, lx, x)) ? 1 : 0;
-                }
-        }
-        for (int off = 32; off > 0; off >>= 1) {
-            const float omx = __shfl_xor(mx, off), osum = __shfl_xor(sum, off);
-            const int oarg = __shfl_xor(arg, off);
-            ahead += __shfl_xor(ahead, off);
-            const float M = fmaxf(mx, omx);
-            if (M != -INFINITY) sum = sum * __expf(mx - M) + osum * __expf(omx - M);
-            if (before(omx, oarg, mx, arg)) arg = oarg;
-            mx = M;
-        }
-        __syncthreads();
-        if (lane == 0) { s_f[wave][0] = mx; s_f[wave][1] = sum; s_i[wave][0] = arg; s_i[wave][1] = ahead; }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            float M = -INFINITY, S = 0.f; int A = 0x7FFFFFFF, rank = 0;
-            for (int w = 0; w < 4; ++w) {
-                const float wm = s_f[w][0];
-                const float nm = fmaxf(M, wm);
-                if (nm != -INFINITY) S = S * __expf(M - nm) + s_f[w][1] * __expf(wm - nm);
-                if (before(wm, s_i[w][0], M, A)) A = s_i[w][0];
-                M = nm;
-                rank += s_i[w][1];
+            for (int j = 0; j < kCandPass; ++j) {
+                const bool have = c0 + j < cn;
+                x[j] = have ? a.cand_x[cb + c0 + j] : -1;
+                lx[j] = have ? a.cand_lx[cb + c0 + j] : -INFINITY;
             }
-            bool ok = false;
-            if (x >= 0) {
-                const float q = __expf(lx - M) / S;
+            float mx = -INFINITY, sum = 0.f;
+            int arg = 0x7FFFFFFF, ahead[kCandPass] = {0, 0, 0, 0};
+            for (int c = threadIdx.x; c < a.chunks; c += 256) {
+                const size_t o = (size_t)row * a.chunks + c;
+                const float cm = a.hp_max[o], cs = a.hp_sum[o];
+                const int ca = a.hp_arg[o];
+                const float M = fmaxf(mx, cm);
+                sum = sum * __expf(mx - M) + cs * __expf(cm - M);
+                if (before(cm, ca, mx, arg)) arg = ca;
+                mx = M;
+                if (cn > 0)
+#pragma unroll
+                    for (int t = 0; t < KT; ++t) {
+                        const float v = a.hp_topv[o * KT + t];
+                        const int i = a.hp_topi[o * KT + t];
+#pragma unroll
+                        for (int j = 0; j < kCandPass; ++j) ahead[j] += (x[j] >= 0 && i != x[j] && before(v, i, lx[j], x[j])) ? 1 : 0;
+                    }
+            }
+            for (int off = 32; off > 0; off >>= 1) {
+                const float omx = __shfl_xor(mx, off), osum = __shfl_xor(sum, off);
+                const int oarg = __shfl_xor(arg, off);
+#pragma unroll
+                for (int j = 0; j < kCandPass; ++j) ahead[j] += __shfl_xor(ahead[j], off);
+                const float M = fmaxf(mx, omx);
+                if (M != -INFINITY) sum = sum * __expf(mx - M) + osum * __expf(omx - M);
+                if (before(omx, oarg, mx, arg)) arg = oarg;
+                mx = M;
+            }
+            __syncthreads();
+            if (lane == 0) {
+                s_f[wave][0] = mx; s_f[wave][1] = sum; s_i[wave][0] = arg;
+#pragma unroll
+                for (int j = 0; j < kCandPass; ++j) s_i[wave][1 + j] = ahead[j];
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                float M = -INFINITY, S = 0.f; int A = 0x7FFFFFFF, rk[kCandPass] = {0, 0, 0, 0};
+                for (int w = 0; w < 4; ++w) {
+                    const float wm = s_f[w][0];
+                    const float nm = fmaxf(M, wm);
+                    if (nm != -INFINITY) S = S * __expf(M - nm) + s_f[w][1] * __expf(wm - nm);
+                    if (before(wm, s_i[w][0], M, A)) A = s_i[w][0];
+                    M = nm;
+#pragma unroll
+                    for (int j = 0; j < kCandPass; ++j) rk[j] += s_i[w][1 + j];
+                }
+                if (c0 == 0) { row_mx[r] = M; row_sum[r] = S; row_arg[r] = A; }
+#pragma unroll
+                for (int j = 0; j < kCandPass; ++j)
+                    if (c0 + j < cn) rank_of[cb - b * a.K + c0 + j] = rk[j];
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int nn = a.n_nodes[b];
+        nn = nn < 0 ? 0 : (nn > a.K ? a.K : nn);
+        unsigned long long ver = 0;                       // bit i: node i is verified
+        signed char depth[LASER_MAX_DRAFT + 1];
+        int best = -1, best_depth = 0;
+        for (int i = 0; i < nn; ++i) {
+            const int par = tree_parent_of(a.parent, b, a.K, i, nn);
+            const int c = a.node_cand[(size_t)b * a.K + i];
+            bool ok = c >= 0 && (par < 0 || ((ver >> par) & 1ull));
+            if (ok) {
+                const int prow = par + 1, rank = rank_of[c - b * a.K];
+                const float q = __expf(a.cand_lx[c] - row_mx[prow]) / row_sum[prow];
                 const bool in_k = rank < a.topk, above = q > a.p, top1 = rank == 0;
                 ok = a.mode == LASER_MODE_RV ? (in_k && above)
                    : a.mode == LASER_MODE_RV_OR_TOP1 ? (top1 || (in_k && above))
                    : a.mode == LASER_MODE_TOPK_ONLY ? in_k : (top1 || above);
             }
-            row_ok[r] = ok ? 1 : 0;
-            row_arg[r] = A;
+            depth[i] = 0;
+            if (ok) {
+                ver |= 1ull << i;
+                depth[i] = (signed char)((par >= 0 ? depth[par] : 0) + 1);
+                if (depth[i] > best_depth) { best = i; best_depth = depth[i]; }
+            }
         }
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int dl = a.draft_len[b];
-        dl = dl < 0 ? 0 : (dl > a.K ? a.K : dl);
-        int n = 0;
-        while (n < dl && row_ok[n]) ++n;
-        a.accept_len[b] = n;
+        a.accept_len[b] = best_depth;
         int32_t* out = a.out_tokens + (size_t)b * R;
-        for (int j = 0; j < R; ++j) out[j] = j < n ? a.drafts[(size_t)b * a.K + j] : (j == n ? row_arg[n] : -1);
+        for (int j = best_depth + 1; j < R; ++j) out[j] = -1;
+        out[best_depth] = row_arg[best + 1];
+        for (int i = best, j = best_depth - 1; j >= 0; --j) {
+            out[j] = a.tokens[(size_t)b * a.K + i];
+            if (a.accept_path) a.accept_path[(size_t)b * a.K + j] = i;
+            i = tree_parent_of(a.parent, b, a.K, i, nn);
+        }
+        if (a.accept_path)
+            for (int j = best_depth; j < a.K; ++j) a.accept_path[(size_t)b * a.K + j] = -1;
     }
 }
 
-// One workgroup per row of the logits matrix: softmax statistics, arg-max (smaller id on ties), the
-// draft's logit, the number of vocabulary entries ordered before the draft, and the row's decision.
-struct StatsArgs {
-    const float* logits; const int32_t* row_x; int V, topk, mode; float p;
-    int32_t* row_ok; int32_t* row_arg;
-};
-
-__global__ __launch_bounds__(256) void head_stats_kernel(StatsArgs a) {
-    __shared__ float s_f[4][2];
-    __shared__ int s_i[4][2];
-    const int row = blockIdx.x;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const float* l = a.logits + (size_t)row * a.V;
-    const int x = a.row_x[row];
-    const float lx = x >= 0 ? l[x] : -INFINITY;
-    float mx = -INFINITY, sum = 0.f;
-    int arg = 0x7FFFFFFF, ahead = 0;
-    for (int n = threadIdx.x * 4; n < a.V; n += 256 * 4) {          // V is a multiple of 16
-        const float4 v = *reinterpret_cast<const float4*>(l + n);
-        const float e[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (e[i] > mx) { sum = sum * __expf(mx - e[i]) + 1.f; mx = e[i]; arg = n + i; }   // ids ascend per thread
-            else sum += __expf(e[i] - mx);
-            ahead += (n + i != x && before(e[i], n + i, lx, x)) ? 1 : 0;
-        }
-    }
-    for (int off = 32; off > 0; off >>= 1) {
-        const float omx = __shfl_xor(mx, off), osum = __shfl_xor(sum, off);
-        const int oarg = __shfl_xor(arg, off);
-        ahead += __shfl_xor(ahead, off);
-        const float M = fmaxf(mx, omx);
-        if (M != -INFINITY) sum = sum * __expf(mx - M) + osum * __expf(omx - M);
-        if (before(omx, oarg, mx, arg)) arg = oarg;
-        mx = M;
-    }
-    if (lane == 0) { s_f[wave][0] = mx; s_f[wave][1] = sum; s_i[wave][0] = arg; s_i[wave][1] = ahead; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        float M = -INFINITY, S = 0.f; int A = 0x7FFFFFFF, rank = 0;
-        for (int w = 0; w < 4; ++w) {
-            const float wm = s_f[w][0];
-            const float nm = fmaxf(M, wm);
-            if (nm != -INFINITY) S = S * __expf(M - nm) + s_f[w][1] * __expf(wm - nm);
-            if (before(wm, s_i[w][0], M, A)) A = s_i[w][0];
-            M = nm;
-            rank += s_i[w][1];
-        }
-        bool ok = false;
-        if (x >= 0) {
-            const float q = __expf(lx - M) / S;
-            const bool in_k = rank < a.topk, above = q > a.p, top1 = rank == 0;
-            ok = a.mode == LASER_MODE_RV ? (in_k && above)
-               : a.mode == LASER_MODE_RV_OR_TOP1 ? (top1 || (in_k && above))
-               : a.mode == LASER_MODE_TOPK_ONLY ? in_k : (top1 || above);
-        }
-        a.row_ok[row] = ok ? 1 : 0;
-        a.row_arg[row] = A;
-    }
-}
-
-// One thread per sequence: longest accepted prefix, then the correction token (Sec. 2.1).
-__global__ void head_scan_kernel(const int32_t* row_ok, const int32_t* row_arg, const int32_t* drafts,
-                                 const int32_t* draft_len, int B, int K, int32_t* accept_len, int32_t* out_tokens) {
-    const int b = blockIdx.x * blockDim.x + threadIdx.x, R = K + 1;
-    if (b >= B) return;
-    int dl = draft_len[b];
-    dl = dl < 0 ? 0 : (dl > K ? K : dl);
-    int n = 0;
-    while (n < dl && row_ok[b * R + n]) ++n;
-    accept_len[b] = n;
-    int32_t* out = out_tokens + (size_t)b * R;
-    for (int j = 0; j < R; ++j) out[j] = j < n ? drafts[(size_t)b * K + j] : (j == n ? row_arg[b * R + n] : -1);
-}
-
-// Device buffers of the streaming head (at most 16 rows): the row's draft token, and per (row, vocabulary chunk) the
-// partial statistics that lm_head_kernel leaves for accept_kernel.
+// Device buffers of the head: the rows' candidate lists, and per (row, vocabulary chunk) the partial statistics that
+// pass 1 leaves for accept_kernel.
 struct HeadBufs {
-    int32_t* row_x; float* hp_max; float* hp_sum; int32_t* hp_arg; float* hp_topv; int32_t* hp_topi; float* hp_lx;
+    int32_t* cand_beg; int32_t* cand_cnt; int32_t* cand_x; int32_t* node_cand; float* cand_lx;
+    float* hp_max; float* hp_sum; int32_t* hp_arg; float* hp_topv; int32_t* hp_topi;
 };
 
-// The streaming head: rows -> lm_head_kernel (every wave a vocabulary chunk) -> accept_kernel. Allocates nothing.
-static int run_head_stream(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len, int B, int K,
-                           int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, float* logits_dbg,
-                           const HeadBufs& hb, hipStream_t stream) {
-    const int M = B * (K + 1);
-    hipLaunchKernelGGL(head_rows_kernel, dim3((M + 255) / 256), dim3(256), 0, stream, drafts, draft_len, B, K,
-                       m->d.vocab, hb.row_x, hb.hp_lx);
-    const int ntiles = m->d.vocab / 16;
-    const int tpw = (ntiles + 1023) / 1024;
-    HeadArgs a{m->d.wlm, h, M, m->d.vocab, m->d.d_model, tpw, m->head_chunks, hb.row_x,
-               hb.hp_max, hb.hp_sum, hb.hp_arg, hb.hp_topv, hb.hp_topi, hb.hp_lx, logits_dbg};
-    dim3 grid((unsigned)((m->head_chunks + 3) / 4), 1u);         // at most 16 rows: one row tile
-    hipLaunchKernelGGL(lm_head_kernel<1>, grid, dim3(256), 0, stream, a);
-    AcceptArgs aa{hb.hp_max, hb.hp_sum, hb.hp_arg, hb.hp_topv, hb.hp_topi, hb.hp_lx, hb.row_x, drafts, draft_len,
-                  K, m->head_chunks, topk, mode, p, accept_len, out_tokens};
+// Chunks per row of the pass-1 kernel a row count takes (the partial arrays must hold rows x this many records).
+static int head_chunks_for(const Model* m, int M) {
+    if (M <= kHeadStreamMaxRows) return m->head_chunks;
+    if (M <= kHeadMidMaxRows && m->d.d_model % kGemmKStep == 0)
+        return (m->d.vocab / 16 + 3) / 4;                          // at most: the 4-wave form has the most workgroups
+    return (m->d.vocab + 127) / 128;
+}
+int head_chunks_cap(const Model* m) {
+    return std::max(m->head_chunks, std::max(head_chunks_for(m, kHeadMidMaxRows), head_chunks_for(m, kHeadMidMaxRows + 1)));
+}
+
+// candidates -> pass 1 -> accept_kernel. Allocates nothing. tokens / parent / n_nodes: the drafts as a pseudo-sequence
+// (parent == NULL: a chain, n_nodes = draft_len).
+static int run_head_bufs(Model* m, const uint16_t* h, const int32_t* tokens, const int32_t* parent, const int32_t* n_nodes, int B, int K,
+                         int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, int32_t* accept_path, float* logits_dbg,
+                         const HeadBufs& hb, hipStream_t stream) {
+    const int M = B * (K + 1), V = m->d.vocab, dm = m->d.d_model;
+    hipLaunchKernelGGL(head_cands_kernel, dim3((B + 63) / 64), dim3(64), 0, stream, tokens, parent, n_nodes, B, K, V,
+                       hb.cand_beg, hb.cand_cnt, hb.cand_x, hb.node_cand, hb.cand_lx);
+    HeadPart hp{hb.cand_beg, hb.cand_cnt, hb.cand_x, hb.cand_lx, hb.hp_max, hb.hp_sum, hb.hp_arg, hb.hp_topv, hb.hp_topi, 0, topk, logits_dbg};
+    if (M <= kHeadStreamMaxRows) {
+        const int ntiles = V / 16;
+        const int tpw = (ntiles + 1023) / 1024;
+        hp.chunks = m->head_chunks;
+        HeadArgs a{m->d.wlm, h, M, V, dm, tpw, hp};
+        dim3 grid((unsigned)((m->head_chunks + 3) / 4), 1u);         // at most 16 rows: one row tile
+        hipLaunchKernelGGL(lm_head_kernel<1>, grid, dim3(256), 0, stream, a);
+    } else if (M <= kHeadMidMaxRows && dm % kGemmKStep == 0) {
+        const GemmMidPlan pl = gemm_mid_plan(M, V, dm, 1, false, 0);
+        hp.chunks = (V / 16 + pl.NW - 1) / pl.NW;                     // = workgroups of the launch
+        GemmMidArgs t{m->d.wlm, h, nullptr, M, V, dm, nullptr, nullptr, nullptr, hp};
+        launch_gemm_mid<EPI_HEAD, false>(t, pl, stream);
+    } else {
+        const int tiles_m = (M + GM_BM - 1) / GM_BM, tiles_n = (V + 127) / 128;
+        hp.chunks = tiles_n;
+        if (m->f16_copies && !m->wlm16) {          // first many-row head: widen the head matrix to fp16 once
+            const uint16_t* src[1] = {m->d.wlm};
+            const size_t n[1] = {(size_t)V * dm};
+            const int rc = widen_copies(src, n, 1, &m->wlm16, stream);
+            if (rc) return rc;
+        }
+        GemmTileArgs t{m->wlm16 ? m->wlm16 : m->d.wlm, h, nullptr, M, V, dm, tiles_m, tiles_n, 1, nullptr, nullptr, hp};
+        const dim3 grid(gemm_mfma_grid(tiles_m, tiles_n));
+        if (m->wlm16) hipLaunchKernelGGL((gemm_mfma_kernel<GEPI_HEAD, 128, false, true>), grid, dim3(256), 0, stream, t);
+        else hipLaunchKernelGGL((gemm_mfma_kernel<GEPI_HEAD, 128, false, false>), grid, dim3(256), 0, stream, t);
+    }
+    AcceptArgs aa{hb.hp_max, hb.hp_sum, hb.hp_arg, hb.hp_topv, hb.hp_topi, hb.cand_beg, hb.cand_cnt, hb.cand_x, hb.cand_lx, hb.node_cand,
+                  tokens, parent, n_nodes, K, hp.chunks, topk, mode, p, accept_len, out_tokens, accept_path};
     hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(256), 0, stream, aa);
     LASER_HIP_CHECK(hipGetLastError());
     return LASER_OK;
 }
 
-int run_head(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len, int B, int K,
-             int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, float* logits_dbg,
+int run_head(Model* m, const uint16_t* h, const int32_t* tokens, const int32_t* parent, const int32_t* n_nodes, int B, int K,
+             int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, int32_t* accept_path, float* logits_dbg,
              hipStream_t stream) {
-    const int R = K + 1, M = B * R;
-    if (M > kHeadStreamMaxRows) {
-        hipLaunchKernelGGL(head_rows_kernel, dim3((M + 255) / 256), dim3(256), 0, stream, drafts, draft_len, B, K,
-                           m->d.vocab, m->row_x, m->hp_lx);
-        float* logits = logits_dbg;
-        if (!logits) {                                   // workspace for max_rows x vocab logits, on first use
-            if (!m->logits_ws) {
-                const size_t bytes = (size_t)m->d.max_rows * m->d.vocab * sizeof(float);
-                hipError_t e = hipMalloc((void**)&m->logits_ws, bytes);
-                LASER_REQUIRE(e == hipSuccess, LASER_E_HIP, "hipMalloc of the %zu-byte logits workspace failed: %s", bytes,
-                              hipGetErrorString(e));
-            }
-            logits = m->logits_ws;
-        }
-        if (M <= kHeadMidMaxRows && m->d.d_model % kGemmKStep == 0 && m->d.vocab % 16 == 0) {
-            GemmMidArgs t{m->d.wlm, h, nullptr, M, m->d.vocab, m->d.d_model, logits, nullptr, nullptr};
-            launch_gemm_mid<EPI_F32, false>(t, gemm_mid_plan(M, m->d.vocab, m->d.d_model, 1, false, 0), stream);
-        } else {
-            const int tiles_m = (M + GM_BM - 1) / GM_BM, tiles_n = (m->d.vocab + 127) / 128;
-            GemmTileArgs t{m->d.wlm, h, nullptr, M, m->d.vocab, m->d.d_model, tiles_m, tiles_n, 1, logits, nullptr};
-            hipLaunchKernelGGL((gemm_mfma_kernel<GEPI_F32, 128, false>), dim3(gemm_mfma_grid(tiles_m, tiles_n)), dim3(256), 0,
-                               stream, t);
-        }
-        int32_t* row_ok = m->hp_arg;                     // per-row scratch: the streaming path's buffers are free here
-        int32_t* row_arg = m->hp_arg + M;
-        StatsArgs sa{logits, m->row_x, m->d.vocab, topk, mode, p, row_ok, row_arg};
-        hipLaunchKernelGGL(head_stats_kernel, dim3(M), dim3(256), 0, stream, sa);
-        hipLaunchKernelGGL(head_scan_kernel, dim3((B + 63) / 64), dim3(64), 0, stream, row_ok, row_arg, drafts, draft_len,
-                           B, K, accept_len, out_tokens);
-        LASER_HIP_CHECK(hipGetLastError());
-        return LASER_OK;
-    }
-    HeadBufs hb{m->row_x, m->hp_max, m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx};
-    return run_head_stream(m, h, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens, logits_dbg, hb, stream);
+    HeadBufs hb{m->cand_beg, m->cand_cnt, m->cand_x, m->node_cand, m->cand_lx, m->hp_max, m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi};
+    return run_head_bufs(m, h, tokens, parent, n_nodes, B, K, topk, p, mode, accept_len, out_tokens, accept_path, logits_dbg, hb, stream);
 }
 
 // ---- the head without any allocation ------------------------------------------------------------------------
@@ -377,8 +321,8 @@ struct HeadScratch {
     int32_t hp_arg[kStaticRows * kStaticChunks];
     float hp_topv[kStaticRows * kStaticChunks * KT];
     int32_t hp_topi[kStaticRows * kStaticChunks * KT];
-    float hp_lx[kStaticRows];
-    int32_t row_x[kStaticRows];
+    int32_t cand_beg[kStaticRows], cand_cnt[kStaticRows], cand_x[kStaticRows], node_cand[kStaticRows];
+    float cand_lx[kStaticRows];
 };
 static __device__ __align__(256) unsigned char scratch[sizeof(HeadScratch)];      // 1.19 MiB per GPU, for the life of the process
 
@@ -410,10 +354,10 @@ int run_head_static(Model* m, const uint16_t* h, const int32_t* drafts, const in
     HeadScratch* sc = nullptr;
     int rc = head_scratch(&sc);
     if (rc) return rc;
-    // Nothing in the array has to start at zero: head_rows_kernel resets row_x and hp_lx for the call's rows, and
+    // Nothing in the array has to start at zero: head_cands_kernel rewrites the candidate lists of the call's rows, and
     // lm_head_kernel overwrites every (row, chunk) record that accept_kernel reads.
-    HeadBufs hb{sc->row_x, sc->hp_max, sc->hp_sum, sc->hp_arg, sc->hp_topv, sc->hp_topi, sc->hp_lx};
-    return run_head_stream(m, h, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens, nullptr, hb, stream);
+    HeadBufs hb{sc->cand_beg, sc->cand_cnt, sc->cand_x, sc->node_cand, sc->cand_lx, sc->hp_max, sc->hp_sum, sc->hp_arg, sc->hp_topv, sc->hp_topi};
+    return run_head_bufs(m, h, drafts, nullptr, draft_len, B, K, topk, p, mode, accept_len, out_tokens, nullptr, nullptr, hb, stream);
 }
 
 }  // namespace laser

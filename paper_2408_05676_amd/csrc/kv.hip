@@ -39,6 +39,33 @@ __global__ void commit_kernel(int32_t* len, const int32_t* seq_ids, const int32_
     if (b < B) len[seq_ids[b]] += accept_len[b] + 1;
 }
 
+// Token trees (Sec. 3.3-3.4): the rows of a verify step sit in slots len + 1 + (node index); the accepted branch's
+// rows (accept_path[b][0 .. accept_len[b]), ascending node indices) move to slots len + 1, len + 2, .. behind the
+// pending token before the length grows. A thread owns one channel of one (sequence, layer, head) and moves its
+// elements branch position by branch position: sources never lie before their destinations (path[j] >= j), and a
+// destination is never a later source, so the in-place order j = 0, 1, .. is safe.
+__global__ void kv_compact_kernel(uint16_t* kpages, uint8_t* klpages, uint16_t* vpages, const int32_t* block_table,
+                                  const int32_t* len, const int32_t* seq_ids, const int32_t* accept_len,
+                                  const int32_t* accept_path, int K, int H, int dh, int mpps, int n_pages) {
+    const int h = blockIdx.x, l = blockIdx.y, b = blockIdx.z, c = threadIdx.x;
+    const int slot = seq_ids[b], len0 = len[slot];
+    int a = accept_len[b];
+    a = a < 0 ? 0 : (a > K ? K : a);
+    const int32_t* bt = block_table + (size_t)slot * mpps;
+    for (int j = 0; j < a; ++j) {
+        const int i = accept_path[(size_t)b * K + j];
+        if (i < j || i >= K) break;                     // not a branch of this step's tree: nothing more to move
+        if (i == j) continue;
+        const int src = len0 + 1 + i, dst = len0 + 1 + j;
+        const size_t sb = (((size_t)l * n_pages + bt[src / kPageSize]) * H + h) * kPageSize * dh;
+        const size_t db = (((size_t)l * n_pages + bt[dst / kPageSize]) * H + h) * kPageSize * dh;
+        const int st = src % kPageSize, dt = dst % kPageSize;
+        kpages[db + (size_t)dt * dh + c] = kpages[sb + (size_t)st * dh + c];
+        klpages[db + (size_t)dt * dh + c] = klpages[sb + (size_t)st * dh + c];
+        vpages[db + (size_t)c * kPageSize + dt] = vpages[sb + (size_t)c * kPageSize + st];
+    }
+}
+
 __global__ void ctx_advance_kernel(int32_t* ctx_tail, int32_t* pending, const int32_t* out_tokens,
                                    const int32_t* accept_len, int B, int K, int n_max) {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
@@ -216,7 +243,9 @@ extern "C" int laser_kv_read_lens(laser_kv* h, const int32_t* seq_ids, int B, in
     return LASER_OK;
 }
 
-extern "C" int laser_kv_commit(laser_kv* h, const int32_t* seq_ids, const int32_t* accept_len, int B, void* stream) {
+// laser_kv_commit and laser_kv_commit_tree (accept_path != NULL: compact the accepted branch first)
+static int commit_impl(laser_kv* h, const int32_t* seq_ids, const int32_t* accept_len, const int32_t* accept_path, int B, int K,
+                       void* stream) {
     KV* kv = reinterpret_cast<KV*>(h);
     LASER_REQUIRE(kv != nullptr && B >= 0, LASER_E_INVALID_ARG, "bad argument");
     if (B == 0) return LASER_OK;
@@ -226,7 +255,9 @@ extern "C" int laser_kv_commit(laser_kv* h, const int32_t* seq_ids, const int32_
     for (int b = 0; b < B; ++b) {
         // the device adds accept_len + 1 <= rows of the verify step before it
         LASER_REQUIRE(kv->h_last_rows[seq_ids[b]] > 0, LASER_E_INVALID_ARG,
-                      "laser_kv_commit on slot %d without a verify step before it", seq_ids[b]);
+                      "commit on slot %d without a verify step before it", seq_ids[b]);
+        LASER_REQUIRE(!accept_path || kv->h_last_rows[seq_ids[b]] == K + 1, LASER_E_INVALID_ARG,
+                      "slot %d: the verify step before this commit had %d rows, not K + 1 = %d", seq_ids[b], kv->h_last_rows[seq_ids[b]], K + 1);
     }
     const int32_t* ids_dev = nullptr;
     int rc = kv->stage_ids(seq_ids, B, (hipStream_t)stream, &ids_dev);
@@ -235,9 +266,24 @@ extern "C" int laser_kv_commit(laser_kv* h, const int32_t* seq_ids, const int32_
         kv->h_len_ub[seq_ids[b]] += kv->h_last_rows[seq_ids[b]];
         kv->h_last_rows[seq_ids[b]] = 0;
     }
+    if (accept_path && K > 0 && kv->d.n_layers > 0)
+        hipLaunchKernelGGL(kv_compact_kernel, dim3(kv->d.n_heads, kv->d.n_layers, B), dim3(kv->d.head_dim), 0, (hipStream_t)stream,
+                           kv->kpages, kv->klpages, kv->vpages, kv->block_table, kv->len, ids_dev, accept_len, accept_path, K,
+                           kv->d.n_heads, kv->d.head_dim, kv->d.max_pages_per_seq, kv->d.n_pages);
     hipLaunchKernelGGL(commit_kernel, dim3((B + 63) / 64), dim3(64), 0, (hipStream_t)stream, kv->len, ids_dev, accept_len, B);
     LASER_HIP_CHECK(hipGetLastError());
     return LASER_OK;
+}
+
+extern "C" int laser_kv_commit(laser_kv* h, const int32_t* seq_ids, const int32_t* accept_len, int B, void* stream) {
+    return commit_impl(h, seq_ids, accept_len, nullptr, B, 0, stream);
+}
+
+extern "C" int laser_kv_commit_tree(laser_kv* h, const int32_t* seq_ids, const int32_t* accept_len, const int32_t* accept_path,
+                                    int B, int K, void* stream) {
+    LASER_REQUIRE(K >= 0 && K <= LASER_MAX_DRAFT, LASER_E_INVALID_ARG, "K %d outside 0..%d", K, LASER_MAX_DRAFT);
+    LASER_REQUIRE(B <= 0 || K == 0 || accept_path, LASER_E_INVALID_ARG, "accept_path is NULL");
+    return commit_impl(h, seq_ids, accept_len, K > 0 ? accept_path : nullptr, B, K, stream);
 }
 
 extern "C" int laser_ctx_advance(int32_t* ctx_tail, int32_t* pending, const int32_t* out_tokens,

@@ -20,9 +20,10 @@ int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, 
 int fused_status(Model* m, hipStream_t stream, int* aborted);
 int fused_read_trace(Model* m, hipStream_t stream, long long* out, int max_elems, int* nwg, int* cap);
 
-int run_head(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len, int B, int K,
-             int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, float* logits_dbg,
+int run_head(Model* m, const uint16_t* h, const int32_t* tokens, const int32_t* parent, const int32_t* n_nodes, int B, int K,
+             int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, int32_t* accept_path, float* logits_dbg,
              hipStream_t stream);
+int head_chunks_cap(const Model* m);
 int run_head_static(Model* m, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len, int B, int K,
                     int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, hipStream_t stream);
 
@@ -36,17 +37,35 @@ __device__ inline float block_sum_256(float v, float* sm /*[4]*/) {
     return sm[0] + sm[1] + sm[2] + sm[3];
 }
 
-// One block per row: token lookup, embedding gather, first RMSNorm, row position.
+// One thread per row: where the row sits. Row r of sequence b holds the pending token (r = 0) or node r - 1 of the
+// drafts' pseudo-sequence (Sec. 3.3). Its key/value go to cache slot len + r; its position is len + its depth in the
+// token tree (chain: depth = r); it attends to the committed cache and to the rows on its own branch (bit mask).
+__global__ void rows_kernel(const int32_t* __restrict__ parent, const int32_t* __restrict__ n_nodes, const int32_t* __restrict__ seq_ids,
+                            const int32_t* __restrict__ lens, int B, int R, int32_t* __restrict__ row_pos,
+                            int32_t* __restrict__ row_slot, unsigned long long* __restrict__ row_anc) {
+    const int m = blockIdx.x * blockDim.x + threadIdx.x;
+    if (m >= B * R) return;
+    const int b = m / R, r = m % R, K = R - 1;
+    const int len = lens[seq_ids[b]];
+    int nn = n_nodes[b];
+    nn = nn < 0 ? 0 : (nn > K ? K : nn);
+    unsigned long long anc = 1ull;                 // the pending token's row
+    int depth = 0;
+    for (int i = r - 1; i >= 0; i = tree_parent_of(parent, b, K, i, nn)) { anc |= 1ull << (i + 1); ++depth; }
+    row_pos[m] = len + depth;
+    row_slot[m] = len + r;
+    row_anc[m] = anc;
+}
+
+// One block per row: token lookup, embedding gather, first RMSNorm.
 __global__ __launch_bounds__(256) void embed_rmsnorm_kernel(
     const uint16_t* __restrict__ emb, const float* __restrict__ gain, const int32_t* __restrict__ pending,
-    const int32_t* __restrict__ drafts, const int32_t* __restrict__ draft_len, const int32_t* __restrict__ seq_ids,
-    const int32_t* __restrict__ lens, int R, int d, int vocab, float eps,
-    float* __restrict__ x, uint16_t* __restrict__ xn, uint16_t* __restrict__ xn_lo, int32_t* __restrict__ row_pos) {
+    const int32_t* __restrict__ drafts, const int32_t* __restrict__ draft_len, int R, int d, int vocab, float eps,
+    float* __restrict__ x, uint16_t* __restrict__ xn, uint16_t* __restrict__ xn_lo) {
     __shared__ float sm[4];
     const int m = blockIdx.x, b = m / R, r = m % R, K = R - 1;
     int tok = r == 0 ? pending[b] : ((r - 1) < draft_len[b] ? drafts[(size_t)b * K + r - 1] : 0);
     if (tok < 0 || tok >= vocab) tok = 0;
-    if (threadIdx.x == 0) row_pos[m] = lens[seq_ids[b]] + r;
     const uint16_t* e = emb + (size_t)tok * d;
     float ss = 0.f;
     for (int i = threadIdx.x; i < d; i += 256) { float v = bf16_to_f32(e[i]); ss += v * v; }
@@ -223,14 +242,50 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
 
 constexpr int kSkinnyMaxRows = 80;   // beyond this the weights would be streamed more than once
 
-// bf16 -> fp16 copy of a weight matrix, 8 elements per thread and iteration
-__global__ __launch_bounds__(256) void widen_weights_kernel(const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, size_t n8) {
+// bf16 -> fp16 copy of a weight matrix, 8 elements per thread and iteration; counts the values whose magnitude fp16
+// cannot hold (they would become infinities)
+__global__ __launch_bounds__(256) void widen_weights_kernel(const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, size_t n8,
+                                                            int* __restrict__ overflow) {
+    int bad = 0;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
         Frag8 f;
         f.u = reinterpret_cast<const uint4*>(src)[i];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) bad += (f.h[j] & 0x7FFFu) > 0x477Fu ? 1 : 0;     // |w| > 65280 (bf16 pattern), inf and NaN included
         bf16x8_to_f16x8(f);
         reinterpret_cast<uint4*>(dst)[i] = f.u;
     }
+    if (bad) atomicAdd(overflow, bad);
+}
+
+// fp16 copies of `n` bf16 matrices for the tiled many-row kernels (made once, at the first call that needs them; that
+// call synchronises the stream). All or nothing: on failure nothing is kept. LASER_E_LIMIT if a weight does not fit fp16.
+int widen_copies(const uint16_t* const* src, const size_t* elems, int n, uint16_t** dst, hipStream_t stream) {
+    uint16_t* cp[4] = {nullptr, nullptr, nullptr, nullptr};
+    int* flag = nullptr;
+    auto drop = [&] { for (int i = 0; i < n; ++i) if (cp[i]) (void)hipFree(cp[i]); if (flag) (void)hipFree(flag); };
+    hipError_t e = hipMalloc((void**)&flag, sizeof(int));
+    for (int i = 0; i < n && e == hipSuccess; ++i) e = hipMalloc((void**)&cp[i], elems[i] * 2);
+    if (e == hipSuccess) e = hipMemsetAsync(flag, 0, sizeof(int), stream);
+    if (e != hipSuccess) {
+        drop();
+        set_error("allocating the fp16 weight copies failed: %s", hipGetErrorString(e));
+        return LASER_E_HIP;
+    }
+    for (int i = 0; i < n; ++i)
+        hipLaunchKernelGGL(widen_weights_kernel, dim3(2048), dim3(256), 0, stream, src[i], cp[i], elems[i] / 8, flag);
+    int bad = 0;
+    e = hipMemcpyAsync(&bad, flag, sizeof(int), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess || bad) {
+        drop();
+        if (e != hipSuccess) { set_error("widening the weights to fp16 failed: %s", hipGetErrorString(e)); return LASER_E_HIP; }
+        set_error("%d weights exceed the fp16 range (|w| > 65280): set option f16_copies = 0 to stream them as bf16", bad);
+        return LASER_E_LIMIT;
+    }
+    (void)hipFree(flag);
+    for (int i = 0; i < n; ++i) dst[i] = cp[i];
+    return LASER_OK;
 }
 
 // Reduction parts for a tiled launch of `tiles` 128 x 128 tiles. Two workgroups share a CU ("slots" = 2 x CUs) and a
@@ -351,7 +406,7 @@ static int launch_gemm(GemmArgs& a_in, hipStream_t stream) {
 // ------------------------------------------------------------------------------------------------
 // One block per row: rotate q and k, store q (fp16) and the row's k, v into its cache slot.
 struct RopeArgs {
-    const float* qkv; const int32_t* row_pos; const int32_t* seq_ids; const int32_t* block_table;
+    const float* qkv; const int32_t* row_pos; const int32_t* row_slot; const int32_t* seq_ids; const int32_t* block_table;
     const float2* rope; uint16_t* q; uint16_t* q_lo; uint16_t* kpages; uint8_t* klpages; uint16_t* vpages;
     int R, d, H, dh, mpps, layer, n_pages;
     int M, ny, B;          // rows, blocks per row; blocks past M * ny write the values (see below)
@@ -382,7 +437,7 @@ __device__ inline void write_values(const RopeArgs& a, int blk) {
     const int item = blk * per_blk + (int)threadIdx.x / a.dh, c = (int)threadIdx.x % a.dh;
     if (item >= a.B * a.H) return;
     const int b = item / a.H, h = item % a.H;
-    const int pos0 = a.row_pos[b * a.R];                    // slot of the sequence's first row
+    const int pos0 = a.row_slot[b * a.R];                   // slot of the sequence's first row
     const int32_t* bt = a.block_table + (size_t)a.seq_ids[b] * a.mpps;
     const float* v = a.qkv + (size_t)b * a.R * 3 * a.d + 2 * a.d + (size_t)h * a.dh + c;
     for (int pg = pos0 / kPageSize; pg <= (pos0 + a.R - 1) / kPageSize; ++pg) {
@@ -413,8 +468,8 @@ template <int NPART>
 __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a) {
     if ((int)blockIdx.x >= a.M * a.ny) { write_values<NPART>(a, (int)blockIdx.x - a.M * a.ny); return; }
     const int m = blockIdx.x / a.ny, by = blockIdx.x % a.ny, b = m / a.R;
-    const int pos = a.row_pos[m];
-    const int pg = a.block_table[(size_t)a.seq_ids[b] * a.mpps + pos / kPageSize], tp = pos % kPageSize;
+    const int pos = a.row_pos[m], slot = a.row_slot[m];       // rotary position (depth in the token tree) / cache slot (row order)
+    const int pg = a.block_table[(size_t)a.seq_ids[b] * a.mpps + slot / kPageSize], tp = slot % kPageSize;
     const int half = a.dh / 2;                            // a multiple of 4 (dh is 64 or 128)
     const float* row = a.qkv + (size_t)m * 3 * a.d;
     // a thread takes 4 consecutive rotary pairs (i .. i+3, partners at + half) of one head: 16-byte loads, 8-byte stores
@@ -458,6 +513,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a) {
 struct AttnArgs {
     const uint16_t* q; const uint16_t* q_lo; const uint16_t* kpages; const uint8_t* klpages; const uint16_t* vpages;
     const int32_t* seq_ids; const int32_t* lens; const int32_t* block_table;
+    const unsigned long long* row_anc;     // per row: the rows of its sequence it attends to (itself and its ancestors)
     uint16_t* out; uint16_t* out_lo; float* part;
     int R, d, H, mpps, layer, n_pages, nsplit, nqt;
     int split_pages;       // pages per context split (kSplitPages, or "all" when the launch is not split)
@@ -490,6 +546,7 @@ __global__ __launch_bounds__(NWV * 64, NWV == 4 ? 4 : 2) void attn_kernel(AttnAr
     // with eight waves, reduce in a different order and may differ from the split form in the last bits.
     const int p0 = split * a.split_pages, p1 = min(npages, p0 + a.split_pages);
 
+    const unsigned long long anc = a.row_anc[(size_t)b * a.R + min(qrow, a.R - 1)];
     Frag8 bq[NC32], bql[NC32];
     {
         const int rowc = min(qrow, a.R - 1);
@@ -546,7 +603,8 @@ __global__ __launch_bounds__(NWV * 64, NWV == 4 ? 4 : 2) void attn_kernel(AttnAr
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int t = p * kPageSize + 4 * g + i;
-            const bool vis = (qrow < a.R) && (t <= len + qrow);
+            // committed slots are visible to every row; a new slot (row t - len of this step) only along the row's branch
+            const bool vis = (qrow < a.R) && (t < len || (t - len < a.R && ((anc >> (t - len)) & 1ull)));
             sv[i] = vis ? s[i] * a.scale : -INFINITY;
             mx = fmaxf(mx, sv[i]);
         }
@@ -673,31 +731,22 @@ __global__ void rope_table_kernel(float2* tab, int max_pos, int half, int dh, do
 }
 
 // ------------------------------------------------------------------------------------------------
+// parent: NULL for a chain of drafts, else the token tree's parent array (see tree_parent_of)
 static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, const int32_t* drafts,
-                   const int32_t* draft_len, int B, int K, int max_len_ub, hipStream_t stream) {
+                   const int32_t* parent, const int32_t* draft_len, int B, int K, int max_len_ub, hipStream_t stream) {
     const laser_model_desc& d = m->d;
     const int R = K + 1, M = B * R, dm = d.d_model, F = d.ffn;
+    hipLaunchKernelGGL(rows_kernel, dim3((M + 255) / 256), dim3(256), 0, stream, parent, draft_len, ids_dev, kv->len, B, R,
+                       m->row_pos, m->row_slot, m->row_anc);
     hipLaunchKernelGGL(embed_rmsnorm_kernel, dim3(M), dim3(256), 0, stream, d.emb, d.g1, pending, drafts, draft_len,
-                       ids_dev, kv->len, R, dm, d.vocab, d.eps, m->x, m->xn, m->xn_lo, m->row_pos);
-    if (M > kSkinnyMaxRows && !m->w16[0]) {
+                       R, dm, d.vocab, d.eps, m->x, m->xn, m->xn_lo);
+    if (M > kSkinnyMaxRows && m->f16_copies && !m->w16[0]) {
         // first many-row step: widen the four projection matrices to fp16 once (same rounding as the kernels' own)
         const size_t n[4] = {(size_t)d.n_layers * 3 * dm * dm, (size_t)d.n_layers * dm * dm, (size_t)d.n_layers * 2 * F * dm,
                              (size_t)d.n_layers * dm * F};
         const uint16_t* src[4] = {d.wqkv, d.wo, d.wgu, d.wdown};
-        uint16_t* cp[4] = {nullptr, nullptr, nullptr, nullptr};      // published only when all four exist
-        for (int i = 0; i < 4; ++i) {
-            const hipError_t e = hipMalloc((void**)&cp[i], n[i] * 2);
-            if (e != hipSuccess) {
-                for (int j = 0; j < i; ++j) (void)hipFree(cp[j]);
-                set_error("hipMalloc of the %zu-byte fp16 weight copy failed: %s", n[i] * 2, hipGetErrorString(e));
-                return LASER_E_HIP;
-            }
-        }
-        for (int i = 0; i < 4; ++i) {
-            hipLaunchKernelGGL(widen_weights_kernel, dim3(2048), dim3(256), 0, stream, src[i], cp[i], n[i] / 8);
-            m->w16[i] = cp[i];
-        }
-        LASER_HIP_CHECK(hipGetLastError());
+        const int rc = widen_copies(src, n, 4, m->w16, stream);
+        if (rc) return rc;
     }
     if (M > 16 && !m->kpart) {
         // workspace for reduction-split partial results: up to 8 parts of [max_rows][d] or 2 of [max_rows][3 d]
@@ -729,11 +778,11 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
         if (l > 0)
             launch_rmsnorm(M, stream, m->x, d.g1 + (size_t)l * dm, dm, d.eps, m->xn, m->xn_lo, (const float*)m->kpart, pend, (size_t)M * dm);
         pend = 0;
-        const bool many = M > kSkinnyMaxRows;      // tiled path: weights from the fp16 copy
+        const bool many = M > kSkinnyMaxRows && m->w16[0];      // tiled path: weights from the fp16 copy (if kept)
         GemmArgs g{d.wqkv + (size_t)l * 3 * dm * dm, many ? m->w16[0] + (size_t)l * 3 * dm * dm : nullptr, m->xn, m->xn_lo, M, 3 * dm, dm, 1, m->qkv, nullptr};
         g.part = m->kpart; g.part_floats = m->kpart_floats; g.want_split = m->ksplit_opt[0]; g.mid_waves = m->mid_waves;
         if ((rc = launch_gemm<EPI_F32>(g, stream))) return rc;
-        RopeArgs ra{g.n_part ? m->kpart : m->qkv, m->row_pos, ids_dev, kv->block_table, m->rope, m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages,
+        RopeArgs ra{g.n_part ? m->kpart : m->qkv, m->row_pos, m->row_slot, ids_dev, kv->block_table, m->rope, m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages,
                     R, dm, d.n_heads, m->dh, kv->d.max_pages_per_seq, l, kv->d.n_pages,
                     M, std::max(1, std::min(4, dm / 2048)), B, std::max(1, g.n_part), (size_t)M * 3 * dm};
         const int v_blocks = (B * d.n_heads + 256 / m->dh - 1) / (256 / m->dh);
@@ -744,7 +793,7 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
             case 4: hipLaunchKernelGGL(rope_kv_kernel<4>, rg, dim3(256), 0, stream, ra); break;
             default: hipLaunchKernelGGL(rope_kv_kernel<8>, rg, dim3(256), 0, stream, ra); break;
         }
-        AttnArgs aa{m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages, ids_dev, kv->len, kv->block_table, m->attn, m->attn_lo, m->att_part,
+        AttnArgs aa{m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages, ids_dev, kv->len, kv->block_table, m->row_anc, m->attn, m->attn_lo, m->att_part,
                     R, dm, d.n_heads, kv->d.max_pages_per_seq, l, kv->d.n_pages, nsplit, nqt, split_pages, 1.0f / sqrtf((float)m->dh)};
         dim3 ag(d.n_heads, B, nsplit * nqt);
         // unsplit contexts in a launch of fewer than two workgroups per compute unit: eight waves share the pages
@@ -791,8 +840,8 @@ using namespace laser;
 extern "C" int laser_model_destroy(laser_model* h) {
     if (!h) return LASER_OK;
     Model* m = reinterpret_cast<Model*>(h);
-    void* ptrs[] = {m->kpart, m->w16[0], m->w16[1], m->w16[2], m->w16[3], m->x, m->xn, m->xn_lo, m->q_lo, m->attn_lo, m->qkv, m->q, m->attn, m->act, m->row_pos, m->att_part, m->rope, m->hp_max,
-                    m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->hp_lx, m->row_x, m->logits_ws};
+    void* ptrs[] = {m->kpart, m->wlm16, m->w16[0], m->w16[1], m->w16[2], m->w16[3], m->x, m->xn, m->xn_lo, m->q_lo, m->attn_lo, m->qkv, m->q, m->attn, m->act, m->row_pos, m->att_part, m->rope, m->hp_max,
+                    m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->cand_beg, m->cand_cnt, m->cand_x, m->node_cand, m->cand_lx, m->row_slot, m->row_anc};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     for (hipEvent_t e : m->prof_ev) (void)hipEventDestroy(e);
     fused_free(m);
@@ -823,8 +872,11 @@ extern "C" int laser_model_create(const laser_model_desc* desc, void* stream_, l
 #define M_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) { set_error("%s: %s", #expr, hipGetErrorString(e_)); return fail(LASER_E_HIP); } } while (0)
     const size_t R = (size_t)d.max_rows, dm = (size_t)d.d_model;
     M_TRY(hipMalloc((void**)&m->xn, R * dm * 2));
-    M_TRY(hipMalloc((void**)&m->row_x, R * 4));
-    M_TRY(hipMalloc((void**)&m->hp_lx, R * 4));
+    M_TRY(hipMalloc((void**)&m->cand_beg, R * 4));
+    M_TRY(hipMalloc((void**)&m->cand_cnt, R * 4));
+    M_TRY(hipMalloc((void**)&m->cand_x, R * 4));
+    M_TRY(hipMalloc((void**)&m->node_cand, R * 4));
+    M_TRY(hipMalloc((void**)&m->cand_lx, R * 4));
     if (d.n_layers > 0) {
         M_TRY(hipMalloc((void**)&m->x, R * dm * 4));
         M_TRY(hipMalloc((void**)&m->qkv, R * dm * 3 * 4));
@@ -835,6 +887,8 @@ extern "C" int laser_model_create(const laser_model_desc* desc, void* stream_, l
         M_TRY(hipMalloc((void**)&m->attn_lo, R * dm * 2));
         M_TRY(hipMalloc((void**)&m->act, R * (size_t)d.ffn * 2));
         M_TRY(hipMalloc((void**)&m->row_pos, R * 4));
+        M_TRY(hipMalloc((void**)&m->row_slot, R * 4));
+        M_TRY(hipMalloc((void**)&m->row_anc, R * 8));
         const size_t nt = (size_t)d.max_pos * (dh / 2);
         M_TRY(hipMalloc((void**)&m->rope, nt * sizeof(float2)));
         hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((nt + 255) / 256)), dim3(256), 0, stream, m->rope,
@@ -845,7 +899,7 @@ extern "C" int laser_model_create(const laser_model_desc* desc, void* stream_, l
         const int ntiles = d.vocab / 16;
         const int tpw = (ntiles + 1023) / 1024;
         m->head_chunks = (ntiles + tpw - 1) / tpw;
-        const size_t n = R * (size_t)m->head_chunks;
+        const size_t n = R * (size_t)head_chunks_cap(m);      // the most records per row any row count produces
         M_TRY(hipMalloc((void**)&m->hp_max, n * 4));
         M_TRY(hipMalloc((void**)&m->hp_sum, n * 4));
         M_TRY(hipMalloc((void**)&m->hp_arg, n * 4));
@@ -870,9 +924,10 @@ static int check_step_args(const Model* m, int B, int K, int topk, int mode, con
     return LASER_OK;
 }
 
-extern "C" int laser_verify_step(laser_model* mh, laser_kv* kh, const int32_t* seq_ids, const int32_t* pending,
-                                 const int32_t* drafts, const int32_t* draft_len, int B, int K, int topk, float p,
-                                 int mode, int32_t* accept_len, int32_t* out_tokens, float* logits_dbg, void* stream_) {
+// laser_verify_step (parent == NULL: a chain, may take the persistent kernel) and laser_verify_tree
+static int verify_impl(laser_model* mh, laser_kv* kh, const int32_t* seq_ids, const int32_t* pending, const int32_t* drafts,
+                       const int32_t* parent, const int32_t* draft_len, int B, int K, int topk, float p, int mode,
+                       int32_t* accept_len, int32_t* out_tokens, int32_t* accept_path, float* logits_dbg, void* stream_) {
     Model* m = reinterpret_cast<Model*>(mh);
     KV* kv = reinterpret_cast<KV*>(kh);
     hipStream_t stream = (hipStream_t)stream_;
@@ -903,17 +958,33 @@ extern "C" int laser_verify_step(laser_model* mh, laser_kv* kh, const int32_t* s
     }
     const int32_t* ids_dev = nullptr;
     if ((rc = kv->stage_ids(seq_ids, B, stream, &ids_dev))) return rc;
-    if (m->use_fused && fused_supported(m, B, K, max_ub)) {
+    if (!parent && m->use_fused && fused_supported(m, B, K, max_ub)) {
         rc = run_fused(m, kv, ids_dev, pending, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens,
                        logits_dbg, max_ub, stream);
     } else {
-        if ((rc = forward(m, kv, ids_dev, pending, drafts, draft_len, B, K, max_ub, stream))) return rc;
-        rc = run_head(m, m->xn, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens, logits_dbg, stream);
+        if ((rc = forward(m, kv, ids_dev, pending, drafts, parent, draft_len, B, K, max_ub, stream))) return rc;
+        rc = run_head(m, m->xn, drafts, parent, draft_len, B, K, topk, p, mode, accept_len, out_tokens, accept_path, logits_dbg, stream);
     }
     // only a step that has been enqueued may be committed
     if (rc == LASER_OK)
         for (int b = 0; b < B; ++b) kv->h_last_rows[seq_ids[b]] = R;
     return rc;
+}
+
+extern "C" int laser_verify_step(laser_model* mh, laser_kv* kh, const int32_t* seq_ids, const int32_t* pending,
+                                 const int32_t* drafts, const int32_t* draft_len, int B, int K, int topk, float p,
+                                 int mode, int32_t* accept_len, int32_t* out_tokens, float* logits_dbg, void* stream) {
+    return verify_impl(mh, kh, seq_ids, pending, drafts, nullptr, draft_len, B, K, topk, p, mode, accept_len, out_tokens, nullptr,
+                       logits_dbg, stream);
+}
+
+extern "C" int laser_verify_tree(laser_model* mh, laser_kv* kh, const int32_t* seq_ids, const int32_t* pending,
+                                 const int32_t* tree_tokens, const int32_t* tree_parent, const int32_t* tree_len, int B, int K,
+                                 int topk, float p, int mode, int32_t* accept_len, int32_t* out_tokens, int32_t* accept_path,
+                                 float* logits_dbg, void* stream) {
+    LASER_REQUIRE(B <= 0 || K == 0 || (tree_parent && accept_path), LASER_E_INVALID_ARG, "NULL tree_parent or accept_path");
+    return verify_impl(mh, kh, seq_ids, pending, tree_tokens, K > 0 ? tree_parent : nullptr, tree_len, B, K, topk, p, mode, accept_len,
+                       out_tokens, accept_path, logits_dbg, stream);
 }
 
 extern "C" int laser_verify_head(laser_model* mh, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len,
@@ -924,7 +995,7 @@ extern "C" int laser_verify_head(laser_model* mh, const uint16_t* h, const int32
     if (rc) return rc;
     if (B == 0) return LASER_OK;
     LASER_REQUIRE(h != nullptr, LASER_E_INVALID_ARG, "h is NULL");
-    return run_head(m, h, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens, logits_dbg, (hipStream_t)stream);
+    return run_head(m, h, drafts, nullptr, draft_len, B, K, topk, p, mode, accept_len, out_tokens, nullptr, logits_dbg, (hipStream_t)stream);
 }
 
 extern "C" int laser_verify_head_static(laser_model* mh, const uint16_t* h, const int32_t* drafts, const int32_t* draft_len,
@@ -974,6 +1045,11 @@ extern "C" int laser_model_set_option(laser_model* mh, const char* name, int val
     if (std::string(name) == "fused") { m->use_fused = value; return LASER_OK; }
     if (std::string(name) == "fused_trace") { m->fused_trace = value; return LASER_OK; }
     if (std::string(name) == "split_ffn") { m->split_ffn = value; return LASER_OK; }
+    if (std::string(name) == "f16_copies") {
+        LASER_REQUIRE(value == 0 || value == 1, LASER_E_INVALID_ARG, "f16_copies must be 0 or 1");
+        m->f16_copies = value;
+        return LASER_OK;
+    }
     if (std::string(name) == "mid_waves") {
         LASER_REQUIRE(value == 0 || value == 4 || value == 8, LASER_E_INVALID_ARG, "mid_waves must be 0 (choose), 4 or 8");
         m->mid_waves = value;

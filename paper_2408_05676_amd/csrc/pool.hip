@@ -315,6 +315,230 @@ __global__ __launch_bounds__(64) void retrieve_kernel(RetrieveArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------- token trees
+// Tree-based drafting (Sec. 3.3): the sub-tree of the key's trie below the node the context suffix reaches, cut to
+// its K most frequent nodes. A node is a path of successor tokens; its frequency is the number of occurrences of the
+// suffix whose continuation starts with that path. Nodes are taken best first: always the best node not yet taken
+// whose parent is taken (higher frequency, then smaller depth, then the parent taken earlier, then the smaller token
+// id); a child is never more frequent than its parent, so these are the K best nodes of the whole sub-tree.
+// One wavefront per context. Taking a node means one vote over the occurrences that continue with its path
+// (re-checked against the path, so any number of occurrences works) to find its children and their frequencies;
+// the best K - (taken) of them join the frontier. The pseudo-sequence lists the taken nodes depth-first, siblings
+// in the order taken.
+constexpr int kTreeMax = LASER_MAX_TREE;                       // nodes of one tree
+constexpr int kFrontier = kTreeMax * (kTreeMax + 1) / 2 + 16;  // every expansion adds at most K - taken children
+
+struct TreeArgs {
+    const int32_t* P; const uint32_t* seq_end; const uint32_t* sa; const IndexEntry* table;
+    uint64_t cap_mask;
+    const int64_t* keys; const int32_t* ctx_tail;
+    int B, n_min, n_max, K, min_tokens;
+    int32_t* tree_tokens; int32_t* tree_parent; int32_t* tree_freq; int32_t* tree_len; int32_t* match_n;
+};
+
+__global__ __launch_bounds__(64) void retrieve_tree_kernel(TreeArgs a) {
+    __shared__ uint32_t cand[kCand];
+    __shared__ uint32_t cand_end[kCand];
+    __shared__ int vote_tok[kVote];
+    __shared__ int vote_cnt[kVote];
+    __shared__ int sh_distinct;
+    __shared__ int t_tok[kTreeMax], t_par[kTreeMax], t_depth[kTreeMax], t_cnt[kTreeMax];     // taken nodes, in the order taken
+    __shared__ int f_tok[kFrontier], f_cnt[kFrontier], f_par[kFrontier], f_depth[kFrontier];
+    __shared__ int ch_tok[kTreeMax], ch_cnt[kTreeMax];                                       // best children of one expansion
+    __shared__ int path[kTreeMax];
+    __shared__ int b_tok[kTreeMax], b_par[kTreeMax], b_cnt[kTreeMax];                        // best tree seen (pseudo-sequence form)
+    __shared__ int o_tok[kTreeMax], o_par[kTreeMax], o_cnt[kTreeMax], dfs_pos[kTreeMax], stack[kTreeMax];
+
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int64_t key = a.keys[b];
+    const int32_t* tail = a.ctx_tail + (size_t)b * a.n_max;
+    int valid = 0;
+    while (valid < a.n_max && tail[a.n_max - 1 - valid] >= 0) ++valid;
+
+    int best_len = 0, best_n = 0, res_len = 0, res_n = 0;
+    bool done = false;
+    const int n_hi = valid < a.n_max ? valid : a.n_max;
+    for (int n = n_hi; n >= a.n_min && !done && a.K > 0; --n) {
+        // ---- index probe (as in retrieve_kernel) ----
+        const int32_t* w = tail + (a.n_max - n);
+        uint64_t slot = ngram_hash(key, n, w) & a.cap_mask;
+        uint32_t start = 0, count = 0;
+        for (;;) {
+            IndexEntry e = a.table[slot];
+            if (e.count_n == 0) break;
+            if (e.key == key && (int)(e.count_n >> 28) == n) {
+                uint32_t e0 = a.sa[e.start];
+                bool same = true;
+                for (int i = 0; i < n; ++i) same = same && (a.P[e0 - (n - 1) + i] == w[i]);
+                if (same) { start = e.start; count = e.count_n & 0x0FFFFFFFu; break; }
+            }
+            slot = (slot + 1) & a.cap_mask;
+        }
+        if (count == 0) continue;
+        const bool in_lds = count <= (uint32_t)kCand;
+        if (in_lds)
+            for (uint32_t i = lane; i < count; i += 64) {
+                const uint32_t e = a.sa[start + i];
+                cand[i] = e;
+                cand_end[i] = a.seq_end[e];
+            }
+        __syncthreads();
+
+        int taken = 0, fsize = 0;
+        // children of taken node `node` (-1: the root) at depth d: the best K - taken of them go to the frontier
+        auto expand = [&](int node, int d) {
+            for (int i = node, j = d - 1; j >= 0; --j) {           // every lane walks the same path (LDS broadcast reads)
+                if (lane == 0) path[j] = t_tok[i];
+                i = t_par[i];
+            }
+            const int want = a.K - taken;
+            int n_ch = 0;                                            // uniform: entries of ch_*
+            __syncthreads();
+            int vsz = 64;
+            while (vsz < kVote && (uint32_t)vsz < 4u * count) vsz *= 2;
+            const int vfill = vsz / 4 * 3;
+            for (uint32_t nparts = 1;; nparts *= 2) {
+                bool overflow = false;
+                n_ch = 0;
+                for (uint32_t part = 0; part < nparts && !overflow; ++part) {
+                    for (int i = lane; i < vsz; i += 64) { vote_tok[i] = kEmptyTok; vote_cnt[i] = 0; }
+                    if (lane == 0) sh_distinct = 0;
+                    __syncthreads();
+                    for (uint32_t i0 = 0; i0 < count; i0 += 64) {
+                        const uint32_t i = i0 + lane;
+                        if (i < count) {
+                            const uint32_t e = in_lds ? cand[i] : a.sa[start + i];
+                            bool ok = (e + (uint32_t)d + 1u) < (in_lds ? cand_end[i] : a.seq_end[e]);
+                            for (int c = 0; c < d && ok; ++c) ok = a.P[e + 1 + c] == path[c];
+                            if (ok) {
+                                const int tok = a.P[e + d + 1];
+                                const uint32_t hh = fmix32((uint32_t)tok);
+                                if (nparts == 1 || (hh / kVote) % nparts == part) {
+                                    uint32_t s = hh & (vsz - 1);
+                                    for (int probe = 0; probe < vsz; ++probe) {
+                                        int cur = vote_tok[s];
+                                        if (cur == kEmptyTok) {
+                                            const int prev = atomicCAS(&vote_tok[s], kEmptyTok, tok);
+                                            if (prev == kEmptyTok) { atomicAdd(&sh_distinct, 1); cur = tok; }
+                                            else cur = prev;
+                                        }
+                                        if (cur == tok) { atomicAdd(&vote_cnt[s], 1); break; }
+                                        s = (s + 1) & (vsz - 1);
+                                    }
+                                }
+                            }
+                        }
+                        if ((i0 & 1023u) == 960u) {
+                            __syncthreads();
+                            if (sh_distinct > vfill) break;
+                        }
+                    }
+                    __syncthreads();
+                    overflow = sh_distinct > vfill;
+                    __syncthreads();
+                    if (overflow) break;
+                    // this part's best `want` (count desc, token asc), merged into the sorted child list
+                    for (int round = 0; round < want; ++round) {
+                        int bc = 0, bt = 0x7FFFFFFF, bs = -1;
+                        for (int i = lane; i < vsz; i += 64) {
+                            const int c = vote_cnt[i], t = vote_tok[i];
+                            if (c > bc || (c == bc && c > 0 && t < bt)) { bc = c; bt = t; bs = i; }
+                        }
+                        for (int off = 32; off > 0; off >>= 1) {
+                            const int oc = __shfl_xor(bc, off), ot = __shfl_xor(bt, off), os = __shfl_xor(bs, off);
+                            if (oc > bc || (oc == bc && oc > 0 && ot < bt)) { bc = oc; bt = ot; bs = os; }
+                        }
+                        if (bc == 0) break;                          // uniform
+                        // insert (bt, bc) into ch_* (sorted, at most `want` entries); lane 0 does the shifting
+                        int pos = n_ch;
+                        while (pos > 0 && (ch_cnt[pos - 1] < bc || (ch_cnt[pos - 1] == bc && ch_tok[pos - 1] > bt))) --pos;
+                        if (pos < want) {
+                            if (lane == 0) {
+                                const int last = n_ch < want ? n_ch : want - 1;
+                                for (int q = last; q > pos; --q) { ch_tok[q] = ch_tok[q - 1]; ch_cnt[q] = ch_cnt[q - 1]; }
+                                ch_tok[pos] = bt; ch_cnt[pos] = bc;
+                                vote_cnt[bs] = 0;
+                            }
+                            if (n_ch < want) ++n_ch;
+                        } else if (lane == 0) {
+                            vote_cnt[bs] = 0;
+                        }
+                        __syncthreads();
+                        if (pos >= want) break;                      // nothing later in this part can enter either
+                    }
+                    __syncthreads();
+                }
+                if (!overflow) break;
+            }
+            for (int i = lane; i < n_ch; i += 64) {
+                f_tok[fsize + i] = ch_tok[i]; f_cnt[fsize + i] = ch_cnt[i]; f_par[fsize + i] = node; f_depth[fsize + i] = d + 1;
+            }
+            fsize += n_ch;
+            __syncthreads();
+        };
+        expand(-1, 0);
+        while (taken < a.K && fsize > 0) {
+            // best frontier entry: count desc, depth asc, parent asc, token asc
+            int bi = -1, bc = 0, bd = 0, bp = 0, bt = 0;
+            auto better = [](int c, int d, int p, int t, int c2, int d2, int p2, int t2) {
+                return c != c2 ? c > c2 : (d != d2 ? d < d2 : (p != p2 ? p < p2 : t < t2));
+            };
+            for (int i = lane; i < fsize; i += 64)
+                if (bi < 0 || better(f_cnt[i], f_depth[i], f_par[i], f_tok[i], bc, bd, bp, bt)) {
+                    bi = i; bc = f_cnt[i]; bd = f_depth[i]; bp = f_par[i]; bt = f_tok[i];
+                }
+            for (int off = 32; off > 0; off >>= 1) {
+                const int oi = __shfl_xor(bi, off), oc = __shfl_xor(bc, off), od = __shfl_xor(bd, off), op = __shfl_xor(bp, off),
+                          ot = __shfl_xor(bt, off);
+                if (oi >= 0 && (bi < 0 || better(oc, od, op, ot, bc, bd, bp, bt))) { bi = oi; bc = oc; bd = od; bp = op; bt = ot; }
+            }
+            __syncthreads();
+            if (lane == 0) {
+                t_tok[taken] = bt; t_par[taken] = bp; t_depth[taken] = bd; t_cnt[taken] = bc;
+                const int last = fsize - 1;
+                f_tok[bi] = f_tok[last]; f_cnt[bi] = f_cnt[last]; f_par[bi] = f_par[last]; f_depth[bi] = f_depth[last];
+            }
+            --fsize;
+            ++taken;
+            __syncthreads();
+            if (taken < a.K) expand(taken - 1, bd);
+        }
+        // ---- pseudo-sequence: depth-first, siblings in the order taken ----
+        if (lane == 0) {
+            int sp = 0, n_out = 0;
+            for (int i = taken - 1; i >= 0; --i) if (t_par[i] < 0) stack[sp++] = i;
+            while (sp > 0) {
+                const int i = stack[--sp];
+                dfs_pos[i] = n_out;
+                o_tok[n_out] = t_tok[i]; o_cnt[n_out] = t_cnt[i];
+                o_par[n_out] = t_par[i] < 0 ? -1 : dfs_pos[t_par[i]];
+                ++n_out;
+                for (int c = taken - 1; c > i; --c) if (t_par[c] == i) stack[sp++] = c;
+            }
+        }
+        __syncthreads();
+        if (taken >= a.min_tokens) {
+            res_len = taken; res_n = n; done = true;
+        } else if (taken > best_len) {
+            best_len = taken; best_n = n;
+            for (int i = lane; i < taken; i += 64) { b_tok[i] = o_tok[i]; b_par[i] = o_par[i]; b_cnt[i] = o_cnt[i]; }
+            __syncthreads();
+        }
+    }
+    const int *s_tok = o_tok, *s_par = o_par, *s_cnt = o_cnt;
+    if (!done) { res_len = best_len; res_n = best_n; s_tok = b_tok; s_par = b_par; s_cnt = b_cnt; }
+    __syncthreads();
+    for (int i = lane; i < a.K; i += 64) {
+        a.tree_tokens[(size_t)b * a.K + i] = i < res_len ? s_tok[i] : -1;
+        a.tree_parent[(size_t)b * a.K + i] = i < res_len ? s_par[i] : -1;
+        if (a.tree_freq) a.tree_freq[(size_t)b * a.K + i] = i < res_len ? s_cnt[i] : 0;
+    }
+    if (lane == 0) {
+        a.tree_len[b] = res_len;
+        a.match_n[b] = res_len > 0 ? res_n : 0;
+    }
+}
+
 // Appends the tokens a step emitted (out_tokens[b][0 .. accept_len[b]]) to row b of the own-text buffer; a full row
 // drops its oldest tokens (sliding window of `cap`). One workgroup per sequence.
 __global__ __launch_bounds__(256) void own_text_append_kernel(int32_t* own, int32_t* own_len, int cap, const int32_t* out_tokens,
@@ -581,6 +805,25 @@ extern "C" int laser_retrieve_drafts_temp(const laser_pool* pool, const int64_t*
     LASER_REQUIRE(B <= 0 || (own_tokens && own_len), LASER_E_INVALID_ARG, "NULL own-text buffer");
     return retrieve_impl(pool, keys, ctx_tail, own_tokens, own_len, own_cap, B, n_min, n_max, K, min_tokens, drafts,
                          draft_len, match_n, pool_index, stream);
+}
+
+extern "C" int laser_retrieve_tree(const laser_pool* pool, const int64_t* keys, const int32_t* ctx_tail, int B, int n_min, int n_max,
+                                   int K, int min_tokens, int32_t* tree_tokens, int32_t* tree_parent, int32_t* tree_freq,
+                                   int32_t* tree_len, int32_t* match_n, void* stream) {
+    LASER_REQUIRE(pool != nullptr, LASER_E_INVALID_ARG, "pool is NULL");
+    const Pool* p = reinterpret_cast<const Pool*>(pool);
+    LASER_REQUIRE(B >= 0, LASER_E_INVALID_ARG, "B < 0");
+    LASER_REQUIRE(K >= 0 && K <= LASER_MAX_TREE, LASER_E_INVALID_ARG, "K %d outside 0..%d", K, LASER_MAX_TREE);
+    LASER_REQUIRE(n_max >= 1 && n_max <= p->n_max, LASER_E_INVALID_ARG, "n_max %d outside 1..%d (the pool's)", n_max, p->n_max);
+    LASER_REQUIRE(n_min >= 1 && n_min <= n_max, LASER_E_INVALID_ARG, "n_min %d outside 1..n_max", n_min);
+    if (B == 0) return LASER_OK;
+    LASER_REQUIRE(keys && ctx_tail && tree_len && match_n && ((tree_tokens && tree_parent) || K == 0), LASER_E_INVALID_ARG,
+                  "NULL device buffer");
+    TreeArgs a{p->P, p->seq_end, p->sa, p->table, p->cap_mask, keys, ctx_tail, B, n_min, n_max, K, min_tokens < 1 ? 1 : min_tokens,
+               tree_tokens, tree_parent, tree_freq, tree_len, match_n};
+    hipLaunchKernelGGL(retrieve_tree_kernel, dim3(B), dim3(64), 0, (hipStream_t)stream, a);
+    LASER_HIP_CHECK(hipGetLastError());
+    return LASER_OK;
 }
 
 extern "C" int laser_own_text_append(int32_t* own_tokens, int32_t* own_len, int own_cap, const int32_t* out_tokens,

@@ -55,20 +55,25 @@ struct Model {
     uint16_t* q = nullptr;       // [max_rows][d]   rotated queries (fp16)
     uint16_t* attn = nullptr;    // [max_rows][d]
     uint16_t* act = nullptr;     // [max_rows][F]
-    int32_t* row_pos = nullptr;  // [max_rows]
+    int32_t* row_pos = nullptr;  // [max_rows] position of the row's token: committed length + depth in the token tree (chain: + row number)
+    int32_t* row_slot = nullptr; // [max_rows] cache slot of the row's key/value: committed length + row number
+    unsigned long long* row_anc = nullptr;   // [max_rows] bit j: row j of the same sequence is this row or one of its ancestors
     float* att_part = nullptr;   // attention split partials
     size_t att_part_floats = 0;
     float2* rope = nullptr;      // [max_pos][dh/2] (cos, sin)
     // output-head partials
     int head_chunks = 0;
-    float* hp_max = nullptr;     // [max_rows][chunks]
+    float* hp_max = nullptr;     // [max_rows][most chunks any row count produces]
     float* hp_sum = nullptr;
     int32_t* hp_arg = nullptr;
     float* hp_topv = nullptr;    // [max_rows][chunks][LASER_MAX_TOPK]
     int32_t* hp_topi = nullptr;
-    float* hp_lx = nullptr;      // [max_rows]
-    int32_t* row_x = nullptr;    // [max_rows] draft token of the row or -1
-    float* logits_ws = nullptr;  // [max_rows][vocab] fp32, allocated at the first many-row head call
+    // candidate lists of the rows (head_part.h): [max_rows] each
+    int32_t* cand_beg = nullptr;
+    int32_t* cand_cnt = nullptr;
+    int32_t* cand_x = nullptr;
+    int32_t* node_cand = nullptr;
+    float* cand_lx = nullptr;
     // optional timing of the dominant kernel (laser_profile_begin / laser_profile_end)
     std::vector<hipEvent_t> prof_ev;   // start/stop pairs
     int prof_cap = 0, prof_n = 0;
@@ -78,6 +83,8 @@ struct Model {
     int fused_trace = 0;               // 1: thread 0 of every workgroup stamps the wall clock at phase edges
     uint16_t* w16[4] = {nullptr, nullptr, nullptr, nullptr};   // fp16 copies of wqkv, wo, wgu, wdown for the tiled many-row
                                                                // kernels, made at the first step with more than 80 rows
+    uint16_t* wlm16 = nullptr;         // fp16 copy of the head matrix, made at the first head call with more than 80 rows
+    int f16_copies = 1;                // 0: the tiled kernels stream the bf16 weights and widen them in the loop (no copies)
     float* kpart = nullptr;            // partial results of reduction-split tiled GEMMs (many-row path), [parts][rows][N]
     size_t kpart_floats = 0;
     int ksplit_opt[3] = {0, 0, 0};     // forced reduction parts for QKV, O, down (0 = choose from the tile count)
