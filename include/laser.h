@@ -143,7 +143,8 @@ int laser_retrieve_tree(const laser_pool* pool, const int64_t* keys, const int32
 
 /* Device-side bookkeeping for the own text: appends the tokens a step emitted,
  * out_tokens[b][0..accept_len[b]] (as written by laser_verify_step), to row b; a row that would overflow drops
- * its oldest tokens first (sliding window of own_cap tokens). own_tokens / own_len [dev] in/out. */
+ * its oldest tokens first (sliding window of own_cap tokens). own_tokens / own_len [dev] in/out. A negative
+ * accept_len[b] leaves row b unchanged. */
 int laser_own_text_append(int32_t* own_tokens, int32_t* own_len, int own_cap, const int32_t* out_tokens,
                           const int32_t* accept_len, int B, int K, void* stream);
 
@@ -296,6 +297,34 @@ int laser_kv_commit_tree(laser_kv* kv, const int32_t* seq_ids, const int32_t* ac
  * token.  ctx_tail [dev] int32[B][n_max] in/out, pending [dev] int32[B] out. */
 int laser_ctx_advance(int32_t* ctx_tail, int32_t* pending, const int32_t* out_tokens,
                       const int32_t* accept_len, int B, int K, int n_max, void* stream);
+
+/* laser_generate: the whole generation of a batch (Sec. 3.1: retrieval, drafting and verification repeated until the
+ * text is complete; Sec. 2.1 for what a step keeps). Every step is laser_retrieve_drafts (or laser_retrieve_tree /
+ * laser_retrieve_drafts_temp) -> laser_verify_step (or laser_verify_tree) -> device-side bookkeeping -> laser_kv_commit
+ * (or laser_kv_commit_tree), enqueued on `stream` without any device->host traffic; only once every
+ * opts->check_every steps the host waits for the stream and reads a counter of finished sequences to stop early. A
+ * sequence finishes when it has emitted max_new_tokens tokens or eos_token (which is kept); it then stays in the batch
+ * without changing. Tokens a step emits beyond either limit are dropped (and not committed).
+ *   pool        may be NULL: plain one-token-per-step decoding (K is ignored)
+ *   seq_ids     [host] int32[B]; every slot needs reserved capacity >= its length bound + max_new_tokens + K + 1
+ *   keys        [dev] int64[B]; ctx_tail [dev] int32[B][n_max] and pending [dev] int32[B] in/out (as laser_ctx_advance)
+ *   own_tokens / own_len [dev] in/out, with opts->own_cap > 0: the temporary branch (chain drafts only); else NULL
+ *   gen_tokens  [dev] int32[B][max_new_tokens] out: the emitted tokens, -1 padded;  gen_len [dev] int32[B] out
+ *   counters    [dev] int32[B][4] out: steps taken, draft tokens offered, draft tokens kept, draft tokens accepted
+ *   steps_run   [host] out: steps enqueued;  retrieve_ms [host] out, may be NULL: summed time of the retrieval kernels
+ * Synchronises `stream` before returning; allocates and frees its own small device buffers. */
+typedef struct laser_generate_opts {
+    int32_t K, n_min, n_max, min_tokens;   /* drafting (see laser_retrieve_drafts)                              */
+    int32_t tree;                          /* 0: chain drafts, 1: token trees (K <= LASER_MAX_TREE)             */
+    int32_t topk; float p; int32_t mode;   /* acceptance rule (LASER_MODE_*)                                    */
+    int32_t max_new_tokens, eos_token;     /* eos_token -1: none                                                */
+    int32_t check_every;                   /* steps between two looks at the finished counter, >= 1             */
+    int32_t own_cap;                       /* > 0: capacity of own_tokens rows (temporary branch)               */
+} laser_generate_opts;
+int laser_generate(laser_model* model, laser_kv* kv, const laser_pool* pool, const int32_t* seq_ids,
+                   const int64_t* keys, int32_t* ctx_tail, int32_t* pending, int32_t* own_tokens,
+                   int32_t* own_len, int B, const laser_generate_opts* opts, int32_t* gen_tokens,
+                   int32_t* gen_len, int32_t* counters, int* steps_run, float* retrieve_ms, void* stream);
 
 /* Options: "fused" = 1 (default) lets laser_verify_step use the persistent whole-step kernel when
  * B*(K+1) <= 16; 0 forces the general multi-kernel path. Both compute the same function.

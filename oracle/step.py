@@ -123,3 +123,40 @@ def laser_tree_step(dec: Decoder, pool: retrieval.RegroupedPool, seqs, n_min: in
     res = verify_tree_step(dec, seqs, tokens, parents, nn, k, p, mode, return_logits)
     res.update({"tree_tokens": tokens, "tree_parent": parents, "tree_len": nn, "match_n": mn})
     return res
+
+
+def generate(dec: Decoder, pool, seqs, n_min: int, n_max: int, K: int, k: int, p: float, mode: int = 0,
+             min_tokens: int = 1, max_new_tokens: int = 64, eos_token: int = -1, tree: bool = False,
+             temporary_branch: int = 0):
+    """The whole generation (Sec. 3.1): Draft-then-Verify steps until every sequence has emitted max_new_tokens
+    tokens or eos_token (which is kept).  What a step emits beyond either limit is dropped, and only the kept
+    tokens are committed.  pool None: one token per step (Eq. 1).  Sequences are independent; each runs its own
+    steps.  Returns (list of emitted-token lists, per-sequence counters [steps, drafts offered, drafts kept,
+    drafts accepted by the rule])."""
+    texts, counters = [], []
+    for s in seqs:
+        emitted, cnt = [], [0, 0, 0, 0]
+        while len(emitted) < max_new_tokens and (not emitted or emitted[-1] != eos_token):
+            before_len, before_tokens = s.cache.length, list(s.tokens)
+            if pool is None:
+                res = verify_step(dec, [s], np.zeros((1, 0), dtype=np.int32), [0], k, p, mode)
+                offered = 0
+            elif tree:
+                res = laser_tree_step(dec, pool, [s], n_min, n_max, K, k, p, mode, min_tokens)
+                offered = int(res["tree_len"][0])
+            else:
+                res = laser_step(dec, pool, [s], n_min, n_max, K, k, p, mode, min_tokens, temporary_branch=temporary_branch)
+                offered = int(res["draft_len"][0])
+            a = int(res["accept_len"][0])
+            out = [int(t) for t in res["out_tokens"][0, :a + 1]]
+            n_emit = min(a + 1, max_new_tokens - len(emitted))
+            if eos_token in out[:n_emit]:
+                n_emit = out.index(eos_token) + 1
+            # keep only n_emit tokens: the step committed a + 1
+            s.cache.length = before_len + n_emit
+            s.tokens = before_tokens + out[:n_emit]
+            emitted += out[:n_emit]
+            cnt[0] += 1; cnt[1] += offered; cnt[2] += n_emit - 1; cnt[3] += a
+        texts.append(emitted)
+        counters.append(cnt)
+    return texts, counters

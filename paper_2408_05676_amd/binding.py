@@ -72,6 +72,7 @@ def lib():
         "laser_verify_head_static": [vp, vp, vp, vp, i32, i32, i32, f32, i32, vp, vp, vp],
         "laser_kv_commit": [vp, vp, vp, i32, vp],
         "laser_kv_commit_tree": [vp, vp, vp, vp, i32, i32, vp],
+        "laser_generate": [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, C.POINTER(C.c_int), C.POINTER(C.c_float), vp],
         "laser_retrieve_tree": [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp],
         "laser_verify_tree": [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, i32, vp, vp, vp, vp, vp],
         "laser_ctx_advance": [vp, vp, vp, vp, i32, i32, i32, vp],
@@ -400,6 +401,36 @@ def kv_commit_tree(kv: "KVCache", seq_ids, accept_len: torch.Tensor, accept_path
     _check(lib().laser_kv_commit_tree(kv._h, ids.ctypes.data, _dev(accept_len, torch.int32, "accept_len"),
                                       _dev(accept_path, torch.int32, "accept_path") if K > 0 else None, ids.size, K,
                                       _stream(stream)), "laser_kv_commit_tree")
+
+
+class GenerateOpts(C.Structure):
+    _fields_ = [("K", C.c_int32), ("n_min", C.c_int32), ("n_max", C.c_int32), ("min_tokens", C.c_int32), ("tree", C.c_int32),
+                ("topk", C.c_int32), ("p", C.c_float), ("mode", C.c_int32), ("max_new_tokens", C.c_int32), ("eos_token", C.c_int32),
+                ("check_every", C.c_int32), ("own_cap", C.c_int32)]
+
+
+def generate(model: "Model", kv: "KVCache", pool, seq_ids, keys, ctx_tail: torch.Tensor, pending: torch.Tensor, K: int, n_min: int,
+             topk: int, p: float, mode: int = MODE_RV, max_new_tokens: int = 64, eos_token: int = -1, tree: bool = False,
+             min_tokens: int = 1, check_every: int = 8, own_tokens=None, own_len=None, time_retrieval: bool = False, stream=None):
+    """laser_generate. Returns (gen_tokens int32 [B][max_new_tokens] (-1 padded), gen_len int32 [B], counters int32 [B][4],
+    steps run, summed retrieval-kernel milliseconds or None)."""
+    ids = _host_i32(seq_ids, "seq_ids")
+    B, n_max = ctx_tail.shape
+    dev = pending.device
+    gen = torch.empty((B, max_new_tokens), dtype=torch.int32, device=dev)
+    glen = torch.empty(B, dtype=torch.int32, device=dev)
+    cnt = torch.empty((B, 4), dtype=torch.int32, device=dev)
+    own_cap = own_tokens.shape[1] if own_tokens is not None else 0
+    o = GenerateOpts(K, n_min, n_max, min_tokens, int(tree), topk, p, mode, max_new_tokens, eos_token, check_every, own_cap)
+    steps, ms = C.c_int(0), C.c_float(0.0)
+    _check(lib().laser_generate(model._h, kv._h, pool._h if pool is not None else None, ids.ctypes.data,
+                                _dev(keys, torch.int64, "keys") if keys is not None else None,
+                                _dev(ctx_tail, torch.int32, "ctx_tail"), _dev(pending, torch.int32, "pending"),
+                                _dev(own_tokens, torch.int32, "own_tokens") if own_tokens is not None else None,
+                                _dev(own_len, torch.int32, "own_len") if own_len is not None else None,
+                                ids.size, C.byref(o), gen.data_ptr(), glen.data_ptr(), cnt.data_ptr(), C.byref(steps),
+                                C.byref(ms) if time_retrieval else None, _stream(stream)), "laser_generate")
+    return gen, glen, cnt, steps.value, (ms.value if time_retrieval else None)
 
 
 def verify_head_static(model: Model, h: torch.Tensor, drafts: torch.Tensor, draft_len: torch.Tensor, topk: int,

@@ -544,9 +544,10 @@ __global__ __launch_bounds__(64) void retrieve_tree_kernel(TreeArgs a) {
 __global__ __launch_bounds__(256) void own_text_append_kernel(int32_t* own, int32_t* own_len, int cap, const int32_t* out_tokens,
                                                               const int32_t* accept_len, int K) {
     const int b = blockIdx.x, tid = threadIdx.x;
+    if (accept_len[b] < 0) return;                     // nothing was emitted for this sequence (it had finished before the step)
     int32_t* row = own + (size_t)b * cap;
     const int32_t* nw = out_tokens + (size_t)b * (K + 1);
-    int n_new = min(max(accept_len[b], 0), K) + 1;
+    int n_new = min(accept_len[b], K) + 1;
     int len = min(max(own_len[b], 0), cap);
     const int skip = max(n_new - cap, 0);              // more new tokens than the row holds: keep the newest
     n_new -= skip;

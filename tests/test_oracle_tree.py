@@ -221,3 +221,26 @@ def test_strict_tree_steps_reproduce_greedy_decoding_and_one_branch_equals_the_c
     assert s3.cache.length == s4.cache.length
     np.testing.assert_allclose(s3.cache.k[:, :s3.cache.length], s4.cache.k[:, :s4.cache.length], atol=1e-12)
     np.testing.assert_allclose(s3.cache.v[:, :s3.cache.length], s4.cache.v[:, :s4.cache.length], atol=1e-12)
+
+
+def test_generate_stops_at_eos_and_max_new_and_matches_greedy_under_strict(tiny):
+    """The generation loop (Sec. 3.1): under strict verification the emitted text is the greedy text, whatever the
+    drafts (chain, tree, temporary branch, none), cut after the end-of-sequence token or at max_new_tokens."""
+    sh, dec = tiny
+    prompts = [synth.uniform_tokens(15 + i, 1, 0, 7 + i, sh.vocab).tolist() for i in range(2)]
+    ref = [step.autoregressive_greedy(dec, step.Sequence(dec, i, pr, 128), 40) for i, pr in enumerate(prompts)]
+    flat = np.concatenate([np.array(pr[-3:] + rf, dtype=np.int32) for pr, rf in zip(prompts, ref)])
+    off = np.array([0, 43, 86]); pool = RegroupedPool(flat, off, np.array([0, 1]))
+    eos = ref[0][17]
+    stop0 = ref[0].index(eos) + 1
+    for kw in (dict(), dict(tree=True), dict(temporary_branch=16)):
+        seqs = [step.Sequence(dec, i, pr, 128) for i, pr in enumerate(prompts)]
+        texts, cnt = step.generate(dec, pool, seqs, 1, 3, 6, 1, -1.0, max_new_tokens=29, eos_token=eos, **kw)
+        want1 = ref[1][:29] if eos not in ref[1][:29] else ref[1][:ref[1].index(eos) + 1]
+        assert texts[0] == ref[0][:min(stop0, 29)] and texts[1] == want1, kw
+        for s, pr, t, c in zip(seqs, prompts, texts, cnt):
+            assert s.tokens == pr + t and s.cache.length == len(s.tokens) - 1
+            assert c[2] == len(t) - c[0] and c[2] <= c[3] <= c[1] and c[0] < len(t)       # several tokens per step
+    seqs = [step.Sequence(dec, i, pr, 128) for i, pr in enumerate(prompts)]
+    texts, cnt = step.generate(dec, None, seqs, 1, 3, 6, 1, -1.0, max_new_tokens=12)
+    assert texts == [r[:12] for r in ref] and all(c == [12, 0, 0, 0] for c in cnt)
