@@ -141,6 +141,13 @@ __global__ __launch_bounds__(256, SPLIT ? 2 : GM_WGS) void gemm_mfma_kernel(Gemm
         wr = wr < wmax ? wr : wmax;
         wb[i] = a.W + (size_t)wr * a.Kd + sk;
     }
+    // head epilogue: thread t will own half of row t / 2; its candidate list is fetched now, under the main loop
+    int hc_b = 0, hc_n = 0, hc_x0 = -1;
+    if constexpr (EPI == GEPI_HEAD) {
+        const int grow = tm * GM_BM + (tid >> 1);
+        if (grow < a.M) { hc_b = a.hp.cand_beg[grow]; hc_n = a.hp.cand_cnt[grow]; }
+        hc_x0 = hc_n > 0 ? a.hp.cand_x[hc_b] : -1;
+    }
     float16_t acc[2][NJ];
     float16_t acl[SPLIT ? 2 : 1][SPLIT ? NJ : 1];
 #pragma unroll
@@ -325,7 +332,11 @@ __global__ __launch_bounds__(256, SPLIT ? 2 : GM_WGS) void gemm_mfma_kernel(Gemm
                 }
                 if (mloc > st.mx) st.arg = n0 + cloc;                                      // ids ascend per thread: earlier ties stay
                 st.mx = m_new;
-                store_candidates(a.hp, grow, n0, 32, [&](int c) { return src[c]; });
+                if (hc_x0 >= n0 && hc_x0 < n0 + 32) a.hp.cand_lx[hc_b] = src[hc_x0 - n0];
+                for (int c = 1; c < hc_n; ++c) {                                         // further children of a tree node
+                    const int x = a.hp.cand_x[hc_b + c];
+                    if (x >= n0 && x < n0 + 32) a.hp.cand_lx[hc_b + c] = src[x - n0];
+                }
 #pragma unroll
                 for (int c = 0; c < 32; ++c) {
                     if (n0 + c < a.N && before(vals[c], n0 + c, thr_v, thr_i)) {

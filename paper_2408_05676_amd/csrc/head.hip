@@ -130,14 +130,12 @@ struct AcceptArgs {
 // emitted (Sec. 3.4; Sec. 2.1 for the correction token). For a chain this is the longest accepted prefix.
 constexpr int kCandPass = 4;          // candidates ranked per pass over a row's chunks
 __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
-    __shared__ float s_f[4][2];
-    __shared__ int s_i[4][1 + kCandPass];
     __shared__ float row_mx[LASER_MAX_DRAFT + 1], row_sum[LASER_MAX_DRAFT + 1];
     __shared__ int row_arg[LASER_MAX_DRAFT + 1];
     __shared__ int rank_of[LASER_MAX_DRAFT + 1];          // by candidate number within the sequence
     const int b = blockIdx.x, R = a.K + 1;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (int r = 0; r < R; ++r) {
+    for (int r = wave; r < R; r += 4) {                   // a wave per row, its lanes over the row's chunks
         const int row = b * R + r;
         const int cb = a.cand_beg[row], cn = a.cand_cnt[row];
         for (int c0 = 0; c0 < (cn > 0 ? cn : 1); c0 += kCandPass) {
@@ -151,7 +149,7 @@ __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
             }
             float mx = -INFINITY, sum = 0.f;
             int arg = 0x7FFFFFFF, ahead[kCandPass] = {0, 0, 0, 0};
-            for (int c = threadIdx.x; c < a.chunks; c += 256) {
+            for (int c = lane; c < a.chunks; c += 64) {
                 const size_t o = (size_t)row * a.chunks + c;
                 const float cm = a.hp_max[o], cs = a.hp_sum[o];
                 const int ca = a.hp_arg[o];
@@ -178,28 +176,11 @@ __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
                 if (before(omx, oarg, mx, arg)) arg = oarg;
                 mx = M;
             }
-            __syncthreads();
             if (lane == 0) {
-                s_f[wave][0] = mx; s_f[wave][1] = sum; s_i[wave][0] = arg;
-#pragma unroll
-                for (int j = 0; j < kCandPass; ++j) s_i[wave][1 + j] = ahead[j];
-            }
-            __syncthreads();
-            if (threadIdx.x == 0) {
-                float M = -INFINITY, S = 0.f; int A = 0x7FFFFFFF, rk[kCandPass] = {0, 0, 0, 0};
-                for (int w = 0; w < 4; ++w) {
-                    const float wm = s_f[w][0];
-                    const float nm = fmaxf(M, wm);
-                    if (nm != -INFINITY) S = S * __expf(M - nm) + s_f[w][1] * __expf(wm - nm);
-                    if (before(wm, s_i[w][0], M, A)) A = s_i[w][0];
-                    M = nm;
-#pragma unroll
-                    for (int j = 0; j < kCandPass; ++j) rk[j] += s_i[w][1 + j];
-                }
-                if (c0 == 0) { row_mx[r] = M; row_sum[r] = S; row_arg[r] = A; }
+                if (c0 == 0) { row_mx[r] = mx; row_sum[r] = sum; row_arg[r] = arg; }
 #pragma unroll
                 for (int j = 0; j < kCandPass; ++j)
-                    if (c0 + j < cn) rank_of[cb - b * a.K + c0 + j] = rk[j];
+                    if (c0 + j < cn) rank_of[cb - b * a.K + c0 + j] = ahead[j];
             }
         }
     }

@@ -600,13 +600,20 @@ __global__ __launch_bounds__(NWV * 64, NWV == 4 ? 4 : 2) void attn_kernel(AttnAr
 #pragma unroll
         for (int i = 0; i < 4; ++i) s[i] += sl[i] * kLoInv;
         float sv[4], mx = -INFINITY;
+        // Committed slots are visible to every row; a new slot (row t - len of this step) only along the row's branch.
+        // Branch-free (a branch here would make the wait for the prefetched page conservative): the lane's four slots
+        // start rel = t0 - len behind the committed length; rel <= -4: all committed; rel >= 0: four bits of the mask.
+        {
+            const int rel = p * kPageSize + 4 * g - len;
+            const unsigned lo = (unsigned)(anc >> min(max(rel, 0), 63));
+            const int sn = min(max(-rel, 0), 4);
+            const unsigned hi = ((unsigned)anc << sn) | ((1u << sn) - 1u);
+            const unsigned vis4 = (qrow < a.R) ? (rel >= 0 ? lo : hi) : 0u;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int t = p * kPageSize + 4 * g + i;
-            // committed slots are visible to every row; a new slot (row t - len of this step) only along the row's branch
-            const bool vis = (qrow < a.R) && (t < len || (t - len < a.R && ((anc >> (t - len)) & 1ull)));
-            sv[i] = vis ? s[i] * a.scale : -INFINITY;
-            mx = fmaxf(mx, sv[i]);
+            for (int i = 0; i < 4; ++i) {
+                sv[i] = ((vis4 >> i) & 1u) ? s[i] * a.scale : -INFINITY;
+                mx = fmaxf(mx, sv[i]);
+            }
         }
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
