@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the retrieve -> verify -> accept -> commit step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c4|7b_b8|1b|tiny]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c4|7b_b8|1b|tiny|stress]
+    python bench.py --study [--study-shape 1b|7b|tiny]     # generation loop: pooling schemes, pool sizes, acceptance rules
 
 A "step" is one pass of the whole hot path over the batch: laser_retrieve_drafts,
 laser_verify_step (embedding .. fused head + acceptance), laser_kv_commit, laser_ctx_advance.
@@ -311,12 +312,270 @@ def run_workload(args, name, steps, warmup, weights_cache):
     return out, sh, wl, tokens_per_step
 
 
+def run_stress(args):
+    """The stress configuration (BASELINE configs[4]): the fused output head + relaxed acceptance at d 4096, vocabulary
+    128256, 256 sequences x 16 rows, and the draft lookup over a pool of 100 M tokens in 1 M keyed sub-pools for 4096
+    concurrent contexts (suffix length 1..4, K = 16); beside them the floor of an empty kernel of as many wavefronts
+    and a lookup batch of 2^20 contexts. One "step" = one lookup batch + one head launch."""
+    import torch
+    import synth
+    from synth.model import torch_gen_weight
+    import paper_2408_05676_amd as laser
+
+    dev = "cuda"
+    torch.cuda.set_device(0)
+    steps = args.steps if args.steps is not None else 10
+    warmup = args.warmup if args.warmup is not None else 2
+    sh = synth.SHAPES["head128k"]
+    B, K = 256, 15
+    R = K + 1
+    w = torch_gen_weight(sh, "wlm", -1, dev).contiguous()
+    model = laser.Model(0, sh.d, sh.n_heads, sh.ffn, sh.vocab, {"wlm": w}, B * R, B, 0)
+    g = torch.Generator(device=dev).manual_seed(7)
+    # hidden states with a planted direction so that drafts land on both sides of the threshold: h = a * w[t] + noise
+    planted = torch.randint(0, sh.vocab, (B, R), generator=g, device=dev)
+    noise = torch.randn((B, R, sh.d), generator=g, device=dev) * 0.5
+    amp = 5.0 + torch.rand((B, R, 1), generator=g, device=dev) * 9.0
+    h = (amp * w[planted].float() + noise).to(torch.float16)
+    drafts = planted[:, :K].to(torch.int32).clone()
+    wrong = torch.rand((B, K), generator=g, device=dev) < 0.12
+    drafts[wrong] = torch.randint(0, sh.vocab, (int(wrong.sum()),), generator=g, device=dev, dtype=torch.int32)
+    dl = torch.full((B,), K, dtype=torch.int32, device=dev)
+    acc = torch.empty(B, dtype=torch.int32, device=dev)
+    out = torch.empty((B, R), dtype=torch.int32, device=dev)
+
+    t0 = time.perf_counter()
+    spec = synth.POOLS["stress"]
+    pool_data = synth.gen_pool(spec)
+    t_gen = time.perf_counter() - t0
+    n_max, Kr, Br = 4, 16, 4096
+    t0 = time.perf_counter()
+    pool = laser.Pool(pool_data["tokens"], pool_data["seq_off"], pool_data["seq_key"], n_max)
+    t_build = time.perf_counter() - t0
+    ctx = synth.gen_contexts(spec, Br, 8, n_max, salt=5)
+    kd = torch.tensor(ctx["keys"].astype(np.int64), device=dev)
+    td = torch.tensor(np.ascontiguousarray(ctx["ctx"][:, -n_max:]).astype(np.int32), device=dev)
+    rout = laser.retrieve_drafts(pool, kd, td, 1, n_max, Kr, 1)
+
+    def step():
+        laser.retrieve_drafts(pool, kd, td, 1, n_max, Kr, 1, out=rout)
+        laser.verify_head(model, h, drafts, dl, 2, 0.1, 0, out=(acc, out))
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    t0 = time.perf_counter()
+    ev[0].record()
+    for _ in range(steps):
+        step()
+    ev[1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    step_ms = max(wall * 1e3, ev[0].elapsed_time(ev[1])) / steps
+    emitted = int((acc + 1).sum())
+    ev[2].record()
+    for _ in range(steps):
+        laser.verify_head(model, h, drafts, dl, 2, 0.1, 0, out=(acc, out))
+    ev[3].record()
+    torch.cuda.synchronize()
+    head_ms = ev[2].elapsed_time(ev[3]) / steps
+    ev[0].record()
+    for _ in range(50):
+        laser.retrieve_drafts(pool, kd, td, 1, n_max, Kr, 1, out=rout)
+    ev[1].record()
+    torch.cuda.synchronize()
+    retr_us = ev[0].elapsed_time(ev[1]) * 1e3 / 50
+    floor_us = laser.probe_launch(Br, 200)
+    # 2^20 contexts: tails of random pool positions under their sub-pool's key (half of them with a replaced last token,
+    # so that shorter suffixes are tried too); positions come from the regrouped token array the library reports
+    n_big = 1 << 20
+    info = pool.info()
+    order = np.argsort(pool_data["seq_key"], kind="stable")
+    lens = (pool_data["seq_off"][1:] - pool_data["seq_off"][:-1])[order]
+    starts = np.concatenate([[0], np.cumsum(lens)])[:-1]
+    r = np.random.default_rng(11)
+    seq = r.integers(0, lens.size, size=n_big)
+    posn = starts[seq] + np.minimum(r.integers(0, 1 << 30, size=n_big) % np.maximum(lens[seq] - 1, 1), lens[seq] - 1)
+    regrouped = np.empty(info["n_tokens"], dtype=np.int32)
+    for s0 in range(0, info["n_tokens"], 1 << 24):
+        c = min(1 << 24, info["n_tokens"] - s0)
+        regrouped[s0:s0 + c] = pool.read_tokens(s0, c)
+    idx = posn[:, None] + np.arange(-n_max + 1, 1)[None, :]
+    tails = np.where(idx >= starts[seq][:, None], regrouped[np.clip(idx, 0, regrouped.size - 1)], -1).astype(np.int32)
+    swap = r.random(n_big) < 0.5
+    tails[swap, -1] = r.integers(0, spec.vocab, size=int(swap.sum()))
+    kbig = torch.tensor(pool_data["seq_key"][order][seq].astype(np.int64), device=dev)
+    tbig = torch.tensor(tails, device=dev)
+    big_out = laser.retrieve_drafts(pool, kbig, tbig, 1, n_max, Kr, 1)
+    torch.cuda.synchronize()
+    ev[0].record()
+    for _ in range(5):
+        laser.retrieve_drafts(pool, kbig, tbig, 1, n_max, Kr, 1, out=big_out)
+    ev[1].record()
+    torch.cuda.synchronize()
+    big_ms = ev[0].elapsed_time(ev[1]) / 5
+    hit_big = float((big_out[1] > 0).float().mean())
+    flops = 2.0 * B * R * sh.d * sh.vocab
+    scratch = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    read_gbs, copy_gbs = laser.probe_hbm(scratch, reps=10)
+    mfma_tflops = laser.probe_mfma_f16(scratch, reps=5)
+    del scratch
+    achieved = flops / (head_ms * 1e-3) / 1e12
+    out_json = {
+        "metric": "accepted tokens/s per verify step (7B shape, bs 1 & 64); % HBM / MFMA peak",
+        "value": emitted / (step_ms * 1e-3), "unit": "accepted tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": step_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 weights x fp16 hidden states, fp32 accumulate; int32 tokens", "data": "synthetic",
+        "config": {"workload": "Retrieval + verify-head stress: pool of 100M tokens over 1M sub-pools, 4096 contexts, suffix 1-4, K=16; "
+                               "head d 4096, vocab 128256, 256 sequences x 16 rows (BASELINE configs[4])",
+                   "head_rows": B * R, "vocab": sh.vocab, "topk": 2, "p": 0.1, "accepted_drafts_per_sequence": emitted / B - 1.0,
+                   "head_ms": head_ms, "retrieval_us_per_4096_lookups": retr_us, "lookups_per_s": Br / (retr_us * 1e-6),
+                   "empty_kernel_us_4096_wavefronts": floor_us, "retrieval_over_floor": retr_us / floor_us,
+                   "contexts_matched": float((rout[1] > 0).float().mean()),
+                   "retrieval_ms_per_2^20_lookups": big_ms, "lookups_per_s_2^20": n_big / (big_ms * 1e-3),
+                   "contexts_matched_2^20": hit_big,
+                   "pool_tokens": int(info["n_tokens"]), "pool_keys": int(info["n_keys"]), "pool_device_GB": info["device_bytes"] / 1e9,
+                   "pool_generate_s": t_gen, "pool_build_s": t_build},
+        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_kernel<head epilogue>", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None, "flops_per_launch": flops,
+                     "avg_launch_us": head_ms * 1e3, "launches": steps, "measured_peak": mfma_tflops,
+                     "frac_of_measured_peak": achieved / mfma_tflops,
+                     "measured": {"hbm_read_GBs": read_gbs, "hbm_copy_GBs": copy_gbs, "mfma_f16_TFLOPs": mfma_tflops}},
+    }
+    model.close()
+    pool.close()
+    return out_json
+
+
+def run_study(args):
+    """Generation-loop study on synthetic data, shaped like the paper's pool study (Sec. 2.2), its ablation of pooling
+    schemes with and without relaxed verification (Sec. 4.3.1) and of the acceptance rules (Sec. 4.3.2). U users in G
+    groups; the text to generate for a user is the model's own greedy continuation of the user's prompt (decoded first,
+    one token per step, through laser_generate without a pool); "earlier knowledge of similar users" is m noisy copies
+    of it (substitution rate s). Pooling schemes: CRP -- a pool per group holding the copies for its members; GRP --
+    one pool for everything; RRP -- same number of pools, every copy in a random one and every user looking in a random
+    one. Every run regenerates all texts with laser_generate (retrieve -> verify -> commit on the device)."""
+    import torch
+    import synth
+    from synth.model import torch_gen_weight
+    import paper_2408_05676_amd as laser
+    from paper_2408_05676_amd.harness import Engine, stacked_weights
+
+    dev = "cuda"
+    torch.cuda.set_device(0)
+    sh = synth.SHAPES[args.study_shape].with_(lm_gain=5.0 if args.study_shape != "tiny" else 4.0)
+    U, G, B, ctx_len, T, K, n_max, m_copies, sub = 32, 8, 8, 96, 96, 8, 3, 4, 0.10
+    eos_class = max(1, sh.vocab // 64)                 # tokens below this id end a text (a 1.6 % class: ~64 tokens expected)
+    weights = stacked_weights(lambda n, l: torch_gen_weight(sh, n, l, dev), sh, dev)
+    eng = Engine(sh, weights, B, 16, ctx_len + T + 64, n_max)          # buffers for up to 16 drafts (the tree run)
+    prompts = synth.uniform_tokens(77, 1, 0, U * ctx_len, sh.vocab).reshape(U, ctx_len)
+    group = np.arange(U) % G
+    r = np.random.default_rng(5)
+
+    def run_all(pool, keys_of_user, topk, p, mode, tree=False, Kd=K):
+        """regenerate every user's text; returns texts, counters, wall seconds, retrieval ms"""
+        texts, cnts, secs, rms, bsteps = [], [], 0.0, 0.0, 0
+        for u0 in range(0, U, B):
+            us = list(range(u0, u0 + B))
+            for b in range(B):
+                eng.kv.set_len(b, 0)
+            eng.prefill(prompts[us])
+            kd = torch.tensor(np.asarray([keys_of_user[u] for u in us], dtype=np.int64), device=dev)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            gen, glen, cnt, steps, ms = laser.generate(eng.model, eng.kv, pool, eng.seq_ids, kd, eng.ctx_tail, eng.pending, Kd, 1, topk, p,
+                                                       mode, max_new_tokens=T, tree=tree, check_every=4, time_retrieval=pool is not None)
+            secs += time.perf_counter() - t0
+            rms += ms or 0.0
+            bsteps += steps
+            texts += [row.tolist() for row in gen.cpu().numpy()]
+            cnts += cnt.cpu().numpy().tolist()
+        return texts, np.asarray(cnts), secs, rms, bsteps
+
+    ar_texts, _, ar_secs, _, ar_steps = run_all(None, np.zeros(U), 1, -1.0, 0)
+    # The reference text is decoded through the SAME launch shape as the runs it is compared with (B x (K + 1) rows, a pool
+    # whose only key nobody looks up): one-token-per-step decoding takes other kernels (fewer rows), whose logits differ in
+    # the last bits, and a random-init model's text forks at every near-tie.
+    nobody = laser.Pool(np.zeros(4, dtype=np.int32), np.array([0, 4], dtype=np.int64), np.array([1 << 40], dtype=np.int64), n_max)
+    greedy, _, _, _, _ = run_all(nobody, np.zeros(U), 1, -1.0, 0)
+    nobody.close()
+    copies = []                                        # (user, noisy text incl. the prompt's last n_max tokens)
+    for u in range(U):
+        full = np.array(list(prompts[u, -n_max:]) + greedy[u], dtype=np.int32)
+        for c in range(m_copies):
+            noisy = full.copy()
+            hit = r.random(noisy.size) < sub
+            hit[:n_max] = False
+            noisy[hit] = r.integers(0, sh.vocab, size=int(hit.sum()))
+            copies.append((u, noisy))
+    distract = [synth.uniform_tokens(78, 2 + i, 0, T, sh.vocab) for i in range(U * m_copies)]     # unrelated texts of the same volume
+
+    def build(scheme, frac=1.0):
+        seqs, keys = [], []
+        rr = np.random.default_rng(9)
+        lookup = {u: int(group[u]) for u in range(U)}
+        if scheme == "RRP":
+            lookup = {u: int(rr.integers(0, G)) for u in range(U)}
+        keep = rr.random(len(copies)) < frac
+        for i, (u, t) in enumerate(copies):
+            if not keep[i]:
+                continue
+            seqs.append(t)
+            keys.append(0 if scheme == "GRP" else (int(group[u]) if scheme == "CRP" else int(rr.integers(0, G))))
+        for i, t in enumerate(distract):
+            if rr.random() < frac:
+                seqs.append(t)
+                keys.append(0 if scheme == "GRP" else i % G)
+        if scheme == "GRP":
+            lookup = {u: 0 for u in range(U)}
+        flat = np.concatenate(seqs).astype(np.int32)
+        off = np.cumsum([0] + [len(t) for t in seqs]).astype(np.int64)
+        return laser.Pool(flat, off, np.asarray(keys, dtype=np.int64), n_max), lookup, int(flat.size)
+
+    def summarise(name, texts, cnt, secs, rms, bsteps, extra=None):
+        n_tok = sum(len([t for t in x if t >= 0]) for x in texts)
+        to_eos = [next((i + 1 for i, t in enumerate(x) if 0 <= t < eos_class), len(x)) for x in texts]
+        differs = sum(1 for u in range(U) if texts[u] != greedy[u])
+        row = {"run": name, "tokens_per_s": n_tok / secs, "accepted_drafts_per_step": float(cnt[:, 2].sum() / max(cnt[:, 0].sum(), 1)),
+               "sequence_steps": int(cnt[:, 0].sum()), "batch_steps": int(bsteps), "ms_per_batch_step": secs * 1e3 / max(bsteps, 1),
+               "retrieval_us_per_batch_step": rms * 1e3 / max(bsteps, 1),
+               "mean_length_to_eos_class": float(np.mean(to_eos)), "texts_differing_from_greedy": differs}
+        row.update(extra or {})
+        return row
+
+    rows = [summarise("autoregressive (no pool, one row per sequence)", ar_texts, np.asarray([[T, 0, 0, 0]] * U), ar_secs, 0.0, ar_steps)]
+    for scheme in ("GRP", "RRP", "CRP"):
+        pool, lookup, n_tok = build(scheme)
+        for rule, (topk, p) in (("strict", (1, -1.0)), ("RV", (2, 0.1))):
+            res = run_all(pool, lookup, topk, p, 0)
+            rows.append(summarise(f"{scheme} {rule}", *res, {"pool_tokens": n_tok}))
+        pool.close()
+    for frac in (0.125, 0.25, 0.5, 1.0):
+        pool, lookup, n_tok = build("CRP", frac)
+        res = run_all(pool, lookup, 2, 0.1, 0)
+        rows.append(summarise(f"CRP RV pool size x{frac}", *res, {"pool_tokens": n_tok}))
+        pool.close()
+    pool, lookup, n_tok = build("CRP")
+    for name, (topk, p, mode) in (("top-1 (strict)", (1, -1.0, 0)), ("top-k only (k=2)", (2, 0.0, 2)), ("top-p only (p=0.1)", (1, 0.1, 3)),
+                                  ("RV (k=2, p=0.1)", (2, 0.1, 0)), ("top-1 or RV", (2, 0.1, 1)), ("top-k only (k=8)", (8, 0.0, 2))):
+        rows.append(summarise(f"rule: {name}", *run_all(pool, lookup, topk, p, mode)))
+    rows.append(summarise("CRP RV, token trees of 16 nodes", *run_all(pool, lookup, 2, 0.1, 0, tree=True, Kd=16)))
+    pool.close()
+    eng.close()
+    return {"study": "generation loop on synthetic users (laser_generate)", "shape": sh.name, "users": U, "groups": G, "batch": B,
+            "prompt": ctx_len, "new_tokens": T, "K": K, "copies_per_user": m_copies, "copy_substitution_rate": sub,
+            "lm_gain": sh.lm_gain, "eos_class_size": eos_class, "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c3", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="c3", choices=sorted(WORKLOADS) + ["stress"])
+    ap.add_argument("--study", action="store_true", help="run the generation-loop study instead of a timed workload (prints one JSON object)")
+    ap.add_argument("--study-shape", default="1b", choices=["tiny", "1b", "7b"])
     ap.add_argument("--regime", default="rv", choices=["rv", "strict", "floor"],
                     help="rv: k=2 p=0.1 (Eq. 8) on a sharpened head; strict: greedy (Eq. 4); floor: no pool replay")
     ap.add_argument("--lm-gain", type=float, default=None)
@@ -345,6 +604,12 @@ def main():
               "--gpus N with N > 1 is not supported.", file=sys.stderr)
         sys.exit(2)
 
+    if args.study:
+        print(json.dumps(run_study(args)))
+        return
+    if args.workload == "stress":
+        print(json.dumps(run_stress(args)))
+        return
     weights_cache = {}
     out, sh, wl, tokens_per_step = run_workload(args, args.workload, args.steps, args.warmup, weights_cache)
     if args.workload == "c3" and not args.no_throughput:

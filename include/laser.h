@@ -372,6 +372,9 @@ int laser_profile_end(laser_model* model, void* stream, float* total_ms, int* n_
  *   (not written); tflops = executed flops per second / 1e12. */
 int laser_probe_hbm(void* buf, size_t bytes, int reps, void* stream, float* read_gbs, float* copy_gbs);
 int laser_probe_mfma_f16(void* scratch, int reps, void* stream, float* tflops);
+/* laser_probe_launch: the floor under a latency-bound kernel such as the draft lookup -- the mean time of `reps`
+ * back-to-back launches of a kernel of `blocks` wavefronts that does nothing (microseconds per launch). */
+int laser_probe_launch(int blocks, int reps, void* stream, float* us_per_launch);
 
 #ifdef __cplusplus
 }

@@ -83,6 +83,7 @@ def lib():
         "laser_profile_end": [vp, vp, C.POINTER(C.c_float), C.POINTER(C.c_int)],
         "laser_probe_hbm": [vp, C.c_size_t, i32, vp, C.POINTER(C.c_float), C.POINTER(C.c_float)],
         "laser_probe_mfma_f16": [vp, i32, vp, C.POINTER(C.c_float)],
+        "laser_probe_launch": [i32, i32, vp, C.POINTER(C.c_float)],
     }
     for name, args in protos.items():
         fn = getattr(L, name)
@@ -483,4 +484,11 @@ def probe_mfma_f16(scratch: torch.Tensor, reps: int = 10, stream=None) -> float:
         raise LaserError("scratch must be a CUDA tensor of at least 4 bytes")
     t = C.c_float()
     _check(lib().laser_probe_mfma_f16(scratch.data_ptr(), reps, _stream(stream), C.byref(t)), "laser_probe_mfma_f16")
+    return t.value
+
+
+def probe_launch(blocks: int, reps: int = 200, stream=None) -> float:
+    """laser_probe_launch: microseconds per launch of an empty kernel of `blocks` wavefronts."""
+    t = C.c_float()
+    _check(lib().laser_probe_launch(blocks, reps, _stream(stream), C.byref(t)), "laser_probe_launch")
     return t.value

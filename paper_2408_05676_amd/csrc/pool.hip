@@ -35,8 +35,8 @@ struct Pool {
 };
 
 // ------------------------------------------------------------------------------------ kernel
-constexpr int kCand = 2048;        // occurrences a wave keeps in LDS
-constexpr int kVote = 1024;        // vote-table slots (power of two)
+constexpr int kCand = 512;         // occurrences a wave keeps in LDS (more: streamed from the index, re-checked against the chain)
+constexpr int kVote = 512;         // vote-table slots (power of two; wider votes are partitioned)
 constexpr int kEmptyTok = -1;
 constexpr int kOwnMax = LASER_MAX_OWN_TEXT;   // tokens of a sequence's own text (temporary branch) a lookup can take
 

@@ -55,6 +55,11 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* sink)
     if (s == 12345.678f) sink[0] = s;
 }
 
+// Nothing at all: what a launch of `blocks` wavefronts costs when no wavefront does any work.
+__global__ __launch_bounds__(64) void probe_empty_kernel(int* sink) {
+    if (sink == nullptr && threadIdx.x == 12345u) *sink = 0;
+}
+
 // A pair of timing events that is destroyed on every way out of a probe.
 struct EventPair {
     hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -130,6 +135,25 @@ extern "C" int laser_probe_mfma_f16(void* scratch, int reps, void* stream_v, flo
     LASER_HIP_CHECK(hipEventElapsedTime(&ms, e0, e1));
     const double flops = (double)grid * 4.0 * 4.0 * iters * 32768.0 * reps;   // workgroups x waves x chains x iters x flops
     *tflops = (float)(flops / (ms * 1e-3) / 1e12);
+    LASER_HIP_CHECK(hipGetLastError());
+    return LASER_OK;
+}
+
+extern "C" int laser_probe_launch(int blocks, int reps, void* stream_v, float* us_per_launch) {
+    LASER_REQUIRE(us_per_launch != nullptr && blocks >= 1 && reps >= 1 && reps <= 100000, LASER_E_INVALID_ARG,
+                  "NULL argument, blocks < 1 or reps outside 1..100000");
+    hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
+    EventPair ev;
+    LASER_HIP_CHECK(ev.create());
+    float ms = 0.f;
+    int* none = nullptr;
+    hipLaunchKernelGGL(probe_empty_kernel, dim3((unsigned)blocks), dim3(64), 0, stream, none);
+    LASER_HIP_CHECK(hipEventRecord(ev.e0, stream));
+    for (int i = 0; i < reps; ++i) hipLaunchKernelGGL(probe_empty_kernel, dim3((unsigned)blocks), dim3(64), 0, stream, none);
+    LASER_HIP_CHECK(hipEventRecord(ev.e1, stream));
+    LASER_HIP_CHECK(hipEventSynchronize(ev.e1));
+    LASER_HIP_CHECK(hipEventElapsedTime(&ms, ev.e0, ev.e1));
+    *us_per_launch = ms * 1e3f / (float)reps;
     LASER_HIP_CHECK(hipGetLastError());
     return LASER_OK;
 }
