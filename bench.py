@@ -29,13 +29,13 @@ sys.path.insert(0, ROOT)
 
 WORKLOADS = {
     #        shape  B   ctx   K  pool             n_max  default steps
-    "c3": dict(shape="7b", B=1, ctx=1024, K=8, pool="7b_latency", n_max=3, steps=40, warmup=5,
+    "c3": dict(shape="7b", B=1, ctx=1024, K=8, pool="7b_latency", n_max=3, steps=50, warmup=5,
                label="7B shape latency: B=1, context 1024, K=8, pool 2k x 256 tokens (BASELINE configs[2])"),
-    "c4": dict(shape="7b", B=64, ctx=512, K=10, pool="7b_throughput", n_max=3, steps=20, warmup=3,
+    "c4": dict(shape="7b", B=64, ctx=512, K=10, pool="7b_throughput", n_max=3, steps=32, warmup=3,
                label="7B shape throughput: B=64, prompt 512 + generated, K=10, paged KV (BASELINE configs[3])"),
-    "7b_b8": dict(shape="7b", B=8, ctx=1024, K=8, pool="7b_latency", n_max=3, steps=30, warmup=4,
+    "7b_b8": dict(shape="7b", B=8, ctx=1024, K=8, pool="7b_latency", n_max=3, steps=50, warmup=4,
                   label="7B shape, small batch: B=8, context 1024, K=8 (72 rows: between the latency and the throughput workload)"),
-    "1b": dict(shape="1b", B=8, ctx=512, K=8, pool="1b", n_max=3, steps=40, warmup=5,
+    "1b": dict(shape="1b", B=8, ctx=512, K=8, pool="1b", n_max=3, steps=50, warmup=5,
                label="1B shape: B=8, context 512, K=8 (BASELINE configs[1])"),
     "tiny": dict(shape="tiny", B=2, ctx=64, K=4, pool="tiny", n_max=3, steps=20, warmup=3,
                  label="Tiny: B=2, context 64, K=4 (BASELINE configs[0])"),
