@@ -12,6 +12,7 @@ import numpy as np
 import torch
 
 MODE_RV, MODE_RV_OR_TOP1, MODE_TOPK_ONLY, MODE_TOPP_ONLY = 0, 1, 2, 3
+MAX_NGRAM, MAX_DRAFT, MAX_TOPK, MAX_TREE, MAX_OWN_TEXT = 8, 63, 8, 32, 4096      # LASER_MAX_* of include/laser.h
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None

@@ -64,3 +64,12 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text, f
+
+
+def test_binding_limits_agree_with_the_header():
+    import re as _re
+    from paper_2408_05676_amd import binding
+    src = open(HEADER).read()
+    for name in ("NGRAM", "DRAFT", "TOPK", "TREE", "OWN_TEXT"):
+        m = _re.search(r"#define\s+LASER_MAX_%s\s+(\d+)" % name, src)
+        assert m and int(m.group(1)) == getattr(binding, "MAX_" + name), name

@@ -293,3 +293,76 @@ def test_tree_loop_against_the_oracle_and_accepted_length_gain():
     print(f"[tree loop] accepted drafts per step and sequence: chain of 8 tokens {accepted[('chain', 8)]:.2f}, tree of 8 nodes "
           f"{accepted[('tree', 8)]:.2f}, tree of 16 nodes {accepted[('tree', 16)]:.2f}")
     assert accepted[("tree", 16)] >= accepted[("chain", 8)] > 0
+
+
+def test_tree_and_generate_edge_cases():
+    """Empty batches and trees, the largest tree, malformed parent entries, a one-token generation and an
+    end-of-sequence token that comes first."""
+    laser = _laser()
+    sh = synth.SHAPES["tiny128"].with_(lm_gain=4.0)
+    dec = _oracle(sh)
+    B, K, ctx_len = 2, laser.binding.MAX_TREE, 19
+    cap = ctx_len + 3 * (K + 1) + 16
+    model = gu.make_model(sh, max_rows=B * (K + 1), max_batch=B, max_pos=cap + 16)
+    kv = gu.make_kv(sh, n_pages=B * (cap // 16 + 2), max_seqs=B, max_pages_per_seq=cap // 16 + 2)
+    ids = [0, 1]
+    for s in ids:
+        kv.reserve(s, cap)
+    prompts = synth.uniform_tokens(33, 60, 0, B * ctx_len, sh.vocab).reshape(B, ctx_len)
+    pend = gu.prefill(model, kv, ids, prompts)
+    seqs = [step.Sequence(dec, 0, prompts[b], cap) for b in range(B)]
+    # B = 0 and K = 0 calls are no-ops / plain one-token steps
+    e = torch.empty((0, 4), dtype=torch.int32, device="cuda")
+    e1 = torch.empty(0, dtype=torch.int32, device="cuda")
+    laser.verify_tree(model, kv, [], e1, e, e, e1, 1, 0.0)
+    laser.kv_commit_tree(kv, [], e1, e)
+    # the largest tree (32 nodes): a wide root, a deep branch, and entries that do not name an earlier node (they hang off the root)
+    r = np.random.default_rng(8)
+    good = step.autoregressive_greedy(dec, _clone(dec, seqs[0], cap), 6)
+    tokens = r.integers(0, sh.vocab, size=(B, K)).astype(np.int32)
+    parents = np.full((B, K), -1, dtype=np.int32)
+    parents[0, 16:] = np.arange(15, K - 1)                    # nodes 16..31: a chain below node 15 ...
+    tokens[0, 15] = good[0]
+    tokens[0, 16:21] = good[1:6]                              # ... that carries the model's own continuation
+    parents[1, 1:] = [int(r.integers(-1, i)) for i in range(1, K)]
+    bad = parents.copy()
+    bad[1, 5], bad[1, 9] = 7, -4                              # not earlier nodes: read as -1
+    parents[1, 5], parents[1, 9] = -1, -1
+    nn = np.array([K, K], dtype=np.int32)
+    acc, out, path, logits = laser.verify_tree(model, kv, ids, pend, torch.tensor(tokens, device="cuda"), torch.tensor(bad, device="cuda"),
+                                               torch.tensor(nn, device="cuda"), 1, -1.0, 0, want_logits=True)
+    laser.kv_commit_tree(kv, ids, acc, path)
+    torch.cuda.synchronize()
+    ora = step.verify_tree_step(dec, seqs, tokens, parents, nn, 1, -1.0, 0, return_logits=True)
+    ok, max_err, ratio = gu.logits_close(logits.cpu().numpy().astype(np.float64), ora["logits"])
+    assert ok, (max_err, ratio)
+    assert acc.cpu().tolist() == ora["accept_len"].tolist() and acc.cpu().tolist()[0] == 6
+    assert path.cpu().numpy().tolist() == ora["accept_path"].tolist() and out.cpu().numpy().tolist() == ora["out_tokens"].tolist()
+    assert kv.read_lens(ids).tolist() == [s.cache.length for s in seqs]
+    # an empty tree is a plain one-token step
+    pend = torch.tensor([s.pending for s in seqs], dtype=torch.int32, device="cuda")
+    zero = torch.zeros(B, dtype=torch.int32, device="cuda")
+    acc, out, path, _ = laser.verify_tree(model, kv, ids, pend, torch.tensor(tokens, device="cuda"), torch.tensor(parents, device="cuda"), zero, 2, 0.1, 0)
+    laser.kv_commit_tree(kv, ids, acc, path)
+    ora = step.verify_tree_step(dec, seqs, tokens, parents, [0, 0], 2, 0.1, 0)
+    assert acc.cpu().tolist() == [0, 0] and out.cpu().numpy()[:, 0].tolist() == ora["out_tokens"][:, 0].tolist() and (out.cpu().numpy()[:, 1:] == -1).all()
+    # generation: one token; an end-of-sequence token that is the very first one; a look at the counter every step
+    pend = torch.tensor([s.pending for s in seqs], dtype=torch.int32, device="cuda")
+    tail = torch.tensor(np.stack([np.array(s.tokens[-3:], dtype=np.int32) for s in seqs]), device="cuda")
+    first = [int(np.argmax(dec.verify_forward(_clone(dec, s, cap).cache, [s.pending])[0])) for s in seqs]
+    gen, glen, cnt, steps, _ = laser.generate(model, kv, None, ids, None, tail, pend, 0, 1, 1, -1.0, 0, max_new_tokens=5, eos_token=first[0], check_every=1)
+    assert glen.cpu().tolist()[0] == 1 and gen.cpu().numpy()[0].tolist() == [first[0], -1, -1, -1, -1]
+    assert glen.cpu().tolist()[1] == (1 if first[1] == first[0] else 5) and steps == glen.max().item()
+    with pytest.raises(laser.LaserError):
+        laser.retrieve_tree(laser.Pool(np.zeros(4, dtype=np.int32), np.array([0, 4]), np.array([1]), 2), torch.zeros(1, dtype=torch.int64, device="cuda"),
+                            torch.zeros((1, 2), dtype=torch.int32, device="cuda"), 1, 2, K + 1)      # more nodes than LASER_MAX_TREE
+    model.close(); kv.close()
+
+
+def _clone(dec, s, cap):
+    c = step.Sequence.__new__(step.Sequence)
+    c.key, c.tokens = s.key, list(s.tokens)
+    c.cache = dec.new_cache(cap)
+    c.cache.k[:], c.cache.v[:] = s.cache.k, s.cache.v
+    c.cache.length = s.cache.length
+    return c
