@@ -278,6 +278,9 @@ def run_workload(args, name, steps, warmup, weights_cache):
     scratch = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     read_gbs, copy_gbs = laser.probe_hbm(scratch, reps=10)
     mfma_tflops = laser.probe_mfma_f16(scratch, reps=5)
+    exchange_us = exchange_errs = None
+    if path == "fused":                  # what one phase boundary of the persistent kernel costs
+        exchange_us, exchange_errs = laser.probe_exchange(scratch, 200)
     del scratch
     measured_peak = max(read_gbs, copy_gbs) if bound == "hbm" else mfma_tflops
     traffic = None
@@ -305,7 +308,8 @@ def run_workload(args, name, steps, warmup, weights_cache):
                      "peak": peak, "unit": unit, "frac": achieved / peak, "traffic": traffic,
                      work_key: dom_work, "avg_launch_us": dom_avg_s * 1e6, "launches": dom_n,
                      "measured_peak": measured_peak, "frac_of_measured_peak": achieved / measured_peak if measured_peak else None,
-                     "measured": {"hbm_read_GBs": read_gbs, "hbm_copy_GBs": copy_gbs, "mfma_f16_TFLOPs": mfma_tflops}},
+                     "measured": {"hbm_read_GBs": read_gbs, "hbm_copy_GBs": copy_gbs, "mfma_f16_TFLOPs": mfma_tflops,
+                                  "grid_exchange_us": exchange_us, "grid_exchange_errors": exchange_errs}},
     }
     eng.close()
     pool.close()

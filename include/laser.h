@@ -375,6 +375,12 @@ int laser_probe_mfma_f16(void* scratch, int reps, void* stream, float* tflops);
 /* laser_probe_launch: the floor under a latency-bound kernel such as the draft lookup -- the mean time of `reps`
  * back-to-back launches of a kernel of `blocks` wavefronts that does nothing (microseconds per launch). */
 int laser_probe_launch(int blocks, int reps, void* stream, float* us_per_launch);
+/* laser_probe_exchange: what one all-to-all exchange between the phases of the persistent few-row kernel costs on this
+ * device: a cooperative launch of one workgroup per compute unit repeats `iters` times { write-through store into a
+ * fresh region; wait for it; grid barrier (counter + flag); read values other workgroups stored } and the mean time of
+ * one round is returned in microseconds. *errors counts stale values read and expired (bounded) waits: it must be 0.
+ * scratch [dev]: caller-owned, at least 4096 + iters * 2048 * (compute units) bytes; it is overwritten. */
+int laser_probe_exchange(void* scratch, size_t bytes, int iters, void* stream, float* us_per_exchange, int* errors);
 
 #ifdef __cplusplus
 }

@@ -85,6 +85,7 @@ def lib():
         "laser_probe_hbm": [vp, C.c_size_t, i32, vp, C.POINTER(C.c_float), C.POINTER(C.c_float)],
         "laser_probe_mfma_f16": [vp, i32, vp, C.POINTER(C.c_float)],
         "laser_probe_launch": [i32, i32, vp, C.POINTER(C.c_float)],
+        "laser_probe_exchange": [vp, C.c_size_t, i32, vp, C.POINTER(C.c_float), C.POINTER(C.c_int)],
     }
     for name, args in protos.items():
         fn = getattr(L, name)
@@ -493,3 +494,13 @@ def probe_launch(blocks: int, reps: int = 200, stream=None) -> float:
     t = C.c_float()
     _check(lib().laser_probe_launch(blocks, reps, _stream(stream), C.byref(t)), "laser_probe_launch")
     return t.value
+
+
+def probe_exchange(scratch: torch.Tensor, iters: int = 200, stream=None):
+    """laser_probe_exchange: (microseconds per all-to-all exchange of a cooperative launch, error count)."""
+    if not (isinstance(scratch, torch.Tensor) and scratch.is_cuda and scratch.is_contiguous()):
+        raise LaserError("scratch must be a contiguous CUDA tensor")
+    t, e = C.c_float(), C.c_int()
+    _check(lib().laser_probe_exchange(scratch.data_ptr(), scratch.numel() * scratch.element_size(), iters, _stream(stream),
+                                      C.byref(t), C.byref(e)), "laser_probe_exchange")
+    return t.value, e.value

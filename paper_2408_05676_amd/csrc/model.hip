@@ -848,7 +848,8 @@ extern "C" int laser_model_destroy(laser_model* h) {
     if (!h) return LASER_OK;
     Model* m = reinterpret_cast<Model*>(h);
     void* ptrs[] = {m->kpart, m->wlm16, m->w16[0], m->w16[1], m->w16[2], m->w16[3], m->x, m->xn, m->xn_lo, m->q_lo, m->attn_lo, m->qkv, m->q, m->attn, m->act, m->row_pos, m->att_part, m->rope, m->hp_max,
-                    m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->cand_beg, m->cand_cnt, m->cand_x, m->node_cand, m->cand_lx, m->row_slot, m->row_anc};
+                    m->hp_sum, m->hp_arg, m->hp_topv, m->hp_topi, m->cand_beg, m->cand_cnt, m->cand_x, m->node_cand, m->cand_lx, m->row_slot, m->row_anc,
+                    m->row_mx, m->row_sum, m->row_arg, m->cand_rank};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     for (hipEvent_t e : m->prof_ev) (void)hipEventDestroy(e);
     fused_free(m);
@@ -884,6 +885,10 @@ extern "C" int laser_model_create(const laser_model_desc* desc, void* stream_, l
     M_TRY(hipMalloc((void**)&m->cand_x, R * 4));
     M_TRY(hipMalloc((void**)&m->node_cand, R * 4));
     M_TRY(hipMalloc((void**)&m->cand_lx, R * 4));
+    M_TRY(hipMalloc((void**)&m->row_mx, R * 4));
+    M_TRY(hipMalloc((void**)&m->row_sum, R * 4));
+    M_TRY(hipMalloc((void**)&m->row_arg, R * 4));
+    M_TRY(hipMalloc((void**)&m->cand_rank, R * 4));
     if (d.n_layers > 0) {
         M_TRY(hipMalloc((void**)&m->x, R * dm * 4));
         M_TRY(hipMalloc((void**)&m->qkv, R * dm * 3 * 4));

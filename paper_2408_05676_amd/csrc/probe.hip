@@ -60,6 +60,47 @@ __global__ __launch_bounds__(64) void probe_empty_kernel(int* sink) {
     if (sink == nullptr && threadIdx.x == 12345u) *sink = 0;
 }
 
+// One exchange between ALL workgroups of a cooperative launch, as the persistent few-row kernel does it between two
+// phases: every thread stores a value into a region nobody has read yet (write-through store), waits for the store to
+// complete, the workgroups meet at a grid barrier (one counter, the last arriver sets a flag on its own line), then
+// every thread reads four values other workgroups wrote (plain cached loads) and checks them. `iters` exchanges in
+// a row, each in a fresh region. Every wait is bounded; an expired wait or a stale value is counted in errs.
+__global__ __launch_bounds__(512) void probe_exchange_kernel(unsigned* count, unsigned* flag, int iters, float* buf, int* errs) {
+    __shared__ int ok_s;
+    const unsigned nwg = gridDim.x;
+    const size_t region = (size_t)512 * nwg;
+    int bad = 0;
+    for (int it = 0; it < iters; ++it) {
+        float* rb = buf + (size_t)it * region;
+        __hip_atomic_store(&rb[(size_t)threadIdx.x * nwg + blockIdx.x], (float)(it * 1000 + (int)blockIdx.x + 1), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const unsigned epoch = (unsigned)it + 1u;
+            bool ok = true;
+            const unsigned old = __hip_atomic_fetch_add(count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (old == epoch * nwg - 1u) {
+                __hip_atomic_store(flag, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                int spins = 0;
+                while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < epoch) {
+                    __builtin_amdgcn_s_sleep(1);
+                    if (++spins > 4000000) { ok = false; break; }
+                }
+            }
+            ok_s = ok ? 1 : 0;
+        }
+        __syncthreads();
+        if (!ok_s) { if (threadIdx.x == 0) atomicAdd(errs, 1000000); return; }
+        for (int j = 0; j < 4; ++j) {
+            const unsigned o = (blockIdx.x + (unsigned)j * 67u + (unsigned)it) % nwg;
+            if (rb[(size_t)threadIdx.x * nwg + o] != (float)(it * 1000 + (int)o + 1)) ++bad;
+        }
+    }
+    if (bad) atomicAdd(errs, bad);
+}
+
 // A pair of timing events that is destroyed on every way out of a probe.
 struct EventPair {
     hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -155,5 +196,44 @@ extern "C" int laser_probe_launch(int blocks, int reps, void* stream_v, float* u
     LASER_HIP_CHECK(hipEventElapsedTime(&ms, ev.e0, ev.e1));
     *us_per_launch = ms * 1e3f / (float)reps;
     LASER_HIP_CHECK(hipGetLastError());
+    return LASER_OK;
+}
+
+extern "C" int laser_probe_exchange(void* scratch, size_t bytes, int iters, void* stream_v, float* us_per_exchange, int* errors) {
+    LASER_REQUIRE(scratch != nullptr && us_per_exchange != nullptr && errors != nullptr, LASER_E_INVALID_ARG, "NULL argument");
+    LASER_REQUIRE(iters >= 1 && iters <= 10000, LASER_E_INVALID_ARG, "iters outside 1..10000");
+    hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
+    int ncu = 0, dev = 0, coop = 0;
+    LASER_HIP_CHECK(hipGetDevice(&dev));
+    LASER_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    LASER_HIP_CHECK(hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev));
+    LASER_REQUIRE(coop != 0, LASER_E_SHAPE, "the device does not support cooperative launches");
+    // layout of the caller's scratch: [0, 4096) counter / flag / error words on separate lines, then the exchange regions
+    const size_t region_bytes = (size_t)512 * ncu * sizeof(float);
+    LASER_REQUIRE(bytes >= 4096 + region_bytes * (size_t)iters, LASER_E_LIMIT, "scratch of %zu bytes is too small for %d exchanges (%zu needed)",
+                  bytes, iters, 4096 + region_bytes * (size_t)iters);
+    unsigned* count = reinterpret_cast<unsigned*>(scratch);
+    unsigned* flag = count + 64;
+    int* errs = reinterpret_cast<int*>(count + 128);
+    float* buf = reinterpret_cast<float*>(reinterpret_cast<char*>(scratch) + 4096);
+    EventPair ev;
+    LASER_HIP_CHECK(ev.create());
+    void* args[] = {&count, &flag, &iters, &buf, &errs};
+    // the first pass over fresh memory is several times slower than the steady state: one untimed launch, then the timed one
+    int total_errs = 0;
+    for (int pass = 0; pass < 2; ++pass) {
+        LASER_HIP_CHECK(hipMemsetAsync(scratch, 0, 4096 + region_bytes * (size_t)iters, stream));
+        LASER_HIP_CHECK(hipEventRecord(ev.e0, stream));
+        LASER_HIP_CHECK(hipLaunchCooperativeKernel(reinterpret_cast<const void*>(probe_exchange_kernel), dim3((unsigned)ncu), dim3(512), args, 0, stream));
+        LASER_HIP_CHECK(hipEventRecord(ev.e1, stream));
+        int e = 0;
+        LASER_HIP_CHECK(hipMemcpyAsync(&e, errs, sizeof(int), hipMemcpyDeviceToHost, stream));
+        LASER_HIP_CHECK(hipStreamSynchronize(stream));
+        total_errs += e;
+    }
+    float ms = 0.f;
+    LASER_HIP_CHECK(hipEventElapsedTime(&ms, ev.e0, ev.e1));
+    *errors = total_errs;
+    *us_per_exchange = ms * 1e3f / (float)iters;
     return LASER_OK;
 }

@@ -74,6 +74,11 @@ struct Model {
     int32_t* cand_x = nullptr;
     int32_t* node_cand = nullptr;
     float* cand_lx = nullptr;
+    // acceptance, between its per-row and its per-sequence kernel: [max_rows] each
+    float* row_mx = nullptr;
+    float* row_sum = nullptr;
+    int32_t* row_arg = nullptr;
+    int32_t* cand_rank = nullptr;
     // optional timing of the dominant kernel (laser_profile_begin / laser_profile_end)
     std::vector<hipEvent_t> prof_ev;   // start/stop pairs
     int prof_cap = 0, prof_n = 0;

@@ -21,3 +21,13 @@ def test_probes_return_plausible_peaks_and_check_arguments():
         laser.probe_hbm(torch.zeros(1024, dtype=torch.uint8, device="cuda"))
     with pytest.raises(laser.LaserError):
         laser.probe_mfma_f16(buf, reps=0)
+
+
+def test_exchange_probe_reads_no_stale_value():
+    """The write-once exchange the persistent kernel relies on (write-through stores, grid barrier, plain cached loads of
+    lines nobody has read before): 300 rounds between all compute units without a stale value or an expired wait."""
+    import paper_2408_05676_amd as laser
+    scratch = torch.empty(4096 + 300 * 2048 * 304, dtype=torch.uint8, device="cuda")
+    us, errs = laser.probe_exchange(scratch, 300)
+    print(f"[probe] one all-to-all exchange: {us:.2f} us")
+    assert errs == 0 and 0.5 < us < 100.0
