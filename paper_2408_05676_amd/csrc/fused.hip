@@ -303,32 +303,32 @@ __device__ inline void prefetch_first(const FusedArgs& a, const Phase& ph, int c
 // Copy rows 0..M-1, steps cs0 .. cs0+ncs-1 of the fp16 activations X[16][Kd] into LDS and, for split
 // activations, of their 8-bit low plane Xlo[16][Kd] right behind them in the same LDS row: a row is
 // ncs*256 bytes (+ ncs*128 bytes) + 16 bytes of padding, so that the 16-byte operand reads of 16 rows
-// fall into distinct banks.
+// fall into distinct banks. The copy uses loads that write LDS directly (16 bytes per lane, lane l of an
+// instruction lands at the instruction's LDS base + 16 l): a block of 64 consecutive pieces of one row and
+// plane per instruction, the blocks dealt round-robin to the waves. No registers hold the data, so all of a
+// wave's blocks are in flight at once and the addressing is a handful of scalar operations per block.
 __device__ inline void stage_x(const FusedArgs& a, uint4* xs, const uint16_t* X, const uint8_t* Xlo, int Kd, int cs0, int ncs) {
-    constexpr int Q = 16;                       // 16-byte pieces per thread and pass: one pass covers 16 rows x 32 steps
-    const int hi_row = ncs * 16, per_row = Xlo ? hi_row + ncs * 8 : hi_row;
-    const int total = a.M * per_row, stride = per_row + 1;
-    const uint32_t inv = 0xFFFFFFFFu / (uint32_t)per_row + 1u;     // i / per_row == umulhi(i, inv) for i * per_row < 2^32
-    const uint4* src = reinterpret_cast<const uint4*>(X) + cs0 * 16;
-    const uint4* src_lo = reinterpret_cast<const uint4*>(Xlo ? (const void*)Xlo : (const void*)X) + cs0 * 8;
-    for (int i0 = threadIdx.x; i0 < total; i0 += FT * Q) {
-        uint4 v[Q];
-        int dst[Q];
-#pragma unroll
-        for (int q = 0; q < Q; ++q) {
-            // every load is issued unconditionally (clamped index): a load under a branch would be
-            // waited for at the branch's join and the pieces would arrive one round trip after the other
-            const int i = i0 + q * FT, ic = min(i, total - 1);
-            const int row = (int)__umulhi((uint32_t)ic, inv), c = ic - row * per_row;
-            dst[q] = i < total ? row * stride + c : -1;
-            const bool low = c >= hi_row;
-            const uint4* p = low ? src_lo + (size_t)row * (Kd / 16) + (c - hi_row) : src + (size_t)row * (Kd / 8) + c;
-            v[q] = *p;
-        }
-#pragma unroll
-        for (int q = 0; q < Q; ++q)
-            if (dst[q] >= 0) xs[dst[q]] = v[q];
+    typedef const void __attribute__((address_space(1))) * gptr_t;
+    typedef void __attribute__((address_space(3))) * lptr_t;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int hi_p = ncs * 16, lo_p = Xlo ? ncs * 8 : 0;              // 16-byte pieces of a row, per plane
+    const int bh = (hi_p + 63) >> 6, bpr = bh + ((lo_p + 63) >> 6);    // 64-piece blocks per row: high plane, both
+    const int stride = hi_p + lo_p + 1, total = a.M * bpr;
+    const char* xh = reinterpret_cast<const char*>(X) + (size_t)cs0 * 256;
+    const char* xl = reinterpret_cast<const char*>(Xlo ? (const void*)Xlo : (const void*)X) + (size_t)cs0 * 128;
+    int row = 0, blk = wave;
+    while (blk >= bpr) { blk -= bpr; ++row; }
+    for (int j = wave; j < total; j += FWAVES) {
+        const bool low = blk >= bh;
+        const int b0 = (low ? blk - bh : blk) * 64;                    // first piece of the block inside its plane
+        const int n = (low ? lo_p : hi_p) - b0;                        // pieces the plane has from there on (>= 1)
+        const char* src = low ? xl + (size_t)row * Kd : xh + (size_t)row * Kd * 2;
+        uint4* dst = xs + row * stride + (low ? hi_p : 0) + b0;
+        if (lane < n) __builtin_amdgcn_global_load_lds((gptr_t)(src + (size_t)(b0 + lane) * 16), (lptr_t)dst, 16, 0, 0);
+        blk += FWAVES;
+        while (blk >= bpr) { blk -= bpr; ++row; }
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 // Streams one chunk: this wave's units x steps, partial sums of finished units to sh.red
