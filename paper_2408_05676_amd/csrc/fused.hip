@@ -8,8 +8,8 @@
 // barrier (one agent-scope atomic counter + a separate flag line); per layer:
 //     QKV(+RoPE) | attention | O-proj(+residual) | gate/up(+SwiGLU) | down(+residual)
 // * Weight streaming: a GEMM unit is a 16-feature tile (or a pair of tiles); the 8 waves of a
-//   workgroup split its reduction dimension, each lane reading 64 contiguous bytes per step
-//   (k-permuted MFMA operands), partial sums meet in LDS. Each wave keeps 16 KiB of weights in
+//   workgroup split its reduction dimension, the four lanes of a weight row reading 64 contiguous bytes
+//   per instruction (the MFMA operands of weights and activations take the same k order), partial sums meet in LDS. Each wave keeps 16 KiB of weights in
 //   flight in a register ring and issues the first steps of the NEXT phase while the barrier
 //   resolves, so HBM stays busy (weights never depend on activations). The few activation rows are
 //   staged into LDS once per workgroup and phase instead of being re-read per step.
@@ -214,9 +214,13 @@ __device__ inline int unit_row(const FusedArgs& a, int kind, int u, int st) {
     return (w + u * nwg) * 16;
 }
 
+// One step of one weight tile: 16 rows x 128 reduction elements. Fragment c of lane (r = lane & 15, g = lane >> 4)
+// holds elements 32 c + 8 g .. + 7 of row r, so the four lanes of a row read 64 contiguous bytes per instruction
+// and an instruction touches 16 half lines (a lane reading its own 64 contiguous bytes would spread every
+// instruction over 32 lines, each requested four times per step).
 __device__ inline void load_w(Frag8 (&f)[4], const uint16_t* p) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) f[c].u = *reinterpret_cast<const uint4*>(p + c * 8);
+    for (int c = 0; c < 4; ++c) f[c].u = *reinterpret_cast<const uint4*>(p + c * 32);
 }
 
 // The reduction dimension is processed in chunks whose activations fit the LDS staging area
@@ -253,7 +257,7 @@ __device__ inline WaveWork wave_work(const FusedArgs& a, const Phase& ph, int ch
 }
 
 __device__ inline const uint16_t* w_ptr(const FusedArgs& a, const Phase& ph, int u, int st, int ks, int lane) {
-    return ph.W + (size_t)(unit_row(a, ph.kind, u, st) + (lane & 15)) * ph.Kd + ks * 128 + (lane >> 4) * 32;
+    return ph.W + (size_t)(unit_row(a, ph.kind, u, st) + (lane & 15)) * ph.Kd + ks * 128 + (lane >> 4) * 8;
 }
 
 // Weight streaming through a register ring. A step (128 reduction elements) of a phase with NA
@@ -383,8 +387,8 @@ __device__ inline void stream_chunk(const FusedArgs& a, Shared& sh, const uint4*
         }
         // this lane's activation operand: row r (padding rows read row 0; their results are dropped)
         const uint4* xrow = xs + (r < a.M ? r : 0) * (w.ncs * (SPLIT ? 24 : 16) + 1);
-        const uint4* xl = xrow + (w.ks0 - w.cs0) * 16 + g * 4;
-        const uint4* xlo = xrow + w.ncs * 16 + (w.ks0 - w.cs0) * 8 + g * 2;    // 8-bit low plane behind the high plane
+        const uint4* xl = xrow + (w.ks0 - w.cs0) * 16 + g;                     // fragment c of step k: xl[16 k + 4 c]
+        const uint2* xlo = reinterpret_cast<const uint2*>(xrow + w.ncs * 16) + (w.ks0 - w.cs0) * 16 + g;   // 8-bit low plane behind the high plane: xlo[16 k + 4 c]
         float4_t acc[NA], acl[NA];
 #pragma unroll
         for (int s = 0; s < NA; ++s) { acc[s] = float4_t{0.f, 0.f, 0.f, 0.f}; acl[s] = float4_t{0.f, 0.f, 0.f, 0.f}; }
@@ -396,13 +400,13 @@ __device__ inline void stream_chunk(const FusedArgs& a, Shared& sh, const uint4*
                 if (t0 + j < w.T) {                           // no vector-memory instructions inside this branch
                     Frag8 Bf[4], Bl[4];
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) Bf[c].u = xl[k * 16 + c];
+                    for (int c = 0; c < 4; ++c) Bf[c].u = xl[k * 16 + c * 4];
                     if constexpr (SPLIT) {
-                        const uint4 l0 = xlo[k * 8], l1 = xlo[k * 8 + 1];
-                        b8x8_to_f16x8(l0.x, l0.y, Bl[0]);
-                        b8x8_to_f16x8(l0.z, l0.w, Bl[1]);
-                        b8x8_to_f16x8(l1.x, l1.y, Bl[2]);
-                        b8x8_to_f16x8(l1.z, l1.w, Bl[3]);
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            const uint2 lo8 = xlo[k * 16 + c * 4];
+                            b8x8_to_f16x8(lo8.x, lo8.y, Bl[c]);
+                        }
                     }
 #pragma unroll
                     for (int s = 0; s < NA; ++s) {
