@@ -271,38 +271,40 @@ __device__ inline const uint16_t* w_ptr(const FusedArgs& a, const Phase& ph, int
 // counters are exact only in straight-line code; finished units leave their partial sums in LDS
 // inside the loop and every epilogue runs after it.
 
-// What survives a phase boundary: the weights issued ahead for the next phase (its first two steps
-// if NA = 2, first four if NA = 1), every fragment (re)defined by prefetch_first so that nothing
-// older stays live across the attention phase.
+// What survives a phase boundary: the weights issued ahead for the next phase (its first step if
+// NA = 2, first two if NA = 1; see prime_steps).
 struct Ring {
-    Frag8 f[4][4];
-    int primed;           // how many leading steps of the coming chunk already have their weights issued
+    Frag8 f[6][4];        // slot (step % DS) * NA + stream; DS - 1 steps are in flight while one is consumed
 };
 template <int NA> struct RingCfg { static constexpr int DS = NA == 2 ? 3 : 5; };
 
-// Issue the weights of this wave's first DS-1 steps of chunk `chunk` of phase `ph` (called while a
-// grid barrier resolves or activations are being staged: weights never depend on activations).
-template <int NA>
-__device__ inline void prefetch_first(const FusedArgs& a, const Phase& ph, int chunk, Ring& R) {
-    constexpr int DS = RingCfg<NA>::DS;
+// Issue the weights of this wave's steps T0 .. T1-1 (of the first DS-1) of chunk `chunk` of phase `ph` into
+// their ring slots. Weights never depend on activations, so the first PF1 steps are issued while the grid
+// barrier in front of the phase resolves and the others right behind the requests that stage the phase's
+// activations. Issuing a wave's whole ring inside the barrier stalls it there for microseconds (the compute
+// unit's memory queues hold less than 8 waves x 16 KiB), which delays the barrier's exit by more than the
+// early start gains: PF1 = half the ring measured best. The loads are unconditional (steps past the wave's
+// last one re-request one cached line), so that the number of vector-memory instructions issued here is a
+// compile-time constant: stage_wait counts on it.
+constexpr int pf1_steps(int NA) { return NA == 2 ? 1 : 2; }
+constexpr int PF1_O = 0;          // the O projection's first steps would queue in front of the attention phase's key / value loads
+template <int NA, int T0, int T1>
+__device__ inline void prime_steps(const FusedArgs& a, const Phase& ph, int chunk, Ring& R) {
     const int lane = threadIdx.x & 63;
     const WaveWork w = wave_work(a, ph, chunk);
-    R.primed = 0;
+    const int nks = max(w.nks, 1);
+    const uint16_t* park = reinterpret_cast<const uint16_t*>(a.gf);
 #pragma unroll
-    for (int t = 0; t < DS - 1; ++t) {
-        if (t < w.T) {
+    for (int t = T0; t < T1; ++t) {
+        const bool on = t < w.T;
+        const int tc = on ? t : 0;
 #pragma unroll
-            for (int s = 0; s < NA; ++s)
-                load_w(R.f[t * NA + s], w_ptr(a, ph, t / w.nks, s, w.ks0 + t % w.nks, lane));
-            R.primed = t + 1;
-        } else {
-#pragma unroll
-            for (int s = 0; s < NA; ++s)
-#pragma unroll
-                for (int c = 0; c < 4; ++c) R.f[t * NA + s][c].u = make_uint4(0, 0, 0, 0);
-        }
+        for (int s = 0; s < NA; ++s)
+            load_w(R.f[t * NA + s], on ? w_ptr(a, ph, tc / nks, s, w.ks0 + tc % nks, lane) : park);
     }
 }
+// vector-memory instructions prime_steps<NA, T0, T1> issues
+template <int NA, int T0, int T1> struct PrimeCount { static constexpr int value = (T1 - T0) * NA * 4; };
 
 // Copy rows 0..M-1, steps cs0 .. cs0+ncs-1 of the fp16 activations X[16][Kd] into LDS and, for split
 // activations, of their 8-bit low plane Xlo[16][Kd] right behind them in the same LDS row: a row is
@@ -310,9 +312,9 @@ __device__ inline void prefetch_first(const FusedArgs& a, const Phase& ph, int c
 // fall into distinct banks. The copy uses loads that write LDS directly (16 bytes per lane, lane l of an
 // instruction lands at the instruction's LDS base + 16 l): a block of 64 consecutive pieces of one row and
 // plane per instruction, the blocks dealt round-robin to the waves. No registers hold the data, so all of a
-// wave's blocks are in flight at once and the addressing is a handful of scalar operations per block.
+// wave's blocks are in flight at once and the addressing is a handful of scalar operations per block. The
+// caller waits for them with stage_wait.
 __device__ inline void stage_x(const FusedArgs& a, uint4* xs, const uint16_t* X, const uint8_t* Xlo, int Kd, int cs0, int ncs) {
-    typedef const void __attribute__((address_space(1))) * gptr_t;
     typedef void __attribute__((address_space(3))) * lptr_t;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int hi_p = ncs * 16, lo_p = Xlo ? ncs * 8 : 0;              // 16-byte pieces of a row, per plane
@@ -328,11 +330,23 @@ __device__ inline void stage_x(const FusedArgs& a, uint4* xs, const uint16_t* X,
         const int n = (low ? lo_p : hi_p) - b0;                        // pieces the plane has from there on (>= 1)
         const char* src = low ? xl + (size_t)row * Kd : xh + (size_t)row * Kd * 2;
         uint4* dst = xs + row * stride + (low ? hi_p : 0) + b0;
-        if (lane < n) __builtin_amdgcn_global_load_lds((gptr_t)(src + (size_t)(b0 + lane) * 16), (lptr_t)dst, 16, 0, 0);
+        // Written as assembly so that the compiler does not track the request: it would wait for it (and for every
+        // weight load behind it) at the first unrelated reuse of the address registers. The caller's stage_wait is the
+        // wait that counts. m0 = the block's LDS byte address; one wait state between writing m0 and its use.
+        const uint32_t lds_at = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lptr_t)dst);
+        const char* g = src + (size_t)(b0 + lane) * 16;
+        if (lane < n)
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_at) : "memory", "m0");
         blk += FWAVES;
         while (blk >= bpr) { blk -= bpr; ++row; }
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+// Waits for this wave's staging requests, leaving the N vector-memory instructions issued after them (the
+// weight steps of prime_steps) in flight: the counter retires in issue order.
+template <int N>
+__device__ inline void stage_wait() {
+    static_assert(N >= 0 && N < 64, "the wait counter has six bits");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
 // Streams one chunk: this wave's units x steps, partial sums of finished units to sh.red
@@ -344,7 +358,7 @@ __device__ inline void stream_chunk(const FusedArgs& a, Shared& sh, const uint4*
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
     if (w.T > 0) {
-        Frag8 A[DS * NA][4];
+        Frag8 (&A)[6][4] = R.f;             // the ring: steps 0 .. DS-2 are on their way (prime_steps)
         const uint16_t* wp[NA];             // this lane's pointers to the next step to request
         int jn = 0, kn = 0;                 // (unit, step) of that step
         // Past the last step the pointers park on one lane-uniform, always-valid address, so the
@@ -372,19 +386,9 @@ __device__ inline void stream_chunk(const FusedArgs& a, Shared& sh, const uint4*
             advance();
         };
         set_unit(0);
-        // prologue: steps 0 .. DS-2 (weights possibly already issued before the barrier)
+        // steps 0 .. DS-2 have been requested by prime_steps: move the request pointers behind them
 #pragma unroll
-        for (int t = 0; t < DS - 1; ++t) {
-            if (t < R.primed) {
-#pragma unroll
-                for (int s = 0; s < NA; ++s)
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) A[t * NA + s][c] = R.f[t * NA + s][c];
-                advance();
-            } else {
-                request(t);
-            }
-        }
+        for (int t = 0; t < DS - 1; ++t) advance();
         // this lane's activation operand: row r (padding rows read row 0; their results are dropped)
         const uint4* xrow = xs + (r < a.M ? r : 0) * (w.ncs * (SPLIT ? 24 : 16) + 1);
         const uint4* xl = xrow + (w.ks0 - w.cs0) * 16 + g;                     // fragment c of step k: xl[16 k + 4 c]
@@ -441,26 +445,39 @@ __device__ inline void stream_chunk(const FusedArgs& a, Shared& sh, const uint4*
 #pragma unroll
             for (int i = 0; i < 4; ++i) sh.red[j][wave][i][lane] = 0.f;
     }
-    R.primed = 0;
 }
 
 // Streams a whole phase: for every chunk stage its activations, stream, and issue the next chunk's
 // first weights before the staging barrier. On return sh.red holds every unit's partial sums and
 // all waves have passed a workgroup barrier.
-template <int NA, bool SPLIT, bool TR>
+template <int NA, bool SPLIT, bool TR, int PF1 = pf1_steps(NA)>
 __device__ inline void stream_phase(const FusedArgs& a, Shared& sh, uint4* xs, const Phase& ph,
                                     const uint16_t* __restrict__ X, const uint8_t* __restrict__ Xlo, Ring& R,
                                     int trace_layer = -1, int trace_slot = 0) {
+    constexpr int DS = RingCfg<NA>::DS;
     const int nch = n_chunks(a, ph);
     for (int c = 0; c < nch; ++c) {
         const WaveWork w = wave_work(a, ph, c);
         if (c > 0) __syncthreads();                     // every wave has finished reading the previous chunk
         if (c == 0) stamp_fine<TR>(a, trace_layer, trace_slot + 2);
         stage_x(a, xs, X, SPLIT ? Xlo : nullptr, ph.Kd, w.cs0, w.ncs);
+        // the ring's remaining steps travel behind the staging requests (chunk 0: steps 0 .. PF1-1 were issued
+        // inside the barrier)
+        // (the fences keep the compiler from moving weight loads in front of the staging requests: stage_wait
+        // relies on the issue order)
+        __builtin_amdgcn_sched_barrier(0);
+        if (c == 0) {
+            prime_steps<NA, PF1, DS - 1>(a, ph, c, R);
+            __builtin_amdgcn_sched_barrier(0);
+            stage_wait<PrimeCount<NA, PF1, DS - 1>::value>();
+        } else {
+            prime_steps<NA, 0, DS - 1>(a, ph, c, R);
+            __builtin_amdgcn_sched_barrier(0);
+            stage_wait<PrimeCount<NA, 0, DS - 1>::value>();
+        }
         __syncthreads();
         if (c == 0) stamp_fine<TR>(a, trace_layer, trace_slot);
         stream_chunk<NA, SPLIT>(a, sh, xs, ph, w, c == 0, R);
-        if (c + 1 < nch) prefetch_first<NA>(a, ph, c + 1, R);
     }
     __syncthreads();
     stamp_fine<TR>(a, trace_layer, trace_slot + 1);
@@ -1001,7 +1018,6 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
     __syncthreads();
 
     Ring ring;
-    ring.primed = 0;
     uint4* xs = reinterpret_cast<uint4*>(smem_raw + XS_OFFSET);
     const Phase p_head{a.wlm, PH_HEAD, a.d, 1};
 
@@ -1042,7 +1058,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         {
             const Phase p_q{a.wqkv + (size_t)l * 3 * a.d * a.d, PH_QKV, a.d, 2};
             stamp<TR>(a, ns);
-            if (!grid_sync(a, sh, epoch, [&] { prefetch_first<1>(a, p_q, 0, ring); })) return;
+            if (!grid_sync(a, sh, epoch, [&] { prime_steps<1, 0, pf1_steps(1)>(a, p_q, 0, ring); })) return;
             stamp<TR>(a, ns);
         }
         const float* x_in = a.xbuf + (size_t)(2 * l) * XS;           // after the previous layer
@@ -1122,7 +1138,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
             });
         }
         stamp<TR>(a, ns);
-        if (!grid_sync(a, sh, epoch, [&] { prefetch_first<1>(a, p_o, 0, ring); })) return;
+        if (!grid_sync(a, sh, epoch, [&] { prime_steps<1, 0, PF1_O>(a, p_o, 0, ring); })) return;
         stamp<TR>(a, ns);
 
         // ---- attention ----
@@ -1135,7 +1151,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         {
             float ss = 0.f;
             const float* g2 = a.g2 + (size_t)l * a.d;
-            stream_phase<1, true, TR>(a, sh, xs, p_o, a.attn + lo, a.attnl + lo, ring, l, 3);
+            stream_phase<1, true, TR, PF1_O>(a, sh, xs, p_o, a.attn + lo, a.attnl + lo, ring, l, 3);
             reduce_epilogue<1>(a, sh, n_units(a, PH_O), [&](int u, int row, int f0, float (&v)[1][2]) {
                 const int item = w + u * nwg;
                 const size_t o = (size_t)row * a.d + item * 16 + f0;
@@ -1151,7 +1167,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
             publish_ss(sh, ss_mid + (size_t)blockIdx.x * 16, ss);
         }
         stamp<TR>(a, ns);
-        if (!grid_sync(a, sh, epoch, [&] { prefetch_first<2>(a, p_gu, 0, ring); })) return;
+        if (!grid_sync(a, sh, epoch, [&] { prime_steps<2, 0, pf1_steps(2)>(a, p_gu, 0, ring); })) return;
         stamp<TR>(a, ns);
 
         // ---- gate/up + SwiGLU ----
@@ -1174,7 +1190,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
             });
         }
         stamp<TR>(a, ns);
-        if (!grid_sync(a, sh, epoch, [&] { prefetch_first<1>(a, p_dn, 0, ring); })) return;
+        if (!grid_sync(a, sh, epoch, [&] { prime_steps<1, 0, pf1_steps(1)>(a, p_dn, 0, ring); })) return;
         stamp<TR>(a, ns);
 
         // ---- down projection + residual; publish x, x*gain(next norm), sum of squares ----
@@ -1199,7 +1215,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         }
     }
     stamp<TR>(a, ns);
-    if (!grid_sync(a, sh, epoch, [&] { prefetch_first<1>(a, p_head, 0, ring); })) return;
+    if (!grid_sync(a, sh, epoch, [&] { prime_steps<1, 0, pf1_steps(1)>(a, p_head, 0, ring); })) return;
     stamp<TR>(a, ns);
 
     // ---- output head + acceptance ----
