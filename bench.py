@@ -572,6 +572,76 @@ def run_study(args):
             "lm_gain": sh.lm_gain, "eos_class_size": eos_class, "rows": rows}
 
 
+def run_phase_trace(args):
+    """Phase table of the persistent few-row kernel (option fused_trace: thread 0 of every workgroup stamps the wall
+    clock at phase edges): the latency workload's launch shape (7B width, B = 1, context 1024, K = 8) on a model of
+    --trace-layers layers, microseconds per layer averaged over the layers and workgroups."""
+    import torch
+    import synth
+    from paper_2408_05676_amd.harness import Engine, stacked_weights
+    from synth.model import torch_gen_weight
+
+    L = args.trace_layers
+    sh = synth.SHAPES["7b"].with_(n_layers=L)
+    B, K, ctx_len, n_max = 1, 8, 1024, 3
+    weights = stacked_weights(lambda n, l: torch_gen_weight(sh, n, l, "cuda"), sh)
+    eng = Engine(sh, weights, B, K, ctx_len + 256, n_max)
+    ctx = synth.gen_contexts(synth.POOLS["7b_latency"], B, ctx_len, n_max, salt=1, min_remaining=K)
+    eng.prefill(ctx["ctx"])
+    eng.draft_len.fill_(K)
+    eng.drafts.fill_(5)
+    for _ in range(3):
+        eng.step(2, 0.1, retrieve=False)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        eng.step(2, 0.1, retrieve=False)
+    e1.record()
+    torch.cuda.synchronize()
+    untraced_ms = e0.elapsed_time(e1) / 10
+    eng.model.set_option("fused_trace", 1)
+    eng.step(2, 0.1, retrieve=False)
+    eng.step(2, 0.1, retrieve=False)
+    torch.cuda.synchronize()
+    tr = eng.model.read_trace().astype(np.float64) / 100.0          # the counter runs at 100 MHz: microseconds
+    names = ["qkv", "attention", "o_proj", "gate_up", "down"]
+    r1 = lambda x: round(float(x), 1)
+    phases = {}
+    i = 2
+    for n in names:
+        body, wait = [], []
+        for l in range(L):
+            j = i + 10 * l
+            body.append(tr[:, j] - tr[:, j - 1])
+            wait.append(tr[:, j + 1] - tr[:, j])
+        body, wait = np.array(body), np.array(wait)
+        phases[n] = {"body_mean": r1(body.mean()), "body_slowest_wg": r1(body.max(axis=1).mean()),
+                     "barrier_wait_mean": r1(wait.mean()), "barrier_wait_last_arriver": r1(wait.min(axis=1).mean())}
+        i += 2
+    fb = 2 * (5 * L + 2) + 4
+    for pi, n in enumerate(["qkv", "o_proj", "gate_up", "down"]):
+        pre, st, sm, ep = [], [], [], []
+        for l in range(L):
+            base = 2 + 10 * l + {0: 0, 1: 4, 2: 6, 3: 8}[pi]          # this phase's stamp in front of its barrier
+            f = tr[:, fb + 16 * l + 3 * pi: fb + 16 * l + 3 * pi + 3]   # staged, streamed, staging begins
+            pre.append(f[:, 2] - tr[:, base - 1])
+            st.append(f[:, 0] - f[:, 2])
+            sm.append(f[:, 1] - f[:, 0])
+            ep.append(tr[:, base] - f[:, 1])
+        phases[n].update({"before_staging": r1(np.mean(pre)), "staging_and_ring_fill": r1(np.mean(st)),
+                          "streaming": r1(np.mean(sm)), "epilogue": r1(np.mean(ep))})
+    i_end = 2 + 10 * L
+    out = {"phase_trace": {"layers": L, "launch_shape": "7B width, B=1, context 1024, K=8 (9 rows)", "unit": "us",
+                           "untraced_ms_per_step": round(untraced_ms, 4),
+                           "per_layer": r1((tr[:, 1 + 10 * L] - tr[:, 1]).mean() / L), "phases": phases,
+                           "embedding": r1((tr[:, 0] - tr[:, 0].min()).max() + np.mean(tr[:, 1] - tr[:, 0])),
+                           "head_body_slowest_wg": r1((tr[:, i_end] - tr[:, i_end - 1]).max()),
+                           "acceptance_slowest_wg": r1((tr[:, i_end + 2] - tr[:, i_end + 1]).max())}}
+    eng.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -580,6 +650,9 @@ def main():
     ap.add_argument("--workload", default="c3", choices=sorted(WORKLOADS) + ["stress"])
     ap.add_argument("--study", action="store_true", help="run the generation-loop study instead of a timed workload (prints one JSON object)")
     ap.add_argument("--study-shape", default="1b", choices=["tiny", "1b", "7b"])
+    ap.add_argument("--phase-trace", action="store_true",
+                    help="print the persistent few-row kernel's per-phase timing table (one JSON object) instead of a timed workload")
+    ap.add_argument("--trace-layers", type=int, default=8, help="layers of the model --phase-trace runs (7B width)")
     ap.add_argument("--regime", default="rv", choices=["rv", "strict", "floor"],
                     help="rv: k=2 p=0.1 (Eq. 8) on a sharpened head; strict: greedy (Eq. 4); floor: no pool replay")
     ap.add_argument("--lm-gain", type=float, default=None)
@@ -610,6 +683,9 @@ def main():
 
     if args.study:
         print(json.dumps(run_study(args)))
+        return
+    if args.phase_trace:
+        print(json.dumps(run_phase_trace(args)))
         return
     if args.workload == "stress":
         print(json.dumps(run_stress(args)))
