@@ -264,32 +264,38 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void gemm_mid_kernel(Gemm
     const int n = tile * 16 + 4 * g;
     if constexpr (EPI == EPI_HEAD) {
         // per wave 16 vocabulary entries of every row: lane statistics, merged over the four lane groups, then over
-        // the workgroup's waves in wave order through LDS (the loop's last barrier freed sx)
-        float* ex = reinterpret_cast<float*>(sx);             // [NW][ROWS][RowStat::kWords]
+        // the workgroup's waves in wave order through LDS (the loop's last barrier freed sx). A call with k <= 2 (the
+        // paper's default, Sec. 4.1.4) keeps two-entry lists, which is all its rank test needs.
+        float* ex = reinterpret_cast<float*>(sx);             // [NW][ROWS][kWords]
+        auto head_epilogue = [&](auto depth) {
+            using Stat = RowStatT<decltype(depth)::value>;
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            const int row = mb * 16 + r;
-            RowStat st;
-            st.init();
-            if (active) {
+            for (int mb = 0; mb < MB; ++mb) {
+                const int row = mb * 16 + r;
+                Stat st;
+                st.init();
+                if (active) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) st.add(v[mb][i], n + i);
-                if (row < a.M)
-                    store_candidates(a.hp, row, n, 4, [&](int c) { return c == 0 ? v[mb][0] : c == 1 ? v[mb][1] : c == 2 ? v[mb][2] : v[mb][3]; });
-                if (a.hp.logits_dbg && row < a.M)
-                    *reinterpret_cast<float4*>(a.hp.logits_dbg + (size_t)row * a.N + n) = make_float4(v[mb][0], v[mb][1], v[mb][2], v[mb][3]);
+                    for (int i = 0; i < 4; ++i) st.add(v[mb][i], n + i);
+                    if (row < a.M)
+                        store_candidates(a.hp, row, n, 4, [&](int c) { return c == 0 ? v[mb][0] : c == 1 ? v[mb][1] : c == 2 ? v[mb][2] : v[mb][3]; });
+                    if (a.hp.logits_dbg && row < a.M)
+                        *reinterpret_cast<float4*>(a.hp.logits_dbg + (size_t)row * a.N + n) = make_float4(v[mb][0], v[mb][1], v[mb][2], v[mb][3]);
+                }
+                st.merge_from_lane(16);
+                st.merge_from_lane(32);
+                if (g == 0) st.to_lds(ex + ((size_t)wave * ROWS + row) * Stat::kWords);
             }
-            st.merge_from_lane(16);
-            st.merge_from_lane(32);
-            if (g == 0) st.to_lds(ex + ((size_t)wave * ROWS + row) * RowStat::kWords);
-        }
-        __syncthreads();
-        if (tid < ROWS && tid < a.M) {
-            RowStat m;
-            m.init();
-            for (int w = 0; w < NW; ++w) m.merge_lds(ex + ((size_t)w * ROWS + tid) * RowStat::kWords);
-            m.store(a.hp, tid, (int)blockIdx.x);
-        }
+            __syncthreads();
+            if (tid < ROWS && tid < a.M) {
+                Stat m;
+                m.init();
+                for (int w = 0; w < NW; ++w) m.merge_lds(ex + ((size_t)w * ROWS + tid) * Stat::kWords);
+                m.store(a.hp, tid, (int)blockIdx.x);
+            }
+        };
+        if (a.hp.topk <= 2) head_epilogue(std::integral_constant<int, 2>{});
+        else head_epilogue(std::integral_constant<int, KT>{});
     } else if constexpr (EPI == EPI_SWIGLU) {
         static_assert((NW / 2) * MB * 4 * 64 * sizeof(float) <= BUFH * sizeof(uint16_t), "the exchange area must fit a chunk buffer");
         float* ex = reinterpret_cast<float*>(sx);             // [pair][mb][i][lane]; the loop's last barrier freed sx

@@ -53,21 +53,25 @@ __device__ inline void store_candidates(const HeadPart& hp, int row, int n0, int
 // ordering of (logit, id): larger logit first, smaller id on ties
 __device__ inline bool before(float v, int i, float w, int j) { return v > w || (v == w && i < j); }
 
-struct RowStat {
+// KD: entries of the list the statistics keep, topk <= KD <= KT (a shorter list is all a call with a small k needs,
+// and costs a fraction of the full one to maintain); the stored record is padded to KT entries.
+template <int KD>
+struct RowStatT {
+    static_assert(KD >= 1 && KD <= KT, "list depth");
     float mx, sum;
     int arg;
-    float tv[KT];
-    int ti[KT];
+    float tv[KD];
+    int ti[KD];
     __device__ void init() {
         mx = -INFINITY; sum = 0.f; arg = 0x7FFFFFFF;
 #pragma unroll
-        for (int j = 0; j < KT; ++j) { tv[j] = -INFINITY; ti[j] = 0x7FFFFFFF; }
+        for (int j = 0; j < KD; ++j) { tv[j] = -INFINITY; ti[j] = 0x7FFFFFFF; }
     }
     __device__ void push_top(float v, int n) {
-        if (!before(v, n, tv[KT - 1], ti[KT - 1])) return;
-        tv[KT - 1] = v; ti[KT - 1] = n;
+        if (!before(v, n, tv[KD - 1], ti[KD - 1])) return;
+        tv[KD - 1] = v; ti[KD - 1] = n;
 #pragma unroll
-        for (int j = KT - 1; j > 0; --j) {
+        for (int j = KD - 1; j > 0; --j) {
             if (before(tv[j], ti[j], tv[j - 1], ti[j - 1])) {
                 float fv = tv[j]; tv[j] = tv[j - 1]; tv[j - 1] = fv;
                 int fi = ti[j]; ti[j] = ti[j - 1]; ti[j - 1] = fi;
@@ -79,20 +83,20 @@ struct RowStat {
         else sum += __expf(v - mx);
         push_top(v, n);
     }
-    __device__ void merge(float omx, float osum, int oarg, const float (&otv)[KT], const int (&oti)[KT]) {
+    __device__ void merge(float omx, float osum, int oarg, const float (&otv)[KD], const int (&oti)[KD]) {
         const float M = fmaxf(mx, omx);
         if (M != -INFINITY) sum = sum * __expf(mx - M) + osum * __expf(omx - M);
         if (before(omx, oarg, mx, arg)) arg = oarg;
         mx = M;
 #pragma unroll
-        for (int j = 0; j < KT; ++j) push_top(otv[j], oti[j]);
+        for (int j = 0; j < KD; ++j) push_top(otv[j], oti[j]);
     }
     __device__ void merge_from_lane(int src_xor) {
         const float omx = __shfl_xor(mx, src_xor), osum = __shfl_xor(sum, src_xor);
         const int oarg = __shfl_xor(arg, src_xor);
-        float otv[KT]; int oti[KT];
+        float otv[KD]; int oti[KD];
 #pragma unroll
-        for (int j = 0; j < KT; ++j) { otv[j] = __shfl_xor(tv[j], src_xor); oti[j] = __shfl_xor(ti[j], src_xor); }
+        for (int j = 0; j < KD; ++j) { otv[j] = __shfl_xor(tv[j], src_xor); oti[j] = __shfl_xor(ti[j], src_xor); }
         merge(omx, osum, oarg, otv, oti);
     }
     // record (row, chunk) of the partial arrays
@@ -100,21 +104,25 @@ struct RowStat {
         const size_t o = (size_t)row * hp.chunks + chunk;
         hp.hp_max[o] = mx; hp.hp_sum[o] = sum; hp.hp_arg[o] = arg;
 #pragma unroll
-        for (int j = 0; j < KT; ++j) { hp.hp_topv[o * KT + j] = tv[j]; hp.hp_topi[o * KT + j] = ti[j]; }
+        for (int j = 0; j < KT; ++j) {
+            hp.hp_topv[o * KT + j] = j < KD ? tv[j < KD ? j : 0] : -INFINITY;
+            hp.hp_topi[o * KT + j] = j < KD ? ti[j < KD ? j : 0] : 0x7FFFFFFF;
+        }
     }
     // the same record in LDS for a merge across the waves of a workgroup
-    static constexpr int kWords = 3 + 2 * KT;
+    static constexpr int kWords = 3 + 2 * KD;
     __device__ void to_lds(float* p) const {
         p[0] = mx; p[1] = sum; p[2] = __int_as_float(arg);
 #pragma unroll
-        for (int j = 0; j < KT; ++j) { p[3 + j] = tv[j]; p[3 + KT + j] = __int_as_float(ti[j]); }
+        for (int j = 0; j < KD; ++j) { p[3 + j] = tv[j]; p[3 + KD + j] = __int_as_float(ti[j]); }
     }
     __device__ void merge_lds(const float* p) {
-        float otv[KT]; int oti[KT];
+        float otv[KD]; int oti[KD];
 #pragma unroll
-        for (int j = 0; j < KT; ++j) { otv[j] = p[3 + j]; oti[j] = __float_as_int(p[3 + KT + j]); }
+        for (int j = 0; j < KD; ++j) { otv[j] = p[3 + j]; oti[j] = __float_as_int(p[3 + KD + j]); }
         merge(p[0], p[1], __float_as_int(p[2]), otv, oti);
     }
 };
+using RowStat = RowStatT<KT>;
 
 }  // namespace laser
