@@ -122,8 +122,8 @@ int laser_retrieve_drafts_temp(const laser_pool* pool, const int64_t* keys, cons
                                int64_t* pool_index, void* stream);
 
 /* laser_retrieve_tree (Sec. 3.3, tree-based drafting): like laser_retrieve_drafts, but instead of one chain the
- * sub-tree of the key's trie below the node the suffix reaches is returned, cut to its K most frequent nodes ("if the
- * number of retrieved tokens exceeds K, the tokens with the highest frequency are selected"). A node is a path of
+ * sub-tree of the key's trie below the node the suffix reaches is returned, cut to its K most frequent nodes (the
+ * paper's rule for a retrieval that returns more than K tokens: keep those of highest frequency). A node is a path of
  * successor tokens; its frequency is the number of occurrences of the suffix that continue with that path. Nodes are
  * taken best first among those whose parent is taken: higher frequency, then smaller depth, then the parent taken
  * earlier, then the smaller token id. The pseudo-sequence lists the taken nodes depth-first, the children of a node
@@ -241,7 +241,7 @@ int laser_verify_step(laser_model* model, laser_kv* kv, const int32_t* seq_ids,
                       int B, int K, int topk, float p, int mode,
                       int32_t* accept_len, int32_t* out_tokens, float* logits_dbg, void* stream);
 
-/* laser_verify_tree (Sec. 3.3 tree attention, Sec. 3.4 "accepting the verified branch with the maximum length"):
+/* laser_verify_tree (Sec. 3.3 tree attention; Sec. 3.4: of the verified branches the longest one is accepted):
  * laser_verify_step for a token tree. Rows r = 1..K hold the nodes of the pseudo-sequence in order (row 0 the pending
  * token); node i sits at position len + depth(i), its key/value go to cache slot len + 1 + i, and it attends to the
  * committed cache, the pending token, its ancestors and itself -- never to a node of another branch. Node i is verified
@@ -278,7 +278,7 @@ int laser_verify_head_static(laser_model* model, const uint16_t* h, const int32_
                              const int32_t* draft_len, int B, int K, int topk, float p, int mode,
                              int32_t* accept_len, int32_t* out_tokens, void* stream);
 
-/* laser_kv_commit ("all drafted tokens after the failing position are discarded", Sec. 2.1):
+/* laser_kv_commit (Sec. 2.1: drafts behind the first failing position are dropped):
  * len[seq_ids[b]] += accept_len[b] + 1, i.e. the pending token and the accepted drafts become
  * permanent; later slots are dead and get overwritten by the next step.
  *   seq_ids [host] int32[B];  accept_len [dev] int32[B] (values 0..K of the verify call before it)

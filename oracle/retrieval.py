@@ -33,8 +33,8 @@ lies in the own text is reported as pool_index = -2 - (position in the own text)
 
 Tree drafts (Sec. 3.3, "tree-based drafting"): instead of one chain, the sub-tree of the trie below the node
 the suffix reaches is retrieved, cut to at most K nodes. A node is a path of successor tokens; its frequency is
-the number of occurrences whose continuation starts with that path. "If the number of retrieved tokens exceeds
-K, the tokens with the highest frequency are selected": nodes are taken one at a time, always the best node not
+the number of occurrences whose continuation starts with that path. The paper keeps the highest-frequency tokens
+when a retrieval returns more than K of them; here that reads: nodes are taken one at a time, always the best node not
 yet taken whose parent is taken (the root's children at the start), best = higher frequency, then smaller
 depth, then the parent that was taken earlier, then the smaller token id. (A child never has a higher frequency
 than its parent, so this yields the K best nodes of the whole sub-tree in that order, and the result is a tree.)
