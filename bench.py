@@ -456,7 +456,7 @@ def run_study(args):
     """Generation-loop study on synthetic data, shaped like the paper's pool study (Sec. 2.2), its ablation of pooling
     schemes with and without relaxed verification (Sec. 4.3.1) and of the acceptance rules (Sec. 4.3.2). U users in G
     groups; the text to generate for a user is the model's own greedy continuation of the user's prompt (decoded first,
-    one token per step, through laser_generate without a pool); "earlier knowledge of similar users" is m noisy copies
+    one token per step, through laser_generate without a pool); the earlier texts of similar users are m noisy copies
     of it (substitution rate s). Pooling schemes: CRP -- a pool per group holding the copies for its members; GRP --
     one pool for everything; RRP -- same number of pools, every copy in a random one and every user looking in a random
     one. Every run regenerates all texts with laser_generate (retrieve -> verify -> commit on the device)."""

@@ -1,5 +1,5 @@
-// The generation loop (Sec. 3.1 overview; Sec. 2.1: draft, verify, keep the accepted tokens, repeat "until the
-// knowledge text is complete"): retrieve drafts -> verify -> bookkeeping -> commit, step after step on one stream,
+// The generation loop (Sec. 3.1 overview; Sec. 2.1: draft, verify, keep the accepted tokens, repeat until the text
+// is complete): retrieve drafts -> verify -> bookkeeping -> commit, step after step on one stream,
 // for a whole batch, until every sequence has emitted max_new_tokens tokens or its end-of-sequence token. The host
 // enqueues the steps and never reads device state on the step path; once every `check_every` steps it looks at a
 // device counter of finished sequences (one stream synchronisation) to stop early. A finished sequence stays in

@@ -34,9 +34,12 @@ __global__ void fill_i32_kernel(int32_t* p, int32_t v, size_t n) {
     if (i < n) p[i] = v;
 }
 
-__global__ void commit_kernel(int32_t* len, const int32_t* seq_ids, const int32_t* accept_len, int B) {
+// max_accept: the most drafts any of the call's sequences had in the verify step before it. The host has already
+// raised its bound of every length by that step's rows; a value outside -1..max_accept (a caller's mistake) is cut
+// to that range so that a length never passes the bound the pages were reserved against.
+__global__ void commit_kernel(int32_t* len, const int32_t* seq_ids, const int32_t* accept_len, int B, int max_accept) {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b < B) len[seq_ids[b]] += accept_len[b] + 1;
+    if (b < B) len[seq_ids[b]] += min(max(accept_len[b], -1), max_accept) + 1;
 }
 
 // Token trees (Sec. 3.3-3.4): the rows of a verify step sit in slots len + 1 + (node index); the accepted branch's
@@ -262,7 +265,9 @@ static int commit_impl(laser_kv* h, const int32_t* seq_ids, const int32_t* accep
     const int32_t* ids_dev = nullptr;
     int rc = kv->stage_ids(seq_ids, B, (hipStream_t)stream, &ids_dev);
     if (rc) return rc;
+    int max_rows = 0;
     for (int b = 0; b < B; ++b) {
+        max_rows = std::max(max_rows, kv->h_last_rows[seq_ids[b]]);
         kv->h_len_ub[seq_ids[b]] += kv->h_last_rows[seq_ids[b]];
         kv->h_last_rows[seq_ids[b]] = 0;
     }
@@ -270,7 +275,7 @@ static int commit_impl(laser_kv* h, const int32_t* seq_ids, const int32_t* accep
         hipLaunchKernelGGL(kv_compact_kernel, dim3(kv->d.n_heads, kv->d.n_layers, B), dim3(kv->d.head_dim), 0, (hipStream_t)stream,
                            kv->kpages, kv->klpages, kv->vpages, kv->block_table, kv->len, ids_dev, accept_len, accept_path, K,
                            kv->d.n_heads, kv->d.head_dim, kv->d.max_pages_per_seq, kv->d.n_pages);
-    hipLaunchKernelGGL(commit_kernel, dim3((B + 63) / 64), dim3(64), 0, (hipStream_t)stream, kv->len, ids_dev, accept_len, B);
+    hipLaunchKernelGGL(commit_kernel, dim3((B + 63) / 64), dim3(64), 0, (hipStream_t)stream, kv->len, ids_dev, accept_len, B, max_rows - 1);
     LASER_HIP_CHECK(hipGetLastError());
     return LASER_OK;
 }
