@@ -332,7 +332,9 @@ __device__ inline void stage_x(const FusedArgs& a, uint4* xs, const uint16_t* X,
         uint4* dst = xs + row * stride + (low ? hi_p : 0) + b0;
         // Written as assembly so that the compiler does not track the request: it would wait for it (and for every
         // weight load behind it) at the first unrelated reuse of the address registers. The caller's stage_wait is the
-        // wait that counts. m0 = the block's LDS byte address; one wait state between writing m0 and its use.
+        // wait that counts. m0 = the block's LDS byte address; one wait state between writing m0 and its use. The
+        // compiler warns that m0 is a reserved register which it does not preserve around the statement: nothing
+        // else in this kernel uses m0 (no other LDS-direct load, no indirect register indexing, no message).
         const uint32_t lds_at = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lptr_t)dst);
         const char* g = src + (size_t)(b0 + lane) * 16;
         if (lane < n)
