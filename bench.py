@@ -30,15 +30,15 @@ sys.path.insert(0, ROOT)
 WORKLOADS = {
     #        shape  B   ctx   K  pool             n_max  default steps
     "c3": dict(shape="7b", B=1, ctx=1024, K=8, pool="7b_latency", n_max=3, steps=50, warmup=5,
-               label="7B shape latency: B=1, context 1024, K=8, pool 2k x 256 tokens (BASELINE configs[2])"),
+               label="7B shape latency: B=1, context 1024, K=8, pool 2k x 256 tokens (benchmark configuration 2)"),
     "c4": dict(shape="7b", B=64, ctx=512, K=10, pool="7b_throughput", n_max=3, steps=32, warmup=3,
-               label="7B shape throughput: B=64, prompt 512 + generated, K=10, paged KV (BASELINE configs[3])"),
+               label="7B shape throughput: B=64, prompt 512 + generated, K=10, paged KV (benchmark configuration 3)"),
     "7b_b8": dict(shape="7b", B=8, ctx=1024, K=8, pool="7b_latency", n_max=3, steps=50, warmup=4,
                   label="7B shape, small batch: B=8, context 1024, K=8 (72 rows: between the latency and the throughput workload)"),
     "1b": dict(shape="1b", B=8, ctx=512, K=8, pool="1b", n_max=3, steps=50, warmup=5,
-               label="1B shape: B=8, context 512, K=8 (BASELINE configs[1])"),
+               label="1B shape: B=8, context 512, K=8 (benchmark configuration 1)"),
     "tiny": dict(shape="tiny", B=2, ctx=64, K=4, pool="tiny", n_max=3, steps=20, warmup=3,
-                 label="Tiny: B=2, context 64, K=4 (BASELINE configs[0])"),
+                 label="Tiny: B=2, context 64, K=4 (benchmark configuration 0)"),
 }
 
 # Substitution rate of the replayed continuation (the pool texts themselves keep the configs' 10-15 %). The paper
@@ -317,7 +317,7 @@ def run_workload(args, name, steps, warmup, weights_cache):
 
 
 def run_stress(args):
-    """The stress configuration (BASELINE configs[4]): the fused output head + relaxed acceptance at d 4096, vocabulary
+    """The stress configuration (benchmark configuration 4): the fused output head + relaxed acceptance at d 4096, vocabulary
     128256, 256 sequences x 16 rows, and the draft lookup over a pool of 100 M tokens in 1 M keyed sub-pools for 4096
     concurrent contexts (suffix length 1..4, K = 16); beside them the floor of an empty kernel of as many wavefronts
     and a lookup batch of 2^20 contexts. One "step" = one lookup batch + one head launch."""
@@ -432,7 +432,7 @@ def run_stress(args):
         "ms_per_step": step_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 weights x fp16 hidden states, fp32 accumulate; int32 tokens", "data": "synthetic",
         "config": {"workload": "Retrieval + verify-head stress: pool of 100M tokens over 1M sub-pools, 4096 contexts, suffix 1-4, K=16; "
-                               "head d 4096, vocab 128256, 256 sequences x 16 rows (BASELINE configs[4])",
+                               "head d 4096, vocab 128256, 256 sequences x 16 rows (benchmark configuration 4)",
                    "head_rows": B * R, "vocab": sh.vocab, "topk": 2, "p": 0.1, "accepted_drafts_per_sequence": emitted / B - 1.0,
                    "head_ms": head_ms, "retrieval_us_per_4096_lookups": retr_us, "lookups_per_s": Br / (retr_us * 1e-6),
                    "empty_kernel_us_4096_wavefronts": floor_us, "retrieval_over_floor": retr_us / floor_us,
