@@ -281,7 +281,10 @@ int laser_verify_head_static(laser_model* model, const uint16_t* h, const int32_
 /* laser_kv_commit (Sec. 2.1: drafts behind the first failing position are dropped):
  * len[seq_ids[b]] += accept_len[b] + 1, i.e. the pending token and the accepted drafts become
  * permanent; later slots are dead and get overwritten by the next step.
- *   seq_ids [host] int32[B];  accept_len [dev] int32[B] (values 0..K of the verify call before it)
+ *   seq_ids [host] int32[B];  accept_len [dev] int32[B] (values 0..K of the verify call before it; -1 commits
+ *   nothing for that sequence, which is how a finished sequence idles in laser_generate; values outside -1..K are
+ *   cut to that range on the device, so that a length never passes the bound its pages were reserved against)
+ * A commit without a verify step on the same slots before it returns LASER_E_INVALID_ARG.
  */
 int laser_kv_commit(laser_kv* kv, const int32_t* seq_ids, const int32_t* accept_len, int B,
                     void* stream);
