@@ -73,3 +73,16 @@ def test_binding_limits_agree_with_the_header():
     for name in ("NGRAM", "DRAFT", "TOPK", "TREE", "OWN_TEXT"):
         m = _re.search(r"#define\s+LASER_MAX_%s\s+(\d+)" % name, src)
         assert m and int(m.group(1)) == getattr(binding, "MAX_" + name), name
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU benchmark: --gpus N with N > 1 (or a multi-rank environment) exits with a message
+    before anything touches a GPU."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+    env = dict(os.environ, WORLD_SIZE="2")
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py")], capture_output=True, text=True, timeout=120, env=env)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr
