@@ -9,7 +9,7 @@
 //     QKV(+RoPE) | attention | O-proj(+residual) | gate/up(+SwiGLU) | down(+residual)
 // * Weight streaming: a GEMM unit is a 16-feature tile (or a pair of tiles); the 8 waves of a
 //   workgroup split its reduction dimension, the four lanes of a weight row reading 64 contiguous bytes
-//   per instruction (the MFMA operands of weights and activations take the same k order), partial sums meet in LDS. Each wave keeps 16 KiB of weights in
+//   per instruction (the MFMA operands of weights and activations take the same k order), partial sums meet in LDS. Each wave keeps 12-16 KiB of weights in
 //   flight in a register ring and issues the first steps of the NEXT phase while the barrier
 //   resolves, so HBM stays busy (weights never depend on activations). The few activation rows are
 //   staged into LDS once per workgroup and phase instead of being re-read per step.
@@ -262,7 +262,8 @@ __device__ inline const uint16_t* w_ptr(const FusedArgs& a, const Phase& ph, int
 
 // Weight streaming through a register ring. A step (128 reduction elements) of a phase with NA
 // streams occupies NA weight fragments (4 x 16 B per lane each); the ring holds DS steps, so DS-1
-// steps of weights (16 KiB per wave: NA = 2, DS = 3 or NA = 1, DS = 5) are in flight while one is
+// steps of weights (NA = 2, DS = 3: 16 KiB per wave; NA = 1, DS = 4: 12 KiB -- DS = 5 and 6 measured 1-2 % slower,
+// the compute unit's memory queues being what they are) are in flight while one is
 // consumed. The activation operand is NOT loaded per step from global memory: measured on this chip,
 // per-step activation loads (L2 hits) cut the weight streaming rate by 30-45 % because they share the
 // vector-memory path; the phase's activations are staged into LDS once per workgroup and read from
@@ -276,7 +277,7 @@ __device__ inline const uint16_t* w_ptr(const FusedArgs& a, const Phase& ph, int
 struct Ring {
     Frag8 f[6][4];        // slot (step % DS) * NA + stream; DS - 1 steps are in flight while one is consumed
 };
-template <int NA> struct RingCfg { static constexpr int DS = NA == 2 ? 3 : 5; };
+template <int NA> struct RingCfg { static constexpr int DS = NA == 2 ? 3 : 4; };
 
 // Issue the weights of this wave's steps T0 .. T1-1 (of the first DS-1) of chunk `chunk` of phase `ph` into
 // their ring slots. Weights never depend on activations, so the first PF1 steps are issued while the grid
