@@ -284,7 +284,7 @@ template <int NA> struct RingCfg { static constexpr int DS = NA == 2 ? 3 : 4; };
 // barrier in front of the phase resolves and the others right behind the requests that stage the phase's
 // activations. Issuing a wave's whole ring inside the barrier stalls it there for microseconds (the compute
 // unit's memory queues hold less than 8 waves x 16 KiB), which delays the barrier's exit by more than the
-// early start gains: PF1 = half the ring measured best. The loads are unconditional (steps past the wave's
+// early start gains: PF1 = two steps (one for pair tiles) measured best. The loads are unconditional (steps past the wave's
 // last one re-request one cached line), so that the number of vector-memory instructions issued here is a
 // compile-time constant: stage_wait counts on it.
 constexpr int pf1_steps(int NA) { return NA == 2 ? 1 : 2; }
