@@ -288,7 +288,6 @@ template <int NA> struct RingCfg { static constexpr int DS = NA == 2 ? 3 : 4; };
 // last one re-request one cached line), so that the number of vector-memory instructions issued here is a
 // compile-time constant: stage_wait counts on it.
 constexpr int pf1_steps(int NA) { return NA == 2 ? 1 : 2; }
-constexpr int PF1_O = 0;          // the O projection's first steps would queue in front of the attention phase's key / value loads
 template <int NA, int T0, int T1>
 __device__ inline void prime_steps(const FusedArgs& a, const Phase& ph, int chunk, Ring& R) {
     const int lane = threadIdx.x & 63;
@@ -1141,20 +1140,22 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
             });
         }
         stamp<TR>(a, ns);
-        if (!grid_sync(a, sh, epoch, [&] { prime_steps<1, 0, PF1_O>(a, p_o, 0, ring); })) return;
+        // (nothing of the O projection is requested here: it would queue in front of the attention phase's key / value
+        // loads; its first steps go into the barrier behind the attention phase)
+        if (!grid_sync(a, sh, epoch, no_prefetch)) return;
         stamp<TR>(a, ns);
 
         // ---- attention ----
         attention_phase<DH, TR>(a, sh, l);
         stamp<TR>(a, ns);
-        if (!grid_sync(a, sh, epoch, no_prefetch)) return;
+        if (!grid_sync(a, sh, epoch, [&] { prime_steps<1, 0, pf1_steps(1)>(a, p_o, 0, ring); })) return;
         stamp<TR>(a, ns);
 
         // ---- O projection + residual; publish x, x*g2, sum of squares ----
         {
             float ss = 0.f;
             const float* g2 = a.g2 + (size_t)l * a.d;
-            stream_phase<1, true, TR, PF1_O>(a, sh, xs, p_o, a.attn + lo, a.attnl + lo, ring, l, 3);
+            stream_phase<1, true, TR>(a, sh, xs, p_o, a.attn + lo, a.attnl + lo, ring, l, 3);
             reduce_epilogue<1>(a, sh, n_units(a, PH_O), [&](int u, int row, int f0, float (&v)[1][2]) {
                 const int item = w + u * nwg;
                 const size_t o = (size_t)row * a.d + item * 16 + f0;
