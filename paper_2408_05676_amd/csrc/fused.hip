@@ -550,8 +550,23 @@ __device__ inline void publish_ss(Shared& sh, float* ss_out /*[16] of this workg
 }
 
 // ---- attention ---------------------------------------------------------------------------------------
+// Block-table entries of this wave's pages of attention item `item` (clamped to a valid item and valid pages, so the
+// loads are unconditional). They do not depend on the layer's activations: the first item's are requested while the
+// grid barrier in front of the attention phase resolves, a later item's at the end of the item before it, which
+// takes one memory round trip out of every item.
+__device__ inline void attn_pages(const FusedArgs& a, const Shared& sh, int item, int (&pg)[PPW]) {
+    const int n_items = a.B * a.H * a.nsplit, wave = threadIdx.x >> 6;
+    item = min(item, n_items - 1);
+    const int split = item % a.nsplit, b = item / a.nsplit / a.H;
+    const int n_pages = (sh.seq_len[b] + a.R + kPageSize - 1) / kPageSize;
+    const int32_t* bt = a.block_table + (size_t)sh.seq_slot[b] * a.mpps;
+    const int pbase = (split * AW + wave) * PPW;
+#pragma unroll
+    for (int pp = 0; pp < PPW; ++pp) pg[pp] = bt[min(pbase + pp, n_pages - 1)];
+}
+
 template <int DH, bool TR>
-__device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer) {
+__device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer, int (&pg_next)[PPW]) {
     constexpr int NC32 = DH / 32, NC16 = DH / 16;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
@@ -577,7 +592,6 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
         // position, never on how many rows are verified with it or on the host's length bound: a token
         // verified as a draft gets bit-identical logits to the same token decoded one at a time.
         const int n_pages = (len + a.R + kPageSize - 1) / kPageSize;
-        const int32_t* bt = a.block_table + (size_t)slot * a.mpps;
 
         float m_run = -INFINITY, l_run = 0.f;
         float4_t acc[NC16];
@@ -586,13 +600,13 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
         if (wave < AW) {
             const int pbase = (split * AW + wave) * PPW;
             if (pbase < n_pages) {
-                // Two round trips: (1) the block-table entries of this wave's pages; (2) the query fragments and
-                // every key / value fragment. All addresses of (2) are formed before its first load is issued, and
+                // One round trip: the query fragments and every key / value fragment (the block-table entries of this
+                // wave's pages were requested ahead). All addresses of (2) are formed before its first load is issued, and
                 // the scheduling fences keep anything else (in particular reloads of spilled pointers, which
                 // would wait for all earlier loads) out of the load block.
                 int pg[PPW];
 #pragma unroll
-                for (int pp = 0; pp < PPW; ++pp) pg[pp] = bt[min(pbase + pp, n_pages - 1)];
+                for (int pp = 0; pp < PPW; ++pp) pg[pp] = pg_next[pp];       // requested ahead (attn_pages)
                 Frag8 bq[NC32], bql[NC32];
                 const size_t qo = (size_t)(b * a.R + min(r, a.R - 1)) * a.d + (size_t)h * DH + g * 8;
                 const uint16_t *qp = qb + qo, *qlp = qlb + qo;
@@ -813,6 +827,7 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
                 }
             }
         }
+        attn_pages(a, sh, item + gridDim.x, pg_next);
         __syncthreads();
     }
 }
@@ -1142,11 +1157,12 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         stamp<TR>(a, ns);
         // (nothing of the O projection is requested here: it would queue in front of the attention phase's key / value
         // loads; its first steps go into the barrier behind the attention phase)
-        if (!grid_sync(a, sh, epoch, no_prefetch)) return;
+        int pg_first[PPW];
+        if (!grid_sync(a, sh, epoch, [&] { attn_pages(a, sh, blockIdx.x, pg_first); })) return;
         stamp<TR>(a, ns);
 
         // ---- attention ----
-        attention_phase<DH, TR>(a, sh, l);
+        attention_phase<DH, TR>(a, sh, l, pg_first);
         stamp<TR>(a, ns);
         if (!grid_sync(a, sh, epoch, [&] { prime_steps<1, 0, pf1_steps(1)>(a, p_o, 0, ring); })) return;
         stamp<TR>(a, ns);
