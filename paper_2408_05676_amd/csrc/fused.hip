@@ -835,21 +835,24 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
 // ---- output head: per-wave vocabulary tiles, running statistics in registers ----------------------
 __device__ inline bool hbefore(float v, int i, float w, int j) { return v > w || (v == w && i < j); }
 
+// KD: entries of the list (the call's k <= KD <= KTOP): a two-entry list is all the paper's default k = 2 needs, and
+// the merges below cost in proportion to KD squared.
+template <int KD>
 struct HStat {
     float mx, sum, lx;
     int arg;
-    float tv[KTOP];
-    int ti[KTOP];
+    float tv[KD];
+    int ti[KD];
     __device__ void init() {
         mx = -INFINITY; sum = 0.f; lx = -INFINITY; arg = 0x7FFFFFFF;
 #pragma unroll
-        for (int j = 0; j < KTOP; ++j) { tv[j] = -INFINITY; ti[j] = 0x7FFFFFFF; }
+        for (int j = 0; j < KD; ++j) { tv[j] = -INFINITY; ti[j] = 0x7FFFFFFF; }
     }
     __device__ void push_top(float v, int n) {
-        if (!hbefore(v, n, tv[KTOP - 1], ti[KTOP - 1])) return;
-        tv[KTOP - 1] = v; ti[KTOP - 1] = n;
+        if (!hbefore(v, n, tv[KD - 1], ti[KD - 1])) return;
+        tv[KD - 1] = v; ti[KD - 1] = n;
 #pragma unroll
-        for (int j = KTOP - 1; j > 0; --j)
+        for (int j = KD - 1; j > 0; --j)
             if (hbefore(tv[j], ti[j], tv[j - 1], ti[j - 1])) {
                 const float fv = tv[j]; tv[j] = tv[j - 1]; tv[j - 1] = fv;
                 const int fi = ti[j]; ti[j] = ti[j - 1]; ti[j - 1] = fi;
@@ -863,24 +866,25 @@ struct HStat {
     __device__ void merge_xor(int off) {
         const float omx = __shfl_xor(mx, off), osum = __shfl_xor(sum, off), olx = __shfl_xor(lx, off);
         const int oarg = __shfl_xor(arg, off);
-        float otv[KTOP]; int oti[KTOP];
+        float otv[KD]; int oti[KD];
 #pragma unroll
-        for (int j = 0; j < KTOP; ++j) { otv[j] = __shfl_xor(tv[j], off); oti[j] = __shfl_xor(ti[j], off); }
+        for (int j = 0; j < KD; ++j) { otv[j] = __shfl_xor(tv[j], off); oti[j] = __shfl_xor(ti[j], off); }
         merge(omx, osum, olx, oarg, otv, oti);
     }
-    __device__ void merge(float omx, float osum, float olx, int oarg, const float (&otv)[KTOP], const int (&oti)[KTOP]) {
+    __device__ void merge(float omx, float osum, float olx, int oarg, const float (&otv)[KD], const int (&oti)[KD]) {
         const float M = fmaxf(mx, omx);
         if (M != -INFINITY) sum = sum * __expf(mx - M) + osum * __expf(omx - M);
         if (hbefore(omx, oarg, mx, arg)) arg = oarg;
         mx = M;
         lx = fmaxf(lx, olx);
 #pragma unroll
-        for (int j = 0; j < KTOP; ++j) push_top(otv[j], oti[j]);
+        for (int j = 0; j < KD; ++j) push_top(otv[j], oti[j]);
     }
 };
 
 // Consumes the logits tiles a wave has accumulated in sh.red (unit u of global wave gw is vocabulary
 // tile gw + u * waves of the launch): per-row running statistics, merged per workgroup.
+template <int KD>
 __device__ inline void head_epilogue(const FusedArgs& a, Shared& sh, uint4* xs, int chunks) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
@@ -892,7 +896,7 @@ __device__ inline void head_epilogue(const FusedArgs& a, Shared& sh, uint4* xs, 
         x = (rr < a.K && rr < a.draft_len[b]) ? a.drafts[(size_t)b * a.K + rr] : -1;
         if (x >= a.V) x = -1;
     }
-    HStat st;
+    HStat<KD> st;
     st.init();
     const float rs = sh.rs[r];
     const int n_my = n_units(a, PH_HEAD);
@@ -913,32 +917,35 @@ __device__ inline void head_epilogue(const FusedArgs& a, Shared& sh, uint4* xs, 
     st.merge_xor(32);
     // merge the 8 waves of the workgroup (fixed order) so that the acceptance phase reads one record per
     // workgroup and row; the staging area is free by now
-    float* ws_f = reinterpret_cast<float*>(xs);                   // [FWAVES][16][3 + KTOP]
-    int* ws_i = reinterpret_cast<int*>(ws_f + FWAVES * 16 * (3 + KTOP));   // [FWAVES][16][1 + KTOP]
+    float* ws_f = reinterpret_cast<float*>(xs);                   // [FWAVES][16][3 + KD]
+    int* ws_i = reinterpret_cast<int*>(ws_f + FWAVES * 16 * (3 + KD));   // [FWAVES][16][1 + KD]
     if (g == 0) {
-        float* f = ws_f + (wave * 16 + r) * (3 + KTOP);
-        int* i = ws_i + (wave * 16 + r) * (1 + KTOP);
+        float* f = ws_f + (wave * 16 + r) * (3 + KD);
+        int* i = ws_i + (wave * 16 + r) * (1 + KD);
         f[0] = st.mx; f[1] = st.sum; f[2] = st.lx; i[0] = st.arg;
 #pragma unroll
-        for (int j = 0; j < KTOP; ++j) { f[3 + j] = st.tv[j]; i[1 + j] = st.ti[j]; }
+        for (int j = 0; j < KD; ++j) { f[3 + j] = st.tv[j]; i[1 + j] = st.ti[j]; }
     }
     __syncthreads();
     if (threadIdx.x < 16 && (int)threadIdx.x < a.M) {
         const int rr = threadIdx.x;
-        HStat m;
+        HStat<KD> m;
         m.init();
         for (int w = 0; w < FWAVES; ++w) {
-            const float* f = ws_f + (w * 16 + rr) * (3 + KTOP);
-            const int* i = ws_i + (w * 16 + rr) * (1 + KTOP);
-            float otv[KTOP]; int oti[KTOP];
+            const float* f = ws_f + (w * 16 + rr) * (3 + KD);
+            const int* i = ws_i + (w * 16 + rr) * (1 + KD);
+            float otv[KD]; int oti[KD];
 #pragma unroll
-            for (int j = 0; j < KTOP; ++j) { otv[j] = f[3 + j]; oti[j] = i[1 + j]; }
+            for (int j = 0; j < KD; ++j) { otv[j] = f[3 + j]; oti[j] = i[1 + j]; }
             m.merge(f[0], f[1], f[2], i[0], otv, oti);
         }
         const size_t o = (size_t)rr * chunks + blockIdx.x;
         st_f32(a.hp_max + o, m.mx); st_f32(a.hp_sum + o, m.sum); st_i32(a.hp_arg + o, m.arg);
 #pragma unroll
-        for (int j = 0; j < KTOP; ++j) { st_f32(a.hp_topv + o * KTOP + j, m.tv[j]); st_i32(a.hp_topi + o * KTOP + j, m.ti[j]); }
+        for (int j = 0; j < KTOP; ++j) {          // the record keeps KTOP entries: the unused ones never rank ahead of anything
+            st_f32(a.hp_topv + o * KTOP + j, j < KD ? m.tv[j < KD ? j : 0] : -INFINITY);
+            st_i32(a.hp_topi + o * KTOP + j, j < KD ? m.ti[j < KD ? j : 0] : 0x7FFFFFFF);
+        }
         if (m.lx != -INFINITY) st_f32(a.hp_lx + rr, m.lx);
     }
 }
@@ -1245,7 +1252,8 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         ss_issue(a.ssbuf + (size_t)(2 * a.L) * nwg * 16, ssv);
         stream_phase<1, false, TR>(a, sh, xs, p_head, a.xgbuf + (size_t)(2 * a.L) * XS, nullptr, ring);
         ss_finish(a, sh, ssv);
-        head_epilogue(a, sh, xs, chunks);
+        if (a.topk <= 2) head_epilogue<2>(a, sh, xs, chunks);
+        else head_epilogue<KTOP>(a, sh, xs, chunks);
     }
     stamp<TR>(a, ns);
     if (!grid_sync(a, sh, epoch, no_prefetch)) return;
