@@ -353,6 +353,36 @@ __device__ inline void stage_x(const FusedArgs& a, uint4* xs, const uint16_t* X,
         while (blk >= bpr) { blk -= bpr; ++row; }
     }
 }
+// The same copy restricted to what THIS wave reads in the streaming loop: every row's pieces of the wave's own steps
+// ks0 .. ks0+nks-1 of the chunk (all waves of a workgroup walk the same units and split the reduction dimension, so no
+// wave reads another wave's columns). The wave's own wait (stage_wait) is then all the synchronisation the staged
+// data needs: no workgroup barrier between staging and streaming.
+__device__ inline void stage_x_own(const FusedArgs& a, uint4* xs, const uint16_t* X, const uint8_t* Xlo, int Kd, const WaveWork& w) {
+    typedef void __attribute__((address_space(3))) * lptr_t;
+    const int lane = threadIdx.x & 63;
+    const int hi_p = w.ncs * 16, lo_p = Xlo ? w.ncs * 8 : 0;
+    const int stride = hi_p + lo_p + 1;
+    const int k0 = w.ks0 - w.cs0;                                      // first own step inside the chunk
+    const int nh = w.nks * 16, nl = Xlo ? w.nks * 8 : 0;              // own pieces per row: high plane, low plane
+    const char* xh = reinterpret_cast<const char*>(X) + (size_t)w.ks0 * 256;
+    const char* xl = reinterpret_cast<const char*>(Xlo ? (const void*)Xlo : (const void*)X) + (size_t)w.ks0 * 128;
+    for (int row = 0; row < a.M; ++row) {
+        for (int b0 = 0; b0 < nh; b0 += 64) {
+            uint4* dst = xs + row * stride + k0 * 16 + b0;
+            const uint32_t lds_at = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lptr_t)dst);
+            const char* g = xh + (size_t)row * Kd * 2 + (size_t)(b0 + lane) * 16;
+            if (lane < nh - b0)
+                asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_at) : "memory", "m0");
+        }
+        for (int b0 = 0; b0 < nl; b0 += 64) {
+            uint4* dst = xs + row * stride + hi_p + k0 * 8 + b0;
+            const uint32_t lds_at = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lptr_t)dst);
+            const char* g = xl + (size_t)row * Kd + (size_t)(b0 + lane) * 16;
+            if (lane < nl - b0)
+                asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_at) : "memory", "m0");
+        }
+    }
+}
 // Waits for this wave's staging requests, leaving the N vector-memory instructions issued after them (the
 // weight steps of prime_steps) in flight: the counter retires in issue order.
 template <int N>
@@ -462,7 +492,7 @@ __device__ inline void stream_chunk(const FusedArgs& a, Shared& sh, const uint4*
 // Streams a whole phase: for every chunk stage its activations, stream, and issue the next chunk's
 // first weights before the staging barrier. On return sh.red holds every unit's partial sums and
 // all waves have passed a workgroup barrier.
-template <int NA, bool SPLIT, bool TR, int PF1 = pf1_steps(NA)>
+template <int NA, bool SPLIT, bool TR, bool OWN = true, int PF1 = pf1_steps(NA)>
 __device__ inline void stream_phase(const FusedArgs& a, Shared& sh, uint4* xs, const Phase& ph,
                                     const uint16_t* __restrict__ X, const uint8_t* __restrict__ Xlo, Ring& R,
                                     int trace_layer = -1, int trace_slot = 0) {
@@ -472,7 +502,8 @@ __device__ inline void stream_phase(const FusedArgs& a, Shared& sh, uint4* xs, c
         const WaveWork w = wave_work(a, ph, c);
         if (c > 0) __syncthreads();                     // every wave has finished reading the previous chunk
         if (c == 0) stamp_fine<TR>(a, trace_layer, trace_slot + 2);
-        stage_x(a, xs, X, SPLIT ? Xlo : nullptr, ph.Kd, w.cs0, w.ncs);
+        if constexpr (OWN) stage_x_own(a, xs, X, SPLIT ? Xlo : nullptr, ph.Kd, w);
+        else stage_x(a, xs, X, SPLIT ? Xlo : nullptr, ph.Kd, w.cs0, w.ncs);
         // the ring's remaining steps travel behind the staging requests (chunk 0: steps 0 .. PF1-1 were issued
         // inside the barrier)
         // (the fences keep the compiler from moving weight loads in front of the staging requests: stage_wait
@@ -487,7 +518,7 @@ __device__ inline void stream_phase(const FusedArgs& a, Shared& sh, uint4* xs, c
             __builtin_amdgcn_sched_barrier(0);
             stage_wait<PrimeCount<NA, 0, DS - 1>::value>();
         }
-        __syncthreads();
+        if constexpr (!OWN) __syncthreads();     // shared staging: every wave's pieces have landed
         if (c == 0) stamp_fine<TR>(a, trace_layer, trace_slot);
         stream_chunk<NA, SPLIT>(a, sh, xs, ph, w, c == 0, R);
     }
@@ -1260,7 +1291,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
     {
         float ssv[8];
         ss_issue(a.ssbuf + (size_t)(2 * a.L) * nwg * 16, ssv);
-        stream_phase<1, false, TR>(a, sh, xs, p_head, a.xgbuf + (size_t)(2 * a.L) * XS, nullptr, ring);
+        stream_phase<1, false, TR, false>(a, sh, xs, p_head, a.xgbuf + (size_t)(2 * a.L) * XS, nullptr, ring);
         ss_finish(a, sh, ssv);
         if (a.topk <= 2) head_epilogue<2>(a, sh, xs, chunks);
         else head_epilogue<KTOP>(a, sh, xs, chunks);
