@@ -272,32 +272,39 @@ __device__ inline const uint16_t* w_ptr(const FusedArgs& a, const Phase& ph, int
 
 // Weight streaming through a register ring. A step (128 reduction elements) of a phase with NA
 // streams occupies NA weight fragments (4 x 16 B per lane each); the ring holds DS steps, so DS-1
-// steps of weights (NA = 2, DS = 3: 16 KiB per wave; NA = 1, DS = 4: 12 KiB -- DS = 5 and 6 measured 1-2 % slower,
-// the compute unit's memory queues being what they are) are in flight while one is
-// consumed. The activation operand is NOT loaded per step from global memory: measured on this chip,
-// per-step activation loads (L2 hits) cut the weight streaming rate by 30-45 % because they share the
-// vector-memory path; the phase's activations are staged into LDS once per workgroup and read from
-// there. The streaming loop is kept free of branches around vector-memory instructions (past the
-// wave's last step it re-requests one cached line and skips the arithmetic), because the wait
+// steps of weights are in flight while one is consumed. The activation operand is NOT loaded per step from
+// global memory: measured on this chip, per-step activation loads (L2 hits) cut the weight streaming rate by
+// 30-45 % because they share the vector-memory path; the phase's activations are staged into LDS once per
+// workgroup and read from there. The streaming loop is kept free of branches around vector-memory instructions
+// (past the wave's last step it re-requests one cached line and skips the arithmetic), because the wait
 // counters are exact only in straight-line code; finished units leave their partial sums in LDS
 // inside the loop and every epilogue runs after it.
 
-// What survives a phase boundary: the weights issued ahead for the next phase (its first step if
-// NA = 2, first two if NA = 1; see prime_steps).
+// What survives a phase boundary: the weights issued ahead for the next phase (see prime_steps).
+constexpr int RING_SLOTS = 6;
 struct Ring {
-    Frag8 f[6][4];        // slot (step % DS) * NA + stream; DS - 1 steps are in flight while one is consumed
+    Frag8 f[RING_SLOTS][4];   // slot (step % DS) * NA + stream
 };
-template <int NA> struct RingCfg { static constexpr int DS = NA == 2 ? 3 : 4; };
+// Per phase: DS = steps the ring holds, PF = steps requested while the grid barrier in front of the phase resolves
+// (the other DS - 1 - PF follow the staging requests). Chosen by sweeps inside ONE run of the nine-row 7B launch (the
+// machines differ by more than the settings do), milliseconds per step relative to the setting kept:
+//   single-tile phases (QKV, O, head): DS 2 / PF 1, i.e. ONE step (4 KiB per wave) in flight; DS 3 / PF 2 +0.4 % (O),
+//     +0.7 % (QKV), DS 4 / PF 2 +2.2 % (all three together), PF 0 +1.5 % (QKV), +1.9 % (O); the head is indifferent;
+//   down: DS 3 / PF 2 (DS 2 / PF 1 +0.5 %, DS 4 / PF 2 or 3 +0.8 %, DS 5 / PF 4 equal);
+//   gate/up (NA = 2): DS 3 / PF 2, the whole ring inside the barrier (PF 1 +1.1 %, PF 0 +2.3 %, DS 2 / PF 1 +0.9 %;
+//     a fourth step needs 8 ring slots and costs 3-4 % in spills).
+// Deeper rings do not stream faster: a compute unit's memory queues hold less than 8 waves x 16 KiB, and whatever is
+// queued in front of the staged activations or the epilogue's stores delays them.
+constexpr int DS_QKV = 2, PF_QKV = 1, DS_O = 2, PF_O = 1, DS_GU = 3, PF_GU = 2, DS_DOWN = 3, PF_DOWN = 2, DS_HEAD = 2, PF_HEAD = 1;
+static_assert(DS_QKV <= RING_SLOTS && DS_O <= RING_SLOTS && DS_DOWN <= RING_SLOTS && DS_HEAD <= RING_SLOTS && 2 * DS_GU <= RING_SLOTS,
+              "the ring holds DS steps of NA fragments");
 
 // Issue the weights of this wave's steps T0 .. T1-1 (of the first DS-1) of chunk `chunk` of phase `ph` into
-// their ring slots. Weights never depend on activations, so the first PF1 steps are issued while the grid
-// barrier in front of the phase resolves and the others right behind the requests that stage the phase's
-// activations. Issuing a wave's whole ring inside the barrier stalls it there for microseconds (the compute
-// unit's memory queues hold less than 8 waves x 16 KiB), which delays the barrier's exit by more than the
-// early start gains: PF1 = two steps (one for pair tiles) measured best. The loads are unconditional (steps past the wave's
-// last one re-request one cached line), so that the number of vector-memory instructions issued here is a
-// compile-time constant: stage_wait counts on it.
-constexpr int pf1_steps(int NA) { return NA == 2 ? 1 : 2; }
+// their ring slots. Weights never depend on activations, so the first PF steps are issued while the grid
+// barrier in front of the phase resolves and the others (if any) right behind the requests that stage the
+// phase's activations. The loads are unconditional (steps past the wave's last one re-request one cached line),
+// so that the number of vector-memory instructions issued here is a compile-time constant: stage_wait counts
+// on it.
 template <int NA, int T0, int T1>
 __device__ inline void prime_steps(const FusedArgs& a, const Phase& ph, int chunk, Ring& R) {
     const int lane = threadIdx.x & 63;
@@ -393,14 +400,13 @@ __device__ inline void stage_wait() {
 
 // Streams one chunk: this wave's units x steps, partial sums of finished units to sh.red
 // (stored on the first chunk, accumulated on later ones; slot = unit * NA + stream).
-template <int NA, bool SPLIT>
+template <int NA, int DS, bool SPLIT>
 __device__ inline void stream_chunk(const FusedArgs& a, Shared& sh, const uint4* xs, const Phase& ph,
                                     const WaveWork& w, bool first, Ring& R) {
-    constexpr int DS = RingCfg<NA>::DS;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
     if (w.T > 0) {
-        Frag8 (&A)[6][4] = R.f;             // the ring: steps 0 .. DS-2 are on their way (prime_steps)
+        Frag8 (&A)[RING_SLOTS][4] = R.f;             // the ring: steps 0 .. DS-2 are on their way (prime_steps)
         const uint16_t* wp[NA];             // this lane's pointers to the next step to request
         int jn = 0, kn = 0;                 // (unit, step) of that step
         // Past the last step the pointers park on one lane-uniform, always-valid address, so the
@@ -492,11 +498,10 @@ __device__ inline void stream_chunk(const FusedArgs& a, Shared& sh, const uint4*
 // Streams a whole phase: for every chunk stage its activations, stream, and issue the next chunk's
 // first weights before the staging barrier. On return sh.red holds every unit's partial sums and
 // all waves have passed a workgroup barrier.
-template <int NA, bool SPLIT, bool TR, bool OWN = true, int PF1 = pf1_steps(NA)>
+template <int NA, bool SPLIT, bool TR, int DS, int PF1, bool OWN = true>
 __device__ inline void stream_phase(const FusedArgs& a, Shared& sh, uint4* xs, const Phase& ph,
                                     const uint16_t* __restrict__ X, const uint8_t* __restrict__ Xlo, Ring& R,
                                     int trace_layer = -1, int trace_slot = 0) {
-    constexpr int DS = RingCfg<NA>::DS;
     const int nch = n_chunks(a, ph);
     for (int c = 0; c < nch; ++c) {
         const WaveWork w = wave_work(a, ph, c);
@@ -520,7 +525,7 @@ __device__ inline void stream_phase(const FusedArgs& a, Shared& sh, uint4* xs, c
         }
         if constexpr (!OWN) __syncthreads();     // shared staging: every wave's pieces have landed
         if (c == 0) stamp_fine<TR>(a, trace_layer, trace_slot);
-        stream_chunk<NA, SPLIT>(a, sh, xs, ph, w, c == 0, R);
+        stream_chunk<NA, DS, SPLIT>(a, sh, xs, ph, w, c == 0, R);
     }
     __syncthreads();
     stamp_fine<TR>(a, trace_layer, trace_slot + 1);
@@ -1123,7 +1128,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         {
             const Phase p_q{a.wqkv + (size_t)l * 3 * a.d * a.d, PH_QKV, a.d, 2};
             stamp<TR>(a, ns);
-            if (!grid_sync(a, sh, epoch, [&] { prime_steps<1, 0, pf1_steps(1)>(a, p_q, 0, ring); })) return;
+            if (!grid_sync(a, sh, epoch, [&] { prime_steps<1, 0, PF_QKV>(a, p_q, 0, ring); })) return;
             stamp<TR>(a, ns);
         }
         const float* x_in = a.xbuf + (size_t)(2 * l) * XS;           // after the previous layer
@@ -1150,7 +1155,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         {
             float ssv[8];
             ss_issue(ss_in, ssv);
-            stream_phase<1, true, TR>(a, sh, xs, p_qkv, xg_in, xgl_in, ring, l, 0);
+            stream_phase<1, true, TR, DS_QKV, PF_QKV>(a, sh, xs, p_qkv, xg_in, xgl_in, ring, l, 0);
             ss_finish(a, sh, ssv);
             const int per = a.d / 32, pph = DH / 32, half = DH / 2;
             const int cnt = count_mine(a.d / 16, w, nwg);
@@ -1212,14 +1217,14 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         // ---- attention ----
         attention_phase<DH, TR>(a, sh, l, pg_first);
         stamp<TR>(a, ns);
-        if (!grid_sync(a, sh, epoch, [&] { prime_steps<1, 0, pf1_steps(1)>(a, p_o, 0, ring); })) return;
+        if (!grid_sync(a, sh, epoch, [&] { prime_steps<1, 0, PF_O>(a, p_o, 0, ring); })) return;
         stamp<TR>(a, ns);
 
         // ---- O projection + residual; publish x, x*g2, sum of squares ----
         {
             float ss = 0.f;
             const float* g2 = a.g2 + (size_t)l * a.d;
-            stream_phase<1, true, TR>(a, sh, xs, p_o, a.attn + lo, a.attnl + lo, ring, l, 3);
+            stream_phase<1, true, TR, DS_O, PF_O>(a, sh, xs, p_o, a.attn + lo, a.attnl + lo, ring, l, 3);
             reduce_epilogue<1>(a, sh, n_units(a, PH_O), [&](int u, int row, int f0, float (&v)[1][2]) {
                 const int item = w + u * nwg;
                 const size_t o = (size_t)row * a.d + item * 16 + f0;
@@ -1235,14 +1240,14 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
             publish_ss(sh, ss_mid + (size_t)blockIdx.x * 16, ss);
         }
         stamp<TR>(a, ns);
-        if (!grid_sync(a, sh, epoch, [&] { prime_steps<2, 0, pf1_steps(2)>(a, p_gu, 0, ring); })) return;
+        if (!grid_sync(a, sh, epoch, [&] { prime_steps<2, 0, PF_GU>(a, p_gu, 0, ring); })) return;
         stamp<TR>(a, ns);
 
         // ---- gate/up + SwiGLU ----
         {
             float ssv[8];
             ss_issue(ss_mid, ssv);
-            stream_phase<2, true, TR>(a, sh, xs, p_gu, xg_mid, xgl_mid, ring, l, 6);
+            stream_phase<2, true, TR, DS_GU, PF_GU>(a, sh, xs, p_gu, xg_mid, xgl_mid, ring, l, 6);
             ss_finish(a, sh, ssv);
             uint16_t* act = a.act + (size_t)l * 16 * a.F;
             reduce_epilogue<2>(a, sh, n_units(a, PH_GU), [&](int u, int row, int f0, float (&v)[2][2]) {
@@ -1258,7 +1263,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
             });
         }
         stamp<TR>(a, ns);
-        if (!grid_sync(a, sh, epoch, [&] { prime_steps<1, 0, pf1_steps(1)>(a, p_dn, 0, ring); })) return;
+        if (!grid_sync(a, sh, epoch, [&] { prime_steps<1, 0, PF_DOWN>(a, p_dn, 0, ring); })) return;
         stamp<TR>(a, ns);
 
         // ---- down projection + residual; publish x, x*gain(next norm), sum of squares ----
@@ -1266,7 +1271,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
             float ss = 0.f;
             const bool last = l + 1 == a.L;
             const float* gn = last ? a.gf : a.g1 + (size_t)(l + 1) * a.d;
-            stream_phase<1, false, TR>(a, sh, xs, p_dn, a.act + (size_t)l * 16 * a.F, nullptr, ring, l, 9);
+            stream_phase<1, false, TR, DS_DOWN, PF_DOWN>(a, sh, xs, p_dn, a.act + (size_t)l * 16 * a.F, nullptr, ring, l, 9);
             reduce_epilogue<1>(a, sh, n_units(a, PH_DOWN), [&](int u, int row, int f0, float (&v)[1][2]) {
                 const int item = w + u * nwg;
                 const size_t o = (size_t)row * a.d + item * 16 + f0;
@@ -1283,7 +1288,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         }
     }
     stamp<TR>(a, ns);
-    if (!grid_sync(a, sh, epoch, [&] { prime_steps<1, 0, pf1_steps(1)>(a, p_head, 0, ring); })) return;
+    if (!grid_sync(a, sh, epoch, [&] { prime_steps<1, 0, PF_HEAD>(a, p_head, 0, ring); })) return;
     stamp<TR>(a, ns);
 
     // ---- output head + acceptance ----
@@ -1291,7 +1296,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
     {
         float ssv[8];
         ss_issue(a.ssbuf + (size_t)(2 * a.L) * nwg * 16, ssv);
-        stream_phase<1, false, TR, false>(a, sh, xs, p_head, a.xgbuf + (size_t)(2 * a.L) * XS, nullptr, ring);
+        stream_phase<1, false, TR, DS_HEAD, PF_HEAD, false>(a, sh, xs, p_head, a.xgbuf + (size_t)(2 * a.L) * XS, nullptr, ring);
         ss_finish(a, sh, ssv);
         if (a.topk <= 2) head_epilogue<2>(a, sh, xs, chunks);
         else head_epilogue<KTOP>(a, sh, xs, chunks);
