@@ -85,6 +85,12 @@ __device__ inline void st_u32(void* p, uint32_t v) {
     __hip_atomic_store(reinterpret_cast<uint32_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ inline void st_f32(float* p, float v) { st_u32(p, __float_as_uint(v)); }
+// two neighbouring floats (8-byte aligned) as one store
+__device__ inline void st_f32x2(float* p, float v0, float v1) {
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p),
+                       (unsigned long long)__float_as_uint(v0) | ((unsigned long long)__float_as_uint(v1) << 32),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ inline void st_i32(int* p, int v) { st_u32(p, (uint32_t)v); }
 __device__ inline void st_u16(void* p, uint16_t v) {
     __hip_atomic_store(reinterpret_cast<uint16_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -548,9 +554,9 @@ __device__ inline void reduce_epilogue(const FusedArgs& a, Shared& sh, int n_my,
                     float t = 0.f;
 #pragma unroll
                     for (int wv = 0; wv < FWAVES; ++wv) t += sh.red[j * NA + s][wv][i][ln];
-                    v[s][q] = row < a.M ? t : 0.f;      // padding rows stay exactly zero
+                    v[s][q] = t;
                 }
-            epi(j, row, f0, v);
+            if (row < a.M) epi(j, row, f0, v);      // padding rows publish nothing (nobody reads rows >= M of an exchange buffer)
         }
     }
     __syncthreads();        // sh.red is free again (it shares LDS with the attention buffers)
@@ -815,8 +821,7 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
                 }
             } else {
                 if (c == 0) { st_f32(part + q, M); st_f32(part + 16 + q, Lq); }
-                st_f32(part + 32 + q * DH + c, O0);
-                st_f32(part + 32 + q * DH + c + 1, O1);
+                st_f32x2(part + 32 + q * DH + c, O0, O1);
             }
         }
         if (S > 1) {
@@ -1108,7 +1113,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
                     v1 = __uint_as_float(e & 0xFFFF0000u);
                 }
                 const size_t o = (size_t)row * a.d + tile * 16 + f0;
-                st_f32(a.xbuf + o, v0); st_f32(a.xbuf + o + 1, v1);
+                st_f32x2(a.xbuf + o, v0, v1);
                 uint32_t hi;
                 uint16_t lw;
                 split_pack_h2_b8(v0 * gain0[tile * 16 + f0], v1 * gain0[tile * 16 + f0 + 1], hi, lw);
@@ -1229,7 +1234,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
                 const int item = w + u * nwg;
                 const size_t o = (size_t)row * a.d + item * 16 + f0;
                 const float n0 = x_in[o] + v[0][0], n1 = x_in[o + 1] + v[0][1];
-                st_f32(x_mid + o, n0); st_f32(x_mid + o + 1, n1);
+                st_f32x2(x_mid + o, n0, n1);
                 uint32_t hi;
                 uint16_t lw;
                 split_pack_h2_b8(n0 * g2[item * 16 + f0], n1 * g2[item * 16 + f0 + 1], hi, lw);
@@ -1276,7 +1281,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
                 const int item = w + u * nwg;
                 const size_t o = (size_t)row * a.d + item * 16 + f0;
                 const float n0 = x_mid[o] + v[0][0], n1 = x_mid[o + 1] + v[0][1];
-                st_f32(x_out + o, n0); st_f32(x_out + o + 1, n1);
+                st_f32x2(x_out + o, n0, n1);
                 uint32_t hi;
                 uint16_t lw;
                 split_pack_h2_b8(n0 * gn[item * 16 + f0], n1 * gn[item * 16 + f0 + 1], hi, lw);
