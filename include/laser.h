@@ -253,8 +253,9 @@ int laser_verify_step(laser_model* model, laser_kv* kv, const int32_t* seq_ids,
  *   accept_len  [dev] int32[B]      out: a = nodes on the accepted branch
  *   out_tokens  [dev] int32[B][K+1] out: the branch's tokens, then argmax of its last node's row (of row 0 if a = 0), then -1
  *   accept_path [dev] int32[B][K]   out: pseudo-sequence indices of the branch's nodes, root side first, then -1
- * A tree whose parent[i] = i - 1 is a chain and gives the results of laser_verify_step on its general path bit for
- * bit. Always runs the general (multi-kernel) path. Follow with laser_kv_commit_tree. */
+ * A tree whose parent[i] = i - 1 is a chain and gives the results of laser_verify_step bit for bit: both calls choose
+ * their path by the row count alone (at most 16 rows in all, B (K + 1) <= 16: the persistent few-row kernel, unless
+ * option "fused" is 0). Follow with laser_kv_commit_tree. */
 int laser_verify_tree(laser_model* model, laser_kv* kv, const int32_t* seq_ids,
                       const int32_t* pending, const int32_t* tree_tokens, const int32_t* tree_parent,
                       const int32_t* tree_len, int B, int K, int topk, float p, int mode,

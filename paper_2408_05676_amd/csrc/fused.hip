@@ -29,6 +29,7 @@
 #include <algorithm>
 #include <cmath>
 
+#include "head_part.h"
 #include "mfma.h"
 #include "state.h"
 
@@ -51,6 +52,13 @@ struct FusedArgs {
     const int32_t *block_table, *lens;
     int mpps, n_pages;
     const int32_t *seq_ids, *pending, *drafts, *draft_len;
+    // Token trees (Sec. 3.3): parent != NULL. drafts / draft_len then hold the nodes of the pseudo-sequence and their
+    // count, parent[b][i] the node's parent (tree_parent_of), row_pos_g / row_anc_g [M] each row's position (committed
+    // length + depth) and the rows of its sequence it attends to (bit j: row j), accept_path the third output.
+    const int32_t* parent;
+    const int32_t* row_pos_g;
+    const unsigned long long* row_anc_g;
+    int32_t* accept_path;
     int B, K, R, M;
     // exchange buffers (write-once per launch)
     float* xbuf;        // [2L+1][16][d]
@@ -617,7 +625,7 @@ __device__ inline void attn_pages(const FusedArgs& a, const Shared& sh, int item
     for (int pp = 0; pp < PPW; ++pp) pg[pp] = bt[min(pbase + pp, n_pages - 1)];
 }
 
-template <int DH, bool TR>
+template <int DH, bool TR, bool TREE>
 __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer, int (&pg_next)[PPW]) {
     constexpr int NC32 = DH / 32, NC16 = DH / 16;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -660,6 +668,9 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
 #pragma unroll
                 for (int pp = 0; pp < PPW; ++pp) pg[pp] = pg_next[pp];       // requested ahead (attn_pages)
                 Frag8 bq[NC32], bql[NC32];
+                // token tree (Sec. 3.3): which new rows query row r sees (bit j: row j of the sequence), itself and its
+                // ancestors; loaded with the fragments
+                const unsigned long long* ancp = a.row_anc_g + b * a.R + min(r, a.R - 1);     // TREE only
                 const size_t qo = (size_t)(b * a.R + min(r, a.R - 1)) * a.d + (size_t)h * DH + g * 8;
                 const uint16_t *qp = qb + qo, *qlp = qlb + qo;
                 Frag8 ak[PPW][NC32];
@@ -689,6 +700,8 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
                     nvp[pp] = p >= pg0 ? vn + ((size_t)(b * npp + pi) * a.H + h) * kPageSize * DH + (size_t)r * kPageSize + 4 * g : vn;
                 }
                 __builtin_amdgcn_sched_barrier(0);
+                unsigned anc = 0;
+                if constexpr (TREE) anc = (unsigned)*ancp;
 #pragma unroll
                 for (int c = 0; c < NC32; ++c) bq[c].u = *reinterpret_cast<const uint4*>(qp + c * 32);
 #pragma unroll
@@ -754,7 +767,10 @@ __device__ inline void attention_phase(const FusedArgs& a, Shared& sh, int layer
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int ts = s0 + 4 * g + i;                 // slot of this score's key
-                        const bool vis = (r < a.R) && (ts <= len + r);   // query row r sits at slot len + r
+                        // chain: query row r sits at slot len + r and sees everything up to itself; tree: committed slots
+                        // are visible to every query row, new rows by the mask (bit ts - len)
+                        const bool vis = TREE ? (r < a.R) && (ts < len || (ts < len + a.R && ((anc >> ((ts - len) & 31)) & 1u)))
+                                              : (r < a.R) && (ts <= len + r);
                         sv[i] = vis ? s[i] * scale : -INFINITY;
                         mx = fmaxf(mx, sv[i]);
                     }
@@ -935,7 +951,7 @@ struct HStat {
 
 // Consumes the logits tiles a wave has accumulated in sh.red (unit u of global wave gw is vocabulary
 // tile gw + u * waves of the launch): per-row running statistics, merged per workgroup.
-template <int KD>
+template <int KD, bool TREE>
 __device__ inline void head_epilogue(const FusedArgs& a, Shared& sh, uint4* xs, int chunks) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
@@ -945,7 +961,7 @@ __device__ inline void head_epilogue(const FusedArgs& a, Shared& sh, uint4* xs, 
     if (row < a.M) {
         const int b = row / a.R, rr = row % a.R;
         x = (rr < a.K && rr < a.draft_len[b]) ? a.drafts[(size_t)b * a.K + rr] : -1;
-        if (x >= a.V) x = -1;
+        if (x >= a.V || TREE) x = -1;               // token trees: the nodes' logits are picked below
     }
     HStat<KD> st;
     st.init();
@@ -963,6 +979,21 @@ __device__ inline void head_epilogue(const FusedArgs& a, Shared& sh, uint4* xs, 
         }
         if (a.logits_dbg && row < a.M)
             *reinterpret_cast<float4*>(a.logits_dbg + (size_t)row * a.V + n) = make_float4(lv[0], lv[1], lv[2], lv[3]);
+    }
+    if constexpr (TREE) {
+        // Token tree: node i of sequence b is judged by the row of its PARENT (row 0, the pending token, for a child of
+        // the root), and a row may have several children. A node whose token lies in one of this wave's vocabulary
+        // tiles takes its logit from the tile's sums: element (row, token % 16) of unit token / 16 / waves.
+        for (int j = lane; j < a.B * a.K; j += 64) {
+            const int b = j / a.K, i = j % a.K;
+            int nn = a.draft_len[b];
+            nn = nn < 0 ? 0 : (nn > a.K ? a.K : nn);
+            const int tok = i < nn ? a.drafts[j] : -1;
+            if (tok >= 0 && tok < a.V && (tok >> 4) % ngw == gw) {
+                const int u = (tok >> 4) / ngw, prow = b * a.R + tree_parent_of(a.parent, b, a.K, i, nn) + 1;
+                st_f32(a.hp_lx + b * a.R + i, sh.red[u][wave][tok & 3][((tok >> 2) & 3) * 16 + prow] * sh.rs[prow]);
+            }
+        }
     }
     st.merge_xor(16);
     st.merge_xor(32);
@@ -1001,8 +1032,56 @@ __device__ inline void head_epilogue(const FusedArgs& a, Shared& sh, uint4* xs, 
     }
 }
 
-// One workgroup per sequence, one wave per row (rows wave, wave + 8, ..): lanes stride over the
-// per-workgroup records (`chunks` = workgroups of the launch), four records in flight per lane.
+// Statistics of row `row` over the per-workgroup records (`chunks` = workgroups of the launch; lanes stride over them,
+// four records in flight per lane) and the verdict of Eq. 8 on candidate token x with logit lx at that row (x < 0: none).
+// Every lane returns the row's arg-max; lane 0's `ok` is the verdict.
+__device__ __forceinline__ void accept_eval(const FusedArgs& a, int chunks, int row, int x, float lx, bool& ok, int& arg_out) {
+    const int lane = threadIdx.x & 63;
+    float mx = -INFINITY, sum = 0.f;
+    int arg = 0x7FFFFFFF, ahead = 0;
+    for (int c0 = lane; c0 < chunks; c0 += 64 * 4) {
+        float cm[4], cs[4], tv[4][KTOP];
+        int ca[4], ti[4][KTOP];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {          // unconditional loads (clamped), all in flight together
+            const size_t o = (size_t)row * chunks + min(c0 + 64 * q, chunks - 1);
+            cm[q] = a.hp_max[o]; cs[q] = a.hp_sum[o]; ca[q] = a.hp_arg[o];
+#pragma unroll
+            for (int j = 0; j < KTOP; ++j) { tv[q][j] = a.hp_topv[o * KTOP + j]; ti[q][j] = a.hp_topi[o * KTOP + j]; }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (c0 + 64 * q >= chunks) continue;
+            const float M = fmaxf(mx, cm[q]);
+            if (M != -INFINITY) sum = sum * __expf(mx - M) + cs[q] * __expf(cm[q] - M);
+            if (hbefore(cm[q], ca[q], mx, arg)) arg = ca[q];
+            mx = M;
+            if (x >= 0)
+#pragma unroll
+                for (int j = 0; j < KTOP; ++j) ahead += (ti[q][j] != x && hbefore(tv[q][j], ti[q][j], lx, x)) ? 1 : 0;
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const float omx = __shfl_xor(mx, off), osum = __shfl_xor(sum, off);
+        const int oarg = __shfl_xor(arg, off);
+        ahead += __shfl_xor(ahead, off);
+        const float M = fmaxf(mx, omx);
+        if (M != -INFINITY) sum = sum * __expf(mx - M) + osum * __expf(omx - M);
+        if (hbefore(omx, oarg, mx, arg)) arg = oarg;
+        mx = M;
+    }
+    ok = false;
+    if (x >= 0) {
+        const float q = __expf(lx - mx) / sum;
+        const bool in_k = ahead < a.topk, above = q > a.p, top1 = ahead == 0;
+        ok = a.mode == LASER_MODE_RV ? (in_k && above)
+           : a.mode == LASER_MODE_RV_OR_TOP1 ? (top1 || (in_k && above))
+           : a.mode == LASER_MODE_TOPK_ONLY ? in_k : (top1 || above);
+    }
+    arg_out = arg;
+}
+
+// One workgroup per sequence, one wave per row (rows wave, wave + 8, ..).
 __device__ inline void accept_phase(const FusedArgs& a, Shared& sh, int chunks) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     for (int b = blockIdx.x; b < a.B; b += gridDim.x) {
@@ -1011,48 +1090,10 @@ __device__ inline void accept_phase(const FusedArgs& a, Shared& sh, int chunks) 
             int x = (r < a.K && r < a.draft_len[b]) ? a.drafts[(size_t)b * a.K + r] : -1;
             if (x >= a.V) x = -1;
             const float lx = x >= 0 ? a.hp_lx[row] : -INFINITY;
-            float mx = -INFINITY, sum = 0.f;
-            int arg = 0x7FFFFFFF, ahead = 0;
-            for (int c0 = lane; c0 < chunks; c0 += 64 * 4) {
-                float cm[4], cs[4], tv[4][KTOP];
-                int ca[4], ti[4][KTOP];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {          // unconditional loads (clamped), all in flight together
-                    const size_t o = (size_t)row * chunks + min(c0 + 64 * q, chunks - 1);
-                    cm[q] = a.hp_max[o]; cs[q] = a.hp_sum[o]; ca[q] = a.hp_arg[o];
-#pragma unroll
-                    for (int j = 0; j < KTOP; ++j) { tv[q][j] = a.hp_topv[o * KTOP + j]; ti[q][j] = a.hp_topi[o * KTOP + j]; }
-                }
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (c0 + 64 * q >= chunks) continue;
-                    const float M = fmaxf(mx, cm[q]);
-                    if (M != -INFINITY) sum = sum * __expf(mx - M) + cs[q] * __expf(cm[q] - M);
-                    if (hbefore(cm[q], ca[q], mx, arg)) arg = ca[q];
-                    mx = M;
-                    if (x >= 0)
-#pragma unroll
-                        for (int j = 0; j < KTOP; ++j) ahead += (ti[q][j] != x && hbefore(tv[q][j], ti[q][j], lx, x)) ? 1 : 0;
-                }
-            }
-            for (int off = 32; off > 0; off >>= 1) {
-                const float omx = __shfl_xor(mx, off), osum = __shfl_xor(sum, off);
-                const int oarg = __shfl_xor(arg, off);
-                ahead += __shfl_xor(ahead, off);
-                const float M = fmaxf(mx, omx);
-                if (M != -INFINITY) sum = sum * __expf(mx - M) + osum * __expf(omx - M);
-                if (hbefore(omx, oarg, mx, arg)) arg = oarg;
-                mx = M;
-            }
+            bool ok;
+            int arg;
+            accept_eval(a, chunks, row, x, lx, ok, arg);
             if (lane == 0) {
-                bool ok = false;
-                if (x >= 0) {
-                    const float q = __expf(lx - mx) / sum;
-                    const bool in_k = ahead < a.topk, above = q > a.p, top1 = ahead == 0;
-                    ok = a.mode == LASER_MODE_RV ? (in_k && above)
-                       : a.mode == LASER_MODE_RV_OR_TOP1 ? (top1 || (in_k && above))
-                       : a.mode == LASER_MODE_TOPK_ONLY ? in_k : (top1 || above);
-                }
                 sh.row_ok[r] = ok ? 1 : 0;
                 sh.row_arg[r] = arg;
             }
@@ -1071,8 +1112,62 @@ __device__ inline void accept_phase(const FusedArgs& a, Shared& sh, int chunks) 
     }
 }
 
+// The same for a token tree (Sec. 3.3, Sec. 3.4): one job per row (its arg-max, for the token that follows the accepted
+// branch) and one per node (Eq. 8 on the node's token against its parent's row), dealt to the waves; then thread 0
+// walks the nodes in pseudo-sequence order: a node is verified iff its parent is and its token passed, the deepest
+// verified node -- the first among equally deep -- ends the accepted branch.
+__device__ inline void accept_phase_tree(const FusedArgs& a, Shared& sh, int chunks) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int b = blockIdx.x; b < a.B; b += gridDim.x) {
+        int nn = a.draft_len[b];
+        nn = nn < 0 ? 0 : (nn > a.K ? a.K : nn);
+        for (int job = wave; job < a.R + nn; job += FWAVES) {
+            bool ok;
+            int arg;
+            if (job < a.R) {
+                accept_eval(a, chunks, b * a.R + job, -1, -INFINITY, ok, arg);
+                if (lane == 0) sh.row_arg[job] = arg;
+            } else {
+                const int i = job - a.R;
+                int x = a.drafts[(size_t)b * a.K + i];
+                if (x >= a.V) x = -1;
+                const float lx = x >= 0 ? a.hp_lx[b * a.R + i] : -INFINITY;
+                accept_eval(a, chunks, b * a.R + tree_parent_of(a.parent, b, a.K, i, nn) + 1, x, lx, ok, arg);
+                if (lane == 0) sh.row_ok[i] = ok ? 1 : 0;
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            unsigned ver = 0;                        // bit i: node i is verified
+            int depth[LASER_MAX_DRAFT + 1];
+            int best = -1, best_depth = 0;
+            for (int i = 0; i < nn; ++i) {
+                const int par = tree_parent_of(a.parent, b, a.K, i, nn);
+                depth[i] = 0;
+                if (sh.row_ok[i] && (par < 0 || ((ver >> par) & 1u))) {
+                    ver |= 1u << i;
+                    depth[i] = par < 0 ? 1 : depth[par] + 1;
+                    if (depth[i] > best_depth) { best = i; best_depth = depth[i]; }
+                }
+            }
+            a.accept_len[b] = best_depth;
+            int32_t* out = a.out_tokens + (size_t)b * a.R;
+            for (int j = best_depth + 1; j < a.R; ++j) out[j] = -1;
+            out[best_depth] = sh.row_arg[best + 1];
+            for (int i = best, j = best_depth - 1; j >= 0; --j) {
+                out[j] = a.drafts[(size_t)b * a.K + i];
+                if (a.accept_path) a.accept_path[(size_t)b * a.K + j] = i;
+                i = tree_parent_of(a.parent, b, a.K, i, nn);
+            }
+            if (a.accept_path)
+                for (int j = best_depth; j < a.K; ++j) a.accept_path[(size_t)b * a.K + j] = -1;
+        }
+        __syncthreads();
+    }
+}
+
 // ---- the kernel --------------------------------------------------------------------------------------
-template <int DH, bool TR>
+template <int DH, bool TR, bool TREE>
 __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Shared& sh = *reinterpret_cast<Shared*>(smem_raw);
@@ -1083,7 +1178,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
     if (threadIdx.x < 16) {
         const int row = threadIdx.x;
         int pos = 0, b = 0;
-        if (row < a.M) { b = row / a.R; pos = a.lens[a.seq_ids[b]] + row % a.R; }
+        if (row < a.M) { b = row / a.R; pos = TREE ? a.row_pos_g[row] : a.lens[a.seq_ids[b]] + row % a.R; }
         sh.row_pos[row] = pos;
         sh.row_b[row] = b;
         const int sl = row < a.B ? a.seq_ids[row] : 0;
@@ -1201,7 +1296,8 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
                 } else {
                     const int idx = w + (u - 2 * cnt) * nwg;
                     // values go into the page-shaped exchange buffer at the row's slot of its page
-                    const int bb = sh.row_b[row], pos = sh.row_pos[row], npp = a.R == 1 ? 1 : 2;
+                    const int bb = sh.row_b[row], npp = a.R == 1 ? 1 : 2;
+                    const int pos = TREE ? sh.seq_len[bb] + row - bb * a.R : sh.row_pos[row];        // cache slot (row order), not the rotary position
                     const int pi = row < a.M ? pos / kPageSize - sh.seq_len[bb] / kPageSize : 0;
                     const int ch = idx * 16 + f0;                          // channel (head * dh + c) of v[0][0]
                     uint16_t* dst = a.vnew + lo * kPageSize + ((size_t)(bb * npp + pi) * a.d + ch) * kPageSize + pos % kPageSize;
@@ -1220,7 +1316,7 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         stamp<TR>(a, ns);
 
         // ---- attention ----
-        attention_phase<DH, TR>(a, sh, l, pg_first);
+        attention_phase<DH, TR, TREE>(a, sh, l, pg_first);
         stamp<TR>(a, ns);
         if (!grid_sync(a, sh, epoch, [&] { prime_steps<1, 0, PF_O>(a, p_o, 0, ring); })) return;
         stamp<TR>(a, ns);
@@ -1303,13 +1399,14 @@ __global__ __launch_bounds__(FT) void verify_fused_kernel(FusedArgs a) {
         ss_issue(a.ssbuf + (size_t)(2 * a.L) * nwg * 16, ssv);
         stream_phase<1, false, TR, DS_HEAD, PF_HEAD, false>(a, sh, xs, p_head, a.xgbuf + (size_t)(2 * a.L) * XS, nullptr, ring);
         ss_finish(a, sh, ssv);
-        if (a.topk <= 2) head_epilogue<2>(a, sh, xs, chunks);
-        else head_epilogue<KTOP>(a, sh, xs, chunks);
+        if (a.topk <= 2) head_epilogue<2, TREE>(a, sh, xs, chunks);
+        else head_epilogue<KTOP, TREE>(a, sh, xs, chunks);
     }
     stamp<TR>(a, ns);
     if (!grid_sync(a, sh, epoch, no_prefetch)) return;
     stamp<TR>(a, ns);
-    accept_phase(a, sh, chunks);
+    if constexpr (TREE) accept_phase_tree(a, sh, chunks);
+    else accept_phase(a, sh, chunks);
     stamp<TR>(a, ns);
 }
 
@@ -1406,8 +1503,9 @@ static int fused_prepare(Model* m, int B, hipStream_t stream, FusedWS** out) {
         ws->hp_topv = (float*)(b + o_tv); ws->hp_topi = (int32_t*)(b + o_ti); ws->hp_lx = (float*)(b + o_lx);
         ws->nwg = nwg; ws->bh_cap = bh_cap;
         const size_t lds = (size_t)g_lds_max;
-        const void* fns[4] = {(const void*)verify_fused_kernel<128, false>, (const void*)verify_fused_kernel<128, true>,
-                              (const void*)verify_fused_kernel<64, false>, (const void*)verify_fused_kernel<64, true>};
+        const void* fns[6] = {(const void*)verify_fused_kernel<128, false, false>, (const void*)verify_fused_kernel<128, true, false>,
+                              (const void*)verify_fused_kernel<64, false, false>, (const void*)verify_fused_kernel<64, true, false>,
+                              (const void*)verify_fused_kernel<128, false, true>, (const void*)verify_fused_kernel<64, false, true>};
         for (const void* f : fns) LASER_HIP_CHECK(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     }
     if (m->fused_trace && !ws->trace) {
@@ -1420,9 +1518,11 @@ static int fused_prepare(Model* m, int B, hipStream_t stream, FusedWS** out) {
     return LASER_OK;
 }
 
-int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, const int32_t* drafts,
+// parent != NULL: a token tree (drafts / draft_len = its nodes and their count); the caller has filled m->row_pos and
+// m->row_anc for this step (rows_kernel) on the same stream.
+int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, const int32_t* drafts, const int32_t* parent,
               const int32_t* draft_len, int B, int K, int topk, float p, int mode, int32_t* accept_len,
-              int32_t* out_tokens, float* logits_dbg, int max_len_ub, hipStream_t stream) {
+              int32_t* out_tokens, int32_t* accept_path, float* logits_dbg, int max_len_ub, hipStream_t stream) {
     FusedWS* ws = nullptr;
     int rc = fused_prepare(m, B, stream, &ws);
     if (rc) return rc;
@@ -1440,6 +1540,7 @@ int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, 
     a.kpages = kv->kpages; a.klpages = kv->klpages; a.vpages = kv->vpages; a.block_table = kv->block_table; a.lens = kv->len;
     a.mpps = kv->d.max_pages_per_seq; a.n_pages = kv->d.n_pages;
     a.seq_ids = ids_dev; a.pending = pending; a.drafts = drafts; a.draft_len = draft_len;
+    a.parent = parent; a.row_pos_g = m->row_pos; a.row_anc_g = m->row_anc; a.accept_path = accept_path;
     a.B = B; a.K = K; a.R = R; a.M = B * R;
     a.xbuf = ws->xbuf; a.xgbuf = ws->xgbuf; a.ssbuf = ws->ssbuf; a.qbuf = ws->qbuf; a.knew = ws->knew; a.vnew = ws->vnew;
     a.attn = ws->attn; a.act = ws->act; a.apart = ws->apart; a.acount = ws->acount; a.nsplit = S;
@@ -1451,12 +1552,14 @@ int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, 
     a.topk = topk; a.mode = mode; a.p = p; a.accept_len = accept_len; a.out_tokens = out_tokens; a.logits_dbg = logits_dbg;
     a.bar_count = ws->bar; a.bar_flag = ws->bar + 128; a.abort_flag = reinterpret_cast<int*>(ws->bar + 64);
     a.epoch0 = ws->epoch;
-    a.trace = m->fused_trace ? ws->trace : nullptr;
+    a.trace = m->fused_trace && !parent ? ws->trace : nullptr;
     a.trace_cap = ws->trace_cap;
     void* args[] = {&a};
     const bool tr = a.trace != nullptr;
-    const void* fn = m->dh == 128 ? (tr ? (const void*)verify_fused_kernel<128, true> : (const void*)verify_fused_kernel<128, false>)
-                                  : (tr ? (const void*)verify_fused_kernel<64, true> : (const void*)verify_fused_kernel<64, false>);
+    // (a token tree is never traced: its launches take the untraced instantiation)
+    const void* fn = parent ? (m->dh == 128 ? (const void*)verify_fused_kernel<128, false, true> : (const void*)verify_fused_kernel<64, false, true>)
+                   : m->dh == 128 ? (tr ? (const void*)verify_fused_kernel<128, true, false> : (const void*)verify_fused_kernel<128, false, false>)
+                                  : (tr ? (const void*)verify_fused_kernel<64, true, false> : (const void*)verify_fused_kernel<64, false, false>);
     const bool prof = m->prof_on && m->prof_n < m->prof_cap;
     if (prof) LASER_HIP_CHECK(hipEventRecord(m->prof_ev[2 * m->prof_n], stream));
     LASER_HIP_CHECK(hipLaunchCooperativeKernel(fn, dim3(ws->nwg), dim3(FT), args, (size_t)g_lds_max, stream));

@@ -14,9 +14,9 @@ namespace laser {
 
 bool fused_supported(const Model* m, int B, int K, int max_len_ub);
 void fused_free(Model* m);
-int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, const int32_t* drafts,
+int run_fused(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pending, const int32_t* drafts, const int32_t* parent,
               const int32_t* draft_len, int B, int K, int topk, float p, int mode, int32_t* accept_len,
-              int32_t* out_tokens, float* logits_dbg, int max_len_ub, hipStream_t stream);
+              int32_t* out_tokens, int32_t* accept_path, float* logits_dbg, int max_len_ub, hipStream_t stream);
 int fused_status(Model* m, hipStream_t stream, int* aborted);
 int fused_read_trace(Model* m, hipStream_t stream, long long* out, int max_elems, int* nwg, int* cap);
 
@@ -936,7 +936,7 @@ static int check_step_args(const Model* m, int B, int K, int topk, int mode, con
     return LASER_OK;
 }
 
-// laser_verify_step (parent == NULL: a chain, may take the persistent kernel) and laser_verify_tree
+// laser_verify_step (parent == NULL: a chain) and laser_verify_tree; both take the persistent kernel where it applies
 static int verify_impl(laser_model* mh, laser_kv* kh, const int32_t* seq_ids, const int32_t* pending, const int32_t* drafts,
                        const int32_t* parent, const int32_t* draft_len, int B, int K, int topk, float p, int mode,
                        int32_t* accept_len, int32_t* out_tokens, int32_t* accept_path, float* logits_dbg, void* stream_) {
@@ -970,9 +970,12 @@ static int verify_impl(laser_model* mh, laser_kv* kh, const int32_t* seq_ids, co
     }
     const int32_t* ids_dev = nullptr;
     if ((rc = kv->stage_ids(seq_ids, B, stream, &ids_dev))) return rc;
-    if (!parent && m->use_fused && fused_supported(m, B, K, max_ub)) {
-        rc = run_fused(m, kv, ids_dev, pending, drafts, draft_len, B, K, topk, p, mode, accept_len, out_tokens,
-                       logits_dbg, max_ub, stream);
+    if (m->use_fused && fused_supported(m, B, K, max_ub)) {
+        if (parent)          // token tree: positions (depth) and ancestor masks of the rows
+            hipLaunchKernelGGL(rows_kernel, dim3((B * R + 255) / 256), dim3(256), 0, stream, parent, draft_len, ids_dev, kv->len, B, R,
+                               m->row_pos, m->row_slot, m->row_anc);
+        rc = run_fused(m, kv, ids_dev, pending, drafts, parent, draft_len, B, K, topk, p, mode, accept_len, out_tokens,
+                       accept_path, logits_dbg, max_ub, stream);
     } else {
         if ((rc = forward(m, kv, ids_dev, pending, drafts, parent, draft_len, B, K, max_ub, stream))) return rc;
         rc = run_head(m, m->xn, drafts, parent, draft_len, B, K, topk, p, mode, accept_len, out_tokens, accept_path, logits_dbg, stream);

@@ -103,7 +103,7 @@ def _random_tree(r, K, n_nodes):
     return par
 
 
-def _run_tree_steps(sh, B, ctx_len, K, n_steps, k, p, mode=0, seed=1, chainlike=False):
+def _run_tree_steps(sh, B, ctx_len, K, n_steps, k, p, mode=0, seed=1, chainlike=False, fused=None):
     """n_steps tree-verify + tree-commit steps on the GPU against the oracle; the trees are random shapes whose
     tokens mix the oracle's own greedy continuation (so that branches get accepted, also second branches) with
     random tokens; ragged node counts. Later steps read what laser_kv_commit_tree moved."""
@@ -111,6 +111,8 @@ def _run_tree_steps(sh, B, ctx_len, K, n_steps, k, p, mode=0, seed=1, chainlike=
     dec = _oracle(sh)
     cap = ctx_len + (K + 1) * (n_steps + 1) + 16
     model = gu.make_model(sh, max_rows=B * max(K + 1, 16), max_batch=B, max_pos=cap + 16)
+    if fused is not None:                # 1: the persistent few-row kernel where it applies (at most 16 rows), 0: never
+        model.set_option("fused", fused)
     kv = gu.make_kv(sh, n_pages=B * (cap // 16 + 2), max_seqs=B + 1, max_pages_per_seq=cap // 16 + 2)
     seq_ids = [B - b for b in range(B)]
     prompts = synth.uniform_tokens(seed, 60, 0, B * ctx_len, sh.vocab).reshape(B, ctx_len)
@@ -189,9 +191,25 @@ def test_verify_tree_against_the_oracle(shape_name):
     sh = synth.SHAPES[shape_name].with_(lm_gain=4.0)
     a, c = _run_tree_steps(sh, B=3, ctx_len=41, K=7, n_steps=5, k=1, p=-1.0, seed=3)           # 24 rows
     assert a > 0 and c > 0          # later steps did read compacted keys/values
-    _run_tree_steps(sh, B=2, ctx_len=300, K=6, n_steps=3, k=2, p=0.005, seed=4)                  # few rows, split context
+    _run_tree_steps(sh, B=2, ctx_len=300, K=6, n_steps=3, k=2, p=0.005, seed=4, fused=0)         # few rows, split context
     _run_tree_steps(sh, B=14, ctx_len=21, K=9, n_steps=2, k=3, p=0.02, mode=1, seed=5)          # 140 rows: tiled GEMMs + tiled head
     _run_tree_steps(sh, B=2, ctx_len=20, K=31, n_steps=2, k=2, p=0.005, seed=6)                  # 32 rows per sequence: two query tiles
+
+
+def test_verify_tree_persistent_kernel():
+    """Token trees of at most 16 rows on the persistent few-row kernel (ancestor mask in its attention phase, depth
+    positions, the nodes' logits picked from their parents' rows, tree walk in its acceptance phase)."""
+    sh = synth.SHAPES["tiny128"].with_(lm_gain=4.0)
+    a, c = _run_tree_steps(sh, B=1, ctx_len=41, K=8, n_steps=6, k=1, p=-1.0, seed=3, fused=1)
+    assert a > 0
+    a2, c2 = _run_tree_steps(sh, B=2, ctx_len=300, K=7, n_steps=4, k=2, p=0.005, seed=4, fused=1)    # 16 rows, split context
+    assert a2 > 0 and c + c2 > 0    # a later step did read compacted keys/values
+    a3, c3 = _run_tree_steps(sh, B=1, ctx_len=20, K=15, n_steps=3, k=3, p=0.02, mode=1, seed=7, fused=1)   # the largest tree it takes
+    assert a3 > 0 and c3 > 0
+    _run_tree_steps(sh, B=3, ctx_len=33, K=4, n_steps=3, k=2, p=0.005, mode=3, seed=6, fused=1)      # three sequences
+    sh7 = synth.SHAPES["7b"].with_(n_layers=2)
+    a7, c7 = _run_tree_steps(sh7, B=1, ctx_len=150, K=8, n_steps=3, k=2, p=0.0, seed=9, fused=1)
+    assert a7 > 0 and c7 > 0
 
 
 def test_verify_tree_7b_width():
@@ -199,17 +217,18 @@ def test_verify_tree_7b_width():
     _run_tree_steps(sh, B=2, ctx_len=150, K=8, n_steps=2, k=2, p=0.0, seed=7)
 
 
-def test_a_chain_given_as_a_tree_is_bit_identical_to_the_chain_call():
+@pytest.mark.parametrize("fused", [0, 1])
+def test_a_chain_given_as_a_tree_is_bit_identical_to_the_chain_call(fused):
     laser = _laser()
     sh = synth.SHAPES["tiny128"].with_(lm_gain=4.0)
-    B, K, ctx_len = 3, 6, 37
+    B, K, ctx_len = (2, 6, 37) if fused else (3, 6, 37)        # 14 rows fit the persistent kernel
     prompts = synth.uniform_tokens(9, 60, 0, B * ctx_len, sh.vocab).reshape(B, ctx_len)
     drafts = torch.tensor(synth.uniform_tokens(9, 61, 0, B * K, sh.vocab).reshape(B, K).astype(np.int32), device="cuda")
-    dl = torch.tensor([6, 3, 0], dtype=torch.int32, device="cuda")
+    dl = torch.tensor([6, 3, 0][:B], dtype=torch.int32, device="cuda")
     res = []
     for tree in (False, True):
         model = gu.make_model(sh, max_rows=B * 16, max_batch=B, max_pos=128)
-        model.set_option("fused", 0)
+        model.set_option("fused", fused)
         kv = gu.make_kv(sh, n_pages=B * 8, max_seqs=B, max_pages_per_seq=8)
         ids = list(range(B))
         for s in ids:
