@@ -477,8 +477,9 @@ def run_study(args):
     group = np.arange(U) % G
     r = np.random.default_rng(5)
 
-    def run_all(pool, keys_of_user, topk, p, mode, tree=False, Kd=K):
-        """regenerate every user's text; returns texts, counters, wall seconds, retrieval ms"""
+    def run_all(pool, keys_of_user, topk, p, mode, tree=False, Kd=K, eng=eng, B=B, U=U):
+        """regenerate every user's text (the first U users, B at a time on engine eng); returns texts, counters, wall
+        seconds, retrieval ms"""
         texts, cnts, secs, rms, bsteps = [], [], 0.0, 0.0, 0
         for u0 in range(0, U, B):
             us = list(range(u0, u0 + B))
@@ -540,7 +541,7 @@ def run_study(args):
     def summarise(name, texts, cnt, secs, rms, bsteps, extra=None):
         n_tok = sum(len([t for t in x if t >= 0]) for x in texts)
         to_eos = [next((i + 1 for i, t in enumerate(x) if 0 <= t < eos_class), len(x)) for x in texts]
-        differs = sum(1 for u in range(U) if texts[u] != greedy[u])
+        differs = sum(1 for u in range(len(texts)) if texts[u] != greedy[u])
         row = {"run": name, "tokens_per_s": n_tok / secs, "accepted_drafts_per_step": float(cnt[:, 2].sum() / max(cnt[:, 0].sum(), 1)),
                "sequence_steps": int(cnt[:, 0].sum()), "batch_steps": int(bsteps), "ms_per_batch_step": secs * 1e3 / max(bsteps, 1),
                "retrieval_us_per_batch_step": rms * 1e3 / max(bsteps, 1),
@@ -565,6 +566,13 @@ def run_study(args):
                                   ("RV (k=2, p=0.1)", (2, 0.1, 0)), ("top-1 or RV", (2, 0.1, 1)), ("top-k only (k=8)", (8, 0.0, 2))):
         rows.append(summarise(f"rule: {name}", *run_all(pool, lookup, topk, p, mode)))
     rows.append(summarise("CRP RV, token trees of 16 nodes", *run_all(pool, lookup, 2, 0.1, 0, tree=True, Kd=16)))
+    # One sequence at a time (the latency regime: K + 1 = 9 rows, the persistent few-row kernel for chains and trees
+    # alike), the first 8 users: a tree of 8 nodes costs the same rows as a chain of 8 drafts. The reference text was
+    # decoded at another launch shape, so "differing" counts near-tie forks of the random-init model here, not errors.
+    eng1 = Engine(sh, weights, 1, 16, ctx_len + T + 64, n_max)
+    for name, tree in (("B=1, CRP RV, chains of 8 drafts", False), ("B=1, CRP RV, token trees of 8 nodes", True)):
+        rows.append(summarise(name, *run_all(pool, lookup, 2, 0.1, 0, tree=tree, Kd=8, eng=eng1, B=1, U=8), {"users": 8}))
+    eng1.close()
     pool.close()
     eng.close()
     return {"study": "generation loop on synthetic users (laser_generate)", "shape": sh.name, "users": U, "groups": G, "batch": B,
