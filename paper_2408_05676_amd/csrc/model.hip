@@ -803,8 +803,10 @@ static int forward(Model* m, KV* kv, const int32_t* ids_dev, const int32_t* pend
         AttnArgs aa{m->q, m->q_lo, kv->kpages, kv->klpages, kv->vpages, ids_dev, kv->len, kv->block_table, m->row_anc, m->attn, m->attn_lo, m->att_part,
                     R, dm, d.n_heads, kv->d.max_pages_per_seq, l, kv->d.n_pages, nsplit, nqt, split_pages, 1.0f / sqrtf((float)m->dh)};
         dim3 ag(d.n_heads, B, nsplit * nqt);
-        // unsplit contexts in a launch of fewer than two workgroups per compute unit: eight waves share the pages
-        const bool wide = whole && (m->attn_waves ? m->attn_waves == 8 : (long)B * d.n_heads * nqt < 2L * ncu);
+        // unsplit contexts: eight waves share the pages of a (sequence, head) up to 16 workgroups per compute unit (compared
+        // inside one run: 128 and 256 workgroups 3-6 % of the step faster than with four waves, 2048 workgroups 0.3-0.6 %,
+        // which is at the edge of that workload's repeatability)
+        const bool wide = whole && (m->attn_waves ? m->attn_waves == 8 : (long)B * d.n_heads * nqt < 16L * ncu);
         if (m->dh == 128) {
             if (wide) hipLaunchKernelGGL((attn_kernel<128, 8>), ag, dim3(512), 0, stream, aa);
             else hipLaunchKernelGGL((attn_kernel<128, 4>), ag, dim3(256), 0, stream, aa);
