@@ -13,7 +13,7 @@ from tests import gpu_util as gu
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("shape_name,fused", [("tiny", 1), ("tiny128", 0)])
+@pytest.mark.parametrize("shape_name,fused", [("tiny", 1), ("tiny128", 0), ("tiny128", 1)])
 def test_generate_against_the_oracle(shape_name, fused):
     import paper_2408_05676_amd as laser
     sh = synth.SHAPES[shape_name].with_(lm_gain=4.0)
